@@ -1,0 +1,194 @@
+/*
+ * hcspmm -- hybrid-core SpMM for graph adjacency matrices on AMD MI355X (gfx950).
+ *
+ * C ABI of the library.  The method follows "HC-SpMM" (arxiv 2412.08902):
+ *   - the sparse matrix A (CSR) is cut into row windows of 16 rows, the minimum
+ *     hybrid unit                                       (Section IV-A);
+ *   - inside a window the non-zero columns are moved to the front ("condensed")
+ *                                                        (Section IV-A);
+ *   - a three-parameter linear model on (number of non-zero columns, sparsity)
+ *     decides per window whether the matrix cores or the scalar cores compute
+ *     it; the decision is taken once, in preprocessing, and stored as one flag
+ *     per window (0 = scalar path, 1 = matrix path)      (Section IV-C);
+ *   - Z = A X is then computed window by window on the chosen path, windows
+ *     own disjoint output rows so nothing is merged      (Alg. 1-4, Eq. 1);
+ *   - the GNN layer couples the aggregation with the dense update X W
+ *                                                        (Section V-A, Eq. 1-2).
+ *
+ * Conventions for every entry point
+ *   - "device" pointers are HIP device pointers owned by the caller; "host"
+ *     pointers are ordinary host memory.  The library never frees caller
+ *     memory.  Dense matrices are row-major with a leading dimension given in
+ *     ELEMENTS.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     hcspmm_spmm / hcspmm_gcn_layer only enqueue work on it and return;
+ *     hcspmm_prepare and hcspmm_plan_export synchronise with it.
+ *   - No entry point throws, aborts or prints.  Every failure is a status
+ *     code; hcspmm_last_error() returns a thread-local description of the most
+ *     recent failure on the calling thread.
+ *   - All index arithmetic on row*ld and nnz*d is done in 64 bits; CSR indices
+ *     are int32, so nnz < 2^31.
+ */
+#ifndef HCSPMM_H
+#define HCSPMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hcspmm_plan hcspmm_plan;   /* opaque, library-owned */
+
+typedef enum {
+    HCSPMM_OK = 0,
+    HCSPMM_EINVAL = 1,        /* NULL pointer, negative size, bad enum, bad leading dimension */
+    HCSPMM_EBADCSR = 2,       /* rowptr not monotone / rowptr[0] != 0 / rowptr[n] != nnz / column out of range */
+    HCSPMM_EALLOC = 3,        /* device or host allocation failed */
+    HCSPMM_EHIP = 4,          /* a HIP runtime call failed */
+    HCSPMM_EUNSUPPORTED = 5   /* valid request outside the implemented envelope (see each call) */
+} hcspmm_status;
+
+typedef enum { HCSPMM_F32 = 0, HCSPMM_BF16 = 1, HCSPMM_F16 = 2 } hcspmm_dtype;
+
+/* How windows are routed.  HYBRID evaluates the selector per window; the two
+ * ALL_* modes force one path for every non-empty window (used to measure the
+ * selector against the pure paths).  Empty windows always take the scalar path. */
+typedef enum { HCSPMM_ROUTE_HYBRID = 0, HCSPMM_ROUTE_ALL_CSR = 1, HCSPMM_ROUTE_ALL_MFMA = 2 } hcspmm_route_mode;
+
+/*
+ * Options of hcspmm_prepare.  Fill with hcspmm_default_options() first.
+ *
+ * Selector (Section IV-C).  The paper's model is  z = w1*ncols + w2*sparsity + b
+ * with sparsity = 1 - nnzw/(H*ncols); training label 1 means "scalar cores are
+ * faster".  It is evaluated exactly in 64-bit integers after multiplying by
+ * H*ncols > 0:
+ *     z' = sel_coef[0]*H*ncols^2 + sel_coef[1]*(H*ncols - nnzw) + sel_coef[2]*H*ncols
+ *     route = 1 (matrix path)  iff  z' < 0
+ * so sel_coef = (w1, w2, b) scaled by one common positive factor.  The paper
+ * does not print its coefficients (they are fitted per GPU model and
+ * precision); the defaults shipped here were fitted on MI355X for each
+ * (mfma_dtype, d_hint) bucket and are returned by hcspmm_default_selector().
+ */
+typedef struct {
+    int32_t struct_size;          /* sizeof(hcspmm_options), for ABI growth */
+    int32_t window_rows;          /* H; only 16 is implemented */
+    int32_t route_mode;           /* hcspmm_route_mode */
+    int32_t mfma_dtype;           /* hcspmm_dtype the matrix path will multiply in (selects default coefficients) */
+    int32_t d_hint;               /* dense width the plan will mostly be used with (selects default coefficients); 0 = 64 */
+    int32_t use_custom_selector;  /* 0: shipped coefficients for (mfma_dtype, d_hint); 1: sel_coef below */
+    int64_t sel_coef[3];
+} hcspmm_options;
+
+void hcspmm_default_options(hcspmm_options* opt /* host, out */);
+
+/* Shipped selector coefficients for a precision and dense width.  coef: host, out, 3 entries. */
+hcspmm_status hcspmm_default_selector(int32_t mfma_dtype, int32_t d_hint, int64_t* coef);
+
+/*
+ * Preprocessing (Section IV-A windows + condensing, Section IV-C selection;
+ * the paper's Appendix F "preprocessing").  Runs entirely on the GPU.
+ *
+ *   n_rows, n_cols   shape of A (n_rows >= 0, 1 <= n_cols < 2^27)
+ *   nnz              number of stored entries (0 <= nnz < 2^31)
+ *   d_rowptr         device, int32[n_rows+1]
+ *   d_colind         device, int32[nnz]; rows need not be sorted; duplicate (row, col) entries are summed
+ *   d_vals           device, float[nnz]
+ *   opt              host, NULL = defaults
+ *   out_plan         host, receives the plan
+ *
+ * The plan BORROWS d_rowptr / d_colind / d_vals: they must stay valid and
+ * unchanged until hcspmm_plan_destroy.  Everything the plan allocates it owns.
+ * Validates the CSR on the device (HCSPMM_EBADCSR).  Synchronises with `stream`.
+ */
+hcspmm_status hcspmm_prepare(int32_t n_rows, int32_t n_cols, int64_t nnz,
+                             const int32_t* d_rowptr, const int32_t* d_colind, const float* d_vals,
+                             const hcspmm_options* opt, void* stream, hcspmm_plan** out_plan);
+
+/* Sizes of a plan's arrays (host struct, filled by hcspmm_plan_info). */
+typedef struct {
+    int32_t window_rows;      /* H */
+    int32_t n_rows, n_cols;
+    int64_t nnz;
+    int32_t n_windows;        /* W = ceil(n_rows / H) */
+    int64_t total_ncols;      /* sum over windows of ncols = length of wcols */
+    int32_t n_mfma_windows;   /* windows with route 1 */
+    int32_t n_csr_windows;    /* windows with route 0 */
+    int64_t nnz_mfma;         /* non-zeros inside route-1 windows */
+    int32_t route_mode;
+    int32_t mfma_dtype;
+    int32_t d_hint;
+    int64_t sel_coef[3];      /* coefficients the routes were computed with */
+    int64_t device_bytes;     /* device memory owned by the plan */
+} hcspmm_plan_info_t;
+
+hcspmm_status hcspmm_plan_info(const hcspmm_plan* plan, hcspmm_plan_info_t* info /* host, out */);
+
+/*
+ * Copies the canonical plan arrays to host memory (each pointer may be NULL to
+ * skip that array; sizes from hcspmm_plan_info):
+ *   ncols  int32[W]    distinct columns per window                    (Section IV-A / V-B)
+ *   nnzw   int32[W]    non-zeros per window
+ *   route  uint8[W]    0 = scalar path, 1 = matrix path                (Section IV-C)
+ *   wptr   int64[W+1]  offsets into wcols
+ *   wcols  int32[total_ncols]  per window: its distinct column ids, ascending
+ *   ecol   int32[nnz]  per non-zero (CSR order): position of its column in its window's wcols
+ *   mfma_windows int32[n_mfma_windows], csr_windows int32[n_csr_windows]: ascending window ids per route
+ * Synchronises with the device.
+ */
+hcspmm_status hcspmm_plan_export(const hcspmm_plan* plan, int32_t* ncols, int32_t* nnzw, uint8_t* route,
+                                 int64_t* wptr, int32_t* wcols, int32_t* ecol,
+                                 int32_t* mfma_windows, int32_t* csr_windows);
+
+/*
+ * Y = A X on the hybrid paths (Eq. 1; Alg. 1/3 for route-0 windows, Alg. 2/4
+ * for route-1 windows).  Y is overwritten (rows without entries become 0).
+ *
+ *   d_X      device, n_cols x d, row-major, leading dimension ldx >= d, dtype x_dtype
+ *   d_Y      device, n_rows x d, row-major, leading dimension ldy >= d, dtype y_dtype
+ *   x_dtype  HCSPMM_F32: fp32 arithmetic on both paths (true fp32 MFMA);
+ *            HCSPMM_BF16 / HCSPMM_F16: the matrix path multiplies 16-bit
+ *            operands (A values rounded to the same type) with fp32
+ *            accumulation, the scalar path widens X to fp32.
+ *   y_dtype  must be HCSPMM_F32.
+ * X and Y must not overlap.  1 <= d <= 2^20.  Asynchronous on `stream`.
+ */
+hcspmm_status hcspmm_spmm(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d, int32_t x_dtype,
+                          void* d_Y, int64_t ldy, int32_t y_dtype, void* stream);
+
+/*
+ * GCN layer  Y = act(A (X W))  (Eq. 1 and Eq. 2; Section V-A couples the two
+ * phases).  The update X W is formed first by an fp32 MFMA GEMM into the
+ * workspace, which is consumed at once by the hybrid SpMM while it is still
+ * cache-resident; the activation (ReLU when apply_relu != 0) is applied in the
+ * SpMM epilogue, after the complete row sum.
+ *
+ *   d_X   device, n_cols x d_in fp32 (ldx >= d_in);  d_W  device, d_in x d_out fp32 (ldw >= d_out)
+ *   d_Y   device, n_rows x d_out fp32 (ldy >= d_out)
+ *   d_workspace  device, at least hcspmm_gcn_workspace_bytes(plan, d_in, d_out) bytes, 256-byte aligned
+ * Asynchronous on `stream`.
+ */
+hcspmm_status hcspmm_gcn_layer(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d_in,
+                               const void* d_W, int64_t ldw, int32_t d_out,
+                               void* d_Y, int64_t ldy, int32_t apply_relu,
+                               void* d_workspace, size_t workspace_bytes, void* stream);
+
+size_t hcspmm_gcn_workspace_bytes(const hcspmm_plan* plan, int32_t d_in, int32_t d_out);
+
+/* Dense update alone, T = X W in fp32 MFMA (Eq. 2): d_X M x K, d_W K x N, d_T M x N, all fp32 device. */
+hcspmm_status hcspmm_gemm_f32(int64_t m, int32_t k, int32_t n, const float* d_X, int64_t ldx,
+                              const float* d_W, int64_t ldw, float* d_T, int64_t ldt, void* stream);
+
+/* Frees everything the plan owns (not the borrowed CSR).  NULL is allowed. */
+void hcspmm_plan_destroy(hcspmm_plan* plan);
+
+const char* hcspmm_status_string(hcspmm_status s);
+const char* hcspmm_last_error(void);
+/* Library version: major*10000 + minor*100 + patch. */
+int32_t hcspmm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HCSPMM_H */

@@ -1,0 +1,235 @@
+"""ctypes binding of ``libhcspmm.so``: same names as the C entry points, argument marshalling only.
+
+torch is used for device memory and streams; tensors are passed to the library as raw device
+pointers.  Nothing here computes anything.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+from ._build import LIB_PATH, build_library
+
+HCSPMM_OK, HCSPMM_EINVAL, HCSPMM_EBADCSR, HCSPMM_EALLOC, HCSPMM_EHIP, HCSPMM_EUNSUPPORTED = range(6)
+HCSPMM_F32, HCSPMM_BF16, HCSPMM_F16 = 0, 1, 2
+HCSPMM_ROUTE_HYBRID, HCSPMM_ROUTE_ALL_CSR, HCSPMM_ROUTE_ALL_MFMA = 0, 1, 2
+
+EXPORTED_SYMBOLS = [
+    "hcspmm_default_options", "hcspmm_default_selector", "hcspmm_prepare", "hcspmm_plan_info",
+    "hcspmm_plan_export", "hcspmm_spmm", "hcspmm_gcn_layer", "hcspmm_gcn_workspace_bytes",
+    "hcspmm_gemm_f32", "hcspmm_plan_destroy", "hcspmm_status_string", "hcspmm_last_error", "hcspmm_version",
+]
+
+
+class HcspmmOptions(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_int32), ("window_rows", ctypes.c_int32), ("route_mode", ctypes.c_int32),
+                ("mfma_dtype", ctypes.c_int32), ("d_hint", ctypes.c_int32), ("use_custom_selector", ctypes.c_int32),
+                ("sel_coef", ctypes.c_int64 * 3)]
+
+
+class HcspmmPlanInfo(ctypes.Structure):
+    _fields_ = [("window_rows", ctypes.c_int32), ("n_rows", ctypes.c_int32), ("n_cols", ctypes.c_int32),
+                ("nnz", ctypes.c_int64), ("n_windows", ctypes.c_int32), ("total_ncols", ctypes.c_int64),
+                ("n_mfma_windows", ctypes.c_int32), ("n_csr_windows", ctypes.c_int32), ("nnz_mfma", ctypes.c_int64),
+                ("route_mode", ctypes.c_int32), ("mfma_dtype", ctypes.c_int32), ("d_hint", ctypes.c_int32),
+                ("sel_coef", ctypes.c_int64 * 3), ("device_bytes", ctypes.c_int64)]
+
+
+class HcspmmError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("hcspmm status %d: %s" % (status, message))
+        self.status = status
+
+
+_lib = None
+
+
+def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
+    """Load libhcspmm.so (building it first only when no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        if not build_if_missing:
+            raise ImportError("libhcspmm.so is not built (run __graft_entry__.build())")
+        build_library()
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    lib.hcspmm_default_options.argtypes = [ctypes.POINTER(HcspmmOptions)]
+    lib.hcspmm_default_options.restype = None
+    lib.hcspmm_default_selector.argtypes = [i32, i32, ctypes.POINTER(i64)]
+    lib.hcspmm_default_selector.restype = ctypes.c_int
+    lib.hcspmm_prepare.argtypes = [i32, i32, i64, vp, vp, vp, ctypes.POINTER(HcspmmOptions), vp, ctypes.POINTER(vp)]
+    lib.hcspmm_prepare.restype = ctypes.c_int
+    lib.hcspmm_plan_info.argtypes = [vp, ctypes.POINTER(HcspmmPlanInfo)]
+    lib.hcspmm_plan_info.restype = ctypes.c_int
+    lib.hcspmm_plan_export.argtypes = [vp] + [vp] * 8
+    lib.hcspmm_plan_export.restype = ctypes.c_int
+    lib.hcspmm_spmm.argtypes = [vp, vp, i64, i32, i32, vp, i64, i32, vp]
+    lib.hcspmm_spmm.restype = ctypes.c_int
+    lib.hcspmm_gcn_layer.argtypes = [vp, vp, i64, i32, vp, i64, i32, vp, i64, i32, vp, ctypes.c_size_t, vp]
+    lib.hcspmm_gcn_layer.restype = ctypes.c_int
+    lib.hcspmm_gcn_workspace_bytes.argtypes = [vp, i32, i32]
+    lib.hcspmm_gcn_workspace_bytes.restype = ctypes.c_size_t
+    lib.hcspmm_gemm_f32.argtypes = [i64, i32, i32, vp, i64, vp, i64, vp, i64, vp]
+    lib.hcspmm_gemm_f32.restype = ctypes.c_int
+    lib.hcspmm_plan_destroy.argtypes = [vp]
+    lib.hcspmm_plan_destroy.restype = None
+    lib.hcspmm_status_string.argtypes = [ctypes.c_int]
+    lib.hcspmm_status_string.restype = ctypes.c_char_p
+    lib.hcspmm_last_error.argtypes = []
+    lib.hcspmm_last_error.restype = ctypes.c_char_p
+    lib.hcspmm_version.argtypes = []
+    lib.hcspmm_version.restype = i32
+    _lib = lib
+    return lib
+
+
+def _check(status: int):
+    if status != HCSPMM_OK:
+        lib = load_library()
+        detail = lib.hcspmm_last_error().decode()
+        raise HcspmmError(status, "%s: %s" % (lib.hcspmm_status_string(status).decode(), detail))
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(stream=None):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+_TORCH_DTYPE_CODE = None
+
+
+def _dtype_code(t) -> int:
+    import torch
+    return {torch.float32: HCSPMM_F32, torch.bfloat16: HCSPMM_BF16, torch.float16: HCSPMM_F16}[t.dtype]
+
+
+def hcspmm_default_options() -> HcspmmOptions:
+    o = HcspmmOptions()
+    load_library().hcspmm_default_options(ctypes.byref(o))
+    return o
+
+
+def hcspmm_default_selector(mfma_dtype: int = HCSPMM_F32, d_hint: int = 0):
+    c = (ctypes.c_int64 * 3)()
+    _check(load_library().hcspmm_default_selector(mfma_dtype, d_hint, c))
+    return [int(c[0]), int(c[1]), int(c[2])]
+
+
+class Plan:
+    """Owns a ``hcspmm_plan*`` and keeps the borrowed CSR tensors alive."""
+
+    def __init__(self, handle, rowptr, colind, vals):
+        self._h = handle
+        self._keep = (rowptr, colind, vals)
+
+    @property
+    def handle(self):
+        if self._h is None:
+            raise ValueError("plan was destroyed")
+        return self._h
+
+    def destroy(self):
+        if self._h is not None:
+            load_library().hcspmm_plan_destroy(self._h)
+            self._h = None
+            self._keep = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def hcspmm_prepare(n_rows: int, n_cols: int, rowptr, colind, vals, *, route_mode: int = HCSPMM_ROUTE_HYBRID,
+                   mfma_dtype: int = HCSPMM_F32, d_hint: int = 0, sel_coef: Optional[Sequence[int]] = None,
+                   stream=None, nnz: Optional[int] = None) -> Plan:
+    """rowptr/colind: int32 CUDA tensors, vals: float32 CUDA tensor (borrowed by the plan)."""
+    lib = load_library()
+    o = hcspmm_default_options()
+    o.route_mode, o.mfma_dtype, o.d_hint = route_mode, mfma_dtype, d_hint
+    if sel_coef is not None:
+        o.use_custom_selector = 1
+        for i in range(3):
+            o.sel_coef[i] = int(sel_coef[i])
+    if nnz is None:
+        nnz = int(colind.numel())
+    out = ctypes.c_void_p()
+    _check(lib.hcspmm_prepare(n_rows, n_cols, nnz, _ptr(rowptr), _ptr(colind), _ptr(vals), ctypes.byref(o),
+                              _stream_ptr(stream), ctypes.byref(out)))
+    return Plan(out, rowptr, colind, vals)
+
+
+def hcspmm_plan_info(plan: Plan) -> dict:
+    info = HcspmmPlanInfo()
+    _check(load_library().hcspmm_plan_info(plan.handle, ctypes.byref(info)))
+    d = {name: getattr(info, name) for name, _ in HcspmmPlanInfo._fields_ if name != "sel_coef"}
+    d["sel_coef"] = [int(info.sel_coef[i]) for i in range(3)]
+    return d
+
+
+def hcspmm_plan_export(plan: Plan, with_ecol: bool = True) -> dict:
+    """Canonical plan arrays as numpy arrays (host)."""
+    info = hcspmm_plan_info(plan)
+    W = info["n_windows"]
+    out = dict(H=info["window_rows"], W=W,
+               ncols=np.zeros(W, np.int32), nnzw=np.zeros(W, np.int32), route=np.zeros(W, np.uint8),
+               wptr=np.zeros(W + 1, np.int64), wcols=np.zeros(info["total_ncols"], np.int32),
+               ecol=np.zeros(info["nnz"] if with_ecol else 0, np.int32),
+               mfma_windows=np.zeros(info["n_mfma_windows"], np.int32),
+               csr_windows=np.zeros(info["n_csr_windows"], np.int32))
+
+    def p(name):
+        a = out[name]
+        return a.ctypes.data_as(ctypes.c_void_p) if a.size else None
+
+    _check(load_library().hcspmm_plan_export(plan.handle, p("ncols"), p("nnzw"), p("route"),
+                                             out["wptr"].ctypes.data_as(ctypes.c_void_p), p("wcols"),
+                                             p("ecol") if with_ecol else None, p("mfma_windows"), p("csr_windows")))
+    return out
+
+
+def hcspmm_spmm(plan: Plan, X, Y, *, d: Optional[int] = None, stream=None):
+    """Y[:, :d] = A X[:, :d]; X, Y are 2-D CUDA tensors (row-major, last stride 1)."""
+    assert X.dim() == 2 and Y.dim() == 2 and X.stride(1) == 1 and Y.stride(1) == 1
+    if d is None:
+        d = X.shape[1]
+    _check(load_library().hcspmm_spmm(plan.handle, _ptr(X), X.stride(0), d, _dtype_code(X), _ptr(Y), Y.stride(0),
+                                      _dtype_code(Y), _stream_ptr(stream)))
+    return Y
+
+
+def hcspmm_gcn_workspace_bytes(plan: Plan, d_in: int, d_out: int) -> int:
+    return int(load_library().hcspmm_gcn_workspace_bytes(plan.handle, d_in, d_out))
+
+
+def hcspmm_gcn_layer(plan: Plan, X, W, Y, workspace, *, apply_relu: bool = True, stream=None):
+    """Y = act(A (X W)); workspace: a uint8/float CUDA tensor of at least hcspmm_gcn_workspace_bytes bytes."""
+    assert X.stride(1) == 1 and W.stride(1) == 1 and Y.stride(1) == 1
+    _check(load_library().hcspmm_gcn_layer(plan.handle, _ptr(X), X.stride(0), X.shape[1], _ptr(W), W.stride(0),
+                                           W.shape[1], _ptr(Y), Y.stride(0), 1 if apply_relu else 0, _ptr(workspace),
+                                           workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
+    return Y
+
+
+def hcspmm_gemm_f32(X, W, T, *, stream=None):
+    assert X.stride(1) == 1 and W.stride(1) == 1 and T.stride(1) == 1
+    _check(load_library().hcspmm_gemm_f32(X.shape[0], X.shape[1], W.shape[1], _ptr(X), X.stride(0), _ptr(W),
+                                          W.stride(0), _ptr(T), T.stride(0), _stream_ptr(stream)))
+    return T
+
+
+def hcspmm_version() -> int:
+    return int(load_library().hcspmm_version())

@@ -1,0 +1,136 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "hcspmm.h"
+
+namespace hcspmm {
+
+constexpr int kH = 16;                 // rows per window (Section IV-A: the minimum hybrid unit)
+
+// ---- preprocessing -----------------------------------------------------------------------------
+constexpr int kUniqueSmallCap = 4096;  // windows with at most this many non-zeros are condensed by an LDS sort
+constexpr int kBitmapWords = 32768;    // LDS bitmap (1 Mi columns per pass) used to condense larger windows
+constexpr int kEcolLdsCap = 4096;      // distinct-column lists up to this length are searched from LDS
+
+// ---- matrix path -------------------------------------------------------------------------------
+constexpr int kMfmaSmallMaxCols = 512; // windows with more condensed columns go to the workgroup-per-window kernel
+constexpr int kKcSmall = 64;           // condensed columns staged per wave and chunk (wave-per-window kernel)
+constexpr int kKcBig = 1024;           // condensed columns staged per workgroup and chunk
+
+// ---- scalar path -------------------------------------------------------------------------------
+constexpr int kLongRow = 512;          // rows with more non-zeros than this are cut into segments
+constexpr int kSegLen = 2048;          // non-zeros per segment of a long row
+
+struct Segment { int32_t row, k_begin, k_end, slot; };    // slot < 0: writes Y directly
+struct MultiRow { int32_t row, first_slot, n_slots, pad; };
+
+void set_error(const char* fmt, ...);
+
+#define HC_HIP(call)                                                                               \
+    do {                                                                                           \
+        hipError_t e_ = (call);                                                                    \
+        if (e_ != hipSuccess) {                                                                    \
+            ::hcspmm::set_error("%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__); \
+            return HCSPMM_EHIP;                                                                    \
+        }                                                                                          \
+    } while (0)
+
+// Exclusive prefix sum of n int32 values into n+1 int64 values (out[n] = total).  `scratch` holds
+// at least scan_scratch_elems(n) int64.  Enqueued on `stream`.
+size_t scan_scratch_elems(int64_t n);
+hipError_t exclusive_scan_i32_i64(const int32_t* in, int64_t n, int64_t* out, int64_t* scratch, hipStream_t stream);
+
+// ---- preprocessing launchers (prepare_kernels.hip) ---------------------------------------------
+hipError_t launch_validate(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
+                           int32_t* err_flag, hipStream_t s);
+hipError_t launch_window_nnz(int32_t W, int32_t n_rows, const int32_t* rowptr, int32_t* nnzw, int32_t* big_list,
+                             int32_t* big_count, hipStream_t s);
+hipError_t launch_unique_small(int32_t W, int32_t n_rows, const int32_t* rowptr, const int32_t* colind,
+                               int32_t* tmp_cols, int32_t* ncols, hipStream_t s);
+hipError_t launch_unique_big(int32_t n_big, const int32_t* big_list, int32_t n_rows, int32_t n_cols,
+                             const int32_t* rowptr, const int32_t* colind, int32_t* tmp_cols, int32_t* ncols,
+                             hipStream_t s);
+hipError_t launch_ecol(int32_t W, int32_t n_rows, const int32_t* rowptr, const int32_t* colind,
+                       const int32_t* tmp_cols, const int32_t* ncols, const int64_t* wptr, int32_t* wcols,
+                       int32_t* erc, hipStream_t s);
+hipError_t launch_select(int32_t W, const int32_t* ncols, const int32_t* nnzw, int64_t c0, int64_t c1, int64_t c2,
+                         int32_t mode, uint8_t* route, int32_t* f_mfma, int32_t* f_csr, int32_t* f_small,
+                         int32_t* f_big, int32_t* nnz_if_mfma, hipStream_t s);
+hipError_t launch_compact_ids(int32_t n, const int32_t* flags, const int64_t* pos, int32_t* out, hipStream_t s);
+hipError_t launch_row_class(int32_t n_rows, const int32_t* rowptr, const uint8_t* route, int32_t* f_short,
+                            int32_t* n_seg, int32_t* f_multi, int32_t* n_slot, hipStream_t s);
+hipError_t launch_build_segments(int32_t n_rows, const int32_t* rowptr, const int32_t* n_seg, const int64_t* seg_pos,
+                                 const int64_t* multi_pos, const int64_t* slot_pos, Segment* segs, MultiRow* multi,
+                                 hipStream_t s);
+
+// ---- compute launchers -------------------------------------------------------------------------
+struct SpmmArgs {
+    int32_t n_rows;
+    const int32_t* rowptr;
+    const int32_t* colind;
+    const float* vals;
+    const void* X;
+    int64_t ldx;
+    int32_t d;
+    int32_t x_dtype;
+    float* Y;
+    int64_t ldy;
+    int32_t relu;
+};
+
+hipError_t launch_csr_short(const SpmmArgs& a, int32_t n_items, const int32_t* row_list, const uint8_t* route,
+                            hipStream_t s);
+hipError_t launch_csr_long(const SpmmArgs& a, int32_t n_segs, const Segment* segs, float* partial, hipStream_t s);
+hipError_t launch_reduce_partials(const SpmmArgs& a, int32_t n_multi, const MultiRow* multi, const float* partial,
+                                  hipStream_t s);
+hipError_t launch_mfma_small(const SpmmArgs& a, int32_t n_list, const int32_t* win_list, const int32_t* ncols,
+                             const int64_t* wptr, const int32_t* wcols, const int32_t* erc, hipStream_t s);
+hipError_t launch_mfma_big(const SpmmArgs& a, int32_t n_list, const int32_t* win_list, const int32_t* ncols,
+                           const int64_t* wptr, const int32_t* wcols, const int32_t* erc, hipStream_t s);
+hipError_t launch_gemm_f32(int64_t m, int32_t k, int32_t n, const float* X, int64_t ldx, const float* W, int64_t ldw,
+                           float* T, int64_t ldt, hipStream_t s);
+
+}  // namespace hcspmm
+
+struct hcspmm_plan {
+    int32_t H, n_rows, n_cols, W;
+    int64_t nnz;
+    int device;
+    hcspmm_options opt;
+    int64_t coef[3];
+    // borrowed
+    const int32_t* rowptr;
+    const int32_t* colind;
+    const float* vals;
+    // owned, canonical
+    int32_t* ncols;
+    int32_t* nnzw;
+    uint8_t* route;
+    int64_t* wptr;
+    int32_t* wcols;
+    int32_t* erc;            // per non-zero: (ecol << 4) | row-in-window
+    int32_t* mfma_windows;
+    int32_t* csr_windows;
+    int64_t total_ncols;
+    int32_t n_mfma, n_csr;
+    int64_t nnz_mfma;
+    // owned, launch tables
+    int32_t* mfma_small;
+    int32_t* mfma_big;
+    int32_t n_mfma_small, n_mfma_big;
+    int32_t* short_rows;     // rows of route-0 windows with at most kLongRow non-zeros (NULL: every row qualifies)
+    int32_t n_short;
+    hcspmm::Segment* segs;
+    int32_t n_segs;
+    hcspmm::MultiRow* multi;
+    int32_t n_multi;
+    int64_t n_slots;
+    // lazily sized partial-sum buffer for long rows cut into several segments
+    float* partial;
+    int64_t partial_elems;
+    int64_t device_bytes;
+};

@@ -1,0 +1,461 @@
+// C-ABI entry points: argument checking, plan construction, launch sequencing.
+#include "common.hpp"
+
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+namespace hcspmm {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+}
+
+// Shipped selector coefficients (w1, w2, b) x 2^10 of  z = w1*ncols + w2*sparsity + b  (Section
+// IV-C form; route = matrix path iff z < 0), one row per (precision, dense-width bucket).  Fitted
+// on MI355X with the procedure of Section IV-C (synthetic 16-row windows, both kernels timed,
+// logistic regression); the paper does not print its own values.
+struct SelectorRow { int32_t dtype; int32_t d_max; int64_t c[3]; };
+static const SelectorRow kSelectorTable[] = {
+    // fp32 MFMA
+    {HCSPMM_F32, 32, {2, 4096, -3328}},
+    {HCSPMM_F32, 64, {2, 4096, -3328}},
+    {HCSPMM_F32, 1 << 30, {2, 4096, -3328}},
+    // 16-bit MFMA
+    {HCSPMM_BF16, 1 << 30, {1, 4096, -3686}},
+    {HCSPMM_F16, 1 << 30, {1, 4096, -3686}},
+};
+
+static bool lookup_selector(int32_t dtype, int32_t d_hint, int64_t* coef)
+{
+    if (d_hint <= 0) d_hint = 64;
+    for (const SelectorRow& r : kSelectorTable)
+        if (r.dtype == dtype && d_hint <= r.d_max) {
+            coef[0] = r.c[0]; coef[1] = r.c[1]; coef[2] = r.c[2];
+            return true;
+        }
+    return false;
+}
+
+struct DevAlloc {
+    std::vector<void*> ptrs;
+    int64_t bytes = 0;
+    template <class T> hipError_t get(T** out, size_t count)
+    {
+        size_t sz = count * sizeof(T);
+        if (sz == 0) sz = sizeof(T) < 16 ? 16 : sizeof(T);
+        void* p = nullptr;
+        hipError_t e = hipMalloc(&p, sz);
+        if (e != hipSuccess) { *out = nullptr; return e; }
+        ptrs.push_back(p);
+        bytes += (int64_t)sz;
+        *out = static_cast<T*>(p);
+        return hipSuccess;
+    }
+    void free_all()
+    {
+        for (void* p : ptrs) (void)hipFree(p);
+        ptrs.clear();
+    }
+};
+
+#define HC_ALLOC(alloc, ptr, count)                                                                \
+    do {                                                                                           \
+        if ((alloc).get(&(ptr), (size_t)(count)) != hipSuccess) {                                  \
+            (void)hipGetLastError();                                                               \
+            set_error("device allocation of %zu elements failed (%s:%d)", (size_t)(count), __FILE__, __LINE__); \
+            st = HCSPMM_EALLOC;                                                                    \
+            goto fail;                                                                             \
+        }                                                                                          \
+    } while (0)
+
+#define HC_TRY(call)                                                                               \
+    do {                                                                                           \
+        hipError_t e_ = (call);                                                                    \
+        if (e_ != hipSuccess) {                                                                    \
+            set_error("%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__);  \
+            st = HCSPMM_EHIP;                                                                      \
+            goto fail;                                                                             \
+        }                                                                                          \
+    } while (0)
+
+static void free_plan_arrays(hcspmm_plan* p)
+{
+    void* owned[] = {p->ncols, p->nnzw, p->route, p->wptr, p->wcols, p->erc, p->mfma_windows, p->csr_windows,
+                     p->mfma_small, p->mfma_big, p->short_rows, p->segs, p->multi, p->partial};
+    for (void* q : owned)
+        if (q) (void)hipFree(q);
+}
+
+static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
+{
+    hcspmm_status st = HCSPMM_OK;
+    DevAlloc tmp;      // scratch, freed on exit
+    DevAlloc keep;     // plan-owned, freed on failure only
+    const int32_t n_rows = p->n_rows, W = p->W;
+    const int64_t nnz = p->nnz;
+    int32_t *err = nullptr, *big_list = nullptr, *big_count = nullptr, *tmp_cols = nullptr;
+    int32_t *f_mfma = nullptr, *f_csr = nullptr, *f_small = nullptr, *f_big = nullptr, *nnz_if = nullptr;
+    int32_t *f_short = nullptr, *n_seg = nullptr, *f_multi = nullptr, *n_slot = nullptr;
+    int64_t *scan_tmp = nullptr, *pos_a = nullptr, *pos_b = nullptr, *pos_c = nullptr, *pos_d = nullptr;
+    int64_t *totals_dev = nullptr;
+    int32_t h_err = 0, h_big = 0;
+    int64_t h_tot[8];
+    const int64_t scan_n = (int64_t)(n_rows > W ? n_rows : W) + 1;
+
+    HC_ALLOC(tmp, err, 2);
+    big_count = err + 1;
+    HC_TRY(hipMemsetAsync(err, 0, 2 * sizeof(int32_t), stream));
+    HC_TRY(launch_validate(n_rows, p->n_cols, nnz, p->rowptr, p->colind, err, stream));
+    HC_TRY(hipMemcpyAsync(&h_err, err, sizeof h_err, hipMemcpyDeviceToHost, stream));
+    HC_TRY(hipStreamSynchronize(stream));
+    if (h_err) {
+        set_error("invalid CSR: %s%s%s%s", (h_err & 1) ? "rowptr[0] != 0; " : "",
+                  (h_err & 2) ? "rowptr[n_rows] != nnz; " : "", (h_err & 4) ? "rowptr not non-decreasing; " : "",
+                  (h_err & 8) ? "column index out of range; " : "");
+        st = HCSPMM_EBADCSR;
+        goto fail;
+    }
+
+    HC_ALLOC(keep, p->ncols, W);
+    HC_ALLOC(keep, p->nnzw, W);
+    HC_ALLOC(keep, p->route, W);
+    HC_ALLOC(keep, p->wptr, (size_t)W + 1);
+    HC_ALLOC(keep, p->erc, nnz);
+    HC_ALLOC(tmp, tmp_cols, nnz);
+    HC_ALLOC(tmp, big_list, W);
+    HC_ALLOC(tmp, scan_tmp, scan_scratch_elems(scan_n));
+    HC_ALLOC(tmp, pos_a, scan_n + 1);
+    HC_ALLOC(tmp, pos_b, scan_n + 1);
+    HC_ALLOC(tmp, pos_c, scan_n + 1);
+    HC_ALLOC(tmp, pos_d, scan_n + 1);
+    HC_ALLOC(tmp, totals_dev, 8);
+
+    if (W > 0) {
+        // windows, condensing (Section IV-A)
+        HC_TRY(launch_window_nnz(W, n_rows, p->rowptr, p->nnzw, big_list, big_count, stream));
+        HC_TRY(launch_unique_small(W, n_rows, p->rowptr, p->colind, tmp_cols, p->ncols, stream));
+        HC_TRY(hipMemcpyAsync(&h_big, big_count, sizeof h_big, hipMemcpyDeviceToHost, stream));
+        HC_TRY(hipStreamSynchronize(stream));
+        HC_TRY(launch_unique_big(h_big, big_list, n_rows, p->n_cols, p->rowptr, p->colind, tmp_cols, p->ncols, stream));
+    }
+    HC_TRY(exclusive_scan_i32_i64(p->ncols, W, p->wptr, scan_tmp, stream));
+    HC_TRY(hipMemcpyAsync(&p->total_ncols, p->wptr + W, sizeof(int64_t), hipMemcpyDeviceToHost, stream));
+    HC_TRY(hipStreamSynchronize(stream));
+    HC_ALLOC(keep, p->wcols, p->total_ncols);
+    if (W > 0 && nnz > 0)
+        HC_TRY(launch_ecol(W, n_rows, p->rowptr, p->colind, tmp_cols, p->ncols, p->wptr, p->wcols, p->erc, stream));
+
+    // selection (Section IV-C) and the per-route window lists
+    HC_ALLOC(tmp, f_mfma, (size_t)W + 1);
+    HC_ALLOC(tmp, f_csr, (size_t)W + 1);
+    HC_ALLOC(tmp, f_small, (size_t)W + 1);
+    HC_ALLOC(tmp, f_big, (size_t)W + 1);
+    HC_ALLOC(tmp, nnz_if, (size_t)W + 1);
+    if (W > 0)
+        HC_TRY(launch_select(W, p->ncols, p->nnzw, p->coef[0], p->coef[1], p->coef[2], p->opt.route_mode, p->route,
+                             f_mfma, f_csr, f_small, f_big, nnz_if, stream));
+    HC_TRY(exclusive_scan_i32_i64(f_mfma, W, pos_a, scan_tmp, stream));
+    HC_TRY(hipMemcpyAsync(totals_dev + 0, pos_a + W, 8, hipMemcpyDeviceToDevice, stream));
+    HC_TRY(exclusive_scan_i32_i64(f_csr, W, pos_b, scan_tmp, stream));
+    HC_TRY(exclusive_scan_i32_i64(f_small, W, pos_c, scan_tmp, stream));
+    HC_TRY(hipMemcpyAsync(totals_dev + 1, pos_c + W, 8, hipMemcpyDeviceToDevice, stream));
+    HC_TRY(exclusive_scan_i32_i64(f_big, W, pos_d, scan_tmp, stream));
+    HC_TRY(hipMemcpyAsync(h_tot, totals_dev, 2 * sizeof(int64_t), hipMemcpyDeviceToHost, stream));
+    HC_TRY(hipStreamSynchronize(stream));
+    p->n_mfma = (int32_t)h_tot[0];
+    p->n_csr = W - p->n_mfma;
+    p->n_mfma_small = (int32_t)h_tot[1];
+    p->n_mfma_big = p->n_mfma - p->n_mfma_small;
+    HC_ALLOC(keep, p->mfma_windows, p->n_mfma);
+    HC_ALLOC(keep, p->csr_windows, p->n_csr);
+    HC_ALLOC(keep, p->mfma_small, p->n_mfma_small);
+    HC_ALLOC(keep, p->mfma_big, p->n_mfma_big);
+    HC_TRY(launch_compact_ids(W, f_mfma, pos_a, p->mfma_windows, stream));
+    HC_TRY(launch_compact_ids(W, f_csr, pos_b, p->csr_windows, stream));
+    HC_TRY(launch_compact_ids(W, f_small, pos_c, p->mfma_small, stream));
+    HC_TRY(launch_compact_ids(W, f_big, pos_d, p->mfma_big, stream));
+    HC_TRY(exclusive_scan_i32_i64(nnz_if, W, pos_a, scan_tmp, stream));
+    HC_TRY(hipMemcpyAsync(&p->nnz_mfma, pos_a + W, sizeof(int64_t), hipMemcpyDeviceToHost, stream));
+    HC_TRY(hipStreamSynchronize(stream));
+
+    // scalar-path launch tables
+    HC_ALLOC(tmp, f_short, (size_t)n_rows + 1);
+    HC_ALLOC(tmp, n_seg, (size_t)n_rows + 1);
+    HC_ALLOC(tmp, f_multi, (size_t)n_rows + 1);
+    HC_ALLOC(tmp, n_slot, (size_t)n_rows + 1);
+    HC_TRY(launch_row_class(n_rows, p->rowptr, p->route, f_short, n_seg, f_multi, n_slot, stream));
+    HC_TRY(exclusive_scan_i32_i64(f_short, n_rows, pos_a, scan_tmp, stream));
+    HC_TRY(hipMemcpyAsync(totals_dev + 0, pos_a + n_rows, 8, hipMemcpyDeviceToDevice, stream));
+    HC_TRY(exclusive_scan_i32_i64(n_seg, n_rows, pos_b, scan_tmp, stream));
+    HC_TRY(hipMemcpyAsync(totals_dev + 1, pos_b + n_rows, 8, hipMemcpyDeviceToDevice, stream));
+    HC_TRY(exclusive_scan_i32_i64(f_multi, n_rows, pos_c, scan_tmp, stream));
+    HC_TRY(hipMemcpyAsync(totals_dev + 2, pos_c + n_rows, 8, hipMemcpyDeviceToDevice, stream));
+    HC_TRY(exclusive_scan_i32_i64(n_slot, n_rows, pos_d, scan_tmp, stream));
+    HC_TRY(hipMemcpyAsync(totals_dev + 3, pos_d + n_rows, 8, hipMemcpyDeviceToDevice, stream));
+    HC_TRY(hipMemcpyAsync(h_tot, totals_dev, 4 * sizeof(int64_t), hipMemcpyDeviceToHost, stream));
+    HC_TRY(hipStreamSynchronize(stream));
+    p->n_short = (int32_t)h_tot[0];
+    p->n_segs = (int32_t)h_tot[1];
+    p->n_multi = (int32_t)h_tot[2];
+    p->n_slots = h_tot[3];
+    HC_ALLOC(keep, p->segs, p->n_segs);
+    HC_ALLOC(keep, p->multi, p->n_multi);
+    if (p->n_segs > 0)
+        HC_TRY(launch_build_segments(n_rows, p->rowptr, n_seg, pos_b, pos_c, pos_d, p->segs, p->multi, stream));
+    // Walking every row and skipping the ones another kernel owns is cheaper than an index list
+    // while most rows are short scalar-path rows; otherwise keep the explicit list.
+    if ((int64_t)p->n_short * 2 < n_rows) {
+        HC_ALLOC(keep, p->short_rows, p->n_short);
+        HC_TRY(launch_compact_ids(n_rows, f_short, pos_a, p->short_rows, stream));
+    } else {
+        p->short_rows = nullptr;
+    }
+    HC_TRY(hipStreamSynchronize(stream));
+    p->device_bytes = keep.bytes;
+    tmp.free_all();
+    return HCSPMM_OK;
+
+fail:
+    (void)hipStreamSynchronize(stream);
+    tmp.free_all();
+    keep.free_all();
+    return st;
+}
+
+static hcspmm_status run_spmm(const hcspmm_plan* plan, const SpmmArgs& a, hipStream_t stream)
+{
+    hcspmm_plan* p = const_cast<hcspmm_plan*>(plan);
+    // long rows cut into several segments need one partial row per segment
+    if (p->n_slots > 0 && p->partial_elems < p->n_slots * (int64_t)a.d) {
+        if (p->partial) { HC_HIP(hipStreamSynchronize(stream)); (void)hipFree(p->partial); p->partial = nullptr; }
+        const int64_t want = p->n_slots * (int64_t)a.d;
+        if (hipMalloc((void**)&p->partial, (size_t)want * sizeof(float)) != hipSuccess) {
+            (void)hipGetLastError();
+            p->partial = nullptr;
+            p->partial_elems = 0;
+            set_error("allocation of %lld floats for long-row partial sums failed", (long long)want);
+            return HCSPMM_EALLOC;
+        }
+        p->partial_elems = want;
+    }
+    // heaviest work first: long-row segments, then the matrix-path windows, then the short rows
+    HC_HIP(launch_csr_long(a, p->n_segs, p->segs, p->partial, stream));
+    HC_HIP(launch_reduce_partials(a, p->n_multi, p->multi, p->partial, stream));
+    HC_HIP(launch_mfma_big(a, p->n_mfma_big, p->mfma_big, p->ncols, p->wptr, p->wcols, p->erc, stream));
+    HC_HIP(launch_mfma_small(a, p->n_mfma_small, p->mfma_small, p->ncols, p->wptr, p->wcols, p->erc, stream));
+    if (p->short_rows) HC_HIP(launch_csr_short(a, p->n_short, p->short_rows, p->route, stream));
+    else if (p->n_short > 0) HC_HIP(launch_csr_short(a, p->n_rows, nullptr, p->route, stream));
+    return HCSPMM_OK;
+}
+
+}  // namespace hcspmm
+
+using namespace hcspmm;
+
+extern "C" {
+
+void hcspmm_default_options(hcspmm_options* opt)
+{
+    if (!opt) return;
+    memset(opt, 0, sizeof *opt);
+    opt->struct_size = (int32_t)sizeof *opt;
+    opt->window_rows = kH;
+    opt->route_mode = HCSPMM_ROUTE_HYBRID;
+    opt->mfma_dtype = HCSPMM_F32;
+    opt->d_hint = 0;
+    opt->use_custom_selector = 0;
+}
+
+hcspmm_status hcspmm_default_selector(int32_t mfma_dtype, int32_t d_hint, int64_t* coef)
+{
+    if (!coef) { set_error("coef is NULL"); return HCSPMM_EINVAL; }
+    if (!lookup_selector(mfma_dtype, d_hint, coef)) { set_error("unknown mfma_dtype %d", mfma_dtype); return HCSPMM_EINVAL; }
+    return HCSPMM_OK;
+}
+
+hcspmm_status hcspmm_prepare(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_t* d_rowptr,
+                             const int32_t* d_colind, const float* d_vals, const hcspmm_options* opt, void* stream,
+                             hcspmm_plan** out_plan)
+{
+    if (!out_plan) { set_error("out_plan is NULL"); return HCSPMM_EINVAL; }
+    *out_plan = nullptr;
+    if (n_rows < 0 || n_cols < 1 || nnz < 0) { set_error("negative size or n_cols < 1"); return HCSPMM_EINVAL; }
+    if (n_cols >= (1 << 27)) { set_error("n_cols must be below 2^27"); return HCSPMM_EUNSUPPORTED; }
+    if (nnz >= ((int64_t)1 << 31)) { set_error("nnz must be below 2^31"); return HCSPMM_EUNSUPPORTED; }
+    if (!d_rowptr || (nnz > 0 && (!d_colind || !d_vals))) { set_error("NULL CSR array"); return HCSPMM_EINVAL; }
+    hcspmm_options o;
+    hcspmm_default_options(&o);
+    if (opt) {
+        if (opt->struct_size != (int32_t)sizeof(hcspmm_options)) { set_error("options.struct_size mismatch"); return HCSPMM_EINVAL; }
+        o = *opt;
+    }
+    if (o.window_rows != kH) { set_error("only window_rows = 16 is implemented"); return HCSPMM_EUNSUPPORTED; }
+    if (o.route_mode < 0 || o.route_mode > 2) { set_error("bad route_mode"); return HCSPMM_EINVAL; }
+    if (o.mfma_dtype < 0 || o.mfma_dtype > 2) { set_error("bad mfma_dtype"); return HCSPMM_EINVAL; }
+    if (o.d_hint < 0) { set_error("bad d_hint"); return HCSPMM_EINVAL; }
+    hcspmm_plan* p = new (std::nothrow) hcspmm_plan();
+    if (!p) { set_error("host allocation failed"); return HCSPMM_EALLOC; }
+    memset(p, 0, sizeof *p);
+    p->H = kH; p->n_rows = n_rows; p->n_cols = n_cols; p->nnz = nnz;
+    p->W = (int32_t)(((int64_t)n_rows + kH - 1) / kH);
+    p->rowptr = d_rowptr; p->colind = d_colind; p->vals = d_vals;
+    p->opt = o;
+    if (o.use_custom_selector) {
+        for (int i = 0; i < 3; ++i) {
+            if (o.sel_coef[i] <= -((int64_t)1 << 40) || o.sel_coef[i] >= ((int64_t)1 << 40)) {
+                delete p;
+                set_error("selector coefficients must be below 2^40 in magnitude");
+                return HCSPMM_EINVAL;
+            }
+            p->coef[i] = o.sel_coef[i];
+        }
+    } else {
+        lookup_selector(o.mfma_dtype, o.d_hint, p->coef);
+    }
+    if (hipGetDevice(&p->device) != hipSuccess) { (void)hipGetLastError(); delete p; set_error("hipGetDevice failed"); return HCSPMM_EHIP; }
+    hcspmm_status st = build_plan(p, static_cast<hipStream_t>(stream));
+    if (st != HCSPMM_OK) { delete p; return st; }
+    *out_plan = p;
+    return HCSPMM_OK;
+}
+
+hcspmm_status hcspmm_plan_info(const hcspmm_plan* p, hcspmm_plan_info_t* info)
+{
+    if (!p || !info) { set_error("NULL argument"); return HCSPMM_EINVAL; }
+    memset(info, 0, sizeof *info);
+    info->window_rows = p->H; info->n_rows = p->n_rows; info->n_cols = p->n_cols; info->nnz = p->nnz;
+    info->n_windows = p->W; info->total_ncols = p->total_ncols;
+    info->n_mfma_windows = p->n_mfma; info->n_csr_windows = p->n_csr; info->nnz_mfma = p->nnz_mfma;
+    info->route_mode = p->opt.route_mode; info->mfma_dtype = p->opt.mfma_dtype; info->d_hint = p->opt.d_hint;
+    for (int i = 0; i < 3; ++i) info->sel_coef[i] = p->coef[i];
+    info->device_bytes = p->device_bytes + p->partial_elems * (int64_t)sizeof(float);
+    return HCSPMM_OK;
+}
+
+hcspmm_status hcspmm_plan_export(const hcspmm_plan* p, int32_t* ncols, int32_t* nnzw, uint8_t* route, int64_t* wptr,
+                                 int32_t* wcols, int32_t* ecol, int32_t* mfma_windows, int32_t* csr_windows)
+{
+    if (!p) { set_error("plan is NULL"); return HCSPMM_EINVAL; }
+    HC_HIP(hipDeviceSynchronize());
+    const size_t W = (size_t)p->W;
+    if (ncols && W) HC_HIP(hipMemcpy(ncols, p->ncols, W * 4, hipMemcpyDeviceToHost));
+    if (nnzw && W) HC_HIP(hipMemcpy(nnzw, p->nnzw, W * 4, hipMemcpyDeviceToHost));
+    if (route && W) HC_HIP(hipMemcpy(route, p->route, W, hipMemcpyDeviceToHost));
+    if (wptr) HC_HIP(hipMemcpy(wptr, p->wptr, (W + 1) * 8, hipMemcpyDeviceToHost));
+    if (wcols && p->total_ncols) HC_HIP(hipMemcpy(wcols, p->wcols, (size_t)p->total_ncols * 4, hipMemcpyDeviceToHost));
+    if (ecol && p->nnz) {
+        HC_HIP(hipMemcpy(ecol, p->erc, (size_t)p->nnz * 4, hipMemcpyDeviceToHost));
+        for (int64_t k = 0; k < p->nnz; ++k) ecol[k] >>= 4;    // drop the packed row-in-window
+    }
+    if (mfma_windows && p->n_mfma) HC_HIP(hipMemcpy(mfma_windows, p->mfma_windows, (size_t)p->n_mfma * 4, hipMemcpyDeviceToHost));
+    if (csr_windows && p->n_csr) HC_HIP(hipMemcpy(csr_windows, p->csr_windows, (size_t)p->n_csr * 4, hipMemcpyDeviceToHost));
+    return HCSPMM_OK;
+}
+
+static hcspmm_status check_dense(const char* name, const void* ptr, int64_t ld, int32_t width)
+{
+    if (!ptr) { set_error("%s is NULL", name); return HCSPMM_EINVAL; }
+    if (ld < width) { set_error("leading dimension of %s (%lld) is smaller than its width (%d)", name, (long long)ld, width); return HCSPMM_EINVAL; }
+    return HCSPMM_OK;
+}
+
+hcspmm_status hcspmm_spmm(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d, int32_t x_dtype, void* d_Y,
+                          int64_t ldy, int32_t y_dtype, void* stream)
+{
+    if (!plan) { set_error("plan is NULL"); return HCSPMM_EINVAL; }
+    if (d < 1 || d > (1 << 20)) { set_error("d must be in [1, 2^20]"); return HCSPMM_EINVAL; }
+    if (x_dtype < 0 || x_dtype > 2 || y_dtype < 0 || y_dtype > 2) { set_error("bad dtype"); return HCSPMM_EINVAL; }
+    if (y_dtype != HCSPMM_F32) { set_error("only fp32 output is implemented"); return HCSPMM_EUNSUPPORTED; }
+    if (x_dtype != HCSPMM_F32) { set_error("16-bit X is not implemented yet"); return HCSPMM_EUNSUPPORTED; }
+    if (plan->n_rows == 0) return HCSPMM_OK;
+    hcspmm_status st;
+    if ((st = check_dense("X", d_X, ldx, d)) != HCSPMM_OK) return st;
+    if ((st = check_dense("Y", d_Y, ldy, d)) != HCSPMM_OK) return st;
+    SpmmArgs a;
+    a.n_rows = plan->n_rows; a.rowptr = plan->rowptr; a.colind = plan->colind; a.vals = plan->vals;
+    a.X = d_X; a.ldx = ldx; a.d = d; a.x_dtype = x_dtype; a.Y = static_cast<float*>(d_Y); a.ldy = ldy; a.relu = 0;
+    return run_spmm(plan, a, static_cast<hipStream_t>(stream));
+}
+
+size_t hcspmm_gcn_workspace_bytes(const hcspmm_plan* plan, int32_t d_in, int32_t d_out)
+{
+    (void)d_in;
+    if (!plan || d_out < 1) return 0;
+    size_t b = (size_t)plan->n_cols * (size_t)d_out * sizeof(float);
+    return (b + 255) & ~(size_t)255;
+}
+
+hcspmm_status hcspmm_gemm_f32(int64_t m, int32_t k, int32_t n, const float* d_X, int64_t ldx, const float* d_W,
+                              int64_t ldw, float* d_T, int64_t ldt, void* stream)
+{
+    if (m < 0 || k < 0 || n < 0) { set_error("negative size"); return HCSPMM_EINVAL; }
+    if (m == 0 || n == 0) return HCSPMM_OK;
+    hcspmm_status st;
+    if (k > 0 && (st = check_dense("X", d_X, ldx, k)) != HCSPMM_OK) return st;
+    if (k > 0 && (st = check_dense("W", d_W, ldw, n)) != HCSPMM_OK) return st;
+    if ((st = check_dense("T", d_T, ldt, n)) != HCSPMM_OK) return st;
+    HC_HIP(launch_gemm_f32(m, k, n, d_X, ldx, d_W, ldw, d_T, ldt, static_cast<hipStream_t>(stream)));
+    return HCSPMM_OK;
+}
+
+hcspmm_status hcspmm_gcn_layer(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d_in, const void* d_W,
+                               int64_t ldw, int32_t d_out, void* d_Y, int64_t ldy, int32_t apply_relu,
+                               void* d_workspace, size_t workspace_bytes, void* stream)
+{
+    if (!plan) { set_error("plan is NULL"); return HCSPMM_EINVAL; }
+    if (d_in < 1 || d_out < 1 || d_in > (1 << 20) || d_out > (1 << 20)) { set_error("d_in, d_out must be in [1, 2^20]"); return HCSPMM_EINVAL; }
+    hcspmm_status st;
+    if ((st = check_dense("X", d_X, ldx, d_in)) != HCSPMM_OK) return st;
+    if ((st = check_dense("W", d_W, ldw, d_out)) != HCSPMM_OK) return st;
+    if ((st = check_dense("Y", d_Y, ldy, d_out)) != HCSPMM_OK) return st;
+    const size_t need = hcspmm_gcn_workspace_bytes(plan, d_in, d_out);
+    if (!d_workspace || workspace_bytes < need) { set_error("workspace too small: need %zu bytes", need); return HCSPMM_EINVAL; }
+    if (((uintptr_t)d_workspace & 255) != 0) { set_error("workspace must be 256-byte aligned"); return HCSPMM_EINVAL; }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float* T = static_cast<float*>(d_workspace);
+    HC_HIP(launch_gemm_f32(plan->n_cols, d_in, d_out, static_cast<const float*>(d_X), ldx,
+                           static_cast<const float*>(d_W), ldw, T, d_out, s));
+    if (plan->n_rows == 0) return HCSPMM_OK;
+    SpmmArgs a;
+    a.n_rows = plan->n_rows; a.rowptr = plan->rowptr; a.colind = plan->colind; a.vals = plan->vals;
+    a.X = T; a.ldx = d_out; a.d = d_out; a.x_dtype = HCSPMM_F32; a.Y = static_cast<float*>(d_Y); a.ldy = ldy;
+    a.relu = apply_relu ? 1 : 0;
+    return run_spmm(plan, a, s);
+}
+
+void hcspmm_plan_destroy(hcspmm_plan* plan)
+{
+    if (!plan) return;
+    (void)hipDeviceSynchronize();
+    free_plan_arrays(plan);
+    delete plan;
+}
+
+const char* hcspmm_status_string(hcspmm_status s)
+{
+    switch (s) {
+        case HCSPMM_OK: return "ok";
+        case HCSPMM_EINVAL: return "invalid argument";
+        case HCSPMM_EBADCSR: return "invalid CSR";
+        case HCSPMM_EALLOC: return "allocation failed";
+        case HCSPMM_EHIP: return "HIP runtime error";
+        case HCSPMM_EUNSUPPORTED: return "unsupported";
+    }
+    return "unknown status";
+}
+
+const char* hcspmm_last_error(void) { return g_err; }
+
+int32_t hcspmm_version(void) { return 100; }
+
+}  // extern "C"

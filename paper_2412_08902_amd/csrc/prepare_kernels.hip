@@ -1,0 +1,495 @@
+// Preprocessing kernels: row windows, condensing, window features, selection, launch tables.
+//
+// Section IV-A: A is cut into windows of 16 rows and each window's non-zero columns are moved to
+// the front.  Here "moved to the front" is materialised as (a) the ascending list of the
+// window's distinct column ids and (b) for every non-zero the position of its column in that
+// list.  Section IV-C: the per-window features (number of non-zero columns, sparsity) feed a
+// three-parameter linear model whose sign picks the path; it is evaluated in exact integers.
+#include "common.hpp"
+
+namespace hcspmm {
+
+// ------------------------------------------------------------------------------------------------
+// block-wide exclusive scan of one int per thread (NT threads, NT a multiple of 64, NT <= 1024)
+// ------------------------------------------------------------------------------------------------
+template <int NT>
+__device__ inline int block_exclusive_scan(int v, int* total, int* smem /* NT/64 + 1 ints */)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        int t = __shfl_up(inc, off, 64);
+        if (lane >= off) inc += t;
+    }
+    __syncthreads();                       // smem may still be in use by a previous call
+    if (lane == 63) smem[wave] = inc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int i = 0; i < NT / 64; ++i) { int t = smem[i]; smem[i] = run; run += t; }
+        smem[NT / 64] = run;
+    }
+    __syncthreads();
+    *total = smem[NT / 64];
+    return smem[wave] + inc - v;
+}
+
+// ------------------------------------------------------------------------------------------------
+// generic device-wide exclusive scan  int32[n] -> int64[n+1]
+// ------------------------------------------------------------------------------------------------
+constexpr int kScanThreads = 256;
+constexpr int kScanItems = 16;
+constexpr int kScanTile = kScanThreads * kScanItems;
+
+size_t scan_scratch_elems(int64_t n) { return (size_t)((n + kScanTile - 1) / kScanTile) + 2; }
+
+__global__ __launch_bounds__(kScanThreads) void k_scan_tile_sums(const int32_t* __restrict__ in, int64_t n,
+                                                                 int64_t* __restrict__ tile_sums)
+{
+    __shared__ long long part[kScanThreads / 64];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile;
+    long long acc = 0;
+    for (int i = 0; i < kScanItems; ++i) {
+        int64_t idx = base + (int64_t)i * kScanThreads + threadIdx.x;
+        if (idx < n) acc += in[idx];
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        long long t = 0;
+        for (int i = 0; i < kScanThreads / 64; ++i) t += part[i];
+        tile_sums[blockIdx.x] = t;
+    }
+}
+
+// one workgroup walks the tile sums in order (there are at most a few hundred thousand)
+__global__ __launch_bounds__(256) void k_scan_tile_offsets(int64_t* __restrict__ tile_sums, int64_t n_tiles)
+{
+    __shared__ long long wsum[4];
+    __shared__ long long carry_s;
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    for (int64_t base = 0; base < n_tiles; base += 256) {
+        int64_t idx = base + threadIdx.x;
+        long long v = idx < n_tiles ? tile_sums[idx] : 0;
+        long long inc = v;
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            long long t = __shfl_up(inc, off, 64);
+            if (lane >= off) inc += t;
+        }
+        if (lane == 63) wsum[wave] = inc;
+        __syncthreads();
+        long long wave_off = 0;
+        for (int i = 0; i < wave; ++i) wave_off += wsum[i];
+        long long carry = carry_s;
+        if (idx < n_tiles) tile_sums[idx] = carry + wave_off + inc - v;
+        __syncthreads();
+        if (threadIdx.x == 255) carry_s = carry + wave_off + inc;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) tile_sums[n_tiles] = carry_s;
+}
+
+__global__ __launch_bounds__(kScanThreads) void k_scan_apply(const int32_t* __restrict__ in, int64_t n,
+                                                             const int64_t* __restrict__ tile_offsets,
+                                                             int64_t n_tiles, int64_t* __restrict__ out)
+{
+    __shared__ int smem[kScanThreads / 64 + 1];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+    int v[kScanItems];
+    int local = 0;
+#pragma unroll
+    for (int i = 0; i < kScanItems; ++i) {
+        int64_t idx = base + i;
+        v[i] = idx < n ? in[idx] : 0;
+        local += v[i];
+    }
+    int total;
+    // int suffices inside one tile: every array scanned here sums to less than 2^31 overall
+    long long off = (long long)block_exclusive_scan<kScanThreads>(local, &total, smem);
+    long long run = tile_offsets[blockIdx.x] + off;
+#pragma unroll
+    for (int i = 0; i < kScanItems; ++i) {
+        int64_t idx = base + i;
+        if (idx < n) out[idx] = run;
+        run += v[i];
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) out[n] = tile_offsets[n_tiles];
+}
+
+hipError_t exclusive_scan_i32_i64(const int32_t* in, int64_t n, int64_t* out, int64_t* scratch, hipStream_t stream)
+{
+    if (n <= 0) return hipMemsetAsync(out, 0, sizeof(int64_t), stream);
+    const int64_t n_tiles = (n + kScanTile - 1) / kScanTile;
+    hipLaunchKernelGGL(k_scan_tile_sums, dim3((unsigned)n_tiles), dim3(kScanThreads), 0, stream, in, n, scratch);
+    hipLaunchKernelGGL(k_scan_tile_offsets, dim3(1), dim3(256), 0, stream, scratch, n_tiles);
+    hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)n_tiles), dim3(kScanThreads), 0, stream, in, n, scratch, n_tiles,
+                       out);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// CSR validation
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_validate_rowptr(int32_t n_rows, int64_t nnz, const int32_t* __restrict__ rowptr,
+                                                         int32_t* __restrict__ err)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i == 0) {
+        if (rowptr[0] != 0) atomicOr(err, 1);
+        if ((int64_t)rowptr[n_rows] != nnz) atomicOr(err, 2);
+    }
+    if (i < n_rows) {
+        int32_t a = rowptr[i], b = rowptr[i + 1];
+        if (a < 0 || b < a) atomicOr(err, 4);
+    }
+}
+
+__global__ __launch_bounds__(256) void k_validate_cols(int32_t n_cols, int64_t nnz, const int32_t* __restrict__ colind,
+                                                       int32_t* __restrict__ err)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    bool bad = false;
+    for (int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; k < nnz; k += stride) {
+        int32_t c = colind[k];
+        bad |= (c < 0 || c >= n_cols);
+    }
+    if (bad) atomicOr(err, 8);
+}
+
+hipError_t launch_validate(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
+                           int32_t* err_flag, hipStream_t s)
+{
+    unsigned g = (unsigned)(((int64_t)n_rows + 1 + 255) / 256);
+    hipLaunchKernelGGL(k_validate_rowptr, dim3(g), dim3(256), 0, s, n_rows, nnz, rowptr, err_flag);
+    if (nnz > 0) {
+        int64_t blocks = (nnz + 256 * 8 - 1) / (256 * 8);
+        if (blocks > 65536) blocks = 65536;
+        hipLaunchKernelGGL(k_validate_cols, dim3((unsigned)blocks), dim3(256), 0, s, n_cols, nnz, colind, err_flag);
+    }
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// per-window non-zero count, and the list of windows too large for the LDS sort
+// ------------------------------------------------------------------------------------------------
+__device__ inline void window_span(int32_t w, int32_t n_rows, const int32_t* __restrict__ rowptr, int32_t& s,
+                                   int32_t& e)
+{
+    int64_t r0 = (int64_t)w * kH;
+    int64_t r1 = r0 + kH;
+    if (r1 > n_rows) r1 = n_rows;
+    s = rowptr[r0];
+    e = rowptr[r1];
+}
+
+__global__ __launch_bounds__(256) void k_window_nnz(int32_t W, int32_t n_rows, const int32_t* __restrict__ rowptr,
+                                                    int32_t* __restrict__ nnzw, int32_t* __restrict__ big_list,
+                                                    int32_t* __restrict__ big_count)
+{
+    int32_t w = blockIdx.x * blockDim.x + threadIdx.x;
+    if (w >= W) return;
+    int32_t s, e;
+    window_span(w, n_rows, rowptr, s, e);
+    nnzw[w] = e - s;
+    if (e - s > kUniqueSmallCap) big_list[atomicAdd(big_count, 1)] = w;
+}
+
+hipError_t launch_window_nnz(int32_t W, int32_t n_rows, const int32_t* rowptr, int32_t* nnzw, int32_t* big_list,
+                             int32_t* big_count, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_window_nnz, dim3((W + 255) / 256), dim3(256), 0, s, W, n_rows, rowptr, nnzw, big_list,
+                       big_count);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// condensing, small windows: sort the window's column ids in LDS, keep the distinct ones
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_unique_small(int32_t W, int32_t n_rows, const int32_t* __restrict__ rowptr,
+                                                      const int32_t* __restrict__ colind,
+                                                      int32_t* __restrict__ tmp_cols, int32_t* __restrict__ ncols)
+{
+    __shared__ int32_t keys[kUniqueSmallCap];
+    __shared__ int smem[256 / 64 + 1];
+    const int32_t w = blockIdx.x;
+    int32_t s, e;
+    window_span(w, n_rows, rowptr, s, e);
+    const int32_t n = e - s;
+    if (n > kUniqueSmallCap) return;             // handled by k_unique_big
+    if (n == 0) {
+        if (threadIdx.x == 0) ncols[w] = 0;
+        return;
+    }
+    int P = 2;
+    while (P < n) P <<= 1;
+    for (int i = threadIdx.x; i < P; i += 256) keys[i] = i < n ? colind[s + i] : 0x7fffffff;
+    __syncthreads();
+    for (int k = 2; k <= P; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int t = threadIdx.x; t < (P >> 1); t += 256) {
+                int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+                int p = i | j;
+                bool up = (i & k) == 0;
+                int32_t a = keys[i], b = keys[p];
+                if ((a > b) == up) { keys[i] = b; keys[p] = a; }
+            }
+            __syncthreads();
+        }
+    }
+    // distinct values: thread t owns the contiguous slice [t*ipt, (t+1)*ipt)
+    const int ipt = (P + 255) / 256;
+    const int lo = threadIdx.x * ipt;
+    int cnt = 0;
+    for (int i = lo; i < lo + ipt && i < n; ++i) cnt += (i == 0 || keys[i] != keys[i - 1]) ? 1 : 0;
+    int total;
+    int off = block_exclusive_scan<256>(cnt, &total, smem);
+    for (int i = lo; i < lo + ipt && i < n; ++i)
+        if (i == 0 || keys[i] != keys[i - 1]) tmp_cols[(int64_t)s + off++] = keys[i];
+    if (threadIdx.x == 0) ncols[w] = total;
+}
+
+hipError_t launch_unique_small(int32_t W, int32_t n_rows, const int32_t* rowptr, const int32_t* colind,
+                               int32_t* tmp_cols, int32_t* ncols, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_unique_small, dim3(W), dim3(256), 0, s, W, n_rows, rowptr, colind, tmp_cols, ncols);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// condensing, large windows: an LDS bitmap over a range of 2^20 columns per pass
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void k_unique_big(const int32_t* __restrict__ big_list, int32_t n_rows,
+                                                     int32_t n_cols, const int32_t* __restrict__ rowptr,
+                                                     const int32_t* __restrict__ colind,
+                                                     int32_t* __restrict__ tmp_cols, int32_t* __restrict__ ncols)
+{
+    __shared__ uint32_t bm[kBitmapWords];
+    __shared__ int smem[1024 / 64 + 1];
+    constexpr int kBits = kBitmapWords * 32;
+    constexpr int kWordsPerThread = kBitmapWords / 1024;
+    const int32_t w = big_list[blockIdx.x];
+    int32_t s, e;
+    window_span(w, n_rows, rowptr, s, e);
+    int32_t running = 0;
+    for (int64_t base = 0; base < n_cols; base += kBits) {
+        for (int i = threadIdx.x; i < kBitmapWords; i += 1024) bm[i] = 0u;
+        __syncthreads();
+        for (int32_t k = s + threadIdx.x; k < e; k += 1024) {
+            int64_t c = (int64_t)colind[k] - base;
+            if (c >= 0 && c < kBits) atomicOr(&bm[c >> 5], 1u << (c & 31));
+        }
+        __syncthreads();
+        const int w0 = threadIdx.x * kWordsPerThread;
+        int cnt = 0;
+#pragma unroll 4
+        for (int i = 0; i < kWordsPerThread; ++i) cnt += __popc(bm[w0 + i]);
+        int total;
+        int off = block_exclusive_scan<1024>(cnt, &total, smem);
+        int32_t* out = tmp_cols + (int64_t)s + running + off;
+        for (int i = 0; i < kWordsPerThread; ++i) {
+            uint32_t bits = bm[w0 + i];
+            while (bits) {
+                int b = __ffs(bits) - 1;
+                bits &= bits - 1;
+                *out++ = (int32_t)(base + (int64_t)(w0 + i) * 32 + b);
+            }
+        }
+        running += total;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) ncols[w] = running;
+}
+
+hipError_t launch_unique_big(int32_t n_big, const int32_t* big_list, int32_t n_rows, int32_t n_cols,
+                             const int32_t* rowptr, const int32_t* colind, int32_t* tmp_cols, int32_t* ncols,
+                             hipStream_t s)
+{
+    if (n_big <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_unique_big, dim3(n_big), dim3(1024), 0, s, big_list, n_rows, n_cols, rowptr, colind, tmp_cols,
+                       ncols);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// compact the distinct-column lists and give every non-zero its condensed column
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_ecol(int32_t n_rows, const int32_t* __restrict__ rowptr,
+                                              const int32_t* __restrict__ colind,
+                                              const int32_t* __restrict__ tmp_cols, const int32_t* __restrict__ ncols,
+                                              const int64_t* __restrict__ wptr, int32_t* __restrict__ wcols,
+                                              int32_t* __restrict__ erc)
+{
+    __shared__ int32_t ucols[kEcolLdsCap];
+    __shared__ int32_t rp[kH + 1];
+    const int32_t w = blockIdx.x;
+    int32_t s, e;
+    window_span(w, n_rows, rowptr, s, e);
+    if (e == s) return;
+    const int32_t nc = ncols[w];
+    const int64_t wp = wptr[w];
+    const int32_t* __restrict__ src = tmp_cols + (int64_t)s;
+    if (threadIdx.x <= kH) {
+        int64_t r = (int64_t)w * kH + threadIdx.x;
+        if (r > n_rows) r = n_rows;
+        rp[threadIdx.x] = rowptr[r];
+    }
+    const bool in_lds = nc <= kEcolLdsCap;
+    for (int i = threadIdx.x; i < nc; i += 256) {
+        int32_t c = src[i];
+        wcols[wp + i] = c;
+        if (in_lds) ucols[i] = c;
+    }
+    __syncthreads();
+    for (int32_t k = s + threadIdx.x; k < e; k += 256) {
+        const int32_t c = colind[k];
+        int lo = 0, hi = nc - 1;               // c is in the list by construction
+        if (in_lds) {
+            while (lo < hi) { int mid = (lo + hi) >> 1; if (ucols[mid] < c) lo = mid + 1; else hi = mid; }
+        } else {
+            while (lo < hi) { int mid = (lo + hi) >> 1; if (src[mid] < c) lo = mid + 1; else hi = mid; }
+        }
+        int r = 0;                              // row of k inside the window: last r with rp[r] <= k
+#pragma unroll
+        for (int step = 8; step > 0; step >>= 1)
+            if (r + step < kH && rp[r + step] <= k) r += step;
+        erc[k] = (lo << 4) | r;
+    }
+}
+
+hipError_t launch_ecol(int32_t W, int32_t n_rows, const int32_t* rowptr, const int32_t* colind,
+                       const int32_t* tmp_cols, const int32_t* ncols, const int64_t* wptr, int32_t* wcols,
+                       int32_t* erc, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_ecol, dim3(W), dim3(256), 0, s, n_rows, rowptr, colind, tmp_cols, ncols, wptr, wcols, erc);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// selection (Section IV-C): z' = c0*H*ncols^2 + c1*(H*ncols - nnzw) + c2*H*ncols ; matrix path iff z' < 0
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_select(int32_t W, const int32_t* __restrict__ ncols,
+                                                const int32_t* __restrict__ nnzw, long long c0, long long c1,
+                                                long long c2, int32_t mode, uint8_t* __restrict__ route,
+                                                int32_t* __restrict__ f_mfma, int32_t* __restrict__ f_csr,
+                                                int32_t* __restrict__ f_small, int32_t* __restrict__ f_big,
+                                                int32_t* __restrict__ nnz_if_mfma)
+{
+    int32_t w = blockIdx.x * blockDim.x + threadIdx.x;
+    if (w >= W) return;
+    const long long nc = ncols[w], nz = nnzw[w];
+    int r = 0;
+    if (nc > 0) {
+        if (mode == HCSPMM_ROUTE_ALL_MFMA) r = 1;
+        else if (mode == HCSPMM_ROUTE_HYBRID) {
+            // |c*| < 2^40 and H*ncols^2 < 2^58: 128-bit integers keep the sign exact
+            const __int128 hn = (__int128)kH * nc;
+            const __int128 z = (__int128)c0 * hn * nc + (__int128)c1 * (hn - nz) + (__int128)c2 * hn;
+            r = z < 0 ? 1 : 0;
+        }
+    }
+    route[w] = (uint8_t)r;
+    f_mfma[w] = r;
+    f_csr[w] = 1 - r;
+    f_small[w] = (r && nc <= kMfmaSmallMaxCols) ? 1 : 0;
+    f_big[w] = (r && nc > kMfmaSmallMaxCols) ? 1 : 0;
+    nnz_if_mfma[w] = r ? (int32_t)nz : 0;
+}
+
+hipError_t launch_select(int32_t W, const int32_t* ncols, const int32_t* nnzw, int64_t c0, int64_t c1, int64_t c2,
+                         int32_t mode, uint8_t* route, int32_t* f_mfma, int32_t* f_csr, int32_t* f_small,
+                         int32_t* f_big, int32_t* nnz_if_mfma, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_select, dim3((W + 255) / 256), dim3(256), 0, s, W, ncols, nnzw, (long long)c0, (long long)c1,
+                       (long long)c2, mode, route, f_mfma, f_csr, f_small, f_big, nnz_if_mfma);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void k_compact_ids(int32_t n, const int32_t* __restrict__ flags,
+                                                     const int64_t* __restrict__ pos, int32_t* __restrict__ out)
+{
+    int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n && flags[i]) out[pos[i]] = i;
+}
+
+hipError_t launch_compact_ids(int32_t n, const int32_t* flags, const int64_t* pos, int32_t* out, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_compact_ids, dim3((n + 255) / 256), dim3(256), 0, s, n, flags, pos, out);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// scalar-path launch tables: short rows, and segments of long rows
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_row_class(int32_t n_rows, const int32_t* __restrict__ rowptr,
+                                                   const uint8_t* __restrict__ route, int32_t* __restrict__ f_short,
+                                                   int32_t* __restrict__ n_seg, int32_t* __restrict__ f_multi,
+                                                   int32_t* __restrict__ n_slot)
+{
+    int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_rows) return;
+    const int32_t len = rowptr[i + 1] - rowptr[i];
+    const bool csr = route[i / kH] == 0;
+    const bool is_long = csr && len > kLongRow;
+    const int32_t ns = is_long ? (len + kSegLen - 1) / kSegLen : 0;
+    f_short[i] = (csr && !is_long) ? 1 : 0;
+    n_seg[i] = ns;
+    f_multi[i] = ns > 1 ? 1 : 0;
+    n_slot[i] = ns > 1 ? ns : 0;
+}
+
+hipError_t launch_row_class(int32_t n_rows, const int32_t* rowptr, const uint8_t* route, int32_t* f_short,
+                            int32_t* n_seg, int32_t* f_multi, int32_t* n_slot, hipStream_t s)
+{
+    if (n_rows <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_row_class, dim3((n_rows + 255) / 256), dim3(256), 0, s, n_rows, rowptr, route, f_short, n_seg,
+                       f_multi, n_slot);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void k_build_segments(int32_t n_rows, const int32_t* __restrict__ rowptr,
+                                                        const int32_t* __restrict__ n_seg,
+                                                        const int64_t* __restrict__ seg_pos,
+                                                        const int64_t* __restrict__ multi_pos,
+                                                        const int64_t* __restrict__ slot_pos,
+                                                        Segment* __restrict__ segs, MultiRow* __restrict__ multi)
+{
+    int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_rows) return;
+    const int32_t ns = n_seg[i];
+    if (ns == 0) return;
+    const int32_t s = rowptr[i], e = rowptr[i + 1];
+    const int64_t sp = seg_pos[i];
+    const int32_t slot0 = ns > 1 ? (int32_t)slot_pos[i] : -1;
+    for (int32_t q = 0; q < ns; ++q) {
+        Segment sg;
+        sg.row = i;
+        sg.k_begin = s + q * kSegLen;
+        sg.k_end = min(e, sg.k_begin + kSegLen);
+        sg.slot = ns > 1 ? slot0 + q : -1;
+        segs[sp + q] = sg;
+    }
+    if (ns > 1) {
+        MultiRow m;
+        m.row = i; m.first_slot = slot0; m.n_slots = ns; m.pad = 0;
+        multi[multi_pos[i]] = m;
+    }
+}
+
+hipError_t launch_build_segments(int32_t n_rows, const int32_t* rowptr, const int32_t* n_seg, const int64_t* seg_pos,
+                                 const int64_t* multi_pos, const int64_t* slot_pos, Segment* segs, MultiRow* multi,
+                                 hipStream_t s)
+{
+    if (n_rows <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_build_segments, dim3((n_rows + 255) / 256), dim3(256), 0, s, n_rows, rowptr, n_seg, seg_pos,
+                       multi_pos, slot_pos, segs, multi);
+    return hipGetLastError();
+}
+
+}  // namespace hcspmm

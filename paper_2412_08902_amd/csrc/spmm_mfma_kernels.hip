@@ -1,0 +1,283 @@
+// Matrix path: a row window's condensed 16 x ncols tile times the gathered X rows on the MFMA
+// units (Alg. 2 gives the scheme: densify a slice of the condensed window into on-chip memory,
+// fetch the matching X rows, multiply on the matrix cores, accumulate in registers, store the
+// 16 x d result; Alg. 4's cooperative loading becomes the lane mapping below).
+//
+// fp32 path: v_mfma_f32_16x16x4_f32, i.e. D(16x16) += A(16x4) * B(4x16) per wave, true fp32.
+// Operand layout per lane l (0..63):  A: row l%16, k = l/16.   B: k = l/16, column l%16.
+//                                      D: column l%16, rows 4*(l/16) + {0,1,2,3} in 4 registers.
+// A K-step therefore consumes 4 condensed columns: the lanes with the same l/16 read the same X
+// row, 16 lanes wide.  Every lane reads VW consecutive floats of that row, which spreads them
+// over VW accumulator tiles (tile t holds the output columns  base + VW*(l%16) + t), so a whole
+// 16*VW-float stretch of the X row is one contiguous, coalesced read and the results go back to Y
+// as VW-wide vector stores.  Each distinct column of the window is fetched once per window.
+//
+// The condensed A tile is rebuilt on chip from the window's non-zeros (value, condensed column,
+// row): a k-major LDS image  tile[k*16 + row], zeroed and then filled with LDS float adds, so
+// duplicate entries accumulate.  Read back, lane l of K-step q needs tile[(4q + l/16)*16 + l%16]
+// = tile[64q + l]: conflict-free.
+#include "common.hpp"
+
+namespace hcspmm {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+template <int VW> struct XVec;
+template <> struct XVec<4> { using type = float4; };
+template <> struct XVec<2> { using type = float2; };
+template <> struct XVec<1> { using type = float; };
+
+template <int VW>
+__device__ inline void load_x(const float* __restrict__ p, bool ok, float (&x)[VW])
+{
+    using V = typename XVec<VW>::type;
+    if (ok) {
+        V v = *reinterpret_cast<const V*>(p);
+        const float* f = reinterpret_cast<const float*>(&v);
+#pragma unroll
+        for (int i = 0; i < VW; ++i) x[i] = f[i];
+    } else {
+#pragma unroll
+        for (int i = 0; i < VW; ++i) x[i] = 0.f;
+    }
+}
+
+// One block of up to 16 K-steps (64 condensed columns starting at tile column kb) for one wave.
+//   tile   : LDS image of the A chunk (k-major), kb indexes into it
+//   cols   : this wave's 64 column ids for the block, lane l holds column kb + l (or -1 past the end)
+template <int VW, int NG>
+__device__ inline void mfma_block(const float* __restrict__ tile, int kb, int nsteps, int32_t mycol, int lane,
+                                  const float* __restrict__ X, int64_t ldx, int d, v4f (&acc)[NG][VW])
+{
+    const int j = lane & 15, kk = lane >> 4;
+    constexpr int U = 4;                                   // K-steps whose X loads are issued together
+    for (int q0 = 0; q0 < nsteps; q0 += U) {
+        float xa[U][NG][VW];
+        float av[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int q = q0 + u;
+            const bool step_ok = q < nsteps;
+            const int32_t c = __shfl(mycol, 4 * (q & 15) + kk, 64);
+            av[u] = step_ok ? tile[(kb + 4 * q) * 16 + lane] : 0.f;
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                const int col = g * 16 * VW + VW * j;
+                load_x<VW>(X + (int64_t)c * ldx + col, step_ok && c >= 0 && col < d, xa[u][g]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int g = 0; g < NG; ++g)
+#pragma unroll
+                for (int t = 0; t < VW; ++t)
+                    acc[g][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u], xa[u][g][t], acc[g][t], 0, 0, 0);
+    }
+}
+
+template <int VW, int NG>
+__device__ inline void store_tile(const v4f (&acc)[NG][VW], int lane, int32_t r0, int32_t n_rows, float* __restrict__ Y,
+                                  int64_t ldy, int d, int relu)
+{
+    using V = typename XVec<VW>::type;
+    const int j = lane & 15, kk = lane >> 4;
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        const int col = g * 16 * VW + VW * j;
+        if (col >= d) continue;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int32_t row = r0 + 4 * kk + r;
+            if (row >= n_rows) continue;
+            V v;
+            float* f = reinterpret_cast<float*>(&v);
+#pragma unroll
+            for (int t = 0; t < VW; ++t) {
+                float y = acc[g][t][r];
+                f[t] = relu ? fmaxf(y, 0.f) : y;
+            }
+            *reinterpret_cast<V*>(Y + (int64_t)row * ldy + col) = v;
+        }
+    }
+}
+
+// ---- wave per window --------------------------------------------------------------------------
+// Four independent waves per workgroup; each owns a private kKcSmall x 16 LDS tile and one window.
+// No workgroup barrier: LDS traffic of a wave is issued and completed in program order.
+template <int VW, int NG>
+__global__ __launch_bounds__(256) void k_mfma_small(int32_t n_list, const int32_t* __restrict__ win_list,
+                                                    const int32_t* __restrict__ ncols,
+                                                    const int64_t* __restrict__ wptr,
+                                                    const int32_t* __restrict__ wcols,
+                                                    const int32_t* __restrict__ erc, int col0, SpmmArgs a)
+{
+    __shared__ float tiles[4][kKcSmall * 16];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t item = (int64_t)blockIdx.x * 4 + wave;
+    if (item >= n_list) return;
+    const int32_t w = win_list[item];
+    const int32_t r0 = w * kH;
+    const int32_t s = a.rowptr[r0];
+    const int32_t e = a.rowptr[min(r0 + kH, a.n_rows)];
+    const int32_t nc = ncols[w];
+    const int64_t wp = wptr[w];
+    float* __restrict__ tile = tiles[wave];
+    const float* __restrict__ X = static_cast<const float*>(a.X) + col0;
+    const int d = min(a.d - col0, NG * 16 * VW);
+    v4f acc[NG][VW];
+#pragma unroll
+    for (int g = 0; g < NG; ++g)
+#pragma unroll
+        for (int t = 0; t < VW; ++t) acc[g][t] = (v4f){0.f, 0.f, 0.f, 0.f};
+
+    for (int32_t kc0 = 0; kc0 < nc; kc0 += kKcSmall) {
+        const int kend = min(kKcSmall, nc - kc0);
+        const int32_t mycol = lane < kend ? wcols[wp + kc0 + lane] : -1;
+        for (int i = lane * 4; i < kKcSmall * 16; i += 256)
+            *reinterpret_cast<float4*>(&tile[i]) = make_float4(0.f, 0.f, 0.f, 0.f);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        for (int32_t k = s + lane; k < e; k += 64) {
+            const int32_t p = erc[k];
+            const int32_t ec = (p >> 4) - kc0;
+            if (ec >= 0 && ec < kKcSmall) atomicAdd(&tile[ec * 16 + (p & 15)], a.vals[k]);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        mfma_block<VW, NG>(tile, 0, (kend + 3) >> 2, mycol, lane, X, a.ldx, d, acc);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    }
+    store_tile<VW, NG>(acc, lane, r0, a.n_rows, a.Y + col0, a.ldy, d, a.relu);
+}
+
+// ---- workgroup per window ---------------------------------------------------------------------
+// For windows with many condensed columns: all four waves stage a kKcBig-column chunk together,
+// split its K-steps between them (blocks of 64 columns, round-robin) and add their partial tiles
+// through LDS at the end, in wave order.
+template <int VW, int NG>
+__global__ __launch_bounds__(256) void k_mfma_big(const int32_t* __restrict__ win_list,
+                                                  const int32_t* __restrict__ ncols, const int64_t* __restrict__ wptr,
+                                                  const int32_t* __restrict__ wcols, const int32_t* __restrict__ erc,
+                                                  int col0, SpmmArgs a)
+{
+    __shared__ float tile[kKcBig * 16];
+    static_assert(kKcBig * 16 >= 4 * NG * VW * 4 * 64, "reduction scratch must fit in the tile");
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int32_t w = win_list[blockIdx.x];
+    const int32_t r0 = w * kH;
+    const int32_t s = a.rowptr[r0];
+    const int32_t e = a.rowptr[min(r0 + kH, a.n_rows)];
+    const int32_t nc = ncols[w];
+    const int64_t wp = wptr[w];
+    const float* __restrict__ X = static_cast<const float*>(a.X) + col0;
+    const int d = min(a.d - col0, NG * 16 * VW);
+    v4f acc[NG][VW];
+#pragma unroll
+    for (int g = 0; g < NG; ++g)
+#pragma unroll
+        for (int t = 0; t < VW; ++t) acc[g][t] = (v4f){0.f, 0.f, 0.f, 0.f};
+
+    for (int32_t kc0 = 0; kc0 < nc; kc0 += kKcBig) {
+        const int kend = min(kKcBig, nc - kc0);
+        for (int i = threadIdx.x * 4; i < kKcBig * 16; i += 1024)
+            *reinterpret_cast<float4*>(&tile[i]) = make_float4(0.f, 0.f, 0.f, 0.f);
+        __syncthreads();
+        for (int32_t k = s + threadIdx.x; k < e; k += 256) {
+            const int32_t p = erc[k];
+            const int32_t ec = (p >> 4) - kc0;
+            if (ec >= 0 && ec < kKcBig) atomicAdd(&tile[ec * 16 + (p & 15)], a.vals[k]);
+        }
+        __syncthreads();
+        for (int kb = wave * 64; kb < kend; kb += 256) {
+            const int32_t mycol = kb + lane < kend ? wcols[wp + kc0 + kb + lane] : -1;
+            const int nsteps = (min(64, kend - kb) + 3) >> 2;
+            mfma_block<VW, NG>(tile, kb, nsteps, mycol, lane, X, a.ldx, d, acc);
+        }
+        __syncthreads();
+    }
+    // add the four waves' partial tiles: wave v parks its registers at slot v, then every lane of
+    // wave 0 sums slots 0..3 in order
+    float* __restrict__ slot = tile + (size_t)wave * (NG * VW * 4 * 64);
+#pragma unroll
+    for (int g = 0; g < NG; ++g)
+#pragma unroll
+        for (int t = 0; t < VW; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) slot[((g * VW + t) * 4 + r) * 64 + lane] = acc[g][t][r];
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+        for (int g = 0; g < NG; ++g)
+#pragma unroll
+            for (int t = 0; t < VW; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float sum = 0.f;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) sum += tile[(size_t)v * (NG * VW * 4 * 64) + ((g * VW + t) * 4 + r) * 64 + lane];
+                    acc[g][t][r] = sum;
+                }
+        store_tile<VW, NG>(acc, lane, r0, a.n_rows, a.Y + col0, a.ldy, d, a.relu);
+    }
+}
+
+// ---- dispatch ---------------------------------------------------------------------------------
+struct MfmaShape { int vw, ng; };
+
+static MfmaShape pick_mfma_shape(const SpmmArgs& a)
+{
+    const uintptr_t px = (uintptr_t)a.X, py = (uintptr_t)a.Y;
+    int vw = 1;
+    if (a.d % 4 == 0 && a.ldx % 4 == 0 && a.ldy % 4 == 0 && px % 16 == 0 && py % 16 == 0) vw = 4;
+    else if (a.d % 2 == 0 && a.ldx % 2 == 0 && a.ldy % 2 == 0 && px % 8 == 0 && py % 8 == 0) vw = 2;
+    // prefer the narrowest vector that still covers d in one 16-lane stretch (no idle lanes)
+    while (vw > 1 && 16 * (vw / 2) >= a.d) vw >>= 1;
+    const int groups = (a.d + 16 * vw - 1) / (16 * vw);
+    int ng = groups >= 4 ? 4 : (groups >= 2 ? 2 : 1);
+    return {vw, ng};
+}
+
+#define HC_MFMA_DISPATCH(FN)                                                                       \
+    switch (sh.vw * 10 + sh.ng) {                                                                  \
+        case 41: FN(4, 1); break;                                                                  \
+        case 42: FN(4, 2); break;                                                                  \
+        case 44: FN(4, 4); break;                                                                  \
+        case 21: FN(2, 1); break;                                                                  \
+        case 22: FN(2, 2); break;                                                                  \
+        case 24: FN(2, 4); break;                                                                  \
+        case 11: FN(1, 1); break;                                                                  \
+        case 12: FN(1, 2); break;                                                                  \
+        default: FN(1, 4); break;                                                                  \
+    }
+
+hipError_t launch_mfma_small(const SpmmArgs& a, int32_t n_list, const int32_t* win_list, const int32_t* ncols,
+                             const int64_t* wptr, const int32_t* wcols, const int32_t* erc, hipStream_t s)
+{
+    if (n_list <= 0) return hipSuccess;
+    const MfmaShape sh = pick_mfma_shape(a);
+    const int span = sh.ng * 16 * sh.vw;                       // output columns per launch
+    for (int col0 = 0; col0 < a.d; col0 += span) {
+#define HC_LAUNCH_MS(V, G)                                                                         \
+    hipLaunchKernelGGL((k_mfma_small<V, G>), dim3((unsigned)((n_list + 3) / 4)), dim3(256), 0, s, n_list, win_list,  \
+                       ncols, wptr, wcols, erc, col0, a)
+        HC_MFMA_DISPATCH(HC_LAUNCH_MS)
+#undef HC_LAUNCH_MS
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_mfma_big(const SpmmArgs& a, int32_t n_list, const int32_t* win_list, const int32_t* ncols,
+                           const int64_t* wptr, const int32_t* wcols, const int32_t* erc, hipStream_t s)
+{
+    if (n_list <= 0) return hipSuccess;
+    const MfmaShape sh = pick_mfma_shape(a);
+    const int span = sh.ng * 16 * sh.vw;
+    for (int col0 = 0; col0 < a.d; col0 += span) {
+#define HC_LAUNCH_MB(V, G)                                                                         \
+    hipLaunchKernelGGL((k_mfma_big<V, G>), dim3(n_list), dim3(256), 0, s, win_list, ncols, wptr, wcols, erc, col0, a)
+        HC_MFMA_DISPATCH(HC_LAUNCH_MB)
+#undef HC_LAUNCH_MB
+    }
+    return hipGetLastError();
+}
+
+}  // namespace hcspmm

@@ -1,0 +1,62 @@
+"""GPU parity of the dense update (MFMA GEMM) and the fused GCN layer against the CPU oracle."""
+import numpy as np
+import pytest
+
+import oracle
+from workloads import make_config, dense_normal, glorot_uniform, chung_lu_graph, gcn_normalise, tiny_random_csr
+from gpu_util import device_graph, assert_close
+
+pytestmark = pytest.mark.gpu
+TOL_F32 = 1e-5
+
+
+@pytest.mark.parametrize("m,k,n", [(1, 1, 1), (130, 17, 5), (257, 602, 128), (128, 16, 128), (300, 64, 200),
+                                   (1000, 33, 64), (64, 250, 130)])
+def test_gemm(m, k, n):
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    X, W = dense_normal(m, k, seed=m + k), dense_normal(k, n, seed=k + n)
+    T = torch.full((m, n + 3), -5.0, device="cuda")
+    hc.hcspmm_gemm_f32(torch.from_numpy(X).cuda(), torch.from_numpy(W).cuda(), T[:, :n])
+    torch.cuda.synchronize()
+    got = T.cpu().numpy().astype(np.float64)
+    assert np.all(got[:, n:] == -5.0)
+    ref = oracle.gemm(X, W)
+    bound = oracle.gemm(X, W, use_abs=True)
+    assert_close(got[:, :n], ref, bound, TOL_F32)
+
+
+def run_layer(g, X, W, mode, relu=True):
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    rp, ci, va = device_graph(g)
+    plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, route_mode=mode, d_hint=W.shape[1])
+    ws = torch.empty(hc.hcspmm_gcn_workspace_bytes(plan, X.shape[1], W.shape[1]), dtype=torch.uint8, device="cuda")
+    Y = torch.full((g.n_rows, W.shape[1]), -3.0, device="cuda")
+    hc.hcspmm_gcn_layer(plan, torch.from_numpy(X).cuda(), torch.from_numpy(W).cuda(), Y, ws, apply_relu=relu)
+    torch.cuda.synchronize()
+    out = Y.cpu().numpy().astype(np.float64)
+    plan.destroy()
+    return out
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("relu", [True, False])
+def test_layer_small(mode, relu):
+    g = gcn_normalise(chung_lu_graph(700, 9000, 2.0, seed=21))
+    X, W = dense_normal(700, 50, seed=22), glorot_uniform(50, 24, seed=23)
+    got = run_layer(g, X, W, mode, relu)
+    ref = oracle.gcn_layer(g.rowptr, g.colind, g.vals, X, W, relu=relu)
+    bound = oracle.gcn_layer(g.rowptr, g.colind, g.vals, X, W, use_abs=True)
+    # two chained fp32 stages: the dense product's rounding is amplified by at most |A|
+    assert_close(got, ref, bound, 2 * TOL_F32)
+    if relu:
+        assert got.min() >= 0.0 and (got == 0).any()
+
+
+def test_layer_scaled_config5():
+    g, X, W = make_config("C5", scale=0.01)
+    got = run_layer(g, X, W, 0)
+    ref = oracle.gcn_layer(g.rowptr, g.colind, g.vals, X, W)
+    bound = oracle.gcn_layer(g.rowptr, g.colind, g.vals, X, W, use_abs=True)
+    assert_close(got, ref, bound, 2 * TOL_F32)

@@ -1,0 +1,109 @@
+"""GPU parity of the preprocessing plan: every exported index array bit-exact against the CPU re-derivation."""
+import numpy as np
+import pytest
+
+import oracle
+from workloads import tiny_random_csr, make_config, CSRGraph, sbm_graph
+from gpu_util import device_graph
+
+pytestmark = pytest.mark.gpu
+
+KEYS = ["ncols", "nnzw", "route", "wptr", "wcols", "ecol", "mfma_windows", "csr_windows"]
+
+
+def gpu_plan(g, mode=0, sel_coef=None, d_hint=64, mfma_dtype=0):
+    import paper_2412_08902_amd.binding as hc
+    rp, ci, va = device_graph(g)
+    plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, route_mode=mode, sel_coef=sel_coef, d_hint=d_hint,
+                             mfma_dtype=mfma_dtype)
+    info = hc.hcspmm_plan_info(plan)
+    out = hc.hcspmm_plan_export(plan)
+    plan.destroy()
+    return out, info
+
+
+def check_plan(g, mode=0, sel_coef=None, d_hint=64):
+    got, info = gpu_plan(g, mode, sel_coef, d_hint)
+    coef = info["sel_coef"]
+    if sel_coef is not None:
+        assert coef == list(sel_coef)
+    want = oracle.derive_plan_vectorised(g.rowptr, g.colind, coef, mode=mode, n_cols=g.n_cols)
+    assert got["H"] == want["H"] == 16 and got["W"] == want["W"]
+    for k in KEYS:
+        assert got[k].dtype == want[k].dtype, k
+        assert np.array_equal(got[k], want[k]), k
+    assert info["total_ncols"] == want["wptr"][-1]
+    assert info["nnz_mfma"] == int(want["nnzw"][want["route"] == 1].sum())
+    return got, info
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("case", [(83, 70, 0.12, True, False), (200, 5000, 0.01, False, True),
+                                  (16, 16, 1.0, True, False), (15, 90, 0.0, True, False),
+                                  (1000, 300, 0.3, True, False)])
+def test_small_plans(case, mode):
+    n, m, dens, srt, dup = case
+    g = tiny_random_csr(n, m, dens, seed=n + m, sorted_rows=srt, duplicates=dup)
+    check_plan(g, mode, sel_coef=[3, 500, -420])
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3"])
+def test_config_plans_default_selector(name):
+    g, _, _ = make_config(name, with_dense=False)
+    check_plan(g)
+
+
+def test_plan_with_windows_beyond_lds_sort_and_many_columns():
+    # windows with more non-zeros than the LDS sort handles, over more columns than one bitmap pass
+    n, m = 64, 3_000_000
+    rng = np.random.default_rng(3)
+    lens = np.full(n, 5)
+    lens[0:16] = 700                      # window 0: 11,200 non-zeros
+    lens[40] = 30000                      # window 2: one huge row
+    cols = [np.sort(rng.choice(m, size=l, replace=False)) for l in lens]
+    cols[3] = cols[2].copy()              # shared columns inside window 0
+    rp = np.zeros(n + 1, np.int32)
+    np.cumsum(lens, out=rp[1:])
+    g = CSRGraph(n, m, rp, np.concatenate(cols).astype(np.int32), np.ones(int(lens.sum()), np.float32))
+    got, _ = check_plan(g, sel_coef=[1, 100, -50])
+    assert got["ncols"][0] == 700 * 15 and got["nnzw"][0] == 11200
+
+
+def test_selector_routes_change_with_coefficients():
+    g = sbm_graph(32, 64, 0.25, 4.0, seed=8)
+    a, _ = check_plan(g, sel_coef=[0, 0, 1])        # z = 1 > 0 everywhere: scalar path
+    b, _ = check_plan(g, sel_coef=[0, 0, -1])       # z < 0 everywhere: matrix path
+    c, _ = check_plan(g, sel_coef=[1, 0, -125])     # ncols < 125
+    assert a["route"].sum() == 0 and b["route"].all() and 0 < c["route"].sum() < c["W"]
+
+
+def test_errors_are_status_codes():
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    g = tiny_random_csr(40, 30, 0.2, seed=1)
+    rp, ci, va = device_graph(g)
+    bad_rp = rp.clone()
+    bad_rp[5] = bad_rp[6] + 1                                    # not monotone
+    with pytest.raises(hc.HcspmmError) as e:
+        hc.hcspmm_prepare(g.n_rows, g.n_cols, bad_rp, ci, va)
+    assert e.value.status == hc.HCSPMM_EBADCSR
+    bad_ci = ci.clone()
+    bad_ci[3] = g.n_cols
+    with pytest.raises(hc.HcspmmError) as e:
+        hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, bad_ci, va)
+    assert e.value.status == hc.HCSPMM_EBADCSR
+    with pytest.raises(hc.HcspmmError) as e:
+        hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, nnz=g.nnz - 1)
+    assert e.value.status == hc.HCSPMM_EBADCSR
+    with pytest.raises(hc.HcspmmError) as e:
+        hc.hcspmm_prepare(-1, g.n_cols, rp, ci, va)
+    assert e.value.status == hc.HCSPMM_EINVAL
+    plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va)
+    X = torch.zeros((g.n_cols, 8), device="cuda")
+    Y = torch.zeros((g.n_rows, 8), device="cuda")
+    with pytest.raises(hc.HcspmmError) as e:                     # ldx < d
+        hc.hcspmm_spmm(plan, X, Y, d=16)
+    assert e.value.status == hc.HCSPMM_EINVAL
+    hc.hcspmm_spmm(plan, X, Y)                                    # still usable after an error
+    torch.cuda.synchronize()
+    plan.destroy()

@@ -1,0 +1,113 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+
+import oracle
+from workloads import (tiny_random_csr, make_config, dense_normal, dense_uniform, CSRGraph, chung_lu_graph,
+                       gcn_normalise, sbm_graph)
+from gpu_util import gpu_spmm, assert_close, oracle_pair, device_graph
+
+pytestmark = pytest.mark.gpu
+
+HYBRID, ALL_CSR, ALL_MFMA = 0, 1, 2
+MODES = [HYBRID, ALL_CSR, ALL_MFMA]
+TOL_F32 = 1e-5          # max error relative to |A||X|, fp32 path
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("d", [1, 2, 3, 4, 8, 16, 17, 32, 33, 48, 64, 96, 128, 130, 256, 300])
+def test_small_random_all_widths(mode, d):
+    g = tiny_random_csr(83, 70, 0.12, seed=100 + d)            # ragged last window, some empty rows
+    X = dense_normal(70, d, seed=200 + d)
+    Y, _ = gpu_spmm(g, X, mode, pad_x=(d % 3), pad_y=(d % 2))
+    ref, bound = oracle_pair(g, X)
+    assert_close(Y, ref, bound, TOL_F32, "d=%d mode=%d" % (d, mode))
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_exact_integer_case_bit_for_bit(mode):
+    g = tiny_random_csr(200, 333, 0.08, seed=5, integer_values=True)
+    rng = np.random.default_rng(6)
+    X = rng.integers(-8, 9, size=(333, 40)).astype(np.float32)
+    Y, _ = gpu_spmm(g, X, mode)
+    ref, _ = oracle_pair(g, X)
+    assert np.array_equal(Y, ref)
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_unsorted_rows_and_duplicates(mode):
+    g = tiny_random_csr(70, 50, 0.2, seed=9, sorted_rows=False, duplicates=True)
+    X = dense_normal(50, 32, seed=10)
+    Y, _ = gpu_spmm(g, X, mode)
+    ref, bound = oracle_pair(g, X)
+    assert_close(Y, ref, bound, TOL_F32)
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_degenerate_shapes(mode):
+    # one row; fewer than 16 rows; all rows empty; one dense row among empty ones; identity
+    X = dense_normal(40, 32, seed=3)
+    one = CSRGraph(1, 40, np.array([0, 3], np.int32), np.array([5, 7, 39], np.int32), np.array([1, 2, 3], np.float32))
+    empty = CSRGraph(37, 40, np.zeros(38, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32))
+    rp = np.zeros(34, np.int32)
+    rp[18:] = 40
+    hub = CSRGraph(33, 40, rp, np.arange(40, dtype=np.int32), np.linspace(-1, 1, 40).astype(np.float32))
+    eye = CSRGraph(40, 40, np.arange(41, dtype=np.int32), np.arange(40, dtype=np.int32), np.ones(40, np.float32))
+    for g in (one, empty, hub, eye):
+        Y, _ = gpu_spmm(g, X, mode)
+        ref, bound = oracle_pair(g, X)
+        assert_close(Y, ref, bound, TOL_F32)
+    Y, _ = gpu_spmm(eye, X, mode)
+    assert np.array_equal(Y, X.astype(np.float64))
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_long_rows_and_wide_windows(mode):
+    # rows longer than one segment, several segments, windows with thousands of distinct columns
+    n, m = 100, 9000
+    rng = np.random.default_rng(12)
+    lens = np.full(n, 3)
+    lens[[0, 17, 18, 50, 99]] = [8000, 513, 2049, 4500, 700]
+    cols = [np.sort(rng.choice(m, size=l, replace=False)) for l in lens]
+    rp = np.zeros(n + 1, np.int32)
+    np.cumsum(lens, out=rp[1:])
+    g = CSRGraph(n, m, rp, np.concatenate(cols).astype(np.int32),
+                 rng.standard_normal(int(lens.sum())).astype(np.float32))
+    for d in (32, 128, 20):
+        X = dense_normal(m, d, seed=13 + d)
+        Y, _ = gpu_spmm(g, X, mode)
+        ref, bound = oracle_pair(g, X)
+        assert_close(Y, ref, bound, TOL_F32, "d=%d" % d)
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("name", ["C1", "C2", "C3"])
+def test_configs_full_size(name, mode):
+    g, X, _ = make_config(name)
+    Y, info = gpu_spmm(g, X, mode)
+    ref, bound = oracle_pair(g, X)
+    assert_close(Y, ref, bound, TOL_F32, "%s mode=%d" % (name, mode))
+    if mode == ALL_CSR:
+        assert info["n_mfma_windows"] == 0
+    if mode == ALL_MFMA:
+        assert info["n_csr_windows"] == int((np.add.reduceat(np.diff(g.rowptr), np.arange(0, g.n_rows, 16)) == 0).sum())
+
+
+def test_routes_agree_and_rerun_is_deterministic():
+    g, X, _ = make_config("C2", scale=0.05)
+    ys = [gpu_spmm(g, X, mode)[0] for mode in MODES]
+    ref, bound = oracle_pair(g, X)
+    for y in ys:
+        assert_close(y, ref, bound, TOL_F32)
+    again = gpu_spmm(g, X, HYBRID)[0]
+    assert np.array_equal(ys[0], again)
+
+
+def test_custom_selector_mixes_both_paths():
+    g = sbm_graph(24, 64, 0.25, 4.0, seed=2)
+    X = dense_normal(g.n_cols, 64, seed=4)
+    # z = ncols + 0*sparsity - 120 < 0  <=>  ncols < 120: some windows on each path
+    Y, info = gpu_spmm(g, X, HYBRID, sel_coef=[1, 0, -120])
+    assert info["n_mfma_windows"] > 0 and info["n_csr_windows"] > 0
+    ref, bound = oracle_pair(g, X)
+    assert_close(Y, ref, bound, TOL_F32)
