@@ -56,6 +56,9 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
         if not build_if_missing:
             raise ImportError("libhcspmm.so is not built (run __graft_entry__.build())")
         build_library()
+    # torch ships its own HIP runtime under the same soname; load it first so that this library
+    # and torch share one runtime (device pointers and streams cross the boundary)
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     lib.hcspmm_default_options.argtypes = [ctypes.POINTER(HcspmmOptions)]

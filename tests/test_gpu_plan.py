@@ -66,7 +66,8 @@ def test_plan_with_windows_beyond_lds_sort_and_many_columns():
     np.cumsum(lens, out=rp[1:])
     g = CSRGraph(n, m, rp, np.concatenate(cols).astype(np.int32), np.ones(int(lens.sum()), np.float32))
     got, _ = check_plan(g, sel_coef=[1, 100, -50])
-    assert got["ncols"][0] == 700 * 15 and got["nnzw"][0] == 11200
+    assert 700 * 14 < got["ncols"][0] <= 700 * 15 and got["nnzw"][0] == 11200
+    assert got["ncols"][2] > 30000 and got["wcols"].max() > (1 << 21)
 
 
 def test_selector_routes_change_with_coefficients():
