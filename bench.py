@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark of the hybrid SpMM hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--modes] [--no-cpu]
+
+One "step" is one `hcspmm_spmm` call (Y = A X on the hybrid plan: every window goes through the
+path its selector flag names) on the named synthetic workload, with the CSR, X, Y and the plan
+already resident in HBM; the plan is built once beforehand, as the method prescribes
+(preprocessing is a one-time cost that is reported separately, in `prepare_ms`).
+
+Prints ONE JSON line:
+  metric/value   SpMM GFLOP/s = 2 nnz d / t over the K timed steps
+  roofline       dominant kernel of the step: algorithmic HBM bytes of its share of the work
+                 divided by its average duration (HIP events on the launch stream), vs 8 TB/s
+  cpu_baseline   the CPU oracle (plain CSR triple loop, fp64) timed on this machine's host cores
+With --modes the JSON also carries the all-CSR and all-MFMA timings of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+WORKLOAD_TEXT = {
+    "C1": "C1 small power-law: N=2,708, 10,556 edges + self-loops, values 1, X 2708x32 fp32 U[-1,1]",
+    "C2": "C2 medium power-law: N=169,343, 2.3M edges + self-loops, GCN-normalised, X Nx128 fp32 N(0,1)",
+    "C3": "C3 community SBM: N=131,072 (2,048 blocks of 64), p_in 0.25, inter degree 4, values 1, X Nx64 fp32 N(0,1)",
+    "C4": "C4 large power-law: N=2,449,029, 123.7M edges + self-loops, GCN-normalised, X Nx32 fp32 U[-1,1]",
+    "C5": "C5 dense-ish power-law, SpMM stage of the GCN layer: N=232,965, 114.6M edges + self-loops, T Nx128 fp32",
+}
+
+
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+def time_steps(fn, steps, warmup, torch):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="C4", choices=sorted(WORKLOAD_TEXT))
+    ap.add_argument("--modes", action="store_true", help="also time the all-CSR and all-MFMA plans")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--cold", action="store_true", help="also report cold-cache time (512 MiB flush between reps)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    from workloads import make_config, dense_normal, CONFIGS
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    name = args.workload
+    t0 = time.time()
+    g, X, _ = make_config(name, with_dense=(name != "C5"))
+    if name == "C5":                      # SpMM stage of the layer: T = X W has the layer's output width
+        X = dense_normal(g.n_rows, CONFIGS["C5"]["d"], seed=1)
+    d = X.shape[1]
+    log("generated %s: N=%d nnz=%d d=%d in %.1fs" % (name, g.n_rows, g.nnz, d, time.time() - t0))
+    rp = torch.from_numpy(g.rowptr).to(dev)
+    ci = torch.from_numpy(g.colind).to(dev)
+    va = torch.from_numpy(g.vals).to(dev)
+    Xd = torch.from_numpy(X).to(dev)
+    Yd = torch.empty((g.n_rows, d), dtype=torch.float32, device=dev)
+    flops = 2.0 * g.nnz * d
+
+    def prepare(mode):
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, route_mode=mode, d_hint=d)
+        torch.cuda.synchronize()
+        return plan, (time.perf_counter() - t) * 1e3
+
+    plan, _ = prepare(hc.HCSPMM_ROUTE_HYBRID)          # first call also pays one-time runtime set-up
+    plan.destroy()
+    plan, prepare_ms = prepare(hc.HCSPMM_ROUTE_HYBRID)
+    info = hc.hcspmm_plan_info(plan)
+    log("plan: %d windows, %d on the matrix path (%d nnz), prepare %.2f ms" %
+        (info["n_windows"], info["n_mfma_windows"], info["nnz_mfma"], prepare_ms))
+
+    ms = time_steps(lambda: hc.hcspmm_spmm(plan, Xd, Yd), args.steps, args.warmup, torch)
+    gflops = flops / (ms * 1e-3) / 1e9
+    log("hybrid: %.3f ms/step, %.1f GFLOP/s" % (ms, gflops))
+
+    # per-stage durations (HIP events on the launch stream), averaged over the same number of launches
+    stage_sum = {}
+    for _ in range(args.steps):
+        st = hc.hcspmm_spmm_timed(plan, Xd, Yd)
+        for k, v in st.items():
+            stage_sum[k] = stage_sum.get(k, 0.0) + v
+    stage_ms = {k: v / args.steps for k, v in stage_sum.items()}
+    log("stages (ms): " + ", ".join("%s=%.4f" % (k[3:], v) for k, v in stage_ms.items()))
+
+    # share of the work per stage -> algorithmic bytes of the dominant kernel
+    nnz_mfma, nnz_long = info["nnz_mfma"], info["nnz_long"]
+    nnz_short = g.nnz - nnz_mfma - nnz_long
+    rows_mfma = info["n_mfma_windows"] * 16
+    sx = 4
+    share = {
+        "ms_csr_short": dict(kernel="k_csr_short", rows=info["n_short_rows"], nnz=nnz_short, extra_per_nnz=0),
+        "ms_csr_long": dict(kernel="k_csr_long", rows=info["n_long_rows"], nnz=nnz_long, extra_per_nnz=0),
+        # the matrix path also reads 4 B per non-zero (condensed column + row) and 4 B per condensed column
+        "ms_mfma_small": dict(kernel="k_mfma_small", rows=min(rows_mfma, g.n_rows), nnz=nnz_mfma, extra_per_nnz=4),
+        "ms_mfma_big": dict(kernel="k_mfma_big", rows=min(rows_mfma, g.n_rows), nnz=nnz_mfma, extra_per_nnz=4),
+    }
+    dom = max(share, key=lambda k: stage_ms.get(k, 0.0))
+    s = share[dom]
+    # B_min of the kernel's share: rowptr + (colind, val) + X read once + its Y rows written once
+    alg_bytes = 4.0 * (s["rows"] + 1) + (8.0 + s["extra_per_nnz"]) * s["nnz"] + g.n_cols * d * sx + s["rows"] * d * 4.0
+    achieved = alg_bytes / (stage_ms[dom] * 1e-3) / 1e9
+    whole_bytes = 4.0 * (g.n_rows + 1) + 8.0 * g.nnz + g.n_cols * d * sx + g.n_rows * d * 4.0
+    roofline = dict(bound="hbm", kernel=s["kernel"], achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
+                    algorithmic_bytes=int(alg_bytes), kernel_ms=round(stage_ms[dom], 5),
+                    whole_step_frac=round(whole_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4))
+
+    out = dict(metric="spmm_gflops (2*nnz*d/t)", value=round(gflops, 2), unit="GFLOP/s", n_gpus=1, steps=args.steps,
+               warmup=args.warmup, ms_per_step=round(ms, 5), higher_is_better=True, scaling="weak", vs_baseline=None,
+               dtype="f32", data="synthetic",
+               config=dict(workload=WORKLOAD_TEXT[name], name=name, n=g.n_rows, nnz=g.nnz, d=d, route_mode="hybrid",
+                           n_windows=info["n_windows"], mfma_windows=info["n_mfma_windows"],
+                           nnz_on_matrix_path=nnz_mfma, sel_coef=info["sel_coef"]),
+               roofline=roofline, prepare_ms=round(prepare_ms, 3),
+               stage_ms={k: round(v, 5) for k, v in stage_ms.items()})
+
+    if args.cold:
+        flush = torch.empty(512 << 20, dtype=torch.uint8, device=dev)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ts = []
+        for _ in range(min(args.steps, 20)):
+            flush.fill_(1)
+            e0.record()
+            hc.hcspmm_spmm(plan, Xd, Yd)
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        out["cold_ms"] = round(float(np.median(ts)), 5)
+        del flush
+
+    Y_hybrid = Yd.cpu().numpy()
+    plan.destroy()
+
+    if args.modes:
+        modes = {}
+        for label, mode in (("all_csr", hc.HCSPMM_ROUTE_ALL_CSR), ("all_mfma", hc.HCSPMM_ROUTE_ALL_MFMA)):
+            p2, pm = prepare(mode)
+            steps = args.steps if label == "all_csr" else max(3, args.steps // 5)
+            m2 = time_steps(lambda: hc.hcspmm_spmm(p2, Xd, Yd), steps, min(args.warmup, 3), torch)
+            modes[label] = dict(ms_per_step=round(m2, 5), gflops=round(flops / (m2 * 1e-3) / 1e9, 2),
+                                prepare_ms=round(pm, 3))
+            log("%s: %.3f ms/step" % (label, m2))
+            p2.destroy()
+        modes["hybrid"] = dict(ms_per_step=round(ms, 5), gflops=round(gflops, 2))
+        out["modes"] = modes
+
+    if not args.no_cpu:
+        import oracle
+        # bounded sample: whole windows spread evenly over the matrix, at most 5e10 multiply-adds
+        budget = 5.0e10
+        total_fma = float(g.nnz) * d
+        W = (g.n_rows + 15) // 16
+        stride = max(1, int(np.ceil(total_fma / budget)))
+        wins = np.arange(0, W, stride)
+        rows = (wins[:, None] * 16 + np.arange(16)[None, :]).reshape(-1)
+        rows = rows[rows < g.n_rows]
+        t1 = time.perf_counter()
+        ref = oracle.spmm_rows(rows, g.rowptr, g.colind, g.vals, X)
+        cpu_s = time.perf_counter() - t1
+        lens = np.diff(g.rowptr.astype(np.int64))[rows]
+        cpu_gflops = 2.0 * float(lens.sum()) * d / cpu_s / 1e9
+        bound = oracle.spmm_rows(rows, g.rowptr, g.colind, g.vals, X, use_abs=True)
+        err = np.abs(Y_hybrid[rows].astype(np.float64) - ref)
+        ok = bool(np.all(err <= 1e-5 * bound + 1e-30))
+        out["cpu_baseline"] = dict(value=round(cpu_gflops, 3), unit="GFLOP/s", cores=oracle.num_threads(), kind="oracle",
+                                   sample="every %d-th 16-row window (%d rows, %d non-zeros), %.1f s" %
+                                          (stride, rows.shape[0], int(lens.sum()), cpu_s))
+        out["parity_on_sample"] = ok
+        log("cpu oracle: %.2f GFLOP/s on %d threads; GPU rows match oracle: %s" % (cpu_gflops, oracle.num_threads(), ok))
+
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

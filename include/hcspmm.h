@@ -121,6 +121,13 @@ typedef struct {
     int32_t d_hint;
     int64_t sel_coef[3];      /* coefficients the routes were computed with */
     int64_t device_bytes;     /* device memory owned by the plan */
+    /* how the scalar path's rows are scheduled (launch tables, not part of the canonical plan) */
+    int32_t n_short_rows;     /* rows handled one lane group per row */
+    int32_t n_long_rows;      /* rows cut into segments, one workgroup per segment */
+    int32_t n_segments;
+    int64_t nnz_long;         /* non-zeros inside long rows */
+    int32_t n_mfma_small;     /* route-1 windows handled one wave per window */
+    int32_t n_mfma_big;       /* route-1 windows handled one workgroup per window */
 } hcspmm_plan_info_t;
 
 hcspmm_status hcspmm_plan_info(const hcspmm_plan* plan, hcspmm_plan_info_t* info /* host, out */);
@@ -156,6 +163,24 @@ hcspmm_status hcspmm_plan_export(const hcspmm_plan* plan, int32_t* ncols, int32_
  */
 hcspmm_status hcspmm_spmm(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d, int32_t x_dtype,
                           void* d_Y, int64_t ldy, int32_t y_dtype, void* stream);
+
+/*
+ * Same as hcspmm_spmm, but brackets every kernel stage with HIP events on `stream`, waits for
+ * completion and reports the elapsed milliseconds per stage (for benchmarks and profiling; the
+ * stages run in this order).  A stage that launches nothing reports 0.
+ */
+typedef struct {
+    float ms_total;
+    float ms_csr_long;        /* segments of long rows (scalar path) */
+    float ms_csr_reduce;      /* sum of the partial rows of multi-segment rows */
+    float ms_mfma_big;        /* matrix path, workgroup per window */
+    float ms_mfma_small;      /* matrix path, wave per window */
+    float ms_csr_short;       /* short rows (scalar path) */
+} hcspmm_stage_times;
+
+hcspmm_status hcspmm_spmm_timed(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d, int32_t x_dtype,
+                                void* d_Y, int64_t ldy, int32_t y_dtype, void* stream,
+                                hcspmm_stage_times* times /* host, out */);
 
 /*
  * GCN layer  Y = act(A (X W))  (Eq. 1 and Eq. 2; Section V-A couples the two

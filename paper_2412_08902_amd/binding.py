@@ -19,7 +19,7 @@ HCSPMM_ROUTE_HYBRID, HCSPMM_ROUTE_ALL_CSR, HCSPMM_ROUTE_ALL_MFMA = 0, 1, 2
 
 EXPORTED_SYMBOLS = [
     "hcspmm_default_options", "hcspmm_default_selector", "hcspmm_prepare", "hcspmm_plan_info",
-    "hcspmm_plan_export", "hcspmm_spmm", "hcspmm_gcn_layer", "hcspmm_gcn_workspace_bytes",
+    "hcspmm_plan_export", "hcspmm_spmm", "hcspmm_spmm_timed", "hcspmm_gcn_layer", "hcspmm_gcn_workspace_bytes",
     "hcspmm_gemm_f32", "hcspmm_plan_destroy", "hcspmm_status_string", "hcspmm_last_error", "hcspmm_version",
 ]
 
@@ -35,7 +35,14 @@ class HcspmmPlanInfo(ctypes.Structure):
                 ("nnz", ctypes.c_int64), ("n_windows", ctypes.c_int32), ("total_ncols", ctypes.c_int64),
                 ("n_mfma_windows", ctypes.c_int32), ("n_csr_windows", ctypes.c_int32), ("nnz_mfma", ctypes.c_int64),
                 ("route_mode", ctypes.c_int32), ("mfma_dtype", ctypes.c_int32), ("d_hint", ctypes.c_int32),
-                ("sel_coef", ctypes.c_int64 * 3), ("device_bytes", ctypes.c_int64)]
+                ("sel_coef", ctypes.c_int64 * 3), ("device_bytes", ctypes.c_int64),
+                ("n_short_rows", ctypes.c_int32), ("n_long_rows", ctypes.c_int32), ("n_segments", ctypes.c_int32),
+                ("nnz_long", ctypes.c_int64), ("n_mfma_small", ctypes.c_int32), ("n_mfma_big", ctypes.c_int32)]
+
+
+class HcspmmStageTimes(ctypes.Structure):
+    _fields_ = [("ms_total", ctypes.c_float), ("ms_csr_long", ctypes.c_float), ("ms_csr_reduce", ctypes.c_float),
+                ("ms_mfma_big", ctypes.c_float), ("ms_mfma_small", ctypes.c_float), ("ms_csr_short", ctypes.c_float)]
 
 
 class HcspmmError(RuntimeError):
@@ -73,6 +80,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.hcspmm_plan_export.restype = ctypes.c_int
     lib.hcspmm_spmm.argtypes = [vp, vp, i64, i32, i32, vp, i64, i32, vp]
     lib.hcspmm_spmm.restype = ctypes.c_int
+    lib.hcspmm_spmm_timed.argtypes = [vp, vp, i64, i32, i32, vp, i64, i32, vp, ctypes.POINTER(HcspmmStageTimes)]
+    lib.hcspmm_spmm_timed.restype = ctypes.c_int
     lib.hcspmm_gcn_layer.argtypes = [vp, vp, i64, i32, vp, i64, i32, vp, i64, i32, vp, ctypes.c_size_t, vp]
     lib.hcspmm_gcn_layer.restype = ctypes.c_int
     lib.hcspmm_gcn_workspace_bytes.argtypes = [vp, i32, i32]
@@ -212,6 +221,17 @@ def hcspmm_spmm(plan: Plan, X, Y, *, d: Optional[int] = None, stream=None):
     _check(load_library().hcspmm_spmm(plan.handle, _ptr(X), X.stride(0), d, _dtype_code(X), _ptr(Y), Y.stride(0),
                                       _dtype_code(Y), _stream_ptr(stream)))
     return Y
+
+
+def hcspmm_spmm_timed(plan: Plan, X, Y, *, d: Optional[int] = None, stream=None) -> dict:
+    """hcspmm_spmm with per-stage HIP-event timing; returns the stage times in milliseconds."""
+    assert X.dim() == 2 and Y.dim() == 2 and X.stride(1) == 1 and Y.stride(1) == 1
+    if d is None:
+        d = X.shape[1]
+    t = HcspmmStageTimes()
+    _check(load_library().hcspmm_spmm_timed(plan.handle, _ptr(X), X.stride(0), d, _dtype_code(X), _ptr(Y),
+                                            Y.stride(0), _dtype_code(Y), _stream_ptr(stream), ctypes.byref(t)))
+    return {name: float(getattr(t, name)) for name, _ in HcspmmStageTimes._fields_}
 
 
 def hcspmm_gcn_workspace_bytes(plan: Plan, d_in: int, d_out: int) -> int:

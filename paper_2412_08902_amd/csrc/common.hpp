@@ -62,7 +62,7 @@ hipError_t launch_select(int32_t W, const int32_t* ncols, const int32_t* nnzw, i
                          int32_t* f_big, int32_t* nnz_if_mfma, hipStream_t s);
 hipError_t launch_compact_ids(int32_t n, const int32_t* flags, const int64_t* pos, int32_t* out, hipStream_t s);
 hipError_t launch_row_class(int32_t n_rows, const int32_t* rowptr, const uint8_t* route, int32_t* f_short,
-                            int32_t* n_seg, int32_t* f_multi, int32_t* n_slot, hipStream_t s);
+                            int32_t* n_seg, int32_t* f_multi, int32_t* n_slot, int32_t* len_long, hipStream_t s);
 hipError_t launch_build_segments(int32_t n_rows, const int32_t* rowptr, const int32_t* n_seg, const int64_t* seg_pos,
                                  const int64_t* multi_pos, const int64_t* slot_pos, Segment* segs, MultiRow* multi,
                                  hipStream_t s);
@@ -129,6 +129,8 @@ struct hcspmm_plan {
     hcspmm::MultiRow* multi;
     int32_t n_multi;
     int64_t n_slots;
+    int32_t n_long_rows;
+    int64_t nnz_long;
     // lazily sized partial-sum buffer for long rows cut into several segments
     float* partial;
     int64_t partial_elems;

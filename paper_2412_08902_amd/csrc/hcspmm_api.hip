@@ -105,7 +105,7 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     const int64_t nnz = p->nnz;
     int32_t *err = nullptr, *big_list = nullptr, *big_count = nullptr, *tmp_cols = nullptr;
     int32_t *f_mfma = nullptr, *f_csr = nullptr, *f_small = nullptr, *f_big = nullptr, *nnz_if = nullptr;
-    int32_t *f_short = nullptr, *n_seg = nullptr, *f_multi = nullptr, *n_slot = nullptr;
+    int32_t *f_short = nullptr, *n_seg = nullptr, *f_multi = nullptr, *n_slot = nullptr, *len_long = nullptr;
     int64_t *scan_tmp = nullptr, *pos_a = nullptr, *pos_b = nullptr, *pos_c = nullptr, *pos_d = nullptr;
     int64_t *totals_dev = nullptr;
     int32_t h_err = 0, h_big = 0;
@@ -193,7 +193,10 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     HC_ALLOC(tmp, n_seg, (size_t)n_rows + 1);
     HC_ALLOC(tmp, f_multi, (size_t)n_rows + 1);
     HC_ALLOC(tmp, n_slot, (size_t)n_rows + 1);
-    HC_TRY(launch_row_class(n_rows, p->rowptr, p->route, f_short, n_seg, f_multi, n_slot, stream));
+    HC_ALLOC(tmp, len_long, (size_t)n_rows + 1);
+    HC_TRY(launch_row_class(n_rows, p->rowptr, p->route, f_short, n_seg, f_multi, n_slot, len_long, stream));
+    HC_TRY(exclusive_scan_i32_i64(len_long, n_rows, pos_a, scan_tmp, stream));
+    HC_TRY(hipMemcpyAsync(totals_dev + 4, pos_a + n_rows, 8, hipMemcpyDeviceToDevice, stream));
     HC_TRY(exclusive_scan_i32_i64(f_short, n_rows, pos_a, scan_tmp, stream));
     HC_TRY(hipMemcpyAsync(totals_dev + 0, pos_a + n_rows, 8, hipMemcpyDeviceToDevice, stream));
     HC_TRY(exclusive_scan_i32_i64(n_seg, n_rows, pos_b, scan_tmp, stream));
@@ -202,12 +205,14 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     HC_TRY(hipMemcpyAsync(totals_dev + 2, pos_c + n_rows, 8, hipMemcpyDeviceToDevice, stream));
     HC_TRY(exclusive_scan_i32_i64(n_slot, n_rows, pos_d, scan_tmp, stream));
     HC_TRY(hipMemcpyAsync(totals_dev + 3, pos_d + n_rows, 8, hipMemcpyDeviceToDevice, stream));
-    HC_TRY(hipMemcpyAsync(h_tot, totals_dev, 4 * sizeof(int64_t), hipMemcpyDeviceToHost, stream));
+    HC_TRY(hipMemcpyAsync(h_tot, totals_dev, 5 * sizeof(int64_t), hipMemcpyDeviceToHost, stream));
     HC_TRY(hipStreamSynchronize(stream));
+    p->nnz_long = h_tot[4];
     p->n_short = (int32_t)h_tot[0];
     p->n_segs = (int32_t)h_tot[1];
     p->n_multi = (int32_t)h_tot[2];
     p->n_slots = h_tot[3];
+    p->n_long_rows = (int32_t)(p->n_segs - p->n_slots + p->n_multi);   // single-segment rows + multi-segment rows
     HC_ALLOC(keep, p->segs, p->n_segs);
     HC_ALLOC(keep, p->multi, p->n_multi);
     if (p->n_segs > 0)
@@ -232,7 +237,8 @@ fail:
     return st;
 }
 
-static hcspmm_status run_spmm(const hcspmm_plan* plan, const SpmmArgs& a, hipStream_t stream)
+static hcspmm_status run_spmm(const hcspmm_plan* plan, const SpmmArgs& a, hipStream_t stream,
+                              hipEvent_t* ev = nullptr /* 6 events when timing stages */)
 {
     hcspmm_plan* p = const_cast<hcspmm_plan*>(plan);
     // long rows cut into several segments need one partial row per segment
@@ -249,12 +255,18 @@ static hcspmm_status run_spmm(const hcspmm_plan* plan, const SpmmArgs& a, hipStr
         p->partial_elems = want;
     }
     // heaviest work first: long-row segments, then the matrix-path windows, then the short rows
+    if (ev) HC_HIP(hipEventRecord(ev[0], stream));
     HC_HIP(launch_csr_long(a, p->n_segs, p->segs, p->partial, stream));
+    if (ev) HC_HIP(hipEventRecord(ev[1], stream));
     HC_HIP(launch_reduce_partials(a, p->n_multi, p->multi, p->partial, stream));
+    if (ev) HC_HIP(hipEventRecord(ev[2], stream));
     HC_HIP(launch_mfma_big(a, p->n_mfma_big, p->mfma_big, p->ncols, p->wptr, p->wcols, p->erc, stream));
+    if (ev) HC_HIP(hipEventRecord(ev[3], stream));
     HC_HIP(launch_mfma_small(a, p->n_mfma_small, p->mfma_small, p->ncols, p->wptr, p->wcols, p->erc, stream));
+    if (ev) HC_HIP(hipEventRecord(ev[4], stream));
     if (p->short_rows) HC_HIP(launch_csr_short(a, p->n_short, p->short_rows, p->route, stream));
     else if (p->n_short > 0) HC_HIP(launch_csr_short(a, p->n_rows, nullptr, p->route, stream));
+    if (ev) HC_HIP(hipEventRecord(ev[5], stream));
     return HCSPMM_OK;
 }
 
@@ -339,6 +351,8 @@ hcspmm_status hcspmm_plan_info(const hcspmm_plan* p, hcspmm_plan_info_t* info)
     info->route_mode = p->opt.route_mode; info->mfma_dtype = p->opt.mfma_dtype; info->d_hint = p->opt.d_hint;
     for (int i = 0; i < 3; ++i) info->sel_coef[i] = p->coef[i];
     info->device_bytes = p->device_bytes + p->partial_elems * (int64_t)sizeof(float);
+    info->n_short_rows = p->n_short; info->n_long_rows = p->n_long_rows; info->n_segments = p->n_segs;
+    info->nnz_long = p->nnz_long; info->n_mfma_small = p->n_mfma_small; info->n_mfma_big = p->n_mfma_big;
     return HCSPMM_OK;
 }
 
@@ -369,8 +383,41 @@ static hcspmm_status check_dense(const char* name, const void* ptr, int64_t ld, 
     return HCSPMM_OK;
 }
 
+static hcspmm_status spmm_impl(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d, int32_t x_dtype,
+                               void* d_Y, int64_t ldy, int32_t y_dtype, void* stream, hipEvent_t* ev);
+
 hcspmm_status hcspmm_spmm(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d, int32_t x_dtype, void* d_Y,
                           int64_t ldy, int32_t y_dtype, void* stream)
+{
+    return spmm_impl(plan, d_X, ldx, d, x_dtype, d_Y, ldy, y_dtype, stream, nullptr);
+}
+
+hcspmm_status hcspmm_spmm_timed(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d, int32_t x_dtype,
+                                void* d_Y, int64_t ldy, int32_t y_dtype, void* stream, hcspmm_stage_times* times)
+{
+    if (!times) { set_error("times is NULL"); return HCSPMM_EINVAL; }
+    memset(times, 0, sizeof *times);
+    hipEvent_t ev[6];
+    int made = 0;
+    hcspmm_status st = HCSPMM_OK;
+    for (; made < 6; ++made)
+        if (hipEventCreate(&ev[made]) != hipSuccess) { (void)hipGetLastError(); set_error("hipEventCreate failed"); st = HCSPMM_EHIP; break; }
+    if (st == HCSPMM_OK) st = spmm_impl(plan, d_X, ldx, d, x_dtype, d_Y, ldy, y_dtype, stream, ev);
+    if (st == HCSPMM_OK && plan->n_rows > 0) {
+        if (hipEventSynchronize(ev[5]) != hipSuccess) { (void)hipGetLastError(); set_error("hipEventSynchronize failed"); st = HCSPMM_EHIP; }
+        else {
+            float* out[5] = {&times->ms_csr_long, &times->ms_csr_reduce, &times->ms_mfma_big, &times->ms_mfma_small,
+                             &times->ms_csr_short};
+            for (int i = 0; i < 5; ++i) (void)hipEventElapsedTime(out[i], ev[i], ev[i + 1]);
+            (void)hipEventElapsedTime(&times->ms_total, ev[0], ev[5]);
+        }
+    }
+    for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
+    return st;
+}
+
+static hcspmm_status spmm_impl(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d, int32_t x_dtype,
+                               void* d_Y, int64_t ldy, int32_t y_dtype, void* stream, hipEvent_t* ev)
 {
     if (!plan) { set_error("plan is NULL"); return HCSPMM_EINVAL; }
     if (d < 1 || d > (1 << 20)) { set_error("d must be in [1, 2^20]"); return HCSPMM_EINVAL; }
@@ -384,7 +431,7 @@ hcspmm_status hcspmm_spmm(const hcspmm_plan* plan, const void* d_X, int64_t ldx,
     SpmmArgs a;
     a.n_rows = plan->n_rows; a.rowptr = plan->rowptr; a.colind = plan->colind; a.vals = plan->vals;
     a.X = d_X; a.ldx = ldx; a.d = d; a.x_dtype = x_dtype; a.Y = static_cast<float*>(d_Y); a.ldy = ldy; a.relu = 0;
-    return run_spmm(plan, a, static_cast<hipStream_t>(stream));
+    return run_spmm(plan, a, static_cast<hipStream_t>(stream), ev);
 }
 
 size_t hcspmm_gcn_workspace_bytes(const hcspmm_plan* plan, int32_t d_in, int32_t d_out)

@@ -430,7 +430,7 @@ hipError_t launch_compact_ids(int32_t n, const int32_t* flags, const int64_t* po
 __global__ __launch_bounds__(256) void k_row_class(int32_t n_rows, const int32_t* __restrict__ rowptr,
                                                    const uint8_t* __restrict__ route, int32_t* __restrict__ f_short,
                                                    int32_t* __restrict__ n_seg, int32_t* __restrict__ f_multi,
-                                                   int32_t* __restrict__ n_slot)
+                                                   int32_t* __restrict__ n_slot, int32_t* __restrict__ len_long)
 {
     int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n_rows) return;
@@ -442,14 +442,15 @@ __global__ __launch_bounds__(256) void k_row_class(int32_t n_rows, const int32_t
     n_seg[i] = ns;
     f_multi[i] = ns > 1 ? 1 : 0;
     n_slot[i] = ns > 1 ? ns : 0;
+    len_long[i] = is_long ? len : 0;
 }
 
 hipError_t launch_row_class(int32_t n_rows, const int32_t* rowptr, const uint8_t* route, int32_t* f_short,
-                            int32_t* n_seg, int32_t* f_multi, int32_t* n_slot, hipStream_t s)
+                            int32_t* n_seg, int32_t* f_multi, int32_t* n_slot, int32_t* len_long, hipStream_t s)
 {
     if (n_rows <= 0) return hipSuccess;
     hipLaunchKernelGGL(k_row_class, dim3((n_rows + 255) / 256), dim3(256), 0, s, n_rows, rowptr, route, f_short, n_seg,
-                       f_multi, n_slot);
+                       f_multi, n_slot, len_long);
     return hipGetLastError();
 }
 
