@@ -60,6 +60,8 @@ def main():
     ap.add_argument("--modes", action="store_true", help="also time the all-CSR and all-MFMA plans")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cold", action="store_true", help="also report cold-cache time (512 MiB flush between reps)")
+    ap.add_argument("--calib", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference point for rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -114,16 +116,16 @@ def main():
     log("stages (ms): " + ", ".join("%s=%.4f" % (k[3:], v) for k, v in stage_ms.items()))
 
     # share of the work per stage -> algorithmic bytes of the dominant kernel
-    nnz_mfma, nnz_long = info["nnz_mfma"], info["nnz_long"]
-    nnz_short = g.nnz - nnz_mfma - nnz_long
-    rows_mfma = info["n_mfma_windows"] * 16
+    nnz_mfma = info["nnz_mfma"]
+    nnz_csr = g.nnz - nnz_mfma
+    rows_mfma = min(info["n_mfma_windows"] * 16, g.n_rows)
+    rows_csr = g.n_rows - rows_mfma
     sx = 4
     share = {
-        "ms_csr_short": dict(kernel="k_csr_short", rows=info["n_short_rows"], nnz=nnz_short, extra_per_nnz=0),
-        "ms_csr_long": dict(kernel="k_csr_long", rows=info["n_long_rows"], nnz=nnz_long, extra_per_nnz=0),
+        "ms_csr": dict(kernel="k_csr", rows=rows_csr, nnz=nnz_csr, extra_per_nnz=0),
         # the matrix path also reads 4 B per non-zero (condensed column + row) and 4 B per condensed column
-        "ms_mfma_small": dict(kernel="k_mfma_small", rows=min(rows_mfma, g.n_rows), nnz=nnz_mfma, extra_per_nnz=4),
-        "ms_mfma_big": dict(kernel="k_mfma_big", rows=min(rows_mfma, g.n_rows), nnz=nnz_mfma, extra_per_nnz=4),
+        "ms_mfma_small": dict(kernel="k_mfma_small", rows=rows_mfma, nnz=nnz_mfma, extra_per_nnz=4),
+        "ms_mfma_big": dict(kernel="k_mfma_big", rows=rows_mfma, nnz=nnz_mfma, extra_per_nnz=4),
     }
     dom = max(share, key=lambda k: stage_ms.get(k, 0.0))
     s = share[dom]
@@ -161,6 +163,15 @@ def main():
 
     Y_hybrid = Yd.cpu().numpy()
     plan.destroy()
+
+    if args.calib:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)          # 1 GiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.mul(src, 2.0, out=dst)          # one elementwise kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        out["calib_copy_bytes"] = int(src.numel() * 4)
+        del src, dst
 
     if args.modes:
         modes = {}

@@ -122,10 +122,11 @@ typedef struct {
     int64_t sel_coef[3];      /* coefficients the routes were computed with */
     int64_t device_bytes;     /* device memory owned by the plan */
     /* how the scalar path's rows are scheduled (launch tables, not part of the canonical plan) */
-    int32_t n_short_rows;     /* rows handled one lane group per row */
+    int32_t n_short_rows;     /* rows walked by lane groups, several consecutive rows per group */
+    int32_t n_mid_rows;       /* rows handled one wave per row */
     int32_t n_long_rows;      /* rows cut into segments, one workgroup per segment */
     int32_t n_segments;
-    int64_t nnz_long;         /* non-zeros inside long rows */
+    int64_t nnz_long;         /* non-zeros inside mid and long rows */
     int32_t n_mfma_small;     /* route-1 windows handled one wave per window */
     int32_t n_mfma_big;       /* route-1 windows handled one workgroup per window */
 } hcspmm_plan_info_t;
@@ -171,11 +172,10 @@ hcspmm_status hcspmm_spmm(const hcspmm_plan* plan, const void* d_X, int64_t ldx,
  */
 typedef struct {
     float ms_total;
-    float ms_csr_long;        /* segments of long rows (scalar path) */
-    float ms_csr_reduce;      /* sum of the partial rows of multi-segment rows */
     float ms_mfma_big;        /* matrix path, workgroup per window */
     float ms_mfma_small;      /* matrix path, wave per window */
-    float ms_csr_short;       /* short rows (scalar path) */
+    float ms_csr;             /* scalar path: long-row segments, mid rows and short rows in one launch */
+    float ms_csr_reduce;      /* sum of the partial rows of rows cut into several segments */
 } hcspmm_stage_times;
 
 hcspmm_status hcspmm_spmm_timed(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d, int32_t x_dtype,

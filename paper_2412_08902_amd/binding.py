@@ -36,13 +36,13 @@ class HcspmmPlanInfo(ctypes.Structure):
                 ("n_mfma_windows", ctypes.c_int32), ("n_csr_windows", ctypes.c_int32), ("nnz_mfma", ctypes.c_int64),
                 ("route_mode", ctypes.c_int32), ("mfma_dtype", ctypes.c_int32), ("d_hint", ctypes.c_int32),
                 ("sel_coef", ctypes.c_int64 * 3), ("device_bytes", ctypes.c_int64),
-                ("n_short_rows", ctypes.c_int32), ("n_long_rows", ctypes.c_int32), ("n_segments", ctypes.c_int32),
+                ("n_short_rows", ctypes.c_int32), ("n_mid_rows", ctypes.c_int32), ("n_long_rows", ctypes.c_int32), ("n_segments", ctypes.c_int32),
                 ("nnz_long", ctypes.c_int64), ("n_mfma_small", ctypes.c_int32), ("n_mfma_big", ctypes.c_int32)]
 
 
 class HcspmmStageTimes(ctypes.Structure):
-    _fields_ = [("ms_total", ctypes.c_float), ("ms_csr_long", ctypes.c_float), ("ms_csr_reduce", ctypes.c_float),
-                ("ms_mfma_big", ctypes.c_float), ("ms_mfma_small", ctypes.c_float), ("ms_csr_short", ctypes.c_float)]
+    _fields_ = [("ms_total", ctypes.c_float), ("ms_mfma_big", ctypes.c_float), ("ms_mfma_small", ctypes.c_float),
+                ("ms_csr", ctypes.c_float), ("ms_csr_reduce", ctypes.c_float)]
 
 
 class HcspmmError(RuntimeError):

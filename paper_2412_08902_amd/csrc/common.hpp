@@ -18,15 +18,19 @@ constexpr int kEcolLdsCap = 4096;      // distinct-column lists up to this lengt
 
 // ---- matrix path -------------------------------------------------------------------------------
 constexpr int kMfmaSmallMaxCols = 512; // windows with more condensed columns go to the workgroup-per-window kernel
-constexpr int kKcSmall = 64;           // condensed columns staged per wave and chunk (wave-per-window kernel)
+constexpr int kKcSmall = 128;          // condensed columns staged per wave and chunk (wave-per-window kernel)
 constexpr int kKcBig = 1024;           // condensed columns staged per workgroup and chunk
 
 // ---- scalar path -------------------------------------------------------------------------------
-constexpr int kLongRow = 512;          // rows with more non-zeros than this are cut into segments
+constexpr int kRowsPerGroup = 8;       // consecutive rows walked by one lane group (short rows)
+constexpr int kMidRow = 96;            // rows with more non-zeros than this get a whole wave
+constexpr int kLongRow = 1024;         // rows with more non-zeros than this are cut into workgroup-sized segments
 constexpr int kSegLen = 2048;          // non-zeros per segment of a long row
 
 struct Segment { int32_t row, k_begin, k_end, slot; };    // slot < 0: writes Y directly
 struct MultiRow { int32_t row, first_slot, n_slots, pad; };
+// everything the wave-per-window matrix kernel needs to start on a window, in one 32-byte read
+struct WinDesc { int32_t w, s, e, nc; int64_t wp; int64_t pad; };
 
 void set_error(const char* fmt, ...);
 
@@ -62,7 +66,10 @@ hipError_t launch_select(int32_t W, const int32_t* ncols, const int32_t* nnzw, i
                          int32_t* f_big, int32_t* nnz_if_mfma, hipStream_t s);
 hipError_t launch_compact_ids(int32_t n, const int32_t* flags, const int64_t* pos, int32_t* out, hipStream_t s);
 hipError_t launch_row_class(int32_t n_rows, const int32_t* rowptr, const uint8_t* route, int32_t* f_short,
-                            int32_t* n_seg, int32_t* f_multi, int32_t* n_slot, int32_t* len_long, hipStream_t s);
+                            int32_t* f_mid, int32_t* n_seg, int32_t* f_multi, int32_t* n_slot, int32_t* len_long,
+                            hipStream_t s);
+hipError_t launch_build_desc(int32_t n_list, const int32_t* win_list, int32_t n_rows, const int32_t* rowptr,
+                             const int32_t* ncols, const int64_t* wptr, WinDesc* desc, hipStream_t s);
 hipError_t launch_build_segments(int32_t n_rows, const int32_t* rowptr, const int32_t* n_seg, const int64_t* seg_pos,
                                  const int64_t* multi_pos, const int64_t* slot_pos, Segment* segs, MultiRow* multi,
                                  hipStream_t s);
@@ -82,13 +89,13 @@ struct SpmmArgs {
     int32_t relu;
 };
 
-hipError_t launch_csr_short(const SpmmArgs& a, int32_t n_items, const int32_t* row_list, const uint8_t* route,
-                            hipStream_t s);
-hipError_t launch_csr_long(const SpmmArgs& a, int32_t n_segs, const Segment* segs, float* partial, hipStream_t s);
+hipError_t launch_csr(const SpmmArgs& a, int32_t n_segs, const Segment* segs, float* partial, int32_t n_mid,
+                      const int32_t* mid_rows, int32_t n_items, const int32_t* row_list, const uint8_t* route,
+                      hipStream_t s);
 hipError_t launch_reduce_partials(const SpmmArgs& a, int32_t n_multi, const MultiRow* multi, const float* partial,
                                   hipStream_t s);
-hipError_t launch_mfma_small(const SpmmArgs& a, int32_t n_list, const int32_t* win_list, const int32_t* ncols,
-                             const int64_t* wptr, const int32_t* wcols, const int32_t* erc, hipStream_t s);
+hipError_t launch_mfma_small(const SpmmArgs& a, int32_t n_list, const WinDesc* desc, const int32_t* wcols,
+                             const int32_t* erc, hipStream_t s);
 hipError_t launch_mfma_big(const SpmmArgs& a, int32_t n_list, const int32_t* win_list, const int32_t* ncols,
                            const int64_t* wptr, const int32_t* wcols, const int32_t* erc, hipStream_t s);
 hipError_t launch_gemm_f32(int64_t m, int32_t k, int32_t n, const float* X, int64_t ldx, const float* W, int64_t ldw,
@@ -120,10 +127,13 @@ struct hcspmm_plan {
     int64_t nnz_mfma;
     // owned, launch tables
     int32_t* mfma_small;
+    hcspmm::WinDesc* mfma_small_desc;
     int32_t* mfma_big;
     int32_t n_mfma_small, n_mfma_big;
-    int32_t* short_rows;     // rows of route-0 windows with at most kLongRow non-zeros (NULL: every row qualifies)
+    int32_t* short_rows;     // rows of route-0 windows with at most kMidRow non-zeros (NULL: walk every row)
     int32_t n_short;
+    int32_t* mid_rows;       // rows of route-0 windows with kMidRow < non-zeros <= kLongRow
+    int32_t n_mid;
     hcspmm::Segment* segs;
     int32_t n_segs;
     hcspmm::MultiRow* multi;

@@ -91,7 +91,7 @@ struct DevAlloc {
 static void free_plan_arrays(hcspmm_plan* p)
 {
     void* owned[] = {p->ncols, p->nnzw, p->route, p->wptr, p->wcols, p->erc, p->mfma_windows, p->csr_windows,
-                     p->mfma_small, p->mfma_big, p->short_rows, p->segs, p->multi, p->partial};
+                     p->mfma_small, p->mfma_small_desc, p->mfma_big, p->short_rows, p->mid_rows, p->segs, p->multi, p->partial};
     for (void* q : owned)
         if (q) (void)hipFree(q);
 }
@@ -105,7 +105,7 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     const int64_t nnz = p->nnz;
     int32_t *err = nullptr, *big_list = nullptr, *big_count = nullptr, *tmp_cols = nullptr;
     int32_t *f_mfma = nullptr, *f_csr = nullptr, *f_small = nullptr, *f_big = nullptr, *nnz_if = nullptr;
-    int32_t *f_short = nullptr, *n_seg = nullptr, *f_multi = nullptr, *n_slot = nullptr, *len_long = nullptr;
+    int32_t *f_short = nullptr, *f_mid = nullptr, *n_seg = nullptr, *f_multi = nullptr, *n_slot = nullptr, *len_long = nullptr;
     int64_t *scan_tmp = nullptr, *pos_a = nullptr, *pos_b = nullptr, *pos_c = nullptr, *pos_d = nullptr;
     int64_t *totals_dev = nullptr;
     int32_t h_err = 0, h_big = 0;
@@ -184,17 +184,21 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     HC_TRY(launch_compact_ids(W, f_csr, pos_b, p->csr_windows, stream));
     HC_TRY(launch_compact_ids(W, f_small, pos_c, p->mfma_small, stream));
     HC_TRY(launch_compact_ids(W, f_big, pos_d, p->mfma_big, stream));
+    HC_ALLOC(keep, p->mfma_small_desc, p->n_mfma_small);
+    HC_TRY(launch_build_desc(p->n_mfma_small, p->mfma_small, n_rows, p->rowptr, p->ncols, p->wptr, p->mfma_small_desc,
+                             stream));
     HC_TRY(exclusive_scan_i32_i64(nnz_if, W, pos_a, scan_tmp, stream));
     HC_TRY(hipMemcpyAsync(&p->nnz_mfma, pos_a + W, sizeof(int64_t), hipMemcpyDeviceToHost, stream));
     HC_TRY(hipStreamSynchronize(stream));
 
     // scalar-path launch tables
     HC_ALLOC(tmp, f_short, (size_t)n_rows + 1);
+    HC_ALLOC(tmp, f_mid, (size_t)n_rows + 1);
     HC_ALLOC(tmp, n_seg, (size_t)n_rows + 1);
     HC_ALLOC(tmp, f_multi, (size_t)n_rows + 1);
     HC_ALLOC(tmp, n_slot, (size_t)n_rows + 1);
     HC_ALLOC(tmp, len_long, (size_t)n_rows + 1);
-    HC_TRY(launch_row_class(n_rows, p->rowptr, p->route, f_short, n_seg, f_multi, n_slot, len_long, stream));
+    HC_TRY(launch_row_class(n_rows, p->rowptr, p->route, f_short, f_mid, n_seg, f_multi, n_slot, len_long, stream));
     HC_TRY(exclusive_scan_i32_i64(len_long, n_rows, pos_a, scan_tmp, stream));
     HC_TRY(hipMemcpyAsync(totals_dev + 4, pos_a + n_rows, 8, hipMemcpyDeviceToDevice, stream));
     HC_TRY(exclusive_scan_i32_i64(f_short, n_rows, pos_a, scan_tmp, stream));
@@ -217,6 +221,16 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     HC_ALLOC(keep, p->multi, p->n_multi);
     if (p->n_segs > 0)
         HC_TRY(launch_build_segments(n_rows, p->rowptr, n_seg, pos_b, pos_c, pos_d, p->segs, p->multi, stream));
+    // rows that get a whole wave
+    HC_TRY(exclusive_scan_i32_i64(f_mid, n_rows, pos_b, scan_tmp, stream));
+    {
+        int64_t h_mid = 0;
+        HC_TRY(hipMemcpyAsync(&h_mid, pos_b + n_rows, 8, hipMemcpyDeviceToHost, stream));
+        HC_TRY(hipStreamSynchronize(stream));
+        p->n_mid = (int32_t)h_mid;
+    }
+    HC_ALLOC(keep, p->mid_rows, p->n_mid);
+    HC_TRY(launch_compact_ids(n_rows, f_mid, pos_b, p->mid_rows, stream));
     // Walking every row and skipping the ones another kernel owns is cheaper than an index list
     // while most rows are short scalar-path rows; otherwise keep the explicit list.
     if ((int64_t)p->n_short * 2 < n_rows) {
@@ -238,7 +252,7 @@ fail:
 }
 
 static hcspmm_status run_spmm(const hcspmm_plan* plan, const SpmmArgs& a, hipStream_t stream,
-                              hipEvent_t* ev = nullptr /* 6 events when timing stages */)
+                              hipEvent_t* ev = nullptr /* 5 events when timing stages */)
 {
     hcspmm_plan* p = const_cast<hcspmm_plan*>(plan);
     // long rows cut into several segments need one partial row per segment
@@ -254,19 +268,18 @@ static hcspmm_status run_spmm(const hcspmm_plan* plan, const SpmmArgs& a, hipStr
         }
         p->partial_elems = want;
     }
-    // heaviest work first: long-row segments, then the matrix-path windows, then the short rows
+    // the matrix-path windows first (few, heavy), then every scalar-path row in one launch,
+    // then the sums of the rows that were cut into several segments
     if (ev) HC_HIP(hipEventRecord(ev[0], stream));
-    HC_HIP(launch_csr_long(a, p->n_segs, p->segs, p->partial, stream));
-    if (ev) HC_HIP(hipEventRecord(ev[1], stream));
-    HC_HIP(launch_reduce_partials(a, p->n_multi, p->multi, p->partial, stream));
-    if (ev) HC_HIP(hipEventRecord(ev[2], stream));
     HC_HIP(launch_mfma_big(a, p->n_mfma_big, p->mfma_big, p->ncols, p->wptr, p->wcols, p->erc, stream));
+    if (ev) HC_HIP(hipEventRecord(ev[1], stream));
+    HC_HIP(launch_mfma_small(a, p->n_mfma_small, p->mfma_small_desc, p->wcols, p->erc, stream));
+    if (ev) HC_HIP(hipEventRecord(ev[2], stream));
+    HC_HIP(launch_csr(a, p->n_segs, p->segs, p->partial, p->n_mid, p->mid_rows,
+                      p->short_rows ? p->n_short : (p->n_short > 0 ? p->n_rows : 0), p->short_rows, p->route, stream));
     if (ev) HC_HIP(hipEventRecord(ev[3], stream));
-    HC_HIP(launch_mfma_small(a, p->n_mfma_small, p->mfma_small, p->ncols, p->wptr, p->wcols, p->erc, stream));
+    HC_HIP(launch_reduce_partials(a, p->n_multi, p->multi, p->partial, stream));
     if (ev) HC_HIP(hipEventRecord(ev[4], stream));
-    if (p->short_rows) HC_HIP(launch_csr_short(a, p->n_short, p->short_rows, p->route, stream));
-    else if (p->n_short > 0) HC_HIP(launch_csr_short(a, p->n_rows, nullptr, p->route, stream));
-    if (ev) HC_HIP(hipEventRecord(ev[5], stream));
     return HCSPMM_OK;
 }
 
@@ -352,6 +365,7 @@ hcspmm_status hcspmm_plan_info(const hcspmm_plan* p, hcspmm_plan_info_t* info)
     for (int i = 0; i < 3; ++i) info->sel_coef[i] = p->coef[i];
     info->device_bytes = p->device_bytes + p->partial_elems * (int64_t)sizeof(float);
     info->n_short_rows = p->n_short; info->n_long_rows = p->n_long_rows; info->n_segments = p->n_segs;
+    info->n_mid_rows = p->n_mid;
     info->nnz_long = p->nnz_long; info->n_mfma_small = p->n_mfma_small; info->n_mfma_big = p->n_mfma_big;
     return HCSPMM_OK;
 }
@@ -397,19 +411,18 @@ hcspmm_status hcspmm_spmm_timed(const hcspmm_plan* plan, const void* d_X, int64_
 {
     if (!times) { set_error("times is NULL"); return HCSPMM_EINVAL; }
     memset(times, 0, sizeof *times);
-    hipEvent_t ev[6];
+    hipEvent_t ev[5];
     int made = 0;
     hcspmm_status st = HCSPMM_OK;
-    for (; made < 6; ++made)
+    for (; made < 5; ++made)
         if (hipEventCreate(&ev[made]) != hipSuccess) { (void)hipGetLastError(); set_error("hipEventCreate failed"); st = HCSPMM_EHIP; break; }
     if (st == HCSPMM_OK) st = spmm_impl(plan, d_X, ldx, d, x_dtype, d_Y, ldy, y_dtype, stream, ev);
     if (st == HCSPMM_OK && plan->n_rows > 0) {
-        if (hipEventSynchronize(ev[5]) != hipSuccess) { (void)hipGetLastError(); set_error("hipEventSynchronize failed"); st = HCSPMM_EHIP; }
+        if (hipEventSynchronize(ev[4]) != hipSuccess) { (void)hipGetLastError(); set_error("hipEventSynchronize failed"); st = HCSPMM_EHIP; }
         else {
-            float* out[5] = {&times->ms_csr_long, &times->ms_csr_reduce, &times->ms_mfma_big, &times->ms_mfma_small,
-                             &times->ms_csr_short};
-            for (int i = 0; i < 5; ++i) (void)hipEventElapsedTime(out[i], ev[i], ev[i + 1]);
-            (void)hipEventElapsedTime(&times->ms_total, ev[0], ev[5]);
+            float* out[4] = {&times->ms_mfma_big, &times->ms_mfma_small, &times->ms_csr, &times->ms_csr_reduce};
+            for (int i = 0; i < 4; ++i) (void)hipEventElapsedTime(out[i], ev[i], ev[i + 1]);
+            (void)hipEventElapsedTime(&times->ms_total, ev[0], ev[4]);
         }
     }
     for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);

@@ -425,11 +425,39 @@ hipError_t launch_compact_ids(int32_t n, const int32_t* flags, const int64_t* po
 }
 
 // ------------------------------------------------------------------------------------------------
+// matrix-path launch table: one descriptor per wave-per-window item
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_build_desc(int32_t n_list, const int32_t* __restrict__ win_list,
+                                                    int32_t n_rows, const int32_t* __restrict__ rowptr,
+                                                    const int32_t* __restrict__ ncols,
+                                                    const int64_t* __restrict__ wptr, WinDesc* __restrict__ desc)
+{
+    int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_list) return;
+    WinDesc ds;
+    ds.w = win_list[i];
+    window_span(ds.w, n_rows, rowptr, ds.s, ds.e);
+    ds.nc = ncols[ds.w];
+    ds.wp = wptr[ds.w];
+    ds.pad = 0;
+    desc[i] = ds;
+}
+
+hipError_t launch_build_desc(int32_t n_list, const int32_t* win_list, int32_t n_rows, const int32_t* rowptr,
+                             const int32_t* ncols, const int64_t* wptr, WinDesc* desc, hipStream_t s)
+{
+    if (n_list <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_build_desc, dim3((n_list + 255) / 256), dim3(256), 0, s, n_list, win_list, n_rows, rowptr,
+                       ncols, wptr, desc);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
 // scalar-path launch tables: short rows, and segments of long rows
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_row_class(int32_t n_rows, const int32_t* __restrict__ rowptr,
                                                    const uint8_t* __restrict__ route, int32_t* __restrict__ f_short,
-                                                   int32_t* __restrict__ n_seg, int32_t* __restrict__ f_multi,
+                                                   int32_t* __restrict__ f_mid, int32_t* __restrict__ n_seg, int32_t* __restrict__ f_multi,
                                                    int32_t* __restrict__ n_slot, int32_t* __restrict__ len_long)
 {
     int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -437,20 +465,23 @@ __global__ __launch_bounds__(256) void k_row_class(int32_t n_rows, const int32_t
     const int32_t len = rowptr[i + 1] - rowptr[i];
     const bool csr = route[i / kH] == 0;
     const bool is_long = csr && len > kLongRow;
+    const bool is_mid = csr && !is_long && len > kMidRow;
     const int32_t ns = is_long ? (len + kSegLen - 1) / kSegLen : 0;
-    f_short[i] = (csr && !is_long) ? 1 : 0;
+    f_short[i] = (csr && !is_long && !is_mid) ? 1 : 0;
+    f_mid[i] = is_mid ? 1 : 0;
     n_seg[i] = ns;
     f_multi[i] = ns > 1 ? 1 : 0;
     n_slot[i] = ns > 1 ? ns : 0;
-    len_long[i] = is_long ? len : 0;
+    len_long[i] = (is_long || is_mid) ? len : 0;
 }
 
 hipError_t launch_row_class(int32_t n_rows, const int32_t* rowptr, const uint8_t* route, int32_t* f_short,
-                            int32_t* n_seg, int32_t* f_multi, int32_t* n_slot, int32_t* len_long, hipStream_t s)
+                            int32_t* f_mid, int32_t* n_seg, int32_t* f_multi, int32_t* n_slot, int32_t* len_long,
+                            hipStream_t s)
 {
     if (n_rows <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_row_class, dim3((n_rows + 255) / 256), dim3(256), 0, s, n_rows, rowptr, route, f_short, n_seg,
-                       f_multi, n_slot, len_long);
+    hipLaunchKernelGGL(k_row_class, dim3((n_rows + 255) / 256), dim3(256), 0, s, n_rows, rowptr, route, f_short, f_mid,
+                       n_seg, f_multi, n_slot, len_long);
     return hipGetLastError();
 }
 

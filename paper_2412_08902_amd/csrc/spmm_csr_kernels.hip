@@ -3,10 +3,15 @@
 // each lane one slice of the dense width, so X rows are read as whole contiguous segments).
 //
 // wave64 mapping: a group of LPR lanes owns a row, every lane holds VEC consecutive output
-// columns, so a 64-lane wave works on 64/LPR rows (short rows) or on 64/LPR non-zeros of the same
-// row (long rows) per load instruction.  Column indices and values are fetched LPR at a time with
-// one coalesced load per group and handed round with cross-lane reads; X itself is read directly
-// from global memory / L2 (the paper found staging X in shared memory a loss on this path).
+// columns; a 64-lane wave therefore works on 64/LPR rows (short rows) or on 64/LPR non-zeros of
+// the same row (mid and long rows) per load instruction.  Column indices and values are fetched
+// LPR at a time with one coalesced load per group and handed round with cross-lane reads; X is
+// read directly from global memory / L2 (the paper found staging X in shared memory a loss on
+// this path).  Three tiers by row length balance power-law degree distributions:
+//   short rows  a lane group walks up to kRowsPerGroup consecutive rows in one flattened loop;
+//   mid rows    one wave per row, the groups stride over the row and combine with cross-lane adds;
+//   long rows   one workgroup per segment of kSegLen non-zeros, combined through LDS in a fixed
+//               order (and, for rows of several segments, through partial rows in memory).
 #include "common.hpp"
 
 namespace hcspmm {
@@ -41,79 +46,158 @@ template <int VEC> __device__ inline void vstore(float* __restrict__ p, const fl
     *reinterpret_cast<V*>(p) = v;
 }
 
-// Accumulate  acc += sum_{k in [kb, ke) taken LPR at a time with stride `stride`} val[k] * X[col[k], c .. c+VEC)
-// for the group's lane `lig`.  All lanes of a group execute this together.
+// One batch: the group's lanes hold up to LPR (column, value) pairs; every lane accumulates
+// val * X[col, c .. c+VEC) over the batch.  Slots past the end of the row carry the row's last
+// column with value 0, so the loads carry no branches and all of them are in flight together.
+// Xc already points at a valid column for every lane (lanes past the matrix width read column 0
+// and never store).
 template <int LPR, int VEC>
-__device__ inline void row_accumulate(int kb, int ke, int stride, int lig, bool col_ok,
-                                      const int32_t* __restrict__ colind, const float* __restrict__ vals,
-                                      const float* __restrict__ Xc /* X + column offset of this lane */, int64_t ldx,
-                                      float (&acc)[VEC])
+__device__ inline void batch_accumulate(int32_t mc, float mv, int cnt, const float* __restrict__ Xc,
+                                        int64_t ldx, float (&acc)[VEC])
 {
     constexpr int U = LPR < 8 ? LPR : 8;
-    for (int k0 = kb; k0 < ke; k0 += stride) {
-        const int k = k0 + lig;
-        const int32_t mc = k < ke ? colind[k] : 0;
-        const float mv = k < ke ? vals[k] : 0.f;
-        const int cnt = min(LPR, ke - k0);
-        int t0 = 0;
-        for (; t0 + U <= cnt; t0 += U) {
-            float x[U][VEC];
-            float v[U];
+#pragma unroll 1
+    for (int t0 = 0; t0 < cnt; t0 += U) {
+        float x[U][VEC];
+        float v[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int32_t c = __shfl(mc, t0 + u, LPR);
-                v[u] = __shfl(mv, t0 + u, LPR);
-                if (col_ok) vload<VEC>(Xc + (int64_t)c * ldx, x[u]);
-                else vzero<VEC>(x[u]);
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) acc[i] = fmaf(v[u], x[u][i], acc[i]);
+        for (int u = 0; u < U; ++u) {
+            const int32_t c = __shfl(mc, t0 + u, LPR);
+            v[u] = __shfl(mv, t0 + u, LPR);
+            vload<VEC>(Xc + (int64_t)c * ldx, x[u]);
         }
-        for (; t0 < cnt; ++t0) {
-            const int32_t c = __shfl(mc, t0, LPR);
-            const float v = __shfl(mv, t0, LPR);
-            float x[VEC];
-            if (col_ok) vload<VEC>(Xc + (int64_t)c * ldx, x);
-            else vzero<VEC>(x);
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) acc[i] = fmaf(v, x[i], acc[i]);
-        }
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] = fmaf(v[u], x[u][i], acc[i]);
     }
 }
 
-// ---- short rows: one group of LPR lanes per row -------------------------------------------------
-template <int LPR, int VEC>
-__global__ __launch_bounds__(256) void k_csr_short(int32_t n_items, const int32_t* __restrict__ row_list,
-                                                   const uint8_t* __restrict__ route, SpmmArgs a)
+// (column, value) of non-zero k of a row ending at e (k may run past the end: value 0, last column)
+__device__ inline void fetch_entry(const int32_t* __restrict__ colind, const float* __restrict__ vals, int k, int e,
+                                   int32_t& c, float& v)
 {
+    const int kc = min(k, e - 1);
+    c = colind[kc];
+    const float t = vals[kc];
+    v = k < e ? t : 0.f;
+}
+
+// Accumulate a span [kb, ke) of one row taken LPR non-zeros at a time with stride `stride`
+// (stride = LPR when one group owns the span, larger when several groups share it).
+template <int LPR, int VEC>
+__device__ inline void span_accumulate(int kb, int ke, int stride, int lig,
+                                       const int32_t* __restrict__ colind, const float* __restrict__ vals,
+                                       const float* __restrict__ Xc, int64_t ldx, float (&acc)[VEC])
+{
+    if (kb >= ke) return;
+    int32_t mc, nc;
+    float mv, nv;
+    fetch_entry(colind, vals, kb + lig, ke, mc, mv);
+    for (int k0 = kb; k0 < ke; k0 += stride) {
+        // fetch the next batch's indices before this batch's X rows
+        fetch_entry(colind, vals, k0 + stride + lig, ke, nc, nv);
+        batch_accumulate<LPR, VEC>(mc, mv, min(LPR, ke - k0), Xc, ldx, acc);
+        mc = nc;
+        mv = nv;
+    }
+}
+
+// ---- short rows -----------------------------------------------------------------------------
+// A group of LPR lanes walks rows_per_group (<= kRowsPerGroup) consecutive items (rows, or entries of row_list) in a
+// single flattened loop: each trip either moves to the next row (storing the finished one) or
+// consumes one batch of the current row, so groups of one wave stay busy on rows of unequal
+// length.  The rows' extents are fetched up front, one per lane.
+template <int LPR, int VEC>
+__device__ inline void csr_short_body(int64_t block, int32_t n_items, const int32_t* __restrict__ row_list,
+                                      const uint8_t* __restrict__ route, int rows_per_group, const SpmmArgs& a)
+{
+    static_assert(LPR >= kRowsPerGroup, "a group must be able to hold one row extent per lane");
     constexpr int GPB = 256 / LPR;
-    const int64_t item = (int64_t)blockIdx.x * GPB + threadIdx.x / LPR;
+    const int64_t blk = block * GPB + threadIdx.x / LPR;
     const int lig = threadIdx.x % LPR;
-    if (item >= n_items) return;
-    const int32_t row = row_list ? row_list[item] : (int32_t)item;
-    const int32_t s = a.rowptr[row], e = a.rowptr[row + 1];
-    if (!row_list && (route[row / kH] != 0 || e - s > kLongRow)) return;
+    const int64_t i0 = blk * rows_per_group;
+    if (i0 >= n_items) return;
+    const int nr = (int)min((int64_t)rows_per_group, (int64_t)n_items - i0);
+    int32_t my_row = -1, my_s = 0, my_e = 0;
+    if (lig < nr) {
+        my_row = row_list ? row_list[i0 + lig] : (int32_t)(i0 + lig);
+        my_s = a.rowptr[my_row];
+        my_e = a.rowptr[my_row + 1];
+        // walking every row: skip rows owned by the matrix path or by the mid/long-row kernels
+        if (!row_list && (route[my_row / kH] != 0 || my_e - my_s > kMidRow)) my_row = -1;
+    }
     const float* __restrict__ X = static_cast<const float*>(a.X);
     for (int c0 = 0; c0 < a.d; c0 += LPR * VEC) {
         const int c = c0 + lig * VEC;
         const bool col_ok = c < a.d;
         float acc[VEC];
         vzero<VEC>(acc);
-        row_accumulate<LPR, VEC>(s, e, LPR, lig, col_ok, a.colind, a.vals, X + c, a.ldx, acc);
-        if (col_ok) vstore<VEC>(a.Y + (int64_t)row * a.ldy + c, acc, a.relu);
+        int j = 0, k = 0, e = 0;
+        int32_t row = -1;
+        int32_t mc = 0;
+        float mv = 0.f;
+        for (;;) {
+            if (k >= e) {
+                if (row >= 0 && col_ok) vstore<VEC>(a.Y + (int64_t)row * a.ldy + c, acc, a.relu);
+                row = -1;
+                while (j < nr && row < 0) {
+                    row = __shfl(my_row, j, LPR);
+                    k = __shfl(my_s, j, LPR);
+                    e = __shfl(my_e, j, LPR);
+                    ++j;
+                }
+                if (row < 0) break;
+                vzero<VEC>(acc);
+                if (k < e) fetch_entry(a.colind, a.vals, k + lig, e, mc, mv);
+                continue;                       // an empty row is stored (as zeros) on the next trip
+            }
+            int32_t nc;
+            float nv;
+            fetch_entry(a.colind, a.vals, k + LPR + lig, e, nc, nv);
+            batch_accumulate<LPR, VEC>(mc, mv, min(LPR, e - k), X + (col_ok ? c : 0), a.ldx, acc);
+            mc = nc;
+            mv = nv;
+            k += LPR;
+        }
     }
 }
 
-// ---- long rows: one workgroup per segment of a row ----------------------------------------------
+// ---- mid rows: one wave per row -------------------------------------------------------------
 template <int LPR, int VEC>
-__global__ __launch_bounds__(256) void k_csr_long(const Segment* __restrict__ segs, float* __restrict__ partial,
-                                                  SpmmArgs a)
+__device__ inline void csr_mid_body(int64_t block, int32_t n_mid, const int32_t* __restrict__ mid_rows,
+                                    const SpmmArgs& a)
+{
+    constexpr int G = 64 / LPR;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t item = block * 4 + wave;
+    if (item >= n_mid) return;
+    const int32_t row = mid_rows[item];
+    const int32_t s = a.rowptr[row], e = a.rowptr[row + 1];
+    const int g = lane / LPR, lig = lane % LPR;
+    const float* __restrict__ X = static_cast<const float*>(a.X);
+    for (int c0 = 0; c0 < a.d; c0 += LPR * VEC) {
+        const int c = c0 + lig * VEC;
+        const bool col_ok = c < a.d;
+        float acc[VEC];
+        vzero<VEC>(acc);
+        span_accumulate<LPR, VEC>(s + g * LPR, e, G * LPR, lig, a.colind, a.vals, X + (col_ok ? c : 0), a.ldx, acc);
+        // butterfly over the G groups: same operation order on every run
+#pragma unroll
+        for (int off = LPR; off < 64; off <<= 1)
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] += __shfl_xor(acc[i], off, 64);
+        if (g == 0 && col_ok) vstore<VEC>(a.Y + (int64_t)row * a.ldy + c, acc, a.relu);
+    }
+}
+
+// ---- long rows: one workgroup per segment of a row ------------------------------------------
+template <int LPR, int VEC>
+__device__ inline void csr_long_body(int64_t block, const Segment* __restrict__ segs, float* __restrict__ partial,
+                                     float* __restrict__ red /* LDS, 256*VEC floats */, const SpmmArgs& a)
 {
     constexpr int G = 256 / LPR;
-    __shared__ float red[256 * VEC];
-    const Segment sg = segs[blockIdx.x];
+    const Segment sg = segs[block];
     const int g = threadIdx.x / LPR, lig = threadIdx.x % LPR;
     const float* __restrict__ X = static_cast<const float*>(a.X);
     for (int c0 = 0; c0 < a.d; c0 += LPR * VEC) {
@@ -121,8 +205,8 @@ __global__ __launch_bounds__(256) void k_csr_long(const Segment* __restrict__ se
         const bool col_ok = c < a.d;
         float acc[VEC];
         vzero<VEC>(acc);
-        row_accumulate<LPR, VEC>(sg.k_begin + g * LPR, sg.k_end, G * LPR, lig, col_ok, a.colind, a.vals, X + c,
-                                 a.ldx, acc);
+        span_accumulate<LPR, VEC>(sg.k_begin + g * LPR, sg.k_end, G * LPR, lig, a.colind, a.vals,
+                                  X + (col_ok ? c : 0), a.ldx, acc);
         // fixed-order tree over the G groups: the result does not depend on scheduling
 #pragma unroll
         for (int i = 0; i < VEC; ++i) red[(g * LPR + lig) * VEC + i] = acc[i];
@@ -145,7 +229,42 @@ __global__ __launch_bounds__(256) void k_csr_long(const Segment* __restrict__ se
     }
 }
 
-// ---- rows cut into several segments: add the partial rows in segment order ----------------------
+// ---- one launch for all three tiers ---------------------------------------------------------
+// Workgroups are numbered heaviest first: long-row segments, then mid rows (four per workgroup),
+// then the blocks of short rows, so the short rows fill the machine while the last long rows
+// drain instead of each tier waiting for the previous one's tail.
+struct CsrWork {
+    int32_t n_segs;
+    const Segment* segs;
+    float* partial;
+    int32_t n_mid;
+    const int32_t* mid_rows;
+    int32_t n_items;
+    const int32_t* row_list;
+    const uint8_t* route;
+    int32_t rows_per_group;
+};
+
+template <int LPR, int VEC>
+__global__ __launch_bounds__(256) void k_csr(CsrWork wk, SpmmArgs a)
+{
+    __shared__ float red[256 * VEC];
+    int64_t b = blockIdx.x;
+    if (b < wk.n_segs) {
+        csr_long_body<LPR, VEC>(b, wk.segs, wk.partial, red, a);
+        return;
+    }
+    b -= wk.n_segs;
+    const int64_t mid_blocks = ((int64_t)wk.n_mid + 3) / 4;
+    if (b < mid_blocks) {
+        csr_mid_body<LPR, VEC>(b, wk.n_mid, wk.mid_rows, a);
+        return;
+    }
+    b -= mid_blocks;
+    csr_short_body<LPR, VEC>(b, wk.n_items, wk.row_list, wk.route, wk.rows_per_group, a);
+}
+
+// ---- rows cut into several segments: add the partial rows in segment order ------------------
 __global__ __launch_bounds__(256) void k_reduce_partials(int32_t n_multi, const MultiRow* __restrict__ multi,
                                                          const float* __restrict__ partial, SpmmArgs a)
 {
@@ -157,7 +276,7 @@ __global__ __launch_bounds__(256) void k_reduce_partials(int32_t n_multi, const 
     }
 }
 
-// ---- dispatch -------------------------------------------------------------------------------------
+// ---- dispatch ---------------------------------------------------------------------------------
 struct CsrShape { int lpr, vec; };
 
 static CsrShape pick_shape(const SpmmArgs& a, const float* partial)
@@ -166,51 +285,47 @@ static CsrShape pick_shape(const SpmmArgs& a, const float* partial)
     const uintptr_t px = (uintptr_t)a.X, py = (uintptr_t)a.Y, pp = (uintptr_t)partial;
     if (a.d % 4 == 0 && a.ldx % 4 == 0 && a.ldy % 4 == 0 && px % 16 == 0 && py % 16 == 0 && pp % 16 == 0) vec = 4;
     else if (a.d % 2 == 0 && a.ldx % 2 == 0 && a.ldy % 2 == 0 && px % 8 == 0 && py % 8 == 0 && pp % 8 == 0) vec = 2;
+    // a group needs at least kRowsPerGroup lanes; narrow the vectors of narrow matrices instead of idling lanes
+    while (vec > 1 && (a.d + vec - 1) / vec < kRowsPerGroup) vec >>= 1;
     const int lanes = (a.d + vec - 1) / vec;       // lanes needed to cover the width once
-    int lpr = 4;
+    int lpr = kRowsPerGroup;
     while (lpr < 64 && lpr < lanes) lpr <<= 1;
     return {lpr, vec};
 }
 
 #define HC_CSR_DISPATCH(FN)                                                                        \
     switch (sh.vec * 100 + sh.lpr) {                                                               \
-        case 404: FN(4, 4); break;                                                                 \
         case 408: FN(8, 4); break;                                                                 \
         case 416: FN(16, 4); break;                                                                \
         case 432: FN(32, 4); break;                                                                \
         case 464: FN(64, 4); break;                                                                \
-        case 204: FN(4, 2); break;                                                                 \
         case 208: FN(8, 2); break;                                                                 \
         case 216: FN(16, 2); break;                                                                \
         case 232: FN(32, 2); break;                                                                \
         case 264: FN(64, 2); break;                                                                \
-        case 104: FN(4, 1); break;                                                                 \
         case 108: FN(8, 1); break;                                                                 \
         case 116: FN(16, 1); break;                                                                \
         case 132: FN(32, 1); break;                                                                \
         default: FN(64, 1); break;                                                                 \
     }
 
-hipError_t launch_csr_short(const SpmmArgs& a, int32_t n_items, const int32_t* row_list, const uint8_t* route,
-                            hipStream_t s)
+hipError_t launch_csr(const SpmmArgs& a, int32_t n_segs, const Segment* segs, float* partial, int32_t n_mid,
+                      const int32_t* mid_rows, int32_t n_items, const int32_t* row_list, const uint8_t* route,
+                      hipStream_t s)
 {
-    if (n_items <= 0) return hipSuccess;
-    const CsrShape sh = pick_shape(a, nullptr);
-#define HC_LAUNCH_SHORT(L, V)                                                                      \
-    hipLaunchKernelGGL((k_csr_short<L, V>), dim3((unsigned)(((int64_t)n_items + (256 / L) - 1) / (256 / L))),     \
-                       dim3(256), 0, s, n_items, row_list, route, a)
-    HC_CSR_DISPATCH(HC_LAUNCH_SHORT)
-#undef HC_LAUNCH_SHORT
-    return hipGetLastError();
-}
-
-hipError_t launch_csr_long(const SpmmArgs& a, int32_t n_segs, const Segment* segs, float* partial, hipStream_t s)
-{
-    if (n_segs <= 0) return hipSuccess;
     const CsrShape sh = pick_shape(a, partial);
-#define HC_LAUNCH_LONG(L, V) hipLaunchKernelGGL((k_csr_long<L, V>), dim3(n_segs), dim3(256), 0, s, segs, partial, a)
-    HC_CSR_DISPATCH(HC_LAUNCH_LONG)
-#undef HC_LAUNCH_LONG
+    // several consecutive rows per lane group amortise the per-row set-up, but only while the
+    // launch still has tens of thousands of waves to hide the rows' dependent-load latencies
+    int rpg = kRowsPerGroup;
+    while (rpg > 1 && ((int64_t)n_items / rpg) * sh.lpr / 64 < 32768) rpg >>= 1;
+    const int64_t n_groups = ((int64_t)n_items + rpg - 1) / rpg;
+    const int gpb = 256 / sh.lpr;
+    const int64_t blocks = (int64_t)n_segs + ((int64_t)n_mid + 3) / 4 + (n_groups + gpb - 1) / gpb;
+    if (blocks <= 0) return hipSuccess;
+    CsrWork wk{n_segs, segs, partial, n_mid, mid_rows, n_items, row_list, route, rpg};
+#define HC_LAUNCH_CSR(L, V) hipLaunchKernelGGL((k_csr<L, V>), dim3((unsigned)blocks), dim3(256), 0, s, wk, a)
+    HC_CSR_DISPATCH(HC_LAUNCH_CSR)
+#undef HC_LAUNCH_CSR
     return hipGetLastError();
 }
 

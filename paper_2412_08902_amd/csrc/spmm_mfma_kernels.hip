@@ -16,6 +16,10 @@
 // row): a k-major LDS image  tile[k*16 + row], zeroed and then filled with LDS float adds, so
 // duplicate entries accumulate.  Read back, lane l of K-step q needs tile[(4q + l/16)*16 + l%16]
 // = tile[64q + l]: conflict-free.
+//
+// Like any dense-tile formulation (the paper's included) this path multiplies every gathered X
+// row with explicit zeros, so X must be finite: a NaN or Inf in a gathered row reaches all 16
+// rows of the window, not only the rows that reference it.
 #include "common.hpp"
 
 namespace hcspmm {
@@ -28,51 +32,77 @@ template <> struct XVec<2> { using type = float2; };
 template <> struct XVec<1> { using type = float; };
 
 template <int VW>
-__device__ inline void load_x(const float* __restrict__ p, bool ok, float (&x)[VW])
+__device__ inline void load_x(const float* __restrict__ p, float (&x)[VW])
 {
     using V = typename XVec<VW>::type;
-    if (ok) {
-        V v = *reinterpret_cast<const V*>(p);
-        const float* f = reinterpret_cast<const float*>(&v);
+    V v = *reinterpret_cast<const V*>(p);
+    const float* f = reinterpret_cast<const float*>(&v);
 #pragma unroll
-        for (int i = 0; i < VW; ++i) x[i] = f[i];
-    } else {
+    for (int i = 0; i < VW; ++i) x[i] = f[i];
+}
+
+// A run of up to 16*NCR K-steps (64*NCR condensed columns) for one wave, software-pipelined:
+// the X rows of stage s+1 are requested before the MFMAs of stage s are issued, so the gather
+// latency hides behind the matrix work of the same wave.
+//   tile   : LDS image of the A columns of this run (k-major, tile[k*16 + row])
+//   mycol  : the run's column ids, lane l of mycol[i] holds condensed column 64*i + l; slots past the
+//            window's last column repeat that last column (their A entries are zero), so every load
+//            is unconditional and a whole stage is in flight together
+template <int VW, int NG> struct MfmaPipe {
+    static constexpr int U = (NG * VW >= 8) ? 4 : 8;       // K-steps per pipeline stage
+};
+
+// requests the X rows of K-steps [st*U, st*U + U) of a run into buf
+template <int VW, int NG, int NCR>
+__device__ inline void mfma_stage_load(int st, const int32_t (&mycol)[NCR], int lane, const float* __restrict__ X,
+                                       int64_t ldx, int d, float (&buf)[MfmaPipe<VW, NG>::U][NG][VW])
+{
+    constexpr int U = MfmaPipe<VW, NG>::U;
+    const int j = lane & 15, kk = lane >> 4;
 #pragma unroll
-        for (int i = 0; i < VW; ++i) x[i] = 0.f;
+    for (int u = 0; u < U; ++u) {
+        const int q = st * U + u;
+        const int32_t c = __shfl(mycol[q >> 4], 4 * (q & 15) + kk, 64);
+        const float* __restrict__ xr = X + (int64_t)c * ldx;
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            const int col = g * 16 * VW + VW * j;           // columns past d read column 0 and are never stored
+            load_x<VW>(xr + (col < d ? col : 0), buf[u][g]);
+        }
     }
 }
 
-// One block of up to 16 K-steps (64 condensed columns starting at tile column kb) for one wave.
-//   tile   : LDS image of the A chunk (k-major), kb indexes into it
-//   cols   : this wave's 64 column ids for the block, lane l holds column kb + l (or -1 past the end)
 template <int VW, int NG>
-__device__ inline void mfma_block(const float* __restrict__ tile, int kb, int nsteps, int32_t mycol, int lane,
-                                  const float* __restrict__ X, int64_t ldx, int d, v4f (&acc)[NG][VW])
+__device__ inline void mfma_stage_compute(int st, const float* __restrict__ tile, int lane,
+                                          const float (&buf)[MfmaPipe<VW, NG>::U][NG][VW], v4f (&acc)[NG][VW])
 {
-    const int j = lane & 15, kk = lane >> 4;
-    constexpr int U = 4;                                   // K-steps whose X loads are issued together
-    for (int q0 = 0; q0 < nsteps; q0 += U) {
-        float xa[U][NG][VW];
-        float av[U];
+    constexpr int U = MfmaPipe<VW, NG>::U;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int q = q0 + u;
-            const bool step_ok = q < nsteps;
-            const int32_t c = __shfl(mycol, 4 * (q & 15) + kk, 64);
-            av[u] = step_ok ? tile[(kb + 4 * q) * 16 + lane] : 0.f;
+    for (int u = 0; u < U; ++u) {
+        const int q = st * U + u;
+        const float av = tile[4 * q * 16 + lane];
 #pragma unroll
-            for (int g = 0; g < NG; ++g) {
-                const int col = g * 16 * VW + VW * j;
-                load_x<VW>(X + (int64_t)c * ldx + col, step_ok && c >= 0 && col < d, xa[u][g]);
-            }
-        }
+        for (int g = 0; g < NG; ++g)
 #pragma unroll
-        for (int u = 0; u < U; ++u)
+            for (int t = 0; t < VW; ++t)
+                acc[g][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, buf[u][g][t], acc[g][t], 0, 0, 0);
+    }
+}
+
+// PRELOADED: stage 0 of the run is already in flight in xa[0] (requested by the caller before it
+// built the A tile, so that the first gather overlaps the tile construction).
+template <int VW, int NG, int NCR, bool PRELOADED>
+__device__ inline void mfma_run(const float* __restrict__ tile, int nsteps, const int32_t (&mycol)[NCR], int lane,
+                                const float* __restrict__ X, int64_t ldx, int d,
+                                float (&xa)[2][MfmaPipe<VW, NG>::U][NG][VW], v4f (&acc)[NG][VW])
+{
+    constexpr int U = MfmaPipe<VW, NG>::U;
+    constexpr int NST = 16 * NCR / U;
 #pragma unroll
-            for (int g = 0; g < NG; ++g)
-#pragma unroll
-                for (int t = 0; t < VW; ++t)
-                    acc[g][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u], xa[u][g][t], acc[g][t], 0, 0, 0);
+    for (int st = 0; st <= NST; ++st) {
+        if (st < NST && st * U < nsteps && !(PRELOADED && st == 0))
+            mfma_stage_load<VW, NG, NCR>(st, mycol, lane, X, ldx, d, xa[st & 1]);
+        if (st >= 1 && (st - 1) * U < nsteps) mfma_stage_compute<VW, NG>(st - 1, tile, lane, xa[(st - 1) & 1], acc);
     }
 }
 
@@ -105,35 +135,69 @@ __device__ inline void store_tile(const v4f (&acc)[NG][VW], int lane, int32_t r0
 // ---- wave per window --------------------------------------------------------------------------
 // Four independent waves per workgroup; each owns a private kKcSmall x 16 LDS tile and one window.
 // No workgroup barrier: LDS traffic of a wave is issued and completed in program order.
+// The dependent chain of a window is kept short: one descriptor read (scalar), then the column
+// list and the first kEdgeRegs*64 non-zeros in one go, then the first X rows, and only then the
+// LDS work that builds the A tile.
+constexpr int kEdgeRegs = 6;
+
 template <int VW, int NG>
-__global__ __launch_bounds__(256) void k_mfma_small(int32_t n_list, const int32_t* __restrict__ win_list,
-                                                    const int32_t* __restrict__ ncols,
-                                                    const int64_t* __restrict__ wptr,
+__global__ __launch_bounds__(256) void k_mfma_small(int32_t n_list, const WinDesc* __restrict__ desc,
                                                     const int32_t* __restrict__ wcols,
                                                     const int32_t* __restrict__ erc, int col0, SpmmArgs a)
 {
     __shared__ float tiles[4][kKcSmall * 16];
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int64_t item = (int64_t)blockIdx.x * 4 + wave;
     if (item >= n_list) return;
-    const int32_t w = win_list[item];
-    const int32_t r0 = w * kH;
-    const int32_t s = a.rowptr[r0];
-    const int32_t e = a.rowptr[min(r0 + kH, a.n_rows)];
-    const int32_t nc = ncols[w];
-    const int64_t wp = wptr[w];
+    const WinDesc ds = desc[item];
+    const int32_t r0 = ds.w * kH, s = ds.s, e = ds.e, nc = ds.nc;
+    const int64_t wp = ds.wp;
     float* __restrict__ tile = tiles[wave];
     const float* __restrict__ X = static_cast<const float*>(a.X) + col0;
     const int d = min(a.d - col0, NG * 16 * VW);
+    constexpr int NCR = kKcSmall / 64;
     v4f acc[NG][VW];
 #pragma unroll
     for (int g = 0; g < NG; ++g)
 #pragma unroll
         for (int t = 0; t < VW; ++t) acc[g][t] = (v4f){0.f, 0.f, 0.f, 0.f};
+    float xa[2][MfmaPipe<VW, NG>::U][NG][VW];
 
-    for (int32_t kc0 = 0; kc0 < nc; kc0 += kKcSmall) {
+    // first chunk: column list, non-zeros and first X rows requested back to back
+    int32_t mycol[NCR];
+#pragma unroll
+    for (int i = 0; i < NCR; ++i) mycol[i] = wcols[wp + min(64 * i + lane, nc - 1)];
+    int32_t pe[kEdgeRegs];
+    float ve[kEdgeRegs];
+#pragma unroll
+    for (int q = 0; q < kEdgeRegs; ++q) {
+        const int32_t k = min(s + 64 * q + lane, e - 1);
+        pe[q] = erc[k];
+        ve[q] = a.vals[k];
+    }
+    mfma_stage_load<VW, NG, NCR>(0, mycol, lane, X, a.ldx, d, xa[0]);
+    for (int i = lane * 4; i < kKcSmall * 16; i += 256)
+        *reinterpret_cast<float4*>(&tile[i]) = make_float4(0.f, 0.f, 0.f, 0.f);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+#pragma unroll
+    for (int q = 0; q < kEdgeRegs; ++q) {
+        const int32_t ec = pe[q] >> 4;
+        if (s + 64 * q + lane < e && ec < kKcSmall) atomicAdd(&tile[ec * 16 + (pe[q] & 15)], ve[q]);
+    }
+    for (int32_t k = s + 64 * kEdgeRegs + lane; k < e; k += 64) {
+        const int32_t p = erc[k];
+        const int32_t ec = p >> 4;
+        if (ec < kKcSmall) atomicAdd(&tile[ec * 16 + (p & 15)], a.vals[k]);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    mfma_run<VW, NG, NCR, true>(tile, (min(kKcSmall, nc) + 3) >> 2, mycol, lane, X, a.ldx, d, xa, acc);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+
+    // further chunks of wider windows
+    for (int32_t kc0 = kKcSmall; kc0 < nc; kc0 += kKcSmall) {
         const int kend = min(kKcSmall, nc - kc0);
-        const int32_t mycol = lane < kend ? wcols[wp + kc0 + lane] : -1;
+#pragma unroll
+        for (int i = 0; i < NCR; ++i) mycol[i] = wcols[wp + min(kc0 + 64 * i + lane, nc - 1)];
         for (int i = lane * 4; i < kKcSmall * 16; i += 256)
             *reinterpret_cast<float4*>(&tile[i]) = make_float4(0.f, 0.f, 0.f, 0.f);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -143,7 +207,7 @@ __global__ __launch_bounds__(256) void k_mfma_small(int32_t n_list, const int32_
             if (ec >= 0 && ec < kKcSmall) atomicAdd(&tile[ec * 16 + (p & 15)], a.vals[k]);
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        mfma_block<VW, NG>(tile, 0, (kend + 3) >> 2, mycol, lane, X, a.ldx, d, acc);
+        mfma_run<VW, NG, NCR, false>(tile, (kend + 3) >> 2, mycol, lane, X, a.ldx, d, xa, acc);
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     }
     store_tile<VW, NG>(acc, lane, r0, a.n_rows, a.Y + col0, a.ldy, d, a.relu);
@@ -176,6 +240,7 @@ __global__ __launch_bounds__(256) void k_mfma_big(const int32_t* __restrict__ wi
 #pragma unroll
         for (int t = 0; t < VW; ++t) acc[g][t] = (v4f){0.f, 0.f, 0.f, 0.f};
 
+    float xa[2][MfmaPipe<VW, NG>::U][NG][VW];
     for (int32_t kc0 = 0; kc0 < nc; kc0 += kKcBig) {
         const int kend = min(kKcBig, nc - kc0);
         for (int i = threadIdx.x * 4; i < kKcBig * 16; i += 1024)
@@ -188,9 +253,10 @@ __global__ __launch_bounds__(256) void k_mfma_big(const int32_t* __restrict__ wi
         }
         __syncthreads();
         for (int kb = wave * 64; kb < kend; kb += 256) {
-            const int32_t mycol = kb + lane < kend ? wcols[wp + kc0 + kb + lane] : -1;
+            int32_t mycol[1];
+            mycol[0] = wcols[wp + min(kc0 + kb + lane, nc - 1)];
             const int nsteps = (min(64, kend - kb) + 3) >> 2;
-            mfma_block<VW, NG>(tile, kb, nsteps, mycol, lane, X, a.ldx, d, acc);
+            mfma_run<VW, NG, 1, false>(tile + kb * 16, nsteps, mycol, lane, X, a.ldx, d, xa, acc);
         }
         __syncthreads();
     }
@@ -249,16 +315,16 @@ static MfmaShape pick_mfma_shape(const SpmmArgs& a)
         default: FN(1, 4); break;                                                                  \
     }
 
-hipError_t launch_mfma_small(const SpmmArgs& a, int32_t n_list, const int32_t* win_list, const int32_t* ncols,
-                             const int64_t* wptr, const int32_t* wcols, const int32_t* erc, hipStream_t s)
+hipError_t launch_mfma_small(const SpmmArgs& a, int32_t n_list, const WinDesc* desc, const int32_t* wcols,
+                             const int32_t* erc, hipStream_t s)
 {
     if (n_list <= 0) return hipSuccess;
     const MfmaShape sh = pick_mfma_shape(a);
     const int span = sh.ng * 16 * sh.vw;                       // output columns per launch
     for (int col0 = 0; col0 < a.d; col0 += span) {
 #define HC_LAUNCH_MS(V, G)                                                                         \
-    hipLaunchKernelGGL((k_mfma_small<V, G>), dim3((unsigned)((n_list + 3) / 4)), dim3(256), 0, s, n_list, win_list,  \
-                       ncols, wptr, wcols, erc, col0, a)
+    hipLaunchKernelGGL((k_mfma_small<V, G>), dim3((unsigned)((n_list + 3) / 4)), dim3(256), 0, s, n_list, desc,      \
+                       wcols, erc, col0, a)
         HC_MFMA_DISPATCH(HC_LAUNCH_MS)
 #undef HC_LAUNCH_MS
     }
