@@ -27,6 +27,13 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM-side bytes per launch of the dominant kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
+# summarised under profiles/ (each counter scaled by what it reads for a 1 GiB copy kernel in the
+# same run).  Keyed by (workload, kernel); None where no counter run exists for the pair.
+MEASURED_TRAFFIC_BYTES = {
+    ("C4", "k_csr"): 16.24e9 + 0.314e9,      # profiles/k_csr_C4_large_powerlaw.md
+}
+
 WORKLOAD_TEXT = {
     "C1": "C1 small power-law: N=2,708, 10,556 edges + self-loops, values 1, X 2708x32 fp32 U[-1,1]",
     "C2": "C2 medium power-law: N=169,343, 2.3M edges + self-loops, GCN-normalised, X Nx128 fp32 N(0,1)",
@@ -134,7 +141,7 @@ def main():
     achieved = alg_bytes / (stage_ms[dom] * 1e-3) / 1e9
     whole_bytes = 4.0 * (g.n_rows + 1) + 8.0 * g.nnz + g.n_cols * d * sx + g.n_rows * d * 4.0
     roofline = dict(bound="hbm", kernel=s["kernel"], achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
+                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=MEASURED_TRAFFIC_BYTES.get((name, s["kernel"])),
                     algorithmic_bytes=int(alg_bytes), kernel_ms=round(stage_ms[dom], 5),
                     whole_step_frac=round(whole_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4))
 
