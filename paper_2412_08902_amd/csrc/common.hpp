@@ -17,13 +17,15 @@ constexpr int kBitmapWords = 32768;    // LDS bitmap (1 Mi columns per pass) use
 constexpr int kEcolLdsCap = 4096;      // distinct-column lists up to this length are searched from LDS
 
 // ---- matrix path -------------------------------------------------------------------------------
-constexpr int kMfmaSmallMaxCols = 512; // windows with more condensed columns go to the workgroup-per-window kernel
+constexpr int kMfmaSmallMaxCols = 256; // windows with more condensed columns go to a workgroup-per-window kernel
+constexpr int kMfmaMidMaxCols = 1024;  // ... with the small LDS chunk up to here, the large chunk beyond
 constexpr int kKcSmall = 128;          // condensed columns staged per wave and chunk (wave-per-window kernel)
-constexpr int kKcBig = 1024;           // condensed columns staged per workgroup and chunk
+constexpr int kKcMid = 256;            // condensed columns staged per workgroup and chunk, medium windows
+constexpr int kKcBig = 1024;           // condensed columns staged per workgroup and chunk, wide windows
 
 // ---- scalar path -------------------------------------------------------------------------------
 constexpr int kRowsPerGroup = 8;       // consecutive rows walked by one lane group (short rows)
-constexpr int kMidRow = 96;            // rows with more non-zeros than this get a whole wave
+constexpr int kMidRow = 256;           // rows with more non-zeros than this get a whole wave
 constexpr int kLongRow = 1024;         // rows with more non-zeros than this are cut into workgroup-sized segments
 constexpr int kSegLen = 2048;          // non-zeros per segment of a long row
 
@@ -60,12 +62,13 @@ hipError_t launch_unique_big(int32_t n_big, const int32_t* big_list, int32_t n_r
                              hipStream_t s);
 hipError_t launch_ecol(int32_t W, int32_t n_rows, const int32_t* rowptr, const int32_t* colind,
                        const int32_t* tmp_cols, const int32_t* ncols, const int64_t* wptr, int32_t* wcols,
-                       int32_t* erc, hipStream_t s);
+                       int32_t* erc, int32_t* unsorted_flag, hipStream_t s);
 hipError_t launch_select(int32_t W, const int32_t* ncols, const int32_t* nnzw, int64_t c0, int64_t c1, int64_t c2,
                          int32_t mode, uint8_t* route, int32_t* f_mfma, int32_t* f_csr, int32_t* f_small,
-                         int32_t* f_big, int32_t* nnz_if_mfma, hipStream_t s);
+                         int32_t* f_mid, int32_t* f_big, int32_t* nnz_if_mfma, hipStream_t s);
 hipError_t launch_compact_ids(int32_t n, const int32_t* flags, const int64_t* pos, int32_t* out, hipStream_t s);
-hipError_t launch_row_class(int32_t n_rows, const int32_t* rowptr, const uint8_t* route, int32_t* f_short,
+hipError_t launch_row_class(int32_t n_rows, const int32_t* rowptr, const uint8_t* route, int32_t mid_row,
+                            int32_t long_row, int32_t* f_short,
                             int32_t* f_mid, int32_t* n_seg, int32_t* f_multi, int32_t* n_slot, int32_t* len_long,
                             hipStream_t s);
 hipError_t launch_build_desc(int32_t n_list, const int32_t* win_list, int32_t n_rows, const int32_t* rowptr,
@@ -91,13 +94,14 @@ struct SpmmArgs {
 
 hipError_t launch_csr(const SpmmArgs& a, int32_t n_segs, const Segment* segs, float* partial, int32_t n_mid,
                       const int32_t* mid_rows, int32_t n_items, const int32_t* row_list, const uint8_t* route,
-                      hipStream_t s);
+                      int32_t mid_row, hipStream_t s);
 hipError_t launch_reduce_partials(const SpmmArgs& a, int32_t n_multi, const MultiRow* multi, const float* partial,
                                   hipStream_t s);
 hipError_t launch_mfma_small(const SpmmArgs& a, int32_t n_list, const WinDesc* desc, const int32_t* wcols,
                              const int32_t* erc, hipStream_t s);
-hipError_t launch_mfma_big(const SpmmArgs& a, int32_t n_list, const int32_t* win_list, const int32_t* ncols,
-                           const int64_t* wptr, const int32_t* wcols, const int32_t* erc, hipStream_t s);
+hipError_t launch_mfma_wg(const SpmmArgs& a, int32_t n_list, const int32_t* win_list, const int32_t* ncols,
+                          const int64_t* wptr, const int32_t* wcols, const int32_t* erc, int rows_sorted,
+                          bool wide, hipStream_t s);
 hipError_t launch_gemm_f32(int64_t m, int32_t k, int32_t n, const float* X, int64_t ldx, const float* W, int64_t ldw,
                            float* T, int64_t ldt, hipStream_t s);
 
@@ -128,11 +132,14 @@ struct hcspmm_plan {
     // owned, launch tables
     int32_t* mfma_small;
     hcspmm::WinDesc* mfma_small_desc;
+    int32_t* mfma_mid;
     int32_t* mfma_big;
-    int32_t n_mfma_small, n_mfma_big;
-    int32_t* short_rows;     // rows of route-0 windows with at most kMidRow non-zeros (NULL: walk every row)
+    int32_t n_mfma_small, n_mfma_mid, n_mfma_big;
+    int32_t rows_sorted;         // 1 when every row's column indices are non-decreasing
+    int32_t mid_row, long_row;   // tier thresholds this plan was built with (defaults kMidRow, kLongRow)
+    int32_t* short_rows;     // rows of route-0 windows with at most mid_row non-zeros (NULL: walk every row)
     int32_t n_short;
-    int32_t* mid_rows;       // rows of route-0 windows with kMidRow < non-zeros <= kLongRow
+    int32_t* mid_rows;       // rows of route-0 windows with mid_row < non-zeros <= long_row
     int32_t n_mid;
     hcspmm::Segment* segs;
     int32_t n_segs;

@@ -3,6 +3,7 @@
 
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <new>
@@ -20,19 +21,30 @@ void set_error(const char* fmt, ...)
     va_end(ap);
 }
 
-// Shipped selector coefficients (w1, w2, b) x 2^10 of  z = w1*ncols + w2*sparsity + b  (Section
+// Shipped selector coefficients (w1, w2, b) x 2^20 of  z = w1*ncols + w2*sparsity + b  (Section
 // IV-C form; route = matrix path iff z < 0), one row per (precision, dense-width bucket).  Fitted
-// on MI355X with the procedure of Section IV-C (synthetic 16-row windows, both kernels timed,
-// logistic regression); the paper does not print its own values.
+// on MI355X with the procedure of Section IV-C (synthetic 16-row windows, both deployed kernels
+// timed; selector_fit.py) and then checked on community graphs of rising density -- the paper does
+// not print its own values.  Read as
+//     matrix path  iff  ncols / N0 + sparsity / S0 < 1 :
+// N0 is the widest window worth a single workgroup's serial pass on the matrix path; S0 is the
+// sparsity below which the matrix path pays.  At d > 64 it pays from ~1.3 non-zeros per condensed
+// column (S0 = 0.92) in the sweep and on the community graphs alike.  At d <= 64 the sweep (whose
+// windows share no columns with their neighbours) favours it from the same density, but on
+// community graphs, where neighbouring rows and windows share columns, the scalar path gets the
+// same reuse out of L1 and the two paths tie within ~10 % up to fully dense blocks; there a tie
+// goes to the scalar path (S0 = 0.25: twelve non-zeros per column, i.e. nearly full tiles only).
 struct SelectorRow { int32_t dtype; int32_t d_max; int64_t c[3]; };
 static const SelectorRow kSelectorTable[] = {
     // fp32 MFMA
-    {HCSPMM_F32, 32, {2, 4096, -3328}},
-    {HCSPMM_F32, 64, {2, 4096, -3328}},
-    {HCSPMM_F32, 1 << 30, {2, 4096, -3328}},
+    {HCSPMM_F32, 32, {2048, 4194304, -1048576}},          // N0 = 512,  S0 = 0.25
+    {HCSPMM_F32, 64, {171, 4194304, -1048576}},           // N0 = 6144, S0 = 0.25
+    {HCSPMM_F32, 1 << 30, {171, 1139756, -1048576}},      // N0 = 6144, S0 = 0.92
     // 16-bit MFMA
-    {HCSPMM_BF16, 1 << 30, {1, 4096, -3686}},
-    {HCSPMM_F16, 1 << 30, {1, 4096, -3686}},
+    {HCSPMM_BF16, 64, {171, 4194304, -1048576}},
+    {HCSPMM_BF16, 1 << 30, {171, 1139756, -1048576}},
+    {HCSPMM_F16, 64, {171, 4194304, -1048576}},
+    {HCSPMM_F16, 1 << 30, {171, 1139756, -1048576}},
 };
 
 static bool lookup_selector(int32_t dtype, int32_t d_hint, int64_t* coef)
@@ -91,7 +103,7 @@ struct DevAlloc {
 static void free_plan_arrays(hcspmm_plan* p)
 {
     void* owned[] = {p->ncols, p->nnzw, p->route, p->wptr, p->wcols, p->erc, p->mfma_windows, p->csr_windows,
-                     p->mfma_small, p->mfma_small_desc, p->mfma_big, p->short_rows, p->mid_rows, p->segs, p->multi, p->partial};
+                     p->mfma_small, p->mfma_small_desc, p->mfma_mid, p->mfma_big, p->short_rows, p->mid_rows, p->segs, p->multi, p->partial};
     for (void* q : owned)
         if (q) (void)hipFree(q);
 }
@@ -104,7 +116,7 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     const int32_t n_rows = p->n_rows, W = p->W;
     const int64_t nnz = p->nnz;
     int32_t *err = nullptr, *big_list = nullptr, *big_count = nullptr, *tmp_cols = nullptr;
-    int32_t *f_mfma = nullptr, *f_csr = nullptr, *f_small = nullptr, *f_big = nullptr, *nnz_if = nullptr;
+    int32_t *f_mfma = nullptr, *f_csr = nullptr, *f_small = nullptr, *f_midw = nullptr, *f_big = nullptr, *nnz_if = nullptr;
     int32_t *f_short = nullptr, *f_mid = nullptr, *n_seg = nullptr, *f_multi = nullptr, *n_slot = nullptr, *len_long = nullptr;
     int64_t *scan_tmp = nullptr, *pos_a = nullptr, *pos_b = nullptr, *pos_c = nullptr, *pos_d = nullptr;
     int64_t *totals_dev = nullptr;
@@ -152,38 +164,50 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     HC_TRY(hipMemcpyAsync(&p->total_ncols, p->wptr + W, sizeof(int64_t), hipMemcpyDeviceToHost, stream));
     HC_TRY(hipStreamSynchronize(stream));
     HC_ALLOC(keep, p->wcols, p->total_ncols);
-    if (W > 0 && nnz > 0)
-        HC_TRY(launch_ecol(W, n_rows, p->rowptr, p->colind, tmp_cols, p->ncols, p->wptr, p->wcols, p->erc, stream));
+    p->rows_sorted = 1;
+    if (W > 0 && nnz > 0) {
+        // err[0] is zero here (validation passed): reuse it as the "some row is unsorted" flag
+        HC_TRY(launch_ecol(W, n_rows, p->rowptr, p->colind, tmp_cols, p->ncols, p->wptr, p->wcols, p->erc, err, stream));
+        HC_TRY(hipMemcpyAsync(&h_err, err, sizeof h_err, hipMemcpyDeviceToHost, stream));
+        HC_TRY(hipStreamSynchronize(stream));
+        p->rows_sorted = h_err ? 0 : 1;
+    }
 
     // selection (Section IV-C) and the per-route window lists
     HC_ALLOC(tmp, f_mfma, (size_t)W + 1);
     HC_ALLOC(tmp, f_csr, (size_t)W + 1);
     HC_ALLOC(tmp, f_small, (size_t)W + 1);
+    HC_ALLOC(tmp, f_midw, (size_t)W + 1);
     HC_ALLOC(tmp, f_big, (size_t)W + 1);
     HC_ALLOC(tmp, nnz_if, (size_t)W + 1);
     if (W > 0)
         HC_TRY(launch_select(W, p->ncols, p->nnzw, p->coef[0], p->coef[1], p->coef[2], p->opt.route_mode, p->route,
-                             f_mfma, f_csr, f_small, f_big, nnz_if, stream));
+                             f_mfma, f_csr, f_small, f_midw, f_big, nnz_if, stream));
     HC_TRY(exclusive_scan_i32_i64(f_mfma, W, pos_a, scan_tmp, stream));
     HC_TRY(hipMemcpyAsync(totals_dev + 0, pos_a + W, 8, hipMemcpyDeviceToDevice, stream));
     HC_TRY(exclusive_scan_i32_i64(f_csr, W, pos_b, scan_tmp, stream));
     HC_TRY(exclusive_scan_i32_i64(f_small, W, pos_c, scan_tmp, stream));
     HC_TRY(hipMemcpyAsync(totals_dev + 1, pos_c + W, 8, hipMemcpyDeviceToDevice, stream));
     HC_TRY(exclusive_scan_i32_i64(f_big, W, pos_d, scan_tmp, stream));
-    HC_TRY(hipMemcpyAsync(h_tot, totals_dev, 2 * sizeof(int64_t), hipMemcpyDeviceToHost, stream));
+    HC_TRY(hipMemcpyAsync(totals_dev + 2, pos_d + W, 8, hipMemcpyDeviceToDevice, stream));
+    HC_TRY(hipMemcpyAsync(h_tot, totals_dev, 3 * sizeof(int64_t), hipMemcpyDeviceToHost, stream));
     HC_TRY(hipStreamSynchronize(stream));
     p->n_mfma = (int32_t)h_tot[0];
     p->n_csr = W - p->n_mfma;
     p->n_mfma_small = (int32_t)h_tot[1];
-    p->n_mfma_big = p->n_mfma - p->n_mfma_small;
+    p->n_mfma_big = (int32_t)h_tot[2];
+    p->n_mfma_mid = p->n_mfma - p->n_mfma_small - p->n_mfma_big;
     HC_ALLOC(keep, p->mfma_windows, p->n_mfma);
     HC_ALLOC(keep, p->csr_windows, p->n_csr);
     HC_ALLOC(keep, p->mfma_small, p->n_mfma_small);
+    HC_ALLOC(keep, p->mfma_mid, p->n_mfma_mid);
     HC_ALLOC(keep, p->mfma_big, p->n_mfma_big);
     HC_TRY(launch_compact_ids(W, f_mfma, pos_a, p->mfma_windows, stream));
     HC_TRY(launch_compact_ids(W, f_csr, pos_b, p->csr_windows, stream));
     HC_TRY(launch_compact_ids(W, f_small, pos_c, p->mfma_small, stream));
     HC_TRY(launch_compact_ids(W, f_big, pos_d, p->mfma_big, stream));
+    HC_TRY(exclusive_scan_i32_i64(f_midw, W, pos_c, scan_tmp, stream));
+    HC_TRY(launch_compact_ids(W, f_midw, pos_c, p->mfma_mid, stream));
     HC_ALLOC(keep, p->mfma_small_desc, p->n_mfma_small);
     HC_TRY(launch_build_desc(p->n_mfma_small, p->mfma_small, n_rows, p->rowptr, p->ncols, p->wptr, p->mfma_small_desc,
                              stream));
@@ -198,7 +222,7 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     HC_ALLOC(tmp, f_multi, (size_t)n_rows + 1);
     HC_ALLOC(tmp, n_slot, (size_t)n_rows + 1);
     HC_ALLOC(tmp, len_long, (size_t)n_rows + 1);
-    HC_TRY(launch_row_class(n_rows, p->rowptr, p->route, f_short, f_mid, n_seg, f_multi, n_slot, len_long, stream));
+    HC_TRY(launch_row_class(n_rows, p->rowptr, p->route, p->mid_row, p->long_row, f_short, f_mid, n_seg, f_multi, n_slot, len_long, stream));
     HC_TRY(exclusive_scan_i32_i64(len_long, n_rows, pos_a, scan_tmp, stream));
     HC_TRY(hipMemcpyAsync(totals_dev + 4, pos_a + n_rows, 8, hipMemcpyDeviceToDevice, stream));
     HC_TRY(exclusive_scan_i32_i64(f_short, n_rows, pos_a, scan_tmp, stream));
@@ -271,12 +295,14 @@ static hcspmm_status run_spmm(const hcspmm_plan* plan, const SpmmArgs& a, hipStr
     // the matrix-path windows first (few, heavy), then every scalar-path row in one launch,
     // then the sums of the rows that were cut into several segments
     if (ev) HC_HIP(hipEventRecord(ev[0], stream));
-    HC_HIP(launch_mfma_big(a, p->n_mfma_big, p->mfma_big, p->ncols, p->wptr, p->wcols, p->erc, stream));
+    HC_HIP(launch_mfma_wg(a, p->n_mfma_big, p->mfma_big, p->ncols, p->wptr, p->wcols, p->erc, p->rows_sorted, true, stream));
+    HC_HIP(launch_mfma_wg(a, p->n_mfma_mid, p->mfma_mid, p->ncols, p->wptr, p->wcols, p->erc, p->rows_sorted, false, stream));
     if (ev) HC_HIP(hipEventRecord(ev[1], stream));
     HC_HIP(launch_mfma_small(a, p->n_mfma_small, p->mfma_small_desc, p->wcols, p->erc, stream));
     if (ev) HC_HIP(hipEventRecord(ev[2], stream));
     HC_HIP(launch_csr(a, p->n_segs, p->segs, p->partial, p->n_mid, p->mid_rows,
-                      p->short_rows ? p->n_short : (p->n_short > 0 ? p->n_rows : 0), p->short_rows, p->route, stream));
+                      p->short_rows ? p->n_short : (p->n_short > 0 ? p->n_rows : 0), p->short_rows, p->route,
+                      p->mid_row, stream));
     if (ev) HC_HIP(hipEventRecord(ev[3], stream));
     HC_HIP(launch_reduce_partials(a, p->n_multi, p->multi, p->partial, stream));
     if (ev) HC_HIP(hipEventRecord(ev[4], stream));
@@ -335,6 +361,12 @@ hcspmm_status hcspmm_prepare(int32_t n_rows, int32_t n_cols, int64_t nnz, const 
     p->W = (int32_t)(((int64_t)n_rows + kH - 1) / kH);
     p->rowptr = d_rowptr; p->colind = d_colind; p->vals = d_vals;
     p->opt = o;
+    p->mid_row = kMidRow;
+    p->long_row = kLongRow;
+    // tuning knobs for experiments (not part of the ABI): override the row-tier thresholds
+    if (const char* v = getenv("HCSPMM_TUNE_MID_ROW")) { int t = atoi(v); if (t >= 1) p->mid_row = t; }
+    if (const char* v = getenv("HCSPMM_TUNE_LONG_ROW")) { int t = atoi(v); if (t >= p->mid_row) p->long_row = t; }
+    if (p->long_row < p->mid_row) p->long_row = p->mid_row;
     if (o.use_custom_selector) {
         for (int i = 0; i < 3; ++i) {
             if (o.sel_coef[i] <= -((int64_t)1 << 40) || o.sel_coef[i] >= ((int64_t)1 << 40)) {
@@ -366,7 +398,8 @@ hcspmm_status hcspmm_plan_info(const hcspmm_plan* p, hcspmm_plan_info_t* info)
     info->device_bytes = p->device_bytes + p->partial_elems * (int64_t)sizeof(float);
     info->n_short_rows = p->n_short; info->n_long_rows = p->n_long_rows; info->n_segments = p->n_segs;
     info->n_mid_rows = p->n_mid;
-    info->nnz_long = p->nnz_long; info->n_mfma_small = p->n_mfma_small; info->n_mfma_big = p->n_mfma_big;
+    info->nnz_long = p->nnz_long; info->n_mfma_small = p->n_mfma_small;
+    info->n_mfma_big = p->n_mfma_mid + p->n_mfma_big;
     return HCSPMM_OK;
 }
 

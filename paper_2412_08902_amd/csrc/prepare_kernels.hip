@@ -323,7 +323,7 @@ __global__ __launch_bounds__(256) void k_ecol(int32_t n_rows, const int32_t* __r
                                               const int32_t* __restrict__ colind,
                                               const int32_t* __restrict__ tmp_cols, const int32_t* __restrict__ ncols,
                                               const int64_t* __restrict__ wptr, int32_t* __restrict__ wcols,
-                                              int32_t* __restrict__ erc)
+                                              int32_t* __restrict__ erc, int32_t* __restrict__ unsorted_flag)
 {
     __shared__ int32_t ucols[kEcolLdsCap];
     __shared__ int32_t rp[kH + 1];
@@ -359,14 +359,17 @@ __global__ __launch_bounds__(256) void k_ecol(int32_t n_rows, const int32_t* __r
         for (int step = 8; step > 0; step >>= 1)
             if (r + step < kH && rp[r + step] <= k) r += step;
         erc[k] = (lo << 4) | r;
+        // note rows whose column indices are not non-decreasing (the matrix path's cursor walk needs them sorted)
+        if (k > rp[r] && colind[k - 1] > c) atomicOr(unsorted_flag, 1);
     }
 }
 
 hipError_t launch_ecol(int32_t W, int32_t n_rows, const int32_t* rowptr, const int32_t* colind,
                        const int32_t* tmp_cols, const int32_t* ncols, const int64_t* wptr, int32_t* wcols,
-                       int32_t* erc, hipStream_t s)
+                       int32_t* erc, int32_t* unsorted_flag, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_ecol, dim3(W), dim3(256), 0, s, n_rows, rowptr, colind, tmp_cols, ncols, wptr, wcols, erc);
+    hipLaunchKernelGGL(k_ecol, dim3(W), dim3(256), 0, s, n_rows, rowptr, colind, tmp_cols, ncols, wptr, wcols, erc,
+                       unsorted_flag);
     return hipGetLastError();
 }
 
@@ -377,8 +380,8 @@ __global__ __launch_bounds__(256) void k_select(int32_t W, const int32_t* __rest
                                                 const int32_t* __restrict__ nnzw, long long c0, long long c1,
                                                 long long c2, int32_t mode, uint8_t* __restrict__ route,
                                                 int32_t* __restrict__ f_mfma, int32_t* __restrict__ f_csr,
-                                                int32_t* __restrict__ f_small, int32_t* __restrict__ f_big,
-                                                int32_t* __restrict__ nnz_if_mfma)
+                                                int32_t* __restrict__ f_small, int32_t* __restrict__ f_mid,
+                                                int32_t* __restrict__ f_big, int32_t* __restrict__ nnz_if_mfma)
 {
     int32_t w = blockIdx.x * blockDim.x + threadIdx.x;
     if (w >= W) return;
@@ -397,16 +400,17 @@ __global__ __launch_bounds__(256) void k_select(int32_t W, const int32_t* __rest
     f_mfma[w] = r;
     f_csr[w] = 1 - r;
     f_small[w] = (r && nc <= kMfmaSmallMaxCols) ? 1 : 0;
-    f_big[w] = (r && nc > kMfmaSmallMaxCols) ? 1 : 0;
+    f_mid[w] = (r && nc > kMfmaSmallMaxCols && nc <= kMfmaMidMaxCols) ? 1 : 0;
+    f_big[w] = (r && nc > kMfmaMidMaxCols) ? 1 : 0;
     nnz_if_mfma[w] = r ? (int32_t)nz : 0;
 }
 
 hipError_t launch_select(int32_t W, const int32_t* ncols, const int32_t* nnzw, int64_t c0, int64_t c1, int64_t c2,
                          int32_t mode, uint8_t* route, int32_t* f_mfma, int32_t* f_csr, int32_t* f_small,
-                         int32_t* f_big, int32_t* nnz_if_mfma, hipStream_t s)
+                         int32_t* f_mid, int32_t* f_big, int32_t* nnz_if_mfma, hipStream_t s)
 {
     hipLaunchKernelGGL(k_select, dim3((W + 255) / 256), dim3(256), 0, s, W, ncols, nnzw, (long long)c0, (long long)c1,
-                       (long long)c2, mode, route, f_mfma, f_csr, f_small, f_big, nnz_if_mfma);
+                       (long long)c2, mode, route, f_mfma, f_csr, f_small, f_mid, f_big, nnz_if_mfma);
     return hipGetLastError();
 }
 
@@ -456,7 +460,8 @@ hipError_t launch_build_desc(int32_t n_list, const int32_t* win_list, int32_t n_
 // scalar-path launch tables: short rows, and segments of long rows
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_row_class(int32_t n_rows, const int32_t* __restrict__ rowptr,
-                                                   const uint8_t* __restrict__ route, int32_t* __restrict__ f_short,
+                                                   const uint8_t* __restrict__ route, int32_t mid_row,
+                                                   int32_t long_row, int32_t* __restrict__ f_short,
                                                    int32_t* __restrict__ f_mid, int32_t* __restrict__ n_seg, int32_t* __restrict__ f_multi,
                                                    int32_t* __restrict__ n_slot, int32_t* __restrict__ len_long)
 {
@@ -464,8 +469,8 @@ __global__ __launch_bounds__(256) void k_row_class(int32_t n_rows, const int32_t
     if (i >= n_rows) return;
     const int32_t len = rowptr[i + 1] - rowptr[i];
     const bool csr = route[i / kH] == 0;
-    const bool is_long = csr && len > kLongRow;
-    const bool is_mid = csr && !is_long && len > kMidRow;
+    const bool is_long = csr && len > long_row;
+    const bool is_mid = csr && !is_long && len > mid_row;
     const int32_t ns = is_long ? (len + kSegLen - 1) / kSegLen : 0;
     f_short[i] = (csr && !is_long && !is_mid) ? 1 : 0;
     f_mid[i] = is_mid ? 1 : 0;
@@ -475,12 +480,14 @@ __global__ __launch_bounds__(256) void k_row_class(int32_t n_rows, const int32_t
     len_long[i] = (is_long || is_mid) ? len : 0;
 }
 
-hipError_t launch_row_class(int32_t n_rows, const int32_t* rowptr, const uint8_t* route, int32_t* f_short,
+hipError_t launch_row_class(int32_t n_rows, const int32_t* rowptr, const uint8_t* route, int32_t mid_row,
+                            int32_t long_row, int32_t* f_short,
                             int32_t* f_mid, int32_t* n_seg, int32_t* f_multi, int32_t* n_slot, int32_t* len_long,
                             hipStream_t s)
 {
     if (n_rows <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_row_class, dim3((n_rows + 255) / 256), dim3(256), 0, s, n_rows, rowptr, route, f_short, f_mid,
+    hipLaunchKernelGGL(k_row_class, dim3((n_rows + 255) / 256), dim3(256), 0, s, n_rows, rowptr, route, mid_row, long_row,
+                       f_short, f_mid,
                        n_seg, f_multi, n_slot, len_long);
     return hipGetLastError();
 }

@@ -110,7 +110,8 @@ __device__ inline void span_accumulate(int kb, int ke, int stride, int lig,
 // length.  The rows' extents are fetched up front, one per lane.
 template <int LPR, int VEC>
 __device__ inline void csr_short_body(int64_t block, int32_t n_items, const int32_t* __restrict__ row_list,
-                                      const uint8_t* __restrict__ route, int rows_per_group, const SpmmArgs& a)
+                                      const uint8_t* __restrict__ route, int rows_per_group, int mid_row,
+                                      const SpmmArgs& a)
 {
     static_assert(LPR >= kRowsPerGroup, "a group must be able to hold one row extent per lane");
     constexpr int GPB = 256 / LPR;
@@ -125,7 +126,7 @@ __device__ inline void csr_short_body(int64_t block, int32_t n_items, const int3
         my_s = a.rowptr[my_row];
         my_e = a.rowptr[my_row + 1];
         // walking every row: skip rows owned by the matrix path or by the mid/long-row kernels
-        if (!row_list && (route[my_row / kH] != 0 || my_e - my_s > kMidRow)) my_row = -1;
+        if (!row_list && (route[my_row / kH] != 0 || my_e - my_s > mid_row)) my_row = -1;
     }
     const float* __restrict__ X = static_cast<const float*>(a.X);
     for (int c0 = 0; c0 < a.d; c0 += LPR * VEC) {
@@ -243,6 +244,7 @@ struct CsrWork {
     const int32_t* row_list;
     const uint8_t* route;
     int32_t rows_per_group;
+    int32_t mid_row;
 };
 
 template <int LPR, int VEC>
@@ -261,7 +263,7 @@ __global__ __launch_bounds__(256) void k_csr(CsrWork wk, SpmmArgs a)
         return;
     }
     b -= mid_blocks;
-    csr_short_body<LPR, VEC>(b, wk.n_items, wk.row_list, wk.route, wk.rows_per_group, a);
+    csr_short_body<LPR, VEC>(b, wk.n_items, wk.row_list, wk.route, wk.rows_per_group, wk.mid_row, a);
 }
 
 // ---- rows cut into several segments: add the partial rows in segment order ------------------
@@ -311,7 +313,7 @@ static CsrShape pick_shape(const SpmmArgs& a, const float* partial)
 
 hipError_t launch_csr(const SpmmArgs& a, int32_t n_segs, const Segment* segs, float* partial, int32_t n_mid,
                       const int32_t* mid_rows, int32_t n_items, const int32_t* row_list, const uint8_t* route,
-                      hipStream_t s)
+                      int32_t mid_row, hipStream_t s)
 {
     const CsrShape sh = pick_shape(a, partial);
     // several consecutive rows per lane group amortise the per-row set-up, but only while the
@@ -322,7 +324,7 @@ hipError_t launch_csr(const SpmmArgs& a, int32_t n_segs, const Segment* segs, fl
     const int gpb = 256 / sh.lpr;
     const int64_t blocks = (int64_t)n_segs + ((int64_t)n_mid + 3) / 4 + (n_groups + gpb - 1) / gpb;
     if (blocks <= 0) return hipSuccess;
-    CsrWork wk{n_segs, segs, partial, n_mid, mid_rows, n_items, row_list, route, rpg};
+    CsrWork wk{n_segs, segs, partial, n_mid, mid_rows, n_items, row_list, route, rpg, mid_row};
 #define HC_LAUNCH_CSR(L, V) hipLaunchKernelGGL((k_csr<L, V>), dim3((unsigned)blocks), dim3(256), 0, s, wk, a)
     HC_CSR_DISPATCH(HC_LAUNCH_CSR)
 #undef HC_LAUNCH_CSR

@@ -214,17 +214,19 @@ __global__ __launch_bounds__(256) void k_mfma_small(int32_t n_list, const WinDes
 }
 
 // ---- workgroup per window ---------------------------------------------------------------------
-// For windows with many condensed columns: all four waves stage a kKcBig-column chunk together,
-// split its K-steps between them (blocks of 64 columns, round-robin) and add their partial tiles
-// through LDS at the end, in wave order.
-template <int VW, int NG>
-__global__ __launch_bounds__(256) void k_mfma_big(const int32_t* __restrict__ win_list,
+// For windows with more condensed columns than one wave's tile holds: all four waves stage a
+// KC-column chunk together, split its K-steps between them (blocks of 64 columns, round-robin)
+// and add their partial tiles through LDS at the end, in wave order.  KC = kKcMid keeps the LDS
+// footprint small for windows of a few hundred columns, KC = kKcBig serves the very wide ones.
+template <int VW, int NG, int KC>
+__global__ __launch_bounds__(256) void k_mfma_wg(const int32_t* __restrict__ win_list,
                                                   const int32_t* __restrict__ ncols, const int64_t* __restrict__ wptr,
                                                   const int32_t* __restrict__ wcols, const int32_t* __restrict__ erc,
-                                                  int col0, SpmmArgs a)
+                                                  int rows_sorted, int col0, SpmmArgs a)
 {
-    __shared__ float tile[kKcBig * 16];
-    static_assert(kKcBig * 16 >= 4 * NG * VW * 4 * 64, "reduction scratch must fit in the tile");
+    constexpr int kAccFloats = NG * VW * 4 * 64;           // one wave's accumulators
+    constexpr int kLdsFloats = KC * 16 > kAccFloats ? KC * 16 : kAccFloats;
+    __shared__ float tile[kLdsFloats];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int32_t w = win_list[blockIdx.x];
     const int32_t r0 = w * kH;
@@ -241,15 +243,39 @@ __global__ __launch_bounds__(256) void k_mfma_big(const int32_t* __restrict__ wi
         for (int t = 0; t < VW; ++t) acc[g][t] = (v4f){0.f, 0.f, 0.f, 0.f};
 
     float xa[2][MfmaPipe<VW, NG>::U][NG][VW];
-    for (int32_t kc0 = 0; kc0 < nc; kc0 += kKcBig) {
-        const int kend = min(kKcBig, nc - kc0);
-        for (int i = threadIdx.x * 4; i < kKcBig * 16; i += 1024)
+    // When every row's columns ascend, so do its condensed columns: 16 threads per row keep a
+    // cursor that only moves forward, and a chunk costs only the entries that fall into it.
+    // Otherwise every chunk scans the whole window.
+    const int my_r = threadIdx.x >> 4, l16 = threadIdx.x & 15;
+    int32_t cur = a.rowptr[min(r0 + my_r, a.n_rows)];
+    const int32_t row_e = a.rowptr[min(r0 + my_r + 1, a.n_rows)];
+    for (int32_t kc0 = 0; kc0 < nc; kc0 += KC) {
+        const int kend = min(KC, nc - kc0);
+        for (int i = threadIdx.x * 4; i < KC * 16; i += 1024)
             *reinterpret_cast<float4*>(&tile[i]) = make_float4(0.f, 0.f, 0.f, 0.f);
         __syncthreads();
-        for (int32_t k = s + threadIdx.x; k < e; k += 256) {
-            const int32_t p = erc[k];
-            const int32_t ec = (p >> 4) - kc0;
-            if (ec >= 0 && ec < kKcBig) atomicAdd(&tile[ec * 16 + (p & 15)], a.vals[k]);
+        if (rows_sorted) {
+            const int32_t limit = kc0 + KC;
+            for (;;) {
+                const int32_t k = cur + l16;
+                int32_t p = 0;
+                bool take = false;
+                if (k < row_e) {
+                    p = erc[k];
+                    take = (p >> 4) < limit;
+                }
+                if (take) atomicAdd(&tile[((p >> 4) - kc0) * 16 + my_r], a.vals[k]);
+                const unsigned long long b = __ballot(take);
+                const int n = __popc((unsigned)((b >> (16 * ((threadIdx.x & 63) >> 4))) & 0xffffu));
+                cur += n;
+                if (n < 16) break;
+            }
+        } else {
+            for (int32_t k = s + threadIdx.x; k < e; k += 256) {
+                const int32_t p = erc[k];
+                const int32_t ec = (p >> 4) - kc0;
+                if (ec >= 0 && ec < KC) atomicAdd(&tile[ec * 16 + (p & 15)], a.vals[k]);
+            }
         }
         __syncthreads();
         for (int kb = wave * 64; kb < kend; kb += 256) {
@@ -260,30 +286,29 @@ __global__ __launch_bounds__(256) void k_mfma_big(const int32_t* __restrict__ wi
         }
         __syncthreads();
     }
-    // add the four waves' partial tiles: wave v parks its registers at slot v, then every lane of
-    // wave 0 sums slots 0..3 in order
-    float* __restrict__ slot = tile + (size_t)wave * (NG * VW * 4 * 64);
+    // add the four waves' partial tiles in wave order: waves 1..3 park their registers in LDS one
+    // after the other and wave 0 adds each in turn
+    for (int v = 1; v < 4; ++v) {
+        if (wave == v) {
 #pragma unroll
-    for (int g = 0; g < NG; ++g)
+            for (int g = 0; g < NG; ++g)
 #pragma unroll
-        for (int t = 0; t < VW; ++t)
+                for (int t = 0; t < VW; ++t)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) slot[((g * VW + t) * 4 + r) * 64 + lane] = acc[g][t][r];
-    __syncthreads();
-    if (wave == 0) {
+                    for (int r = 0; r < 4; ++r) tile[((g * VW + t) * 4 + r) * 64 + lane] = acc[g][t][r];
+        }
+        __syncthreads();
+        if (wave == 0) {
 #pragma unroll
-        for (int g = 0; g < NG; ++g)
+            for (int g = 0; g < NG; ++g)
 #pragma unroll
-            for (int t = 0; t < VW; ++t)
+                for (int t = 0; t < VW; ++t)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    float sum = 0.f;
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) sum += tile[(size_t)v * (NG * VW * 4 * 64) + ((g * VW + t) * 4 + r) * 64 + lane];
-                    acc[g][t][r] = sum;
-                }
-        store_tile<VW, NG>(acc, lane, r0, a.n_rows, a.Y + col0, a.ldy, d, a.relu);
+                    for (int r = 0; r < 4; ++r) acc[g][t][r] += tile[((g * VW + t) * 4 + r) * 64 + lane];
+        }
+        __syncthreads();
     }
+    if (wave == 0) store_tile<VW, NG>(acc, lane, r0, a.n_rows, a.Y + col0, a.ldy, d, a.relu);
 }
 
 // ---- dispatch ---------------------------------------------------------------------------------
@@ -331,15 +356,21 @@ hipError_t launch_mfma_small(const SpmmArgs& a, int32_t n_list, const WinDesc* d
     return hipGetLastError();
 }
 
-hipError_t launch_mfma_big(const SpmmArgs& a, int32_t n_list, const int32_t* win_list, const int32_t* ncols,
-                           const int64_t* wptr, const int32_t* wcols, const int32_t* erc, hipStream_t s)
+hipError_t launch_mfma_wg(const SpmmArgs& a, int32_t n_list, const int32_t* win_list, const int32_t* ncols,
+                          const int64_t* wptr, const int32_t* wcols, const int32_t* erc, int rows_sorted,
+                          bool wide, hipStream_t s)
 {
     if (n_list <= 0) return hipSuccess;
     const MfmaShape sh = pick_mfma_shape(a);
     const int span = sh.ng * 16 * sh.vw;
     for (int col0 = 0; col0 < a.d; col0 += span) {
 #define HC_LAUNCH_MB(V, G)                                                                         \
-    hipLaunchKernelGGL((k_mfma_big<V, G>), dim3(n_list), dim3(256), 0, s, win_list, ncols, wptr, wcols, erc, col0, a)
+    if (wide)                                                                                      \
+        hipLaunchKernelGGL((k_mfma_wg<V, G, kKcBig>), dim3(n_list), dim3(256), 0, s, win_list, ncols, wptr, wcols,   \
+                           erc, rows_sorted, col0, a);                                             \
+    else                                                                                           \
+        hipLaunchKernelGGL((k_mfma_wg<V, G, kKcMid>), dim3(n_list), dim3(256), 0, s, win_list, ncols, wptr, wcols,   \
+                           erc, rows_sorted, col0, a)
         HC_MFMA_DISPATCH(HC_LAUNCH_MB)
 #undef HC_LAUNCH_MB
     }

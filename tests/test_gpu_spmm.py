@@ -81,6 +81,23 @@ def test_long_rows_and_wide_windows(mode):
 
 
 @pytest.mark.parametrize("mode", MODES)
+def test_wide_windows_with_unsorted_rows(mode):
+    # windows with thousands of condensed columns whose rows are NOT sorted by column
+    n, m = 48, 20000
+    rng = np.random.default_rng(77)
+    lens = rng.integers(200, 1500, size=n)
+    cols = [rng.choice(m, size=l, replace=False) for l in lens]          # random order inside each row
+    rp = np.zeros(n + 1, np.int32)
+    np.cumsum(lens, out=rp[1:])
+    g = CSRGraph(n, m, rp, np.concatenate(cols).astype(np.int32),
+                 rng.standard_normal(int(lens.sum())).astype(np.float32))
+    X = dense_normal(m, 64, seed=78)
+    Y, _ = gpu_spmm(g, X, mode)
+    ref, bound = oracle_pair(g, X)
+    assert_close(Y, ref, bound, TOL_F32)
+
+
+@pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("name", ["C1", "C2", "C3"])
 def test_configs_full_size(name, mode):
     g, X, _ = make_config(name)
