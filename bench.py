@@ -67,6 +67,7 @@ def main():
     ap.add_argument("--modes", action="store_true", help="also time the all-CSR and all-MFMA plans")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cold", action="store_true", help="also report cold-cache time (512 MiB flush between reps)")
+    ap.add_argument("--sel-coef", default=None, help="three comma-separated integers overriding the shipped selector")
     ap.add_argument("--calib", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -95,10 +96,12 @@ def main():
     Yd = torch.empty((g.n_rows, d), dtype=torch.float32, device=dev)
     flops = 2.0 * g.nnz * d
 
+    sel_coef = [int(v) for v in args.sel_coef.split(",")] if args.sel_coef else None
+
     def prepare(mode):
         torch.cuda.synchronize()
         t = time.perf_counter()
-        plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, route_mode=mode, d_hint=d)
+        plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, route_mode=mode, d_hint=d, sel_coef=sel_coef)
         torch.cuda.synchronize()
         return plan, (time.perf_counter() - t) * 1e3
 

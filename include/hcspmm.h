@@ -69,7 +69,7 @@ typedef enum { HCSPMM_ROUTE_HYBRID = 0, HCSPMM_ROUTE_ALL_CSR = 1, HCSPMM_ROUTE_A
  * so sel_coef = (w1, w2, b) scaled by one common positive factor.  The paper
  * does not print its coefficients (they are fitted per GPU model and
  * precision); the defaults shipped here were fitted on MI355X for each
- * (mfma_dtype, d_hint) bucket and are returned by hcspmm_default_selector().
+ * (mfma_dtype, d_hint, nnz) bucket and are returned by hcspmm_default_selector().
  */
 typedef struct {
     int32_t struct_size;          /* sizeof(hcspmm_options), for ABI growth */
@@ -83,8 +83,9 @@ typedef struct {
 
 void hcspmm_default_options(hcspmm_options* opt /* host, out */);
 
-/* Shipped selector coefficients for a precision and dense width.  coef: host, out, 3 entries. */
-hcspmm_status hcspmm_default_selector(int32_t mfma_dtype, int32_t d_hint, int64_t* coef);
+/* Shipped selector coefficients for a precision, dense width and matrix size (the table has one
+ * row per precision, width bucket and non-zero-count bucket).  coef: host, out, 3 entries. */
+hcspmm_status hcspmm_default_selector(int32_t mfma_dtype, int32_t d_hint, int64_t nnz, int64_t* coef);
 
 /*
  * Preprocessing (Section IV-A windows + condensing, Section IV-C selection;

@@ -70,7 +70,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     lib.hcspmm_default_options.argtypes = [ctypes.POINTER(HcspmmOptions)]
     lib.hcspmm_default_options.restype = None
-    lib.hcspmm_default_selector.argtypes = [i32, i32, ctypes.POINTER(i64)]
+    lib.hcspmm_default_selector.argtypes = [i32, i32, i64, ctypes.POINTER(i64)]
     lib.hcspmm_default_selector.restype = ctypes.c_int
     lib.hcspmm_prepare.argtypes = [i32, i32, i64, vp, vp, vp, ctypes.POINTER(HcspmmOptions), vp, ctypes.POINTER(vp)]
     lib.hcspmm_prepare.restype = ctypes.c_int
@@ -133,9 +133,9 @@ def hcspmm_default_options() -> HcspmmOptions:
     return o
 
 
-def hcspmm_default_selector(mfma_dtype: int = HCSPMM_F32, d_hint: int = 0):
+def hcspmm_default_selector(mfma_dtype: int = HCSPMM_F32, d_hint: int = 0, nnz: int = 0):
     c = (ctypes.c_int64 * 3)()
-    _check(load_library().hcspmm_default_selector(mfma_dtype, d_hint, c))
+    _check(load_library().hcspmm_default_selector(mfma_dtype, d_hint, nnz, c))
     return [int(c[0]), int(c[1]), int(c[2])]
 
 

@@ -22,6 +22,7 @@ constexpr int kMfmaMidMaxCols = 1024;  // ... with the small LDS chunk up to her
 constexpr int kKcSmall = 128;          // condensed columns staged per wave and chunk (wave-per-window kernel)
 constexpr int kKcMid = 256;            // condensed columns staged per workgroup and chunk, medium windows
 constexpr int kKcBig = 1024;           // condensed columns staged per workgroup and chunk, wide windows
+constexpr int kSliceCols = 4096;       // condensed columns per workgroup; wider windows are cut into slices
 
 // ---- scalar path -------------------------------------------------------------------------------
 constexpr int kRowsPerGroup = 8;       // consecutive rows walked by one lane group (short rows)
@@ -32,6 +33,8 @@ constexpr int kSegLen = 2048;          // non-zeros per segment of a long row
 struct Segment { int32_t row, k_begin, k_end, slot; };    // slot < 0: writes Y directly
 struct MultiRow { int32_t row, first_slot, n_slots, pad; };
 // everything the wave-per-window matrix kernel needs to start on a window, in one 32-byte read
+// one workgroup's share of a matrix-path window: condensed columns [kc_begin, kc_end); slot < 0: writes Y
+struct WgSlice { int32_t w, kc_begin, kc_end, slot; };
 struct WinDesc { int32_t w, s, e, nc; int64_t wp; int64_t pad; };
 
 void set_error(const char* fmt, ...);
@@ -66,6 +69,7 @@ hipError_t launch_ecol(int32_t W, int32_t n_rows, const int32_t* rowptr, const i
 hipError_t launch_select(int32_t W, const int32_t* ncols, const int32_t* nnzw, int64_t c0, int64_t c1, int64_t c2,
                          int32_t mode, uint8_t* route, int32_t* f_mfma, int32_t* f_csr, int32_t* f_small,
                          int32_t* f_mid, int32_t* f_big, int32_t* nnz_if_mfma, hipStream_t s);
+hipError_t launch_masked_copy(int32_t n, const int32_t* flags, const int32_t* src, int32_t* dst, hipStream_t s);
 hipError_t launch_compact_ids(int32_t n, const int32_t* flags, const int64_t* pos, int32_t* out, hipStream_t s);
 hipError_t launch_row_class(int32_t n_rows, const int32_t* rowptr, const uint8_t* route, int32_t mid_row,
                             int32_t long_row, int32_t* f_short,
@@ -73,6 +77,11 @@ hipError_t launch_row_class(int32_t n_rows, const int32_t* rowptr, const uint8_t
                             hipStream_t s);
 hipError_t launch_build_desc(int32_t n_list, const int32_t* win_list, int32_t n_rows, const int32_t* rowptr,
                              const int32_t* ncols, const int64_t* wptr, WinDesc* desc, hipStream_t s);
+hipError_t launch_slice_count(int32_t n_list, const int32_t* win_list, const int32_t* ncols, int32_t slice_cols,
+                              int32_t* n_slices, int32_t* f_multi, int32_t* n_slots, hipStream_t s);
+hipError_t launch_slice_fill(int32_t n_list, const int32_t* win_list, const int32_t* ncols, int32_t slice_cols,
+                             const int64_t* slice_pos, const int64_t* multi_pos, const int64_t* slot_pos,
+                             WgSlice* slices, MultiRow* multi, hipStream_t s);
 hipError_t launch_build_segments(int32_t n_rows, const int32_t* rowptr, const int32_t* n_seg, const int64_t* seg_pos,
                                  const int64_t* multi_pos, const int64_t* slot_pos, Segment* segs, MultiRow* multi,
                                  hipStream_t s);
@@ -99,9 +108,13 @@ hipError_t launch_reduce_partials(const SpmmArgs& a, int32_t n_multi, const Mult
                                   hipStream_t s);
 hipError_t launch_mfma_small(const SpmmArgs& a, int32_t n_list, const WinDesc* desc, const int32_t* wcols,
                              const int32_t* erc, hipStream_t s);
-hipError_t launch_mfma_wg(const SpmmArgs& a, int32_t n_list, const int32_t* win_list, const int32_t* ncols,
+hipError_t launch_mfma_wg(const SpmmArgs& a, int32_t n_list, const WgSlice* slices, const int32_t* ncols,
                           const int64_t* wptr, const int32_t* wcols, const int32_t* erc, int rows_sorted,
-                          bool wide, hipStream_t s);
+                          const int32_t* slice_rows, float* tile_partial, bool wide, hipStream_t s);
+hipError_t launch_slice_rows(int32_t n_slices, const WgSlice* slices, int32_t n_rows, const int32_t* rowptr,
+                             const int32_t* erc, int32_t* slice_rows, hipStream_t s);
+hipError_t launch_reduce_tiles(const SpmmArgs& a, int32_t n_multi, const MultiRow* multi, const float* tile_partial,
+                               hipStream_t s);
 hipError_t launch_gemm_f32(int64_t m, int32_t k, int32_t n, const float* X, int64_t ldx, const float* W, int64_t ldw,
                            float* T, int64_t ldt, hipStream_t s);
 
@@ -135,7 +148,17 @@ struct hcspmm_plan {
     int32_t* mfma_mid;
     int32_t* mfma_big;
     int32_t n_mfma_small, n_mfma_mid, n_mfma_big;
+    hcspmm::WgSlice* mid_slices;     // one per medium window
+    hcspmm::WgSlice* big_slices;     // wide windows cut into kSliceCols-column slices
+    int32_t n_big_slices;
+    int32_t* big_slice_rows;         // per slice and window row: first non-zero inside the slice (sorted rows only)
+    hcspmm::MultiRow* tile_multi;    // windows with several slices (row = window id)
+    int32_t n_tile_multi;
+    int64_t n_tile_slots;
+    float* tile_partial;             // lazily sized: n_tile_slots x 16 x d
+    int64_t tile_partial_elems;
     int32_t rows_sorted;         // 1 when every row's column indices are non-decreasing
+    int32_t slice_cols;          // condensed columns per workgroup slice of a wide window (default kSliceCols)
     int32_t mid_row, long_row;   // tier thresholds this plan was built with (defaults kMidRow, kLongRow)
     int32_t* short_rows;     // rows of route-0 windows with at most mid_row non-zeros (NULL: walk every row)
     int32_t n_short;
@@ -152,4 +175,8 @@ struct hcspmm_plan {
     float* partial;
     int64_t partial_elems;
     int64_t device_bytes;
+    // side streams / events used to run the matrix and scalar paths concurrently
+    int32_t side_ok;
+    hipStream_t side[2];
+    hipEvent_t ev_fork, ev_join[2];
 };

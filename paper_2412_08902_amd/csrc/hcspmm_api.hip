@@ -27,31 +27,40 @@ void set_error(const char* fmt, ...)
 // timed; selector_fit.py) and then checked on community graphs of rising density -- the paper does
 // not print its own values.  Read as
 //     matrix path  iff  ncols / N0 + sparsity / S0 < 1 :
-// N0 is the widest window worth a single workgroup's serial pass on the matrix path; S0 is the
-// sparsity below which the matrix path pays.  At d > 64 it pays from ~1.3 non-zeros per condensed
-// column (S0 = 0.92) in the sweep and on the community graphs alike.  At d <= 64 the sweep (whose
-// windows share no columns with their neighbours) favours it from the same density, but on
-// community graphs, where neighbouring rows and windows share columns, the scalar path gets the
-// same reuse out of L1 and the two paths tie within ~10 % up to fully dense blocks; there a tie
-// goes to the scalar path (S0 = 0.25: twelve non-zeros per column, i.e. nearly full tiles only).
-struct SelectorRow { int32_t dtype; int32_t d_max; int64_t c[3]; };
+// N0 bounds the window width, S0 is the sparsity below which the matrix path pays.
+//  * d > 64: the matrix path wins or ties from ~1.02 non-zeros per condensed column at every
+//    width in the sweep, on community graphs of any density (-24..-38 %) and on the dense
+//    power-law graph of the benchmark set (-19 %); wide windows are cut into column slices as far
+//    as parallelism needs, so no width limit (w1 = 0), S0 = 0.936.
+//  * d <= 64: the sweep (whose windows share no columns with their neighbours) favours the
+//    matrix path from ~1.3 non-zeros per column, but on community graphs, where neighbouring rows
+//    and windows share columns, the scalar path gets the same reuse out of L1 and the two paths
+//    tie within ~10 % up to fully dense blocks; a tie goes to the scalar path (S0 = 0.25: twelve
+//    non-zeros per column, i.e. nearly full tiles only).
+struct SelectorRow { int32_t dtype; int32_t d_max; int64_t nnz_min; int64_t c[3]; };
 static const SelectorRow kSelectorTable[] = {
     // fp32 MFMA
-    {HCSPMM_F32, 32, {2048, 4194304, -1048576}},          // N0 = 512,  S0 = 0.25
-    {HCSPMM_F32, 64, {171, 4194304, -1048576}},           // N0 = 6144, S0 = 0.25
-    {HCSPMM_F32, 1 << 30, {171, 1139756, -1048576}},      // N0 = 6144, S0 = 0.92
+    {HCSPMM_F32, 32, 0, {2048, 4194304, -1048576}},              // N0 = 512,  S0 = 0.25
+    {HCSPMM_F32, 64, 0, {171, 4194304, -1048576}},               // N0 = 6144, S0 = 0.25
+    // d > 64.  A workgroup-per-window launch has tens of microseconds of fixed latency per
+    // workgroup, which only a large matrix amortises: below 16 M non-zeros windows wider than a
+    // few hundred columns stay on the scalar path (N0 = 2048), above there is no width limit.
+    {HCSPMM_F32, 1 << 30, 16000000, {0, 1120000, -1048576}},     // S0 = 0.936
+    {HCSPMM_F32, 1 << 30, 0, {512, 1120000, -1048576}},          // N0 = 2048, S0 = 0.936
     // 16-bit MFMA
-    {HCSPMM_BF16, 64, {171, 4194304, -1048576}},
-    {HCSPMM_BF16, 1 << 30, {171, 1139756, -1048576}},
-    {HCSPMM_F16, 64, {171, 4194304, -1048576}},
-    {HCSPMM_F16, 1 << 30, {171, 1139756, -1048576}},
+    {HCSPMM_BF16, 64, 0, {171, 4194304, -1048576}},
+    {HCSPMM_BF16, 1 << 30, 16000000, {0, 1120000, -1048576}},
+    {HCSPMM_BF16, 1 << 30, 0, {512, 1120000, -1048576}},
+    {HCSPMM_F16, 64, 0, {171, 4194304, -1048576}},
+    {HCSPMM_F16, 1 << 30, 16000000, {0, 1120000, -1048576}},
+    {HCSPMM_F16, 1 << 30, 0, {512, 1120000, -1048576}},
 };
 
-static bool lookup_selector(int32_t dtype, int32_t d_hint, int64_t* coef)
+static bool lookup_selector(int32_t dtype, int32_t d_hint, int64_t nnz, int64_t* coef)
 {
     if (d_hint <= 0) d_hint = 64;
     for (const SelectorRow& r : kSelectorTable)
-        if (r.dtype == dtype && d_hint <= r.d_max) {
+        if (r.dtype == dtype && d_hint <= r.d_max && nnz >= r.nnz_min) {
             coef[0] = r.c[0]; coef[1] = r.c[1]; coef[2] = r.c[2];
             return true;
         }
@@ -103,7 +112,8 @@ struct DevAlloc {
 static void free_plan_arrays(hcspmm_plan* p)
 {
     void* owned[] = {p->ncols, p->nnzw, p->route, p->wptr, p->wcols, p->erc, p->mfma_windows, p->csr_windows,
-                     p->mfma_small, p->mfma_small_desc, p->mfma_mid, p->mfma_big, p->short_rows, p->mid_rows, p->segs, p->multi, p->partial};
+                     p->mfma_small, p->mfma_small_desc, p->mfma_mid, p->mfma_big, p->mid_slices, p->big_slices, p->big_slice_rows, p->tile_multi,
+                     p->tile_partial, p->short_rows, p->mid_rows, p->segs, p->multi, p->partial};
     for (void* q : owned)
         if (q) (void)hipFree(q);
 }
@@ -208,12 +218,60 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     HC_TRY(launch_compact_ids(W, f_big, pos_d, p->mfma_big, stream));
     HC_TRY(exclusive_scan_i32_i64(f_midw, W, pos_c, scan_tmp, stream));
     HC_TRY(launch_compact_ids(W, f_midw, pos_c, p->mfma_mid, stream));
-    HC_ALLOC(keep, p->mfma_small_desc, p->n_mfma_small);
-    HC_TRY(launch_build_desc(p->n_mfma_small, p->mfma_small, n_rows, p->rowptr, p->ncols, p->wptr, p->mfma_small_desc,
-                             stream));
     HC_TRY(exclusive_scan_i32_i64(nnz_if, W, pos_a, scan_tmp, stream));
     HC_TRY(hipMemcpyAsync(&p->nnz_mfma, pos_a + W, sizeof(int64_t), hipMemcpyDeviceToHost, stream));
     HC_TRY(hipStreamSynchronize(stream));
+    if (W > 0) HC_TRY(launch_masked_copy(W, f_big, p->ncols, nnz_if, stream));     // nnz_if <- ncols of wide windows, else 0
+    // workgroup slices: one per medium window, slice_cols condensed columns each for wide windows
+    {
+        int32_t* sc_n = f_mfma;      // the flag arrays are free again: reuse them as scratch (W + 1 ints each)
+        int32_t* sc_multi = f_csr;
+        int32_t* sc_slots = f_small;
+        HC_ALLOC(keep, p->mid_slices, p->n_mfma_mid);
+        HC_TRY(launch_slice_count(p->n_mfma_mid, p->mfma_mid, p->ncols, 0x40000000, sc_n, sc_multi, sc_slots, stream));
+        HC_TRY(exclusive_scan_i32_i64(sc_n, p->n_mfma_mid, pos_a, scan_tmp, stream));
+        HC_TRY(exclusive_scan_i32_i64(sc_multi, p->n_mfma_mid, pos_b, scan_tmp, stream));
+        HC_TRY(exclusive_scan_i32_i64(sc_slots, p->n_mfma_mid, pos_d, scan_tmp, stream));
+        HC_TRY(launch_slice_fill(p->n_mfma_mid, p->mfma_mid, p->ncols, 0x40000000, pos_a, pos_b, pos_d, p->mid_slices,
+                                 nullptr, stream));
+        // Wide windows are cut into slices only as far as parallelism needs it (a slice loses the
+        // alignment of concurrently running windows on the same hot low-numbered columns): aim
+        // at ~4 workgroups per CU over the summed width of the wide windows.
+        if (!getenv("HCSPMM_TUNE_SLICE_COLS") && p->n_mfma_big > 0) {
+            HC_TRY(exclusive_scan_i32_i64(nnz_if, W, pos_a, scan_tmp, stream));     // nnz_if holds ncols of wide windows here
+            int64_t wide_cols = 0;
+            HC_TRY(hipMemcpyAsync(&wide_cols, pos_a + W, 8, hipMemcpyDeviceToHost, stream));
+            HC_TRY(hipStreamSynchronize(stream));
+            int64_t want = wide_cols / 1024;
+            if (want < kKcBig) want = kKcBig;
+            if (want > (1 << 27)) want = 1 << 27;
+            p->slice_cols = (int32_t)((want + kKcBig - 1) / kKcBig * kKcBig);
+        }
+        HC_TRY(launch_slice_count(p->n_mfma_big, p->mfma_big, p->ncols, p->slice_cols, sc_n, sc_multi, sc_slots, stream));
+        HC_TRY(exclusive_scan_i32_i64(sc_n, p->n_mfma_big, pos_a, scan_tmp, stream));
+        HC_TRY(hipMemcpyAsync(totals_dev + 0, pos_a + p->n_mfma_big, 8, hipMemcpyDeviceToDevice, stream));
+        HC_TRY(exclusive_scan_i32_i64(sc_multi, p->n_mfma_big, pos_b, scan_tmp, stream));
+        HC_TRY(hipMemcpyAsync(totals_dev + 1, pos_b + p->n_mfma_big, 8, hipMemcpyDeviceToDevice, stream));
+        HC_TRY(exclusive_scan_i32_i64(sc_slots, p->n_mfma_big, pos_d, scan_tmp, stream));
+        HC_TRY(hipMemcpyAsync(totals_dev + 2, pos_d + p->n_mfma_big, 8, hipMemcpyDeviceToDevice, stream));
+        HC_TRY(hipMemcpyAsync(h_tot, totals_dev, 3 * sizeof(int64_t), hipMemcpyDeviceToHost, stream));
+        HC_TRY(hipStreamSynchronize(stream));
+        p->n_big_slices = (int32_t)h_tot[0];
+        p->n_tile_multi = (int32_t)h_tot[1];
+        p->n_tile_slots = h_tot[2];
+        HC_ALLOC(keep, p->big_slices, p->n_big_slices);
+        HC_ALLOC(keep, p->tile_multi, p->n_tile_multi);
+        HC_TRY(launch_slice_fill(p->n_mfma_big, p->mfma_big, p->ncols, p->slice_cols, pos_a, pos_b, pos_d, p->big_slices,
+                                 p->tile_multi, stream));
+        if (p->rows_sorted && p->n_big_slices > 0) {
+            HC_ALLOC(keep, p->big_slice_rows, (size_t)p->n_big_slices * kH);
+            HC_TRY(launch_slice_rows(p->n_big_slices, p->big_slices, n_rows, p->rowptr, p->erc, p->big_slice_rows,
+                                     stream));
+        }
+    }
+    HC_ALLOC(keep, p->mfma_small_desc, p->n_mfma_small);
+    HC_TRY(launch_build_desc(p->n_mfma_small, p->mfma_small, n_rows, p->rowptr, p->ncols, p->wptr, p->mfma_small_desc,
+                             stream));
 
     // scalar-path launch tables
     HC_ALLOC(tmp, f_short, (size_t)n_rows + 1);
@@ -292,13 +350,39 @@ static hcspmm_status run_spmm(const hcspmm_plan* plan, const SpmmArgs& a, hipStr
         }
         p->partial_elems = want;
     }
-    // the matrix-path windows first (few, heavy), then every scalar-path row in one launch,
-    // then the sums of the rows that were cut into several segments
+    if (p->n_tile_slots > 0 && p->tile_partial_elems < p->n_tile_slots * kH * (int64_t)a.d) {
+        if (p->tile_partial) { HC_HIP(hipStreamSynchronize(stream)); (void)hipFree(p->tile_partial); p->tile_partial = nullptr; }
+        const int64_t want = p->n_tile_slots * kH * (int64_t)a.d;
+        if (hipMalloc((void**)&p->tile_partial, (size_t)want * sizeof(float)) != hipSuccess) {
+            (void)hipGetLastError();
+            p->tile_partial = nullptr;
+            p->tile_partial_elems = 0;
+            set_error("allocation of %lld floats for wide-window partial tiles failed", (long long)want);
+            return HCSPMM_EALLOC;
+        }
+        p->tile_partial_elems = want;
+    }
+    const bool has_wg = p->n_big_slices > 0 || p->n_mfma_mid > 0;
+    const bool has_small = p->n_mfma_small > 0;
+    const bool has_csr = p->n_segs > 0 || p->n_mid > 0 || p->n_short > 0;
+    // The paths own disjoint rows of Y.  When more than one has work (and the stages are not being
+    // timed one by one) they run side by side: the matrix-path kernels on the plan's two side
+    // streams, forked from and joined back to the caller's stream with events.
+    const bool side = !ev && p->side_ok && (int)has_wg + (int)has_small + (int)has_csr > 1;
+    hipStream_t s_wg = stream, s_small = stream;
+    if (side) {
+        HC_HIP(hipEventRecord(p->ev_fork, stream));
+        if (has_wg && has_csr) { s_wg = p->side[0]; HC_HIP(hipStreamWaitEvent(s_wg, p->ev_fork, 0)); }
+        if (has_small && (has_csr || has_wg)) { s_small = p->side[1]; HC_HIP(hipStreamWaitEvent(s_small, p->ev_fork, 0)); }
+    }
     if (ev) HC_HIP(hipEventRecord(ev[0], stream));
-    HC_HIP(launch_mfma_wg(a, p->n_mfma_big, p->mfma_big, p->ncols, p->wptr, p->wcols, p->erc, p->rows_sorted, true, stream));
-    HC_HIP(launch_mfma_wg(a, p->n_mfma_mid, p->mfma_mid, p->ncols, p->wptr, p->wcols, p->erc, p->rows_sorted, false, stream));
+    HC_HIP(launch_mfma_wg(a, p->n_big_slices, p->big_slices, p->ncols, p->wptr, p->wcols, p->erc, p->rows_sorted,
+                          p->big_slice_rows, p->tile_partial, true, s_wg));
+    HC_HIP(launch_reduce_tiles(a, p->n_tile_multi, p->tile_multi, p->tile_partial, s_wg));
+    HC_HIP(launch_mfma_wg(a, p->n_mfma_mid, p->mid_slices, p->ncols, p->wptr, p->wcols, p->erc, p->rows_sorted,
+                          nullptr, p->tile_partial, false, s_wg));
     if (ev) HC_HIP(hipEventRecord(ev[1], stream));
-    HC_HIP(launch_mfma_small(a, p->n_mfma_small, p->mfma_small_desc, p->wcols, p->erc, stream));
+    HC_HIP(launch_mfma_small(a, p->n_mfma_small, p->mfma_small_desc, p->wcols, p->erc, s_small));
     if (ev) HC_HIP(hipEventRecord(ev[2], stream));
     HC_HIP(launch_csr(a, p->n_segs, p->segs, p->partial, p->n_mid, p->mid_rows,
                       p->short_rows ? p->n_short : (p->n_short > 0 ? p->n_rows : 0), p->short_rows, p->route,
@@ -306,6 +390,14 @@ static hcspmm_status run_spmm(const hcspmm_plan* plan, const SpmmArgs& a, hipStr
     if (ev) HC_HIP(hipEventRecord(ev[3], stream));
     HC_HIP(launch_reduce_partials(a, p->n_multi, p->multi, p->partial, stream));
     if (ev) HC_HIP(hipEventRecord(ev[4], stream));
+    if (s_wg != stream) {
+        HC_HIP(hipEventRecord(p->ev_join[0], s_wg));
+        HC_HIP(hipStreamWaitEvent(stream, p->ev_join[0], 0));
+    }
+    if (s_small != stream) {
+        HC_HIP(hipEventRecord(p->ev_join[1], s_small));
+        HC_HIP(hipStreamWaitEvent(stream, p->ev_join[1], 0));
+    }
     return HCSPMM_OK;
 }
 
@@ -327,10 +419,11 @@ void hcspmm_default_options(hcspmm_options* opt)
     opt->use_custom_selector = 0;
 }
 
-hcspmm_status hcspmm_default_selector(int32_t mfma_dtype, int32_t d_hint, int64_t* coef)
+hcspmm_status hcspmm_default_selector(int32_t mfma_dtype, int32_t d_hint, int64_t nnz, int64_t* coef)
 {
     if (!coef) { set_error("coef is NULL"); return HCSPMM_EINVAL; }
-    if (!lookup_selector(mfma_dtype, d_hint, coef)) { set_error("unknown mfma_dtype %d", mfma_dtype); return HCSPMM_EINVAL; }
+    if (nnz < 0) { set_error("nnz is negative"); return HCSPMM_EINVAL; }
+    if (!lookup_selector(mfma_dtype, d_hint, nnz, coef)) { set_error("unknown mfma_dtype %d", mfma_dtype); return HCSPMM_EINVAL; }
     return HCSPMM_OK;
 }
 
@@ -367,6 +460,8 @@ hcspmm_status hcspmm_prepare(int32_t n_rows, int32_t n_cols, int64_t nnz, const 
     if (const char* v = getenv("HCSPMM_TUNE_MID_ROW")) { int t = atoi(v); if (t >= 1) p->mid_row = t; }
     if (const char* v = getenv("HCSPMM_TUNE_LONG_ROW")) { int t = atoi(v); if (t >= p->mid_row) p->long_row = t; }
     if (p->long_row < p->mid_row) p->long_row = p->mid_row;
+    p->slice_cols = kSliceCols;
+    if (const char* v = getenv("HCSPMM_TUNE_SLICE_COLS")) { int t = atoi(v); if (t >= kKcBig) p->slice_cols = t / kKcBig * kKcBig; }
     if (o.use_custom_selector) {
         for (int i = 0; i < 3; ++i) {
             if (o.sel_coef[i] <= -((int64_t)1 << 40) || o.sel_coef[i] >= ((int64_t)1 << 40)) {
@@ -377,11 +472,23 @@ hcspmm_status hcspmm_prepare(int32_t n_rows, int32_t n_cols, int64_t nnz, const 
             p->coef[i] = o.sel_coef[i];
         }
     } else {
-        lookup_selector(o.mfma_dtype, o.d_hint, p->coef);
+        lookup_selector(o.mfma_dtype, o.d_hint, nnz, p->coef);
     }
     if (hipGetDevice(&p->device) != hipSuccess) { (void)hipGetLastError(); delete p; set_error("hipGetDevice failed"); return HCSPMM_EHIP; }
     hcspmm_status st = build_plan(p, static_cast<hipStream_t>(stream));
     if (st != HCSPMM_OK) { delete p; return st; }
+    // side streams (default priority) and events for running the paths side by side; optional
+    p->side_ok = 0;
+    // (the fork/join costs ~20 us of launch latency, so only matrices with milliseconds of work use them)
+    if (p->n_mfma > 0 && p->n_mfma < p->W && p->nnz >= 16000000 && !getenv("HCSPMM_TUNE_SERIAL")) {
+        bool ok = hipStreamCreateWithFlags(&p->side[0], hipStreamNonBlocking) == hipSuccess;
+        ok = ok && hipStreamCreateWithFlags(&p->side[1], hipStreamNonBlocking) == hipSuccess;
+        ok = ok && hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming) == hipSuccess;
+        ok = ok && hipEventCreateWithFlags(&p->ev_join[0], hipEventDisableTiming) == hipSuccess;
+        ok = ok && hipEventCreateWithFlags(&p->ev_join[1], hipEventDisableTiming) == hipSuccess;
+        if (!ok) (void)hipGetLastError();
+        p->side_ok = ok ? 1 : 0;
+    }
     *out_plan = p;
     return HCSPMM_OK;
 }
@@ -395,7 +502,7 @@ hcspmm_status hcspmm_plan_info(const hcspmm_plan* p, hcspmm_plan_info_t* info)
     info->n_mfma_windows = p->n_mfma; info->n_csr_windows = p->n_csr; info->nnz_mfma = p->nnz_mfma;
     info->route_mode = p->opt.route_mode; info->mfma_dtype = p->opt.mfma_dtype; info->d_hint = p->opt.d_hint;
     for (int i = 0; i < 3; ++i) info->sel_coef[i] = p->coef[i];
-    info->device_bytes = p->device_bytes + p->partial_elems * (int64_t)sizeof(float);
+    info->device_bytes = p->device_bytes + (p->partial_elems + p->tile_partial_elems) * (int64_t)sizeof(float);
     info->n_short_rows = p->n_short; info->n_long_rows = p->n_long_rows; info->n_segments = p->n_segs;
     info->n_mid_rows = p->n_mid;
     info->nnz_long = p->nnz_long; info->n_mfma_small = p->n_mfma_small;
@@ -530,6 +637,11 @@ void hcspmm_plan_destroy(hcspmm_plan* plan)
 {
     if (!plan) return;
     (void)hipDeviceSynchronize();
+    if (plan->side[0]) (void)hipStreamDestroy(plan->side[0]);
+    if (plan->side[1]) (void)hipStreamDestroy(plan->side[1]);
+    if (plan->ev_fork) (void)hipEventDestroy(plan->ev_fork);
+    if (plan->ev_join[0]) (void)hipEventDestroy(plan->ev_join[0]);
+    if (plan->ev_join[1]) (void)hipEventDestroy(plan->ev_join[1]);
     free_plan_arrays(plan);
     delete plan;
 }

@@ -421,6 +421,20 @@ __global__ __launch_bounds__(256) void k_compact_ids(int32_t n, const int32_t* _
     if (i < n && flags[i]) out[pos[i]] = i;
 }
 
+__global__ __launch_bounds__(256) void k_masked_copy(int32_t n, const int32_t* __restrict__ flags,
+                                                     const int32_t* __restrict__ src, int32_t* __restrict__ dst)
+{
+    int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = flags[i] ? src[i] : 0;
+}
+
+hipError_t launch_masked_copy(int32_t n, const int32_t* flags, const int32_t* src, int32_t* dst, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_masked_copy, dim3((n + 255) / 256), dim3(256), 0, s, n, flags, src, dst);
+    return hipGetLastError();
+}
+
 hipError_t launch_compact_ids(int32_t n, const int32_t* flags, const int64_t* pos, int32_t* out, hipStream_t s)
 {
     if (n <= 0) return hipSuccess;
@@ -453,6 +467,96 @@ hipError_t launch_build_desc(int32_t n_list, const int32_t* win_list, int32_t n_
     if (n_list <= 0) return hipSuccess;
     hipLaunchKernelGGL(k_build_desc, dim3((n_list + 255) / 256), dim3(256), 0, s, n_list, win_list, n_rows, rowptr,
                        ncols, wptr, desc);
+    return hipGetLastError();
+}
+
+// matrix-path launch table: workgroup slices of medium and wide windows
+__global__ __launch_bounds__(256) void k_slice_count(int32_t n_list, const int32_t* __restrict__ win_list,
+                                                     const int32_t* __restrict__ ncols, int32_t slice_cols,
+                                                     int32_t* __restrict__ n_slices, int32_t* __restrict__ f_multi,
+                                                     int32_t* __restrict__ n_slots)
+{
+    int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_list) return;
+    const int32_t nc = ncols[win_list[i]];
+    const int32_t ns = (nc + slice_cols - 1) / slice_cols;
+    n_slices[i] = ns;
+    f_multi[i] = ns > 1 ? 1 : 0;
+    n_slots[i] = ns > 1 ? ns : 0;
+}
+
+__global__ __launch_bounds__(256) void k_slice_fill(int32_t n_list, const int32_t* __restrict__ win_list,
+                                                    const int32_t* __restrict__ ncols, int32_t slice_cols,
+                                                    const int64_t* __restrict__ slice_pos,
+                                                    const int64_t* __restrict__ multi_pos,
+                                                    const int64_t* __restrict__ slot_pos, WgSlice* __restrict__ slices,
+                                                    MultiRow* __restrict__ multi)
+{
+    int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_list) return;
+    const int32_t w = win_list[i];
+    const int32_t nc = ncols[w];
+    const int32_t ns = (nc + slice_cols - 1) / slice_cols;
+    const int32_t slot0 = ns > 1 ? (int32_t)slot_pos[i] : -1;
+    for (int32_t q = 0; q < ns; ++q) {
+        WgSlice sl;
+        sl.w = w;
+        sl.kc_begin = q * slice_cols;
+        sl.kc_end = min(nc, sl.kc_begin + slice_cols);
+        sl.slot = ns > 1 ? slot0 + q : -1;
+        slices[slice_pos[i] + q] = sl;
+    }
+    if (ns > 1) {
+        MultiRow m;
+        m.row = w; m.first_slot = slot0; m.n_slots = ns; m.pad = 0;
+        multi[multi_pos[i]] = m;
+    }
+}
+
+// per slice and window row: the first non-zero of the row whose condensed column is inside the slice
+// (rows with ascending columns only: their condensed columns ascend too)
+__global__ __launch_bounds__(256) void k_slice_rows(int32_t n_slices, const WgSlice* __restrict__ slices,
+                                                    int32_t n_rows, const int32_t* __restrict__ rowptr,
+                                                    const int32_t* __restrict__ erc, int32_t* __restrict__ slice_rows)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (int64_t)n_slices * kH) return;
+    const WgSlice sl = slices[t / kH];
+    const int64_t row = (int64_t)sl.w * kH + (t % kH);
+    int32_t lo = rowptr[min(row, (int64_t)n_rows)], hi = rowptr[min(row + 1, (int64_t)n_rows)];
+    while (lo < hi) {
+        const int32_t mid = lo + ((hi - lo) >> 1);
+        if ((erc[mid] >> 4) < sl.kc_begin) lo = mid + 1; else hi = mid;
+    }
+    slice_rows[t] = lo;
+}
+
+hipError_t launch_slice_rows(int32_t n_slices, const WgSlice* slices, int32_t n_rows, const int32_t* rowptr,
+                             const int32_t* erc, int32_t* slice_rows, hipStream_t s)
+{
+    if (n_slices <= 0) return hipSuccess;
+    const int64_t n = (int64_t)n_slices * kH;
+    hipLaunchKernelGGL(k_slice_rows, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n_slices, slices, n_rows,
+                       rowptr, erc, slice_rows);
+    return hipGetLastError();
+}
+
+hipError_t launch_slice_count(int32_t n_list, const int32_t* win_list, const int32_t* ncols, int32_t slice_cols,
+                              int32_t* n_slices, int32_t* f_multi, int32_t* n_slots, hipStream_t s)
+{
+    if (n_list <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_slice_count, dim3((n_list + 255) / 256), dim3(256), 0, s, n_list, win_list, ncols, slice_cols,
+                       n_slices, f_multi, n_slots);
+    return hipGetLastError();
+}
+
+hipError_t launch_slice_fill(int32_t n_list, const int32_t* win_list, const int32_t* ncols, int32_t slice_cols,
+                             const int64_t* slice_pos, const int64_t* multi_pos, const int64_t* slot_pos,
+                             WgSlice* slices, MultiRow* multi, hipStream_t s)
+{
+    if (n_list <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_slice_fill, dim3((n_list + 255) / 256), dim3(256), 0, s, n_list, win_list, ncols, slice_cols,
+                       slice_pos, multi_pos, slot_pos, slices, multi);
     return hipGetLastError();
 }
 

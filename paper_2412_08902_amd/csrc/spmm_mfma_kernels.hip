@@ -218,21 +218,26 @@ __global__ __launch_bounds__(256) void k_mfma_small(int32_t n_list, const WinDes
 // KC-column chunk together, split its K-steps between them (blocks of 64 columns, round-robin)
 // and add their partial tiles through LDS at the end, in wave order.  KC = kKcMid keeps the LDS
 // footprint small for windows of a few hundred columns, KC = kKcBig serves the very wide ones.
+// A workgroup owns one slice of a window's condensed columns: windows wider than kSliceCols are
+// cut into several slices so that a hub window is not one workgroup's serial work; the slices'
+// partial tiles go to memory and k_reduce_tiles adds them in slice order (deterministic).
 template <int VW, int NG, int KC>
-__global__ __launch_bounds__(256) void k_mfma_wg(const int32_t* __restrict__ win_list,
+__global__ __launch_bounds__(256) void k_mfma_wg(const WgSlice* __restrict__ slices,
                                                   const int32_t* __restrict__ ncols, const int64_t* __restrict__ wptr,
                                                   const int32_t* __restrict__ wcols, const int32_t* __restrict__ erc,
-                                                  int rows_sorted, int col0, SpmmArgs a)
+                                                  int rows_sorted, const int32_t* __restrict__ slice_rows,
+                                                  float* __restrict__ tile_partial, int col0, SpmmArgs a)
 {
     constexpr int kAccFloats = NG * VW * 4 * 64;           // one wave's accumulators
     constexpr int kLdsFloats = KC * 16 > kAccFloats ? KC * 16 : kAccFloats;
     __shared__ float tile[kLdsFloats];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int32_t w = win_list[blockIdx.x];
+    const WgSlice sl = slices[blockIdx.x];
+    const int32_t w = sl.w;
     const int32_t r0 = w * kH;
     const int32_t s = a.rowptr[r0];
     const int32_t e = a.rowptr[min(r0 + kH, a.n_rows)];
-    const int32_t nc = ncols[w];
+    const int32_t nc = min(ncols[w], sl.kc_end);           // this workgroup owns condensed columns [kc_begin, nc)
     const int64_t wp = wptr[w];
     const float* __restrict__ X = static_cast<const float*>(a.X) + col0;
     const int d = min(a.d - col0, NG * 16 * VW);
@@ -249,7 +254,20 @@ __global__ __launch_bounds__(256) void k_mfma_wg(const int32_t* __restrict__ win
     const int my_r = threadIdx.x >> 4, l16 = threadIdx.x & 15;
     int32_t cur = a.rowptr[min(r0 + my_r, a.n_rows)];
     const int32_t row_e = a.rowptr[min(r0 + my_r + 1, a.n_rows)];
-    for (int32_t kc0 = 0; kc0 < nc; kc0 += KC) {
+    // a later slice of a wide window starts each row at its first entry inside the slice (found at prepare time)
+    if (rows_sorted && slice_rows) cur = slice_rows[(int64_t)blockIdx.x * kH + my_r];
+    // Each wave owns the 64-column blocks wave, wave+4, ... of every chunk.  Its gather pipeline
+    // runs across block and chunk boundaries: the next block's column ids are fetched one block
+    // ahead and its first X rows are requested before the current block's last MFMAs -- for the
+    // first block of a chunk that is before the chunk's A tile is even built.
+    constexpr int U = MfmaPipe<VW, NG>::U;
+    constexpr int NST = 16 / U;
+    int32_t col_cur[1] = {0}, col_next[1] = {0};
+    if (wave * 64 < min(KC, nc - sl.kc_begin)) {
+        col_cur[0] = wcols[wp + min(sl.kc_begin + wave * 64 + lane, nc - 1)];
+        mfma_stage_load<VW, NG, 1>(0, col_cur, lane, X, a.ldx, d, xa[0]);
+    }
+    for (int32_t kc0 = sl.kc_begin; kc0 < nc; kc0 += KC) {
         const int kend = min(KC, nc - kc0);
         for (int i = threadIdx.x * 4; i < KC * 16; i += 1024)
             *reinterpret_cast<float4*>(&tile[i]) = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -279,10 +297,22 @@ __global__ __launch_bounds__(256) void k_mfma_wg(const int32_t* __restrict__ win
         }
         __syncthreads();
         for (int kb = wave * 64; kb < kend; kb += 256) {
-            int32_t mycol[1];
-            mycol[0] = wcols[wp + min(kc0 + kb + lane, nc - 1)];
             const int nsteps = (min(64, kend - kb) + 3) >> 2;
-            mfma_run<VW, NG, 1, false>(tile + kb * 16, nsteps, mycol, lane, X, a.ldx, d, xa, acc);
+            int32_t nkc0 = kc0, nkb = kb + 256;
+            if (nkb >= kend) { nkc0 = kc0 + KC; nkb = wave * 64; }
+            const bool has_next = nkc0 < nc && nkb < min(KC, nc - nkc0);
+            col_next[0] = has_next ? wcols[wp + min(nkc0 + nkb + lane, nc - 1)] : col_cur[0];
+            const float* __restrict__ blk = tile + kb * 16;
+#pragma unroll
+            for (int st = 0; st < NST; ++st) {
+                if (st + 1 < NST) {
+                    if ((st + 1) * U < nsteps) mfma_stage_load<VW, NG, 1>(st + 1, col_cur, lane, X, a.ldx, d, xa[(st + 1) & 1]);
+                } else if (has_next) {
+                    mfma_stage_load<VW, NG, 1>(0, col_next, lane, X, a.ldx, d, xa[0]);
+                }
+                if (st * U < nsteps) mfma_stage_compute<VW, NG>(st, blk, lane, xa[st & 1], acc);
+            }
+            col_cur[0] = col_next[0];
         }
         __syncthreads();
     }
@@ -308,7 +338,25 @@ __global__ __launch_bounds__(256) void k_mfma_wg(const int32_t* __restrict__ win
         }
         __syncthreads();
     }
-    if (wave == 0) store_tile<VW, NG>(acc, lane, r0, a.n_rows, a.Y + col0, a.ldy, d, a.relu);
+    if (wave == 0) {
+        if (sl.slot < 0) store_tile<VW, NG>(acc, lane, r0, a.n_rows, a.Y + col0, a.ldy, d, a.relu);
+        else store_tile<VW, NG>(acc, lane, sl.slot * kH, 0x7fffffff, tile_partial + col0, a.d, d, 0);
+    }
+}
+
+// windows cut into several column slices: add the slices' 16 x d partial tiles in slice order
+__global__ __launch_bounds__(256) void k_reduce_tiles(const MultiRow* __restrict__ multi,
+                                                      const float* __restrict__ tile_partial, SpmmArgs a)
+{
+    const MultiRow m = multi[blockIdx.x];                 // row = window id
+    for (int i = threadIdx.x; i < kH * a.d; i += 256) {
+        const int r = i / a.d, c = i - r * a.d;
+        const int64_t row = (int64_t)m.row * kH + r;
+        if (row >= a.n_rows) continue;
+        float acc = 0.f;
+        for (int q = 0; q < m.n_slots; ++q) acc += tile_partial[((int64_t)(m.first_slot + q) * kH + r) * a.d + c];
+        a.Y[row * a.ldy + c] = a.relu ? fmaxf(acc, 0.f) : acc;
+    }
 }
 
 // ---- dispatch ---------------------------------------------------------------------------------
@@ -356,9 +404,9 @@ hipError_t launch_mfma_small(const SpmmArgs& a, int32_t n_list, const WinDesc* d
     return hipGetLastError();
 }
 
-hipError_t launch_mfma_wg(const SpmmArgs& a, int32_t n_list, const int32_t* win_list, const int32_t* ncols,
+hipError_t launch_mfma_wg(const SpmmArgs& a, int32_t n_list, const WgSlice* slices, const int32_t* ncols,
                           const int64_t* wptr, const int32_t* wcols, const int32_t* erc, int rows_sorted,
-                          bool wide, hipStream_t s)
+                          const int32_t* slice_rows, float* tile_partial, bool wide, hipStream_t s)
 {
     if (n_list <= 0) return hipSuccess;
     const MfmaShape sh = pick_mfma_shape(a);
@@ -366,14 +414,22 @@ hipError_t launch_mfma_wg(const SpmmArgs& a, int32_t n_list, const int32_t* win_
     for (int col0 = 0; col0 < a.d; col0 += span) {
 #define HC_LAUNCH_MB(V, G)                                                                         \
     if (wide)                                                                                      \
-        hipLaunchKernelGGL((k_mfma_wg<V, G, kKcBig>), dim3(n_list), dim3(256), 0, s, win_list, ncols, wptr, wcols,   \
-                           erc, rows_sorted, col0, a);                                             \
+        hipLaunchKernelGGL((k_mfma_wg<V, G, kKcBig>), dim3(n_list), dim3(256), 0, s, slices, ncols, wptr, wcols,     \
+                           erc, rows_sorted, slice_rows, tile_partial, col0, a);                   \
     else                                                                                           \
-        hipLaunchKernelGGL((k_mfma_wg<V, G, kKcMid>), dim3(n_list), dim3(256), 0, s, win_list, ncols, wptr, wcols,   \
-                           erc, rows_sorted, col0, a)
+        hipLaunchKernelGGL((k_mfma_wg<V, G, kKcMid>), dim3(n_list), dim3(256), 0, s, slices, ncols, wptr, wcols,     \
+                           erc, rows_sorted, slice_rows, tile_partial, col0, a)
         HC_MFMA_DISPATCH(HC_LAUNCH_MB)
 #undef HC_LAUNCH_MB
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_reduce_tiles(const SpmmArgs& a, int32_t n_multi, const MultiRow* multi, const float* tile_partial,
+                               hipStream_t s)
+{
+    if (n_multi <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_reduce_tiles, dim3(n_multi), dim3(256), 0, s, multi, tile_partial, a);
     return hipGetLastError();
 }
 

@@ -35,8 +35,9 @@ def test_host_only_calls():
     assert o.struct_size == ctypes.sizeof(hc.HcspmmOptions) and o.window_rows == 16 and o.route_mode == 0
     for dt in (hc.HCSPMM_F32, hc.HCSPMM_BF16, hc.HCSPMM_F16):
         for d in (0, 16, 32, 64, 128, 602):
-            c = hc.hcspmm_default_selector(dt, d)
-            assert len(c) == 3 and c[0] >= 0 and c[1] >= 0 and c[2] < 0      # monotone in the paper's directions
+            for nnz in (0, 10 ** 6, 10 ** 8):
+                c = hc.hcspmm_default_selector(dt, d, nnz)
+                assert len(c) == 3 and c[0] >= 0 and c[1] >= 0 and c[2] < 0  # monotone in the paper's directions
     lib = hc.load_library()
     assert lib.hcspmm_status_string(0) == b"ok"
     assert lib.hcspmm_status_string(2) == b"invalid CSR"
