@@ -113,6 +113,7 @@ hipError_t launch_mfma_wg(const SpmmArgs& a, int32_t n_list, const WgSlice* slic
                           const int32_t* slice_rows, float* tile_partial, bool wide, hipStream_t s);
 hipError_t launch_slice_rows(int32_t n_slices, const WgSlice* slices, int32_t n_rows, const int32_t* rowptr,
                              const int32_t* erc, int32_t* slice_rows, hipStream_t s);
+bool mfma_shape_supported(const SpmmArgs& a);
 hipError_t launch_reduce_tiles(const SpmmArgs& a, int32_t n_multi, const MultiRow* multi, const float* tile_partial,
                                hipStream_t s);
 hipError_t launch_gemm_f32(int64_t m, int32_t k, int32_t n, const float* X, int64_t ldx, const float* W, int64_t ldw,

@@ -576,7 +576,6 @@ static hcspmm_status spmm_impl(const hcspmm_plan* plan, const void* d_X, int64_t
     if (d < 1 || d > (1 << 20)) { set_error("d must be in [1, 2^20]"); return HCSPMM_EINVAL; }
     if (x_dtype < 0 || x_dtype > 2 || y_dtype < 0 || y_dtype > 2) { set_error("bad dtype"); return HCSPMM_EINVAL; }
     if (y_dtype != HCSPMM_F32) { set_error("only fp32 output is implemented"); return HCSPMM_EUNSUPPORTED; }
-    if (x_dtype != HCSPMM_F32) { set_error("16-bit X is not implemented yet"); return HCSPMM_EUNSUPPORTED; }
     if (plan->n_rows == 0) return HCSPMM_OK;
     hcspmm_status st;
     if ((st = check_dense("X", d_X, ldx, d)) != HCSPMM_OK) return st;
@@ -584,6 +583,10 @@ static hcspmm_status spmm_impl(const hcspmm_plan* plan, const void* d_X, int64_t
     SpmmArgs a;
     a.n_rows = plan->n_rows; a.rowptr = plan->rowptr; a.colind = plan->colind; a.vals = plan->vals;
     a.X = d_X; a.ldx = ldx; a.d = d; a.x_dtype = x_dtype; a.Y = static_cast<float*>(d_Y); a.ldy = ldy; a.relu = 0;
+    if (plan->n_mfma > 0 && !mfma_shape_supported(a)) {
+        set_error("16-bit X on the matrix path needs d, ldx and ldy to be multiples of 4 and 8-byte aligned X, 16-byte aligned Y");
+        return HCSPMM_EUNSUPPORTED;
+    }
     return run_spmm(plan, a, static_cast<hipStream_t>(stream), ev);
 }
 

@@ -16,10 +16,9 @@
 
 namespace hcspmm {
 
-template <int VEC> struct VecT;
-template <> struct VecT<4> { using type = float4; };
-template <> struct VecT<2> { using type = float2; };
-template <> struct VecT<1> { using type = float; };
+// XK: element kind of X -- 0 fp32, 1 bf16, 2 fp16.  16-bit elements are widened to fp32 on load;
+// all arithmetic of this path is fp32.
+template <int XK> struct XElem { static constexpr int size = XK == 0 ? 4 : 2; };
 
 template <int VEC> __device__ inline void vzero(float (&a)[VEC])
 {
@@ -27,23 +26,53 @@ template <int VEC> __device__ inline void vzero(float (&a)[VEC])
     for (int i = 0; i < VEC; ++i) a[i] = 0.f;
 }
 
-template <int VEC> __device__ inline void vload(const float* __restrict__ p, float (&x)[VEC])
+__device__ inline float widen16(uint32_t bits, int xk)
 {
-    using V = typename VecT<VEC>::type;
-    V v = *reinterpret_cast<const V*>(p);
-    const float* f = reinterpret_cast<const float*>(&v);
+    if (xk == 1) return __uint_as_float(bits << 16);
+    const _Float16 h = __builtin_bit_cast(_Float16, (unsigned short)bits);
+    return (float)h;
+}
+
+// reads VEC consecutive elements starting at byte address p (aligned to the vector size)
+template <int VEC, int XK> __device__ inline void vload(const char* __restrict__ p, float (&x)[VEC])
+{
+    if constexpr (XK == 0) {
+        static_assert(VEC == 4 || VEC == 2 || VEC == 1, "fp32 vectors are 1, 2 or 4 wide");
+        if constexpr (VEC == 4) { const float4 v = *reinterpret_cast<const float4*>(p); x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w; }
+        else if constexpr (VEC == 2) { const float2 v = *reinterpret_cast<const float2*>(p); x[0] = v.x; x[1] = v.y; }
+        else { x[0] = *reinterpret_cast<const float*>(p); }
+    } else {
+        static_assert(VEC == 8 || VEC == 4 || VEC == 1, "16-bit vectors are 1, 4 or 8 wide");
+        if constexpr (VEC == 8) {
+            const uint4 v = *reinterpret_cast<const uint4*>(p);
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) x[i] = f[i];
+            for (int i = 0; i < 4; ++i) { x[2 * i] = widen16(w[i] & 0xffffu, XK); x[2 * i + 1] = widen16(w[i] >> 16, XK); }
+        } else if constexpr (VEC == 4) {
+            const uint2 v = *reinterpret_cast<const uint2*>(p);
+            x[0] = widen16(v.x & 0xffffu, XK); x[1] = widen16(v.x >> 16, XK);
+            x[2] = widen16(v.y & 0xffffu, XK); x[3] = widen16(v.y >> 16, XK);
+        } else {
+            x[0] = widen16(*reinterpret_cast<const unsigned short*>(p), XK);
+        }
+    }
 }
 
 template <int VEC> __device__ inline void vstore(float* __restrict__ p, const float (&x)[VEC], int relu)
 {
-    using V = typename VecT<VEC>::type;
-    V v;
-    float* f = reinterpret_cast<float*>(&v);
+    float y[VEC];
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) f[i] = relu ? fmaxf(x[i], 0.f) : x[i];
-    *reinterpret_cast<V*>(p) = v;
+    for (int i = 0; i < VEC; ++i) y[i] = relu ? fmaxf(x[i], 0.f) : x[i];
+    if constexpr (VEC == 8) {
+        *reinterpret_cast<float4*>(p) = make_float4(y[0], y[1], y[2], y[3]);
+        *reinterpret_cast<float4*>(p + 4) = make_float4(y[4], y[5], y[6], y[7]);
+    } else if constexpr (VEC == 4) {
+        *reinterpret_cast<float4*>(p) = make_float4(y[0], y[1], y[2], y[3]);
+    } else if constexpr (VEC == 2) {
+        *reinterpret_cast<float2*>(p) = make_float2(y[0], y[1]);
+    } else {
+        *p = y[0];
+    }
 }
 
 // One batch: the group's lanes hold up to LPR (column, value) pairs; every lane accumulates
@@ -51,9 +80,9 @@ template <int VEC> __device__ inline void vstore(float* __restrict__ p, const fl
 // column with value 0, so the loads carry no branches and all of them are in flight together.
 // Xc already points at a valid column for every lane (lanes past the matrix width read column 0
 // and never store).
-template <int LPR, int VEC>
-__device__ inline void batch_accumulate(int32_t mc, float mv, int cnt, const float* __restrict__ Xc,
-                                        int64_t ldx, float (&acc)[VEC])
+template <int LPR, int VEC, int XK>
+__device__ inline void batch_accumulate(int32_t mc, float mv, int cnt, const char* __restrict__ Xc,
+                                        int64_t ldx /* bytes */, float (&acc)[VEC])
 {
     constexpr int U = LPR < 8 ? LPR : 8;
 #pragma unroll 1
@@ -64,7 +93,7 @@ __device__ inline void batch_accumulate(int32_t mc, float mv, int cnt, const flo
         for (int u = 0; u < U; ++u) {
             const int32_t c = __shfl(mc, t0 + u, LPR);
             v[u] = __shfl(mv, t0 + u, LPR);
-            vload<VEC>(Xc + (int64_t)c * ldx, x[u]);
+            vload<VEC, XK>(Xc + (int64_t)c * ldx, x[u]);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u)
@@ -85,10 +114,10 @@ __device__ inline void fetch_entry(const int32_t* __restrict__ colind, const flo
 
 // Accumulate a span [kb, ke) of one row taken LPR non-zeros at a time with stride `stride`
 // (stride = LPR when one group owns the span, larger when several groups share it).
-template <int LPR, int VEC>
+template <int LPR, int VEC, int XK>
 __device__ inline void span_accumulate(int kb, int ke, int stride, int lig,
                                        const int32_t* __restrict__ colind, const float* __restrict__ vals,
-                                       const float* __restrict__ Xc, int64_t ldx, float (&acc)[VEC])
+                                       const char* __restrict__ Xc, int64_t ldx, float (&acc)[VEC])
 {
     if (kb >= ke) return;
     int32_t mc, nc;
@@ -97,7 +126,7 @@ __device__ inline void span_accumulate(int kb, int ke, int stride, int lig,
     for (int k0 = kb; k0 < ke; k0 += stride) {
         // fetch the next batch's indices before this batch's X rows
         fetch_entry(colind, vals, k0 + stride + lig, ke, nc, nv);
-        batch_accumulate<LPR, VEC>(mc, mv, min(LPR, ke - k0), Xc, ldx, acc);
+        batch_accumulate<LPR, VEC, XK>(mc, mv, min(LPR, ke - k0), Xc, ldx, acc);
         mc = nc;
         mv = nv;
     }
@@ -108,7 +137,7 @@ __device__ inline void span_accumulate(int kb, int ke, int stride, int lig,
 // single flattened loop: each trip either moves to the next row (storing the finished one) or
 // consumes one batch of the current row, so groups of one wave stay busy on rows of unequal
 // length.  The rows' extents are fetched up front, one per lane.
-template <int LPR, int VEC>
+template <int LPR, int VEC, int XK>
 __device__ inline void csr_short_body(int64_t block, int32_t n_items, const int32_t* __restrict__ row_list,
                                       const uint8_t* __restrict__ route, int rows_per_group, int mid_row,
                                       const SpmmArgs& a)
@@ -128,7 +157,9 @@ __device__ inline void csr_short_body(int64_t block, int32_t n_items, const int3
         // walking every row: skip rows owned by the matrix path or by the mid/long-row kernels
         if (!row_list && (route[my_row / kH] != 0 || my_e - my_s > mid_row)) my_row = -1;
     }
-    const float* __restrict__ X = static_cast<const float*>(a.X);
+    const char* __restrict__ X = static_cast<const char*>(a.X);
+    constexpr int ES = XElem<XK>::size;
+    const int64_t ldxb = a.ldx * ES;
     for (int c0 = 0; c0 < a.d; c0 += LPR * VEC) {
         const int c = c0 + lig * VEC;
         const bool col_ok = c < a.d;
@@ -156,7 +187,7 @@ __device__ inline void csr_short_body(int64_t block, int32_t n_items, const int3
             int32_t nc;
             float nv;
             fetch_entry(a.colind, a.vals, k + LPR + lig, e, nc, nv);
-            batch_accumulate<LPR, VEC>(mc, mv, min(LPR, e - k), X + (col_ok ? c : 0), a.ldx, acc);
+            batch_accumulate<LPR, VEC, XK>(mc, mv, min(LPR, e - k), X + (col_ok ? c : 0) * ES, ldxb, acc);
             mc = nc;
             mv = nv;
             k += LPR;
@@ -165,7 +196,7 @@ __device__ inline void csr_short_body(int64_t block, int32_t n_items, const int3
 }
 
 // ---- mid rows: one wave per row -------------------------------------------------------------
-template <int LPR, int VEC>
+template <int LPR, int VEC, int XK>
 __device__ inline void csr_mid_body(int64_t block, int32_t n_mid, const int32_t* __restrict__ mid_rows,
                                     const SpmmArgs& a)
 {
@@ -176,13 +207,15 @@ __device__ inline void csr_mid_body(int64_t block, int32_t n_mid, const int32_t*
     const int32_t row = mid_rows[item];
     const int32_t s = a.rowptr[row], e = a.rowptr[row + 1];
     const int g = lane / LPR, lig = lane % LPR;
-    const float* __restrict__ X = static_cast<const float*>(a.X);
+    const char* __restrict__ X = static_cast<const char*>(a.X);
+    constexpr int ES = XElem<XK>::size;
+    const int64_t ldxb = a.ldx * ES;
     for (int c0 = 0; c0 < a.d; c0 += LPR * VEC) {
         const int c = c0 + lig * VEC;
         const bool col_ok = c < a.d;
         float acc[VEC];
         vzero<VEC>(acc);
-        span_accumulate<LPR, VEC>(s + g * LPR, e, G * LPR, lig, a.colind, a.vals, X + (col_ok ? c : 0), a.ldx, acc);
+        span_accumulate<LPR, VEC, XK>(s + g * LPR, e, G * LPR, lig, a.colind, a.vals, X + (col_ok ? c : 0) * ES, ldxb, acc);
         // butterfly over the G groups: same operation order on every run
 #pragma unroll
         for (int off = LPR; off < 64; off <<= 1)
@@ -193,21 +226,23 @@ __device__ inline void csr_mid_body(int64_t block, int32_t n_mid, const int32_t*
 }
 
 // ---- long rows: one workgroup per segment of a row ------------------------------------------
-template <int LPR, int VEC>
+template <int LPR, int VEC, int XK>
 __device__ inline void csr_long_body(int64_t block, const Segment* __restrict__ segs, float* __restrict__ partial,
                                      float* __restrict__ red /* LDS, 256*VEC floats */, const SpmmArgs& a)
 {
     constexpr int G = 256 / LPR;
     const Segment sg = segs[block];
     const int g = threadIdx.x / LPR, lig = threadIdx.x % LPR;
-    const float* __restrict__ X = static_cast<const float*>(a.X);
+    const char* __restrict__ X = static_cast<const char*>(a.X);
+    constexpr int ES = XElem<XK>::size;
+    const int64_t ldxb = a.ldx * ES;
     for (int c0 = 0; c0 < a.d; c0 += LPR * VEC) {
         const int c = c0 + lig * VEC;
         const bool col_ok = c < a.d;
         float acc[VEC];
         vzero<VEC>(acc);
-        span_accumulate<LPR, VEC>(sg.k_begin + g * LPR, sg.k_end, G * LPR, lig, a.colind, a.vals,
-                                  X + (col_ok ? c : 0), a.ldx, acc);
+        span_accumulate<LPR, VEC, XK>(sg.k_begin + g * LPR, sg.k_end, G * LPR, lig, a.colind, a.vals,
+                                      X + (col_ok ? c : 0) * ES, ldxb, acc);
         // fixed-order tree over the G groups: the result does not depend on scheduling
 #pragma unroll
         for (int i = 0; i < VEC; ++i) red[(g * LPR + lig) * VEC + i] = acc[i];
@@ -247,23 +282,23 @@ struct CsrWork {
     int32_t mid_row;
 };
 
-template <int LPR, int VEC>
+template <int LPR, int VEC, int XK>
 __global__ __launch_bounds__(256) void k_csr(CsrWork wk, SpmmArgs a)
 {
     __shared__ float red[256 * VEC];
     int64_t b = blockIdx.x;
     if (b < wk.n_segs) {
-        csr_long_body<LPR, VEC>(b, wk.segs, wk.partial, red, a);
+        csr_long_body<LPR, VEC, XK>(b, wk.segs, wk.partial, red, a);
         return;
     }
     b -= wk.n_segs;
     const int64_t mid_blocks = ((int64_t)wk.n_mid + 3) / 4;
     if (b < mid_blocks) {
-        csr_mid_body<LPR, VEC>(b, wk.n_mid, wk.mid_rows, a);
+        csr_mid_body<LPR, VEC, XK>(b, wk.n_mid, wk.mid_rows, a);
         return;
     }
     b -= mid_blocks;
-    csr_short_body<LPR, VEC>(b, wk.n_items, wk.row_list, wk.route, wk.rows_per_group, wk.mid_row, a);
+    csr_short_body<LPR, VEC, XK>(b, wk.n_items, wk.row_list, wk.route, wk.rows_per_group, wk.mid_row, a);
 }
 
 // ---- rows cut into several segments: add the partial rows in segment order ------------------
@@ -285,30 +320,41 @@ static CsrShape pick_shape(const SpmmArgs& a, const float* partial)
 {
     int vec = 1;
     const uintptr_t px = (uintptr_t)a.X, py = (uintptr_t)a.Y, pp = (uintptr_t)partial;
-    if (a.d % 4 == 0 && a.ldx % 4 == 0 && a.ldy % 4 == 0 && px % 16 == 0 && py % 16 == 0 && pp % 16 == 0) vec = 4;
-    else if (a.d % 2 == 0 && a.ldx % 2 == 0 && a.ldy % 2 == 0 && px % 8 == 0 && py % 8 == 0 && pp % 8 == 0) vec = 2;
+    const bool y4 = a.ldy % 4 == 0 && py % 16 == 0 && pp % 16 == 0;
+    if (a.x_dtype == HCSPMM_F32) {
+        if (a.d % 4 == 0 && a.ldx % 4 == 0 && px % 16 == 0 && y4) vec = 4;
+        else if (a.d % 2 == 0 && a.ldx % 2 == 0 && a.ldy % 2 == 0 && px % 8 == 0 && py % 8 == 0 && pp % 8 == 0) vec = 2;
+    } else {
+        if (a.d % 8 == 0 && a.ldx % 8 == 0 && px % 16 == 0 && y4) vec = 8;
+        else if (a.d % 4 == 0 && a.ldx % 4 == 0 && px % 8 == 0 && y4) vec = 4;
+    }
     // a group needs at least kRowsPerGroup lanes; narrow the vectors of narrow matrices instead of idling lanes
-    while (vec > 1 && (a.d + vec - 1) / vec < kRowsPerGroup) vec >>= 1;
+    const int min_vec = 1;
+    while (vec > min_vec && (a.d + vec - 1) / vec < kRowsPerGroup) {
+        vec >>= 1;
+        if (a.x_dtype != HCSPMM_F32 && vec == 2) vec = 1;      // 16-bit inputs have no 2-wide variant
+    }
     const int lanes = (a.d + vec - 1) / vec;       // lanes needed to cover the width once
     int lpr = kRowsPerGroup;
     while (lpr < 64 && lpr < lanes) lpr <<= 1;
     return {lpr, vec};
 }
 
+#define HC_CSR_CASES(FN, XK, V)                                                                    \
+    switch (sh.lpr) {                                                                              \
+        case 8: FN(8, V, XK); break;                                                               \
+        case 16: FN(16, V, XK); break;                                                             \
+        case 32: FN(32, V, XK); break;                                                             \
+        default: FN(64, V, XK); break;                                                             \
+    }
+
 #define HC_CSR_DISPATCH(FN)                                                                        \
-    switch (sh.vec * 100 + sh.lpr) {                                                               \
-        case 408: FN(8, 4); break;                                                                 \
-        case 416: FN(16, 4); break;                                                                \
-        case 432: FN(32, 4); break;                                                                \
-        case 464: FN(64, 4); break;                                                                \
-        case 208: FN(8, 2); break;                                                                 \
-        case 216: FN(16, 2); break;                                                                \
-        case 232: FN(32, 2); break;                                                                \
-        case 264: FN(64, 2); break;                                                                \
-        case 108: FN(8, 1); break;                                                                 \
-        case 116: FN(16, 1); break;                                                                \
-        case 132: FN(32, 1); break;                                                                \
-        default: FN(64, 1); break;                                                                 \
+    if (a.x_dtype == HCSPMM_F32) {                                                                 \
+        if (sh.vec == 4) { HC_CSR_CASES(FN, 0, 4) } else if (sh.vec == 2) { HC_CSR_CASES(FN, 0, 2) } else { HC_CSR_CASES(FN, 0, 1) } \
+    } else if (a.x_dtype == HCSPMM_BF16) {                                                         \
+        if (sh.vec == 8) { HC_CSR_CASES(FN, 1, 8) } else if (sh.vec == 4) { HC_CSR_CASES(FN, 1, 4) } else { HC_CSR_CASES(FN, 1, 1) } \
+    } else {                                                                                       \
+        if (sh.vec == 8) { HC_CSR_CASES(FN, 2, 8) } else if (sh.vec == 4) { HC_CSR_CASES(FN, 2, 4) } else { HC_CSR_CASES(FN, 2, 1) } \
     }
 
 hipError_t launch_csr(const SpmmArgs& a, int32_t n_segs, const Segment* segs, float* partial, int32_t n_mid,
@@ -325,7 +371,7 @@ hipError_t launch_csr(const SpmmArgs& a, int32_t n_segs, const Segment* segs, fl
     const int64_t blocks = (int64_t)n_segs + ((int64_t)n_mid + 3) / 4 + (n_groups + gpb - 1) / gpb;
     if (blocks <= 0) return hipSuccess;
     CsrWork wk{n_segs, segs, partial, n_mid, mid_rows, n_items, row_list, route, rpg, mid_row};
-#define HC_LAUNCH_CSR(L, V) hipLaunchKernelGGL((k_csr<L, V>), dim3((unsigned)blocks), dim3(256), 0, s, wk, a)
+#define HC_LAUNCH_CSR(L, V, K) hipLaunchKernelGGL((k_csr<L, V, K>), dim3((unsigned)blocks), dim3(256), 0, s, wk, a)
     HC_CSR_DISPATCH(HC_LAUNCH_CSR)
 #undef HC_LAUNCH_CSR
     return hipGetLastError();

@@ -17,6 +17,14 @@
 // duplicate entries accumulate.  Read back, lane l of K-step q needs tile[(4q + l/16)*16 + l%16]
 // = tile[64q + l]: conflict-free.
 //
+// 16-bit path (X in bf16 or fp16): v_mfma_f32_16x16x16 with fp32 accumulation; a K-step is 16
+// condensed columns, lane l supplies A(row l%16, k 4*(l/16)+{0..3}) and B(k 4*(l/16)+{0..3}, col
+// l%16).  A lane reads VW consecutive 16-bit elements from each of its four X rows and transposes
+// them in registers into VW B operands (one per accumulator tile), so the global reads are the
+// same contiguous row stretches as on the fp32 path.  The A slice is accumulated in fp32 in LDS
+// (layout [k/4][row][k%4], so a lane's four values are one 16-byte read) and rounded to the
+// 16-bit type when it is read.
+//
 // Like any dense-tile formulation (the paper's included) this path multiplies every gathered X
 // row with explicit zeros, so X must be finite: a NaN or Inf in a gathered row reaches all 16
 // rows of the window, not only the rows that reference it.
@@ -25,84 +33,155 @@
 namespace hcspmm {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef short v4s __attribute__((ext_vector_type(4)));
+typedef _Float16 v4h __attribute__((ext_vector_type(4)));
 
-template <int VW> struct XVec;
-template <> struct XVec<4> { using type = float4; };
-template <> struct XVec<2> { using type = float2; };
-template <> struct XVec<1> { using type = float; };
+// ------------------------------------------------------------------------------------------------
+// Path policies.  A policy fixes, for one element kind XK (0 fp32, 1 bf16, 2 fp16), lane vector
+// width VW and number of 16*VW-column groups NG:
+//   SCOLS         condensed columns per pipeline stage (a 64-column block has 64/SCOLS stages)
+//   Buf           registers of one stage's gathered X rows
+//   load/compute  request a stage's X rows / issue its MFMAs
+//   tidx          position of A(row r, condensed column k) in the LDS tile
+// Column ids arrive as one register per 64-column block: lane l holds condensed column l of the
+// block; slots past the window's last column repeat that last column (their A entries are zero),
+// so every load is unconditional and a whole stage is in flight together.
+// ------------------------------------------------------------------------------------------------
+template <int XK, int VW, int NG> struct Path;
 
-template <int VW>
-__device__ inline void load_x(const float* __restrict__ p, float (&x)[VW])
-{
-    using V = typename XVec<VW>::type;
-    V v = *reinterpret_cast<const V*>(p);
-    const float* f = reinterpret_cast<const float*>(&v);
+template <int VW, int NG> struct Path<0, VW, NG> {
+    static constexpr int ES = 4;
+    static constexpr int SCOLS = (NG * VW >= 8) ? 16 : 32;
+    static constexpr int U = SCOLS / 4;                        // K-steps (4 columns each) per stage
+    struct Buf { float x[U][NG][VW]; };
+    __device__ static inline int tidx(int k, int r) { return k * 16 + r; }
+    __device__ static inline void load(int st, int32_t mycol, int lane, const char* __restrict__ X, int64_t ldxb, int d,
+                                       Buf& b)
+    {
+        const int j = lane & 15, kk = lane >> 4;
 #pragma unroll
-    for (int i = 0; i < VW; ++i) x[i] = f[i];
-}
-
-// A run of up to 16*NCR K-steps (64*NCR condensed columns) for one wave, software-pipelined:
-// the X rows of stage s+1 are requested before the MFMAs of stage s are issued, so the gather
-// latency hides behind the matrix work of the same wave.
-//   tile   : LDS image of the A columns of this run (k-major, tile[k*16 + row])
-//   mycol  : the run's column ids, lane l of mycol[i] holds condensed column 64*i + l; slots past the
-//            window's last column repeat that last column (their A entries are zero), so every load
-//            is unconditional and a whole stage is in flight together
-template <int VW, int NG> struct MfmaPipe {
-    static constexpr int U = (NG * VW >= 8) ? 4 : 8;       // K-steps per pipeline stage
-};
-
-// requests the X rows of K-steps [st*U, st*U + U) of a run into buf
-template <int VW, int NG, int NCR>
-__device__ inline void mfma_stage_load(int st, const int32_t (&mycol)[NCR], int lane, const float* __restrict__ X,
-                                       int64_t ldx, int d, float (&buf)[MfmaPipe<VW, NG>::U][NG][VW])
-{
-    constexpr int U = MfmaPipe<VW, NG>::U;
-    const int j = lane & 15, kk = lane >> 4;
+        for (int u = 0; u < U; ++u) {
+            const int q = st * U + u;                          // K-step inside the 64-column block
+            const int32_t c = __shfl(mycol, 4 * q + kk, 64);
+            const char* __restrict__ xr = X + (int64_t)c * ldxb;
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int q = st * U + u;
-        const int32_t c = __shfl(mycol[q >> 4], 4 * (q & 15) + kk, 64);
-        const float* __restrict__ xr = X + (int64_t)c * ldx;
-#pragma unroll
-        for (int g = 0; g < NG; ++g) {
-            const int col = g * 16 * VW + VW * j;           // columns past d read column 0 and are never stored
-            load_x<VW>(xr + (col < d ? col : 0), buf[u][g]);
+            for (int g = 0; g < NG; ++g) {
+                const int col = g * 16 * VW + VW * j;          // columns past d read column 0 and are never stored
+                const char* p = xr + (col < d ? col : 0) * ES;
+                if constexpr (VW == 4) { const float4 v = *reinterpret_cast<const float4*>(p); b.x[u][g][0] = v.x; b.x[u][g][1] = v.y; b.x[u][g][2] = v.z; b.x[u][g][3] = v.w; }
+                else if constexpr (VW == 2) { const float2 v = *reinterpret_cast<const float2*>(p); b.x[u][g][0] = v.x; b.x[u][g][1] = v.y; }
+                else { b.x[u][g][0] = *reinterpret_cast<const float*>(p); }
+            }
         }
     }
-}
-
-template <int VW, int NG>
-__device__ inline void mfma_stage_compute(int st, const float* __restrict__ tile, int lane,
-                                          const float (&buf)[MfmaPipe<VW, NG>::U][NG][VW], v4f (&acc)[NG][VW])
-{
-    constexpr int U = MfmaPipe<VW, NG>::U;
+    __device__ static inline void compute(int st, const float* __restrict__ blk, int lane, const Buf& b, v4f (&acc)[NG][VW])
+    {
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int q = st * U + u;
-        const float av = tile[4 * q * 16 + lane];
+        for (int u = 0; u < U; ++u) {
+            const int q = st * U + u;
+            const float av = blk[64 * q + lane];               // tidx(4q + lane/16, lane%16)
 #pragma unroll
-        for (int g = 0; g < NG; ++g)
+            for (int g = 0; g < NG; ++g)
 #pragma unroll
-            for (int t = 0; t < VW; ++t)
-                acc[g][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, buf[u][g][t], acc[g][t], 0, 0, 0);
+                for (int t = 0; t < VW; ++t)
+                    acc[g][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, b.x[u][g][t], acc[g][t], 0, 0, 0);
+        }
     }
+};
+
+__device__ inline uint32_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);                           // round to nearest even (finite inputs)
+    return u >> 16;
 }
 
-// PRELOADED: stage 0 of the run is already in flight in xa[0] (requested by the caller before it
-// built the A tile, so that the first gather overlaps the tile construction).
-template <int VW, int NG, int NCR, bool PRELOADED>
-__device__ inline void mfma_run(const float* __restrict__ tile, int nsteps, const int32_t (&mycol)[NCR], int lane,
-                                const float* __restrict__ X, int64_t ldx, int d,
-                                float (&xa)[2][MfmaPipe<VW, NG>::U][NG][VW], v4f (&acc)[NG][VW])
-{
-    constexpr int U = MfmaPipe<VW, NG>::U;
-    constexpr int NST = 16 * NCR / U;
+template <int XK, int VW, int NG> struct Path {
+    static_assert(XK == 1 || XK == 2, "16-bit element kinds");
+    static_assert(VW == 4 || VW == 8, "a lane reads 4 or 8 consecutive 16-bit elements");
+    static constexpr int ES = 2;
+    static constexpr int SCOLS = (NG * VW >= 8) ? 16 : 32;
+    static constexpr int U = SCOLS / 16;                       // K-steps (16 columns each) per stage
+    struct Buf { uint32_t w[U][NG][4][VW / 2]; };
+    __device__ static inline int tidx(int k, int r) { return ((k >> 2) * 16 + r) * 4 + (k & 3); }
+    __device__ static inline void load(int st, int32_t mycol, int lane, const char* __restrict__ X, int64_t ldxb, int d,
+                                       Buf& b)
+    {
+        const int j = lane & 15, kg = lane >> 4;
 #pragma unroll
-    for (int st = 0; st <= NST; ++st) {
-        if (st < NST && st * U < nsteps && !(PRELOADED && st == 0))
-            mfma_stage_load<VW, NG, NCR>(st, mycol, lane, X, ldx, d, xa[st & 1]);
-        if (st >= 1 && (st - 1) * U < nsteps) mfma_stage_compute<VW, NG>(st - 1, tile, lane, xa[(st - 1) & 1], acc);
+        for (int u = 0; u < U; ++u) {
+            const int q = st * U + u;                          // K-step inside the 64-column block
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int32_t c = __shfl(mycol, 16 * q + 4 * kg + t, 64);
+                const char* __restrict__ xr = X + (int64_t)c * ldxb;
+#pragma unroll
+                for (int g = 0; g < NG; ++g) {
+                    const int col = g * 16 * VW + VW * j;
+                    const char* p = xr + (col < d ? col : 0) * ES;
+                    if constexpr (VW == 8) { const uint4 v = *reinterpret_cast<const uint4*>(p); b.w[u][g][t][0] = v.x; b.w[u][g][t][1] = v.y; b.w[u][g][t][2] = v.z; b.w[u][g][t][3] = v.w; }
+                    else { const uint2 v = *reinterpret_cast<const uint2*>(p); b.w[u][g][t][0] = v.x; b.w[u][g][t][1] = v.y; }
+                }
+            }
+        }
+    }
+    __device__ static inline void compute(int st, const float* __restrict__ blk, int lane, const Buf& b, v4f (&acc)[NG][VW])
+    {
+        const int i = lane & 15, kg = lane >> 4;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int q = st * U + u;
+            // A(i, 16q + 4kg + {0..3}) accumulated in fp32, rounded here to the 16-bit type
+            const float4 af = *reinterpret_cast<const float4*>(&blk[((4 * q + kg) * 16 + i) * 4]);
+            uint32_t a_lo, a_hi;
+            if constexpr (XK == 1) {
+                a_lo = f32_to_bf16_bits(af.x) | (f32_to_bf16_bits(af.y) << 16);
+                a_hi = f32_to_bf16_bits(af.z) | (f32_to_bf16_bits(af.w) << 16);
+            } else {
+                a_lo = (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)af.x) | ((uint32_t)__builtin_bit_cast(unsigned short, (_Float16)af.y) << 16);
+                a_hi = (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)af.z) | ((uint32_t)__builtin_bit_cast(unsigned short, (_Float16)af.w) << 16);
+            }
+            const uint2 a2 = make_uint2(a_lo, a_hi);
+#pragma unroll
+            for (int g = 0; g < NG; ++g)
+#pragma unroll
+                for (int m = 0; m < VW / 2; ++m) {
+                    // transpose: element 2m / 2m+1 of the four rows -> the B operands of tiles 2m / 2m+1
+                    const uint32_t w0 = b.w[u][g][0][m], w1 = b.w[u][g][1][m], w2 = b.w[u][g][2][m], w3 = b.w[u][g][3][m];
+                    const uint2 be = make_uint2((w0 & 0xffffu) | (w1 << 16), (w2 & 0xffffu) | (w3 << 16));
+                    const uint2 bo = make_uint2((w0 >> 16) | (w1 & 0xffff0000u), (w2 >> 16) | (w3 & 0xffff0000u));
+                    if constexpr (XK == 1) {
+                        acc[g][2 * m] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(v4s, a2), __builtin_bit_cast(v4s, be), acc[g][2 * m], 0, 0, 0);
+                        acc[g][2 * m + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(v4s, a2), __builtin_bit_cast(v4s, bo), acc[g][2 * m + 1], 0, 0, 0);
+                    } else {
+                        acc[g][2 * m] = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(v4h, a2), __builtin_bit_cast(v4h, be), acc[g][2 * m], 0, 0, 0);
+                        acc[g][2 * m + 1] = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(v4h, a2), __builtin_bit_cast(v4h, bo), acc[g][2 * m + 1], 0, 0, 0);
+                    }
+                }
+        }
+    }
+};
+
+// The stages of one 64-column block, software-pipelined: the X rows of stage s+1 -- or, after the
+// block's last stage, of the next block's first stage -- are requested before the MFMAs of stage s
+// are issued, so the gather latency hides behind the matrix work of the same wave.
+//   blk       LDS image of the block's A columns;  ncols_blk: valid columns in the block (1..64)
+//   xa        the two stage buffers; stage 0 of this block is already in flight in xa[0]
+template <class P, int NG, int VW>
+__device__ inline void block_stages(const float* __restrict__ blk, int ncols_blk, int32_t col_cur, bool has_next,
+                                    int32_t col_next, int lane, const char* __restrict__ X, int64_t ldxb, int d,
+                                    typename P::Buf (&xa)[2], v4f (&acc)[NG][VW])
+{
+    constexpr int NST = 64 / P::SCOLS;
+    static_assert(NST % 2 == 0, "stage buffers alternate, a block must end on buffer 1");
+#pragma unroll
+    for (int st = 0; st < NST; ++st) {
+        if (st + 1 < NST) {
+            if ((st + 1) * P::SCOLS < ncols_blk) P::load(st + 1, col_cur, lane, X, ldxb, d, xa[(st + 1) & 1]);
+        } else if (has_next) {
+            P::load(0, col_next, lane, X, ldxb, d, xa[0]);
+        }
+        if (st * P::SCOLS < ncols_blk) P::compute(st, blk, lane, xa[st & 1], acc);
     }
 }
 
@@ -110,7 +189,6 @@ template <int VW, int NG>
 __device__ inline void store_tile(const v4f (&acc)[NG][VW], int lane, int32_t r0, int32_t n_rows, float* __restrict__ Y,
                                   int64_t ldy, int d, int relu)
 {
-    using V = typename XVec<VW>::type;
     const int j = lane & 15, kk = lane >> 4;
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
@@ -120,14 +198,20 @@ __device__ inline void store_tile(const v4f (&acc)[NG][VW], int lane, int32_t r0
         for (int r = 0; r < 4; ++r) {
             const int32_t row = r0 + 4 * kk + r;
             if (row >= n_rows) continue;
-            V v;
-            float* f = reinterpret_cast<float*>(&v);
+            float y[VW];
 #pragma unroll
-            for (int t = 0; t < VW; ++t) {
-                float y = acc[g][t][r];
-                f[t] = relu ? fmaxf(y, 0.f) : y;
+            for (int t = 0; t < VW; ++t) y[t] = relu ? fmaxf(acc[g][t][r], 0.f) : acc[g][t][r];
+            float* __restrict__ p = Y + (int64_t)row * ldy + col;
+            if constexpr (VW == 8) {
+                *reinterpret_cast<float4*>(p) = make_float4(y[0], y[1], y[2], y[3]);
+                *reinterpret_cast<float4*>(p + 4) = make_float4(y[4], y[5], y[6], y[7]);
+            } else if constexpr (VW == 4) {
+                *reinterpret_cast<float4*>(p) = make_float4(y[0], y[1], y[2], y[3]);
+            } else if constexpr (VW == 2) {
+                *reinterpret_cast<float2*>(p) = make_float2(y[0], y[1]);
+            } else {
+                *p = y[0];
             }
-            *reinterpret_cast<V*>(Y + (int64_t)row * ldy + col) = v;
         }
     }
 }
@@ -140,11 +224,12 @@ __device__ inline void store_tile(const v4f (&acc)[NG][VW], int lane, int32_t r0
 // LDS work that builds the A tile.
 constexpr int kEdgeRegs = 6;
 
-template <int VW, int NG>
+template <int XK, int VW, int NG>
 __global__ __launch_bounds__(256) void k_mfma_small(int32_t n_list, const WinDesc* __restrict__ desc,
                                                     const int32_t* __restrict__ wcols,
                                                     const int32_t* __restrict__ erc, int col0, SpmmArgs a)
 {
+    using P = Path<XK, VW, NG>;
     __shared__ float tiles[4][kKcSmall * 16];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int64_t item = (int64_t)blockIdx.x * 4 + wave;
@@ -153,20 +238,21 @@ __global__ __launch_bounds__(256) void k_mfma_small(int32_t n_list, const WinDes
     const int32_t r0 = ds.w * kH, s = ds.s, e = ds.e, nc = ds.nc;
     const int64_t wp = ds.wp;
     float* __restrict__ tile = tiles[wave];
-    const float* __restrict__ X = static_cast<const float*>(a.X) + col0;
+    const char* __restrict__ X = static_cast<const char*>(a.X) + (int64_t)col0 * P::ES;
+    const int64_t ldxb = a.ldx * P::ES;
     const int d = min(a.d - col0, NG * 16 * VW);
-    constexpr int NCR = kKcSmall / 64;
+    constexpr int NB = kKcSmall / 64;                          // 64-column blocks per chunk
     v4f acc[NG][VW];
 #pragma unroll
     for (int g = 0; g < NG; ++g)
 #pragma unroll
         for (int t = 0; t < VW; ++t) acc[g][t] = (v4f){0.f, 0.f, 0.f, 0.f};
-    float xa[2][MfmaPipe<VW, NG>::U][NG][VW];
+    typename P::Buf xa[2];
 
     // first chunk: column list, non-zeros and first X rows requested back to back
-    int32_t mycol[NCR];
+    int32_t mycol[NB];
 #pragma unroll
-    for (int i = 0; i < NCR; ++i) mycol[i] = wcols[wp + min(64 * i + lane, nc - 1)];
+    for (int i = 0; i < NB; ++i) mycol[i] = wcols[wp + min(64 * i + lane, nc - 1)];
     int32_t pe[kEdgeRegs];
     float ve[kEdgeRegs];
 #pragma unroll
@@ -175,39 +261,46 @@ __global__ __launch_bounds__(256) void k_mfma_small(int32_t n_list, const WinDes
         pe[q] = erc[k];
         ve[q] = a.vals[k];
     }
-    mfma_stage_load<VW, NG, NCR>(0, mycol, lane, X, a.ldx, d, xa[0]);
+    P::load(0, mycol[0], lane, X, ldxb, d, xa[0]);
     for (int i = lane * 4; i < kKcSmall * 16; i += 256)
         *reinterpret_cast<float4*>(&tile[i]) = make_float4(0.f, 0.f, 0.f, 0.f);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
 #pragma unroll
     for (int q = 0; q < kEdgeRegs; ++q) {
         const int32_t ec = pe[q] >> 4;
-        if (s + 64 * q + lane < e && ec < kKcSmall) atomicAdd(&tile[ec * 16 + (pe[q] & 15)], ve[q]);
+        if (s + 64 * q + lane < e && ec < kKcSmall) atomicAdd(&tile[P::tidx(ec, pe[q] & 15)], ve[q]);
     }
     for (int32_t k = s + 64 * kEdgeRegs + lane; k < e; k += 64) {
         const int32_t p = erc[k];
         const int32_t ec = p >> 4;
-        if (ec < kKcSmall) atomicAdd(&tile[ec * 16 + (p & 15)], a.vals[k]);
+        if (ec < kKcSmall) atomicAdd(&tile[P::tidx(ec, p & 15)], a.vals[k]);
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    mfma_run<VW, NG, NCR, true>(tile, (min(kKcSmall, nc) + 3) >> 2, mycol, lane, X, a.ldx, d, xa, acc);
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-
-    // further chunks of wider windows
-    for (int32_t kc0 = kKcSmall; kc0 < nc; kc0 += kKcSmall) {
+    for (int32_t kc0 = 0;;) {
         const int kend = min(kKcSmall, nc - kc0);
 #pragma unroll
-        for (int i = 0; i < NCR; ++i) mycol[i] = wcols[wp + min(kc0 + 64 * i + lane, nc - 1)];
+        for (int b = 0; b < NB; ++b) {
+            if (64 * b < kend) {
+                const bool has_next = b + 1 < NB && 64 * (b + 1) < kend;
+                block_stages<P, NG, VW>(tile + 64 * b * 16, min(64, kend - 64 * b), mycol[b], has_next,
+                                        mycol[b + 1 < NB ? b + 1 : b], lane, X, ldxb, d, xa, acc);
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        // further chunks of wider windows: rebuild the tile from all the window's non-zeros
+        kc0 += kKcSmall;
+        if (kc0 >= nc) break;
+#pragma unroll
+        for (int i = 0; i < NB; ++i) mycol[i] = wcols[wp + min(kc0 + 64 * i + lane, nc - 1)];
         for (int i = lane * 4; i < kKcSmall * 16; i += 256)
             *reinterpret_cast<float4*>(&tile[i]) = make_float4(0.f, 0.f, 0.f, 0.f);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        P::load(0, mycol[0], lane, X, ldxb, d, xa[0]);
         for (int32_t k = s + lane; k < e; k += 64) {
             const int32_t p = erc[k];
             const int32_t ec = (p >> 4) - kc0;
-            if (ec >= 0 && ec < kKcSmall) atomicAdd(&tile[ec * 16 + (p & 15)], a.vals[k]);
+            if (ec >= 0 && ec < kKcSmall) atomicAdd(&tile[P::tidx(ec, p & 15)], a.vals[k]);
         }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        mfma_run<VW, NG, NCR, false>(tile, (kend + 3) >> 2, mycol, lane, X, a.ldx, d, xa, acc);
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     }
     store_tile<VW, NG>(acc, lane, r0, a.n_rows, a.Y + col0, a.ldy, d, a.relu);
@@ -218,16 +311,18 @@ __global__ __launch_bounds__(256) void k_mfma_small(int32_t n_list, const WinDes
 // KC-column chunk together, split its K-steps between them (blocks of 64 columns, round-robin)
 // and add their partial tiles through LDS at the end, in wave order.  KC = kKcMid keeps the LDS
 // footprint small for windows of a few hundred columns, KC = kKcBig serves the very wide ones.
-// A workgroup owns one slice of a window's condensed columns: windows wider than kSliceCols are
-// cut into several slices so that a hub window is not one workgroup's serial work; the slices'
-// partial tiles go to memory and k_reduce_tiles adds them in slice order (deterministic).
-template <int VW, int NG, int KC>
+// A workgroup owns one slice of a window's condensed columns: windows wider than the plan's
+// slice width are cut into several slices so that a hub window is not one workgroup's serial
+// work; the slices' partial tiles go to memory and k_reduce_tiles adds them in slice order
+// (deterministic).
+template <int XK, int VW, int NG, int KC>
 __global__ __launch_bounds__(256) void k_mfma_wg(const WgSlice* __restrict__ slices,
                                                   const int32_t* __restrict__ ncols, const int64_t* __restrict__ wptr,
                                                   const int32_t* __restrict__ wcols, const int32_t* __restrict__ erc,
                                                   int rows_sorted, const int32_t* __restrict__ slice_rows,
                                                   float* __restrict__ tile_partial, int col0, SpmmArgs a)
 {
+    using P = Path<XK, VW, NG>;
     constexpr int kAccFloats = NG * VW * 4 * 64;           // one wave's accumulators
     constexpr int kLdsFloats = KC * 16 > kAccFloats ? KC * 16 : kAccFloats;
     __shared__ float tile[kLdsFloats];
@@ -239,15 +334,16 @@ __global__ __launch_bounds__(256) void k_mfma_wg(const WgSlice* __restrict__ sli
     const int32_t e = a.rowptr[min(r0 + kH, a.n_rows)];
     const int32_t nc = min(ncols[w], sl.kc_end);           // this workgroup owns condensed columns [kc_begin, nc)
     const int64_t wp = wptr[w];
-    const float* __restrict__ X = static_cast<const float*>(a.X) + col0;
+    const char* __restrict__ X = static_cast<const char*>(a.X) + (int64_t)col0 * P::ES;
+    const int64_t ldxb = a.ldx * P::ES;
     const int d = min(a.d - col0, NG * 16 * VW);
     v4f acc[NG][VW];
 #pragma unroll
     for (int g = 0; g < NG; ++g)
 #pragma unroll
         for (int t = 0; t < VW; ++t) acc[g][t] = (v4f){0.f, 0.f, 0.f, 0.f};
+    typename P::Buf xa[2];
 
-    float xa[2][MfmaPipe<VW, NG>::U][NG][VW];
     // When every row's columns ascend, so do its condensed columns: 16 threads per row keep a
     // cursor that only moves forward, and a chunk costs only the entries that fall into it.
     // Otherwise every chunk scans the whole window.
@@ -256,16 +352,15 @@ __global__ __launch_bounds__(256) void k_mfma_wg(const WgSlice* __restrict__ sli
     const int32_t row_e = a.rowptr[min(r0 + my_r + 1, a.n_rows)];
     // a later slice of a wide window starts each row at its first entry inside the slice (found at prepare time)
     if (rows_sorted && slice_rows) cur = slice_rows[(int64_t)blockIdx.x * kH + my_r];
+
     // Each wave owns the 64-column blocks wave, wave+4, ... of every chunk.  Its gather pipeline
     // runs across block and chunk boundaries: the next block's column ids are fetched one block
     // ahead and its first X rows are requested before the current block's last MFMAs -- for the
     // first block of a chunk that is before the chunk's A tile is even built.
-    constexpr int U = MfmaPipe<VW, NG>::U;
-    constexpr int NST = 16 / U;
-    int32_t col_cur[1] = {0}, col_next[1] = {0};
+    int32_t col_cur = 0, col_next = 0;
     if (wave * 64 < min(KC, nc - sl.kc_begin)) {
-        col_cur[0] = wcols[wp + min(sl.kc_begin + wave * 64 + lane, nc - 1)];
-        mfma_stage_load<VW, NG, 1>(0, col_cur, lane, X, a.ldx, d, xa[0]);
+        col_cur = wcols[wp + min(sl.kc_begin + wave * 64 + lane, nc - 1)];
+        P::load(0, col_cur, lane, X, ldxb, d, xa[0]);
     }
     for (int32_t kc0 = sl.kc_begin; kc0 < nc; kc0 += KC) {
         const int kend = min(KC, nc - kc0);
@@ -282,7 +377,7 @@ __global__ __launch_bounds__(256) void k_mfma_wg(const WgSlice* __restrict__ sli
                     p = erc[k];
                     take = (p >> 4) < limit;
                 }
-                if (take) atomicAdd(&tile[((p >> 4) - kc0) * 16 + my_r], a.vals[k]);
+                if (take) atomicAdd(&tile[P::tidx((p >> 4) - kc0, my_r)], a.vals[k]);
                 const unsigned long long b = __ballot(take);
                 const int n = __popc((unsigned)((b >> (16 * ((threadIdx.x & 63) >> 4))) & 0xffffu));
                 cur += n;
@@ -292,27 +387,18 @@ __global__ __launch_bounds__(256) void k_mfma_wg(const WgSlice* __restrict__ sli
             for (int32_t k = s + threadIdx.x; k < e; k += 256) {
                 const int32_t p = erc[k];
                 const int32_t ec = (p >> 4) - kc0;
-                if (ec >= 0 && ec < KC) atomicAdd(&tile[ec * 16 + (p & 15)], a.vals[k]);
+                if (ec >= 0 && ec < KC) atomicAdd(&tile[P::tidx(ec, p & 15)], a.vals[k]);
             }
         }
         __syncthreads();
         for (int kb = wave * 64; kb < kend; kb += 256) {
-            const int nsteps = (min(64, kend - kb) + 3) >> 2;
             int32_t nkc0 = kc0, nkb = kb + 256;
             if (nkb >= kend) { nkc0 = kc0 + KC; nkb = wave * 64; }
             const bool has_next = nkc0 < nc && nkb < min(KC, nc - nkc0);
-            col_next[0] = has_next ? wcols[wp + min(nkc0 + nkb + lane, nc - 1)] : col_cur[0];
-            const float* __restrict__ blk = tile + kb * 16;
-#pragma unroll
-            for (int st = 0; st < NST; ++st) {
-                if (st + 1 < NST) {
-                    if ((st + 1) * U < nsteps) mfma_stage_load<VW, NG, 1>(st + 1, col_cur, lane, X, a.ldx, d, xa[(st + 1) & 1]);
-                } else if (has_next) {
-                    mfma_stage_load<VW, NG, 1>(0, col_next, lane, X, a.ldx, d, xa[0]);
-                }
-                if (st * U < nsteps) mfma_stage_compute<VW, NG>(st, blk, lane, xa[st & 1], acc);
-            }
-            col_cur[0] = col_next[0];
+            col_next = has_next ? wcols[wp + min(nkc0 + nkb + lane, nc - 1)] : col_cur;
+            block_stages<P, NG, VW>(tile + kb * 16, min(64, kend - kb), col_cur, has_next, col_next, lane, X, ldxb, d,
+                                    xa, acc);
+            col_cur = col_next;
         }
         __syncthreads();
     }
@@ -362,41 +448,76 @@ __global__ __launch_bounds__(256) void k_reduce_tiles(const MultiRow* __restrict
 // ---- dispatch ---------------------------------------------------------------------------------
 struct MfmaShape { int vw, ng; };
 
-static MfmaShape pick_mfma_shape(const SpmmArgs& a)
+// 0 when the matrix path has no kernel for this combination of width, leading dimensions and alignment
+static bool pick_mfma_shape(const SpmmArgs& a, MfmaShape& sh)
 {
     const uintptr_t px = (uintptr_t)a.X, py = (uintptr_t)a.Y;
     int vw = 1;
-    if (a.d % 4 == 0 && a.ldx % 4 == 0 && a.ldy % 4 == 0 && px % 16 == 0 && py % 16 == 0) vw = 4;
-    else if (a.d % 2 == 0 && a.ldx % 2 == 0 && a.ldy % 2 == 0 && px % 8 == 0 && py % 8 == 0) vw = 2;
-    // prefer the narrowest vector that still covers d in one 16-lane stretch (no idle lanes)
-    while (vw > 1 && 16 * (vw / 2) >= a.d) vw >>= 1;
+    if (a.x_dtype == HCSPMM_F32) {
+        if (a.d % 4 == 0 && a.ldx % 4 == 0 && a.ldy % 4 == 0 && px % 16 == 0 && py % 16 == 0) vw = 4;
+        else if (a.d % 2 == 0 && a.ldx % 2 == 0 && a.ldy % 2 == 0 && px % 8 == 0 && py % 8 == 0) vw = 2;
+        // prefer the narrowest vector that still covers d in one 16-lane stretch (no idle lanes)
+        while (vw > 1 && 16 * (vw / 2) >= a.d) vw >>= 1;
+    } else {
+        const bool y4 = a.ldy % 4 == 0 && py % 16 == 0 && a.d % 4 == 0;
+        if (a.d % 8 == 0 && a.ldx % 8 == 0 && px % 16 == 0 && y4 && a.d > 64) vw = 8;
+        else if (a.d % 4 == 0 && a.ldx % 4 == 0 && px % 8 == 0 && y4) vw = 4;
+        else return false;
+    }
     const int groups = (a.d + 16 * vw - 1) / (16 * vw);
     int ng = groups >= 4 ? 4 : (groups >= 2 ? 2 : 1);
-    return {vw, ng};
+    if (a.x_dtype != HCSPMM_F32 && vw == 8 && ng > 2) ng = 2;   // 16 accumulator tiles at most
+    sh = {vw, ng};
+    return true;
+}
+
+bool mfma_shape_supported(const SpmmArgs& a)
+{
+    MfmaShape sh;
+    return pick_mfma_shape(a, sh);
 }
 
 #define HC_MFMA_DISPATCH(FN)                                                                       \
-    switch (sh.vw * 10 + sh.ng) {                                                                  \
-        case 41: FN(4, 1); break;                                                                  \
-        case 42: FN(4, 2); break;                                                                  \
-        case 44: FN(4, 4); break;                                                                  \
-        case 21: FN(2, 1); break;                                                                  \
-        case 22: FN(2, 2); break;                                                                  \
-        case 24: FN(2, 4); break;                                                                  \
-        case 11: FN(1, 1); break;                                                                  \
-        case 12: FN(1, 2); break;                                                                  \
-        default: FN(1, 4); break;                                                                  \
+    if (a.x_dtype == HCSPMM_F32) {                                                                 \
+        switch (sh.vw * 10 + sh.ng) {                                                              \
+            case 41: FN(0, 4, 1); break;                                                           \
+            case 42: FN(0, 4, 2); break;                                                           \
+            case 44: FN(0, 4, 4); break;                                                           \
+            case 21: FN(0, 2, 1); break;                                                           \
+            case 22: FN(0, 2, 2); break;                                                           \
+            case 24: FN(0, 2, 4); break;                                                           \
+            case 11: FN(0, 1, 1); break;                                                           \
+            case 12: FN(0, 1, 2); break;                                                           \
+            default: FN(0, 1, 4); break;                                                           \
+        }                                                                                          \
+    } else if (a.x_dtype == HCSPMM_BF16) {                                                         \
+        switch (sh.vw * 10 + sh.ng) {                                                              \
+            case 41: FN(1, 4, 1); break;                                                           \
+            case 42: FN(1, 4, 2); break;                                                           \
+            case 44: FN(1, 4, 4); break;                                                           \
+            case 81: FN(1, 8, 1); break;                                                           \
+            default: FN(1, 8, 2); break;                                                           \
+        }                                                                                          \
+    } else {                                                                                       \
+        switch (sh.vw * 10 + sh.ng) {                                                              \
+            case 41: FN(2, 4, 1); break;                                                           \
+            case 42: FN(2, 4, 2); break;                                                           \
+            case 44: FN(2, 4, 4); break;                                                           \
+            case 81: FN(2, 8, 1); break;                                                           \
+            default: FN(2, 8, 2); break;                                                           \
+        }                                                                                          \
     }
 
 hipError_t launch_mfma_small(const SpmmArgs& a, int32_t n_list, const WinDesc* desc, const int32_t* wcols,
                              const int32_t* erc, hipStream_t s)
 {
     if (n_list <= 0) return hipSuccess;
-    const MfmaShape sh = pick_mfma_shape(a);
+    MfmaShape sh;
+    if (!pick_mfma_shape(a, sh)) return hipErrorInvalidValue;
     const int span = sh.ng * 16 * sh.vw;                       // output columns per launch
     for (int col0 = 0; col0 < a.d; col0 += span) {
-#define HC_LAUNCH_MS(V, G)                                                                         \
-    hipLaunchKernelGGL((k_mfma_small<V, G>), dim3((unsigned)((n_list + 3) / 4)), dim3(256), 0, s, n_list, desc,      \
+#define HC_LAUNCH_MS(K, V, G)                                                                      \
+    hipLaunchKernelGGL((k_mfma_small<K, V, G>), dim3((unsigned)((n_list + 3) / 4)), dim3(256), 0, s, n_list, desc,   \
                        wcols, erc, col0, a)
         HC_MFMA_DISPATCH(HC_LAUNCH_MS)
 #undef HC_LAUNCH_MS
@@ -409,15 +530,16 @@ hipError_t launch_mfma_wg(const SpmmArgs& a, int32_t n_list, const WgSlice* slic
                           const int32_t* slice_rows, float* tile_partial, bool wide, hipStream_t s)
 {
     if (n_list <= 0) return hipSuccess;
-    const MfmaShape sh = pick_mfma_shape(a);
+    MfmaShape sh;
+    if (!pick_mfma_shape(a, sh)) return hipErrorInvalidValue;
     const int span = sh.ng * 16 * sh.vw;
     for (int col0 = 0; col0 < a.d; col0 += span) {
-#define HC_LAUNCH_MB(V, G)                                                                         \
+#define HC_LAUNCH_MB(K, V, G)                                                                      \
     if (wide)                                                                                      \
-        hipLaunchKernelGGL((k_mfma_wg<V, G, kKcBig>), dim3(n_list), dim3(256), 0, s, slices, ncols, wptr, wcols,     \
+        hipLaunchKernelGGL((k_mfma_wg<K, V, G, kKcBig>), dim3(n_list), dim3(256), 0, s, slices, ncols, wptr, wcols,  \
                            erc, rows_sorted, slice_rows, tile_partial, col0, a);                   \
     else                                                                                           \
-        hipLaunchKernelGGL((k_mfma_wg<V, G, kKcMid>), dim3(n_list), dim3(256), 0, s, slices, ncols, wptr, wcols,     \
+        hipLaunchKernelGGL((k_mfma_wg<K, V, G, kKcMid>), dim3(n_list), dim3(256), 0, s, slices, ncols, wptr, wcols,  \
                            erc, rows_sorted, slice_rows, tile_partial, col0, a)
         HC_MFMA_DISPATCH(HC_LAUNCH_MB)
 #undef HC_LAUNCH_MB

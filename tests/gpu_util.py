@@ -12,18 +12,25 @@ def device_graph(g):
             torch.from_numpy(np.ascontiguousarray(g.vals)).to(dev))
 
 
-def gpu_spmm(g, X, mode, d_hint=None, sel_coef=None, pad_x=0, pad_y=0, dev_graph=None):
-    """Run prepare + spmm on the GPU through the C ABI; returns (Y numpy, plan info dict)."""
+def gpu_spmm(g, X, mode, d_hint=None, sel_coef=None, pad_x=0, pad_y=0, dev_graph=None, x_bits=None, mfma_dtype=0):
+    """Run prepare + spmm on the GPU through the C ABI; returns (Y numpy, plan info dict).
+
+    x_bits = "bf16" / "f16": X is a uint16 array of bit patterns and is handed over as that 16-bit type."""
     import torch
     import paper_2412_08902_amd.binding as hc
     dev = torch.device("cuda:0")
     rp, ci, va = dev_graph if dev_graph is not None else device_graph(g)
     d = X.shape[1]
-    Xd_full = torch.full((X.shape[0], d + pad_x), float("nan"), dtype=torch.float32, device=dev)
-    Xd_full[:, :d] = torch.from_numpy(X).to(dev)
+    if x_bits is None:
+        Xd_full = torch.full((X.shape[0], d + pad_x), float("nan"), dtype=torch.float32, device=dev)
+        Xd_full[:, :d] = torch.from_numpy(X).to(dev)
+    else:
+        tdt = torch.bfloat16 if x_bits == "bf16" else torch.float16
+        Xd_full = torch.full((X.shape[0], d + pad_x), float("nan"), dtype=tdt, device=dev)
+        Xd_full[:, :d] = torch.from_numpy(X.view(np.int16)).to(dev).view(tdt)
     Yd_full = torch.full((g.n_rows, d + pad_y), -777.0, dtype=torch.float32, device=dev)
     plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, route_mode=mode,
-                             d_hint=d if d_hint is None else d_hint, sel_coef=sel_coef)
+                             d_hint=d if d_hint is None else d_hint, sel_coef=sel_coef, mfma_dtype=mfma_dtype)
     info = hc.hcspmm_plan_info(plan)
     hc.hcspmm_spmm(plan, Xd_full, Yd_full, d=d)
     torch.cuda.synchronize()

@@ -1,0 +1,109 @@
+"""GPU parity at the benchmark's full sizes (C4, C5), in the launch configuration bench.py times:
+sampled output rows against the oracle, sampled windows of the plan against the CPU re-derivation,
+and properties that hold at any size."""
+import numpy as np
+import pytest
+
+import oracle
+from workloads import make_config, CONFIGS, dense_normal
+from gpu_util import device_graph, assert_close
+
+pytestmark = pytest.mark.gpu
+TOL_F32 = 1e-5
+
+
+def sample_rows(g, n, seed):
+    rng = np.random.default_rng(seed)
+    deg = np.diff(g.rowptr)
+    rows = set(rng.choice(g.n_rows, n, replace=False).tolist())
+    rows.update([0, 1, 15, 16, g.n_rows - 1, int(np.argmax(deg)), int(np.argmin(deg))])
+    # some rows of every length tier: longest, around the tier boundaries, shortest
+    order = np.argsort(deg)
+    for frac in (0.0, 0.5, 0.9, 0.99, 0.999, 0.9999):
+        rows.add(int(order[min(g.n_rows - 1, int(frac * g.n_rows))]))
+    for bound in (256, 257, 1024, 1025, 2048, 2049):
+        idx = np.nonzero(deg == bound)[0]
+        if idx.size:
+            rows.add(int(idx[0]))
+    return np.array(sorted(rows), dtype=np.int64)
+
+
+def check_plan_windows(g, plan_arrays, info, windows):
+    coef = info["sel_coef"]
+    for w in windows:
+        wc, ec, cnt = oracle.derive_window(int(w), g.rowptr, g.colind)
+        lo, hi = plan_arrays["wptr"][w], plan_arrays["wptr"][w + 1]
+        s = g.rowptr[min(16 * w, g.n_rows)]
+        assert plan_arrays["nnzw"][w] == cnt and plan_arrays["ncols"][w] == wc.shape[0]
+        assert np.array_equal(plan_arrays["wcols"][lo:hi], wc)
+        assert np.array_equal(plan_arrays["ecol"][s:s + cnt], ec)
+        assert plan_arrays["route"][w] == oracle.select_route(wc.shape[0], cnt, coef)
+
+
+@pytest.fixture(scope="module")
+def c4():
+    print("generating C4 ...", flush=True)
+    g, X, _ = make_config("C4")
+    return g, X
+
+
+def test_c4_spmm_and_plan(c4):
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    g, X = c4
+    rp, ci, va = device_graph(g)
+    plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, d_hint=X.shape[1])
+    info = hc.hcspmm_plan_info(plan)
+    Xd = torch.from_numpy(X).cuda()
+    Y = torch.full((g.n_rows, X.shape[1]), float("nan"), device="cuda")
+    hc.hcspmm_spmm(plan, Xd, Y)
+    torch.cuda.synchronize()
+    assert not torch.isnan(Y).any().item()                       # every row was written
+    rows = sample_rows(g, 4096, seed=1)
+    got = Y[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.float64)
+    ref = oracle.spmm_rows(rows, g.rowptr, g.colind, g.vals, X)
+    bound = oracle.spmm_rows(rows, g.rowptr, g.colind, g.vals, X, use_abs=True)
+    assert_close(got, ref, bound, TOL_F32, "C4 sampled rows")
+    # property at any size: A applied to the all-ones matrix gives the row sums of the stored values
+    ones = torch.ones((g.n_cols, 8), device="cuda")
+    Y1 = torch.empty((g.n_rows, 8), device="cuda")
+    hc.hcspmm_spmm(plan, ones, Y1)
+    rs = np.add.reduceat(g.vals.astype(np.float64), g.rowptr[:-1].astype(np.int64))
+    np.testing.assert_allclose(Y1[:, 0].cpu().numpy(), rs, rtol=2e-5)
+    # plan: aggregate invariants everywhere, exact arrays on sampled windows
+    arrays = hc.hcspmm_plan_export(plan)
+    W = info["n_windows"]
+    assert W == (g.n_rows + 15) // 16 and int(arrays["nnzw"].sum()) == g.nnz
+    assert arrays["wptr"][-1] == info["total_ncols"] == int(arrays["ncols"].sum())
+    assert np.all(arrays["ncols"] <= arrays["nnzw"]) and np.all((arrays["ncols"] > 0) == (arrays["nnzw"] > 0))
+    assert np.array_equal(np.sort(np.concatenate([arrays["mfma_windows"], arrays["csr_windows"]])), np.arange(W))
+    wins = np.unique(np.concatenate([[0, 1, 2, 100, W - 1, W - 2], np.random.default_rng(2).choice(W, 300)]))
+    check_plan_windows(g, arrays, info, wins)
+    plan.destroy()
+
+
+def test_c5_layer_and_plan():
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    print("generating C5 ...", flush=True)
+    g, X, Wm = make_config("C5")
+    rp, ci, va = device_graph(g)
+    d_out = Wm.shape[1]
+    plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, d_hint=d_out)
+    info = hc.hcspmm_plan_info(plan)
+    assert info["n_mfma_windows"] > 0 and info["n_csr_windows"] > 0          # both paths are exercised
+    ws = torch.empty(hc.hcspmm_gcn_workspace_bytes(plan, X.shape[1], d_out), dtype=torch.uint8, device="cuda")
+    Y = torch.full((g.n_rows, d_out), float("nan"), device="cuda")
+    hc.hcspmm_gcn_layer(plan, torch.from_numpy(X).cuda(), torch.from_numpy(Wm).cuda(), Y, ws)
+    torch.cuda.synchronize()
+    assert not torch.isnan(Y).any().item() and Y.min().item() >= 0.0
+    rows = sample_rows(g, 48, seed=3)
+    got = Y[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.float64)
+    ref = oracle.gcn_layer_rows(rows, g.rowptr, g.colind, g.vals, X, Wm)
+    bound = oracle.gcn_layer_rows(rows, g.rowptr, g.colind, g.vals, X, Wm, use_abs=True)
+    assert_close(got, ref, bound, 2 * TOL_F32, "C5 layer sampled rows")
+    arrays = hc.hcspmm_plan_export(plan)
+    W = info["n_windows"]
+    wins = np.unique(np.concatenate([[0, 1, W - 1], np.random.default_rng(4).choice(W, 40)]))
+    check_plan_windows(g, arrays, info, wins)
+    plan.destroy()
