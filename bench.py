@@ -67,6 +67,9 @@ def main():
     ap.add_argument("--modes", action="store_true", help="also time the all-CSR and all-MFMA plans")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cold", action="store_true", help="also report cold-cache time (512 MiB flush between reps)")
+    ap.add_argument("--x-dtype", default="f32", choices=["f32", "bf16", "f16"], help="storage type of X")
+    ap.add_argument("--layer", action="store_true",
+                    help="C5 only: time the whole GCN layer Y = ReLU(A (X W)) (GEMM + hybrid SpMM) instead of the SpMM")
     ap.add_argument("--sel-coef", default=None, help="three comma-separated integers overriding the shipped selector")
     ap.add_argument("--calib", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for rocprofv3 byte counters)")
@@ -84,16 +87,26 @@ def main():
     dev = torch.device("cuda:0")
     name = args.workload
     t0 = time.time()
-    g, X, _ = make_config(name, with_dense=(name != "C5"))
+    g, X, Wm = make_config(name, with_dense=(name != "C5" or args.layer))
+    X_in = X
     if name == "C5":                      # SpMM stage of the layer: T = X W has the layer's output width
         X = dense_normal(g.n_rows, CONFIGS["C5"]["d"], seed=1)
     d = X.shape[1]
+    from workloads import to_bf16_bits, to_f16_bits
+    x_bits = None
+    if args.x_dtype != "f32":
+        x_bits = to_bf16_bits(X) if args.x_dtype == "bf16" else to_f16_bits(X)
     log("generated %s: N=%d nnz=%d d=%d in %.1fs" % (name, g.n_rows, g.nnz, d, time.time() - t0))
     rp = torch.from_numpy(g.rowptr).to(dev)
     ci = torch.from_numpy(g.colind).to(dev)
     va = torch.from_numpy(g.vals).to(dev)
-    Xd = torch.from_numpy(X).to(dev)
+    if x_bits is None:
+        Xd = torch.from_numpy(X).to(dev)
+    else:
+        Xd = torch.from_numpy(x_bits.view(np.int16)).to(dev).view(torch.bfloat16 if args.x_dtype == "bf16" else torch.float16)
     Yd = torch.empty((g.n_rows, d), dtype=torch.float32, device=dev)
+    mfma_dtype = {"f32": hc.HCSPMM_F32, "bf16": hc.HCSPMM_BF16, "f16": hc.HCSPMM_F16}[args.x_dtype]
+    sx = 4 if x_bits is None else 2
     flops = 2.0 * g.nnz * d
 
     sel_coef = [int(v) for v in args.sel_coef.split(",")] if args.sel_coef else None
@@ -101,7 +114,8 @@ def main():
     def prepare(mode):
         torch.cuda.synchronize()
         t = time.perf_counter()
-        plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, route_mode=mode, d_hint=d, sel_coef=sel_coef)
+        plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, route_mode=mode, d_hint=d, sel_coef=sel_coef,
+                                 mfma_dtype=mfma_dtype)
         torch.cuda.synchronize()
         return plan, (time.perf_counter() - t) * 1e3
 
@@ -130,12 +144,11 @@ def main():
     nnz_csr = g.nnz - nnz_mfma
     rows_mfma = min(info["n_mfma_windows"] * 16, g.n_rows)
     rows_csr = g.n_rows - rows_mfma
-    sx = 4
     share = {
         "ms_csr": dict(kernel="k_csr", rows=rows_csr, nnz=nnz_csr, extra_per_nnz=0),
         # the matrix path also reads 4 B per non-zero (condensed column + row) and 4 B per condensed column
         "ms_mfma_small": dict(kernel="k_mfma_small", rows=rows_mfma, nnz=nnz_mfma, extra_per_nnz=4),
-        "ms_mfma_big": dict(kernel="k_mfma_big", rows=rows_mfma, nnz=nnz_mfma, extra_per_nnz=4),
+        "ms_mfma_big": dict(kernel="k_mfma_wg", rows=rows_mfma, nnz=nnz_mfma, extra_per_nnz=4),
     }
     dom = max(share, key=lambda k: stage_ms.get(k, 0.0))
     s = share[dom]
@@ -150,12 +163,29 @@ def main():
 
     out = dict(metric="spmm_gflops (2*nnz*d/t)", value=round(gflops, 2), unit="GFLOP/s", n_gpus=1, steps=args.steps,
                warmup=args.warmup, ms_per_step=round(ms, 5), higher_is_better=True, scaling="weak", vs_baseline=None,
-               dtype="f32", data="synthetic",
+               dtype=args.x_dtype, data="synthetic",
                config=dict(workload=WORKLOAD_TEXT[name], name=name, n=g.n_rows, nnz=g.nnz, d=d, route_mode="hybrid",
                            n_windows=info["n_windows"], mfma_windows=info["n_mfma_windows"],
                            nnz_on_matrix_path=nnz_mfma, sel_coef=info["sel_coef"]),
                roofline=roofline, prepare_ms=round(prepare_ms, 3),
                stage_ms={k: round(v, 5) for k, v in stage_ms.items()})
+
+    Y_hybrid = Yd.cpu().numpy()                      # output of the timed SpMM, checked against the oracle below
+
+    if args.layer and name == "C5":
+        Xin_d = torch.from_numpy(X_in).to(dev)
+        Wd = torch.from_numpy(Wm).to(dev)
+        ws = torch.empty(hc.hcspmm_gcn_workspace_bytes(plan, X_in.shape[1], d), dtype=torch.uint8, device=dev)
+        Tg = torch.empty((g.n_rows, d), dtype=torch.float32, device=dev)
+        ms_gemm = time_steps(lambda: hc.hcspmm_gemm_f32(Xin_d, Wd, Tg), args.steps, args.warmup, torch)
+        ms_layer = time_steps(lambda: hc.hcspmm_gcn_layer(plan, Xin_d, Wd, Yd, ws), args.steps, args.warmup, torch)
+        gemm_flops = 2.0 * g.n_rows * X_in.shape[1] * d
+        out["layer"] = dict(ms_per_layer=round(ms_layer, 5), ms_gemm=round(ms_gemm, 5),
+                            gemm_tflops=round(gemm_flops / (ms_gemm * 1e-3) / 1e12, 2),
+                            gemm_frac_of_fp32_mfma_peak=round(gemm_flops / (ms_gemm * 1e-3) / 157.3e12, 4),
+                            total_gflops=round((gemm_flops + flops) / (ms_layer * 1e-3) / 1e9, 1))
+        log("layer: %.3f ms (gemm alone %.3f ms = %.1f TFLOP/s)" % (ms_layer, ms_gemm, out["layer"]["gemm_tflops"]))
+        del Xin_d, Wd, ws, Tg
 
     if args.cold:
         flush = torch.empty(512 << 20, dtype=torch.uint8, device=dev)
@@ -171,7 +201,6 @@ def main():
         out["cold_ms"] = round(float(np.median(ts)), 5)
         del flush
 
-    Y_hybrid = Yd.cpu().numpy()
     plan.destroy()
 
     if args.calib:
@@ -207,13 +236,14 @@ def main():
         rows = (wins[:, None] * 16 + np.arange(16)[None, :]).reshape(-1)
         rows = rows[rows < g.n_rows]
         t1 = time.perf_counter()
-        ref = oracle.spmm_rows(rows, g.rowptr, g.colind, g.vals, X)
+        x_or, code = (X, None) if x_bits is None else (x_bits, oracle.DT_BF16 if args.x_dtype == "bf16" else oracle.DT_F16)
+        ref = oracle.spmm_rows(rows, g.rowptr, g.colind, g.vals, x_or, code)
         cpu_s = time.perf_counter() - t1
         lens = np.diff(g.rowptr.astype(np.int64))[rows]
         cpu_gflops = 2.0 * float(lens.sum()) * d / cpu_s / 1e9
-        bound = oracle.spmm_rows(rows, g.rowptr, g.colind, g.vals, X, use_abs=True)
+        bound = oracle.spmm_rows(rows, g.rowptr, g.colind, g.vals, x_or, code, use_abs=True)
         err = np.abs(Y_hybrid[rows].astype(np.float64) - ref)
-        ok = bool(np.all(err <= 1e-5 * bound + 1e-30))
+        ok = bool(np.all(err <= (1e-5 if x_bits is None else 2e-2) * bound + 1e-30))
         out["cpu_baseline"] = dict(value=round(cpu_gflops, 3), unit="GFLOP/s", cores=oracle.num_threads(), kind="oracle",
                                    sample="every %d-th 16-row window (%d rows, %d non-zeros), %.1f s" %
                                           (stride, rows.shape[0], int(lens.sum()), cpu_s))
