@@ -29,9 +29,12 @@ HBM_PEAK_GBS = 8000.0
 
 # HBM-side bytes per launch of the dominant kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
 # summarised under profiles/ (each counter scaled by what it reads for a 1 GiB copy kernel in the
-# same run).  Keyed by (workload, kernel); None where no counter run exists for the pair.
+# same run).  Keyed by (workload, kernel, X dtype); None where no counter run exists for the triple.
 MEASURED_TRAFFIC_BYTES = {
-    ("C4", "k_csr"): 16.24e9 + 0.314e9,      # profiles/k_csr_C4_large_powerlaw.md
+    ("C4", "k_csr", "f32"): 16.24e9 + 0.314e9,      # profiles/k_csr_C4_large_powerlaw.md
+    ("C5", "k_mfma_wg", "f32"): 34.58e9 + 0.090e9,  # profiles/k_mfma_wg_C5_dense_powerlaw.md
+    ("C2", "k_csr", "f32"): 0.738e9 + 0.087e9,      # profiles/k_csr_C2_C3.md
+    ("C3", "k_csr", "f32"): 0.272e9 + 0.034e9,      # profiles/k_csr_C2_C3.md
 }
 
 WORKLOAD_TEXT = {
@@ -157,7 +160,7 @@ def main():
     achieved = alg_bytes / (stage_ms[dom] * 1e-3) / 1e9
     whole_bytes = 4.0 * (g.n_rows + 1) + 8.0 * g.nnz + g.n_cols * d * sx + g.n_rows * d * 4.0
     roofline = dict(bound="hbm", kernel=s["kernel"], achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=MEASURED_TRAFFIC_BYTES.get((name, s["kernel"])),
+                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=MEASURED_TRAFFIC_BYTES.get((name, s["kernel"], args.x_dtype)),
                     algorithmic_bytes=int(alg_bytes), kernel_ms=round(stage_ms[dom], 5),
                     whole_step_frac=round(whole_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4))
 
