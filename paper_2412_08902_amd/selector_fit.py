@@ -47,8 +47,8 @@ def make_matrix(torch, W, c, nnz_w, n_cols, seed, dev):
     return rowptr.to(torch.int32), colind.contiguous(), vals
 
 
-def time_mode(torch, hc, n_rows, n_cols, rp, ci, va, X, Y, mode, reps):
-    plan = hc.hcspmm_prepare(n_rows, n_cols, rp, ci, va, route_mode=mode)
+def time_mode(torch, hc, n_rows, n_cols, rp, ci, va, X, Y, mode, reps, mfma_dtype=0):
+    plan = hc.hcspmm_prepare(n_rows, n_cols, rp, ci, va, route_mode=mode, mfma_dtype=mfma_dtype)
     for _ in range(3):
         hc.hcspmm_spmm(plan, X, Y)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -100,6 +100,7 @@ def main():
     ap.add_argument("--windows", type=int, default=8192)
     ap.add_argument("--n-cols", type=int, default=1 << 18)
     ap.add_argument("--reps", type=int, default=20)
+    ap.add_argument("--x-dtype", default="f32", choices=["f32", "bf16", "f16"], help="storage type of X")
     ap.add_argument("--out", default=None, help="write a markdown summary here")
     ap.add_argument("--json", default=None, help="write all samples and fits here")
     args = ap.parse_args()
@@ -110,7 +111,9 @@ def main():
 
     dev = torch.device("cuda:0")
     d, W, n_cols = args.d, args.windows, args.n_cols
-    X = torch.randn((n_cols, d), device=dev)
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[args.x_dtype]
+    mfma_dtype = {"f32": hc.HCSPMM_F32, "bf16": hc.HCSPMM_BF16, "f16": hc.HCSPMM_F16}[args.x_dtype]
+    X = torch.randn((n_cols, d), device=dev).to(tdt)
     Y = torch.empty((W * 16, d), device=dev)
     cs = [2, 4, 8, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256, 384, 512, 768, 1024, 2048, 4096, 8192, 16384]
     fills = [1, 1.5, 2, 3, 4, 6, 8, 11, 15]                # non-zeros per column: sparsity 15/16 .. 1/16
@@ -122,8 +125,8 @@ def main():
         for f in fills:
             nnz_w = int(min(15 * c, max(c, round(c * f))))
             rp, ci, va = make_matrix(torch, Wc, c, nnz_w, n_cols, seed=1000 * c + int(10 * f), dev=dev)
-            t_csr = time_mode(torch, hc, Wc * 16, n_cols, rp, ci, va, X, Y, hc.HCSPMM_ROUTE_ALL_CSR, args.reps)
-            t_mfma = time_mode(torch, hc, Wc * 16, n_cols, rp, ci, va, X, Y, hc.HCSPMM_ROUTE_ALL_MFMA, args.reps)
+            t_csr = time_mode(torch, hc, Wc * 16, n_cols, rp, ci, va, X, Y, hc.HCSPMM_ROUTE_ALL_CSR, args.reps, mfma_dtype)
+            t_mfma = time_mode(torch, hc, Wc * 16, n_cols, rp, ci, va, X, Y, hc.HCSPMM_ROUTE_ALL_MFMA, args.reps, mfma_dtype)
             sp = 1.0 - nnz_w / (16.0 * c)
             rows.append(dict(ncols=c, nnzw=nnz_w, sparsity=sp, ms_csr=t_csr, ms_mfma=t_mfma,
                              label=int(t_csr < t_mfma)))
@@ -131,7 +134,7 @@ def main():
                   (c, nnz_w, sp, t_csr, t_mfma, "scalar" if t_csr < t_mfma else "matrix"), flush=True)
     feats = np.array([[r["ncols"], r["sparsity"]] for r in rows], dtype=np.float64)
     labels = np.array([r["label"] for r in rows])
-    result = dict(d=d, windows=W, n_cols=n_cols, samples=rows)
+    result = dict(d=d, x_dtype=args.x_dtype, windows=W, n_cols=n_cols, samples=rows)
     if labels.min() == labels.max():
         # one path wins everywhere in the sampled region: encode "always" with the constant term only
         coef = [0, 0, 1 if labels[0] == 1 else -1]
@@ -169,9 +172,10 @@ def main():
             json.dump(result, f)
     if args.out:
         with open(args.out, "w") as f:
-            f.write("# Selector sweep, fp32 MFMA, d = %d (%d windows per matrix, X %d x %d)\n\n" % (d, W, n_cols, d))
-            f.write("Command: `python -m paper_2412_08902_amd.selector_fit --d %d --windows %d --n-cols %d`\n\n" %
-                    (d, W, n_cols))
+            f.write("# Selector sweep, X in %s, d = %d (up to %d windows per matrix, X %d x %d)\n\n" %
+                    (args.x_dtype, d, W, n_cols, d))
+            f.write("Command: `python -m paper_2412_08902_amd.selector_fit --d %d --x-dtype %s --windows %d --n-cols %d`\n\n" %
+                    (d, args.x_dtype, W, n_cols))
             f.write("Fit: z = w1*ncols + w2*sparsity + b, w = %s, accuracy %.3f; sel_coef = %s\n\n" %
                     (result["w"], result["accuracy"], result["sel_coef"]))
             f.write("Time-minimising coefficients in the same family (w1, w2 >= 0 > b): sel_coef = %s, summed time %.3f x "
