@@ -202,6 +202,26 @@ hcspmm_status hcspmm_gcn_layer(const hcspmm_plan* plan, const void* d_X, int64_t
 
 size_t hcspmm_gcn_workspace_bytes(const hcspmm_plan* plan, int32_t d_in, int32_t d_out);
 
+/*
+ * Aggregate-then-update layer  Y = act((A X) W)  -- the association of GIN's forward pass and of
+ * GCN's backward pass, for which Section V-A describes the coupled kernel (aggregate a window,
+ * then multiply its result tile by W).  The aggregation Z = A X runs on the hybrid paths into the
+ * workspace; the update multiplies Z by W on the fp32 matrix cores with the activation in its
+ * epilogue.
+ *
+ *   d_X   device, n_cols x d_in, element type x_dtype (ldx >= d_in)
+ *   d_W   device, d_in x d_out fp32 (ldw >= d_out);  d_Y  device, n_rows x d_out fp32 (ldy >= d_out)
+ *   d_workspace  device, at least hcspmm_aggregate_update_workspace_bytes(plan, d_in, d_out) bytes,
+ *                256-byte aligned; holds Z (n_rows x d_in fp32) on return
+ * Asynchronous on `stream`.  Errors as hcspmm_spmm.
+ */
+hcspmm_status hcspmm_aggregate_update(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d_in,
+                                      int32_t x_dtype, const void* d_W, int64_t ldw, int32_t d_out,
+                                      void* d_Y, int64_t ldy, int32_t apply_relu,
+                                      void* d_workspace, size_t workspace_bytes, void* stream);
+
+size_t hcspmm_aggregate_update_workspace_bytes(const hcspmm_plan* plan, int32_t d_in, int32_t d_out);
+
 /* Dense update alone, T = X W in fp32 MFMA (Eq. 2): d_X M x K, d_W K x N, d_T M x N, all fp32 device. */
 hcspmm_status hcspmm_gemm_f32(int64_t m, int32_t k, int32_t n, const float* d_X, int64_t ldx,
                               const float* d_W, int64_t ldw, float* d_T, int64_t ldt, void* stream);

@@ -11,6 +11,8 @@ from .numeric import (  # noqa: F401
     gemm,
     gcn_layer,
     gcn_layer_rows,
+    aggregate_update,
+    aggregate_update_rows,
     num_threads,
     set_num_threads,
     DT_F32, DT_BF16, DT_F16, DT_F64,

@@ -149,3 +149,27 @@ def gcn_layer_rows(rows, rowptr, colind, vals, X, W, relu: bool = True, use_abs:
     if relu and not use_abs:
         Y = np.maximum(Y, 0.0)
     return Y
+
+
+def aggregate_update(rowptr, colind, vals, X, W, relu: bool = True, x_dtype: Optional[int] = None,
+                     use_abs: bool = False) -> np.ndarray:
+    """fp64 Y = ReLU((A X) W): the CSR loop first (Eq. 1), then the dense product with W, then max(0, .).
+
+    This is the aggregate-then-update association (GIN forward, GCN backward) whose coupled
+    kernel Section V-A describes; Z = A X stays in fp64 between the two loops.
+    """
+    Z = spmm(rowptr, colind, vals, X, x_dtype, use_abs=use_abs)
+    Y = gemm(Z, W, use_abs=use_abs)
+    if relu and not use_abs:
+        Y = np.maximum(Y, 0.0)
+    return Y
+
+
+def aggregate_update_rows(rows, rowptr, colind, vals, X, W, relu: bool = True, x_dtype: Optional[int] = None,
+                          use_abs: bool = False) -> np.ndarray:
+    """Rows ``rows`` of ReLU((A X) W)."""
+    Z = spmm_rows(rows, rowptr, colind, vals, X, x_dtype, use_abs=use_abs)
+    Y = gemm(Z, W, use_abs=use_abs)
+    if relu and not use_abs:
+        Y = np.maximum(Y, 0.0)
+    return Y

@@ -20,6 +20,7 @@ HCSPMM_ROUTE_HYBRID, HCSPMM_ROUTE_ALL_CSR, HCSPMM_ROUTE_ALL_MFMA = 0, 1, 2
 EXPORTED_SYMBOLS = [
     "hcspmm_default_options", "hcspmm_default_selector", "hcspmm_prepare", "hcspmm_plan_info",
     "hcspmm_plan_export", "hcspmm_spmm", "hcspmm_spmm_timed", "hcspmm_gcn_layer", "hcspmm_gcn_workspace_bytes",
+    "hcspmm_aggregate_update", "hcspmm_aggregate_update_workspace_bytes",
     "hcspmm_gemm_f32", "hcspmm_plan_destroy", "hcspmm_status_string", "hcspmm_last_error", "hcspmm_version",
 ]
 
@@ -86,6 +87,10 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.hcspmm_gcn_layer.restype = ctypes.c_int
     lib.hcspmm_gcn_workspace_bytes.argtypes = [vp, i32, i32]
     lib.hcspmm_gcn_workspace_bytes.restype = ctypes.c_size_t
+    lib.hcspmm_aggregate_update.argtypes = [vp, vp, i64, i32, i32, vp, i64, i32, vp, i64, i32, vp, ctypes.c_size_t, vp]
+    lib.hcspmm_aggregate_update.restype = ctypes.c_int
+    lib.hcspmm_aggregate_update_workspace_bytes.argtypes = [vp, i32, i32]
+    lib.hcspmm_aggregate_update_workspace_bytes.restype = ctypes.c_size_t
     lib.hcspmm_gemm_f32.argtypes = [i64, i32, i32, vp, i64, vp, i64, vp, i64, vp]
     lib.hcspmm_gemm_f32.restype = ctypes.c_int
     lib.hcspmm_plan_destroy.argtypes = [vp]
@@ -244,6 +249,20 @@ def hcspmm_gcn_layer(plan: Plan, X, W, Y, workspace, *, apply_relu: bool = True,
     _check(load_library().hcspmm_gcn_layer(plan.handle, _ptr(X), X.stride(0), X.shape[1], _ptr(W), W.stride(0),
                                            W.shape[1], _ptr(Y), Y.stride(0), 1 if apply_relu else 0, _ptr(workspace),
                                            workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
+    return Y
+
+
+def hcspmm_aggregate_update_workspace_bytes(plan: Plan, d_in: int, d_out: int) -> int:
+    return int(load_library().hcspmm_aggregate_update_workspace_bytes(plan.handle, d_in, d_out))
+
+
+def hcspmm_aggregate_update(plan: Plan, X, W, Y, workspace, *, apply_relu: bool = True, stream=None):
+    """Y = act((A X) W); workspace: a CUDA tensor of at least hcspmm_aggregate_update_workspace_bytes bytes."""
+    assert X.stride(1) == 1 and W.stride(1) == 1 and Y.stride(1) == 1
+    _check(load_library().hcspmm_aggregate_update(plan.handle, _ptr(X), X.stride(0), X.shape[1], _dtype_code(X),
+                                                  _ptr(W), W.stride(0), W.shape[1], _ptr(Y), Y.stride(0),
+                                                  1 if apply_relu else 0, _ptr(workspace),
+                                                  workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
     return Y
 
 

@@ -117,7 +117,7 @@ bool mfma_shape_supported(const SpmmArgs& a);
 hipError_t launch_reduce_tiles(const SpmmArgs& a, int32_t n_multi, const MultiRow* multi, const float* tile_partial,
                                hipStream_t s);
 hipError_t launch_gemm_f32(int64_t m, int32_t k, int32_t n, const float* X, int64_t ldx, const float* W, int64_t ldw,
-                           float* T, int64_t ldt, hipStream_t s);
+                           float* T, int64_t ldt, int relu, hipStream_t s);
 
 }  // namespace hcspmm
 

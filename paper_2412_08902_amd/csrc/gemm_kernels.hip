@@ -1,4 +1,4 @@
-// Dense update T = X W (Eq. 2) in true fp32 on the MFMA units: v_mfma_f32_32x32x2_f32.
+// Dense update T = act(X W) (Eq. 2; the activation is optional) in true fp32 on the MFMA units: v_mfma_f32_32x32x2_f32.
 //
 // Operand layout per lane l: A: row l%32, k = l/32.  B: k = l/32, column l%32.
 // D (32x32, 16 registers): column l%32, row 8*(v/4) + 4*(l/32) + v%4 for register v.
@@ -22,7 +22,7 @@ constexpr int LDB_S = BN + 4;
 template <int XV>
 __global__ __launch_bounds__(256) void k_gemm_f32(int64_t M, int32_t K, int32_t N, const float* __restrict__ X,
                                                   int64_t ldx, const float* __restrict__ Wm, int64_t ldw,
-                                                  float* __restrict__ T, int64_t ldt)
+                                                  float* __restrict__ T, int64_t ldt, int relu)
 {
     __shared__ float As[BK * LDA_S];
     __shared__ float Bs[BK * LDB_S];
@@ -113,23 +113,23 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int64_t M, int32_t K, int32_t 
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int64_t row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * lk + (v & 3);
-                if (row < M) T[row * ldt + col] = acc[i][j][v];
+                if (row < M) T[row * ldt + col] = relu ? fmaxf(acc[i][j][v], 0.f) : acc[i][j][v];
             }
         }
 }
 
 hipError_t launch_gemm_f32(int64_t m, int32_t k, int32_t n, const float* X, int64_t ldx, const float* W, int64_t ldw,
-                           float* T, int64_t ldt, hipStream_t s)
+                           float* T, int64_t ldt, int relu, hipStream_t s)
 {
     if (m <= 0 || n <= 0) return hipSuccess;
     dim3 grid((unsigned)((m + BM - 1) / BM), (unsigned)((n + BN - 1) / BN));
     const uintptr_t px = (uintptr_t)X;
     if (ldx % 4 == 0 && px % 16 == 0)
-        hipLaunchKernelGGL((k_gemm_f32<4>), grid, dim3(256), 0, s, m, k, n, X, ldx, W, ldw, T, ldt);
+        hipLaunchKernelGGL((k_gemm_f32<4>), grid, dim3(256), 0, s, m, k, n, X, ldx, W, ldw, T, ldt, relu);
     else if (ldx % 2 == 0 && px % 8 == 0)
-        hipLaunchKernelGGL((k_gemm_f32<2>), grid, dim3(256), 0, s, m, k, n, X, ldx, W, ldw, T, ldt);
+        hipLaunchKernelGGL((k_gemm_f32<2>), grid, dim3(256), 0, s, m, k, n, X, ldx, W, ldw, T, ldt, relu);
     else
-        hipLaunchKernelGGL((k_gemm_f32<1>), grid, dim3(256), 0, s, m, k, n, X, ldx, W, ldw, T, ldt);
+        hipLaunchKernelGGL((k_gemm_f32<1>), grid, dim3(256), 0, s, m, k, n, X, ldx, W, ldw, T, ldt, relu);
     return hipGetLastError();
 }
 

@@ -607,7 +607,7 @@ hcspmm_status hcspmm_gemm_f32(int64_t m, int32_t k, int32_t n, const float* d_X,
     if (k > 0 && (st = check_dense("X", d_X, ldx, k)) != HCSPMM_OK) return st;
     if (k > 0 && (st = check_dense("W", d_W, ldw, n)) != HCSPMM_OK) return st;
     if ((st = check_dense("T", d_T, ldt, n)) != HCSPMM_OK) return st;
-    HC_HIP(launch_gemm_f32(m, k, n, d_X, ldx, d_W, ldw, d_T, ldt, static_cast<hipStream_t>(stream)));
+    HC_HIP(launch_gemm_f32(m, k, n, d_X, ldx, d_W, ldw, d_T, ldt, 0, static_cast<hipStream_t>(stream)));
     return HCSPMM_OK;
 }
 
@@ -627,13 +627,48 @@ hcspmm_status hcspmm_gcn_layer(const hcspmm_plan* plan, const void* d_X, int64_t
     hipStream_t s = static_cast<hipStream_t>(stream);
     float* T = static_cast<float*>(d_workspace);
     HC_HIP(launch_gemm_f32(plan->n_cols, d_in, d_out, static_cast<const float*>(d_X), ldx,
-                           static_cast<const float*>(d_W), ldw, T, d_out, s));
+                           static_cast<const float*>(d_W), ldw, T, d_out, 0, s));
     if (plan->n_rows == 0) return HCSPMM_OK;
     SpmmArgs a;
     a.n_rows = plan->n_rows; a.rowptr = plan->rowptr; a.colind = plan->colind; a.vals = plan->vals;
     a.X = T; a.ldx = d_out; a.d = d_out; a.x_dtype = HCSPMM_F32; a.Y = static_cast<float*>(d_Y); a.ldy = ldy;
     a.relu = apply_relu ? 1 : 0;
     return run_spmm(plan, a, s);
+}
+
+size_t hcspmm_aggregate_update_workspace_bytes(const hcspmm_plan* plan, int32_t d_in, int32_t d_out)
+{
+    (void)d_out;
+    if (!plan || d_in < 1) return 0;
+    size_t b = (size_t)plan->n_rows * (size_t)d_in * sizeof(float);
+    return (b + 255) & ~(size_t)255;
+}
+
+hcspmm_status hcspmm_aggregate_update(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d_in,
+                                      int32_t x_dtype, const void* d_W, int64_t ldw, int32_t d_out, void* d_Y,
+                                      int64_t ldy, int32_t apply_relu, void* d_workspace, size_t workspace_bytes,
+                                      void* stream)
+{
+    if (!plan) { set_error("plan is NULL"); return HCSPMM_EINVAL; }
+    if (d_in < 1 || d_out < 1 || d_in > (1 << 20) || d_out > (1 << 20)) { set_error("d_in, d_out must be in [1, 2^20]"); return HCSPMM_EINVAL; }
+    if (x_dtype != HCSPMM_F32 && x_dtype != HCSPMM_BF16 && x_dtype != HCSPMM_F16) { set_error("x_dtype %d is not a dtype code", x_dtype); return HCSPMM_EINVAL; }
+    hcspmm_status st;
+    if ((st = check_dense("X", d_X, ldx, d_in)) != HCSPMM_OK) return st;
+    if ((st = check_dense("W", d_W, ldw, d_out)) != HCSPMM_OK) return st;
+    if ((st = check_dense("Y", d_Y, ldy, d_out)) != HCSPMM_OK) return st;
+    const size_t need = hcspmm_aggregate_update_workspace_bytes(plan, d_in, d_out);
+    if (!d_workspace || workspace_bytes < need) { set_error("workspace too small: need %zu bytes", need); return HCSPMM_EINVAL; }
+    if (((uintptr_t)d_workspace & 255) != 0) { set_error("workspace must be 256-byte aligned"); return HCSPMM_EINVAL; }
+    if (plan->n_rows == 0) return HCSPMM_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float* Z = static_cast<float*>(d_workspace);
+    SpmmArgs a;
+    a.n_rows = plan->n_rows; a.rowptr = plan->rowptr; a.colind = plan->colind; a.vals = plan->vals;
+    a.X = d_X; a.ldx = ldx; a.d = d_in; a.x_dtype = x_dtype; a.Y = Z; a.ldy = d_in; a.relu = 0;
+    if ((st = run_spmm(plan, a, s)) != HCSPMM_OK) return st;
+    HC_HIP(launch_gemm_f32(plan->n_rows, d_in, d_out, Z, d_in, static_cast<const float*>(d_W), ldw,
+                           static_cast<float*>(d_Y), ldy, apply_relu ? 1 : 0, s));
+    return HCSPMM_OK;
 }
 
 void hcspmm_plan_destroy(hcspmm_plan* plan)

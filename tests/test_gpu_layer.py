@@ -60,3 +60,76 @@ def test_layer_scaled_config5():
     ref = oracle.gcn_layer(g.rowptr, g.colind, g.vals, X, W)
     bound = oracle.gcn_layer(g.rowptr, g.colind, g.vals, X, W, use_abs=True)
     assert_close(got, ref, bound, 2 * TOL_F32)
+
+
+def run_aggregate_update(g, X, W, mode, relu=True, x_bits=None, ldy_pad=0):
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    rp, ci, va = device_graph(g)
+    plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, route_mode=mode, d_hint=X.shape[1],
+                             mfma_dtype={None: 0, "bf16": 1, "f16": 2}[x_bits])
+    ws = torch.empty(hc.hcspmm_aggregate_update_workspace_bytes(plan, X.shape[1], W.shape[1]), dtype=torch.uint8,
+                     device="cuda")
+    Y = torch.full((g.n_rows, W.shape[1] + ldy_pad), -3.0, device="cuda")
+    if x_bits is None:
+        Xd = torch.from_numpy(X).cuda()
+    else:
+        Xd = torch.from_numpy(X.view(np.int16)).cuda().view(torch.bfloat16 if x_bits == "bf16" else torch.float16)
+    hc.hcspmm_aggregate_update(plan, Xd, torch.from_numpy(W).cuda(), Y[:, :W.shape[1]], ws, apply_relu=relu)
+    torch.cuda.synchronize()
+    out = Y.cpu().numpy().astype(np.float64)
+    plan.destroy()
+    assert np.all(out[:, W.shape[1]:] == -3.0)
+    return out[:, :W.shape[1]]
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("relu", [True, False])
+def test_aggregate_update_small(mode, relu):
+    """Y = act((A X) W), the aggregate-then-update association, on all three routings."""
+    g = gcn_normalise(chung_lu_graph(700, 9000, 2.0, seed=31))
+    X, W = dense_normal(700, 40, seed=32), glorot_uniform(40, 56, seed=33)
+    got = run_aggregate_update(g, X, W, mode, relu, ldy_pad=3)
+    ref = oracle.aggregate_update(g.rowptr, g.colind, g.vals, X, W, relu=relu)
+    bound = oracle.aggregate_update(g.rowptr, g.colind, g.vals, X, W, use_abs=True)
+    assert_close(got, ref, bound, 2 * TOL_F32)
+    if relu:
+        assert got.min() >= 0.0 and (got == 0).any()
+
+
+@pytest.mark.parametrize("din,dout", [(32, 32), (64, 16), (128, 128), (20, 7)])
+def test_aggregate_update_widths(din, dout):
+    from workloads import sbm_graph
+    g = sbm_graph(24, 64, 0.4, 3.0, seed=41)
+    X, W = dense_normal(g.n_cols, din, seed=42), glorot_uniform(din, dout, seed=43)
+    got = run_aggregate_update(g, X, W, 0)
+    ref = oracle.aggregate_update(g.rowptr, g.colind, g.vals, X, W)
+    bound = oracle.aggregate_update(g.rowptr, g.colind, g.vals, X, W, use_abs=True)
+    assert_close(got, ref, bound, 2 * TOL_F32)
+
+
+def test_aggregate_update_bf16_x():
+    from workloads import sbm_graph, to_bf16_bits
+    g = sbm_graph(24, 64, 0.4, 3.0, seed=51)
+    X, W = dense_normal(g.n_cols, 64, seed=52), glorot_uniform(64, 32, seed=53)
+    Xb = to_bf16_bits(X)
+    got = run_aggregate_update(g, Xb, W, 0, x_bits="bf16")
+    ref = oracle.aggregate_update(g.rowptr, g.colind, g.vals, Xb, W, x_dtype=oracle.DT_BF16)
+    bound = oracle.aggregate_update(g.rowptr, g.colind, g.vals, Xb, W, x_dtype=oracle.DT_BF16, use_abs=True)
+    assert_close(got, ref, bound, 2e-2)
+
+
+def test_aggregate_update_empty_and_errors():
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    g = tiny_random_csr(40, 40, 0.0, seed=3)          # no entries at all: Y = act(0 W) = 0
+    X, W = dense_normal(40, 8, seed=4), glorot_uniform(8, 8, seed=5)
+    got = run_aggregate_update(g, X, W, 0)
+    assert np.all(got == 0.0)
+    rp, ci, va = device_graph(g)
+    plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va)
+    Y = torch.empty(40, 8, device="cuda")
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(hc.HcspmmError):
+        hc.hcspmm_aggregate_update(plan, torch.from_numpy(X).cuda(), torch.from_numpy(W).cuda(), Y, small)
+    plan.destroy()

@@ -208,3 +208,32 @@ def test_layer_rows_subset():
     rows = np.array([3, 79, 0, 40])
     full = oracle.gcn_layer(g.rowptr, g.colind, g.vals, X, W)
     np.testing.assert_allclose(oracle.gcn_layer_rows(rows, g.rowptr, g.colind, g.vals, X, W), full[rows], atol=1e-13)
+
+
+def test_aggregate_update_pins():
+    """Y = ReLU((A X) W) against scipy/numpy dense algebra, its reductions and the other association."""
+    n, din, dout = 70, 11, 6
+    g = gcn_normalise(chung_lu_graph(n, 420, 2.1, seed=24))
+    X, W = dense_normal(n, din, 25), dense_normal(din, dout, 26)
+    A = sp.csr_matrix((g.vals.astype(np.float64), g.colind, g.rowptr), shape=(n, n)).toarray()
+    dense = np.maximum((A @ X.astype(np.float64)) @ W.astype(np.float64), 0.0)
+    Y = oracle.aggregate_update(g.rowptr, g.colind, g.vals, X, W)
+    np.testing.assert_allclose(Y, dense, atol=1e-12)
+    # same value as the update-then-aggregate oracle up to rounding order
+    np.testing.assert_allclose(Y, oracle.gcn_layer(g.rowptr, g.colind, g.vals, X, W), atol=1e-12)
+    # W = I: ReLU(A X) exactly; no activation: signs survive
+    np.testing.assert_array_equal(oracle.aggregate_update(g.rowptr, g.colind, g.vals, X, np.eye(din, dtype=np.float32)),
+                                  np.maximum(oracle.spmm(g.rowptr, g.colind, g.vals, X), 0.0))
+    raw = oracle.aggregate_update(g.rowptr, g.colind, g.vals, X, W, relu=False)
+    np.testing.assert_allclose(raw, (A @ X.astype(np.float64)) @ W.astype(np.float64), atol=1e-12)
+    assert raw.min() < 0
+    # a transposed W or a swapped operand order cannot pass: W is not square
+    assert Y.shape == (n, dout)
+    rows = np.array([5, 69, 0, 33])
+    np.testing.assert_allclose(oracle.aggregate_update_rows(rows, g.rowptr, g.colind, g.vals, X, W), Y[rows], atol=1e-13)
+    # 16-bit X is widened exactly before the sums
+    Xb = to_bf16_bits(X)
+    Yb = oracle.aggregate_update(g.rowptr, g.colind, g.vals, Xb, W, x_dtype=oracle.DT_BF16)
+    from workloads import bf16_bits_to_f32
+    np.testing.assert_allclose(Yb, np.maximum((A @ bf16_bits_to_f32(Xb).astype(np.float64)) @ W.astype(np.float64), 0.0),
+                               atol=1e-12)
