@@ -74,6 +74,10 @@ def main():
     ap.add_argument("--layer", action="store_true",
                     help="C5 only: time the whole GCN layer Y = ReLU(A (X W)) (GEMM + hybrid SpMM) instead of the SpMM")
     ap.add_argument("--sel-coef", default=None, help="three comma-separated integers overriding the shipped selector")
+    ap.add_argument("--scramble", action="store_true",
+                    help="relabel the vertices at random first (a layout with no locality)")
+    ap.add_argument("--loa", type=int, default=None, metavar="VW",
+                    help="reformat the layout first (Section V-B) with a vertices window of VW")
     ap.add_argument("--calib", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -91,6 +95,21 @@ def main():
     name = args.workload
     t0 = time.time()
     g, X, Wm = make_config(name, with_dense=(name != "C5" or args.layer))
+    layout = None
+    if args.scramble or args.loa is not None:
+        from workloads import random_relabel, CSRGraph
+        layout = {"scrambled": bool(args.scramble), "loa_vw": args.loa}
+        if args.scramble:
+            g = random_relabel(g, seed=777)
+        if args.loa is not None:
+            t1 = time.perf_counter()
+            order = hc.hcspmm_loa_order(g.n_rows, g.n_cols, g.rowptr, g.colind, args.loa)
+            layout["loa_order_ms"] = round((time.perf_counter() - t1) * 1e3, 1)
+            t1 = time.perf_counter()
+            rp2, ci2, va2 = hc.hcspmm_permute_csr(g.n_rows, g.rowptr, g.colind, g.vals, order)
+            layout["permute_ms"] = round((time.perf_counter() - t1) * 1e3, 1)
+            g = CSRGraph(g.n_rows, g.n_cols, rp2, ci2, va2)
+        log("layout: %s" % layout)
     X_in = X
     if name == "C5":                      # SpMM stage of the layer: T = X W has the layer's output width
         X = dense_normal(g.n_rows, CONFIGS["C5"]["d"], seed=1)
@@ -172,6 +191,10 @@ def main():
                            nnz_on_matrix_path=nnz_mfma, sel_coef=info["sel_coef"]),
                roofline=roofline, prepare_ms=round(prepare_ms, 3),
                stage_ms={k: round(v, 5) for k, v in stage_ms.items()})
+
+    if layout is not None:
+        layout["computing_intensity"] = round(g.nnz / max(1, info["total_ncols"]), 4)      # Eq. 5 over all windows
+        out["layout"] = layout
 
     Y_hybrid = Yd.cpu().numpy()                      # output of the timed SpMM, checked against the oracle below
 

@@ -52,10 +52,17 @@ typedef enum {
 
 typedef enum { HCSPMM_F32 = 0, HCSPMM_BF16 = 1, HCSPMM_F16 = 2 } hcspmm_dtype;
 
-/* How windows are routed.  HYBRID evaluates the selector per window; the two
- * ALL_* modes force one path for every non-empty window (used to measure the
- * selector against the pure paths).  Empty windows always take the scalar path. */
-typedef enum { HCSPMM_ROUTE_HYBRID = 0, HCSPMM_ROUTE_ALL_CSR = 1, HCSPMM_ROUTE_ALL_MFMA = 2 } hcspmm_route_mode;
+/* How windows are routed.  PER_WINDOW is the selector of Section IV-C as it stands: one decision
+ * per window, nothing else.  HYBRID (the default) takes the same decisions and then applies a
+ * launch guard, because here the two paths are separate kernel launches: when both paths got
+ * work and the smaller side holds fewer than 2^18 non-zeros and less than 1/8 of all non-zeros,
+ * its windows join the other path (the scalar side is checked for the matrix side's windows
+ * first) -- a launch that cannot repay its fixed cost is not made.  The two ALL_* modes force one
+ * path for every non-empty window (used to measure the selector against the pure paths).
+ * Empty windows always take the scalar path. */
+typedef enum {
+    HCSPMM_ROUTE_HYBRID = 0, HCSPMM_ROUTE_ALL_CSR = 1, HCSPMM_ROUTE_ALL_MFMA = 2, HCSPMM_ROUTE_PER_WINDOW = 3
+} hcspmm_route_mode;
 
 /*
  * Options of hcspmm_prepare.  Fill with hcspmm_default_options() first.
@@ -225,6 +232,34 @@ size_t hcspmm_aggregate_update_workspace_bytes(const hcspmm_plan* plan, int32_t 
 /* Dense update alone, T = X W in fp32 MFMA (Eq. 2): d_X M x K, d_W K x N, d_T M x N, all fp32 device. */
 hcspmm_status hcspmm_gemm_f32(int64_t m, int32_t k, int32_t n, const float* d_X, int64_t ldx,
                               const float* d_W, int64_t ldw, float* d_T, int64_t ldt, void* stream);
+
+/*
+ * Layout reformatting (Section V-B, Alg. 5/6, Eq. 5/6): an offline, host-side regrouping of the
+ * vertices into row windows of higher computing intensity (#non-zeros / #non-zero columns), so
+ * that more windows suit the matrix path.  Vertices are sorted by their smallest neighbour index;
+ * each window is seeded with the first unplaced vertex of that list and grown window_rows - 1
+ * times by the unplaced vertex, among the sorted positions seed .. seed + vw, that maximises the
+ * window's intensity (ties: more neighbours, then the earlier position; intensities compared as
+ * exact rationals).  If those positions hold no unplaced vertex the next unplaced vertex of the
+ * list is taken.
+ *
+ *   h_rowptr, h_colind   host, CSR structure of the n_rows x n_cols matrix (rows need not be sorted)
+ *   vw                   size of the vertices window (>= 0);  window_rows: 16 for hcspmm_prepare
+ *   h_order              host, n_rows entries, out: h_order[i] = old id of the vertex placed i-th
+ * Runs on the calling thread; touches no GPU.  HCSPMM_EBADCSR for an inconsistent CSR.
+ */
+hcspmm_status hcspmm_loa_order(int32_t n_rows, int32_t n_cols, const int32_t* h_rowptr, const int32_t* h_colind,
+                               int32_t vw, int32_t window_rows, int32_t* h_order /* host, out */);
+
+/*
+ * Applies a vertex order to a square CSR matrix on the host ("reorder G", Alg. 5): row and column
+ * h_order[i] of the input become row and column i of the output, columns ascending within a row.
+ * With P the permutation matrix of the order, the output is P A P^T, so Y' = A' X' holds for
+ * X' = P X and Y' = P Y.  Output arrays are caller-allocated with the input's sizes.
+ */
+hcspmm_status hcspmm_permute_csr(int32_t n, const int32_t* h_rowptr, const int32_t* h_colind, const float* h_vals,
+                                 const int32_t* h_order, int32_t* h_out_rowptr, int32_t* h_out_colind,
+                                 float* h_out_vals);
 
 /* Frees everything the plan owns (not the borrowed CSR).  NULL is allowed. */
 void hcspmm_plan_destroy(hcspmm_plan* plan);

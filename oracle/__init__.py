@@ -22,6 +22,7 @@ from .plan import (  # noqa: F401
     sparsity,
     computing_intensity,
     select_route,
+    launch_guard,
     derive_plan,
     derive_plan_vectorised,
     derive_window,

@@ -19,6 +19,11 @@ Steps, in the paper's order (Section IV-A "Combination Strategy", Section IV-C
        route = 1 (matrix path)  iff  z < 0 ;  an empty window gets route 0.
    The coefficients are inputs to this module (the paper does not print its
    own, they are fitted per GPU and precision).
+4b. launch guard (a choice of this implementation, not of the paper, whose single kernel
+   has no per-path launch cost): in hybrid mode, when both paths got work and the smaller
+   side holds fewer than 2^18 non-zeros and less than 1/8 of all non-zeros, all its windows
+   take the other path -- checked for the matrix side first, then for the scalar side.
+   Mode ROUTE_PER_WINDOW skips this step.
 5. the ascending lists of window ids per route.
 
 All arithmetic is Python / numpy integer arithmetic.
@@ -30,7 +35,8 @@ from typing import Dict, Sequence
 
 import numpy as np
 
-ROUTE_HYBRID, ROUTE_ALL_CSR, ROUTE_ALL_MFMA = 0, 1, 2
+ROUTE_HYBRID, ROUTE_ALL_CSR, ROUTE_ALL_MFMA, ROUTE_PER_WINDOW = 0, 1, 2, 3
+GUARD_NNZ, GUARD_SHARE = 1 << 18, 8
 
 
 def window_features(cols_in_window: np.ndarray):
@@ -61,6 +67,20 @@ def select_route(ncols: int, nnzw: int, coef: Sequence[int], H: int = 16, mode: 
     c0, c1, c2 = (int(c) for c in coef[:3])
     z = c0 * H * ncols * ncols + c1 * (H * ncols - nnzw) + c2 * H * ncols
     return 1 if z < 0 else 0
+
+
+def launch_guard(route: np.ndarray, ncols: np.ndarray, nnzw: np.ndarray) -> np.ndarray:
+    """Step 4b: returns the routes after the launch guard (integer arithmetic only)."""
+    route = np.asarray(route).astype(np.uint8).copy()
+    total = int(np.asarray(nnzw, dtype=np.int64).sum())
+    on_matrix = int(np.asarray(nnzw, dtype=np.int64)[route == 1].sum())
+    on_scalar = total - on_matrix
+    if on_matrix > 0 and on_scalar > 0:
+        if on_matrix < GUARD_NNZ and GUARD_SHARE * on_matrix < total:
+            route[:] = 0
+        elif on_scalar < GUARD_NNZ and GUARD_SHARE * on_scalar < total:
+            route = (np.asarray(ncols) > 0).astype(np.uint8)
+    return route
 
 
 def derive_window(w: int, rowptr: np.ndarray, colind: np.ndarray, H: int = 16):
@@ -96,6 +116,8 @@ def derive_plan(rowptr: np.ndarray, colind: np.ndarray, coef: Sequence[int], H: 
         wptr[w + 1] = wptr[w] + wc.shape[0]
         wcols_parts.append(wc)
         route[w] = select_route(wc.shape[0], cnt, coef, H, mode)
+    if mode == ROUTE_HYBRID:
+        route = launch_guard(route, ncols, nnzw)
     wcols = np.concatenate(wcols_parts).astype(np.int32) if wcols_parts else np.zeros(0, dtype=np.int32)
     ids = np.arange(W, dtype=np.int32)
     return dict(H=H, W=W, ncols=ncols, nnzw=nnzw, route=route, wptr=wptr, wcols=wcols, ecol=ecol,
@@ -132,6 +154,8 @@ def derive_plan_vectorised(rowptr: np.ndarray, colind: np.ndarray, coef: Sequenc
         assert (abs(c1) + abs(c2)) * H * int(max(ncols.max(initial=0), nnzw.max(initial=0))) < 2 ** 62
         z = c0 * H * ncols * ncols + c1 * (H * ncols - nnzw) + c2 * H * ncols
         route = ((z < 0) & (ncols > 0)).astype(np.uint8)
+        if mode == ROUTE_HYBRID:
+            route = launch_guard(route, ncols, nnzw)
     ids = np.arange(W, dtype=np.int32)
     return dict(H=H, W=W, ncols=ncols.astype(np.int32), nnzw=nnzw.astype(np.int32), route=route, wptr=wptr,
                 wcols=wcols.astype(np.int32), ecol=ecol.astype(np.int32),

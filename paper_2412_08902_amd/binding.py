@@ -15,13 +15,13 @@ from ._build import LIB_PATH, build_library
 
 HCSPMM_OK, HCSPMM_EINVAL, HCSPMM_EBADCSR, HCSPMM_EALLOC, HCSPMM_EHIP, HCSPMM_EUNSUPPORTED = range(6)
 HCSPMM_F32, HCSPMM_BF16, HCSPMM_F16 = 0, 1, 2
-HCSPMM_ROUTE_HYBRID, HCSPMM_ROUTE_ALL_CSR, HCSPMM_ROUTE_ALL_MFMA = 0, 1, 2
+HCSPMM_ROUTE_HYBRID, HCSPMM_ROUTE_ALL_CSR, HCSPMM_ROUTE_ALL_MFMA, HCSPMM_ROUTE_PER_WINDOW = 0, 1, 2, 3
 
 EXPORTED_SYMBOLS = [
     "hcspmm_default_options", "hcspmm_default_selector", "hcspmm_prepare", "hcspmm_plan_info",
     "hcspmm_plan_export", "hcspmm_spmm", "hcspmm_spmm_timed", "hcspmm_gcn_layer", "hcspmm_gcn_workspace_bytes",
     "hcspmm_aggregate_update", "hcspmm_aggregate_update_workspace_bytes",
-    "hcspmm_gemm_f32", "hcspmm_plan_destroy", "hcspmm_status_string", "hcspmm_last_error", "hcspmm_version",
+    "hcspmm_gemm_f32", "hcspmm_loa_order", "hcspmm_permute_csr", "hcspmm_plan_destroy", "hcspmm_status_string", "hcspmm_last_error", "hcspmm_version",
 ]
 
 
@@ -91,6 +91,10 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.hcspmm_aggregate_update.restype = ctypes.c_int
     lib.hcspmm_aggregate_update_workspace_bytes.argtypes = [vp, i32, i32]
     lib.hcspmm_aggregate_update_workspace_bytes.restype = ctypes.c_size_t
+    lib.hcspmm_loa_order.argtypes = [i32, i32, vp, vp, i32, i32, vp]
+    lib.hcspmm_loa_order.restype = ctypes.c_int
+    lib.hcspmm_permute_csr.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.hcspmm_permute_csr.restype = ctypes.c_int
     lib.hcspmm_gemm_f32.argtypes = [i64, i32, i32, vp, i64, vp, i64, vp, i64, vp]
     lib.hcspmm_gemm_f32.restype = ctypes.c_int
     lib.hcspmm_plan_destroy.argtypes = [vp]
@@ -271,6 +275,37 @@ def hcspmm_gemm_f32(X, W, T, *, stream=None):
     _check(load_library().hcspmm_gemm_f32(X.shape[0], X.shape[1], W.shape[1], _ptr(X), X.stride(0), _ptr(W),
                                           W.stride(0), _ptr(T), T.stride(0), _stream_ptr(stream)))
     return T
+
+
+def _host_ptr(a):
+    return ctypes.c_void_p(a.ctypes.data) if a.size else None
+
+
+def hcspmm_loa_order(n_rows: int, n_cols: int, rowptr, colind, vw: int, window_rows: int = 16):
+    """Layout reformatting on the host; rowptr/colind are int32 numpy arrays.  Returns the order (int32 numpy)."""
+    import numpy as np
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int32)
+    colind = np.ascontiguousarray(colind, dtype=np.int32)
+    assert rowptr.shape[0] == n_rows + 1
+    order = np.empty(n_rows, dtype=np.int32)
+    _check(load_library().hcspmm_loa_order(n_rows, n_cols, _host_ptr(rowptr), _host_ptr(colind), vw, window_rows,
+                                           _host_ptr(order)))
+    return order
+
+
+def hcspmm_permute_csr(n: int, rowptr, colind, vals, order):
+    """P A P^T on the host for the vertex order ``order``; returns (rowptr, colind, vals) numpy arrays."""
+    import numpy as np
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int32)
+    colind = np.ascontiguousarray(colind, dtype=np.int32)
+    vals = np.ascontiguousarray(vals, dtype=np.float32)
+    order = np.ascontiguousarray(order, dtype=np.int32)
+    assert rowptr.shape[0] == n + 1 and order.shape[0] == n
+    out_rp, out_ci, out_va = np.empty_like(rowptr), np.empty_like(colind), np.empty_like(vals)
+    _check(load_library().hcspmm_permute_csr(n, _host_ptr(rowptr), _host_ptr(colind), _host_ptr(vals),
+                                             _host_ptr(order), _host_ptr(out_rp), _host_ptr(out_ci),
+                                             _host_ptr(out_va)))
+    return out_rp, out_ci, out_va
 
 
 def hcspmm_version() -> int:

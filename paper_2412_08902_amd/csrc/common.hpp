@@ -10,6 +10,10 @@
 namespace hcspmm {
 
 constexpr int kH = 16;                 // rows per window (Section IV-A: the minimum hybrid unit)
+// launch guard of the hybrid routing: a path with fewer non-zeros than kGuardNnz and less than
+// 1/kGuardShare of the matrix gives its windows to the other path
+constexpr int64_t kGuardNnz = 1 << 18;
+constexpr int64_t kGuardShare = 8;
 
 // ---- preprocessing -----------------------------------------------------------------------------
 constexpr int kUniqueSmallCap = 4096;  // windows with at most this many non-zeros are condensed by an LDS sort

@@ -190,9 +190,26 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     HC_ALLOC(tmp, f_midw, (size_t)W + 1);
     HC_ALLOC(tmp, f_big, (size_t)W + 1);
     HC_ALLOC(tmp, nnz_if, (size_t)W + 1);
-    if (W > 0)
+    if (W > 0) {
         HC_TRY(launch_select(W, p->ncols, p->nnzw, p->coef[0], p->coef[1], p->coef[2], p->opt.route_mode, p->route,
                              f_mfma, f_csr, f_small, f_midw, f_big, nnz_if, stream));
+        if (p->opt.route_mode == HCSPMM_ROUTE_HYBRID) {
+            // launch guard: a path whose share cannot repay a kernel launch of its own joins the other path
+            int64_t on_matrix = 0;
+            HC_TRY(exclusive_scan_i32_i64(nnz_if, W, pos_a, scan_tmp, stream));
+            HC_TRY(hipMemcpyAsync(&on_matrix, pos_a + W, sizeof(int64_t), hipMemcpyDeviceToHost, stream));
+            HC_TRY(hipStreamSynchronize(stream));
+            const int64_t on_scalar = p->nnz - on_matrix;
+            int32_t forced = -1;
+            if (on_matrix > 0 && on_scalar > 0) {
+                if (on_matrix < kGuardNnz && kGuardShare * on_matrix < p->nnz) forced = HCSPMM_ROUTE_ALL_CSR;
+                else if (on_scalar < kGuardNnz && kGuardShare * on_scalar < p->nnz) forced = HCSPMM_ROUTE_ALL_MFMA;
+            }
+            if (forced >= 0)
+                HC_TRY(launch_select(W, p->ncols, p->nnzw, p->coef[0], p->coef[1], p->coef[2], forced, p->route,
+                                     f_mfma, f_csr, f_small, f_midw, f_big, nnz_if, stream));
+        }
+    }
     HC_TRY(exclusive_scan_i32_i64(f_mfma, W, pos_a, scan_tmp, stream));
     HC_TRY(hipMemcpyAsync(totals_dev + 0, pos_a + W, 8, hipMemcpyDeviceToDevice, stream));
     HC_TRY(exclusive_scan_i32_i64(f_csr, W, pos_b, scan_tmp, stream));
@@ -444,7 +461,7 @@ hcspmm_status hcspmm_prepare(int32_t n_rows, int32_t n_cols, int64_t nnz, const 
         o = *opt;
     }
     if (o.window_rows != kH) { set_error("only window_rows = 16 is implemented"); return HCSPMM_EUNSUPPORTED; }
-    if (o.route_mode < 0 || o.route_mode > 2) { set_error("bad route_mode"); return HCSPMM_EINVAL; }
+    if (o.route_mode < 0 || o.route_mode > 3) { set_error("bad route_mode"); return HCSPMM_EINVAL; }
     if (o.mfma_dtype < 0 || o.mfma_dtype > 2) { set_error("bad mfma_dtype"); return HCSPMM_EINVAL; }
     if (o.d_hint < 0) { set_error("bad d_hint"); return HCSPMM_EINVAL; }
     hcspmm_plan* p = new (std::nothrow) hcspmm_plan();

@@ -389,7 +389,7 @@ __global__ __launch_bounds__(256) void k_select(int32_t W, const int32_t* __rest
     int r = 0;
     if (nc > 0) {
         if (mode == HCSPMM_ROUTE_ALL_MFMA) r = 1;
-        else if (mode == HCSPMM_ROUTE_HYBRID) {
+        else if (mode == HCSPMM_ROUTE_HYBRID || mode == HCSPMM_ROUTE_PER_WINDOW) {
             // |c*| < 2^40 and H*ncols^2 < 2^58: 128-bit integers keep the sign exact
             const __int128 hn = (__int128)kH * nc;
             const __int128 z = (__int128)c0 * hn * nc + (__int128)c1 * (hn - nz) + (__int128)c2 * hn;

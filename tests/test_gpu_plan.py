@@ -37,7 +37,7 @@ def check_plan(g, mode=0, sel_coef=None, d_hint=64):
     return got, info
 
 
-@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("mode", [0, 1, 2, 3])
 @pytest.mark.parametrize("case", [(83, 70, 0.12, True, False), (200, 5000, 0.01, False, True),
                                   (16, 16, 1.0, True, False), (15, 90, 0.0, True, False),
                                   (1000, 300, 0.3, True, False)])
@@ -74,8 +74,29 @@ def test_selector_routes_change_with_coefficients():
     g = sbm_graph(32, 64, 0.25, 4.0, seed=8)
     a, _ = check_plan(g, sel_coef=[0, 0, 1])        # z = 1 > 0 everywhere: scalar path
     b, _ = check_plan(g, sel_coef=[0, 0, -1])       # z < 0 everywhere: matrix path
-    c, _ = check_plan(g, sel_coef=[1, 0, -125])     # ncols < 125
+    c, _ = check_plan(g, mode=3, sel_coef=[1, 0, -125])     # ncols < 125, decision per window as it stands
     assert a["route"].sum() == 0 and b["route"].all() and 0 < c["route"].sum() < c["W"]
+    check_plan(g, mode=0, sel_coef=[1, 0, -125])            # with the launch guard on top
+
+
+def test_launch_guard_merges_a_small_side():
+    """Hybrid mode: a handful of dense windows in a sparse matrix do not get a launch of their own,
+    and a handful of sparse windows in a dense matrix do not either; per-window mode keeps them."""
+    dense = sbm_graph(2, 64, 1.0, 0.0, seed=5)              # 8 windows of 64 shared columns
+    sparse = tiny_random_csr(128 * 400, 128, 0.02, seed=6)
+    rows = np.concatenate([np.diff(dense.rowptr), np.diff(sparse.rowptr)])
+    rp = np.zeros(rows.shape[0] + 1, np.int32)
+    np.cumsum(rows, out=rp[1:])
+    g = CSRGraph(rows.shape[0], 128, rp, np.concatenate([dense.colind, sparse.colind]).astype(np.int32),
+                 np.concatenate([dense.vals, sparse.vals]).astype(np.float32))
+    coef = [0, 1 << 20, -(1 << 19)]                         # matrix path iff sparsity < 1/2
+    per, _ = check_plan(g, mode=3, sel_coef=coef)
+    hyb, _ = check_plan(g, mode=0, sel_coef=coef)
+    assert per["route"][:8].all() and per["route"].sum() == 8 and hyb["route"].sum() == 0
+    coef = [0, -(1 << 20), 1 << 19]                         # matrix path iff sparsity > 1/2
+    per, _ = check_plan(g, mode=3, sel_coef=coef)
+    hyb, _ = check_plan(g, mode=0, sel_coef=coef)
+    assert not per["route"][:8].any() and per["route"][8:].all() and hyb["route"].all()
 
 
 def test_errors_are_status_codes():

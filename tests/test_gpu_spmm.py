@@ -9,7 +9,7 @@ from gpu_util import gpu_spmm, assert_close, oracle_pair, device_graph
 
 pytestmark = pytest.mark.gpu
 
-HYBRID, ALL_CSR, ALL_MFMA = 0, 1, 2
+HYBRID, ALL_CSR, ALL_MFMA, PER_WINDOW = 0, 1, 2, 3
 MODES = [HYBRID, ALL_CSR, ALL_MFMA]
 TOL_F32 = 1e-5          # max error relative to |A||X|, fp32 path
 
@@ -124,7 +124,10 @@ def test_custom_selector_mixes_both_paths():
     g = sbm_graph(24, 64, 0.25, 4.0, seed=2)
     X = dense_normal(g.n_cols, 64, seed=4)
     # z = ncols + 0*sparsity - 120 < 0  <=>  ncols < 120: some windows on each path
-    Y, info = gpu_spmm(g, X, HYBRID, sel_coef=[1, 0, -120])
+    Y, info = gpu_spmm(g, X, PER_WINDOW, sel_coef=[1, 0, -120])
     assert info["n_mfma_windows"] > 0 and info["n_csr_windows"] > 0
     ref, bound = oracle_pair(g, X)
+    assert_close(Y, ref, bound, TOL_F32)
+    # the hybrid mode may merge a small side into the other path; the values stay the same product
+    Y, info = gpu_spmm(g, X, HYBRID, sel_coef=[1, 0, -120])
     assert_close(Y, ref, bound, TOL_F32)

@@ -1,0 +1,75 @@
+"""Layout reformatting in the library (host code, Alg. 6 / Eq. 6) against the oracle (Alg. 5 / Eq. 5):
+index work, so the vertex orders must be identical."""
+import numpy as np
+import pytest
+
+from oracle import loa as oracle_loa
+from workloads import chung_lu_graph, sbm_graph, random_relabel, tiny_random_csr
+from test_oracle_loa import read_examples, csr_of
+
+
+def lib_order(rowptr, colind, n_cols, vw, window_rows=16):
+    import paper_2412_08902_amd.binding as hc
+    return hc.hcspmm_loa_order(len(rowptr) - 1, n_cols, rowptr, colind, vw, window_rows)
+
+
+@pytest.mark.parametrize("ex", read_examples(), ids=lambda e: e["name"])
+def test_worked_examples(ex):
+    rowptr, colind = csr_of(ex["rows"])
+    got = lib_order(rowptr, colind, int(colind.max()) + 1, ex["vw"], ex["window_rows"])
+    assert got.tolist() == ex["order"]
+
+
+@pytest.mark.parametrize("seed,n,edges,vw,h", [(1, 200, 1500, 16, 16), (2, 333, 4000, 64, 16), (3, 100, 300, 5, 4),
+                                               (4, 257, 2000, 0, 16), (5, 180, 2500, 1000, 16), (6, 64, 900, 7, 3)])
+def test_power_law_graphs_match_oracle(seed, n, edges, vw, h):
+    g = chung_lu_graph(n, edges, 2.1, seed=seed)
+    want = oracle_loa.loa_order(g.rowptr, g.colind, vw, window_rows=h)
+    got = lib_order(g.rowptr, g.colind, g.n_cols, vw, h)
+    np.testing.assert_array_equal(got, want)
+
+
+@pytest.mark.parametrize("seed", [11, 12])
+def test_scrambled_communities_match_oracle(seed):
+    g = random_relabel(sbm_graph(10, 32, 0.4, 2.0, seed=seed), seed=seed + 1)
+    for vw in (8, 48, g.n_rows):
+        np.testing.assert_array_equal(lib_order(g.rowptr, g.colind, g.n_cols, vw),
+                                      oracle_loa.loa_order(g.rowptr, g.colind, vw))
+
+
+def test_unsorted_duplicate_empty_and_rectangular_rows():
+    g = tiny_random_csr(90, 140, 0.05, seed=21, sorted_rows=False, duplicates=True)
+    assert (np.diff(g.rowptr) == 0).any()
+    np.testing.assert_array_equal(lib_order(g.rowptr, g.colind, g.n_cols, 20),
+                                  oracle_loa.loa_order(g.rowptr, g.colind, 20))
+    empty = tiny_random_csr(40, 40, 0.0, seed=1)
+    assert lib_order(empty.rowptr, empty.colind, 40, 8).tolist() == list(range(40))
+    assert lib_order(np.zeros(1, dtype=np.int32), np.empty(0, dtype=np.int32), 0, 4).tolist() == []
+
+
+def test_permute_csr_matches_oracle_and_rejects_bad_orders():
+    import paper_2412_08902_amd.binding as hc
+    g = chung_lu_graph(120, 800, 2.1, seed=31)
+    order = lib_order(g.rowptr, g.colind, g.n_cols, 32)
+    rp, ci, va = hc.hcspmm_permute_csr(g.n_rows, g.rowptr, g.colind, g.vals, order)
+    wrp, wci, wva = oracle_loa.permute_graph(g.rowptr, g.colind, g.vals, order)
+    np.testing.assert_array_equal(rp, wrp)
+    np.testing.assert_array_equal(ci, wci)
+    np.testing.assert_array_equal(va, wva)
+    bad = order.copy()
+    bad[0] = bad[1]
+    with pytest.raises(hc.HcspmmError):
+        hc.hcspmm_permute_csr(g.n_rows, g.rowptr, g.colind, g.vals, bad)
+
+
+def test_bad_arguments():
+    import paper_2412_08902_amd.binding as hc
+    g = chung_lu_graph(50, 200, 2.1, seed=41)
+    with pytest.raises(hc.HcspmmError):
+        lib_order(g.rowptr, g.colind, g.n_cols, -1)
+    with pytest.raises(hc.HcspmmError):
+        lib_order(g.rowptr, g.colind, 10, 4)                 # column indices beyond n_cols
+    rp = g.rowptr.copy()
+    rp[5] = rp[6] + 1
+    with pytest.raises(hc.HcspmmError):
+        lib_order(rp, g.colind, g.n_cols, 4)

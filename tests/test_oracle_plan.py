@@ -139,3 +139,36 @@ def test_eq6_equals_eq5_on_the_enlarged_window():
     cols = np.concatenate([np.array(sorted(r)) for r in rw + [v]])
     ncols, nnzw = oracle.window_features(cols)
     assert oracle.computing_intensity(ncols, nnzw) == eq6
+
+
+def test_launch_guard_cases():
+    """The launch guard of the hybrid mode on hand-set routes: the smaller side moves only when it is
+    below 2^18 non-zeros AND below one eighth of the matrix; the matrix side is examined first."""
+    ncols = np.array([10, 10, 10, 0, 10], dtype=np.int32)
+    # matrix side 100 of 1000 non-zeros (< 1/8, < 2^18): joins the scalar path
+    assert oracle.launch_guard([1, 0, 0, 0, 0], ncols, [100, 300, 300, 0, 300]).tolist() == [0, 0, 0, 0, 0]
+    # matrix side 125 of 1000 = exactly 1/8: stays
+    assert oracle.launch_guard([1, 0, 0, 0, 0], ncols, [125, 300, 300, 0, 275]).tolist() == [1, 0, 0, 0, 0]
+    # scalar side small: joins the matrix path, the empty window keeps route 0
+    assert oracle.launch_guard([1, 1, 0, 0, 1], ncols, [400, 400, 50, 0, 400]).tolist() == [1, 1, 1, 0, 1]
+    # a side of 2^18 non-zeros or more is never moved, however small its share
+    big = 1 << 18
+    assert oracle.launch_guard([1, 0, 0, 0, 0], ncols, [big, 40 * big, 0, 0, 0]).tolist() == [1, 0, 0, 0, 0]
+    assert oracle.launch_guard([1, 0, 0, 0, 0], ncols, [big - 1, 40 * big, 0, 0, 0]).tolist() == [0, 0, 0, 0, 0]
+    # pure plans are left alone
+    assert oracle.launch_guard([0, 0, 0, 0, 0], ncols, [5, 5, 5, 0, 5]).tolist() == [0, 0, 0, 0, 0]
+    assert oracle.launch_guard([1, 1, 1, 0, 1], ncols, [5, 5, 5, 0, 5]).tolist() == [1, 1, 1, 0, 1]
+
+
+def test_guard_applies_to_hybrid_mode_only():
+    from workloads import sbm_graph
+    g = sbm_graph(6, 64, 0.5, 1.0, seed=3)
+    # a selector that sends exactly the windows with fewer than 70 columns to the matrix path
+    coef = [1 << 20, 0, -70 * (1 << 20)]
+    per_window = oracle.derive_plan(g.rowptr, g.colind, coef, mode=oracle.plan.ROUTE_PER_WINDOW)
+    hybrid = oracle.derive_plan(g.rowptr, g.colind, coef, mode=oracle.plan.ROUTE_HYBRID)
+    expect = np.array([oracle.select_route(c, z, coef) for c, z in zip(per_window["ncols"], per_window["nnzw"])])
+    np.testing.assert_array_equal(per_window["route"], expect)
+    np.testing.assert_array_equal(hybrid["route"], oracle.launch_guard(expect, per_window["ncols"], per_window["nnzw"]))
+    vec = oracle.derive_plan_vectorised(g.rowptr, g.colind, coef, mode=oracle.plan.ROUTE_HYBRID, n_cols=g.n_cols)
+    np.testing.assert_array_equal(vec["route"], hybrid["route"])
