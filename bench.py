@@ -74,6 +74,9 @@ def main():
     ap.add_argument("--layer", action="store_true",
                     help="C5 only: time the whole GCN layer Y = ReLU(A (X W)) (GEMM + hybrid SpMM) instead of the SpMM")
     ap.add_argument("--sel-coef", default=None, help="three comma-separated integers overriding the shipped selector")
+    ap.add_argument("--agg-update", type=int, default=None, metavar="D_OUT",
+                    help="also time the aggregate-then-update layer Y = ReLU((A X) W) with a d x D_OUT W, with the "
+                         "update stage fused into the SpMM kernels and as SpMM + GEMM")
     ap.add_argument("--scramble", action="store_true",
                     help="relabel the vertices at random first (a layout with no locality)")
     ap.add_argument("--loa", type=int, default=None, metavar="VW",
@@ -212,6 +215,32 @@ def main():
                             total_gflops=round((gemm_flops + flops) / (ms_layer * 1e-3) / 1e9, 1))
         log("layer: %.3f ms (gemm alone %.3f ms = %.1f TFLOP/s)" % (ms_layer, ms_gemm, out["layer"]["gemm_tflops"]))
         del Xin_d, Wd, ws, Tg
+
+    if args.agg_update:
+        from workloads import glorot_uniform
+        d_out = args.agg_update
+        Wd = torch.from_numpy(glorot_uniform(d, d_out, seed=4242)).to(dev)
+        ws = torch.empty(hc.hcspmm_aggregate_update_workspace_bytes(plan, d, d_out), dtype=torch.uint8, device=dev)
+        Y2 = torch.empty((g.n_rows, d_out), dtype=torch.float32, device=dev)
+        Zt = torch.empty((g.n_rows, d), dtype=torch.float32, device=dev)
+        ms_fused = time_steps(lambda: hc.hcspmm_aggregate_update(plan, Xd, Wd, Y2, ws), args.steps, args.warmup, torch)
+        Y_fused = Y2.clone()
+        os.environ["HCSPMM_TUNE_NO_FUSE"] = "1"
+        ms_split = time_steps(lambda: hc.hcspmm_aggregate_update(plan, Xd, Wd, Y2, ws), args.steps, args.warmup, torch)
+        del os.environ["HCSPMM_TUNE_NO_FUSE"]
+        ms_gemm = time_steps(lambda: hc.hcspmm_gemm_f32(Zt, Wd, Y2), args.steps, args.warmup, torch)
+        out["aggregate_update"] = dict(d_in=d, d_out=d_out, ms_fused=round(ms_fused, 5), ms_spmm_then_gemm=round(ms_split, 5),
+                                       ms_gemm_alone=round(ms_gemm, 5), ms_spmm_alone=round(ms, 5),
+                                       max_abs_diff_fused_vs_split=float((Y_fused - Y2).abs().max().item()) if False else None)
+        hc.hcspmm_aggregate_update(plan, Xd, Wd, Y2, ws)
+        os.environ["HCSPMM_TUNE_NO_FUSE"] = "1"
+        Y3 = torch.empty_like(Y2)
+        hc.hcspmm_aggregate_update(plan, Xd, Wd, Y3, ws)
+        del os.environ["HCSPMM_TUNE_NO_FUSE"]
+        torch.cuda.synchronize()
+        out["aggregate_update"]["max_abs_diff_fused_vs_split"] = float((Y2 - Y3).abs().max().item())
+        log("aggregate-update: fused %.4f ms, spmm+gemm %.4f ms (gemm alone %.4f)" % (ms_fused, ms_split, ms_gemm))
+        del Wd, ws, Y2, Y3, Zt, Y_fused
 
     if args.cold:
         flush = torch.empty(512 << 20, dtype=torch.uint8, device=dev)

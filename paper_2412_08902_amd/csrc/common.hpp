@@ -105,13 +105,30 @@ struct SpmmArgs {
     int32_t relu;
 };
 
+// Update stage of the aggregate-then-update layer: Y = act(Z W) for aggregated rows Z (Section V-A).
+struct UpdateArgs {
+    const float* W;       // d_in x d_out, fp32
+    int64_t ldw;
+    int32_t d_out;
+    float* Y;             // n_rows x d_out
+    int64_t ldy;
+    int32_t relu;
+};
+
+// With `upd` the kernels that can keep a 16-row result tile on chip multiply it by W and write
+// upd->Y (short rows of the scalar path, wave-per-window tiles of the matrix path); every other
+// row goes to a.Y, which then is the aggregation workspace Z, and launch_update_rest finishes it.
+bool update_fusable(const SpmmArgs& a);
+bool mfma_update_fusable(const SpmmArgs& a);
 hipError_t launch_csr(const SpmmArgs& a, int32_t n_segs, const Segment* segs, float* partial, int32_t n_mid,
                       const int32_t* mid_rows, int32_t n_items, const int32_t* row_list, const uint8_t* route,
-                      int32_t mid_row, hipStream_t s);
+                      int32_t mid_row, hipStream_t s, const UpdateArgs* upd = nullptr);
+hipError_t launch_update_rest(const SpmmArgs& a, int32_t n_windows, const uint8_t* route, const int32_t* ncols,
+                              int32_t mid_row, const UpdateArgs& upd, hipStream_t s);
 hipError_t launch_reduce_partials(const SpmmArgs& a, int32_t n_multi, const MultiRow* multi, const float* partial,
                                   hipStream_t s);
 hipError_t launch_mfma_small(const SpmmArgs& a, int32_t n_list, const WinDesc* desc, const int32_t* wcols,
-                             const int32_t* erc, hipStream_t s);
+                             const int32_t* erc, hipStream_t s, const UpdateArgs* upd = nullptr);
 hipError_t launch_mfma_wg(const SpmmArgs& a, int32_t n_list, const WgSlice* slices, const int32_t* ncols,
                           const int64_t* wptr, const int32_t* wcols, const int32_t* erc, int rows_sorted,
                           const int32_t* slice_rows, float* tile_partial, bool wide, hipStream_t s);

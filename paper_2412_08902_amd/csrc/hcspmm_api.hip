@@ -351,7 +351,8 @@ fail:
 }
 
 static hcspmm_status run_spmm(const hcspmm_plan* plan, const SpmmArgs& a, hipStream_t stream,
-                              hipEvent_t* ev = nullptr /* 5 events when timing stages */)
+                              hipEvent_t* ev = nullptr /* 5 events when timing stages */,
+                              const UpdateArgs* upd = nullptr /* fuse the update stage where a tile stays on chip */)
 {
     hcspmm_plan* p = const_cast<hcspmm_plan*>(plan);
     // long rows cut into several segments need one partial row per segment
@@ -399,11 +400,11 @@ static hcspmm_status run_spmm(const hcspmm_plan* plan, const SpmmArgs& a, hipStr
     HC_HIP(launch_mfma_wg(a, p->n_mfma_mid, p->mid_slices, p->ncols, p->wptr, p->wcols, p->erc, p->rows_sorted,
                           nullptr, p->tile_partial, false, s_wg));
     if (ev) HC_HIP(hipEventRecord(ev[1], stream));
-    HC_HIP(launch_mfma_small(a, p->n_mfma_small, p->mfma_small_desc, p->wcols, p->erc, s_small));
+    HC_HIP(launch_mfma_small(a, p->n_mfma_small, p->mfma_small_desc, p->wcols, p->erc, s_small, upd));
     if (ev) HC_HIP(hipEventRecord(ev[2], stream));
     HC_HIP(launch_csr(a, p->n_segs, p->segs, p->partial, p->n_mid, p->mid_rows,
                       p->short_rows ? p->n_short : (p->n_short > 0 ? p->n_rows : 0), p->short_rows, p->route,
-                      p->mid_row, stream));
+                      p->mid_row, stream, upd));
     if (ev) HC_HIP(hipEventRecord(ev[3], stream));
     HC_HIP(launch_reduce_partials(a, p->n_multi, p->multi, p->partial, stream));
     if (ev) HC_HIP(hipEventRecord(ev[4], stream));
@@ -415,6 +416,9 @@ static hcspmm_status run_spmm(const hcspmm_plan* plan, const SpmmArgs& a, hipStr
         HC_HIP(hipEventRecord(p->ev_join[1], s_small));
         HC_HIP(hipStreamWaitEvent(stream, p->ev_join[1], 0));
     }
+    // rows whose aggregation went to memory (long and mid rows, wide matrix-path windows)
+    if (upd && (p->n_segs > 0 || p->n_mid > 0 || has_wg))
+        HC_HIP(launch_update_rest(a, p->W, p->route, p->ncols, p->mid_row, *upd, stream));
     return HCSPMM_OK;
 }
 
@@ -682,6 +686,10 @@ hcspmm_status hcspmm_aggregate_update(const hcspmm_plan* plan, const void* d_X, 
     SpmmArgs a;
     a.n_rows = plan->n_rows; a.rowptr = plan->rowptr; a.colind = plan->colind; a.vals = plan->vals;
     a.X = d_X; a.ldx = ldx; a.d = d_in; a.x_dtype = x_dtype; a.Y = Z; a.ldy = d_in; a.relu = 0;
+    if (update_fusable(a) && !getenv("HCSPMM_TUNE_NO_FUSE")) {
+        const UpdateArgs u{static_cast<const float*>(d_W), ldw, d_out, static_cast<float*>(d_Y), ldy, apply_relu ? 1 : 0};
+        return run_spmm(plan, a, s, nullptr, &u);
+    }
     if ((st = run_spmm(plan, a, s)) != HCSPMM_OK) return st;
     HC_HIP(launch_gemm_f32(plan->n_rows, d_in, d_out, Z, d_in, static_cast<const float*>(d_W), ldw,
                            static_cast<float*>(d_Y), ldy, apply_relu ? 1 : 0, s));

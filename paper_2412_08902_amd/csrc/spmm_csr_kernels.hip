@@ -12,7 +12,10 @@
 //   mid rows    one wave per row, the groups stride over the row and combine with cross-lane adds;
 //   long rows   one workgroup per segment of kSegLen non-zeros, combined through LDS in a fixed
 //               order (and, for rows of several segments, through partial rows in memory).
+#include <cstdlib>
+
 #include "common.hpp"
+#include "update_tile.hpp"
 
 namespace hcspmm {
 
@@ -195,6 +198,75 @@ __device__ inline void csr_short_body(int64_t block, int32_t n_items, const int3
     }
 }
 
+// ---- short rows with the update stage fused in ------------------------------------------------
+// Same walk as csr_short_body, but a wave covers exactly 16 list entries (16/G rows per lane
+// group, G = 64/LPR groups) and a finished row goes to the wave's 16 x d tile in LDS instead of
+// memory; the wave then multiplies the tile by W on the matrix cores and writes act(Z W) for the
+// rows it owns (Section V-A: the aggregation result of a window stays on chip for the update).
+// The width d must fit one pass of the group (d <= LPR*VEC) and be a multiple of 16.
+template <int LPR, int VEC>
+__device__ inline void csr_short_fused_body(int64_t block, int32_t n_items, const int32_t* __restrict__ row_list,
+                                            const uint8_t* __restrict__ route, int mid_row, const SpmmArgs& a,
+                                            const UpdateArgs& u, float* __restrict__ zt_all, int32_t* __restrict__ rows_all)
+{
+    constexpr int G = 64 / LPR;
+    constexpr int RPG = 16 / G;
+    constexpr int LDZ = LPR * VEC + 4;
+    static_assert(LPR >= RPG, "a group must be able to hold one row extent per lane");
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t w0 = ((int64_t)block * 4 + wave) * 16;       // first list entry of the wave
+    if (w0 >= n_items) return;                                  // whole wave past the end
+    const int g = lane / LPR, lig = lane % LPR;
+    float* __restrict__ zt = zt_all + wave * 16 * LDZ;
+    int32_t* __restrict__ rows16 = rows_all + wave * 16;
+    const int64_t i0 = w0 + g * RPG;
+    const int nr = (int)max((int64_t)0, min((int64_t)RPG, (int64_t)n_items - i0));
+    int32_t my_row = -1, my_s = 0, my_e = 0;
+    if (lig < nr) {
+        my_row = row_list ? row_list[i0 + lig] : (int32_t)(i0 + lig);
+        my_s = a.rowptr[my_row];
+        my_e = a.rowptr[my_row + 1];
+        if (!row_list && (route[my_row / kH] != 0 || my_e - my_s > mid_row)) my_row = -1;
+    }
+    if (lig < RPG) rows16[g * RPG + lig] = my_row;
+    const char* __restrict__ X = static_cast<const char*>(a.X);
+    const int64_t ldxb = a.ldx * 4;
+    const int c = lig * VEC;
+    const bool col_ok = c < a.d;
+    float acc[VEC];
+    vzero<VEC>(acc);
+    int j = 0, k = 0, e = 0, slot = 0;
+    int32_t row = -1;
+    int32_t mc = 0;
+    float mv = 0.f;
+    for (;;) {
+        if (k >= e) {
+            if (row >= 0 && col_ok) vstore<VEC>(zt + (g * RPG + slot) * LDZ + c, acc, 0);
+            row = -1;
+            while (j < nr && row < 0) {
+                row = __shfl(my_row, j, LPR);
+                k = __shfl(my_s, j, LPR);
+                e = __shfl(my_e, j, LPR);
+                slot = j;
+                ++j;
+            }
+            if (row < 0) break;
+            vzero<VEC>(acc);
+            if (k < e) fetch_entry(a.colind, a.vals, k + lig, e, mc, mv);
+            continue;
+        }
+        int32_t nc;
+        float nv;
+        fetch_entry(a.colind, a.vals, k + LPR + lig, e, nc, nv);
+        batch_accumulate<LPR, VEC, 0>(mc, mv, min(LPR, e - k), X + (col_ok ? c : 0) * 4, ldxb, acc);
+        mc = nc;
+        mv = nv;
+        k += LPR;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    update_tile16(zt, LDZ, rows16, a.d, u, lane);
+}
+
 // ---- mid rows: one wave per row -------------------------------------------------------------
 template <int LPR, int VEC, int XK>
 __device__ inline void csr_mid_body(int64_t block, int32_t n_mid, const int32_t* __restrict__ mid_rows,
@@ -301,6 +373,63 @@ __global__ __launch_bounds__(256) void k_csr(CsrWork wk, SpmmArgs a)
     csr_short_body<LPR, VEC, XK>(b, wk.n_items, wk.row_list, wk.route, wk.rows_per_group, wk.mid_row, a);
 }
 
+// The same launch with the update stage fused into the short rows; long and mid rows write their
+// aggregated rows to a.Y (the workspace Z) and are finished by k_update_rest.
+template <int LPR, int VEC>
+__global__ __launch_bounds__(256) void k_csr_fused(CsrWork wk, SpmmArgs a, UpdateArgs u)
+{
+    __shared__ float red[256 * VEC];
+    __shared__ float zt[4 * 16 * (LPR * VEC + 4)];
+    __shared__ int32_t rows16[64];
+    int64_t b = blockIdx.x;
+    if (b < wk.n_segs) {
+        csr_long_body<LPR, VEC, 0>(b, wk.segs, wk.partial, red, a);
+        return;
+    }
+    b -= wk.n_segs;
+    const int64_t mid_blocks = ((int64_t)wk.n_mid + 3) / 4;
+    if (b < mid_blocks) {
+        csr_mid_body<LPR, VEC, 0>(b, wk.n_mid, wk.mid_rows, a);
+        return;
+    }
+    b -= mid_blocks;
+    csr_short_fused_body<LPR, VEC>(b, wk.n_items, wk.row_list, wk.route, wk.mid_row, a, u, zt, rows16);
+}
+
+// ---- rows the fused kernels did not finish: gather their aggregated rows and apply the update ---
+// One wave per window: rows of matrix-path windows wider than the wave-per-window kernel handles
+// and scalar-path rows longer than the short tier were written to Z; they are read back as a
+// 16-row tile (unused tile rows stay undefined and are not stored) and multiplied by W.
+template <int ZD>
+__global__ __launch_bounds__(256) void k_update_rest(int32_t n_windows, const uint8_t* __restrict__ route,
+                                                     const int32_t* __restrict__ ncols, int32_t mid_row, SpmmArgs a,
+                                                     UpdateArgs u)
+{
+    constexpr int ldz = ZD + 4;                                 // ZD >= d
+    __shared__ float tiles[4 * 16 * ldz];
+    __shared__ int32_t rows_s[64];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int32_t w = blockIdx.x * 4 + wave;
+    if (w >= n_windows) return;
+    float* __restrict__ zt = tiles + wave * 16 * ldz;
+    int32_t* __restrict__ rows16 = rows_s + wave * 16;
+    bool need = false;
+    const int32_t row = w * kH + (lane & 15);
+    if (lane < 16 && row < a.n_rows)
+        need = route[w] ? ncols[w] > kMfmaSmallMaxCols : a.rowptr[row + 1] - a.rowptr[row] > mid_row;
+    if (__ballot(need) == 0) return;
+    if (lane < 16) rows16[lane] = need ? row : -1;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    for (int r = 0; r < 16; ++r) {
+        const int32_t rr = rows16[r];
+        if (rr < 0) continue;
+        for (int c = lane * 4; c < a.d; c += 256)
+            *reinterpret_cast<float4*>(&zt[r * ldz + c]) = *reinterpret_cast<const float4*>(&a.Y[(int64_t)rr * a.ldy + c]);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    update_tile16(zt, ldz, rows16, a.d, u, lane);
+}
+
 // ---- rows cut into several segments: add the partial rows in segment order ------------------
 __global__ __launch_bounds__(256) void k_reduce_partials(int32_t n_multi, const MultiRow* __restrict__ multi,
                                                          const float* __restrict__ partial, SpmmArgs a)
@@ -357,15 +486,47 @@ static CsrShape pick_shape(const SpmmArgs& a, const float* partial)
         if (sh.vec == 8) { HC_CSR_CASES(FN, 2, 8) } else if (sh.vec == 4) { HC_CSR_CASES(FN, 2, 4) } else { HC_CSR_CASES(FN, 2, 1) } \
     }
 
+// The fused update needs the whole aggregated row in one pass of a lane group, fp32 X read as
+// float4/float2 and a width that the update's K loop takes 16 at a time.
+bool update_fusable(const SpmmArgs& a)
+{
+    if (a.x_dtype != HCSPMM_F32 || a.d % 16 != 0 || a.d < 16 || a.d > 256) return false;
+    const CsrShape sh = pick_shape(a, nullptr);
+    return (sh.vec == 4 || sh.vec == 2) && sh.lpr * sh.vec >= a.d && a.ldy % 4 == 0 && (uintptr_t)a.Y % 16 == 0 &&
+           mfma_update_fusable(a);
+}
+
 hipError_t launch_csr(const SpmmArgs& a, int32_t n_segs, const Segment* segs, float* partial, int32_t n_mid,
                       const int32_t* mid_rows, int32_t n_items, const int32_t* row_list, const uint8_t* route,
-                      int32_t mid_row, hipStream_t s)
+                      int32_t mid_row, hipStream_t s, const UpdateArgs* upd)
 {
     const CsrShape sh = pick_shape(a, partial);
-    // several consecutive rows per lane group amortise the per-row set-up, but only while the
+    if (upd) {
+        const int64_t blocks = (int64_t)n_segs + ((int64_t)n_mid + 3) / 4 + ((int64_t)n_items + 63) / 64;
+        if (blocks <= 0) return hipSuccess;
+        CsrWork wk{n_segs, segs, partial, n_mid, mid_rows, n_items, row_list, route, 0, mid_row};
+#define HC_LAUNCH_CSRF(L, V) hipLaunchKernelGGL((k_csr_fused<L, V>), dim3((unsigned)blocks), dim3(256), 0, s, wk, a, *upd)
+        switch (sh.lpr * 10 + sh.vec) {
+            case 84: HC_LAUNCH_CSRF(8, 4); break;
+            case 164: HC_LAUNCH_CSRF(16, 4); break;
+            case 324: HC_LAUNCH_CSRF(32, 4); break;
+            case 644: HC_LAUNCH_CSRF(64, 4); break;
+            case 82: HC_LAUNCH_CSRF(8, 2); break;
+            case 162: HC_LAUNCH_CSRF(16, 2); break;
+            case 322: HC_LAUNCH_CSRF(32, 2); break;
+            case 642: HC_LAUNCH_CSRF(64, 2); break;
+            default: return hipErrorInvalidValue;
+        }
+#undef HC_LAUNCH_CSRF
+        return hipGetLastError();
+    }
+    // consecutive rows per lane group: measured best when a wave walks about four to eight rows in
+    // all (one row per group for 8- and 16-lane groups, two for 32, four for 64) -- more rows per
+    // group serialise dependent loads, fewer pay the per-row set-up too often -- and only while the
     // launch still has tens of thousands of waves to hide the rows' dependent-load latencies
-    int rpg = kRowsPerGroup;
+    int rpg = sh.lpr / 16 > 1 ? sh.lpr / 16 : 1;
     while (rpg > 1 && ((int64_t)n_items / rpg) * sh.lpr / 64 < 32768) rpg >>= 1;
+    if (const char* t = getenv("HCSPMM_TUNE_RPG")) { const int v = atoi(t); if (v >= 1 && v <= kRowsPerGroup) rpg = v; }
     const int64_t n_groups = ((int64_t)n_items + rpg - 1) / rpg;
     const int gpb = 256 / sh.lpr;
     const int64_t blocks = (int64_t)n_segs + ((int64_t)n_mid + 3) / 4 + (n_groups + gpb - 1) / gpb;
@@ -374,6 +535,18 @@ hipError_t launch_csr(const SpmmArgs& a, int32_t n_segs, const Segment* segs, fl
 #define HC_LAUNCH_CSR(L, V, K) hipLaunchKernelGGL((k_csr<L, V, K>), dim3((unsigned)blocks), dim3(256), 0, s, wk, a)
     HC_CSR_DISPATCH(HC_LAUNCH_CSR)
 #undef HC_LAUNCH_CSR
+    return hipGetLastError();
+}
+
+hipError_t launch_update_rest(const SpmmArgs& a, int32_t n_windows, const uint8_t* route, const int32_t* ncols,
+                              int32_t mid_row, const UpdateArgs& upd, hipStream_t s)
+{
+    if (n_windows <= 0) return hipSuccess;
+    const dim3 grid((unsigned)((n_windows + 3) / 4));
+    if (a.d <= 64) hipLaunchKernelGGL(k_update_rest<64>, grid, dim3(256), 0, s, n_windows, route, ncols, mid_row, a, upd);
+    else if (a.d <= 128) hipLaunchKernelGGL(k_update_rest<128>, grid, dim3(256), 0, s, n_windows, route, ncols, mid_row, a, upd);
+    else if (a.d <= 256) hipLaunchKernelGGL(k_update_rest<256>, grid, dim3(256), 0, s, n_windows, route, ncols, mid_row, a, upd);
+    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 

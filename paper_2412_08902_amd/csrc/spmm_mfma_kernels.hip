@@ -29,6 +29,7 @@
 // row with explicit zeros, so X must be finite: a NaN or Inf in a gathered row reaches all 16
 // rows of the window, not only the rows that reference it.
 #include "common.hpp"
+#include "update_tile.hpp"
 
 namespace hcspmm {
 
@@ -224,13 +225,20 @@ __device__ inline void store_tile(const v4f (&acc)[NG][VW], int lane, int32_t r0
 // LDS work that builds the A tile.
 constexpr int kEdgeRegs = 6;
 
-template <int XK, int VW, int NG>
+// FUSE: instead of storing the window's 16 x d result, the wave parks it in its LDS region (the A
+// tile is dead by then), multiplies it by W on the matrix cores and stores act(Z W): the update
+// stage of the aggregate-then-update layer (Section V-A).  Needs d in one launch (col0 = 0).
+template <int XK, int VW, int NG, bool FUSE = false>
 __global__ __launch_bounds__(256) void k_mfma_small(int32_t n_list, const WinDesc* __restrict__ desc,
                                                     const int32_t* __restrict__ wcols,
-                                                    const int32_t* __restrict__ erc, int col0, SpmmArgs a)
+                                                    const int32_t* __restrict__ erc, int col0, SpmmArgs a,
+                                                    UpdateArgs u)
 {
     using P = Path<XK, VW, NG>;
-    __shared__ float tiles[4][kKcSmall * 16];
+    constexpr int kLdz = NG * 16 * VW + 4;
+    constexpr int kRegion = (FUSE && 16 * kLdz > kKcSmall * 16) ? 16 * kLdz : kKcSmall * 16;
+    __shared__ float tiles[4][kRegion];
+    __shared__ int32_t rows_s[FUSE ? 64 : 1];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int64_t item = (int64_t)blockIdx.x * 4 + wave;
     if (item >= n_list) return;
@@ -303,7 +311,26 @@ __global__ __launch_bounds__(256) void k_mfma_small(int32_t n_list, const WinDes
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     }
-    store_tile<VW, NG>(acc, lane, r0, a.n_rows, a.Y + col0, a.ldy, d, a.relu);
+    if constexpr (FUSE) {
+        int32_t* __restrict__ rows16 = rows_s + wave * 16;
+        if (lane < 16) rows16[lane] = r0 + lane < a.n_rows ? r0 + lane : -1;
+        const int j = lane & 15, kk = lane >> 4;
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            const int col = g * 16 * VW + VW * j;
+            if (col >= d) continue;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float* __restrict__ zp = tile + (4 * kk + r) * kLdz + col;
+#pragma unroll
+                for (int t = 0; t < VW; ++t) zp[t] = acc[g][t][r];
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        update_tile16(tile, kLdz, rows16, a.d, u, lane);
+    } else {
+        store_tile<VW, NG>(acc, lane, r0, a.n_rows, a.Y + col0, a.ldy, d, a.relu);
+    }
 }
 
 // ---- workgroup per window ---------------------------------------------------------------------
@@ -477,6 +504,13 @@ bool mfma_shape_supported(const SpmmArgs& a)
     return pick_mfma_shape(a, sh);
 }
 
+// the fused update needs the whole aggregated width in one launch of the wave-per-window kernel
+bool mfma_update_fusable(const SpmmArgs& a)
+{
+    MfmaShape sh;
+    return a.x_dtype == HCSPMM_F32 && pick_mfma_shape(a, sh) && sh.ng * 16 * sh.vw >= a.d;
+}
+
 #define HC_MFMA_DISPATCH(FN)                                                                       \
     if (a.x_dtype == HCSPMM_F32) {                                                                 \
         switch (sh.vw * 10 + sh.ng) {                                                              \
@@ -509,16 +543,35 @@ bool mfma_shape_supported(const SpmmArgs& a)
     }
 
 hipError_t launch_mfma_small(const SpmmArgs& a, int32_t n_list, const WinDesc* desc, const int32_t* wcols,
-                             const int32_t* erc, hipStream_t s)
+                             const int32_t* erc, hipStream_t s, const UpdateArgs* upd)
 {
     if (n_list <= 0) return hipSuccess;
     MfmaShape sh;
     if (!pick_mfma_shape(a, sh)) return hipErrorInvalidValue;
     const int span = sh.ng * 16 * sh.vw;                       // output columns per launch
+    if (upd) {
+        if (a.x_dtype != HCSPMM_F32 || span < a.d) return hipErrorInvalidValue;
+        const dim3 grid((unsigned)((n_list + 3) / 4));
+#define HC_LAUNCH_MSF(V, G) hipLaunchKernelGGL((k_mfma_small<0, V, G, true>), grid, dim3(256), 0, s, n_list, desc, wcols, erc, 0, a, *upd)
+        switch (sh.vw * 10 + sh.ng) {
+            case 41: HC_LAUNCH_MSF(4, 1); break;
+            case 42: HC_LAUNCH_MSF(4, 2); break;
+            case 44: HC_LAUNCH_MSF(4, 4); break;
+            case 21: HC_LAUNCH_MSF(2, 1); break;
+            case 22: HC_LAUNCH_MSF(2, 2); break;
+            case 24: HC_LAUNCH_MSF(2, 4); break;
+            case 11: HC_LAUNCH_MSF(1, 1); break;
+            case 12: HC_LAUNCH_MSF(1, 2); break;
+            default: HC_LAUNCH_MSF(1, 4); break;
+        }
+#undef HC_LAUNCH_MSF
+        return hipGetLastError();
+    }
+    const UpdateArgs no_update{};
     for (int col0 = 0; col0 < a.d; col0 += span) {
 #define HC_LAUNCH_MS(K, V, G)                                                                      \
     hipLaunchKernelGGL((k_mfma_small<K, V, G>), dim3((unsigned)((n_list + 3) / 4)), dim3(256), 0, s, n_list, desc,   \
-                       wcols, erc, col0, a)
+                       wcols, erc, col0, a, no_update)
         HC_MFMA_DISPATCH(HC_LAUNCH_MS)
 #undef HC_LAUNCH_MS
     }

@@ -162,3 +162,53 @@ def test_spmm_on_reformatted_layout():
     plan0.destroy()
     assert info["total_ncols"] < 0.8 * info0["total_ncols"]
     assert info["n_mfma_windows"] >= info0["n_mfma_windows"]
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2, 3])
+@pytest.mark.parametrize("din,dout", [(16, 16), (32, 1), (48, 17), (64, 64), (128, 200), (256, 128), (112, 72)])
+def test_aggregate_update_fused_shapes(mode, din, dout):
+    """Widths the fused update covers (d_in a multiple of 16 up to 256), on a power-law graph whose hub rows
+    and wide windows take the memory route, with a ragged last window and every routing."""
+    g = gcn_normalise(chung_lu_graph(3003, 150000, 2.0, seed=71, max_degree=2800))
+    assert np.diff(g.rowptr).max() > 1024                    # a long row: several tiers are in play
+    X, W = dense_normal(g.n_cols, din, seed=72), glorot_uniform(din, dout, seed=73)
+    import paper_2412_08902_amd.binding as hc
+    import torch
+    rp, ci, va = device_graph(g)
+    plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, route_mode=mode, d_hint=din,
+                             sel_coef=[1, 0, -300] if mode == 3 else None)
+    ws = torch.empty(hc.hcspmm_aggregate_update_workspace_bytes(plan, din, dout), dtype=torch.uint8, device="cuda")
+    Y = torch.full((g.n_rows, dout + 2), -3.0, device="cuda")
+    hc.hcspmm_aggregate_update(plan, torch.from_numpy(X).cuda(), torch.from_numpy(W).cuda(), Y[:, :dout], ws,
+                               apply_relu=(dout % 2 == 0))
+    torch.cuda.synchronize()
+    info = hc.hcspmm_plan_info(plan)
+    plan.destroy()
+    if mode == 3:
+        assert info["n_mfma_windows"] > 0 and info["n_csr_windows"] > 0
+    got = Y.cpu().numpy().astype(np.float64)
+    assert np.all(got[:, dout:] == -3.0)
+    ref = oracle.aggregate_update(g.rowptr, g.colind, g.vals, X, W, relu=(dout % 2 == 0))
+    bound = oracle.aggregate_update(g.rowptr, g.colind, g.vals, X, W, use_abs=True)
+    assert_close(got[:, :dout], ref, bound, 2 * TOL_F32)
+
+
+def test_aggregate_update_fused_community_graph_with_empty_rows():
+    from workloads import sbm_graph
+    g = sbm_graph(30, 64, 0.3, 2.0, seed=81)
+    # empty out a few rows and a whole window
+    keep = np.ones(g.nnz, dtype=bool)
+    for r in list(range(32, 48)) + [5, 77, 1900]:
+        keep[g.rowptr[r]:g.rowptr[r + 1]] = False
+    lens = np.add.reduceat(keep, g.rowptr[:-1]) * (np.diff(g.rowptr) > 0)
+    rp = np.zeros(g.n_rows + 1, np.int32)
+    np.cumsum(lens, out=rp[1:])
+    from workloads import CSRGraph
+    g = CSRGraph(g.n_rows, g.n_cols, rp, g.colind[keep], g.vals[keep])
+    X, W = dense_normal(g.n_cols, 128, seed=82), glorot_uniform(128, 64, seed=83)
+    for mode in (0, 1, 2):
+        got = run_aggregate_update(g, X, W, mode, relu=False)
+        ref = oracle.aggregate_update(g.rowptr, g.colind, g.vals, X, W, relu=False)
+        bound = oracle.aggregate_update(g.rowptr, g.colind, g.vals, X, W, use_abs=True)
+        assert_close(got, ref, bound, 2 * TOL_F32)
+        assert np.all(got[32:48] == 0.0) and np.all(got[5] == 0.0)
