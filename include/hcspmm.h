@@ -212,9 +212,12 @@ size_t hcspmm_gcn_workspace_bytes(const hcspmm_plan* plan, int32_t d_in, int32_t
 /*
  * Aggregate-then-update layer  Y = act((A X) W)  -- the association of GIN's forward pass and of
  * GCN's backward pass, for which Section V-A describes the coupled kernel (aggregate a window,
- * then multiply its result tile by W).  The aggregation Z = A X runs on the hybrid paths into the
- * workspace; the update multiplies Z by W on the fp32 matrix cores with the activation in its
- * epilogue.
+ * then multiply its result tile by W).  With fp32 X and d_in a multiple of 16 up to 256 the update
+ * is fused into the aggregation kernels: short scalar-path rows and wave-per-window matrix-path
+ * tiles stay in LDS and are multiplied by W on the fp32 matrix cores before anything is stored;
+ * the remaining rows (long rows, very wide windows) pass through the workspace.  Otherwise, and when
+ * those remaining rows are a quarter of the matrix or more, Z = A X is written to the workspace
+ * and one fp32 MFMA GEMM applies W and the activation.
  *
  *   d_X   device, n_cols x d_in, element type x_dtype (ldx >= d_in)
  *   d_W   device, d_in x d_out fp32 (ldw >= d_out);  d_Y  device, n_rows x d_out fp32 (ldy >= d_out)

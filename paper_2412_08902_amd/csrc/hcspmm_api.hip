@@ -686,7 +686,12 @@ hcspmm_status hcspmm_aggregate_update(const hcspmm_plan* plan, const void* d_X, 
     SpmmArgs a;
     a.n_rows = plan->n_rows; a.rowptr = plan->rowptr; a.colind = plan->colind; a.vals = plan->vals;
     a.X = d_X; a.ldx = ldx; a.d = d_in; a.x_dtype = x_dtype; a.Y = Z; a.ldy = d_in; a.relu = 0;
-    if (update_fusable(a) && !getenv("HCSPMM_TUNE_NO_FUSE")) {
+    // The fused update pays where most rows can keep their tile on chip; rows that go through the
+    // workspace anyway (wide matrix-path windows, mid and long rows) are finished 16 at a time, which
+    // a plain GEMM does better once they are a large share of the matrix.
+    const int64_t rest_rows = ((int64_t)plan->n_mfma_mid + plan->n_mfma_big) * kH + plan->n_mid + plan->n_long_rows;
+    const bool worth = 4 * rest_rows < plan->n_rows || getenv("HCSPMM_TUNE_FORCE_FUSE");
+    if (update_fusable(a) && worth && !getenv("HCSPMM_TUNE_NO_FUSE")) {
         const UpdateArgs u{static_cast<const float*>(d_W), ldw, d_out, static_cast<float*>(d_Y), ldy, apply_relu ? 1 : 0};
         return run_spmm(plan, a, s, nullptr, &u);
     }

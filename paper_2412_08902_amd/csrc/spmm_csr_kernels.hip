@@ -199,27 +199,34 @@ __device__ inline void csr_short_body(int64_t block, int32_t n_items, const int3
 }
 
 // ---- short rows with the update stage fused in ------------------------------------------------
-// Same walk as csr_short_body, but a wave covers exactly 16 list entries (16/G rows per lane
-// group, G = 64/LPR groups) and a finished row goes to the wave's 16 x d tile in LDS instead of
-// memory; the wave then multiplies the tile by W on the matrix cores and writes act(Z W) for the
-// rows it owns (Section V-A: the aggregation result of a window stays on chip for the update).
+// Same walk as csr_short_body, but a workgroup covers exactly 16 (or, with 8-lane groups, 32) list
+// entries and a finished row goes to a 16 x d tile in LDS instead of memory; after a barrier the
+// four waves share the tile(s), each multiplying it by an interleaved quarter (half) of W's
+// 16-column blocks on the matrix cores, and write act(Z W) for the rows the workgroup owns
+// (Section V-A: the aggregation result of a window stays on chip for the update).
 // The width d must fit one pass of the group (d <= LPR*VEC) and be a multiple of 16.
+template <int LPR, int VEC> struct FusedShape {
+    static constexpr int G = 64 / LPR;                          // lane groups per wave
+    static constexpr int RPG = LPR / 16 > 1 ? LPR / 16 : 1;     // consecutive rows per group
+    static constexpr int ROWS = 4 * G * RPG;                    // list entries per workgroup
+    static constexpr int T = ROWS / 16;                         // 16-row tiles per workgroup
+    static constexpr int LDZ = LPR * VEC + 4;
+    static_assert(ROWS % 16 == 0 && (T == 1 || T == 2), "one or two tiles per workgroup");
+};
+
 template <int LPR, int VEC>
 __device__ inline void csr_short_fused_body(int64_t block, int32_t n_items, const int32_t* __restrict__ row_list,
                                             const uint8_t* __restrict__ route, int mid_row, const SpmmArgs& a,
-                                            const UpdateArgs& u, float* __restrict__ zt_all, int32_t* __restrict__ rows_all)
+                                            const UpdateArgs& u, float* __restrict__ zt, int32_t* __restrict__ rows_s)
 {
-    constexpr int G = 64 / LPR;
-    constexpr int RPG = 16 / G;
-    constexpr int LDZ = LPR * VEC + 4;
+    using S = FusedShape<LPR, VEC>;
+    constexpr int RPG = S::RPG, LDZ = S::LDZ;
     static_assert(LPR >= RPG, "a group must be able to hold one row extent per lane");
+    const int64_t b0 = (int64_t)block * S::ROWS;                // first list entry of the workgroup
+    if (b0 >= n_items) return;                                  // whole workgroup past the end
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int64_t w0 = ((int64_t)block * 4 + wave) * 16;       // first list entry of the wave
-    if (w0 >= n_items) return;                                  // whole wave past the end
-    const int g = lane / LPR, lig = lane % LPR;
-    float* __restrict__ zt = zt_all + wave * 16 * LDZ;
-    int32_t* __restrict__ rows16 = rows_all + wave * 16;
-    const int64_t i0 = w0 + g * RPG;
+    const int gw = threadIdx.x / LPR, lig = threadIdx.x % LPR;  // group within the workgroup
+    const int64_t i0 = b0 + gw * RPG;
     const int nr = (int)max((int64_t)0, min((int64_t)RPG, (int64_t)n_items - i0));
     int32_t my_row = -1, my_s = 0, my_e = 0;
     if (lig < nr) {
@@ -228,7 +235,7 @@ __device__ inline void csr_short_fused_body(int64_t block, int32_t n_items, cons
         my_e = a.rowptr[my_row + 1];
         if (!row_list && (route[my_row / kH] != 0 || my_e - my_s > mid_row)) my_row = -1;
     }
-    if (lig < RPG) rows16[g * RPG + lig] = my_row;
+    if (lig < RPG) rows_s[gw * RPG + lig] = my_row;
     const char* __restrict__ X = static_cast<const char*>(a.X);
     const int64_t ldxb = a.ldx * 4;
     const int c = lig * VEC;
@@ -241,7 +248,7 @@ __device__ inline void csr_short_fused_body(int64_t block, int32_t n_items, cons
     float mv = 0.f;
     for (;;) {
         if (k >= e) {
-            if (row >= 0 && col_ok) vstore<VEC>(zt + (g * RPG + slot) * LDZ + c, acc, 0);
+            if (row >= 0 && col_ok) vstore<VEC>(zt + (gw * RPG + slot) * LDZ + c, acc, 0);
             row = -1;
             while (j < nr && row < 0) {
                 row = __shfl(my_row, j, LPR);
@@ -263,8 +270,10 @@ __device__ inline void csr_short_fused_body(int64_t block, int32_t n_items, cons
         mv = nv;
         k += LPR;
     }
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    update_tile16(zt, LDZ, rows16, a.d, u, lane);
+    __syncthreads();
+    constexpr int WPT = 4 / S::T;                               // waves sharing one tile
+    const int tile = wave / WPT;
+    update_tile16(zt + tile * 16 * LDZ, LDZ, rows_s + tile * 16, a.d, u, lane, wave % WPT, WPT);
 }
 
 // ---- mid rows: one wave per row -------------------------------------------------------------
@@ -378,9 +387,10 @@ __global__ __launch_bounds__(256) void k_csr(CsrWork wk, SpmmArgs a)
 template <int LPR, int VEC>
 __global__ __launch_bounds__(256) void k_csr_fused(CsrWork wk, SpmmArgs a, UpdateArgs u)
 {
+    using S = FusedShape<LPR, VEC>;
     __shared__ float red[256 * VEC];
-    __shared__ float zt[4 * 16 * (LPR * VEC + 4)];
-    __shared__ int32_t rows16[64];
+    __shared__ float zt[S::ROWS * S::LDZ];
+    __shared__ int32_t rows16[S::ROWS];
     int64_t b = blockIdx.x;
     if (b < wk.n_segs) {
         csr_long_body<LPR, VEC, 0>(b, wk.segs, wk.partial, red, a);
@@ -502,7 +512,8 @@ hipError_t launch_csr(const SpmmArgs& a, int32_t n_segs, const Segment* segs, fl
 {
     const CsrShape sh = pick_shape(a, partial);
     if (upd) {
-        const int64_t blocks = (int64_t)n_segs + ((int64_t)n_mid + 3) / 4 + ((int64_t)n_items + 63) / 64;
+        const int rows_per_wg = sh.lpr == 8 ? 32 : 16;          // FusedShape<LPR, VEC>::ROWS
+        const int64_t blocks = (int64_t)n_segs + ((int64_t)n_mid + 3) / 4 + ((int64_t)n_items + rows_per_wg - 1) / rows_per_wg;
         if (blocks <= 0) return hipSuccess;
         CsrWork wk{n_segs, segs, partial, n_mid, mid_rows, n_items, row_list, route, 0, mid_row};
 #define HC_LAUNCH_CSRF(L, V) hipLaunchKernelGGL((k_csr_fused<L, V>), dim3((unsigned)blocks), dim3(256), 0, s, wk, a, *upd)

@@ -164,11 +164,15 @@ def test_spmm_on_reformatted_layout():
     assert info["n_mfma_windows"] >= info0["n_mfma_windows"]
 
 
+@pytest.mark.parametrize("force", [False, True])
 @pytest.mark.parametrize("mode", [0, 1, 2, 3])
 @pytest.mark.parametrize("din,dout", [(16, 16), (32, 1), (48, 17), (64, 64), (128, 200), (256, 128), (112, 72)])
-def test_aggregate_update_fused_shapes(mode, din, dout):
+def test_aggregate_update_fused_shapes(mode, din, dout, force, monkeypatch):
     """Widths the fused update covers (d_in a multiple of 16 up to 256), on a power-law graph whose hub rows
-    and wide windows take the memory route, with a ragged last window and every routing."""
+    and wide windows take the memory route, with a ragged last window and every routing.  `force` keeps the
+    fused kernels on even where the library would judge the workspace rows too many to bother."""
+    if force:
+        monkeypatch.setenv("HCSPMM_TUNE_FORCE_FUSE", "1")
     g = gcn_normalise(chung_lu_graph(3003, 150000, 2.0, seed=71, max_degree=2800))
     assert np.diff(g.rowptr).max() > 1024                    # a long row: several tiers are in play
     X, W = dense_normal(g.n_cols, din, seed=72), glorot_uniform(din, dout, seed=73)
