@@ -123,8 +123,10 @@ bool mfma_update_fusable(const SpmmArgs& a);
 hipError_t launch_csr(const SpmmArgs& a, int32_t n_segs, const Segment* segs, float* partial, int32_t n_mid,
                       const int32_t* mid_rows, int32_t n_items, const int32_t* row_list, const uint8_t* route,
                       int32_t mid_row, hipStream_t s, const UpdateArgs* upd = nullptr);
-hipError_t launch_update_rest(const SpmmArgs& a, int32_t n_windows, const uint8_t* route, const int32_t* ncols,
-                              int32_t mid_row, const UpdateArgs& upd, hipStream_t s);
+hipError_t launch_update_rest(const SpmmArgs& a, int32_t n_rest, const int32_t* rest_rows, const UpdateArgs& upd,
+                              hipStream_t s);
+hipError_t launch_rest_flag(int32_t n_rows, const int32_t* rowptr, const uint8_t* route, const int32_t* ncols,
+                            int32_t mid_row, int32_t* flag, hipStream_t s);
 hipError_t launch_reduce_partials(const SpmmArgs& a, int32_t n_multi, const MultiRow* multi, const float* partial,
                                   hipStream_t s);
 hipError_t launch_mfma_small(const SpmmArgs& a, int32_t n_list, const WinDesc* desc, const int32_t* wcols,
@@ -192,6 +194,8 @@ struct hcspmm_plan {
     int32_t n_multi;
     int64_t n_slots;
     int32_t n_long_rows;
+    int32_t n_rest;                 // rows finished through the workspace by the fused update
+    int32_t* rest_rows;
     int64_t nnz_long;
     // lazily sized partial-sum buffer for long rows cut into several segments
     float* partial;

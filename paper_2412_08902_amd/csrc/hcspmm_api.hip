@@ -113,7 +113,7 @@ static void free_plan_arrays(hcspmm_plan* p)
 {
     void* owned[] = {p->ncols, p->nnzw, p->route, p->wptr, p->wcols, p->erc, p->mfma_windows, p->csr_windows,
                      p->mfma_small, p->mfma_small_desc, p->mfma_mid, p->mfma_big, p->mid_slices, p->big_slices, p->big_slice_rows, p->tile_multi,
-                     p->tile_partial, p->short_rows, p->mid_rows, p->segs, p->multi, p->partial};
+                     p->tile_partial, p->short_rows, p->mid_rows, p->segs, p->multi, p->partial, p->rest_rows};
     for (void* q : owned)
         if (q) (void)hipFree(q);
 }
@@ -338,6 +338,18 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     } else {
         p->short_rows = nullptr;
     }
+    // rows the fused update finishes through the workspace
+    {
+        int32_t* f_rest = f_multi;                               // free again after the segment tables
+        HC_TRY(launch_rest_flag(n_rows, p->rowptr, p->route, p->ncols, p->mid_row, f_rest, stream));
+        HC_TRY(exclusive_scan_i32_i64(f_rest, n_rows, pos_c, scan_tmp, stream));
+        int64_t h_rest = 0;
+        HC_TRY(hipMemcpyAsync(&h_rest, pos_c + n_rows, 8, hipMemcpyDeviceToHost, stream));
+        HC_TRY(hipStreamSynchronize(stream));
+        p->n_rest = (int32_t)h_rest;
+        HC_ALLOC(keep, p->rest_rows, p->n_rest);
+        HC_TRY(launch_compact_ids(n_rows, f_rest, pos_c, p->rest_rows, stream));
+    }
     HC_TRY(hipStreamSynchronize(stream));
     p->device_bytes = keep.bytes;
     tmp.free_all();
@@ -417,8 +429,7 @@ static hcspmm_status run_spmm(const hcspmm_plan* plan, const SpmmArgs& a, hipStr
         HC_HIP(hipStreamWaitEvent(stream, p->ev_join[1], 0));
     }
     // rows whose aggregation went to memory (long and mid rows, wide matrix-path windows)
-    if (upd && (p->n_segs > 0 || p->n_mid > 0 || has_wg))
-        HC_HIP(launch_update_rest(a, p->W, p->route, p->ncols, p->mid_row, *upd, stream));
+    if (upd) HC_HIP(launch_update_rest(a, p->n_rest, p->rest_rows, *upd, stream));
     return HCSPMM_OK;
 }
 
@@ -689,8 +700,7 @@ hcspmm_status hcspmm_aggregate_update(const hcspmm_plan* plan, const void* d_X, 
     // The fused update pays where most rows can keep their tile on chip; rows that go through the
     // workspace anyway (wide matrix-path windows, mid and long rows) are finished 16 at a time, which
     // a plain GEMM does better once they are a large share of the matrix.
-    const int64_t rest_rows = ((int64_t)plan->n_mfma_mid + plan->n_mfma_big) * kH + plan->n_mid + plan->n_long_rows;
-    const bool worth = 4 * rest_rows < plan->n_rows || getenv("HCSPMM_TUNE_FORCE_FUSE");
+    const bool worth = 4 * (int64_t)plan->n_rest < plan->n_rows || getenv("HCSPMM_TUNE_FORCE_FUSE");
     if (update_fusable(a) && worth && !getenv("HCSPMM_TUNE_NO_FUSE")) {
         const UpdateArgs u{static_cast<const float*>(d_W), ldw, d_out, static_cast<float*>(d_Y), ldy, apply_relu ? 1 : 0};
         return run_spmm(plan, a, s, nullptr, &u);

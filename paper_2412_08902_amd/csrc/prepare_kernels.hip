@@ -596,6 +596,27 @@ hipError_t launch_row_class(int32_t n_rows, const int32_t* rowptr, const uint8_t
     return hipGetLastError();
 }
 
+// rows whose aggregated values reach memory even when the update stage is fused into the SpMM
+// kernels: scalar-path rows above the short tier and all rows of matrix-path windows too wide for
+// the wave-per-window kernel
+__global__ __launch_bounds__(256) void k_rest_flag(int32_t n_rows, const int32_t* __restrict__ rowptr,
+                                                   const uint8_t* __restrict__ route, const int32_t* __restrict__ ncols,
+                                                   int32_t mid_row, int32_t* __restrict__ flag)
+{
+    int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_rows) return;
+    const int32_t w = i / kH;
+    flag[i] = route[w] ? (ncols[w] > kMfmaSmallMaxCols ? 1 : 0) : (rowptr[i + 1] - rowptr[i] > mid_row ? 1 : 0);
+}
+
+hipError_t launch_rest_flag(int32_t n_rows, const int32_t* rowptr, const uint8_t* route, const int32_t* ncols,
+                            int32_t mid_row, int32_t* flag, hipStream_t s)
+{
+    if (n_rows <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_rest_flag, dim3((n_rows + 255) / 256), dim3(256), 0, s, n_rows, rowptr, route, ncols, mid_row, flag);
+    return hipGetLastError();
+}
+
 __global__ __launch_bounds__(256) void k_build_segments(int32_t n_rows, const int32_t* __restrict__ rowptr,
                                                         const int32_t* __restrict__ n_seg,
                                                         const int64_t* __restrict__ seg_pos,

@@ -407,32 +407,26 @@ __global__ __launch_bounds__(256) void k_csr_fused(CsrWork wk, SpmmArgs a, Updat
 }
 
 // ---- rows the fused kernels did not finish: gather their aggregated rows and apply the update ---
-// One wave per window: rows of matrix-path windows wider than the wave-per-window kernel handles
-// and scalar-path rows longer than the short tier were written to Z; they are read back as a
-// 16-row tile (unused tile rows stay undefined and are not stored) and multiplied by W.
+// One wave per 16 entries of the plan's list of such rows (rows of matrix-path windows wider than
+// the wave-per-window kernel handles, scalar-path rows above the short tier): they were written to
+// Z, are read back as a 16-row tile and multiplied by W.
 template <int ZD>
-__global__ __launch_bounds__(256) void k_update_rest(int32_t n_windows, const uint8_t* __restrict__ route,
-                                                     const int32_t* __restrict__ ncols, int32_t mid_row, SpmmArgs a,
+__global__ __launch_bounds__(256) void k_update_rest(int32_t n_rest, const int32_t* __restrict__ rest_rows, SpmmArgs a,
                                                      UpdateArgs u)
 {
     constexpr int ldz = ZD + 4;                                 // ZD >= d
     __shared__ float tiles[4 * 16 * ldz];
     __shared__ int32_t rows_s[64];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int32_t w = blockIdx.x * 4 + wave;
-    if (w >= n_windows) return;
+    const int64_t i0 = ((int64_t)blockIdx.x * 4 + wave) * 16;
+    if (i0 >= n_rest) return;
     float* __restrict__ zt = tiles + wave * 16 * ldz;
     int32_t* __restrict__ rows16 = rows_s + wave * 16;
-    bool need = false;
-    const int32_t row = w * kH + (lane & 15);
-    if (lane < 16 && row < a.n_rows)
-        need = route[w] ? ncols[w] > kMfmaSmallMaxCols : a.rowptr[row + 1] - a.rowptr[row] > mid_row;
-    if (__ballot(need) == 0) return;
-    if (lane < 16) rows16[lane] = need ? row : -1;
+    if (lane < 16) rows16[lane] = i0 + lane < n_rest ? rest_rows[i0 + lane] : -1;
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     for (int r = 0; r < 16; ++r) {
         const int32_t rr = rows16[r];
-        if (rr < 0) continue;
+        if (rr < 0) continue;                                   // tile rows past the list stay undefined, never stored
         for (int c = lane * 4; c < a.d; c += 256)
             *reinterpret_cast<float4*>(&zt[r * ldz + c]) = *reinterpret_cast<const float4*>(&a.Y[(int64_t)rr * a.ldy + c]);
     }
@@ -549,14 +543,14 @@ hipError_t launch_csr(const SpmmArgs& a, int32_t n_segs, const Segment* segs, fl
     return hipGetLastError();
 }
 
-hipError_t launch_update_rest(const SpmmArgs& a, int32_t n_windows, const uint8_t* route, const int32_t* ncols,
-                              int32_t mid_row, const UpdateArgs& upd, hipStream_t s)
+hipError_t launch_update_rest(const SpmmArgs& a, int32_t n_rest, const int32_t* rest_rows, const UpdateArgs& upd,
+                              hipStream_t s)
 {
-    if (n_windows <= 0) return hipSuccess;
-    const dim3 grid((unsigned)((n_windows + 3) / 4));
-    if (a.d <= 64) hipLaunchKernelGGL(k_update_rest<64>, grid, dim3(256), 0, s, n_windows, route, ncols, mid_row, a, upd);
-    else if (a.d <= 128) hipLaunchKernelGGL(k_update_rest<128>, grid, dim3(256), 0, s, n_windows, route, ncols, mid_row, a, upd);
-    else if (a.d <= 256) hipLaunchKernelGGL(k_update_rest<256>, grid, dim3(256), 0, s, n_windows, route, ncols, mid_row, a, upd);
+    if (n_rest <= 0) return hipSuccess;
+    const dim3 grid((unsigned)((n_rest + 63) / 64));
+    if (a.d <= 64) hipLaunchKernelGGL(k_update_rest<64>, grid, dim3(256), 0, s, n_rest, rest_rows, a, upd);
+    else if (a.d <= 128) hipLaunchKernelGGL(k_update_rest<128>, grid, dim3(256), 0, s, n_rest, rest_rows, a, upd);
+    else if (a.d <= 256) hipLaunchKernelGGL(k_update_rest<256>, grid, dim3(256), 0, s, n_rest, rest_rows, a, upd);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
