@@ -30,7 +30,8 @@ constexpr int kSliceCols = 4096;       // condensed columns per workgroup; wider
 
 // ---- scalar path -------------------------------------------------------------------------------
 constexpr int kRowsPerGroup = 8;       // consecutive rows walked by one lane group (short rows)
-constexpr int kMidRow = 256;           // rows with more non-zeros than this get a whole wave
+constexpr int kMidRow = 64;            // rows with more non-zeros than this get a whole wave
+constexpr int kFusedMidRow = 256;      // with the update stage fused in, rows up to this length stay in the workgroup's tile
 constexpr int kLongRow = 1024;         // rows with more non-zeros than this are cut into workgroup-sized segments
 constexpr int kSegLen = 2048;          // non-zeros per segment of a long row
 
@@ -184,6 +185,7 @@ struct hcspmm_plan {
     int32_t rows_sorted;         // 1 when every row's column indices are non-decreasing
     int32_t slice_cols;          // condensed columns per workgroup slice of a wide window (default kSliceCols)
     int32_t mid_row, long_row;   // tier thresholds this plan was built with (defaults kMidRow, kLongRow)
+    int32_t fused_mid_row;       // short-tier limit of the fused aggregate-then-update launch (>= mid_row)
     int32_t* short_rows;     // rows of route-0 windows with at most mid_row non-zeros (NULL: walk every row)
     int32_t n_short;
     int32_t* mid_rows;       // rows of route-0 windows with mid_row < non-zeros <= long_row

@@ -341,7 +341,7 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     // rows the fused update finishes through the workspace
     {
         int32_t* f_rest = f_multi;                               // free again after the segment tables
-        HC_TRY(launch_rest_flag(n_rows, p->rowptr, p->route, p->ncols, p->mid_row, f_rest, stream));
+        HC_TRY(launch_rest_flag(n_rows, p->rowptr, p->route, p->ncols, p->fused_mid_row, f_rest, stream));
         HC_TRY(exclusive_scan_i32_i64(f_rest, n_rows, pos_c, scan_tmp, stream));
         int64_t h_rest = 0;
         HC_TRY(hipMemcpyAsync(&h_rest, pos_c + n_rows, 8, hipMemcpyDeviceToHost, stream));
@@ -414,9 +414,13 @@ static hcspmm_status run_spmm(const hcspmm_plan* plan, const SpmmArgs& a, hipStr
     if (ev) HC_HIP(hipEventRecord(ev[1], stream));
     HC_HIP(launch_mfma_small(a, p->n_mfma_small, p->mfma_small_desc, p->wcols, p->erc, s_small, upd));
     if (ev) HC_HIP(hipEventRecord(ev[2], stream));
-    HC_HIP(launch_csr(a, p->n_segs, p->segs, p->partial, p->n_mid, p->mid_rows,
-                      p->short_rows ? p->n_short : (p->n_short > 0 ? p->n_rows : 0), p->short_rows, p->route,
-                      p->mid_row, stream, upd));
+    if (upd)        // the fused launch walks every row: its tile tier also takes the shorter mid rows
+        HC_HIP(launch_csr(a, p->n_segs, p->segs, p->partial, p->n_mid, p->mid_rows, p->n_csr > 0 ? p->n_rows : 0, nullptr,
+                          p->route, p->fused_mid_row, stream, upd));
+    else
+        HC_HIP(launch_csr(a, p->n_segs, p->segs, p->partial, p->n_mid, p->mid_rows,
+                          p->short_rows ? p->n_short : (p->n_short > 0 ? p->n_rows : 0), p->short_rows, p->route,
+                          p->mid_row, stream));
     if (ev) HC_HIP(hipEventRecord(ev[3], stream));
     HC_HIP(launch_reduce_partials(a, p->n_multi, p->multi, p->partial, stream));
     if (ev) HC_HIP(hipEventRecord(ev[4], stream));
@@ -492,6 +496,7 @@ hcspmm_status hcspmm_prepare(int32_t n_rows, int32_t n_cols, int64_t nnz, const 
     if (const char* v = getenv("HCSPMM_TUNE_MID_ROW")) { int t = atoi(v); if (t >= 1) p->mid_row = t; }
     if (const char* v = getenv("HCSPMM_TUNE_LONG_ROW")) { int t = atoi(v); if (t >= p->mid_row) p->long_row = t; }
     if (p->long_row < p->mid_row) p->long_row = p->mid_row;
+    p->fused_mid_row = kFusedMidRow < p->mid_row ? p->mid_row : (kFusedMidRow > p->long_row ? p->long_row : kFusedMidRow);
     p->slice_cols = kSliceCols;
     if (const char* v = getenv("HCSPMM_TUNE_SLICE_COLS")) { int t = atoi(v); if (t >= kKcBig) p->slice_cols = t / kKcBig * kKcBig; }
     if (o.use_custom_selector) {

@@ -279,7 +279,7 @@ __device__ inline void csr_short_fused_body(int64_t block, int32_t n_items, cons
 // ---- mid rows: one wave per row -------------------------------------------------------------
 template <int LPR, int VEC, int XK>
 __device__ inline void csr_mid_body(int64_t block, int32_t n_mid, const int32_t* __restrict__ mid_rows,
-                                    const SpmmArgs& a)
+                                    const SpmmArgs& a, int min_len = 0 /* rows this short belong to another tier */)
 {
     constexpr int G = 64 / LPR;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -287,6 +287,7 @@ __device__ inline void csr_mid_body(int64_t block, int32_t n_mid, const int32_t*
     if (item >= n_mid) return;
     const int32_t row = mid_rows[item];
     const int32_t s = a.rowptr[row], e = a.rowptr[row + 1];
+    if (e - s <= min_len) return;
     const int g = lane / LPR, lig = lane % LPR;
     const char* __restrict__ X = static_cast<const char*>(a.X);
     constexpr int ES = XElem<XK>::size;
@@ -399,7 +400,7 @@ __global__ __launch_bounds__(256) void k_csr_fused(CsrWork wk, SpmmArgs a, Updat
     b -= wk.n_segs;
     const int64_t mid_blocks = ((int64_t)wk.n_mid + 3) / 4;
     if (b < mid_blocks) {
-        csr_mid_body<LPR, VEC, 0>(b, wk.n_mid, wk.mid_rows, a);
+        csr_mid_body<LPR, VEC, 0>(b, wk.n_mid, wk.mid_rows, a, wk.mid_row);   // the fused tier takes rows up to mid_row
         return;
     }
     b -= mid_blocks;
