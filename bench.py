@@ -77,6 +77,9 @@ def main():
     ap.add_argument("--agg-update", type=int, default=None, metavar="D_OUT",
                     help="also time the aggregate-then-update layer Y = ReLU((A X) W) with a d x D_OUT W, with the "
                          "update stage fused into the SpMM kernels and as SpMM + GEMM")
+    ap.add_argument("--graph", type=int, default=0, metavar="N",
+                    help="also capture N back-to-back SpMM calls in a HIP graph and time its replays "
+                         "(separates launch latency from kernel time on the small configs)")
     ap.add_argument("--scramble", action="store_true",
                     help="relabel the vertices at random first (a layout with no locality)")
     ap.add_argument("--loa", type=int, default=None, metavar="VW",
@@ -215,6 +218,31 @@ def main():
                             total_gflops=round((gemm_flops + flops) / (ms_layer * 1e-3) / 1e9, 1))
         log("layer: %.3f ms (gemm alone %.3f ms = %.1f TFLOP/s)" % (ms_layer, ms_gemm, out["layer"]["gemm_tflops"]))
         del Xin_d, Wd, ws, Tg
+
+    if args.graph > 0:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            hc.hcspmm_spmm(plan, Xd, Yd)                       # every lazy allocation happens before the capture
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(args.graph):
+                hc.hcspmm_spmm(plan, Xd, Yd)
+        reps = max(3, args.steps // 10)
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        ms_graph = (time.perf_counter() - t0) * 1e3 / (reps * args.graph)
+        same = bool(np.array_equal(Yd.cpu().numpy(), Y_hybrid))
+        out["graph_replay"] = dict(calls_per_graph=args.graph, replays=reps, ms_per_call=round(ms_graph, 5),
+                                   bitwise_equal_to_eager=same)
+        log("graph replay: %.5f ms per SpMM call (eager %.5f), same bits: %s" % (ms_graph, ms, same))
+        del graph
 
     if args.agg_update:
         from workloads import glorot_uniform
