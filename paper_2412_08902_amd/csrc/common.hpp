@@ -70,7 +70,8 @@ hipError_t launch_unique_big(int32_t n_big, const int32_t* big_list, int32_t n_r
                              hipStream_t s);
 hipError_t launch_ecol(int32_t W, int32_t n_rows, const int32_t* rowptr, const int32_t* colind,
                        const int32_t* tmp_cols, const int32_t* ncols, const int64_t* wptr, int32_t* wcols,
-                       int32_t* erc, int32_t* unsorted_flag, hipStream_t s);
+                       int32_t* erc, int32_t* unsorted_flag, const uint8_t* route, int want,
+                       hipStream_t s);
 hipError_t launch_select(int32_t W, const int32_t* ncols, const int32_t* nnzw, int64_t c0, int64_t c1, int64_t c2,
                          int32_t mode, uint8_t* route, int32_t* f_mfma, int32_t* f_csr, int32_t* f_small,
                          int32_t* f_mid, int32_t* f_big, int32_t* nnz_if_mfma, hipStream_t s);
@@ -196,6 +197,7 @@ struct hcspmm_plan {
     int32_t n_multi;
     int64_t n_slots;
     int32_t n_long_rows;
+    int32_t condensed_complete;     // 0: wcols / erc are filled for matrix-path windows only (the rest on export)
     int32_t n_rest;                 // rows finished through the workspace by the fused update
     int32_t* rest_rows;
     int64_t nnz_long;

@@ -122,6 +122,37 @@ static void free_plan_arrays(hcspmm_plan* p)
         if (q) (void)hipFree(q);
 }
 
+// Fills wcols / erc for the scalar-path windows too (hcspmm_prepare leaves them out: no kernel reads
+// them); the distinct-column lists are recomputed into scratch memory.  Default stream, synchronous.
+static hcspmm_status complete_condensed(hcspmm_plan* p)
+{
+    hcspmm_status st = HCSPMM_OK;
+    DevAlloc tmp;
+    int32_t *tmp_cols = nullptr, *big_list = nullptr, *cnt = nullptr, *nc_tmp = nullptr, *nz_tmp = nullptr;
+    int32_t h_big = 0;
+    const int32_t W = p->W;
+    HC_ALLOC(tmp, tmp_cols, p->nnz);
+    HC_ALLOC(tmp, big_list, W);
+    HC_ALLOC(tmp, cnt, 2);
+    HC_ALLOC(tmp, nc_tmp, W);
+    HC_ALLOC(tmp, nz_tmp, W);
+    HC_TRY(hipMemsetAsync(cnt, 0, 2 * sizeof(int32_t), nullptr));
+    HC_TRY(launch_window_nnz(W, p->n_rows, p->rowptr, nz_tmp, big_list, cnt + 1, nullptr));
+    HC_TRY(launch_unique_small(W, p->n_rows, p->rowptr, p->colind, tmp_cols, nc_tmp, nullptr));
+    HC_TRY(hipMemcpy(&h_big, cnt + 1, sizeof h_big, hipMemcpyDeviceToHost));
+    HC_TRY(launch_unique_big(h_big, big_list, p->n_rows, p->n_cols, p->rowptr, p->colind, tmp_cols, nc_tmp, nullptr));
+    HC_TRY(launch_ecol(W, p->n_rows, p->rowptr, p->colind, tmp_cols, p->ncols, p->wptr, p->wcols, p->erc, cnt, p->route, 0,
+                       nullptr));
+    HC_TRY(hipDeviceSynchronize());
+    p->condensed_complete = 1;
+    tmp.free_all();
+    return HCSPMM_OK;
+fail:
+    (void)hipDeviceSynchronize();
+    tmp.free_all();
+    return st;
+}
+
 static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
 {
     hcspmm_status st = HCSPMM_OK;
@@ -179,13 +210,6 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     HC_TRY(hipStreamSynchronize(stream));
     HC_ALLOC(keep, p->wcols, p->total_ncols);
     p->rows_sorted = 1;
-    if (W > 0 && nnz > 0) {
-        // err[0] is zero here (validation passed): reuse it as the "some row is unsorted" flag
-        HC_TRY(launch_ecol(W, n_rows, p->rowptr, p->colind, tmp_cols, p->ncols, p->wptr, p->wcols, p->erc, err, stream));
-        HC_TRY(hipMemcpyAsync(&h_err, err, sizeof h_err, hipMemcpyDeviceToHost, stream));
-        HC_TRY(hipStreamSynchronize(stream));
-        p->rows_sorted = h_err ? 0 : 1;
-    }
 
     // selection (Section IV-C) and the per-route window lists
     HC_ALLOC(tmp, f_mfma, (size_t)W + 1);
@@ -213,6 +237,19 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
                 HC_TRY(launch_select(W, p->ncols, p->nnzw, p->coef[0], p->coef[1], p->coef[2], forced, p->route,
                                      f_mfma, f_csr, f_small, f_midw, f_big, nnz_if, stream));
         }
+    }
+    // condensed structure (column lists, condensed column of every non-zero) of the matrix-path
+    // windows; scalar-path windows never read theirs at SpMM time and get it on export only
+    p->condensed_complete = 0;
+    if (W > 0 && nnz > 0) {
+        // err[0] is zero here (validation passed): reuse it as the "some row is unsorted" flag
+        HC_TRY(launch_ecol(W, n_rows, p->rowptr, p->colind, tmp_cols, p->ncols, p->wptr, p->wcols, p->erc, err, p->route, 1,
+                           stream));
+        HC_TRY(hipMemcpyAsync(&h_err, err, sizeof h_err, hipMemcpyDeviceToHost, stream));
+        HC_TRY(hipStreamSynchronize(stream));
+        p->rows_sorted = h_err ? 0 : 1;
+    } else {
+        p->condensed_complete = 1;
     }
     HC_TRY(exclusive_scan_i32_i64(f_mfma, W, pos_a, scan_tmp, stream));
     HC_TRY(hipMemcpyAsync(totals_dev + 0, pos_a + W, 8, hipMemcpyDeviceToDevice, stream));
@@ -556,6 +593,10 @@ hcspmm_status hcspmm_plan_export(const hcspmm_plan* p, int32_t* ncols, int32_t* 
 {
     if (!p) { set_error("plan is NULL"); return HCSPMM_EINVAL; }
     HC_HIP(hipDeviceSynchronize());
+    if ((wcols || ecol) && !p->condensed_complete) {
+        const hcspmm_status st = complete_condensed(const_cast<hcspmm_plan*>(p));
+        if (st != HCSPMM_OK) return st;
+    }
     const size_t W = (size_t)p->W;
     if (ncols && W) HC_HIP(hipMemcpy(ncols, p->ncols, W * 4, hipMemcpyDeviceToHost));
     if (nnzw && W) HC_HIP(hipMemcpy(nnzw, p->nnzw, W * 4, hipMemcpyDeviceToHost));

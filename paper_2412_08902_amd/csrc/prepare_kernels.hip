@@ -323,11 +323,13 @@ __global__ __launch_bounds__(256) void k_ecol(int32_t n_rows, const int32_t* __r
                                               const int32_t* __restrict__ colind,
                                               const int32_t* __restrict__ tmp_cols, const int32_t* __restrict__ ncols,
                                               const int64_t* __restrict__ wptr, int32_t* __restrict__ wcols,
-                                              int32_t* __restrict__ erc, int32_t* __restrict__ unsorted_flag)
+                                              int32_t* __restrict__ erc, int32_t* __restrict__ unsorted_flag,
+                                              const uint8_t* __restrict__ route, int want)
 {
     __shared__ int32_t ucols[kEcolLdsCap];
     __shared__ int32_t rp[kH + 1];
     const int32_t w = blockIdx.x;
+    if ((route[w] != 0) != (want != 0)) return;      // only the windows of one route
     int32_t s, e;
     window_span(w, n_rows, rowptr, s, e);
     if (e == s) return;
@@ -366,10 +368,10 @@ __global__ __launch_bounds__(256) void k_ecol(int32_t n_rows, const int32_t* __r
 
 hipError_t launch_ecol(int32_t W, int32_t n_rows, const int32_t* rowptr, const int32_t* colind,
                        const int32_t* tmp_cols, const int32_t* ncols, const int64_t* wptr, int32_t* wcols,
-                       int32_t* erc, int32_t* unsorted_flag, hipStream_t s)
+                       int32_t* erc, int32_t* unsorted_flag, const uint8_t* route, int want, hipStream_t s)
 {
     hipLaunchKernelGGL(k_ecol, dim3(W), dim3(256), 0, s, n_rows, rowptr, colind, tmp_cols, ncols, wptr, wcols, erc,
-                       unsorted_flag);
+                       unsorted_flag, route, want);
     return hipGetLastError();
 }
 
