@@ -131,6 +131,14 @@ static hcspmm_status complete_condensed(hcspmm_plan* p)
     int32_t *tmp_cols = nullptr, *big_list = nullptr, *cnt = nullptr, *nc_tmp = nullptr, *nz_tmp = nullptr;
     int32_t h_big = 0;
     const int32_t W = p->W;
+    if (!p->erc && hipMalloc((void**)&p->erc, (size_t)(p->nnz > 0 ? p->nnz : 1) * sizeof(int32_t)) != hipSuccess) {
+        (void)hipGetLastError(); p->erc = nullptr;
+        set_error("device allocation failed while completing the condensed structure"); return HCSPMM_EALLOC;
+    }
+    if (!p->wcols && hipMalloc((void**)&p->wcols, (size_t)(p->total_ncols > 0 ? p->total_ncols : 1) * sizeof(int32_t)) != hipSuccess) {
+        (void)hipGetLastError(); p->wcols = nullptr;
+        set_error("device allocation failed while completing the condensed structure"); return HCSPMM_EALLOC;
+    }
     HC_ALLOC(tmp, tmp_cols, p->nnz);
     HC_ALLOC(tmp, big_list, W);
     HC_ALLOC(tmp, cnt, 2);
@@ -187,7 +195,6 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     HC_ALLOC(keep, p->nnzw, W);
     HC_ALLOC(keep, p->route, W);
     HC_ALLOC(keep, p->wptr, (size_t)W + 1);
-    HC_ALLOC(keep, p->erc, nnz);
     HC_ALLOC(tmp, tmp_cols, nnz);
     HC_ALLOC(tmp, big_list, W);
     HC_ALLOC(tmp, scan_tmp, scan_scratch_elems(scan_n));
@@ -208,7 +215,6 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     HC_TRY(exclusive_scan_i32_i64(p->ncols, W, p->wptr, scan_tmp, stream));
     HC_TRY(hipMemcpyAsync(&p->total_ncols, p->wptr + W, sizeof(int64_t), hipMemcpyDeviceToHost, stream));
     HC_TRY(hipStreamSynchronize(stream));
-    HC_ALLOC(keep, p->wcols, p->total_ncols);
     p->rows_sorted = 1;
 
     // selection (Section IV-C) and the per-route window lists
@@ -238,19 +244,6 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
                                      f_mfma, f_csr, f_small, f_midw, f_big, nnz_if, stream));
         }
     }
-    // condensed structure (column lists, condensed column of every non-zero) of the matrix-path
-    // windows; scalar-path windows never read theirs at SpMM time and get it on export only
-    p->condensed_complete = 0;
-    if (W > 0 && nnz > 0) {
-        // err[0] is zero here (validation passed): reuse it as the "some row is unsorted" flag
-        HC_TRY(launch_ecol(W, n_rows, p->rowptr, p->colind, tmp_cols, p->ncols, p->wptr, p->wcols, p->erc, err, p->route, 1,
-                           stream));
-        HC_TRY(hipMemcpyAsync(&h_err, err, sizeof h_err, hipMemcpyDeviceToHost, stream));
-        HC_TRY(hipStreamSynchronize(stream));
-        p->rows_sorted = h_err ? 0 : 1;
-    } else {
-        p->condensed_complete = 1;
-    }
     HC_TRY(exclusive_scan_i32_i64(f_mfma, W, pos_a, scan_tmp, stream));
     HC_TRY(hipMemcpyAsync(totals_dev + 0, pos_a + W, 8, hipMemcpyDeviceToDevice, stream));
     HC_TRY(exclusive_scan_i32_i64(f_csr, W, pos_b, scan_tmp, stream));
@@ -265,6 +258,22 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     p->n_mfma_small = (int32_t)h_tot[1];
     p->n_mfma_big = (int32_t)h_tot[2];
     p->n_mfma_mid = p->n_mfma - p->n_mfma_small - p->n_mfma_big;
+    // condensed structure (column lists, condensed column of every non-zero) of the matrix-path
+    // windows; scalar-path windows never read theirs at SpMM time and get it on export only, and a
+    // plan without matrix-path windows does not even allocate the arrays
+    p->condensed_complete = 0;
+    if (p->n_mfma > 0) {
+        HC_ALLOC(keep, p->erc, nnz);
+        HC_ALLOC(keep, p->wcols, p->total_ncols);
+        // err[0] is zero here (validation passed): reuse it as the "some row is unsorted" flag
+        HC_TRY(launch_ecol(W, n_rows, p->rowptr, p->colind, tmp_cols, p->ncols, p->wptr, p->wcols, p->erc, err, p->route, 1,
+                           stream));
+        HC_TRY(hipMemcpyAsync(&h_err, err, sizeof h_err, hipMemcpyDeviceToHost, stream));
+        HC_TRY(hipStreamSynchronize(stream));
+        p->rows_sorted = h_err ? 0 : 1;
+    } else if (nnz == 0) {
+        p->condensed_complete = 1;
+    }
     HC_ALLOC(keep, p->mfma_windows, p->n_mfma);
     HC_ALLOC(keep, p->csr_windows, p->n_csr);
     HC_ALLOC(keep, p->mfma_small, p->n_mfma_small);
