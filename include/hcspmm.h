@@ -150,6 +150,8 @@ hcspmm_status hcspmm_plan_info(const hcspmm_plan* plan, hcspmm_plan_info_t* info
  *   wptr   int64[W+1]  offsets into wcols
  *   wcols  int32[total_ncols]  per window: its distinct column ids, ascending
  *   ecol   int32[nnz]  per non-zero (CSR order): position of its column in its window's wcols
+ *          (hcspmm_prepare builds wcols / ecol for matrix-path windows only, no kernel reads the
+ *          others; asking for either array here computes the rest first)
  *   mfma_windows int32[n_mfma_windows], csr_windows int32[n_csr_windows]: ascending window ids per route
  * Synchronises with the device.
  */
@@ -169,6 +171,14 @@ hcspmm_status hcspmm_plan_export(const hcspmm_plan* plan, int32_t* ncols, int32_
  *            accumulation, the scalar path widens X to fp32.
  *   y_dtype  must be HCSPMM_F32.
  * X and Y must not overlap.  1 <= d <= 2^20.  Asynchronous on `stream`.
+ *
+ * A plan holds scratch buffers of its own (partial rows of long rows, partial tiles of wide
+ * windows; allocated on the first call that needs them, which synchronises `stream` if it has to
+ * grow them): calls that use the same plan must be ordered, i.e. issued on one stream or
+ * otherwise serialised by the caller.  Different plans are independent.  Once a call with the
+ * largest d in use has been made, later calls allocate nothing and can be captured in a HIP graph.
+ * On the matrix path X must be finite: the dense-tile product multiplies every gathered row with
+ * explicit zeros, so a NaN or Inf in a gathered row reaches all 16 rows of its window.
  */
 hcspmm_status hcspmm_spmm(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d, int32_t x_dtype,
                           void* d_Y, int64_t ldy, int32_t y_dtype, void* stream);
