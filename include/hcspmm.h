@@ -106,8 +106,13 @@ hcspmm_status hcspmm_default_selector(int32_t mfma_dtype, int32_t d_hint, int64_
  *   opt              host, NULL = defaults
  *   out_plan         host, receives the plan
  *
- * The plan BORROWS d_rowptr / d_colind / d_vals: they must stay valid and
- * unchanged until hcspmm_plan_destroy.  Everything the plan allocates it owns.
+ * The plan BORROWS d_rowptr / d_colind / d_vals: they must stay valid until
+ * hcspmm_plan_destroy, and d_rowptr / d_colind unchanged.  The plan depends on the
+ * structure only (windows, condensed columns, selector features are functions of the indices),
+ * and every kernel reads the values through d_vals at call time: the CALLER MAY OVERWRITE
+ * d_vals IN PLACE between calls (edge weights that change per layer or per epoch) without
+ * preparing again.  A structural change needs a new plan (a prepare costs 2-3 SpMM calls on the
+ * large configurations).  Everything the plan allocates it owns.
  * Validates the CSR on the device (HCSPMM_EBADCSR).  Synchronises with `stream`.
  */
 hcspmm_status hcspmm_prepare(int32_t n_rows, int32_t n_cols, int64_t nnz,

@@ -168,3 +168,27 @@ def test_hip_graph_replays_match_eager():
     assert_close(Y.cpu().numpy().astype(np.float64), ref, bound, TOL_F32)
     del graph
     plan.destroy()
+
+
+@pytest.mark.parametrize("mode", [PER_WINDOW, ALL_CSR, ALL_MFMA])
+def test_values_may_change_in_place_under_a_plan(mode):
+    """The plan is a function of the structure only: new edge values written into the borrowed array are
+    picked up by the next call on both paths."""
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    g = sbm_graph(16, 64, 0.3, 3.0, seed=12)
+    X = dense_normal(g.n_cols, 48, seed=13)
+    rp, ci, va = device_graph(g)
+    plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, route_mode=mode, d_hint=48, sel_coef=[1, 0, -118])
+    Xd = torch.from_numpy(X).cuda()
+    Y = torch.empty(g.n_rows, 48, device="cuda")
+    rng = np.random.default_rng(14)
+    for rep in range(3):
+        new_vals = rng.standard_normal(g.nnz).astype(np.float32)
+        va.copy_(torch.from_numpy(new_vals).cuda())
+        hc.hcspmm_spmm(plan, Xd, Y)
+        torch.cuda.synchronize()
+        g2 = CSRGraph(g.n_rows, g.n_cols, g.rowptr, g.colind, new_vals)
+        ref, bound = oracle_pair(g2, X)
+        assert_close(Y.cpu().numpy().astype(np.float64), ref, bound, TOL_F32, "values of round %d" % rep)
+    plan.destroy()
