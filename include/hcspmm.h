@@ -111,8 +111,8 @@ hcspmm_status hcspmm_default_selector(int32_t mfma_dtype, int32_t d_hint, int64_
  * structure only (windows, condensed columns, selector features are functions of the indices),
  * and every kernel reads the values through d_vals at call time: the CALLER MAY OVERWRITE
  * d_vals IN PLACE between calls (edge weights that change per layer or per epoch) without
- * preparing again.  A structural change needs a new plan (a prepare costs 2-3 SpMM calls on the
- * large configurations).  Everything the plan allocates it owns.
+ * preparing again.  A structural change needs a new plan (a prepare costs about two SpMM calls on
+ * the large configurations).  Everything the plan allocates it owns.
  * Validates the CSR on the device (HCSPMM_EBADCSR).  Synchronises with `stream`.
  */
 hcspmm_status hcspmm_prepare(int32_t n_rows, int32_t n_cols, int64_t nnz,

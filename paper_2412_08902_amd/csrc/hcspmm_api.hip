@@ -74,10 +74,30 @@ static bool lookup_selector(int32_t dtype, int32_t d_hint, int64_t nnz, int64_t*
 struct DevAlloc {
     std::vector<void*> ptrs;
     int64_t bytes = 0;
+    char* arena = nullptr;          // optional: one allocation that get() carves up (scratch of known total size)
+    size_t arena_size = 0, arena_used = 0;
+    hipError_t reserve(size_t total)
+    {
+        void* p = nullptr;
+        hipError_t e = hipMalloc(&p, total ? total : 256);
+        if (e != hipSuccess) return e;
+        ptrs.push_back(p);
+        arena = static_cast<char*>(p);
+        arena_size = total;
+        arena_used = 0;
+        return hipSuccess;
+    }
+    static size_t padded(size_t sz) { return (sz + 255) & ~(size_t)255; }
     template <class T> hipError_t get(T** out, size_t count)
     {
         size_t sz = count * sizeof(T);
         if (sz == 0) sz = sizeof(T) < 16 ? 16 : sizeof(T);
+        if (arena && arena_used + padded(sz) <= arena_size) {
+            *out = reinterpret_cast<T*>(arena + arena_used);
+            arena_used += padded(sz);
+            bytes += (int64_t)sz;
+            return hipSuccess;
+        }
         void* p = nullptr;
         hipError_t e = hipMalloc(&p, sz);
         if (e != hipSuccess) { *out = nullptr; return e; }
@@ -90,6 +110,8 @@ struct DevAlloc {
     {
         for (void* p : ptrs) (void)hipFree(p);
         ptrs.clear();
+        arena = nullptr;
+        arena_size = arena_used = 0;
     }
 };
 
@@ -177,6 +199,20 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     int64_t h_tot[8];
     const int64_t scan_n = (int64_t)(n_rows > W ? n_rows : W) + 1;
 
+    {
+        // every scratch array of this function has a size known from (n_rows, W, nnz): one allocation
+        const size_t i32 = sizeof(int32_t), i64 = sizeof(int64_t);
+        size_t total = DevAlloc::padded(2 * i32) + DevAlloc::padded((size_t)nnz * i32) + DevAlloc::padded((size_t)W * i32) +
+                       DevAlloc::padded((size_t)scan_scratch_elems(scan_n) * i64) + 4 * DevAlloc::padded((size_t)(scan_n + 1) * i64) +
+                       DevAlloc::padded(8 * i64) + 6 * DevAlloc::padded(((size_t)W + 1) * i32) +
+                       6 * DevAlloc::padded(((size_t)n_rows + 1) * i32) + 64 * 256;
+        if (tmp.reserve(total) != hipSuccess) {
+            (void)hipGetLastError();
+            set_error("device allocation of %zu scratch bytes failed", total);
+            st = HCSPMM_EALLOC;
+            goto fail;
+        }
+    }
     HC_ALLOC(tmp, err, 2);
     big_count = err + 1;
     HC_TRY(hipMemsetAsync(err, 0, 2 * sizeof(int32_t), stream));
