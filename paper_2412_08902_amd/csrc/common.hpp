@@ -30,7 +30,7 @@ constexpr int kSliceCols = 4096;       // condensed columns per workgroup; wider
 
 // ---- scalar path -------------------------------------------------------------------------------
 constexpr int kRowsPerGroup = 8;       // consecutive rows walked by one lane group (short rows)
-constexpr int kMidRow = 64;            // rows with more non-zeros than this get a whole wave
+constexpr int kMidRow = 128;           // rows with more non-zeros than this get a whole wave
 constexpr int kFusedMidRow = 256;      // with the update stage fused in, rows up to this length stay in the workgroup's tile
 constexpr int kLongRow = 1024;         // rows with more non-zeros than this are cut into workgroup-sized segments
 constexpr int kSegLen = 2048;          // non-zeros per segment of a long row

@@ -29,9 +29,11 @@ void set_error(const char* fmt, ...)
 //     matrix path  iff  ncols / N0 + sparsity / S0 < 1 :
 // N0 bounds the window width, S0 is the sparsity below which the matrix path pays.
 //  * d > 64: the matrix path wins or ties from ~1.02 non-zeros per condensed column at every
-//    width in the sweep, on community graphs of any density (-24..-38 %) and on the dense
-//    power-law graph of the benchmark set (-19 %); wide windows are cut into column slices as far
-//    as parallelism needs, so no width limit (w1 = 0), S0 = 0.936.
+//    width in the sweep and on the dense power-law graph of the benchmark set (-17 %); wide windows
+//    are cut into column slices as far as parallelism needs, so no width limit (w1 = 0) and
+//    S0 = 0.936 for large matrices.  On community graphs at d = 128 (blocks of 64, 128-column
+//    windows) the scalar path with its XCD-local row order wins at sparsity 0.84 (76 vs 84 us) and
+//    loses from 0.72 down (120 vs 96, 143 vs 106, 178 vs 118 us): S0 = 0.83 for smaller matrices.
 //  * d <= 64: the sweep (whose windows share no columns with their neighbours) favours the
 //    matrix path from ~1.3 non-zeros per column, but on community graphs, where neighbouring rows
 //    and windows share columns, the scalar path gets the same reuse out of L1 and the two paths
@@ -46,7 +48,7 @@ static const SelectorRow kSelectorTable[] = {
     // workgroup, which only a large matrix amortises: below 16 M non-zeros windows wider than a
     // few hundred columns stay on the scalar path (N0 = 2048), above there is no width limit.
     {HCSPMM_F32, 1 << 30, 16000000, {0, 1120000, -1048576}},     // S0 = 0.936
-    {HCSPMM_F32, 1 << 30, 0, {512, 1120000, -1048576}},          // N0 = 2048, S0 = 0.936
+    {HCSPMM_F32, 1 << 30, 0, {512, 1263344, -1048576}},          // N0 = 2048, S0 = 0.83
     // 16-bit X.  Half the gather bytes make the scalar path more than twice as fast on the large
     // dense power-law graph (X fits the caches better), while the matrix path gains less: there the
     // scalar path wins on every window (2.87 vs 3.48 ms all-matrix), so large matrices keep only

@@ -362,6 +362,9 @@ struct CsrWork {
     const uint8_t* route;
     int32_t rows_per_group;
     int32_t mid_row;
+    int32_t xcd_chunk;          // short-row workgroups per XCD-local run (0: plain order)
+    int64_t mid_blocks;         // workgroups of the mid tier (padded to whole rounds of runs when xcd_chunk_mid > 0)
+    int32_t xcd_chunk_mid;
 };
 
 template <int LPR, int VEC, int XK>
@@ -374,12 +377,25 @@ __global__ __launch_bounds__(256) void k_csr(CsrWork wk, SpmmArgs a)
         return;
     }
     b -= wk.n_segs;
-    const int64_t mid_blocks = ((int64_t)wk.n_mid + 3) / 4;
+    const int64_t mid_blocks = wk.mid_blocks;
     if (b < mid_blocks) {
+        if (wk.xcd_chunk_mid > 0) {                              // same XCD-local runs as for the short rows below
+            const int64_t x = blockIdx.x & 7, q = b >> 3;
+            b = ((q / wk.xcd_chunk_mid) * 8 + x) * wk.xcd_chunk_mid + q % wk.xcd_chunk_mid;
+        }
         csr_mid_body<LPR, VEC, XK>(b, wk.n_mid, wk.mid_rows, a);
         return;
     }
     b -= mid_blocks;
+    if (wk.xcd_chunk > 0) {
+        // Workgroups go to the eight XCDs round-robin by their linear id, and each XCD has an L2 of
+        // its own.  Hand out the short rows in runs of xcd_chunk consecutive workgroups, run r to XCD
+        // r % 8: neighbouring rows -- which share columns in graphs with any locality -- then meet in
+        // one L2 close in time, while all XCDs still advance through the matrix side by side (rows
+        // sorted by degree stay balanced).
+        const int64_t x = blockIdx.x & 7, q = b >> 3;
+        b = ((q / wk.xcd_chunk) * 8 + x) * wk.xcd_chunk + q % wk.xcd_chunk;
+    }
     csr_short_body<LPR, VEC, XK>(b, wk.n_items, wk.row_list, wk.route, wk.rows_per_group, wk.mid_row, a);
 }
 
@@ -398,7 +414,7 @@ __global__ __launch_bounds__(256) void k_csr_fused(CsrWork wk, SpmmArgs a, Updat
         return;
     }
     b -= wk.n_segs;
-    const int64_t mid_blocks = ((int64_t)wk.n_mid + 3) / 4;
+    const int64_t mid_blocks = wk.mid_blocks;
     if (b < mid_blocks) {
         csr_mid_body<LPR, VEC, 0>(b, wk.n_mid, wk.mid_rows, a, wk.mid_row);   // the fused tier takes rows up to mid_row
         return;
@@ -510,7 +526,7 @@ hipError_t launch_csr(const SpmmArgs& a, int32_t n_segs, const Segment* segs, fl
         const int rows_per_wg = sh.lpr == 8 ? 32 : 16;          // FusedShape<LPR, VEC>::ROWS
         const int64_t blocks = (int64_t)n_segs + ((int64_t)n_mid + 3) / 4 + ((int64_t)n_items + rows_per_wg - 1) / rows_per_wg;
         if (blocks <= 0) return hipSuccess;
-        CsrWork wk{n_segs, segs, partial, n_mid, mid_rows, n_items, row_list, route, 0, mid_row};
+        CsrWork wk{n_segs, segs, partial, n_mid, mid_rows, n_items, row_list, route, 0, mid_row, 0, ((int64_t)n_mid + 3) / 4, 0};
 #define HC_LAUNCH_CSRF(L, V) hipLaunchKernelGGL((k_csr_fused<L, V>), dim3((unsigned)blocks), dim3(256), 0, s, wk, a, *upd)
         switch (sh.lpr * 10 + sh.vec) {
             case 84: HC_LAUNCH_CSRF(8, 4); break;
@@ -535,9 +551,22 @@ hipError_t launch_csr(const SpmmArgs& a, int32_t n_segs, const Segment* segs, fl
     if (const char* t = getenv("HCSPMM_TUNE_RPG")) { const int v = atoi(t); if (v >= 1 && v <= kRowsPerGroup) rpg = v; }
     const int64_t n_groups = ((int64_t)n_items + rpg - 1) / rpg;
     const int gpb = 256 / sh.lpr;
-    const int64_t blocks = (int64_t)n_segs + ((int64_t)n_mid + 3) / 4 + (n_groups + gpb - 1) / gpb;
+    // XCD-local runs (see k_csr): tiers of at least 1024 workgroups are padded to whole rounds of
+    // eight runs; the surplus workgroups exit at once
+    int run = 32;
+    if (const char* t = getenv("HCSPMM_TUNE_XCD_CHUNK")) run = atoi(t);
+    auto pad_runs = [run](int64_t n, int32_t& chunk) {
+        chunk = 0;
+        if (run <= 0 || n < 1024) return n;
+        chunk = run;
+        return (n + 8 * run - 1) / (8 * run) * (8 * (int64_t)run);
+    };
+    int32_t xcd_chunk = 0, xcd_chunk_mid = 0;
+    const int64_t short_blocks = pad_runs((n_groups + gpb - 1) / gpb, xcd_chunk);
+    const int64_t mid_blocks = pad_runs(((int64_t)n_mid + 3) / 4, xcd_chunk_mid);
+    const int64_t blocks = (int64_t)n_segs + mid_blocks + short_blocks;
     if (blocks <= 0) return hipSuccess;
-    CsrWork wk{n_segs, segs, partial, n_mid, mid_rows, n_items, row_list, route, rpg, mid_row};
+    CsrWork wk{n_segs, segs, partial, n_mid, mid_rows, n_items, row_list, route, rpg, mid_row, xcd_chunk, mid_blocks, xcd_chunk_mid};
 #define HC_LAUNCH_CSR(L, V, K) hipLaunchKernelGGL((k_csr<L, V, K>), dim3((unsigned)blocks), dim3(256), 0, s, wk, a)
     HC_CSR_DISPATCH(HC_LAUNCH_CSR)
 #undef HC_LAUNCH_CSR

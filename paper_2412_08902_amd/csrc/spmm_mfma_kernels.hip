@@ -28,6 +28,8 @@
 // Like any dense-tile formulation (the paper's included) this path multiplies every gathered X
 // row with explicit zeros, so X must be finite: a NaN or Inf in a gathered row reaches all 16
 // rows of the window, not only the rows that reference it.
+#include <cstdlib>
+
 #include "common.hpp"
 #include "update_tile.hpp"
 
@@ -231,8 +233,8 @@ constexpr int kEdgeRegs = 6;
 template <int XK, int VW, int NG, bool FUSE = false>
 __global__ __launch_bounds__(256) void k_mfma_small(int32_t n_list, const WinDesc* __restrict__ desc,
                                                     const int32_t* __restrict__ wcols,
-                                                    const int32_t* __restrict__ erc, int col0, SpmmArgs a,
-                                                    UpdateArgs u)
+                                                    const int32_t* __restrict__ erc, int col0, int xcd_chunk,
+                                                    SpmmArgs a, UpdateArgs u)
 {
     using P = Path<XK, VW, NG>;
     constexpr int kLdz = NG * 16 * VW + 4;
@@ -240,7 +242,14 @@ __global__ __launch_bounds__(256) void k_mfma_small(int32_t n_list, const WinDes
     __shared__ float tiles[4][kRegion];
     __shared__ int32_t rows_s[FUSE ? 64 : 1];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    const int64_t item = (int64_t)blockIdx.x * 4 + wave;
+    int64_t blk = blockIdx.x;
+    if (xcd_chunk > 0) {
+        // runs of xcd_chunk consecutive workgroups (4 neighbouring windows each) go to one XCD, run r
+        // to XCD r % 8, so that windows which share columns meet in one L2 close in time
+        const int64_t x = blockIdx.x & 7, q = blk >> 3;
+        blk = ((q / xcd_chunk) * 8 + x) * xcd_chunk + q % xcd_chunk;
+    }
+    const int64_t item = blk * 4 + wave;
     if (item >= n_list) return;
     const WinDesc ds = desc[item];
     const int32_t r0 = ds.w * kH, s = ds.s, e = ds.e, nc = ds.nc;
@@ -549,10 +558,18 @@ hipError_t launch_mfma_small(const SpmmArgs& a, int32_t n_list, const WinDesc* d
     MfmaShape sh;
     if (!pick_mfma_shape(a, sh)) return hipErrorInvalidValue;
     const int span = sh.ng * 16 * sh.vw;                       // output columns per launch
+    int64_t n_blocks = ((int64_t)n_list + 3) / 4;
+    int xcd_chunk = 0;
+    if (n_blocks >= 1024) {                      // pad to whole rounds of eight runs; surplus workgroups exit at once
+        xcd_chunk = 32;
+        if (const char* t = getenv("HCSPMM_TUNE_XCD_CHUNK")) xcd_chunk = atoi(t);
+        if (xcd_chunk > 0) n_blocks = (n_blocks + 8 * xcd_chunk - 1) / (8 * xcd_chunk) * (8 * xcd_chunk);
+        else xcd_chunk = 0;
+    }
     if (upd) {
         if (a.x_dtype != HCSPMM_F32 || span < a.d) return hipErrorInvalidValue;
-        const dim3 grid((unsigned)((n_list + 3) / 4));
-#define HC_LAUNCH_MSF(V, G) hipLaunchKernelGGL((k_mfma_small<0, V, G, true>), grid, dim3(256), 0, s, n_list, desc, wcols, erc, 0, a, *upd)
+        const dim3 grid((unsigned)n_blocks);
+#define HC_LAUNCH_MSF(V, G) hipLaunchKernelGGL((k_mfma_small<0, V, G, true>), grid, dim3(256), 0, s, n_list, desc, wcols, erc, 0, xcd_chunk, a, *upd)
         switch (sh.vw * 10 + sh.ng) {
             case 41: HC_LAUNCH_MSF(4, 1); break;
             case 42: HC_LAUNCH_MSF(4, 2); break;
@@ -570,8 +587,8 @@ hipError_t launch_mfma_small(const SpmmArgs& a, int32_t n_list, const WinDesc* d
     const UpdateArgs no_update{};
     for (int col0 = 0; col0 < a.d; col0 += span) {
 #define HC_LAUNCH_MS(K, V, G)                                                                      \
-    hipLaunchKernelGGL((k_mfma_small<K, V, G>), dim3((unsigned)((n_list + 3) / 4)), dim3(256), 0, s, n_list, desc,   \
-                       wcols, erc, col0, a, no_update)
+    hipLaunchKernelGGL((k_mfma_small<K, V, G>), dim3((unsigned)n_blocks), dim3(256), 0, s, n_list, desc,   \
+                       wcols, erc, col0, xcd_chunk, a, no_update)
         HC_MFMA_DISPATCH(HC_LAUNCH_MS)
 #undef HC_LAUNCH_MS
     }
