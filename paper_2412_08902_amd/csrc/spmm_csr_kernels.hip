@@ -420,6 +420,10 @@ __global__ __launch_bounds__(256) void k_csr_fused(CsrWork wk, SpmmArgs a, Updat
         return;
     }
     b -= mid_blocks;
+    if (wk.xcd_chunk > 0) {                                     // XCD-local runs, as in k_csr
+        const int64_t x = blockIdx.x & 7, q = b >> 3;
+        b = ((q / wk.xcd_chunk) * 8 + x) * wk.xcd_chunk + q % wk.xcd_chunk;
+    }
     csr_short_fused_body<LPR, VEC>(b, wk.n_items, wk.row_list, wk.route, wk.mid_row, a, u, zt, rows16);
 }
 
@@ -522,11 +526,23 @@ hipError_t launch_csr(const SpmmArgs& a, int32_t n_segs, const Segment* segs, fl
                       int32_t mid_row, hipStream_t s, const UpdateArgs* upd)
 {
     const CsrShape sh = pick_shape(a, partial);
+    // XCD-local runs (see k_csr): tiers of at least 1024 workgroups are padded to whole rounds of
+    // eight runs; the surplus workgroups exit at once
+    int run = 32;
+    if (const char* t = getenv("HCSPMM_TUNE_XCD_CHUNK")) run = atoi(t);
+    auto pad_runs = [run](int64_t n, int32_t& chunk) {
+        chunk = 0;
+        if (run <= 0 || n < 1024) return n;
+        chunk = run;
+        return (n + 8 * run - 1) / (8 * run) * (8 * (int64_t)run);
+    };
     if (upd) {
         const int rows_per_wg = sh.lpr == 8 ? 32 : 16;          // FusedShape<LPR, VEC>::ROWS
-        const int64_t blocks = (int64_t)n_segs + ((int64_t)n_mid + 3) / 4 + ((int64_t)n_items + rows_per_wg - 1) / rows_per_wg;
+        int32_t xcd_chunk = 0;
+        const int64_t short_blocks = pad_runs(((int64_t)n_items + rows_per_wg - 1) / rows_per_wg, xcd_chunk);
+        const int64_t blocks = (int64_t)n_segs + ((int64_t)n_mid + 3) / 4 + short_blocks;
         if (blocks <= 0) return hipSuccess;
-        CsrWork wk{n_segs, segs, partial, n_mid, mid_rows, n_items, row_list, route, 0, mid_row, 0, ((int64_t)n_mid + 3) / 4, 0};
+        CsrWork wk{n_segs, segs, partial, n_mid, mid_rows, n_items, row_list, route, 0, mid_row, xcd_chunk, ((int64_t)n_mid + 3) / 4, 0};
 #define HC_LAUNCH_CSRF(L, V) hipLaunchKernelGGL((k_csr_fused<L, V>), dim3((unsigned)blocks), dim3(256), 0, s, wk, a, *upd)
         switch (sh.lpr * 10 + sh.vec) {
             case 84: HC_LAUNCH_CSRF(8, 4); break;
@@ -551,16 +567,6 @@ hipError_t launch_csr(const SpmmArgs& a, int32_t n_segs, const Segment* segs, fl
     if (const char* t = getenv("HCSPMM_TUNE_RPG")) { const int v = atoi(t); if (v >= 1 && v <= kRowsPerGroup) rpg = v; }
     const int64_t n_groups = ((int64_t)n_items + rpg - 1) / rpg;
     const int gpb = 256 / sh.lpr;
-    // XCD-local runs (see k_csr): tiers of at least 1024 workgroups are padded to whole rounds of
-    // eight runs; the surplus workgroups exit at once
-    int run = 32;
-    if (const char* t = getenv("HCSPMM_TUNE_XCD_CHUNK")) run = atoi(t);
-    auto pad_runs = [run](int64_t n, int32_t& chunk) {
-        chunk = 0;
-        if (run <= 0 || n < 1024) return n;
-        chunk = run;
-        return (n + 8 * run - 1) / (8 * run) * (8 * (int64_t)run);
-    };
     int32_t xcd_chunk = 0, xcd_chunk_mid = 0;
     const int64_t short_blocks = pad_runs((n_groups + gpb - 1) / gpb, xcd_chunk);
     const int64_t mid_blocks = pad_runs(((int64_t)n_mid + 3) / 4, xcd_chunk_mid);
