@@ -33,8 +33,8 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES = {
     ("C4", "k_csr", "f32"): 15.14e9 + 0.314e9,      # profiles/k_csr_C4_large_powerlaw.md
     ("C5", "k_mfma_wg", "f32"): 34.58e9 + 0.090e9,  # profiles/k_mfma_wg_C5_dense_powerlaw.md
-    ("C2", "k_csr", "f32"): 0.738e9 + 0.087e9,      # profiles/k_csr_C2_C3.md
-    ("C3", "k_csr", "f32"): 0.272e9 + 0.034e9,      # profiles/k_csr_C2_C3.md
+    ("C2", "k_csr", "f32"): 0.735e9 + 0.087e9,      # profiles/k_csr_C2_C3.md
+    ("C3", "k_csr", "f32"): 0.176e9 + 0.034e9,      # profiles/k_csr_C2_C3.md
 }
 
 WORKLOAD_TEXT = {
