@@ -192,3 +192,31 @@ def test_values_may_change_in_place_under_a_plan(mode):
         ref, bound = oracle_pair(g2, X)
         assert_close(Y.cpu().numpy().astype(np.float64), ref, bound, TOL_F32, "values of round %d" % rep)
     plan.destroy()
+
+
+def test_two_plans_on_two_streams():
+    """Different plans are independent: two SpMMs enqueued on two streams at once both match the oracle,
+    and a plan prepared with one width hint serves another width."""
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    ga = gcn_normalise(chung_lu_graph(3000, 60000, 2.0, seed=91, max_degree=1500))
+    gb = sbm_graph(40, 64, 0.5, 3.0, seed=92)
+    Xa, Xb = dense_normal(ga.n_cols, 96, seed=93), dense_normal(gb.n_cols, 128, seed=94)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    pa = hc.hcspmm_prepare(ga.n_rows, ga.n_cols, *device_graph(ga), d_hint=32)          # hint differs from the width used
+    pb = hc.hcspmm_prepare(gb.n_rows, gb.n_cols, *device_graph(gb), d_hint=128)
+    Xad, Xbd = torch.from_numpy(Xa).cuda(), torch.from_numpy(Xb).cuda()
+    Ya = torch.empty(ga.n_rows, 96, device="cuda")
+    Yb = torch.empty(gb.n_rows, 128, device="cuda")
+    torch.cuda.synchronize()
+    for _ in range(3):
+        hc.hcspmm_spmm(pa, Xad, Ya, stream=sa)
+        hc.hcspmm_spmm(pb, Xbd, Yb, stream=sb)
+    sa.synchronize()
+    sb.synchronize()
+    ra, ba = oracle_pair(ga, Xa)
+    rb, bb = oracle_pair(gb, Xb)
+    assert_close(Ya.cpu().numpy().astype(np.float64), ra, ba, TOL_F32, "plan a")
+    assert_close(Yb.cpu().numpy().astype(np.float64), rb, bb, TOL_F32, "plan b")
+    pa.destroy()
+    pb.destroy()
