@@ -220,3 +220,38 @@ def test_two_plans_on_two_streams():
     assert_close(Yb.cpu().numpy().astype(np.float64), rb, bb, TOL_F32, "plan b")
     pa.destroy()
     pb.destroy()
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_very_wide_dense_operand(mode):
+    """d far beyond one pass of a lane group or one launch of the matrix-path kernels (several column chunks)."""
+    g = gcn_normalise(chung_lu_graph(300, 4000, 2.1, seed=101))
+    X = dense_normal(g.n_cols, 1030, seed=102)
+    Y, _ = gpu_spmm(g, X, mode, pad_x=2, pad_y=6)
+    ref, bound = oracle_pair(g, X)
+    assert_close(Y, ref, bound, TOL_F32)
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_column_count_at_the_documented_limit(mode):
+    """n_cols = 2^27 - 1 (the largest the packed per-non-zero index allows), entries spread over the whole range:
+    exercises the bitmap passes of the big-window unique kernel and 64-bit addressing of X."""
+    n_cols = (1 << 27) - 1
+    rng = np.random.default_rng(111)
+    n_rows = 40
+    lens = np.full(n_rows, 6)
+    lens[0:16] = 400                                   # window 0 beyond the LDS-sort capacity
+    cols = [np.sort(rng.choice(n_cols, size=int(l), replace=False)) for l in lens]
+    cols[17][-1] = n_cols - 1                          # the last column itself
+    cols[18][0] = 0
+    rp = np.zeros(n_rows + 1, np.int32)
+    np.cumsum(lens, out=rp[1:])
+    vals = rng.standard_normal(int(lens.sum())).astype(np.float32)
+    g = CSRGraph(n_rows, n_cols, rp, np.concatenate(cols).astype(np.int32), vals)
+    X = np.zeros((n_cols, 1), dtype=np.float32)        # 512 MiB; only the referenced rows carry values
+    used = np.unique(g.colind)
+    X[used, 0] = rng.standard_normal(used.shape[0]).astype(np.float32)
+    Y, info = gpu_spmm(g, X, mode)
+    ref, bound = oracle_pair(g, X)
+    assert_close(Y, ref, bound, TOL_F32)
+    assert info["n_cols"] == n_cols
