@@ -21,7 +21,7 @@ def sample_rows(g, n, seed):
     order = np.argsort(deg)
     for frac in (0.0, 0.5, 0.9, 0.99, 0.999, 0.9999):
         rows.add(int(order[min(g.n_rows - 1, int(frac * g.n_rows))]))
-    for bound in (256, 257, 1024, 1025, 2048, 2049):
+    for bound in (128, 129, 256, 257, 1024, 1025, 2048, 2049):
         idx = np.nonzero(deg == bound)[0]
         if idx.size:
             rows.add(int(idx[0]))
@@ -106,4 +106,39 @@ def test_c5_layer_and_plan():
     W = info["n_windows"]
     wins = np.unique(np.concatenate([[0, 1, W - 1], np.random.default_rng(4).choice(W, 40)]))
     check_plan_windows(g, arrays, info, wins)
+    plan.destroy()
+
+
+@pytest.mark.parametrize("name,d_out", [("C3", 64), ("C2", 128), ("C4", 32)])
+def test_aggregate_update_fused_at_full_size(name, d_out):
+    """The fused aggregate-then-update launch at sizes where its workgroups are handed out in XCD-local runs:
+    sampled rows of Y = ReLU((A X) W) against the oracle, and the whole Y against the SpMM + GEMM route."""
+    import os
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    from workloads import glorot_uniform
+    g, X, _ = make_config(name)
+    Wm = glorot_uniform(X.shape[1], d_out, seed=77)
+    rp, ci, va = device_graph(g)
+    plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, d_hint=X.shape[1])
+    Xd, Wd = torch.from_numpy(X).cuda(), torch.from_numpy(Wm).cuda()
+    ws = torch.empty(hc.hcspmm_aggregate_update_workspace_bytes(plan, X.shape[1], d_out), dtype=torch.uint8, device="cuda")
+    Y = torch.full((g.n_rows, d_out), float("nan"), device="cuda")
+    hc.hcspmm_aggregate_update(plan, Xd, Wd, Y, ws)
+    torch.cuda.synchronize()
+    rows = sample_rows(g, 300, seed=5)
+    ref = oracle.aggregate_update_rows(rows, g.rowptr, g.colind, g.vals, X, Wm)
+    bound = oracle.aggregate_update_rows(rows, g.rowptr, g.colind, g.vals, X, Wm, use_abs=True)
+    got = Y[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.float64)
+    assert_close(got, ref, bound, 2 * TOL_F32, name)
+    assert torch.isfinite(Y).all()
+    os.environ["HCSPMM_TUNE_NO_FUSE"] = "1"
+    try:
+        Y2 = torch.empty_like(Y)
+        hc.hcspmm_aggregate_update(plan, Xd, Wd, Y2, ws)
+        torch.cuda.synchronize()
+    finally:
+        del os.environ["HCSPMM_TUNE_NO_FUSE"]
+    # same mathematics, different summation order in the update: agree to fp32 rounding of the row sums
+    assert float((Y - Y2).abs().max()) <= 1e-4 * max(1.0, float(Y2.abs().max()))
     plan.destroy()
