@@ -227,7 +227,8 @@ size_t hcspmm_gcn_workspace_bytes(const hcspmm_plan* plan, int32_t d_in, int32_t
 /*
  * Aggregate-then-update layer  Y = act((A X) W)  -- the association of GIN's forward pass and of
  * GCN's backward pass, for which Section V-A describes the coupled kernel (aggregate a window,
- * then multiply its result tile by W).  With fp32 X and d_in a multiple of 16 up to 256 the update
+ * then multiply its result tile by W).  With d_in a multiple of 16 up to 256 (and X aligned for
+ * vector loads) the update
  * is fused into the aggregation kernels: short scalar-path rows and wave-per-window matrix-path
  * tiles stay in LDS and are multiplied by W on the fp32 matrix cores before anything is stored;
  * the remaining rows (long rows, very wide windows) pass through the workspace.  Otherwise, and when

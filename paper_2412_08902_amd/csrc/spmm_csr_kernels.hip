@@ -214,7 +214,7 @@ template <int LPR, int VEC> struct FusedShape {
     static_assert(ROWS % 16 == 0 && (T == 1 || T == 2), "one or two tiles per workgroup");
 };
 
-template <int LPR, int VEC>
+template <int LPR, int VEC, int XK>
 __device__ inline void csr_short_fused_body(int64_t block, int32_t n_items, const int32_t* __restrict__ row_list,
                                             const uint8_t* __restrict__ route, int mid_row, const SpmmArgs& a,
                                             const UpdateArgs& u, float* __restrict__ zt, int32_t* __restrict__ rows_s)
@@ -237,7 +237,8 @@ __device__ inline void csr_short_fused_body(int64_t block, int32_t n_items, cons
     }
     if (lig < RPG) rows_s[gw * RPG + lig] = my_row;
     const char* __restrict__ X = static_cast<const char*>(a.X);
-    const int64_t ldxb = a.ldx * 4;
+    constexpr int ES = XElem<XK>::size;
+    const int64_t ldxb = a.ldx * ES;
     const int c = lig * VEC;
     const bool col_ok = c < a.d;
     float acc[VEC];
@@ -265,7 +266,7 @@ __device__ inline void csr_short_fused_body(int64_t block, int32_t n_items, cons
         int32_t nc;
         float nv;
         fetch_entry(a.colind, a.vals, k + LPR + lig, e, nc, nv);
-        batch_accumulate<LPR, VEC, 0>(mc, mv, min(LPR, e - k), X + (col_ok ? c : 0) * 4, ldxb, acc);
+        batch_accumulate<LPR, VEC, XK>(mc, mv, min(LPR, e - k), X + (col_ok ? c : 0) * ES, ldxb, acc);
         mc = nc;
         mv = nv;
         k += LPR;
@@ -401,7 +402,7 @@ __global__ __launch_bounds__(256) void k_csr(CsrWork wk, SpmmArgs a)
 
 // The same launch with the update stage fused into the short rows; long and mid rows write their
 // aggregated rows to a.Y (the workspace Z) and are finished by k_update_rest.
-template <int LPR, int VEC>
+template <int LPR, int VEC, int XK>
 __global__ __launch_bounds__(256) void k_csr_fused(CsrWork wk, SpmmArgs a, UpdateArgs u)
 {
     using S = FusedShape<LPR, VEC>;
@@ -410,13 +411,13 @@ __global__ __launch_bounds__(256) void k_csr_fused(CsrWork wk, SpmmArgs a, Updat
     __shared__ int32_t rows16[S::ROWS];
     int64_t b = blockIdx.x;
     if (b < wk.n_segs) {
-        csr_long_body<LPR, VEC, 0>(b, wk.segs, wk.partial, red, a);
+        csr_long_body<LPR, VEC, XK>(b, wk.segs, wk.partial, red, a);
         return;
     }
     b -= wk.n_segs;
     const int64_t mid_blocks = wk.mid_blocks;
     if (b < mid_blocks) {
-        csr_mid_body<LPR, VEC, 0>(b, wk.n_mid, wk.mid_rows, a, wk.mid_row);   // the fused tier takes rows up to mid_row
+        csr_mid_body<LPR, VEC, XK>(b, wk.n_mid, wk.mid_rows, a, wk.mid_row);   // the fused tier takes rows up to mid_row
         return;
     }
     b -= mid_blocks;
@@ -424,7 +425,7 @@ __global__ __launch_bounds__(256) void k_csr_fused(CsrWork wk, SpmmArgs a, Updat
         const int64_t x = blockIdx.x & 7, q = b >> 3;
         b = ((q / wk.xcd_chunk) * 8 + x) * wk.xcd_chunk + q % wk.xcd_chunk;
     }
-    csr_short_fused_body<LPR, VEC>(b, wk.n_items, wk.row_list, wk.route, wk.mid_row, a, u, zt, rows16);
+    csr_short_fused_body<LPR, VEC, XK>(b, wk.n_items, wk.row_list, wk.route, wk.mid_row, a, u, zt, rows16);
 }
 
 // ---- rows the fused kernels did not finish: gather their aggregated rows and apply the update ---
@@ -515,10 +516,10 @@ static CsrShape pick_shape(const SpmmArgs& a, const float* partial)
 // float4/float2 and a width that the update's K loop takes 16 at a time.
 bool update_fusable(const SpmmArgs& a)
 {
-    if (a.x_dtype != HCSPMM_F32 || a.d % 16 != 0 || a.d < 16 || a.d > 256) return false;
+    if (a.d % 16 != 0 || a.d < 16 || a.d > 256) return false;
     const CsrShape sh = pick_shape(a, nullptr);
-    return (sh.vec == 4 || sh.vec == 2) && sh.lpr * sh.vec >= a.d && a.ldy % 4 == 0 && (uintptr_t)a.Y % 16 == 0 &&
-           mfma_update_fusable(a);
+    const bool vec_ok = a.x_dtype == HCSPMM_F32 ? (sh.vec == 4 || sh.vec == 2) : (sh.vec == 8 || sh.vec == 4);
+    return vec_ok && sh.lpr * sh.vec >= a.d && a.ldy % 4 == 0 && (uintptr_t)a.Y % 16 == 0 && mfma_update_fusable(a);
 }
 
 hipError_t launch_csr(const SpmmArgs& a, int32_t n_segs, const Segment* segs, float* partial, int32_t n_mid,
@@ -543,18 +544,22 @@ hipError_t launch_csr(const SpmmArgs& a, int32_t n_segs, const Segment* segs, fl
         const int64_t blocks = (int64_t)n_segs + ((int64_t)n_mid + 3) / 4 + short_blocks;
         if (blocks <= 0) return hipSuccess;
         CsrWork wk{n_segs, segs, partial, n_mid, mid_rows, n_items, row_list, route, 0, mid_row, xcd_chunk, ((int64_t)n_mid + 3) / 4, 0};
-#define HC_LAUNCH_CSRF(L, V) hipLaunchKernelGGL((k_csr_fused<L, V>), dim3((unsigned)blocks), dim3(256), 0, s, wk, a, *upd)
-        switch (sh.lpr * 10 + sh.vec) {
-            case 84: HC_LAUNCH_CSRF(8, 4); break;
-            case 164: HC_LAUNCH_CSRF(16, 4); break;
-            case 324: HC_LAUNCH_CSRF(32, 4); break;
-            case 644: HC_LAUNCH_CSRF(64, 4); break;
-            case 82: HC_LAUNCH_CSRF(8, 2); break;
-            case 162: HC_LAUNCH_CSRF(16, 2); break;
-            case 322: HC_LAUNCH_CSRF(32, 2); break;
-            case 642: HC_LAUNCH_CSRF(64, 2); break;
-            default: return hipErrorInvalidValue;
+#define HC_LAUNCH_CSRF(L, V, K) hipLaunchKernelGGL((k_csr_fused<L, V, K>), dim3((unsigned)blocks), dim3(256), 0, s, wk, a, *upd)
+#define HC_CSRF_CASES(V, K)                                                                        \
+    switch (sh.lpr) {                                                                              \
+        case 8: HC_LAUNCH_CSRF(8, V, K); break;                                                    \
+        case 16: HC_LAUNCH_CSRF(16, V, K); break;                                                  \
+        case 32: HC_LAUNCH_CSRF(32, V, K); break;                                                  \
+        default: HC_LAUNCH_CSRF(64, V, K); break;                                                  \
+    }
+        if (a.x_dtype == HCSPMM_F32) {
+            if (sh.vec == 4) { HC_CSRF_CASES(4, 0) } else if (sh.vec == 2) { HC_CSRF_CASES(2, 0) } else return hipErrorInvalidValue;
+        } else if (a.x_dtype == HCSPMM_BF16) {
+            if (sh.vec == 8) { HC_CSRF_CASES(8, 1) } else if (sh.vec == 4) { HC_CSRF_CASES(4, 1) } else return hipErrorInvalidValue;
+        } else {
+            if (sh.vec == 8) { HC_CSRF_CASES(8, 2) } else if (sh.vec == 4) { HC_CSRF_CASES(4, 2) } else return hipErrorInvalidValue;
         }
+#undef HC_CSRF_CASES
 #undef HC_LAUNCH_CSRF
         return hipGetLastError();
     }

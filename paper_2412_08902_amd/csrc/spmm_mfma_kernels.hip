@@ -517,7 +517,7 @@ bool mfma_shape_supported(const SpmmArgs& a)
 bool mfma_update_fusable(const SpmmArgs& a)
 {
     MfmaShape sh;
-    return a.x_dtype == HCSPMM_F32 && pick_mfma_shape(a, sh) && sh.ng * 16 * sh.vw >= a.d;
+    return pick_mfma_shape(a, sh) && sh.ng * 16 * sh.vw >= a.d;
 }
 
 #define HC_MFMA_DISPATCH(FN)                                                                       \
@@ -567,20 +567,10 @@ hipError_t launch_mfma_small(const SpmmArgs& a, int32_t n_list, const WinDesc* d
         else xcd_chunk = 0;
     }
     if (upd) {
-        if (a.x_dtype != HCSPMM_F32 || span < a.d) return hipErrorInvalidValue;
+        if (span < a.d) return hipErrorInvalidValue;
         const dim3 grid((unsigned)n_blocks);
-#define HC_LAUNCH_MSF(V, G) hipLaunchKernelGGL((k_mfma_small<0, V, G, true>), grid, dim3(256), 0, s, n_list, desc, wcols, erc, 0, xcd_chunk, a, *upd)
-        switch (sh.vw * 10 + sh.ng) {
-            case 41: HC_LAUNCH_MSF(4, 1); break;
-            case 42: HC_LAUNCH_MSF(4, 2); break;
-            case 44: HC_LAUNCH_MSF(4, 4); break;
-            case 21: HC_LAUNCH_MSF(2, 1); break;
-            case 22: HC_LAUNCH_MSF(2, 2); break;
-            case 24: HC_LAUNCH_MSF(2, 4); break;
-            case 11: HC_LAUNCH_MSF(1, 1); break;
-            case 12: HC_LAUNCH_MSF(1, 2); break;
-            default: HC_LAUNCH_MSF(1, 4); break;
-        }
+#define HC_LAUNCH_MSF(K, V, G) hipLaunchKernelGGL((k_mfma_small<K, V, G, true>), grid, dim3(256), 0, s, n_list, desc, wcols, erc, 0, xcd_chunk, a, *upd)
+        HC_MFMA_DISPATCH(HC_LAUNCH_MSF)
 #undef HC_LAUNCH_MSF
         return hipGetLastError();
     }

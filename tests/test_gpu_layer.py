@@ -216,3 +216,31 @@ def test_aggregate_update_fused_community_graph_with_empty_rows():
         bound = oracle.aggregate_update(g.rowptr, g.colind, g.vals, X, W, use_abs=True)
         assert_close(got, ref, bound, 2 * TOL_F32)
         assert np.all(got[32:48] == 0.0) and np.all(got[5] == 0.0)
+
+
+@pytest.mark.parametrize("kind", ["bf16", "f16"])
+@pytest.mark.parametrize("mode", [0, 1, 2, 3])
+@pytest.mark.parametrize("din,dout", [(32, 48), (64, 64), (128, 32), (256, 130), (80, 16)])
+def test_aggregate_update_fused_16bit_x(kind, mode, din, dout, monkeypatch):
+    """16-bit X through the fused update (fp32 tile in LDS, fp32 update): scalar path exact widening, matrix
+    path 16-bit products; hub rows and wide windows go through the workspace."""
+    monkeypatch.setenv("HCSPMM_TUNE_FORCE_FUSE", "1")
+    from workloads import to_bf16_bits, to_f16_bits
+    g = gcn_normalise(chung_lu_graph(3003, 150000, 2.0, seed=171, max_degree=2800))
+    X, W = dense_normal(g.n_cols, din, seed=172), glorot_uniform(din, dout, seed=173)
+    Xb = to_bf16_bits(X) if kind == "bf16" else to_f16_bits(X)
+    code = oracle.DT_BF16 if kind == "bf16" else oracle.DT_F16
+    import paper_2412_08902_amd.binding as hc
+    import torch
+    rp, ci, va = device_graph(g)
+    plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, route_mode=mode, d_hint=din,
+                             mfma_dtype=1 if kind == "bf16" else 2, sel_coef=[1, 0, -300] if mode == 3 else None)
+    ws = torch.empty(hc.hcspmm_aggregate_update_workspace_bytes(plan, din, dout), dtype=torch.uint8, device="cuda")
+    Y = torch.full((g.n_rows, dout), -3.0, device="cuda")
+    Xd = torch.from_numpy(Xb.view(np.int16)).cuda().view(torch.bfloat16 if kind == "bf16" else torch.float16)
+    hc.hcspmm_aggregate_update(plan, Xd, torch.from_numpy(W).cuda(), Y, ws, apply_relu=False)
+    torch.cuda.synchronize()
+    plan.destroy()
+    ref = oracle.aggregate_update(g.rowptr, g.colind, g.vals, Xb, W, relu=False, x_dtype=code)
+    bound = oracle.aggregate_update(g.rowptr, g.colind, g.vals, Xb, W, x_dtype=code, use_abs=True)
+    assert_close(Y.cpu().numpy().astype(np.float64), ref, bound, 2e-2 if mode != 1 else 2 * TOL_F32)
