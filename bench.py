@@ -73,6 +73,8 @@ def main():
     ap.add_argument("--x-dtype", default="f32", choices=["f32", "bf16", "f16"], help="storage type of X")
     ap.add_argument("--layer", action="store_true",
                     help="C5 only: time the whole GCN layer Y = ReLU(A (X W)) (GEMM + hybrid SpMM) instead of the SpMM")
+    ap.add_argument("--t-dtype", default="f32", choices=["f32", "bf16", "f16"],
+                    help="with --layer: storage type of the intermediate X W (f32 is the headline layer)")
     ap.add_argument("--sel-coef", default=None, help="three comma-separated integers overriding the shipped selector")
     ap.add_argument("--agg-update", type=int, default=None, metavar="D_OUT",
                     help="also time the aggregate-then-update layer Y = ReLU((A X) W) with a d x D_OUT W, with the "
@@ -211,8 +213,16 @@ def main():
         Tg = torch.empty((g.n_rows, d), dtype=torch.float32, device=dev)
         ms_gemm = time_steps(lambda: hc.hcspmm_gemm_f32(Xin_d, Wd, Tg), args.steps, args.warmup, torch)
         ms_layer = time_steps(lambda: hc.hcspmm_gcn_layer(plan, Xin_d, Wd, Yd, ws), args.steps, args.warmup, torch)
+        if args.t_dtype != "f32":
+            code = hc.HCSPMM_BF16 if args.t_dtype == "bf16" else hc.HCSPMM_F16
+            plan16 = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, d_hint=d, mfma_dtype=code)
+            ms16 = time_steps(lambda: hc.hcspmm_gcn_layer_ex(plan16, Xin_d, Wd, Yd, ws, t_dtype=code), args.steps,
+                              args.warmup, torch)
+            plan16.destroy()
+            log("layer with %s intermediate: %.3f ms" % (args.t_dtype, ms16))
         gemm_flops = 2.0 * g.n_rows * X_in.shape[1] * d
         out["layer"] = dict(ms_per_layer=round(ms_layer, 5), ms_gemm=round(ms_gemm, 5),
+                            **({"ms_per_layer_%s_intermediate" % args.t_dtype: round(ms16, 5)} if args.t_dtype != "f32" else {}),
                             gemm_tflops=round(gemm_flops / (ms_gemm * 1e-3) / 1e12, 2),
                             gemm_frac_of_fp32_mfma_peak=round(gemm_flops / (ms_gemm * 1e-3) / 157.3e12, 4),
                             total_gflops=round((gemm_flops + flops) / (ms_layer * 1e-3) / 1e9, 1))

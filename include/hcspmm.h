@@ -222,6 +222,21 @@ hcspmm_status hcspmm_gcn_layer(const hcspmm_plan* plan, const void* d_X, int64_t
                                void* d_Y, int64_t ldy, int32_t apply_relu,
                                void* d_workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * The same layer with the intermediate T = X W stored as t_dtype: HCSPMM_F32 is hcspmm_gcn_layer;
+ * HCSPMM_BF16 / HCSPMM_F16 round the fp32 MFMA accumulators of the update once (nearest even) and
+ * let the aggregation gather half the bytes, with the arithmetic hcspmm_spmm documents for a
+ * 16-bit X (the plan should then have been prepared with mfma_dtype = t_dtype, which selects the
+ * selector coefficients fitted for 16-bit gathers).  X, W and Y stay fp32; the workspace
+ * requirement is that of hcspmm_gcn_workspace_bytes.  HCSPMM_EUNSUPPORTED when the plan has
+ * matrix-path windows and d_out / ldy do not fit the 16-bit matrix-path kernels (d_out % 4,
+ * 16-byte aligned Y rows).
+ */
+hcspmm_status hcspmm_gcn_layer_ex(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d_in,
+                                  const void* d_W, int64_t ldw, int32_t d_out,
+                                  void* d_Y, int64_t ldy, int32_t apply_relu, int32_t t_dtype,
+                                  void* d_workspace, size_t workspace_bytes, void* stream);
+
 size_t hcspmm_gcn_workspace_bytes(const hcspmm_plan* plan, int32_t d_in, int32_t d_out);
 
 /*

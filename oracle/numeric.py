@@ -123,10 +123,29 @@ def gemm(X, W, rows=None, x_dtype: Optional[int] = None, w_dtype: Optional[int] 
     return T
 
 
-def gcn_layer(rowptr, colind, vals, X, W, relu: bool = True, use_abs: bool = False) -> np.ndarray:
-    """fp64 Y = ReLU(A (X W)): full dense product first, then the CSR loop, then max(0, .)."""
+def round_to_16bit(T: np.ndarray, dtype_code: int) -> np.ndarray:
+    """Bit patterns (uint16) of T rounded to bf16 / fp16, nearest even, through fp32 as the device does
+    (its accumulators are fp32).  Finite inputs."""
+    t32 = np.ascontiguousarray(T, dtype=np.float32)
+    if dtype_code == DT_F16:
+        return t32.astype(np.float16).view(np.uint16)
+    assert dtype_code == DT_BF16
+    u = t32.view(np.uint32).astype(np.uint64)
+    u = u + 0x7FFF + ((u >> 16) & 1)
+    return (u >> 16).astype(np.uint16)
+
+
+def gcn_layer(rowptr, colind, vals, X, W, relu: bool = True, use_abs: bool = False,
+              t_dtype: Optional[int] = None) -> np.ndarray:
+    """fp64 Y = ReLU(A (X W)): full dense product first, then the CSR loop, then max(0, .).
+
+    t_dtype = DT_BF16 / DT_F16: the intermediate X W is rounded once to that type before the CSR loop
+    (the layer variant that stores it in 16 bits); the magnitude bound (use_abs) is not rounded."""
     T = gemm(X, W, use_abs=use_abs)
-    Y = spmm(rowptr, colind, vals, T, DT_F64, use_abs=use_abs)
+    if t_dtype in (DT_BF16, DT_F16) and not use_abs:
+        Y = spmm(rowptr, colind, vals, round_to_16bit(T, t_dtype), t_dtype, use_abs=use_abs)
+    else:
+        Y = spmm(rowptr, colind, vals, T, DT_F64, use_abs=use_abs)
     if relu and not use_abs:
         Y = np.maximum(Y, 0.0)
     return Y

@@ -19,7 +19,7 @@ HCSPMM_ROUTE_HYBRID, HCSPMM_ROUTE_ALL_CSR, HCSPMM_ROUTE_ALL_MFMA, HCSPMM_ROUTE_P
 
 EXPORTED_SYMBOLS = [
     "hcspmm_default_options", "hcspmm_default_selector", "hcspmm_prepare", "hcspmm_plan_info",
-    "hcspmm_plan_export", "hcspmm_spmm", "hcspmm_spmm_timed", "hcspmm_gcn_layer", "hcspmm_gcn_workspace_bytes",
+    "hcspmm_plan_export", "hcspmm_spmm", "hcspmm_spmm_timed", "hcspmm_gcn_layer", "hcspmm_gcn_layer_ex", "hcspmm_gcn_workspace_bytes",
     "hcspmm_aggregate_update", "hcspmm_aggregate_update_workspace_bytes",
     "hcspmm_gemm_f32", "hcspmm_loa_order", "hcspmm_permute_csr", "hcspmm_plan_destroy", "hcspmm_status_string", "hcspmm_last_error", "hcspmm_version",
 ]
@@ -85,6 +85,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.hcspmm_spmm_timed.restype = ctypes.c_int
     lib.hcspmm_gcn_layer.argtypes = [vp, vp, i64, i32, vp, i64, i32, vp, i64, i32, vp, ctypes.c_size_t, vp]
     lib.hcspmm_gcn_layer.restype = ctypes.c_int
+    lib.hcspmm_gcn_layer_ex.argtypes = [vp, vp, i64, i32, vp, i64, i32, vp, i64, i32, i32, vp, ctypes.c_size_t, vp]
+    lib.hcspmm_gcn_layer_ex.restype = ctypes.c_int
     lib.hcspmm_gcn_workspace_bytes.argtypes = [vp, i32, i32]
     lib.hcspmm_gcn_workspace_bytes.restype = ctypes.c_size_t
     lib.hcspmm_aggregate_update.argtypes = [vp, vp, i64, i32, i32, vp, i64, i32, vp, i64, i32, vp, ctypes.c_size_t, vp]
@@ -267,6 +269,16 @@ def hcspmm_aggregate_update(plan: Plan, X, W, Y, workspace, *, apply_relu: bool 
                                                   _ptr(W), W.stride(0), W.shape[1], _ptr(Y), Y.stride(0),
                                                   1 if apply_relu else 0, _ptr(workspace),
                                                   workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
+    return Y
+
+
+def hcspmm_gcn_layer_ex(plan: Plan, X, W, Y, workspace, *, t_dtype: int = HCSPMM_F32, apply_relu: bool = True, stream=None):
+    """Y = act(A (X W)) with the intermediate X W stored as t_dtype (HCSPMM_F32 / BF16 / F16)."""
+    assert X.stride(1) == 1 and W.stride(1) == 1 and Y.stride(1) == 1
+    _check(load_library().hcspmm_gcn_layer_ex(plan.handle, _ptr(X), X.stride(0), X.shape[1], _ptr(W), W.stride(0),
+                                              W.shape[1], _ptr(Y), Y.stride(0), 1 if apply_relu else 0, t_dtype,
+                                              _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                              _stream_ptr(stream)))
     return Y
 
 

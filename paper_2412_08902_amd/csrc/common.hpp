@@ -143,6 +143,9 @@ hipError_t launch_reduce_tiles(const SpmmArgs& a, int32_t n_multi, const MultiRo
                                hipStream_t s);
 hipError_t launch_gemm_f32(int64_t m, int32_t k, int32_t n, const float* X, int64_t ldx, const float* W, int64_t ldw,
                            float* T, int64_t ldt, int relu, hipStream_t s);
+// same product with the output stored as t_dtype (fp32, or bf16 / fp16 rounded from the fp32 accumulators)
+hipError_t launch_gemm_f32_out(int64_t m, int32_t k, int32_t n, const float* X, int64_t ldx, const float* W, int64_t ldw,
+                               void* T, int64_t ldt, int32_t t_dtype, int relu, hipStream_t s);
 
 }  // namespace hcspmm
 

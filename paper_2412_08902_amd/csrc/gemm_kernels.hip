@@ -19,10 +19,11 @@ constexpr int LDB_S = BN + 4;
 
 // XV: floats per global load of X (4, 2 or 1, by alignment of ldx); W rows are read one float at a
 // time per lane and 64 lanes wide (always coalesced).
-template <int XV>
+// TK: element kind of the output -- 0 fp32, 1 bf16 (round to nearest even), 2 fp16.
+template <int XV, int TK = 0>
 __global__ __launch_bounds__(256) void k_gemm_f32(int64_t M, int32_t K, int32_t N, const float* __restrict__ X,
                                                   int64_t ldx, const float* __restrict__ Wm, int64_t ldw,
-                                                  float* __restrict__ T, int64_t ldt, int relu)
+                                                  void* __restrict__ Tv, int64_t ldt, int relu)
 {
     __shared__ float As[BK * LDA_S];
     __shared__ float Bs[BK * LDB_S];
@@ -113,7 +114,17 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int64_t M, int32_t K, int32_t 
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int64_t row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * lk + (v & 3);
-                if (row < M) T[row * ldt + col] = relu ? fmaxf(acc[i][j][v], 0.f) : acc[i][j][v];
+                if (row >= M) continue;
+                const float y = relu ? fmaxf(acc[i][j][v], 0.f) : acc[i][j][v];
+                if constexpr (TK == 0) {
+                    static_cast<float*>(Tv)[row * ldt + col] = y;
+                } else if constexpr (TK == 1) {
+                    uint32_t u = __float_as_uint(y);
+                    u += 0x7fffu + ((u >> 16) & 1u);                 // round to nearest even (finite values)
+                    static_cast<unsigned short*>(Tv)[row * ldt + col] = (unsigned short)(u >> 16);
+                } else {
+                    static_cast<_Float16*>(Tv)[row * ldt + col] = (_Float16)y;
+                }
             }
         }
 }
@@ -121,15 +132,24 @@ __global__ __launch_bounds__(256) void k_gemm_f32(int64_t M, int32_t K, int32_t 
 hipError_t launch_gemm_f32(int64_t m, int32_t k, int32_t n, const float* X, int64_t ldx, const float* W, int64_t ldw,
                            float* T, int64_t ldt, int relu, hipStream_t s)
 {
+    return launch_gemm_f32_out(m, k, n, X, ldx, W, ldw, T, ldt, HCSPMM_F32, relu, s);
+}
+
+hipError_t launch_gemm_f32_out(int64_t m, int32_t k, int32_t n, const float* X, int64_t ldx, const float* W, int64_t ldw,
+                               void* T, int64_t ldt, int32_t t_dtype, int relu, hipStream_t s)
+{
     if (m <= 0 || n <= 0) return hipSuccess;
     dim3 grid((unsigned)((m + BM - 1) / BM), (unsigned)((n + BN - 1) / BN));
     const uintptr_t px = (uintptr_t)X;
-    if (ldx % 4 == 0 && px % 16 == 0)
-        hipLaunchKernelGGL((k_gemm_f32<4>), grid, dim3(256), 0, s, m, k, n, X, ldx, W, ldw, T, ldt, relu);
-    else if (ldx % 2 == 0 && px % 8 == 0)
-        hipLaunchKernelGGL((k_gemm_f32<2>), grid, dim3(256), 0, s, m, k, n, X, ldx, W, ldw, T, ldt, relu);
-    else
-        hipLaunchKernelGGL((k_gemm_f32<1>), grid, dim3(256), 0, s, m, k, n, X, ldx, W, ldw, T, ldt, relu);
+    const int xv = (ldx % 4 == 0 && px % 16 == 0) ? 4 : ((ldx % 2 == 0 && px % 8 == 0) ? 2 : 1);
+#define HC_LAUNCH_GEMM(V, TK) hipLaunchKernelGGL((k_gemm_f32<V, TK>), grid, dim3(256), 0, s, m, k, n, X, ldx, W, ldw, T, ldt, relu)
+#define HC_GEMM_XV(TK) if (xv == 4) HC_LAUNCH_GEMM(4, TK); else if (xv == 2) HC_LAUNCH_GEMM(2, TK); else HC_LAUNCH_GEMM(1, TK)
+    if (t_dtype == HCSPMM_F32) { HC_GEMM_XV(0); }
+    else if (t_dtype == HCSPMM_BF16) { HC_GEMM_XV(1); }
+    else if (t_dtype == HCSPMM_F16) { HC_GEMM_XV(2); }
+    else return hipErrorInvalidValue;
+#undef HC_GEMM_XV
+#undef HC_LAUNCH_GEMM
     return hipGetLastError();
 }
 

@@ -744,24 +744,36 @@ hcspmm_status hcspmm_gcn_layer(const hcspmm_plan* plan, const void* d_X, int64_t
                                int64_t ldw, int32_t d_out, void* d_Y, int64_t ldy, int32_t apply_relu,
                                void* d_workspace, size_t workspace_bytes, void* stream)
 {
+    return hcspmm_gcn_layer_ex(plan, d_X, ldx, d_in, d_W, ldw, d_out, d_Y, ldy, apply_relu, HCSPMM_F32, d_workspace,
+                               workspace_bytes, stream);
+}
+
+hcspmm_status hcspmm_gcn_layer_ex(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d_in, const void* d_W,
+                                  int64_t ldw, int32_t d_out, void* d_Y, int64_t ldy, int32_t apply_relu, int32_t t_dtype,
+                                  void* d_workspace, size_t workspace_bytes, void* stream)
+{
     if (!plan) { set_error("plan is NULL"); return HCSPMM_EINVAL; }
     if (d_in < 1 || d_out < 1 || d_in > (1 << 20) || d_out > (1 << 20)) { set_error("d_in, d_out must be in [1, 2^20]"); return HCSPMM_EINVAL; }
+    if (t_dtype != HCSPMM_F32 && t_dtype != HCSPMM_BF16 && t_dtype != HCSPMM_F16) { set_error("t_dtype %d is not a dtype code", t_dtype); return HCSPMM_EINVAL; }
     hcspmm_status st;
     if ((st = check_dense("X", d_X, ldx, d_in)) != HCSPMM_OK) return st;
     if ((st = check_dense("W", d_W, ldw, d_out)) != HCSPMM_OK) return st;
     if ((st = check_dense("Y", d_Y, ldy, d_out)) != HCSPMM_OK) return st;
-    const size_t need = hcspmm_gcn_workspace_bytes(plan, d_in, d_out);
+    const size_t need = hcspmm_gcn_workspace_bytes(plan, d_in, d_out);      // sized for fp32 T; 16-bit T uses half of it
     if (!d_workspace || workspace_bytes < need) { set_error("workspace too small: need %zu bytes", need); return HCSPMM_EINVAL; }
     if (((uintptr_t)d_workspace & 255) != 0) { set_error("workspace must be 256-byte aligned"); return HCSPMM_EINVAL; }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    float* T = static_cast<float*>(d_workspace);
-    HC_HIP(launch_gemm_f32(plan->n_cols, d_in, d_out, static_cast<const float*>(d_X), ldx,
-                           static_cast<const float*>(d_W), ldw, T, d_out, 0, s));
-    if (plan->n_rows == 0) return HCSPMM_OK;
     SpmmArgs a;
     a.n_rows = plan->n_rows; a.rowptr = plan->rowptr; a.colind = plan->colind; a.vals = plan->vals;
-    a.X = T; a.ldx = d_out; a.d = d_out; a.x_dtype = HCSPMM_F32; a.Y = static_cast<float*>(d_Y); a.ldy = ldy;
+    a.X = d_workspace; a.ldx = d_out; a.d = d_out; a.x_dtype = t_dtype; a.Y = static_cast<float*>(d_Y); a.ldy = ldy;
     a.relu = apply_relu ? 1 : 0;
+    if (t_dtype != HCSPMM_F32 && plan->n_mfma > 0 && !mfma_shape_supported(a)) {
+        set_error("the matrix path with 16-bit T needs d_out a multiple of 4 and 16-byte aligned Y rows");
+        return HCSPMM_EUNSUPPORTED;
+    }
+    HC_HIP(launch_gemm_f32_out(plan->n_cols, d_in, d_out, static_cast<const float*>(d_X), ldx,
+                               static_cast<const float*>(d_W), ldw, d_workspace, d_out, t_dtype, 0, s));
+    if (plan->n_rows == 0) return HCSPMM_OK;
     return run_spmm(plan, a, s);
 }
 

@@ -244,3 +244,30 @@ def test_aggregate_update_fused_16bit_x(kind, mode, din, dout, monkeypatch):
     ref = oracle.aggregate_update(g.rowptr, g.colind, g.vals, Xb, W, relu=False, x_dtype=code)
     bound = oracle.aggregate_update(g.rowptr, g.colind, g.vals, Xb, W, x_dtype=code, use_abs=True)
     assert_close(Y.cpu().numpy().astype(np.float64), ref, bound, 2e-2 if mode != 1 else 2 * TOL_F32)
+
+
+@pytest.mark.parametrize("kind,code", [("bf16", 1), ("f16", 2)])
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_layer_with_16bit_intermediate(kind, code, mode):
+    """Y = act(A (X W)) with X W stored in 16 bits: against the oracle that rounds the intermediate once."""
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    from workloads import sbm_graph
+    g = sbm_graph(20, 64, 0.4, 3.0, seed=181) if mode == 2 else gcn_normalise(chung_lu_graph(2000, 40000, 2.0, seed=182, max_degree=900))
+    X, W = dense_normal(g.n_cols, 70, seed=183), glorot_uniform(70, 64, seed=184)
+    rp, ci, va = device_graph(g)
+    plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, route_mode=mode, d_hint=64, mfma_dtype=code)
+    ws = torch.empty(hc.hcspmm_gcn_workspace_bytes(plan, 70, 64), dtype=torch.uint8, device="cuda")
+    Y = torch.full((g.n_rows, 64), -3.0, device="cuda")
+    hc.hcspmm_gcn_layer_ex(plan, torch.from_numpy(X).cuda(), torch.from_numpy(W).cuda(), Y, ws, t_dtype=code)
+    torch.cuda.synchronize()
+    plan.destroy()
+    ocode = oracle.DT_BF16 if kind == "bf16" else oracle.DT_F16
+    ref = oracle.gcn_layer(g.rowptr, g.colind, g.vals, X, W, t_dtype=ocode)
+    bound = oracle.gcn_layer(g.rowptr, g.colind, g.vals, X, W, use_abs=True)
+    # one 16-bit rounding of the intermediate (the device rounds its fp32 sums, the oracle its fp64 sums: they may
+    # land on neighbouring 16-bit values) plus the 16-bit matrix path: the 2e-2 gate of the 16-bit paths
+    assert_close(Y.cpu().numpy().astype(np.float64), ref, bound, 2e-2)
+    # and it is not the fp32 layer in disguise: the rounding is visible
+    exact = oracle.gcn_layer(g.rowptr, g.colind, g.vals, X, W)
+    assert np.abs(Y.cpu().numpy() - exact).max() > 1e-5 * np.abs(exact).max()

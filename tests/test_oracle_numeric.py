@@ -237,3 +237,26 @@ def test_aggregate_update_pins():
     from workloads import bf16_bits_to_f32
     np.testing.assert_allclose(Yb, np.maximum((A @ bf16_bits_to_f32(Xb).astype(np.float64)) @ W.astype(np.float64), 0.0),
                                atol=1e-12)
+
+
+def test_layer_with_16bit_intermediate():
+    """Rounding the intermediate once: the result differs from the exact layer by at most the 16-bit unit
+    roundoff times the magnitude bound, and equals the exact layer when X W is representable."""
+    n, din, dout = 64, 9, 6
+    g = gcn_normalise(chung_lu_graph(n, 380, 2.1, seed=34))
+    X, W = dense_normal(n, din, 35), dense_normal(din, dout, 36)
+    exact = oracle.gcn_layer(g.rowptr, g.colind, g.vals, X, W, relu=False)
+    bound = oracle.gcn_layer(g.rowptr, g.colind, g.vals, X, W, use_abs=True)
+    for code, u in ((oracle.DT_BF16, 2.0 ** -8), (oracle.DT_F16, 2.0 ** -11)):
+        got = oracle.gcn_layer(g.rowptr, g.colind, g.vals, X, W, relu=False, t_dtype=code)
+        assert np.all(np.abs(got - exact) <= 1.01 * u * bound) and np.any(got != exact)
+    # small integers survive both 16-bit formats: no difference at all
+    Xi = np.round(X * 2).astype(np.float32)
+    Wi = np.round(W * 2).astype(np.float32)
+    gi = chung_lu_graph(n, 380, 2.1, seed=34)            # values 1
+    np.testing.assert_array_equal(oracle.gcn_layer(gi.rowptr, gi.colind, gi.vals, Xi, Wi, t_dtype=oracle.DT_BF16),
+                                  oracle.gcn_layer(gi.rowptr, gi.colind, gi.vals, Xi, Wi))
+    # the rounding itself: ties to even on the bf16 grid
+    from oracle.numeric import round_to_16bit
+    t = np.array([[1.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -2.5, 0.0]], dtype=np.float64)
+    assert round_to_16bit(t, oracle.DT_BF16).tolist() == [[0x3F80, 0x3F80, 0x3F82, 0xC020, 0x0000]]
