@@ -29,7 +29,7 @@ constexpr int kKcBig = 1024;           // condensed columns staged per workgroup
 constexpr int kSliceCols = 4096;       // condensed columns per workgroup; wider windows are cut into slices
 
 // ---- scalar path -------------------------------------------------------------------------------
-constexpr int kRowsPerGroup = 8;       // consecutive rows walked by one lane group (short rows)
+constexpr int kRowsPerGroup = 8;       // most consecutive rows one lane group may walk (short rows); also the narrowest group
 constexpr int kMidRow = 128;           // rows with more non-zeros than this get a whole wave
 constexpr int kFusedMidRow = 256;      // with the update stage fused in, rows up to this length stay in the workgroup's tile
 constexpr int kLongRow = 1024;         // rows with more non-zeros than this are cut into workgroup-sized segments

@@ -8,7 +8,8 @@
 // LPR at a time with one coalesced load per group and handed round with cross-lane reads; X is
 // read directly from global memory / L2 (the paper found staging X in shared memory a loss on
 // this path).  Three tiers by row length balance power-law degree distributions:
-//   short rows  a lane group walks up to kRowsPerGroup consecutive rows in one flattened loop;
+//   short rows  a lane group walks one to four consecutive rows in one flattened loop, and the
+//               workgroups reach the XCDs in runs so that neighbouring rows share an L2;
 //   mid rows    one wave per row, the groups stride over the row and combine with cross-lane adds;
 //   long rows   one workgroup per segment of kSegLen non-zeros, combined through LDS in a fixed
 //               order (and, for rows of several segments, through partial rows in memory).
