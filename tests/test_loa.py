@@ -73,3 +73,19 @@ def test_bad_arguments():
     rp[5] = rp[6] + 1
     with pytest.raises(hc.HcspmmError):
         lib_order(rp, g.colind, g.n_cols, 4)
+
+
+def test_random_structures_match_oracle():
+    """Many small random structures (unsorted rows, duplicates, empty rows, rectangular), several window sizes."""
+    from hypothesis import given, settings, strategies as st
+    from test_oracle_properties import csr_structures
+
+    @settings(max_examples=80, deadline=None)
+    @given(csr_structures(), st.integers(0, 40), st.integers(1, 16))
+    def check(csr, vw, window_rows):
+        n_rows, n_cols, rowptr, colind = csr
+        want = oracle_loa.loa_order(rowptr, colind, vw, window_rows=window_rows)
+        got = lib_order(rowptr, colind, n_cols, vw, window_rows)
+        np.testing.assert_array_equal(got, want)
+
+    check()
