@@ -129,3 +129,35 @@ def test_errors_are_status_codes():
     hc.hcspmm_spmm(plan, X, Y)                                    # still usable after an error
     torch.cuda.synchronize()
     plan.destroy()
+
+
+def test_random_structures_plan_and_product():
+    """Randomised small structures (hypothesis): unsorted rows, duplicates, empty rows and windows, ragged last
+    window, random selector coefficients and widths -- plan arrays bit-exact, product within the fp32 gate."""
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    from hypothesis import given, settings, strategies as st
+    from test_oracle_properties import csr_structures
+    from gpu_util import assert_close
+
+    @settings(max_examples=40, deadline=None)
+    @given(csr_structures(), st.integers(0, 40), st.integers(0, 2 ** 21), st.integers(-2 ** 21, -1), st.sampled_from([0, 3]),
+           st.sampled_from([1, 3, 8, 16, 33, 64, 130]), st.integers(0, 2 ** 31 - 1))
+    def check(csr, c0, c1, c2, mode, d, seed):
+        n_rows, n_cols, rowptr, colind = csr
+        rng = np.random.default_rng(seed)
+        vals = rng.standard_normal(len(colind)).astype(np.float32)
+        g = CSRGraph(n_rows, n_cols, rowptr, colind, vals)
+        got, info = check_plan(g, mode=mode, sel_coef=[c0, c1, c2], d_hint=d)
+        X = rng.standard_normal((n_cols, d)).astype(np.float32)
+        rp, ci, va = device_graph(g)
+        plan = hc.hcspmm_prepare(n_rows, n_cols, rp, ci, va, route_mode=mode, sel_coef=[c0, c1, c2], d_hint=d)
+        Y = torch.full((n_rows, d), float("nan"), device="cuda")
+        hc.hcspmm_spmm(plan, torch.from_numpy(X).cuda(), Y)
+        torch.cuda.synchronize()
+        plan.destroy()
+        ref = oracle.spmm(rowptr, colind, vals, X)
+        bound = oracle.spmm(rowptr, colind, vals, X, use_abs=True)
+        assert_close(Y.cpu().numpy().astype(np.float64), ref, bound, 1e-5)
+
+    check()
