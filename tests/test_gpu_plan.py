@@ -140,7 +140,10 @@ def test_random_structures_plan_and_product():
     from test_oracle_properties import csr_structures
     from gpu_util import assert_close
 
-    @settings(max_examples=40, deadline=None, derandomize=True)
+    import os
+    n_examples = int(os.environ.get("HCSPMM_TEST_EXAMPLES", "40"))      # a larger, non-derandomised hunt on request
+
+    @settings(max_examples=n_examples, deadline=None, derandomize=(n_examples == 40))
     @given(csr_structures(), st.integers(0, 40), st.integers(0, 2 ** 21), st.integers(-2 ** 21, -1), st.sampled_from([0, 3]),
            st.sampled_from([1, 3, 8, 16, 33, 64, 130]), st.integers(0, 2 ** 31 - 1))
     def check(csr, c0, c1, c2, mode, d, seed):
@@ -159,5 +162,61 @@ def test_random_structures_plan_and_product():
         ref = oracle.spmm(rowptr, colind, vals, X)
         bound = oracle.spmm(rowptr, colind, vals, X, use_abs=True)
         assert_close(Y.cpu().numpy().astype(np.float64), ref, bound, 1e-5)
+
+    check()
+
+
+def test_random_skewed_structures_plan_product_and_layer():
+    """Seeded random structures with heavy-tailed row lengths (rows of every tier, windows of every width class,
+    unsorted rows, duplicates): plan bit-exact; SpMM and the fused aggregate-then-update layer within the gates."""
+    import os
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    from hypothesis import given, settings, strategies as st
+    from gpu_util import assert_close
+    from workloads import glorot_uniform
+    n_examples = int(os.environ.get("HCSPMM_TEST_EXAMPLES", "25"))
+
+    @settings(max_examples=n_examples, deadline=None, derandomize=(n_examples == 25))
+    @given(st.integers(0, 2 ** 31 - 1), st.integers(1, 260), st.integers(1, 6000), st.sampled_from([0, 1, 2, 3]),
+           st.sampled_from([16, 32, 48, 64, 128, 256, 20, 7]), st.sampled_from([1, 16, 40, 64]), st.booleans())
+    def check(seed, n_rows, n_cols, mode, d, d_out, sort_rows):
+        rng = np.random.default_rng(seed)
+        lens = np.minimum((rng.pareto(0.9, n_rows) * 3).astype(np.int64), 3500)
+        lens[rng.random(n_rows) < 0.1] = 0
+        cols = []
+        for l in lens:
+            c = rng.integers(0, n_cols, size=int(l))
+            cols.append(np.sort(c) if sort_rows else c)
+        rowptr = np.zeros(n_rows + 1, dtype=np.int32)
+        np.cumsum(lens, out=rowptr[1:])
+        colind = (np.concatenate(cols) if lens.sum() else np.empty(0)).astype(np.int32)
+        vals = rng.standard_normal(len(colind)).astype(np.float32)
+        g = CSRGraph(n_rows, n_cols, rowptr, colind, vals)
+        coef = [int(rng.integers(0, 64)), int(rng.integers(0, 2 ** 21)), -int(rng.integers(1, 2 ** 21))]
+        check_plan(g, mode=mode, sel_coef=coef, d_hint=d)
+        X = rng.standard_normal((n_cols, d)).astype(np.float32)
+        rp, ci, va = device_graph(g)
+        plan = hc.hcspmm_prepare(n_rows, n_cols, rp, ci, va, route_mode=mode, sel_coef=coef, d_hint=d)
+        Xd = torch.from_numpy(X).cuda()
+        Y = torch.full((n_rows, d), float("nan"), device="cuda")
+        hc.hcspmm_spmm(plan, Xd, Y)
+        torch.cuda.synchronize()
+        ref = oracle.spmm(rowptr, colind, vals, X)
+        bound = oracle.spmm(rowptr, colind, vals, X, use_abs=True)
+        assert_close(Y.cpu().numpy().astype(np.float64), ref, bound, 1e-5, "spmm")
+        W = glorot_uniform(d, d_out, seed=seed % 1000)
+        ws = torch.empty(hc.hcspmm_aggregate_update_workspace_bytes(plan, d, d_out), dtype=torch.uint8, device="cuda")
+        Y2 = torch.full((n_rows, d_out), float("nan"), device="cuda")
+        os.environ["HCSPMM_TUNE_FORCE_FUSE"] = "1"
+        try:
+            hc.hcspmm_aggregate_update(plan, Xd, torch.from_numpy(W).cuda(), Y2, ws, apply_relu=False)
+            torch.cuda.synchronize()
+        finally:
+            del os.environ["HCSPMM_TUNE_FORCE_FUSE"]
+        plan.destroy()
+        ref2 = oracle.aggregate_update(rowptr, colind, vals, X, W, relu=False)
+        bound2 = oracle.aggregate_update(rowptr, colind, vals, X, W, use_abs=True)
+        assert_close(Y2.cpu().numpy().astype(np.float64), ref2, bound2, 2e-5, "aggregate-update")
 
     check()
