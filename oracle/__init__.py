@@ -13,6 +13,7 @@ from .numeric import (  # noqa: F401
     gcn_layer_rows,
     aggregate_update,
     aggregate_update_rows,
+    layer_backward,
     num_threads,
     set_num_threads,
     DT_F32, DT_BF16, DT_F16, DT_F64,

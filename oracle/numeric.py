@@ -192,3 +192,27 @@ def aggregate_update_rows(rows, rowptr, colind, vals, X, W, relu: bool = True, x
     if relu and not use_abs:
         Y = np.maximum(Y, 0.0)
     return Y
+
+
+def layer_backward(rowptr, colind, vals, G, X, W, Y_fwd=None, use_abs: bool = False):
+    """fp64 gradients of the layer X_next = act(A (X W)) given G = dL/dX_next (Eq. 3 and Eq. 4).
+
+    In the backward pass of this layer the aggregation comes first and both products of the update
+    follow it (Section V-A: the stage where the update follows the aggregation):
+        Gm = G where Y_fwd > 0, else 0      (derivative of max(0, .); Y_fwd None: no activation)
+        S  = A Gm                           (Eq. 4; A is the matrix the plan holds: the transpose of
+                                             the forward one, itself when it is symmetric)
+        dX = S W^T                          (second product of Eq. 3)
+        dW = X^T S                          (first product of Eq. 3: the transposed operand is the
+                                             dense matrix whose rows match the aggregated rows)
+    Returns (dX, dW).  use_abs gives the magnitude bounds |A| |Gm| |W|^T and |X|^T |A| |Gm|.
+    """
+    G64 = np.asarray(G, dtype=np.float64)
+    if Y_fwd is not None:
+        G64 = np.where(np.asarray(Y_fwd) > 0, G64, 0.0)
+    S = spmm(rowptr, colind, vals, np.ascontiguousarray(G64), DT_F64, use_abs=use_abs)
+    Wt = np.ascontiguousarray(np.asarray(W, dtype=np.float64).T)
+    Xt = np.ascontiguousarray(np.asarray(X, dtype=np.float64).T)
+    dX = gemm(S, Wt, x_dtype=DT_F64, w_dtype=DT_F64, use_abs=use_abs)
+    dW = gemm(Xt, S, x_dtype=DT_F64, w_dtype=DT_F64, use_abs=use_abs)
+    return dX, dW

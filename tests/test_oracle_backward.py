@@ -1,0 +1,162 @@
+"""Pins for the backward-layer oracle (Eq. 3 and Eq. 4): hand-computed numbers, dense fp64 numpy
+products, central differences of the forward layer, the bilinear form's Euler identities and
+special cases.  None of them calls the oracle's own loops to produce the expected value."""
+import numpy as np
+import pytest
+
+import oracle
+from workloads import tiny_random_csr, dense_normal
+
+
+def dense_of(g) -> np.ndarray:
+    a = np.zeros((g.n_rows, g.n_cols), dtype=np.float64)
+    for i in range(g.n_rows):
+        for k in range(g.rowptr[i], g.rowptr[i + 1]):
+            a[i, g.colind[k]] += float(g.vals[k])
+    return a
+
+
+def test_hand_computed_2x2():
+    # A = [[1, 2], [0, 3]], G = [[1, 0], [0, 1]] (so S = A), X = [[1, 2, 3], [4, 5, 6]], W = [[1, 0], [0, 1], [2, 2]]
+    rowptr = np.array([0, 2, 3], dtype=np.int32)
+    colind = np.array([0, 1, 1], dtype=np.int32)
+    vals = np.array([1, 2, 3], dtype=np.float32)
+    G = np.eye(2, dtype=np.float32)
+    X = np.array([[1, 2, 3], [4, 5, 6]], dtype=np.float32)
+    W = np.array([[1, 0], [0, 1], [2, 2]], dtype=np.float32)
+    dX, dW = oracle.layer_backward(rowptr, colind, vals, G, X, W)
+    # S = [[1, 2], [0, 3]];  dX = S W^T: row0 = [1, 2, 2+4], row1 = [0, 3, 6]
+    assert dX.tolist() == [[1.0, 2.0, 6.0], [0.0, 3.0, 6.0]]
+    # dW = X^T S: [[1*1+4*0, 1*2+4*3], [2*1+5*0, 2*2+5*3], [3*1+6*0, 3*2+6*3]]
+    assert dW.tolist() == [[1.0, 14.0], [2.0, 19.0], [3.0, 24.0]]
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_matches_dense_numpy(seed):
+    g = tiny_random_csr(37, 37, 0.15, seed=seed)
+    d_in, d_out = 5, 7
+    X = dense_normal(37, d_in, seed=seed + 10)
+    W = dense_normal(d_in, d_out, seed=seed + 20)
+    G = dense_normal(37, d_out, seed=seed + 30)
+    A = dense_of(g)
+    S = A @ G.astype(np.float64)
+    dX, dW = oracle.layer_backward(g.rowptr, g.colind, g.vals, G, X, W)
+    np.testing.assert_allclose(dX, S @ W.astype(np.float64).T, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(dW, X.astype(np.float64).T @ S, rtol=1e-12, atol=1e-12)
+    assert dX.shape == (37, d_in) and dW.shape == (d_in, d_out)
+
+
+def _forward_dense(A, X, W, relu):
+    Y = A @ (X @ W)
+    return np.maximum(Y, 0.0) if relu else Y
+
+
+@pytest.mark.parametrize("relu", [False, True])
+def test_central_differences_of_the_forward_layer(relu):
+    """dL/dW and dL/dX of L = sum(C * act(A (X W))) by central differences, for symmetric A (the
+    backward pass then multiplies by A itself, as Eq. 4 is written)."""
+    rng = np.random.default_rng(5)
+    n, d_in, d_out = 12, 4, 3
+    B = (rng.random((n, n)) < 0.3) * rng.standard_normal((n, n))
+    A = (B + B.T).astype(np.float32).astype(np.float64)
+    rows, cols = np.nonzero(A)
+    rowptr = np.zeros(n + 1, dtype=np.int32)
+    np.cumsum(np.bincount(rows, minlength=n), out=rowptr[1:])
+    colind = cols.astype(np.int32)
+    vals = A[rows, cols].astype(np.float32)
+    X = rng.standard_normal((n, d_in))
+    W = rng.standard_normal((d_in, d_out))
+    C = rng.standard_normal((n, d_out))
+    Y = _forward_dense(A, X, W, relu)
+    if relu:
+        assert np.min(np.abs(A @ (X @ W))) > 1e-4          # no pre-activation sits on the kink
+    dX, dW = oracle.layer_backward(rowptr, colind, vals, C, X, W, Y_fwd=Y if relu else None)
+    h = 1e-6
+    num_dW = np.zeros_like(W)
+    for a in range(d_in):
+        for b in range(d_out):
+            Wp, Wm = W.copy(), W.copy()
+            Wp[a, b] += h
+            Wm[a, b] -= h
+            num_dW[a, b] = (np.sum(C * _forward_dense(A, X, Wp, relu)) - np.sum(C * _forward_dense(A, X, Wm, relu))) / (2 * h)
+    num_dX = np.zeros_like(X)
+    for i in range(n):
+        for a in range(d_in):
+            Xp, Xm = X.copy(), X.copy()
+            Xp[i, a] += h
+            Xm[i, a] -= h
+            num_dX[i, a] = (np.sum(C * _forward_dense(A, Xp, W, relu)) - np.sum(C * _forward_dense(A, Xm, W, relu))) / (2 * h)
+    np.testing.assert_allclose(dW, num_dW, rtol=1e-6, atol=1e-7)
+    np.testing.assert_allclose(dX, num_dX, rtol=1e-6, atol=1e-7)
+
+
+def test_euler_identities_of_the_bilinear_form():
+    # without activation L = <G, A X W> is linear in X and in W: <dW, W> = L = <dX, X> when the plan's
+    # matrix is the transpose of the forward one
+    g = tiny_random_csr(29, 29, 0.2, seed=9)
+    A = dense_of(g)
+    X = dense_normal(29, 6, seed=1).astype(np.float64)
+    W = dense_normal(6, 4, seed=2).astype(np.float64)
+    G = dense_normal(29, 4, seed=3)
+    L = np.sum(G * (A.T @ (X @ W)))                        # forward with A^T, backward multiplies by A
+    dX, dW = oracle.layer_backward(g.rowptr, g.colind, g.vals, G, X, W)
+    assert abs(np.sum(dW * W) - L) <= 1e-10 * max(1.0, abs(L))
+    assert abs(np.sum(dX * X) - L) <= 1e-10 * max(1.0, abs(L))
+
+
+def test_special_cases():
+    n, d_in, d_out = 19, 3, 5
+    X = dense_normal(n, d_in, seed=4)
+    W = dense_normal(d_in, d_out, seed=5)
+    G = dense_normal(n, d_out, seed=6)
+    # A = I: dX = G W^T, dW = X^T G
+    rowptr = np.arange(n + 1, dtype=np.int32)
+    colind = np.arange(n, dtype=np.int32)
+    vals = np.ones(n, dtype=np.float32)
+    dX, dW = oracle.layer_backward(rowptr, colind, vals, G, X, W)
+    np.testing.assert_allclose(dX, G.astype(np.float64) @ W.astype(np.float64).T, rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(dW, X.astype(np.float64).T @ G.astype(np.float64), rtol=1e-13, atol=1e-13)
+    # W = I (d_in = d_out): dX = A G
+    g = tiny_random_csr(n, n, 0.25, seed=8)
+    G2 = dense_normal(n, d_in, seed=7)
+    dX2, _ = oracle.layer_backward(g.rowptr, g.colind, g.vals, G2, X, np.eye(d_in, dtype=np.float32))
+    np.testing.assert_allclose(dX2, dense_of(g) @ G2.astype(np.float64), rtol=1e-12, atol=1e-12)
+
+
+def test_activation_mask_zeroes_whole_entries():
+    # Y_fwd <= 0 removes the entry of G before the aggregation, not after it
+    g = tiny_random_csr(23, 23, 0.2, seed=12)
+    X = dense_normal(23, 4, seed=1)
+    W = dense_normal(4, 6, seed=2)
+    G = dense_normal(23, 6, seed=3)
+    Y = dense_normal(23, 6, seed=4)
+    Y[::3] = 0.0                                           # exactly zero counts as inactive
+    Gm = np.where(Y > 0, G, 0.0).astype(np.float64)
+    S = dense_of(g) @ Gm
+    dX, dW = oracle.layer_backward(g.rowptr, g.colind, g.vals, G, X, W, Y_fwd=Y)
+    np.testing.assert_allclose(dX, S @ W.astype(np.float64).T, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(dW, X.astype(np.float64).T @ S, rtol=1e-12, atol=1e-12)
+
+
+def test_equation_3_with_the_aggregated_matrix_transposed():
+    # Eq. 3 as printed, W' = Z^T X' with Z = A X the aggregated matrix: the same reduction with the
+    # roles of the two dense matrices exchanged gives its transpose
+    g = tiny_random_csr(31, 31, 0.2, seed=15)
+    Xk = dense_normal(31, 5, seed=1)
+    Xp = dense_normal(31, 3, seed=2)                       # X' (gradient of the next layer's input)
+    Z = dense_of(g) @ Xk.astype(np.float64)
+    _, dW = oracle.layer_backward(g.rowptr, g.colind, g.vals, Xk, Xp, np.zeros((3, 5), dtype=np.float32))
+    np.testing.assert_allclose(dW.T, Z.T @ Xp.astype(np.float64), rtol=1e-12, atol=1e-12)
+
+
+def test_magnitude_bound_dominates():
+    g = tiny_random_csr(27, 27, 0.2, seed=21)
+    X = dense_normal(27, 4, seed=1)
+    W = dense_normal(4, 5, seed=2)
+    G = dense_normal(27, 5, seed=3)
+    dX, dW = oracle.layer_backward(g.rowptr, g.colind, g.vals, G, X, W)
+    bX, bW = oracle.layer_backward(g.rowptr, g.colind, g.vals, G, X, W, use_abs=True)
+    A = np.abs(dense_of(g))
+    np.testing.assert_allclose(bX, (A @ np.abs(G)) @ np.abs(W).T.astype(np.float64), rtol=1e-12)
+    np.testing.assert_allclose(bW, np.abs(X).T.astype(np.float64) @ (A @ np.abs(G)), rtol=1e-12)
+    assert np.all(np.abs(dX) <= bX + 1e-300) and np.all(np.abs(dW) <= bW + 1e-300)
