@@ -253,7 +253,7 @@ size_t hcspmm_gcn_workspace_bytes(const hcspmm_plan* plan, int32_t d_in, int32_t
  *   d_X   device, n_cols x d_in, element type x_dtype (ldx >= d_in)
  *   d_W   device, d_in x d_out fp32 (ldw >= d_out);  d_Y  device, n_rows x d_out fp32 (ldy >= d_out)
  *   d_workspace  device, at least hcspmm_aggregate_update_workspace_bytes(plan, d_in, d_out) bytes,
- *                256-byte aligned; holds Z (n_rows x d_in fp32) on return
+ *                256-byte aligned; holds Z (n_rows x d_in fp32) on return when the update was not fused
  * Asynchronous on `stream`.  Errors as hcspmm_spmm.
  */
 hcspmm_status hcspmm_aggregate_update(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d_in,
@@ -262,6 +262,43 @@ hcspmm_status hcspmm_aggregate_update(const hcspmm_plan* plan, const void* d_X, 
                                       void* d_workspace, size_t workspace_bytes, void* stream);
 
 size_t hcspmm_aggregate_update_workspace_bytes(const hcspmm_plan* plan, int32_t d_in, int32_t d_out);
+
+/*
+ * Backward pass of the layer  X_next = act(A_f (X W))  (Eq. 3 and Eq. 4), given G = dL/dX_next:
+ *     Gm = G where Y_fwd > 0, else 0        (only with d_Yfwd; the derivative of max(0, .))
+ *     S  = A Gm                             (Eq. 4; A is the plan's matrix: the transpose of the forward
+ *                                            matrix A_f -- the same plan when A_f is symmetric, as the
+ *                                            normalised adjacency of an undirected graph is)
+ *     dX = S W^T                            (n_rows x d_in)
+ *     dW = X^T S                            (d_in x d_out)
+ * This is the stage of training where the update follows the aggregation (Section V-A): dX is
+ * computed like hcspmm_aggregate_update computes its Y, the aggregated tile multiplied by W^T on the
+ * matrix cores without a round trip (under the same conditions: d_out a multiple of 16 up to 256,
+ * few long rows), else by a GEMM.  dW is a reduction over all rows of the graph: S is also written
+ * to the workspace, and one streaming fp32 MFMA kernel forms X^T S from contiguous row spans whose
+ * partial products are added in span order (the result does not depend on scheduling).
+ * Eq. 3 as printed, W' = Z^T X' with the aggregated Z = A X_k, is the same call with the dense
+ * operands exchanged (d_G = X_k, d_X = X'): d_dW then holds W' transposed.
+ *
+ *   d_G     device, n_cols x d_out fp32 (ldg >= d_out): gradient with respect to the layer's output
+ *   d_Yfwd  device, n_cols x d_out fp32 (ldyf >= d_out): the layer's forward output, or NULL when the
+ *           layer had no activation
+ *   d_X     device, n_rows x d_in fp32 (ldx >= d_in): the layer's forward input
+ *   d_W     device, d_in x d_out fp32 (ldw >= d_out)
+ *   d_dX    device, n_rows x d_in fp32 (lddx >= d_in), overwritten;  NULL: dX is not computed
+ *   d_dW    device, d_in x d_out fp32 (lddw >= d_out), overwritten;  NULL: dW is not computed
+ *   d_workspace  device, at least hcspmm_layer_backward_workspace_bytes(plan, d_in, d_out) bytes,
+ *                256-byte aligned; its first n_rows x d_out floats hold S on return
+ * Outputs must not alias inputs.  Asynchronous on `stream`.  Errors as hcspmm_spmm.
+ */
+hcspmm_status hcspmm_layer_backward(const hcspmm_plan* plan, const void* d_G, int64_t ldg, int32_t d_out,
+                                    const void* d_Yfwd, int64_t ldyf,
+                                    const void* d_X, int64_t ldx, int32_t d_in,
+                                    const void* d_W, int64_t ldw,
+                                    void* d_dX, int64_t lddx, void* d_dW, int64_t lddw,
+                                    void* d_workspace, size_t workspace_bytes, void* stream);
+
+size_t hcspmm_layer_backward_workspace_bytes(const hcspmm_plan* plan, int32_t d_in, int32_t d_out);
 
 /* Dense update alone, T = X W in fp32 MFMA (Eq. 2): d_X M x K, d_W K x N, d_T M x N, all fp32 device. */
 hcspmm_status hcspmm_gemm_f32(int64_t m, int32_t k, int32_t n, const float* d_X, int64_t ldx,

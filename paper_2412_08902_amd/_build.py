@@ -11,7 +11,7 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 INCLUDE = os.path.join(os.path.dirname(PKG_DIR), "include")
 LIB_PATH = os.path.join(PKG_DIR, "libhcspmm.so")
 SOURCES = ["hcspmm_api.hip", "prepare_kernels.hip", "spmm_csr_kernels.hip", "spmm_mfma_kernels.hip",
-           "gemm_kernels.hip", "loa.cpp"]
+           "gemm_kernels.hip", "backward_kernels.hip", "loa.cpp"]
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                "-Wno-unused-command-line-argument"]

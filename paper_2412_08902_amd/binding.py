@@ -21,6 +21,7 @@ EXPORTED_SYMBOLS = [
     "hcspmm_default_options", "hcspmm_default_selector", "hcspmm_prepare", "hcspmm_plan_info",
     "hcspmm_plan_export", "hcspmm_spmm", "hcspmm_spmm_timed", "hcspmm_gcn_layer", "hcspmm_gcn_layer_ex", "hcspmm_gcn_workspace_bytes",
     "hcspmm_aggregate_update", "hcspmm_aggregate_update_workspace_bytes",
+    "hcspmm_layer_backward", "hcspmm_layer_backward_workspace_bytes",
     "hcspmm_gemm_f32", "hcspmm_loa_order", "hcspmm_permute_csr", "hcspmm_plan_destroy", "hcspmm_status_string", "hcspmm_last_error", "hcspmm_version",
 ]
 
@@ -93,6 +94,11 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.hcspmm_aggregate_update.restype = ctypes.c_int
     lib.hcspmm_aggregate_update_workspace_bytes.argtypes = [vp, i32, i32]
     lib.hcspmm_aggregate_update_workspace_bytes.restype = ctypes.c_size_t
+    lib.hcspmm_layer_backward.argtypes = [vp, vp, i64, i32, vp, i64, vp, i64, i32, vp, i64, vp, i64, vp, i64, vp,
+                                          ctypes.c_size_t, vp]
+    lib.hcspmm_layer_backward.restype = ctypes.c_int
+    lib.hcspmm_layer_backward_workspace_bytes.argtypes = [vp, i32, i32]
+    lib.hcspmm_layer_backward_workspace_bytes.restype = ctypes.c_size_t
     lib.hcspmm_loa_order.argtypes = [i32, i32, vp, vp, i32, i32, vp]
     lib.hcspmm_loa_order.restype = ctypes.c_int
     lib.hcspmm_permute_csr.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp]
@@ -270,6 +276,27 @@ def hcspmm_aggregate_update(plan: Plan, X, W, Y, workspace, *, apply_relu: bool 
                                                   1 if apply_relu else 0, _ptr(workspace),
                                                   workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
     return Y
+
+
+def hcspmm_layer_backward_workspace_bytes(plan: Plan, d_in: int, d_out: int) -> int:
+    return int(load_library().hcspmm_layer_backward_workspace_bytes(plan.handle, d_in, d_out))
+
+
+def hcspmm_layer_backward(plan: Plan, G, X, W, dX, dW, workspace, *, Y_fwd=None, stream=None):
+    """S = A (G masked by Y_fwd > 0), dX = S W^T, dW = X^T S; dX or dW may be None (not computed)."""
+    assert G.stride(1) == 1 and X.stride(1) == 1 and W.stride(1) == 1
+    assert dX is None or dX.stride(1) == 1
+    assert dW is None or dW.stride(1) == 1
+    assert Y_fwd is None or (Y_fwd.stride(1) == 1 and Y_fwd.shape == G.shape)
+    assert W.shape == (X.shape[1], G.shape[1])
+    _check(load_library().hcspmm_layer_backward(
+        plan.handle, _ptr(G), G.stride(0), G.shape[1],
+        _ptr(Y_fwd) if Y_fwd is not None else None, Y_fwd.stride(0) if Y_fwd is not None else 0,
+        _ptr(X), X.stride(0), X.shape[1], _ptr(W), W.stride(0),
+        _ptr(dX) if dX is not None else None, dX.stride(0) if dX is not None else 0,
+        _ptr(dW) if dW is not None else None, dW.stride(0) if dW is not None else 0,
+        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
+    return dX, dW
 
 
 def hcspmm_gcn_layer_ex(plan: Plan, X, W, Y, workspace, *, t_dtype: int = HCSPMM_F32, apply_relu: bool = True, stream=None):

@@ -820,6 +820,84 @@ hcspmm_status hcspmm_aggregate_update(const hcspmm_plan* plan, const void* d_X, 
     return HCSPMM_OK;
 }
 
+static size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+// workspace of the backward pass: S | masked G | W^T | partial products of dW
+struct BackwardLayout { size_t s_off, gm_off, wt_off, part_off, total; };
+
+static BackwardLayout backward_layout(const hcspmm_plan* plan, int32_t d_in, int32_t d_out)
+{
+    BackwardLayout l;
+    l.s_off = 0;
+    l.gm_off = l.s_off + align256((size_t)plan->n_rows * d_out * sizeof(float));
+    l.wt_off = l.gm_off + align256((size_t)plan->n_cols * d_out * sizeof(float));
+    l.part_off = l.wt_off + align256((size_t)d_in * d_out * sizeof(float));
+    l.total = l.part_off + align256((size_t)gemm_tn_spans(plan->n_rows, d_in, d_out) * d_in * d_out * sizeof(float));
+    return l;
+}
+
+size_t hcspmm_layer_backward_workspace_bytes(const hcspmm_plan* plan, int32_t d_in, int32_t d_out)
+{
+    if (!plan || d_in < 1 || d_out < 1) return 0;
+    return backward_layout(plan, d_in, d_out).total;
+}
+
+hcspmm_status hcspmm_layer_backward(const hcspmm_plan* plan, const void* d_G, int64_t ldg, int32_t d_out,
+                                    const void* d_Yfwd, int64_t ldyf, const void* d_X, int64_t ldx, int32_t d_in,
+                                    const void* d_W, int64_t ldw, void* d_dX, int64_t lddx, void* d_dW, int64_t lddw,
+                                    void* d_workspace, size_t workspace_bytes, void* stream)
+{
+    if (!plan) { set_error("plan is NULL"); return HCSPMM_EINVAL; }
+    if (d_in < 1 || d_out < 1 || d_in > (1 << 20) || d_out > (1 << 20)) { set_error("d_in, d_out must be in [1, 2^20]"); return HCSPMM_EINVAL; }
+    hcspmm_status st;
+    if ((st = check_dense("G", d_G, ldg, d_out)) != HCSPMM_OK) return st;
+    if (d_Yfwd && (st = check_dense("Yfwd", d_Yfwd, ldyf, d_out)) != HCSPMM_OK) return st;
+    if ((st = check_dense("W", d_W, ldw, d_out)) != HCSPMM_OK) return st;
+    if (d_dX && (st = check_dense("dX", d_dX, lddx, d_in)) != HCSPMM_OK) return st;
+    if (d_dW) {
+        if ((st = check_dense("dW", d_dW, lddw, d_out)) != HCSPMM_OK) return st;
+        if ((st = check_dense("X", d_X, ldx, d_in)) != HCSPMM_OK) return st;
+    }
+    const BackwardLayout l = backward_layout(plan, d_in, d_out);
+    if (!d_workspace || workspace_bytes < l.total) { set_error("workspace too small: need %zu bytes", l.total); return HCSPMM_EINVAL; }
+    if (((uintptr_t)d_workspace & 255) != 0) { set_error("workspace must be 256-byte aligned"); return HCSPMM_EINVAL; }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* ws = static_cast<char*>(d_workspace);
+    float* S = reinterpret_cast<float*>(ws + l.s_off);
+    float* Gm = reinterpret_cast<float*>(ws + l.gm_off);
+    float* Wt = reinterpret_cast<float*>(ws + l.wt_off);
+    float* part = reinterpret_cast<float*>(ws + l.part_off);
+    const float* G = static_cast<const float*>(d_G);
+    int64_t g_ld = ldg;
+    if (d_Yfwd && plan->n_cols > 0) {
+        HC_HIP(launch_relu_mask(plan->n_cols, d_out, G, ldg, static_cast<const float*>(d_Yfwd), ldyf, Gm, s));
+        G = Gm;
+        g_ld = d_out;
+    }
+    if (plan->n_rows > 0) {
+        SpmmArgs a;
+        a.n_rows = plan->n_rows; a.rowptr = plan->rowptr; a.colind = plan->colind; a.vals = plan->vals;
+        a.X = G; a.ldx = g_ld; a.d = d_out; a.x_dtype = HCSPMM_F32; a.Y = S; a.ldy = d_out; a.relu = 0;
+        if (d_dX) {
+            HC_HIP(launch_transpose(d_in, d_out, static_cast<const float*>(d_W), ldw, Wt, s));
+            const bool worth = 4 * (int64_t)plan->n_rest < plan->n_rows || getenv("HCSPMM_TUNE_FORCE_FUSE");
+            if (update_fusable(a) && worth && !getenv("HCSPMM_TUNE_NO_FUSE")) {
+                const UpdateArgs u{Wt, d_in, d_in, static_cast<float*>(d_dX), lddx, 0, d_dW ? 1 : 0};
+                if ((st = run_spmm(plan, a, s, nullptr, &u)) != HCSPMM_OK) return st;
+            } else {
+                if ((st = run_spmm(plan, a, s)) != HCSPMM_OK) return st;
+                HC_HIP(launch_gemm_f32(plan->n_rows, d_out, d_in, S, d_out, Wt, d_in, static_cast<float*>(d_dX), lddx, 0, s));
+            }
+        } else if ((st = run_spmm(plan, a, s)) != HCSPMM_OK) {
+            return st;
+        }
+    }
+    if (d_dW)
+        HC_HIP(launch_gemm_tn(plan->n_rows, static_cast<const float*>(d_X), ldx, d_in, S, d_out, d_out,
+                              static_cast<float*>(d_dW), lddw, part, s));
+    return HCSPMM_OK;
+}
+
 void hcspmm_plan_destroy(hcspmm_plan* plan)
 {
     if (!plan) return;

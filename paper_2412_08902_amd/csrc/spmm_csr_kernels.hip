@@ -273,6 +273,7 @@ __device__ inline void csr_short_fused_body(int64_t block, int32_t n_items, cons
         k += LPR;
     }
     __syncthreads();
+    if (u.keep_z) store_tile_rows(zt, LDZ, rows_s, S::ROWS, a.d, a.Y, a.ldy, threadIdx.x, 256);
     constexpr int WPT = 4 / S::T;                               // waves sharing one tile
     const int tile = wave / WPT;
     update_tile16(zt + tile * 16 * LDZ, LDZ, rows_s + tile * 16, a.d, u, lane, wave % WPT, WPT);

@@ -336,6 +336,7 @@ __global__ __launch_bounds__(256) void k_mfma_small(int32_t n_list, const WinDes
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        if (u.keep_z) store_tile_rows(tile, kLdz, rows16, 16, a.d, a.Y, a.ldy, lane, 64);
         update_tile16(tile, kLdz, rows16, a.d, u, lane);
     } else {
         store_tile<VW, NG>(acc, lane, r0, a.n_rows, a.Y + col0, a.ldy, d, a.relu);

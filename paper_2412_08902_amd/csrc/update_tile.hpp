@@ -85,6 +85,20 @@ __device__ inline void update_tile16_nt(const float* zt, int ldz, const int32_t*
     }
 }
 
+// Copies the rows of an LDS tile that have an output row to Z (row pitch ldz_out, 16-byte aligned rows,
+// d a multiple of 4); the nthreads callers share the work.
+__device__ inline void store_tile_rows(const float* zt, int ldz, const int32_t* rows, int n_tile_rows, int d,
+                                       float* __restrict__ Z, int64_t ldz_out, int tid, int nthreads)
+{
+    const int per_row = d >> 2;
+    for (int idx = tid; idx < n_tile_rows * per_row; idx += nthreads) {
+        const int r = idx / per_row, c = (idx % per_row) * 4;
+        const int32_t row = rows[r];
+        if (row >= 0)
+            *reinterpret_cast<float4*>(Z + (int64_t)row * ldz_out + c) = *reinterpret_cast<const float4*>(&zt[r * ldz + c]);
+    }
+}
+
 // Picks the widest vector the operands allow, narrowed until the waves sharing the tile all get a pass.
 __device__ inline void update_tile16(const float* zt, int ldz, const int32_t* rows16, int d_in, const UpdateArgs& u,
                                      int lane, int pass_first = 0, int pass_step = 1)

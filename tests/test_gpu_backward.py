@@ -1,0 +1,191 @@
+"""GPU parity of the layer's backward pass (S = A G, dX = S W^T, dW = X^T S) against the CPU oracle."""
+import numpy as np
+import pytest
+
+import oracle
+from workloads import (make_config, dense_normal, glorot_uniform, chung_lu_graph, gcn_normalise, tiny_random_csr,
+                       sbm_graph)
+from gpu_util import device_graph, assert_close
+
+pytestmark = pytest.mark.gpu
+TOL_F32 = 1e-5
+
+
+def run_backward(g, G, X, W, mode=0, Y_fwd=None, want_dx=True, want_dw=True, pad=0, sel_coef=None):
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    rp, ci, va = device_graph(g)
+    d_in, d_out = W.shape
+    plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, route_mode=mode, d_hint=d_out, sel_coef=sel_coef)
+    ws = torch.empty(hc.hcspmm_layer_backward_workspace_bytes(plan, d_in, d_out), dtype=torch.uint8, device="cuda")
+    dX = torch.full((g.n_rows, d_in + pad), -3.0, device="cuda") if want_dx else None
+    dW = torch.full((d_in, d_out + pad), -3.0, device="cuda") if want_dw else None
+    hc.hcspmm_layer_backward(plan, torch.from_numpy(G).cuda(), torch.from_numpy(X).cuda(), torch.from_numpy(W).cuda(),
+                             dX[:, :d_in] if want_dx else None, dW[:, :d_out] if want_dw else None, ws,
+                             Y_fwd=None if Y_fwd is None else torch.from_numpy(Y_fwd).cuda())
+    torch.cuda.synchronize()
+    S = ws[:g.n_rows * d_out * 4].view(torch.float32).reshape(g.n_rows, d_out).cpu().numpy().astype(np.float64)
+    plan.destroy()
+    out_dx = dX.cpu().numpy().astype(np.float64) if want_dx else None
+    out_dw = dW.cpu().numpy().astype(np.float64) if want_dw else None
+    if pad:
+        assert out_dx is None or np.all(out_dx[:, d_in:] == -3.0)
+        assert out_dw is None or np.all(out_dw[:, d_out:] == -3.0)
+    return (None if out_dx is None else out_dx[:, :d_in]), (None if out_dw is None else out_dw[:, :d_out]), S
+
+
+def check(g, G, X, W, dX, dW, S, Y_fwd=None):
+    ref_dx, ref_dw = oracle.layer_backward(g.rowptr, g.colind, g.vals, G, X, W, Y_fwd=Y_fwd)
+    b_dx, b_dw = oracle.layer_backward(g.rowptr, g.colind, g.vals, G, X, W, Y_fwd=Y_fwd, use_abs=True)
+    Gm = G if Y_fwd is None else np.where(Y_fwd > 0, G, 0).astype(np.float32)
+    ref_s = oracle.spmm(g.rowptr, g.colind, g.vals, Gm)
+    b_s = oracle.spmm(g.rowptr, g.colind, g.vals, Gm, use_abs=True)
+    if dW is not None or dX is None:
+        assert_close(S, ref_s, b_s, TOL_F32, "S")
+    # two chained fp32 stages: the aggregation's rounding is amplified by at most |W| resp. |X|
+    if dX is not None:
+        assert_close(dX, ref_dx, b_dx, 2 * TOL_F32, "dX")
+    if dW is not None:
+        assert_close(dW, ref_dw, b_dw, 2 * TOL_F32, "dW")
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("relu", [False, True])
+def test_backward_small(mode, relu):
+    g = gcn_normalise(chung_lu_graph(700, 9000, 2.0, seed=21))
+    X, W = dense_normal(700, 50, seed=22), glorot_uniform(50, 24, seed=23)
+    G = dense_normal(700, 24, seed=24)
+    Y = dense_normal(700, 24, seed=25) if relu else None
+    if relu:
+        Y[::7] = 0.0
+    dX, dW, S = run_backward(g, G, X, W, mode, Y_fwd=Y, pad=3)
+    check(g, G, X, W, dX, dW, S, Y_fwd=Y)
+
+
+@pytest.mark.parametrize("force", [False, True])
+@pytest.mark.parametrize("mode", [0, 1, 2, 3])
+@pytest.mark.parametrize("din,dout", [(16, 16), (1, 32), (17, 48), (64, 64), (200, 128), (128, 256), (72, 112),
+                                      (602, 128), (40, 300)])
+def test_backward_shapes(mode, din, dout, force, monkeypatch):
+    """Widths in and out of the fused update's range (d_out a multiple of 16 up to 256), on a power-law graph whose
+    hub rows and wide windows take the memory route, with a ragged last window and every routing."""
+    if force:
+        monkeypatch.setenv("HCSPMM_TUNE_FORCE_FUSE", "1")
+    g = gcn_normalise(chung_lu_graph(3003, 150000, 2.0, seed=71, max_degree=2800))
+    X, W = dense_normal(g.n_rows, din, seed=72), glorot_uniform(din, dout, seed=73)
+    G = dense_normal(g.n_cols, dout, seed=74)
+    dX, dW, S = run_backward(g, G, X, W, mode, pad=2, sel_coef=[1, 0, -300] if mode == 3 else None)
+    check(g, G, X, W, dX, dW, S)
+
+
+def test_backward_matches_central_differences_of_the_forward_layer():
+    """The forward layer on the GPU (hcspmm_gcn_layer) differentiated numerically in fp64 through the oracle is
+    covered on the CPU; here the GPU backward is checked against the GPU forward by the bilinear identities
+    <dW, W> = <G, A X W> = <dX, X> (no activation), which tie the two entry points together."""
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    g = gcn_normalise(chung_lu_graph(2000, 30000, 2.0, seed=5))
+    X, W = dense_normal(2000, 64, seed=6), glorot_uniform(64, 32, seed=7)
+    G = dense_normal(2000, 32, seed=8)
+    dX, dW, _ = run_backward(g, G, X, W)
+    rp, ci, va = device_graph(g)
+    plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, d_hint=32)
+    ws = torch.empty(hc.hcspmm_gcn_workspace_bytes(plan, 64, 32), dtype=torch.uint8, device="cuda")
+    Y = torch.empty((2000, 32), device="cuda")
+    hc.hcspmm_gcn_layer(plan, torch.from_numpy(X).cuda(), torch.from_numpy(W).cuda(), Y, ws, apply_relu=False)
+    torch.cuda.synchronize()
+    plan.destroy()
+    L = float(np.sum(G.astype(np.float64) * Y.cpu().numpy().astype(np.float64)))
+    scale = float(np.sum(np.abs(G) * oracle.gcn_layer(g.rowptr, g.colind, g.vals, X, W, use_abs=True)))
+    assert abs(np.sum(dW * W) - L) <= 1e-5 * scale
+    assert abs(np.sum(dX * X) - L) <= 1e-5 * scale
+
+
+def test_backward_only_one_gradient():
+    g = gcn_normalise(chung_lu_graph(900, 12000, 2.0, seed=31))
+    X, W = dense_normal(900, 32, seed=32), glorot_uniform(32, 64, seed=33)
+    G = dense_normal(900, 64, seed=34)
+    dX, dW, S = run_backward(g, G, X, W, want_dw=False)
+    assert dW is None
+    check(g, G, X, W, dX, None, S)
+    dX, dW, S = run_backward(g, G, X, W, want_dx=False)
+    assert dX is None
+    check(g, G, X, W, None, dW, S)
+
+
+def test_backward_community_graph_with_empty_rows():
+    from workloads import CSRGraph
+    g = sbm_graph(30, 64, 0.3, 2.0, seed=81)
+    keep = np.ones(g.nnz, dtype=bool)
+    for r in list(range(32, 48)) + [5, 77, 1900]:
+        keep[g.rowptr[r]:g.rowptr[r + 1]] = False
+    lens = np.add.reduceat(keep, g.rowptr[:-1]) * (np.diff(g.rowptr) > 0)
+    rp = np.zeros(g.n_rows + 1, np.int32)
+    np.cumsum(lens, out=rp[1:])
+    g = CSRGraph(g.n_rows, g.n_cols, rp, g.colind[keep], g.vals[keep])
+    X, W = dense_normal(g.n_rows, 48, seed=82), glorot_uniform(48, 64, seed=83)
+    G = dense_normal(g.n_cols, 64, seed=84)
+    for mode in (0, 1, 2):
+        dX, dW, S = run_backward(g, G, X, W, mode)
+        check(g, G, X, W, dX, dW, S)
+        assert np.all(dX[32:48] == 0.0) and np.all(S[5] == 0.0)
+
+
+def test_backward_exact_on_integers():
+    """0/1 adjacency, small-integer G, X and W: every partial sum is an integer below 2^24, so S, dX and dW must be
+    bit-exact whatever the summation order."""
+    rng = np.random.default_rng(3)
+    g = tiny_random_csr(1500, 1500, 0.01, seed=9)
+    g.vals[:] = 1.0
+    G = rng.integers(-3, 4, size=(1500, 32)).astype(np.float32)
+    X = rng.integers(-2, 3, size=(1500, 48)).astype(np.float32)
+    W = rng.integers(-2, 3, size=(48, 32)).astype(np.float32)
+    for mode in (0, 1, 2):
+        dX, dW, S = run_backward(g, G, X, W, mode)
+        ref_dx, ref_dw = oracle.layer_backward(g.rowptr, g.colind, g.vals, G, X, W)
+        assert np.array_equal(dX, ref_dx) and np.array_equal(dW, ref_dw)
+
+
+def test_backward_rectangular_and_errors():
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    # rectangular A (n_rows != n_cols): G has n_cols rows, X and dX have n_rows rows
+    g = tiny_random_csr(333, 500, 0.03, seed=41)
+    X, W = dense_normal(333, 24, seed=42), glorot_uniform(24, 32, seed=43)
+    G = dense_normal(500, 32, seed=44)
+    Y = dense_normal(500, 32, seed=45)
+    dX, dW, S = run_backward(g, G, X, W, Y_fwd=Y)
+    check(g, G, X, W, dX, dW, S, Y_fwd=Y)
+    rp, ci, va = device_graph(g)
+    plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, d_hint=32)
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    dXt = torch.empty((333, 24), device="cuda")
+    dWt = torch.empty((24, 32), device="cuda")
+    with pytest.raises(hc.HcspmmError):
+        hc.hcspmm_layer_backward(plan, torch.from_numpy(G).cuda(), torch.from_numpy(X).cuda(),
+                                 torch.from_numpy(W).cuda(), dXt, dWt, small)
+    plan.destroy()
+    # a matrix with no entries: S, dX and dW are all zeros
+    e = tiny_random_csr(40, 40, 0.0, seed=1)
+    dX, dW, S = run_backward(e, dense_normal(40, 16, seed=2), dense_normal(40, 8, seed=3), glorot_uniform(8, 16, seed=4))
+    assert np.all(dX == 0.0) and np.all(dW == 0.0) and np.all(S == 0.0)
+
+
+def test_backward_scaled_config5():
+    g, X, W = make_config("C5", scale=0.01)
+    G = dense_normal(g.n_cols, W.shape[1], seed=91)
+    ref_y = oracle.gcn_layer(g.rowptr, g.colind, g.vals, X, W)
+    Y = ref_y.astype(np.float32)
+    dX, dW, S = run_backward(g, G, X, W, Y_fwd=Y)
+    check(g, G, X, W, dX, dW, S, Y_fwd=Y)
+
+
+def test_backward_is_deterministic():
+    """dW is a sum over all rows: spans and their order are fixed, so two calls give the same bits."""
+    g = gcn_normalise(chung_lu_graph(20000, 300000, 2.0, seed=51))
+    X, W = dense_normal(20000, 64, seed=52), glorot_uniform(64, 64, seed=53)
+    G = dense_normal(20000, 64, seed=54)
+    a = run_backward(g, G, X, W)
+    b = run_backward(g, G, X, W)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2])
+    check(g, G, X, W, *a)
