@@ -79,6 +79,8 @@ def main():
     ap.add_argument("--agg-update", type=int, default=None, metavar="D_OUT",
                     help="also time the aggregate-then-update layer Y = ReLU((A X) W) with a d x D_OUT W, with the "
                          "update stage fused into the SpMM kernels and as SpMM + GEMM")
+    ap.add_argument("--backward", type=int, default=0, metavar="D_IN",
+                    help="also time the layer's backward pass (S = A G, dX = S W^T, dW = X^T S) for a D_IN x d W")
     ap.add_argument("--graph", type=int, default=0, metavar="N",
                     help="also capture N back-to-back SpMM calls in a HIP graph and time its replays "
                          "(separates launch latency from kernel time on the small configs)")
@@ -279,6 +281,33 @@ def main():
         out["aggregate_update"]["max_abs_diff_fused_vs_split"] = float((Y2 - Y3).abs().max().item())
         log("aggregate-update: fused %.4f ms, spmm+gemm %.4f ms (gemm alone %.4f)" % (ms_fused, ms_split, ms_gemm))
         del Wd, ws, Y2, Y3, Zt, Y_fused
+
+    if args.backward:
+        # backward pass of a layer with a D_IN x d weight matrix: G is n x d (d = the workload's width), X is n x D_IN
+        from workloads import glorot_uniform
+        d_in = args.backward
+        Wb = torch.from_numpy(glorot_uniform(d_in, d, seed=4343)).to(dev)
+        Xb = torch.from_numpy(dense_normal(g.n_rows, d_in, seed=4344)).to(dev)
+        Gb = Xd if args.x_dtype == "f32" else torch.from_numpy(dense_normal(g.n_cols, d, seed=4345)).to(dev)
+        Yf = torch.from_numpy(dense_normal(g.n_cols, d, seed=4346)).to(dev)
+        wsb = torch.empty(hc.hcspmm_layer_backward_workspace_bytes(plan, d_in, d), dtype=torch.uint8, device=dev)
+        dXb = torch.empty((g.n_rows, d_in), dtype=torch.float32, device=dev)
+        dWb = torch.empty((d_in, d), dtype=torch.float32, device=dev)
+        bw = lambda **kw: hc.hcspmm_layer_backward(plan, Gb, Xb, Wb, dXb, dWb, wsb, **kw)
+        ms_b = time_steps(lambda: bw(), args.steps, args.warmup, torch)
+        ms_b_mask = time_steps(lambda: bw(Y_fwd=Yf), args.steps, args.warmup, torch)
+        ms_dx = time_steps(lambda: hc.hcspmm_layer_backward(plan, Gb, Xb, Wb, dXb, None, wsb), args.steps, args.warmup, torch)
+        ms_dw = time_steps(lambda: hc.hcspmm_layer_backward(plan, Gb, Xb, Wb, None, dWb, wsb), args.steps, args.warmup, torch)
+        os.environ["HCSPMM_TUNE_NO_FUSE"] = "1"
+        ms_b_split = time_steps(lambda: bw(), args.steps, args.warmup, torch)
+        del os.environ["HCSPMM_TUNE_NO_FUSE"]
+        out["layer_backward"] = dict(d_in=d_in, d_out=d, ms=round(ms_b, 5), ms_with_activation_mask=round(ms_b_mask, 5),
+                                     ms_unfused=round(ms_b_split, 5), ms_dx_only=round(ms_dx, 5), ms_dw_only=round(ms_dw, 5),
+                                     ms_spmm_alone=round(ms, 5),
+                                     dw_stream_gbps=round((g.n_rows * (d_in + d) * 4) / max(ms_dw - ms, 1e-6) / 1e6, 1))
+        log("layer backward: %.4f ms (unfused %.4f; dX only %.4f, dW only %.4f, with mask %.4f; spmm alone %.4f)"
+            % (ms_b, ms_b_split, ms_dx, ms_dw, ms_b_mask, ms))
+        del Wb, Xb, Yf, wsb, dXb, dWb
 
     if args.cold:
         flush = torch.empty(512 << 20, dtype=torch.uint8, device=dev)

@@ -109,24 +109,37 @@ __global__ __launch_bounds__(256) void k_gemm_tn(int64_t n_rows, int64_t rows_pe
     }
 }
 
+// out[e] = sum over spans of partial[span][e], in an order that depends only on the span count: 16
+// threads per output each add every 16th span in ascending order, then one of them adds the 16 sums
+// in ascending order.
 __global__ __launch_bounds__(256) void k_sum_partials(int32_t n_spans, int64_t count, int32_t d,
                                                       const float* __restrict__ partial, float* __restrict__ out,
                                                       int64_t ldo)
 {
-    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (e >= count) return;
+    __shared__ float red[16][17];
+    const int o = threadIdx.x & 15, j = threadIdx.x >> 4;
+    const int64_t e = (int64_t)blockIdx.x * 16 + o;
     float s = 0.f;
-    for (int32_t p = 0; p < n_spans; ++p) s += partial[(int64_t)p * count + e];
-    out[(e / d) * ldo + e % d] = s;
+    if (e < count) {
+#pragma unroll 4
+        for (int32_t p = j; p < n_spans; p += 16) s += partial[(int64_t)p * count + e];
+    }
+    red[j][o] = s;
+    __syncthreads();
+    if (j == 0 && e < count) {
+        float t = 0.f;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) t += red[k][o];
+        out[(e / d) * ldo + e % d] = t;
+    }
 }
 
 int32_t gemm_tn_spans(int64_t n_rows, int32_t d_in, int32_t d)
 {
     const int64_t gy = (d_in + kTnM - 1) / kTnM, gz = (d + 255) / 256;
     const int64_t stages = (n_rows + kTnRows - 1) / kTnRows;
-    int64_t spans = 1024 / (gy * gz);
-    if (spans < 1) spans = 1;
-    if (spans > stages) spans = stages;
+    int64_t spans = 1024 / (gy * gz);                                // about four workgroups per CU in all
+    if (spans > stages / 8) spans = stages / 8;                      // at least eight stages per span
     if (spans < 1) spans = 1;
     return (int32_t)spans;
 }
@@ -160,7 +173,7 @@ hipError_t launch_gemm_tn(int64_t n_rows, const float* X, int64_t ldx, int32_t d
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int64_t count = (int64_t)d_in * d;
-    hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, spans, count, d, partial,
+    hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((count + 15) / 16)), dim3(256), 0, s, spans, count, d, partial,
                        dW, lddw);
     return hipGetLastError();
 }

@@ -880,7 +880,10 @@ hcspmm_status hcspmm_layer_backward(const hcspmm_plan* plan, const void* d_G, in
         a.X = G; a.ldx = g_ld; a.d = d_out; a.x_dtype = HCSPMM_F32; a.Y = S; a.ldy = d_out; a.relu = 0;
         if (d_dX) {
             HC_HIP(launch_transpose(d_in, d_out, static_cast<const float*>(d_W), ldw, Wt, s));
-            const bool worth = 4 * (int64_t)plan->n_rest < plan->n_rows || getenv("HCSPMM_TUNE_FORCE_FUSE");
+            // as in hcspmm_aggregate_update; when dW needs S in memory as well, the fused kernels store every
+            // tile besides multiplying it, which measured faster than the separate GEMM only for narrow S
+            const bool worth = (4 * (int64_t)plan->n_rest < plan->n_rows && (!d_dW || d_out <= 32)) ||
+                               getenv("HCSPMM_TUNE_FORCE_FUSE");
             if (update_fusable(a) && worth && !getenv("HCSPMM_TUNE_NO_FUSE")) {
                 const UpdateArgs u{Wt, d_in, d_in, static_cast<float*>(d_dX), lddx, 0, d_dW ? 1 : 0};
                 if ((st = run_spmm(plan, a, s, nullptr, &u)) != HCSPMM_OK) return st;

@@ -40,11 +40,21 @@ def check_plan_windows(g, plan_arrays, info, windows):
         assert plan_arrays["route"][w] == oracle.select_route(wc.shape[0], cnt, coef)
 
 
+_CONFIG_CACHE = {}
+
+
+def cached_config(name):
+    """Graph and dense matrix of a benchmark configuration, generated once per test process."""
+    if name not in _CONFIG_CACHE:
+        print("generating %s ..." % name, flush=True)
+        g, X, _ = make_config(name)
+        _CONFIG_CACHE[name] = (g, X)
+    return _CONFIG_CACHE[name]
+
+
 @pytest.fixture(scope="module")
 def c4():
-    print("generating C4 ...", flush=True)
-    g, X, _ = make_config("C4")
-    return g, X
+    return cached_config("C4")
 
 
 def test_c4_spmm_and_plan(c4):
@@ -117,7 +127,7 @@ def test_aggregate_update_fused_at_full_size(name, d_out):
     import torch
     import paper_2412_08902_amd.binding as hc
     from workloads import glorot_uniform
-    g, X, _ = make_config(name)
+    g, X = cached_config(name)
     Wm = glorot_uniform(X.shape[1], d_out, seed=77)
     rp, ci, va = device_graph(g)
     plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, d_hint=X.shape[1])
@@ -142,3 +152,32 @@ def test_aggregate_update_fused_at_full_size(name, d_out):
     # same mathematics, different summation order in the update: agree to fp32 rounding of the row sums
     assert float((Y - Y2).abs().max()) <= 1e-4 * max(1.0, float(Y2.abs().max()))
     plan.destroy()
+
+
+@pytest.mark.parametrize("name,d_in", [("C3", 64), ("C2", 128), ("C4", 32)])
+def test_layer_backward_at_full_size(name, d_in):
+    """Backward pass at the benchmark sizes: the whole dW (a reduction over every row) and sampled rows of dX against
+    the oracle, with the workload's dense matrix as the incoming gradient."""
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    from workloads import glorot_uniform
+    g, G = cached_config(name)
+    d_out = G.shape[1]
+    Wm = glorot_uniform(d_in, d_out, seed=78)
+    X = dense_normal(g.n_rows, d_in, seed=79)
+    rp, ci, va = device_graph(g)
+    plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, d_hint=d_out)
+    ws = torch.empty(hc.hcspmm_layer_backward_workspace_bytes(plan, d_in, d_out), dtype=torch.uint8, device="cuda")
+    dX = torch.full((g.n_rows, d_in), float("nan"), device="cuda")
+    dW = torch.full((d_in, d_out), float("nan"), device="cuda")
+    hc.hcspmm_layer_backward(plan, torch.from_numpy(G).cuda(), torch.from_numpy(X).cuda(), torch.from_numpy(Wm).cuda(),
+                             dX, dW, ws)
+    torch.cuda.synchronize()
+    plan.destroy()
+    assert torch.isfinite(dX).all()
+    ref_dx, ref_dw = oracle.layer_backward(g.rowptr, g.colind, g.vals, G, X, Wm)
+    b_dx, b_dw = oracle.layer_backward(g.rowptr, g.colind, g.vals, G, X, Wm, use_abs=True)
+    assert_close(dW.cpu().numpy().astype(np.float64), ref_dw, b_dw, 2 * TOL_F32, name + " dW")
+    rows = sample_rows(g, 300, seed=6)
+    got = dX[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.float64)
+    assert_close(got, ref_dx[rows], b_dx[rows], 2 * TOL_F32, name + " dX")
