@@ -59,7 +59,12 @@ typedef enum { HCSPMM_F32 = 0, HCSPMM_BF16 = 1, HCSPMM_F16 = 2 } hcspmm_dtype;
  * its windows join the other path (the scalar side is checked for the matrix side's windows
  * first) -- a launch that cannot repay its fixed cost is not made.  The two ALL_* modes force one
  * path for every non-empty window (used to measure the selector against the pure paths).
- * Empty windows always take the scalar path. */
+ * Empty windows always take the scalar path.
+ * ALL_CSR is also the plan for a matrix whose structure keeps changing: the scalar path reads
+ * plain CSR (the paper's scalar path has no preprocessing either), so hcspmm_prepare skips the
+ * condensing step and only validates the arrays and builds the row-length launch tables; the
+ * window features (ncols, wptr, total_ncols) of such a plan are computed on the first
+ * hcspmm_plan_info / hcspmm_plan_export call instead. */
 typedef enum {
     HCSPMM_ROUTE_HYBRID = 0, HCSPMM_ROUTE_ALL_CSR = 1, HCSPMM_ROUTE_ALL_MFMA = 2, HCSPMM_ROUTE_PER_WINDOW = 3
 } hcspmm_route_mode;
@@ -144,6 +149,8 @@ typedef struct {
     int32_t n_mfma_big;       /* route-1 windows handled one workgroup per window */
 } hcspmm_plan_info_t;
 
+/* Synchronises with the device the first time it is called on an HCSPMM_ROUTE_ALL_CSR plan (it then
+ * computes the window features that prepare skipped); otherwise host-only. */
 hcspmm_status hcspmm_plan_info(const hcspmm_plan* plan, hcspmm_plan_info_t* info /* host, out */);
 
 /*

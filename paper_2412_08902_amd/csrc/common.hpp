@@ -209,6 +209,7 @@ struct hcspmm_plan {
     int64_t n_slots;
     int32_t n_long_rows;
     int32_t condensed_complete;     // 0: wcols / erc are filled for matrix-path windows only (the rest on export)
+    int32_t features_complete;    // ncols / wptr / total_ncols are filled (a scalar-only plan computes them on first request)
     int32_t n_rest;                 // rows finished through the workspace by the fused update
     int32_t* rest_rows;
     int64_t nnz_long;

@@ -146,37 +146,53 @@ static void free_plan_arrays(hcspmm_plan* p)
         if (q) (void)hipFree(q);
 }
 
-// Fills wcols / erc for the scalar-path windows too (hcspmm_prepare leaves them out: no kernel reads
-// them); the distinct-column lists are recomputed into scratch memory.  Default stream, synchronous.
-static hcspmm_status complete_condensed(hcspmm_plan* p)
+// Completes what hcspmm_prepare leaves out because no kernel reads it: the window features (ncols,
+// wptr, total_ncols) of a scalar-only plan, and -- unless features_only -- wcols / erc of the
+// scalar-path windows.  The distinct-column lists are recomputed into scratch memory.  Default
+// stream, synchronous.
+static hcspmm_status complete_condensed(hcspmm_plan* p, bool features_only)
 {
     hcspmm_status st = HCSPMM_OK;
     DevAlloc tmp;
     int32_t *tmp_cols = nullptr, *big_list = nullptr, *cnt = nullptr, *nc_tmp = nullptr, *nz_tmp = nullptr;
+    int64_t* scan_tmp = nullptr;
     int32_t h_big = 0;
     const int32_t W = p->W;
-    if (!p->erc && hipMalloc((void**)&p->erc, (size_t)(p->nnz > 0 ? p->nnz : 1) * sizeof(int32_t)) != hipSuccess) {
-        (void)hipGetLastError(); p->erc = nullptr;
-        set_error("device allocation failed while completing the condensed structure"); return HCSPMM_EALLOC;
-    }
-    if (!p->wcols && hipMalloc((void**)&p->wcols, (size_t)(p->total_ncols > 0 ? p->total_ncols : 1) * sizeof(int32_t)) != hipSuccess) {
-        (void)hipGetLastError(); p->wcols = nullptr;
-        set_error("device allocation failed while completing the condensed structure"); return HCSPMM_EALLOC;
-    }
     HC_ALLOC(tmp, tmp_cols, p->nnz);
     HC_ALLOC(tmp, big_list, W);
     HC_ALLOC(tmp, cnt, 2);
     HC_ALLOC(tmp, nc_tmp, W);
     HC_ALLOC(tmp, nz_tmp, W);
+    HC_ALLOC(tmp, scan_tmp, scan_scratch_elems((int64_t)W + 1));
     HC_TRY(hipMemsetAsync(cnt, 0, 2 * sizeof(int32_t), nullptr));
-    HC_TRY(launch_window_nnz(W, p->n_rows, p->rowptr, nz_tmp, big_list, cnt + 1, nullptr));
-    HC_TRY(launch_unique_small(W, p->n_rows, p->rowptr, p->colind, tmp_cols, nc_tmp, nullptr));
-    HC_TRY(hipMemcpy(&h_big, cnt + 1, sizeof h_big, hipMemcpyDeviceToHost));
-    HC_TRY(launch_unique_big(h_big, big_list, p->n_rows, p->n_cols, p->rowptr, p->colind, tmp_cols, nc_tmp, nullptr));
-    HC_TRY(launch_ecol(W, p->n_rows, p->rowptr, p->colind, tmp_cols, p->ncols, p->wptr, p->wcols, p->erc, cnt, p->route, 0,
-                       nullptr));
+    if (W > 0) {
+        HC_TRY(launch_window_nnz(W, p->n_rows, p->rowptr, nz_tmp, big_list, cnt + 1, nullptr));
+        HC_TRY(launch_unique_small(W, p->n_rows, p->rowptr, p->colind, tmp_cols, nc_tmp, nullptr));
+        HC_TRY(hipMemcpy(&h_big, cnt + 1, sizeof h_big, hipMemcpyDeviceToHost));
+        HC_TRY(launch_unique_big(h_big, big_list, p->n_rows, p->n_cols, p->rowptr, p->colind, tmp_cols, nc_tmp, nullptr));
+    }
+    if (!p->features_complete) {
+        if (W > 0) HC_TRY(hipMemcpyAsync(p->ncols, nc_tmp, (size_t)W * sizeof(int32_t), hipMemcpyDeviceToDevice, nullptr));
+        HC_TRY(exclusive_scan_i32_i64(p->ncols, W, p->wptr, scan_tmp, nullptr));
+        HC_TRY(hipMemcpy(&p->total_ncols, p->wptr + W, sizeof(int64_t), hipMemcpyDeviceToHost));
+        p->features_complete = 1;
+    }
+    if (!features_only && !p->condensed_complete) {
+        if (!p->erc && hipMalloc((void**)&p->erc, (size_t)(p->nnz > 0 ? p->nnz : 1) * sizeof(int32_t)) != hipSuccess) {
+            (void)hipGetLastError(); p->erc = nullptr;
+            set_error("device allocation failed while completing the condensed structure"); st = HCSPMM_EALLOC; goto fail;
+        }
+        if (!p->wcols && hipMalloc((void**)&p->wcols, (size_t)(p->total_ncols > 0 ? p->total_ncols : 1) * sizeof(int32_t)) != hipSuccess) {
+            (void)hipGetLastError(); p->wcols = nullptr;
+            set_error("device allocation failed while completing the condensed structure"); st = HCSPMM_EALLOC; goto fail;
+        }
+        if (W > 0)
+            HC_TRY(launch_ecol(W, p->n_rows, p->rowptr, p->colind, tmp_cols, p->ncols, p->wptr, p->wcols, p->erc, cnt, p->route, 0,
+                               nullptr));
+        HC_TRY(hipDeviceSynchronize());
+        p->condensed_complete = 1;
+    }
     HC_TRY(hipDeviceSynchronize());
-    p->condensed_complete = 1;
     tmp.free_all();
     return HCSPMM_OK;
 fail:
@@ -242,17 +258,30 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     HC_ALLOC(tmp, pos_d, scan_n + 1);
     HC_ALLOC(tmp, totals_dev, 8);
 
+    // A scalar-only plan never reads the condensed structure (the paper has no preprocessing for its
+    // scalar path either): its window features stay zero here and are computed when first asked for
+    // (hcspmm_plan_info / hcspmm_plan_export), which makes prepare cheap for matrices that keep changing.
+    p->features_complete = (p->opt.route_mode == HCSPMM_ROUTE_ALL_CSR && nnz > 0) ? 0 : 1;
     if (W > 0) {
         // windows, condensing (Section IV-A)
         HC_TRY(launch_window_nnz(W, n_rows, p->rowptr, p->nnzw, big_list, big_count, stream));
-        HC_TRY(launch_unique_small(W, n_rows, p->rowptr, p->colind, tmp_cols, p->ncols, stream));
-        HC_TRY(hipMemcpyAsync(&h_big, big_count, sizeof h_big, hipMemcpyDeviceToHost, stream));
-        HC_TRY(hipStreamSynchronize(stream));
-        HC_TRY(launch_unique_big(h_big, big_list, n_rows, p->n_cols, p->rowptr, p->colind, tmp_cols, p->ncols, stream));
+        if (p->features_complete) {
+            HC_TRY(launch_unique_small(W, n_rows, p->rowptr, p->colind, tmp_cols, p->ncols, stream));
+            HC_TRY(hipMemcpyAsync(&h_big, big_count, sizeof h_big, hipMemcpyDeviceToHost, stream));
+            HC_TRY(hipStreamSynchronize(stream));
+            HC_TRY(launch_unique_big(h_big, big_list, n_rows, p->n_cols, p->rowptr, p->colind, tmp_cols, p->ncols, stream));
+        } else {
+            HC_TRY(hipMemsetAsync(p->ncols, 0, (size_t)W * sizeof(int32_t), stream));
+        }
     }
-    HC_TRY(exclusive_scan_i32_i64(p->ncols, W, p->wptr, scan_tmp, stream));
-    HC_TRY(hipMemcpyAsync(&p->total_ncols, p->wptr + W, sizeof(int64_t), hipMemcpyDeviceToHost, stream));
-    HC_TRY(hipStreamSynchronize(stream));
+    if (p->features_complete) {
+        HC_TRY(exclusive_scan_i32_i64(p->ncols, W, p->wptr, scan_tmp, stream));
+        HC_TRY(hipMemcpyAsync(&p->total_ncols, p->wptr + W, sizeof(int64_t), hipMemcpyDeviceToHost, stream));
+        HC_TRY(hipStreamSynchronize(stream));
+    } else {
+        HC_TRY(hipMemsetAsync(p->wptr, 0, ((size_t)W + 1) * sizeof(int64_t), stream));
+        p->total_ncols = 0;
+    }
     p->rows_sorted = 1;
 
     // selection (Section IV-C) and the per-route window lists
@@ -621,6 +650,10 @@ hcspmm_status hcspmm_prepare(int32_t n_rows, int32_t n_cols, int64_t nnz, const 
 hcspmm_status hcspmm_plan_info(const hcspmm_plan* p, hcspmm_plan_info_t* info)
 {
     if (!p || !info) { set_error("NULL argument"); return HCSPMM_EINVAL; }
+    if (!p->features_complete) {
+        const hcspmm_status st = complete_condensed(const_cast<hcspmm_plan*>(p), true);
+        if (st != HCSPMM_OK) return st;
+    }
     memset(info, 0, sizeof *info);
     info->window_rows = p->H; info->n_rows = p->n_rows; info->n_cols = p->n_cols; info->nnz = p->nnz;
     info->n_windows = p->W; info->total_ncols = p->total_ncols;
@@ -640,8 +673,8 @@ hcspmm_status hcspmm_plan_export(const hcspmm_plan* p, int32_t* ncols, int32_t* 
 {
     if (!p) { set_error("plan is NULL"); return HCSPMM_EINVAL; }
     HC_HIP(hipDeviceSynchronize());
-    if ((wcols || ecol) && !p->condensed_complete) {
-        const hcspmm_status st = complete_condensed(const_cast<hcspmm_plan*>(p));
+    if (!p->features_complete || ((wcols || ecol) && !p->condensed_complete)) {
+        const hcspmm_status st = complete_condensed(const_cast<hcspmm_plan*>(p), !(wcols || ecol));
         if (st != HCSPMM_OK) return st;
     }
     const size_t W = (size_t)p->W;

@@ -220,3 +220,40 @@ def test_random_skewed_structures_plan_product_and_layer():
         assert_close(Y2.cpu().numpy().astype(np.float64), ref2, bound2, 2e-5, "aggregate-update")
 
     check()
+
+
+def test_scalar_only_plan_defers_the_window_features():
+    """A scalar-only plan skips the condensing step: SpMM works at once, and the features arrive on the first
+    export (asked for here through the C function directly, before any info call) or info call, bit-exact."""
+    import ctypes
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    from workloads import chung_lu_graph, dense_normal
+    from gpu_util import assert_close, oracle_pair
+    g = chung_lu_graph(5000, 90000, 2.0, seed=11, max_degree=3000)
+    rp, ci, va = device_graph(g)
+    want = oracle.derive_plan_vectorised(g.rowptr, g.colind, [1, 1, 1], mode=1, n_cols=g.n_cols)
+    for first in ("export", "info"):
+        plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, route_mode=hc.HCSPMM_ROUTE_ALL_CSR, d_hint=32)
+        X = dense_normal(g.n_cols, 32, seed=12)
+        Y = torch.empty((g.n_rows, 32), device="cuda")
+        hc.hcspmm_spmm(plan, torch.from_numpy(X).cuda(), Y)
+        torch.cuda.synchronize()
+        ref, bound = oracle_pair(g, X)
+        assert_close(Y.cpu().numpy().astype(np.float64), ref, bound, 1e-5)
+        if first == "export":
+            ncols = np.full(want["W"], -1, np.int32)
+            wptr = np.full(want["W"] + 1, -1, np.int64)
+            st = hc.load_library().hcspmm_plan_export(plan.handle, ncols.ctypes.data_as(ctypes.c_void_p), None, None,
+                                                      wptr.ctypes.data_as(ctypes.c_void_p), None, None, None, None)
+            assert st == 0
+            assert np.array_equal(ncols, want["ncols"]) and np.array_equal(wptr, want["wptr"])
+        info = hc.hcspmm_plan_info(plan)
+        assert info["total_ncols"] == want["wptr"][-1] and info["n_mfma_windows"] == 0
+        got = hc.hcspmm_plan_export(plan)
+        for k in KEYS:
+            assert np.array_equal(got[k], want[k]), k
+        hc.hcspmm_spmm(plan, torch.from_numpy(X).cuda(), Y)       # still usable after the completion
+        torch.cuda.synchronize()
+        assert_close(Y.cpu().numpy().astype(np.float64), ref, bound, 1e-5)
+        plan.destroy()
