@@ -17,6 +17,7 @@ constexpr int64_t kGuardShare = 8;
 
 // ---- preprocessing -----------------------------------------------------------------------------
 constexpr int kUniqueSmallCap = 4096;  // windows with at most this many non-zeros are condensed by an LDS sort
+constexpr int kCountMidCap = 16384;    // windows up to this many non-zeros are counted with an LDS hash set (128 KB)
 constexpr int kBitmapWords = 32768;    // LDS bitmap (1 Mi columns per pass) used to condense larger windows
 constexpr int kEcolLdsCap = 4096;      // distinct-column lists up to this length are searched from LDS
 
@@ -63,11 +64,19 @@ hipError_t launch_validate(int32_t n_rows, int32_t n_cols, int64_t nnz, const in
                            int32_t* err_flag, hipStream_t s);
 hipError_t launch_window_nnz(int32_t W, int32_t n_rows, const int32_t* rowptr, int32_t* nnzw, int32_t* big_list,
                              int32_t* big_count, hipStream_t s);
+// sorted distinct-column lists (route: null = every window, else only windows with route != 0)
 hipError_t launch_unique_small(int32_t W, int32_t n_rows, const int32_t* rowptr, const int32_t* colind,
-                               int32_t* tmp_cols, int32_t* ncols, hipStream_t s);
+                               int32_t* tmp_cols, int32_t* ncols, const uint8_t* route, hipStream_t s);
 hipError_t launch_unique_big(int32_t n_big, const int32_t* big_list, int32_t n_rows, int32_t n_cols,
                              const int32_t* rowptr, const int32_t* colind, int32_t* tmp_cols, int32_t* ncols,
-                             hipStream_t s);
+                             const uint8_t* route, hipStream_t s);
+// distinct-column counts only (LDS hash sets); windows above kCountMidCap non-zeros go to launch_unique_big
+hipError_t launch_window_classes(int32_t W, int32_t n_rows, const int32_t* rowptr, int32_t* nnzw, int32_t* mid_list,
+                                 int32_t* huge_list, int32_t* counts, hipStream_t s);
+hipError_t launch_count_small(int32_t W, int32_t n_rows, const int32_t* rowptr, const int32_t* colind, int32_t* ncols,
+                              hipStream_t s);
+hipError_t launch_count_mid(int32_t n_mid, const int32_t* mid_list, int32_t n_rows, const int32_t* rowptr,
+                            const int32_t* colind, int32_t* ncols, hipStream_t s);
 hipError_t launch_ecol(int32_t W, int32_t n_rows, const int32_t* rowptr, const int32_t* colind,
                        const int32_t* tmp_cols, const int32_t* ncols, const int64_t* wptr, int32_t* wcols,
                        int32_t* erc, int32_t* unsorted_flag, const uint8_t* route, int want,

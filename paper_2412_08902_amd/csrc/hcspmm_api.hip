@@ -167,9 +167,9 @@ static hcspmm_status complete_condensed(hcspmm_plan* p, bool features_only)
     HC_TRY(hipMemsetAsync(cnt, 0, 2 * sizeof(int32_t), nullptr));
     if (W > 0) {
         HC_TRY(launch_window_nnz(W, p->n_rows, p->rowptr, nz_tmp, big_list, cnt + 1, nullptr));
-        HC_TRY(launch_unique_small(W, p->n_rows, p->rowptr, p->colind, tmp_cols, nc_tmp, nullptr));
+        HC_TRY(launch_unique_small(W, p->n_rows, p->rowptr, p->colind, tmp_cols, nc_tmp, nullptr, nullptr));
         HC_TRY(hipMemcpy(&h_big, cnt + 1, sizeof h_big, hipMemcpyDeviceToHost));
-        HC_TRY(launch_unique_big(h_big, big_list, p->n_rows, p->n_cols, p->rowptr, p->colind, tmp_cols, nc_tmp, nullptr));
+        HC_TRY(launch_unique_big(h_big, big_list, p->n_rows, p->n_cols, p->rowptr, p->colind, tmp_cols, nc_tmp, nullptr, nullptr));
     }
     if (!p->features_complete) {
         if (W > 0) HC_TRY(hipMemcpyAsync(p->ncols, nc_tmp, (size_t)W * sizeof(int32_t), hipMemcpyDeviceToDevice, nullptr));
@@ -208,19 +208,19 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     DevAlloc keep;     // plan-owned, freed on failure only
     const int32_t n_rows = p->n_rows, W = p->W;
     const int64_t nnz = p->nnz;
-    int32_t *err = nullptr, *big_list = nullptr, *big_count = nullptr, *tmp_cols = nullptr;
+    int32_t *err = nullptr, *big_list = nullptr, *huge_list = nullptr, *big_count = nullptr, *tmp_cols = nullptr;
     int32_t *f_mfma = nullptr, *f_csr = nullptr, *f_small = nullptr, *f_midw = nullptr, *f_big = nullptr, *nnz_if = nullptr;
     int32_t *f_short = nullptr, *f_mid = nullptr, *n_seg = nullptr, *f_multi = nullptr, *n_slot = nullptr, *len_long = nullptr;
     int64_t *scan_tmp = nullptr, *pos_a = nullptr, *pos_b = nullptr, *pos_c = nullptr, *pos_d = nullptr;
     int64_t *totals_dev = nullptr;
-    int32_t h_err = 0, h_big = 0;
+    int32_t h_err = 0, h_big = 0, h_cls[2] = {0, 0};
     int64_t h_tot[8];
     const int64_t scan_n = (int64_t)(n_rows > W ? n_rows : W) + 1;
 
     {
         // every scratch array of this function has a size known from (n_rows, W, nnz): one allocation
         const size_t i32 = sizeof(int32_t), i64 = sizeof(int64_t);
-        size_t total = DevAlloc::padded(2 * i32) + DevAlloc::padded((size_t)nnz * i32) + DevAlloc::padded((size_t)W * i32) +
+        size_t total = DevAlloc::padded(4 * i32) + DevAlloc::padded((size_t)nnz * i32) + 2 * DevAlloc::padded((size_t)W * i32) +
                        DevAlloc::padded((size_t)scan_scratch_elems(scan_n) * i64) + 4 * DevAlloc::padded((size_t)(scan_n + 1) * i64) +
                        DevAlloc::padded(8 * i64) + 6 * DevAlloc::padded(((size_t)W + 1) * i32) +
                        6 * DevAlloc::padded(((size_t)n_rows + 1) * i32) + 64 * 256;
@@ -231,9 +231,9 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
             goto fail;
         }
     }
-    HC_ALLOC(tmp, err, 2);
-    big_count = err + 1;
-    HC_TRY(hipMemsetAsync(err, 0, 2 * sizeof(int32_t), stream));
+    HC_ALLOC(tmp, err, 4);
+    big_count = err + 1;                           // two counters: windows for the large hash set, for the bitmap
+    HC_TRY(hipMemsetAsync(err, 0, 4 * sizeof(int32_t), stream));
     HC_TRY(launch_validate(n_rows, p->n_cols, nnz, p->rowptr, p->colind, err, stream));
     HC_TRY(hipMemcpyAsync(&h_err, err, sizeof h_err, hipMemcpyDeviceToHost, stream));
     HC_TRY(hipStreamSynchronize(stream));
@@ -251,6 +251,7 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     HC_ALLOC(keep, p->wptr, (size_t)W + 1);
     HC_ALLOC(tmp, tmp_cols, nnz);
     HC_ALLOC(tmp, big_list, W);
+    HC_ALLOC(tmp, huge_list, W);
     HC_ALLOC(tmp, scan_tmp, scan_scratch_elems(scan_n));
     HC_ALLOC(tmp, pos_a, scan_n + 1);
     HC_ALLOC(tmp, pos_b, scan_n + 1);
@@ -264,12 +265,18 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     p->features_complete = (p->opt.route_mode == HCSPMM_ROUTE_ALL_CSR && nnz > 0) ? 0 : 1;
     if (W > 0) {
         // windows, condensing (Section IV-A)
-        HC_TRY(launch_window_nnz(W, n_rows, p->rowptr, p->nnzw, big_list, big_count, stream));
+        // The selector needs the number of distinct columns of every window but the sorted lists only
+        // for the windows it sends to the matrix path: count with LDS hash sets first (bitmap passes for
+        // the few windows beyond the hash set's capacity, which leave their lists behind as well).
+        HC_TRY(launch_window_classes(W, n_rows, p->rowptr, p->nnzw, big_list, huge_list, big_count, stream));
         if (p->features_complete) {
-            HC_TRY(launch_unique_small(W, n_rows, p->rowptr, p->colind, tmp_cols, p->ncols, stream));
-            HC_TRY(hipMemcpyAsync(&h_big, big_count, sizeof h_big, hipMemcpyDeviceToHost, stream));
+            HC_TRY(launch_count_small(W, n_rows, p->rowptr, p->colind, p->ncols, stream));
+            HC_TRY(hipMemcpyAsync(h_cls, big_count, sizeof h_cls, hipMemcpyDeviceToHost, stream));
             HC_TRY(hipStreamSynchronize(stream));
-            HC_TRY(launch_unique_big(h_big, big_list, n_rows, p->n_cols, p->rowptr, p->colind, tmp_cols, p->ncols, stream));
+            h_big = h_cls[0];
+            HC_TRY(launch_count_mid(h_big, big_list, n_rows, p->rowptr, p->colind, p->ncols, stream));
+            HC_TRY(launch_unique_big(h_cls[1], huge_list, n_rows, p->n_cols, p->rowptr, p->colind, tmp_cols, p->ncols,
+                                     nullptr, stream));
         } else {
             HC_TRY(hipMemsetAsync(p->ncols, 0, (size_t)W * sizeof(int32_t), stream));
         }
@@ -332,6 +339,10 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     if (p->n_mfma > 0) {
         HC_ALLOC(keep, p->erc, nnz);
         HC_ALLOC(keep, p->wcols, p->total_ncols);
+        // sorted distinct-column lists of the matrix path's windows (the widest ones have theirs already)
+        HC_TRY(launch_unique_small(W, n_rows, p->rowptr, p->colind, tmp_cols, p->ncols, p->route, stream));
+        HC_TRY(launch_unique_big(h_big, big_list, n_rows, p->n_cols, p->rowptr, p->colind, tmp_cols, p->ncols, p->route,
+                                 stream));
         // err[0] is zero here (validation passed): reuse it as the "some row is unsorted" flag
         HC_TRY(launch_ecol(W, n_rows, p->rowptr, p->colind, tmp_cols, p->ncols, p->wptr, p->wcols, p->erc, err, p->route, 1,
                            stream));

@@ -213,11 +213,13 @@ hipError_t launch_window_nnz(int32_t W, int32_t n_rows, const int32_t* rowptr, i
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_unique_small(int32_t W, int32_t n_rows, const int32_t* __restrict__ rowptr,
                                                       const int32_t* __restrict__ colind,
-                                                      int32_t* __restrict__ tmp_cols, int32_t* __restrict__ ncols)
+                                                      int32_t* __restrict__ tmp_cols, int32_t* __restrict__ ncols,
+                                                      const uint8_t* __restrict__ route /* may be null: every window */)
 {
     __shared__ int32_t keys[kUniqueSmallCap];
     __shared__ int smem[256 / 64 + 1];
     const int32_t w = blockIdx.x;
+    if (route && route[w] == 0) return;          // only the matrix path's windows need the list
     int32_t s, e;
     window_span(w, n_rows, rowptr, s, e);
     const int32_t n = e - s;
@@ -255,9 +257,9 @@ __global__ __launch_bounds__(256) void k_unique_small(int32_t W, int32_t n_rows,
 }
 
 hipError_t launch_unique_small(int32_t W, int32_t n_rows, const int32_t* rowptr, const int32_t* colind,
-                               int32_t* tmp_cols, int32_t* ncols, hipStream_t s)
+                               int32_t* tmp_cols, int32_t* ncols, const uint8_t* route, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_unique_small, dim3(W), dim3(256), 0, s, W, n_rows, rowptr, colind, tmp_cols, ncols);
+    hipLaunchKernelGGL(k_unique_small, dim3(W), dim3(256), 0, s, W, n_rows, rowptr, colind, tmp_cols, ncols, route);
     return hipGetLastError();
 }
 
@@ -267,13 +269,15 @@ hipError_t launch_unique_small(int32_t W, int32_t n_rows, const int32_t* rowptr,
 __global__ __launch_bounds__(1024) void k_unique_big(const int32_t* __restrict__ big_list, int32_t n_rows,
                                                      int32_t n_cols, const int32_t* __restrict__ rowptr,
                                                      const int32_t* __restrict__ colind,
-                                                     int32_t* __restrict__ tmp_cols, int32_t* __restrict__ ncols)
+                                                     int32_t* __restrict__ tmp_cols, int32_t* __restrict__ ncols,
+                                                     const uint8_t* __restrict__ route /* may be null: every listed window */)
 {
     __shared__ uint32_t bm[kBitmapWords];
     __shared__ int smem[1024 / 64 + 1];
     constexpr int kBits = kBitmapWords * 32;
     constexpr int kWordsPerThread = kBitmapWords / 1024;
     const int32_t w = big_list[blockIdx.x];
+    if (route && route[w] == 0) return;
     int32_t s, e;
     window_span(w, n_rows, rowptr, s, e);
     int32_t running = 0;
@@ -308,11 +312,111 @@ __global__ __launch_bounds__(1024) void k_unique_big(const int32_t* __restrict__
 
 hipError_t launch_unique_big(int32_t n_big, const int32_t* big_list, int32_t n_rows, int32_t n_cols,
                              const int32_t* rowptr, const int32_t* colind, int32_t* tmp_cols, int32_t* ncols,
-                             hipStream_t s)
+                             const uint8_t* route, hipStream_t s)
 {
     if (n_big <= 0) return hipSuccess;
     hipLaunchKernelGGL(k_unique_big, dim3(n_big), dim3(1024), 0, s, big_list, n_rows, n_cols, rowptr, colind, tmp_cols,
-                       ncols);
+                       ncols, route);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// window features without the lists: the selector needs only the NUMBER of distinct columns, which
+// an LDS hash set gives for a fraction of the sort's cost; the sorted lists are then built for the
+// matrix path's windows alone
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_window_classes(int32_t W, int32_t n_rows, const int32_t* __restrict__ rowptr,
+                                                        int32_t* __restrict__ nnzw, int32_t* __restrict__ mid_list,
+                                                        int32_t* __restrict__ huge_list, int32_t* __restrict__ counts)
+{
+    int32_t w = blockIdx.x * blockDim.x + threadIdx.x;
+    if (w >= W) return;
+    int32_t s, e;
+    window_span(w, n_rows, rowptr, s, e);
+    const int32_t n = e - s;
+    nnzw[w] = n;
+    if (n > kCountMidCap) huge_list[atomicAdd(counts + 1, 1)] = w;
+    else if (n > kUniqueSmallCap) mid_list[atomicAdd(counts, 1)] = w;
+}
+
+hipError_t launch_window_classes(int32_t W, int32_t n_rows, const int32_t* rowptr, int32_t* nnzw, int32_t* mid_list,
+                                 int32_t* huge_list, int32_t* counts, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_window_classes, dim3((W + 255) / 256), dim3(256), 0, s, W, n_rows, rowptr, nnzw, mid_list,
+                       huge_list, counts);
+    return hipGetLastError();
+}
+
+// Inserts the window's column ids into an open-addressing set of SLOTS >= 2n entries (linear probing,
+// empty = -1; ids are non-negative) and counts the insertions that found an empty slot.  The set is
+// never more than half full, so every probe sequence ends.
+template <int NT, int SLOTS>
+__device__ inline void count_distinct_body(int32_t w, int32_t n_rows, const int32_t* __restrict__ rowptr,
+                                           const int32_t* __restrict__ colind, int32_t* __restrict__ ncols,
+                                           int32_t* table, int* smem)
+{
+    int32_t s, e;
+    window_span(w, n_rows, rowptr, s, e);
+    const int32_t n = e - s;
+    if (n == 0) {
+        if (threadIdx.x == 0) ncols[w] = 0;
+        return;
+    }
+    int T = NT;                                   // power of two, at least twice the entries
+    while (T < 2 * n) T <<= 1;
+    const uint32_t mask = (uint32_t)T - 1;
+    for (int i = threadIdx.x; i < T; i += NT) table[i] = -1;
+    __syncthreads();
+    int cnt = 0;
+    for (int32_t k = s + threadIdx.x; k < e; k += NT) {
+        const int32_t c = colind[k];
+        uint32_t h = ((uint32_t)c * 0x9E3779B1u >> 12) & mask;
+        for (;;) {
+            const int32_t prev = atomicCAS(&table[h], -1, c);
+            if (prev == -1) { ++cnt; break; }
+            if (prev == c) break;
+            h = (h + 1) & mask;
+        }
+    }
+    int total;
+    (void)block_exclusive_scan<NT>(cnt, &total, smem);
+    if (threadIdx.x == 0) ncols[w] = total;
+}
+
+__global__ __launch_bounds__(256) void k_count_small(int32_t W, int32_t n_rows, const int32_t* __restrict__ rowptr,
+                                                     const int32_t* __restrict__ colind, int32_t* __restrict__ ncols)
+{
+    __shared__ int32_t table[2 * kUniqueSmallCap];
+    __shared__ int smem[256 / 64 + 1];
+    const int32_t w = blockIdx.x;
+    int32_t s, e;
+    window_span(w, n_rows, rowptr, s, e);
+    if (e - s > kUniqueSmallCap) return;          // listed for k_count_mid or the bitmap kernel
+    count_distinct_body<256, 2 * kUniqueSmallCap>(w, n_rows, rowptr, colind, ncols, table, smem);
+}
+
+__global__ __launch_bounds__(1024) void k_count_mid(const int32_t* __restrict__ mid_list, int32_t n_rows,
+                                                    const int32_t* __restrict__ rowptr,
+                                                    const int32_t* __restrict__ colind, int32_t* __restrict__ ncols)
+{
+    __shared__ int32_t table[2 * kCountMidCap];
+    __shared__ int smem[1024 / 64 + 1];
+    count_distinct_body<1024, 2 * kCountMidCap>(mid_list[blockIdx.x], n_rows, rowptr, colind, ncols, table, smem);
+}
+
+hipError_t launch_count_small(int32_t W, int32_t n_rows, const int32_t* rowptr, const int32_t* colind, int32_t* ncols,
+                              hipStream_t s)
+{
+    if (W <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_count_small, dim3(W), dim3(256), 0, s, W, n_rows, rowptr, colind, ncols);
+    return hipGetLastError();
+}
+
+hipError_t launch_count_mid(int32_t n_mid, const int32_t* mid_list, int32_t n_rows, const int32_t* rowptr,
+                            const int32_t* colind, int32_t* ncols, hipStream_t s)
+{
+    if (n_mid <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_count_mid, dim3(n_mid), dim3(1024), 0, s, mid_list, n_rows, rowptr, colind, ncols);
     return hipGetLastError();
 }
 
