@@ -80,7 +80,12 @@ hipError_t launch_count_mid(int32_t n_mid, const int32_t* mid_list, int32_t n_ro
 hipError_t launch_ecol(int32_t W, int32_t n_rows, const int32_t* rowptr, const int32_t* colind,
                        const int32_t* tmp_cols, const int32_t* ncols, const int64_t* wptr, int32_t* wcols,
                        int32_t* erc, int32_t* unsorted_flag, const uint8_t* route, int want,
-                       hipStream_t s);
+                       int32_t skip_above /* leave windows with more non-zeros alone */, hipStream_t s);
+// sorted list and condensed positions of the listed matrix-path windows by bitmap ranks (no search)
+hipError_t launch_condense_rank(int32_t n_list, const int32_t* list, int32_t n_rows, const int32_t* rowptr,
+                                const int32_t* colind, const uint8_t* route, const int64_t* wptr, int32_t* wcols,
+                                int32_t* erc, int32_t* unsorted_flag, hipStream_t s);
+constexpr int64_t kRankMaxCols = (int64_t)8 << 19;   // beyond this many columns a window's bitmap passes cost more than searching
 hipError_t launch_select(int32_t W, const int32_t* ncols, const int32_t* nnzw, int64_t c0, int64_t c1, int64_t c2,
                          int32_t mode, uint8_t* route, int32_t* f_mfma, int32_t* f_csr, int32_t* f_small,
                          int32_t* f_mid, int32_t* f_big, int32_t* nnz_if_mfma, hipStream_t s);

@@ -188,7 +188,7 @@ static hcspmm_status complete_condensed(hcspmm_plan* p, bool features_only)
         }
         if (W > 0)
             HC_TRY(launch_ecol(W, p->n_rows, p->rowptr, p->colind, tmp_cols, p->ncols, p->wptr, p->wcols, p->erc, cnt, p->route, 0,
-                               nullptr));
+                               0x7fffffff, nullptr));
         HC_TRY(hipDeviceSynchronize());
         p->condensed_complete = 1;
     }
@@ -339,13 +339,23 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     if (p->n_mfma > 0) {
         HC_ALLOC(keep, p->erc, nnz);
         HC_ALLOC(keep, p->wcols, p->total_ncols);
-        // sorted distinct-column lists of the matrix path's windows (the widest ones have theirs already)
+        // err[0] is zero here (validation passed): reuse it as the "some row is unsorted" flag.
+        // Windows up to kUniqueSmallCap non-zeros: sorted list by the LDS sort, positions by binary search in it.
+        // Larger ones: list and positions together from bitmap ranks, unless the matrix is so wide that the
+        // bitmap passes would cost more than searching (then the bitmap list + search route serves them too).
+        const bool by_rank = p->n_cols <= kRankMaxCols;
         HC_TRY(launch_unique_small(W, n_rows, p->rowptr, p->colind, tmp_cols, p->ncols, p->route, stream));
-        HC_TRY(launch_unique_big(h_big, big_list, n_rows, p->n_cols, p->rowptr, p->colind, tmp_cols, p->ncols, p->route,
-                                 stream));
-        // err[0] is zero here (validation passed): reuse it as the "some row is unsorted" flag
+        if (by_rank) {
+            HC_TRY(launch_condense_rank(h_big, big_list, n_rows, p->rowptr, p->colind, p->route, p->wptr, p->wcols, p->erc,
+                                        err, stream));
+            HC_TRY(launch_condense_rank(h_cls[1], huge_list, n_rows, p->rowptr, p->colind, p->route, p->wptr, p->wcols,
+                                        p->erc, err, stream));
+        } else {
+            HC_TRY(launch_unique_big(h_big, big_list, n_rows, p->n_cols, p->rowptr, p->colind, tmp_cols, p->ncols, p->route,
+                                     stream));
+        }
         HC_TRY(launch_ecol(W, n_rows, p->rowptr, p->colind, tmp_cols, p->ncols, p->wptr, p->wcols, p->erc, err, p->route, 1,
-                           stream));
+                           by_rank ? kUniqueSmallCap : 0x7fffffff, stream));
         HC_TRY(hipMemcpyAsync(&h_err, err, sizeof h_err, hipMemcpyDeviceToHost, stream));
         HC_TRY(hipStreamSynchronize(stream));
         p->rows_sorted = h_err ? 0 : 1;

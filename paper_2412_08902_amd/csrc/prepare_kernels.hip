@@ -428,7 +428,7 @@ __global__ __launch_bounds__(256) void k_ecol(int32_t n_rows, const int32_t* __r
                                               const int32_t* __restrict__ tmp_cols, const int32_t* __restrict__ ncols,
                                               const int64_t* __restrict__ wptr, int32_t* __restrict__ wcols,
                                               int32_t* __restrict__ erc, int32_t* __restrict__ unsorted_flag,
-                                              const uint8_t* __restrict__ route, int want)
+                                              const uint8_t* __restrict__ route, int want, int32_t skip_above)
 {
     __shared__ int32_t ucols[kEcolLdsCap];
     __shared__ int32_t rp[kH + 1];
@@ -436,7 +436,7 @@ __global__ __launch_bounds__(256) void k_ecol(int32_t n_rows, const int32_t* __r
     if ((route[w] != 0) != (want != 0)) return;      // only the windows of one route
     int32_t s, e;
     window_span(w, n_rows, rowptr, s, e);
-    if (e == s) return;
+    if (e == s || e - s > skip_above) return;        // larger windows were condensed by k_condense_rank
     const int32_t nc = ncols[w];
     const int64_t wp = wptr[w];
     const int32_t* __restrict__ src = tmp_cols + (int64_t)s;
@@ -472,10 +472,114 @@ __global__ __launch_bounds__(256) void k_ecol(int32_t n_rows, const int32_t* __r
 
 hipError_t launch_ecol(int32_t W, int32_t n_rows, const int32_t* rowptr, const int32_t* colind,
                        const int32_t* tmp_cols, const int32_t* ncols, const int64_t* wptr, int32_t* wcols,
-                       int32_t* erc, int32_t* unsorted_flag, const uint8_t* route, int want, hipStream_t s)
+                       int32_t* erc, int32_t* unsorted_flag, const uint8_t* route, int want, int32_t skip_above,
+                       hipStream_t s)
 {
     hipLaunchKernelGGL(k_ecol, dim3(W), dim3(256), 0, s, n_rows, rowptr, colind, tmp_cols, ncols, wptr, wcols, erc,
-                       unsorted_flag, route, want);
+                       unsorted_flag, route, want, skip_above);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// condensing of large matrix-path windows in one go: an LDS bitmap of the window's columns plus a
+// prefix count per bitmap word gives the sorted list AND every non-zero's position in it (its rank)
+// without a search; 2^19 columns per pass over the window's own column range
+// ------------------------------------------------------------------------------------------------
+constexpr int kRankWords = 16384;
+
+__global__ __launch_bounds__(1024) void k_condense_rank(const int32_t* __restrict__ list, int32_t n_rows,
+                                                        const int32_t* __restrict__ rowptr,
+                                                        const int32_t* __restrict__ colind,
+                                                        const uint8_t* __restrict__ route,
+                                                        const int64_t* __restrict__ wptr, int32_t* __restrict__ wcols,
+                                                        int32_t* __restrict__ erc, int32_t* __restrict__ unsorted_flag)
+{
+    __shared__ uint32_t bm[kRankWords];
+    __shared__ int32_t pre[kRankWords];
+    __shared__ int smem[1024 / 64 + 1];
+    __shared__ int32_t rp[kH + 1];
+    __shared__ int32_t span_lo, span_hi;
+    constexpr int kBits = kRankWords * 32;
+    constexpr int kWordsPerThread = kRankWords / 1024;
+    const int32_t w = list[blockIdx.x];
+    if (route[w] == 0) return;
+    int32_t s, e;
+    window_span(w, n_rows, rowptr, s, e);
+    if (e == s) return;
+    const int64_t wp = wptr[w];
+    if (threadIdx.x <= kH) {
+        int64_t r = (int64_t)w * kH + threadIdx.x;
+        if (r > n_rows) r = n_rows;
+        rp[threadIdx.x] = rowptr[r];
+    }
+    if (threadIdx.x == 0) { span_lo = 0x7fffffff; span_hi = -1; }
+    __syncthreads();
+    {
+        int32_t lo = 0x7fffffff, hi = -1;
+        for (int32_t k = s + threadIdx.x; k < e; k += 1024) {
+            const int32_t c = colind[k];
+            lo = min(lo, c);
+            hi = max(hi, c);
+        }
+        if (hi >= 0) { atomicMin(&span_lo, lo); atomicMax(&span_hi, hi); }
+    }
+    __syncthreads();
+    const int32_t cmax = span_hi;
+    int32_t running = 0;
+    const int w0 = threadIdx.x * kWordsPerThread;
+    for (int64_t base = span_lo & ~31; base <= cmax; base += kBits) {
+        for (int i = threadIdx.x; i < kRankWords; i += 1024) bm[i] = 0u;
+        __syncthreads();
+        for (int32_t k = s + threadIdx.x; k < e; k += 1024) {
+            const int64_t c = (int64_t)colind[k] - base;
+            if (c >= 0 && c < kBits) atomicOr(&bm[c >> 5], 1u << (c & 31));
+        }
+        __syncthreads();
+        int cnt = 0;
+#pragma unroll 4
+        for (int i = 0; i < kWordsPerThread; ++i) cnt += __popc(bm[w0 + i]);
+        int total;
+        const int off = block_exclusive_scan<1024>(cnt, &total, smem);
+        {
+            int run = off;
+            int32_t* out = wcols + wp + running + off;
+            for (int i = 0; i < kWordsPerThread; ++i) {
+                uint32_t bits = bm[w0 + i];
+                pre[w0 + i] = run;
+                run += __popc(bits);
+                while (bits) {
+                    const int b = __ffs(bits) - 1;
+                    bits &= bits - 1;
+                    *out++ = (int32_t)(base + (int64_t)(w0 + i) * 32 + b);
+                }
+            }
+        }
+        __syncthreads();
+        for (int32_t k = s + threadIdx.x; k < e; k += 1024) {
+            const int32_t col = colind[k];
+            const int64_t c = (int64_t)col - base;
+            if (c < 0 || c >= kBits) continue;
+            const int word = (int)(c >> 5);
+            const int rank = running + pre[word] + __popc(bm[word] & ((1u << (c & 31)) - 1u));
+            int r = 0;                              // row of k inside the window: last r with rp[r] <= k
+#pragma unroll
+            for (int step = 8; step > 0; step >>= 1)
+                if (r + step < kH && rp[r + step] <= k) r += step;
+            erc[k] = (rank << 4) | r;
+            if (k > rp[r] && colind[k - 1] > col) atomicOr(unsorted_flag, 1);
+        }
+        running += total;
+        __syncthreads();
+    }
+}
+
+hipError_t launch_condense_rank(int32_t n_list, const int32_t* list, int32_t n_rows, const int32_t* rowptr,
+                                const int32_t* colind, const uint8_t* route, const int64_t* wptr, int32_t* wcols,
+                                int32_t* erc, int32_t* unsorted_flag, hipStream_t s)
+{
+    if (n_list <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_condense_rank, dim3(n_list), dim3(1024), 0, s, list, n_rows, rowptr, colind, route, wptr, wcols,
+                       erc, unsorted_flag);
     return hipGetLastError();
 }
 

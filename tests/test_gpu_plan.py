@@ -257,3 +257,39 @@ def test_scalar_only_plan_defers_the_window_features():
         torch.cuda.synchronize()
         assert_close(Y.cpu().numpy().astype(np.float64), ref, bound, 1e-5)
         plan.destroy()
+
+
+@pytest.mark.parametrize("m", [200_000, 3_000_000, 6_000_000])
+@pytest.mark.parametrize("srt", [True, False])
+def test_large_matrix_path_windows_lists_and_positions(m, srt):
+    """Windows beyond the LDS sort (11,200 and 30,000+ non-zeros) forced onto the matrix path: their sorted column
+    lists and every non-zero's position come from bitmap ranks (narrower matrices) or from the bitmap list plus a
+    search (matrices too wide for that), with sorted and with shuffled rows; plan bit-exact, product within the gate."""
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    from workloads import dense_normal
+    from gpu_util import assert_close, oracle_pair
+    n = 64
+    rng = np.random.default_rng(5)
+    lens = np.full(n, 5)
+    lens[0:16] = 700
+    lens[40] = 30000
+    lens[50] = 4100
+    cols = [rng.choice(m, size=l, replace=False) for l in lens]
+    cols[3] = cols[2].copy()
+    cols = [np.sort(c) if srt else c for c in cols]
+    rp = np.zeros(n + 1, np.int32)
+    np.cumsum(lens, out=rp[1:])
+    vals = rng.standard_normal(int(lens.sum())).astype(np.float32)
+    g = CSRGraph(n, m, rp, np.concatenate(cols).astype(np.int32), vals)
+    got, info = check_plan(g, mode=2)
+    assert info["n_mfma_windows"] == 4 and got["ncols"][2] > 30000
+    X = dense_normal(m, 16, seed=6)
+    rpd, cid, vad = device_graph(g)
+    plan = hc.hcspmm_prepare(n, m, rpd, cid, vad, route_mode=2, d_hint=16)
+    Y = torch.empty((n, 16), device="cuda")
+    hc.hcspmm_spmm(plan, torch.from_numpy(X).cuda(), Y)
+    torch.cuda.synchronize()
+    plan.destroy()
+    ref, bound = oracle_pair(g, X)
+    assert_close(Y.cpu().numpy().astype(np.float64), ref, bound, 1e-5)
