@@ -401,24 +401,44 @@ __global__ __launch_bounds__(256) void k_mfma_wg(const WgSlice* __restrict__ sli
     }
     for (int32_t kc0 = sl.kc_begin; kc0 < nc; kc0 += KC) {
         const int kend = min(KC, nc - kc0);
+        // a row's 16 threads take its next kRound*16 entries per round: the round's loads are
+        // independent (one memory latency per round, not per 16 entries) and the first round is
+        // requested before the tile is cleared
+        constexpr int kRound = 4;
+        int32_t pr[kRound];
+        float vr[kRound];
+        auto fetch_round = [&]() {
+#pragma unroll
+            for (int j = 0; j < kRound; ++j) {
+                const int32_t k = cur + 16 * j + l16;
+                pr[j] = 0x7fffffff;                            // past the row's end: never taken
+                vr[j] = 0.f;
+                if (k < row_e) {
+                    pr[j] = erc[k];
+                    vr[j] = a.vals[k];
+                }
+            }
+        };
+        if (rows_sorted) fetch_round();
         for (int i = threadIdx.x * 4; i < KC * 16; i += 1024)
             *reinterpret_cast<float4*>(&tile[i]) = make_float4(0.f, 0.f, 0.f, 0.f);
         __syncthreads();
         if (rows_sorted) {
             const int32_t limit = kc0 + KC;
+            const int shift = 16 * ((threadIdx.x & 63) >> 4);
             for (;;) {
-                const int32_t k = cur + l16;
-                int32_t p = 0;
-                bool take = false;
-                if (k < row_e) {
-                    p = erc[k];
-                    take = (p >> 4) < limit;
+                int n = 0;
+#pragma unroll
+                for (int j = 0; j < kRound; ++j) {
+                    // entries ascend, so the ones taken are a prefix; 0x7fffffff is no packed entry (positions stay below 2^27 - 1)
+                    const bool take = pr[j] != 0x7fffffff && (pr[j] >> 4) < limit;
+                    if (take) atomicAdd(&tile[P::tidx((pr[j] >> 4) - kc0, my_r)], vr[j]);
+                    const unsigned long long b = __ballot(take);
+                    n += __popc((unsigned)((b >> shift) & 0xffffu));
                 }
-                if (take) atomicAdd(&tile[P::tidx((p >> 4) - kc0, my_r)], a.vals[k]);
-                const unsigned long long b = __ballot(take);
-                const int n = __popc((unsigned)((b >> (16 * ((threadIdx.x & 63) >> 4))) & 0xffffu));
                 cur += n;
-                if (n < 16) break;
+                if (n < 16 * kRound) break;
+                fetch_round();
             }
         } else {
             for (int32_t k = s + threadIdx.x; k < e; k += 256) {
