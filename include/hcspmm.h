@@ -189,6 +189,8 @@ hcspmm_status hcspmm_plan_export(const hcspmm_plan* plan, int32_t* ncols, int32_
  * grow them): calls that use the same plan must be ordered, i.e. issued on one stream or
  * otherwise serialised by the caller.  Different plans are independent.  Once a call with the
  * largest d in use has been made, later calls allocate nothing and can be captured in a HIP graph.
+ * The same holds for hcspmm_gcn_layer(_ex), hcspmm_aggregate_update and hcspmm_layer_backward: after
+ * one eager call of each with the shapes in use they only enqueue kernels on `stream`.
  * On the matrix path X must be finite: the dense-tile product multiplies every gathered row with
  * explicit zeros, so a NaN or Inf in a gathered row reaches all 16 rows of its window.
  */

@@ -158,9 +158,13 @@ hipError_t launch_gemm_tn(int64_t n_rows, const float* X, int64_t ldx, int32_t d
 #define HC_TN(NB)                                                                                              \
     {                                                                                                          \
         const size_t lds_bytes = (size_t)(kTnRows * kTnLdx + kTnRows * TnShape<NB>::LDS_S) * sizeof(float);    \
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_tn<NB>),                      \
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);        \
-        if (e != hipSuccess) return e;                                                                         \
+        static bool attr_set = false;      /* once per process: later calls may run under stream capture */    \
+        if (!attr_set) {                                                                                       \
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_tn<NB>),                  \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);    \
+            if (e != hipSuccess) return e;                                                                     \
+            attr_set = true;                                                                                   \
+        }                                                                                                      \
         hipLaunchKernelGGL((k_gemm_tn<NB>), grid, dim3(256), lds_bytes, s, n_rows, rows_per_span, X, ldx, d_in, S, lds_, \
                            d, partial, xvec, svec);                                                            \
     }

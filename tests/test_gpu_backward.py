@@ -189,3 +189,58 @@ def test_backward_is_deterministic():
     b = run_backward(g, G, X, W)
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2])
     check(g, G, X, W, *a)
+
+
+def test_layer_calls_replay_from_a_hip_graph():
+    """Forward layer, fused aggregate-update and backward pass enqueue kernels only (after a first eager call that
+    sizes the plan's lazily allocated buffers), so they can be captured; replays with new inputs written eagerly in
+    between must reproduce the eager results bit for bit."""
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    g = gcn_normalise(chung_lu_graph(6000, 120000, 2.0, seed=61, max_degree=2500))
+    rp, ci, va = device_graph(g)
+    plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, d_hint=32)
+    d_in, d_out = 48, 32
+    Xs = [torch.from_numpy(dense_normal(g.n_rows, d_in, seed=70 + i)).cuda() for i in range(2)]
+    Gs = [torch.from_numpy(dense_normal(g.n_rows, d_out, seed=80 + i)).cuda() for i in range(2)]
+    W = torch.from_numpy(glorot_uniform(d_in, d_out, seed=62)).cuda()
+    W2 = torch.from_numpy(glorot_uniform(d_out, d_in, seed=63)).cuda()
+    X, G = Xs[0].clone(), Gs[0].clone()
+    Y = torch.empty((g.n_rows, d_out), device="cuda")
+    Z = torch.empty((g.n_rows, d_in), device="cuda")
+    dX = torch.empty((g.n_rows, d_in), device="cuda")
+    dW = torch.empty((d_in, d_out), device="cuda")
+    ws1 = torch.empty(hc.hcspmm_gcn_workspace_bytes(plan, d_in, d_out), dtype=torch.uint8, device="cuda")
+    ws2 = torch.empty(hc.hcspmm_aggregate_update_workspace_bytes(plan, d_out, d_in), dtype=torch.uint8, device="cuda")
+    ws3 = torch.empty(hc.hcspmm_layer_backward_workspace_bytes(plan, d_in, d_out), dtype=torch.uint8, device="cuda")
+
+    def step():
+        hc.hcspmm_gcn_layer(plan, X, W, Y, ws1)                       # Y = ReLU(A (X W))
+        hc.hcspmm_aggregate_update(plan, G, W2, Z, ws2)               # Z = ReLU((A G) W2)
+        hc.hcspmm_layer_backward(plan, G, X, W, dX, dW, ws3, Y_fwd=Y)
+
+    eager = []
+    for Xi, Gi in zip(Xs, Gs):
+        X.copy_(Xi)
+        G.copy_(Gi)
+        step()
+        torch.cuda.synchronize()
+        eager.append([t.clone() for t in (Y, Z, dX, dW)])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for rep in range(2):
+        for i in range(2):
+            X.copy_(Xs[i])
+            G.copy_(Gs[i])
+            for t in (Y, Z, dX, dW):
+                t.fill_(-1.0)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for got, want, name in zip((Y, Z, dX, dW), eager[i], ("Y", "Z", "dX", "dW")):
+                assert torch.equal(got, want), "replay %d, input %d: %s differs from the eager result" % (rep, i, name)
+    del graph
+    plan.destroy()
