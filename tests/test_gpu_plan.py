@@ -168,7 +168,8 @@ def test_random_structures_plan_and_product():
 
 def test_random_skewed_structures_plan_product_and_layer():
     """Seeded random structures with heavy-tailed row lengths (rows of every tier, windows of every width class,
-    unsorted rows, duplicates): plan bit-exact; SpMM and the fused aggregate-then-update layer within the gates."""
+    unsorted rows, duplicates): plan bit-exact; SpMM, the fused aggregate-then-update layer and the backward pass
+    (fused update forced on) within the gates."""
     import os
     import torch
     import paper_2412_08902_amd.binding as hc
@@ -212,12 +213,26 @@ def test_random_skewed_structures_plan_product_and_layer():
         try:
             hc.hcspmm_aggregate_update(plan, Xd, torch.from_numpy(W).cuda(), Y2, ws, apply_relu=False)
             torch.cuda.synchronize()
+            # backward pass of a layer with a d_out x d weight matrix: G = X (n_cols x d), layer input n_rows x d_out
+            Xin = rng.standard_normal((n_rows, d_out)).astype(np.float32)
+            Wb = glorot_uniform(d_out, d, seed=seed % 999)
+            Yf = rng.standard_normal((n_cols, d)).astype(np.float32)
+            ws3 = torch.empty(max(256, hc.hcspmm_layer_backward_workspace_bytes(plan, d_out, d)), dtype=torch.uint8, device="cuda")
+            dX = torch.full((n_rows, d_out), float("nan"), device="cuda")
+            dW = torch.full((d_out, d), float("nan"), device="cuda")
+            hc.hcspmm_layer_backward(plan, Xd, torch.from_numpy(Xin).cuda(), torch.from_numpy(Wb).cuda(), dX, dW, ws3,
+                                     Y_fwd=torch.from_numpy(Yf).cuda())
+            torch.cuda.synchronize()
         finally:
             del os.environ["HCSPMM_TUNE_FORCE_FUSE"]
         plan.destroy()
         ref2 = oracle.aggregate_update(rowptr, colind, vals, X, W, relu=False)
         bound2 = oracle.aggregate_update(rowptr, colind, vals, X, W, use_abs=True)
         assert_close(Y2.cpu().numpy().astype(np.float64), ref2, bound2, 2e-5, "aggregate-update")
+        ref_dx, ref_dw = oracle.layer_backward(rowptr, colind, vals, X, Xin, Wb, Y_fwd=Yf)
+        b_dx, b_dw = oracle.layer_backward(rowptr, colind, vals, X, Xin, Wb, Y_fwd=Yf, use_abs=True)
+        assert_close(dX.cpu().numpy().astype(np.float64), ref_dx, b_dx, 2e-5, "backward dX")
+        assert_close(dW.cpu().numpy().astype(np.float64), ref_dw, b_dw, 2e-5, "backward dW")
 
     check()
 
