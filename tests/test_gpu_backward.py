@@ -244,3 +244,55 @@ def test_layer_calls_replay_from_a_hip_graph():
                 assert torch.equal(got, want), "replay %d, input %d: %s differs from the eager result" % (rep, i, name)
     del graph
     plan.destroy()
+
+
+def test_two_layer_gcn_forward_and_backward_compose():
+    """out = A (ReLU(A (X W1)) W2), L = <C, out>: both layers' forward and backward calls chained on the GPU against the
+    same chain of oracle calls.  The hidden activations the GPU computed are handed to the oracle as they are (fp32),
+    so the activation mask and the second layer's input are the same bits on both sides."""
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    g = gcn_normalise(chung_lu_graph(4000, 70000, 2.0, seed=91, max_degree=1500))
+    n, d0, d1, d2 = g.n_rows, 40, 32, 16
+    X, W1, W2 = dense_normal(n, d0, seed=92), glorot_uniform(d0, d1, seed=93), glorot_uniform(d1, d2, seed=94)
+    C = dense_normal(n, d2, seed=95)
+    rp, ci, va = device_graph(g)
+    dev = lambda a: torch.from_numpy(a).cuda()
+    Xd, W1d, W2d, Cd = dev(X), dev(W1), dev(W2), dev(C)
+    H1 = torch.empty((n, d1), device="cuda")
+    out = torch.empty((n, d2), device="cuda")
+    dH1 = torch.empty((n, d1), device="cuda")
+    dW2 = torch.empty((d1, d2), device="cuda")
+    dX = torch.empty((n, d0), device="cuda")
+    dW1 = torch.empty((d0, d1), device="cuda")
+    plan1 = hc.hcspmm_prepare(n, n, rp, ci, va, d_hint=d1)
+    plan2 = hc.hcspmm_prepare(n, n, rp, ci, va, d_hint=d2)
+    ws = torch.empty(max(hc.hcspmm_gcn_workspace_bytes(plan1, d0, d1), hc.hcspmm_gcn_workspace_bytes(plan2, d1, d2),
+                         hc.hcspmm_layer_backward_workspace_bytes(plan1, d0, d1),
+                         hc.hcspmm_layer_backward_workspace_bytes(plan2, d1, d2)), dtype=torch.uint8, device="cuda")
+    hc.hcspmm_gcn_layer(plan1, Xd, W1d, H1, ws, apply_relu=True)
+    hc.hcspmm_gcn_layer(plan2, H1, W2d, out, ws, apply_relu=False)
+    hc.hcspmm_layer_backward(plan2, Cd, H1, W2d, dH1, dW2, ws)                    # layer 2: no activation
+    hc.hcspmm_layer_backward(plan1, dH1, Xd, W1d, dX, dW1, ws, Y_fwd=H1)          # layer 1: masked by its output
+    torch.cuda.synchronize()
+    plan1.destroy()
+    plan2.destroy()
+    f64 = lambda t: t.cpu().numpy().astype(np.float64)
+    H1h = H1.cpu().numpy()
+    a = (g.rowptr, g.colind, g.vals)
+    # forward
+    assert_close(f64(H1), oracle.gcn_layer(*a, X, W1), oracle.gcn_layer(*a, X, W1, use_abs=True), 2 * TOL_F32, "H1")
+    assert_close(f64(out), oracle.gcn_layer(*a, H1h, W2, relu=False), oracle.gcn_layer(*a, H1h, W2, use_abs=True),
+                 2 * TOL_F32, "out")
+    # backward, layer 2 then layer 1 (the oracle's layer-1 input gradient is its own fp64 dH1)
+    r_dH1, r_dW2 = oracle.layer_backward(*a, C, H1h, W2)
+    b_dH1, b_dW2 = oracle.layer_backward(*a, C, H1h, W2, use_abs=True)
+    assert_close(f64(dH1), r_dH1, b_dH1, 2 * TOL_F32, "dH1")
+    assert_close(f64(dW2), r_dW2, b_dW2, 2 * TOL_F32, "dW2")
+    r_dX, r_dW1 = oracle.layer_backward(*a, r_dH1, X, W1, Y_fwd=H1h)
+    b_dX, b_dW1 = oracle.layer_backward(*a, b_dH1, X, W1, Y_fwd=H1h, use_abs=True)
+    assert_close(f64(dX), r_dX, b_dX, 4 * TOL_F32, "dX")
+    assert_close(f64(dW1), r_dW1, b_dW1, 4 * TOL_F32, "dW1")
+    # the bilinear identity of the last layer ties the loss to its weight gradient: <dW2, W2> = <C, out>
+    L = float(np.sum(C.astype(np.float64) * f64(out)))
+    assert abs(float(np.sum(f64(dW2) * W2)) - L) <= 1e-5 * float(np.sum(np.abs(C) * oracle.gcn_layer(*a, H1h, W2, use_abs=True)))
