@@ -283,7 +283,8 @@ size_t hcspmm_aggregate_update_workspace_bytes(const hcspmm_plan* plan, int32_t 
  * This is the stage of training where the update follows the aggregation (Section V-A): dX is
  * computed like hcspmm_aggregate_update computes its Y, the aggregated tile multiplied by W^T on the
  * matrix cores without a round trip (under the same conditions: d_out a multiple of 16 up to 256,
- * few long rows), else by a GEMM.  dW is a reduction over all rows of the graph: S is also written
+ * few long rows; with d_dW given, which makes the kernels store the tile as well, only for d_out <= 32,
+ * where that measured faster), else by a GEMM.  dW is a reduction over all rows of the graph: S is also written
  * to the workspace, and one streaming fp32 MFMA kernel forms X^T S from contiguous row spans whose
  * partial products are added in span order (the result does not depend on scheduling).
  * Eq. 3 as printed, W' = Z^T X' with the aggregated Z = A X_k, is the same call with the dense
@@ -297,7 +298,7 @@ size_t hcspmm_aggregate_update_workspace_bytes(const hcspmm_plan* plan, int32_t 
  *   d_dX    device, n_rows x d_in fp32 (lddx >= d_in), overwritten;  NULL: dX is not computed
  *   d_dW    device, d_in x d_out fp32 (lddw >= d_out), overwritten;  NULL: dW is not computed
  *   d_workspace  device, at least hcspmm_layer_backward_workspace_bytes(plan, d_in, d_out) bytes,
- *                256-byte aligned; its first n_rows x d_out floats hold S on return
+ *                256-byte aligned; its first n_rows x d_out floats hold S on return when d_dW was given
  * Outputs must not alias inputs.  Asynchronous on `stream`.  Errors as hcspmm_spmm.
  */
 hcspmm_status hcspmm_layer_backward(const hcspmm_plan* plan, const void* d_G, int64_t ldg, int32_t d_out,
