@@ -52,3 +52,42 @@ def test_host_only_calls():
     assert lib.hcspmm_gcn_layer(None, None, 0, 4, None, 0, 4, None, 0, 1, None, 0, None) == hc.HCSPMM_EINVAL
     assert lib.hcspmm_gcn_workspace_bytes(None, 4, 4) == 0
     lib.hcspmm_plan_destroy(None)
+
+
+def test_header_is_plain_c(tmp_path):
+    """The public header must compile as C (no C++ constructs, no HIP or torch types) and link against the library."""
+    import shutil
+    import subprocess
+    import paper_2412_08902_amd.binding as hc
+    gcc = shutil.which("gcc")
+    assert gcc, "gcc is part of the image"
+    src = tmp_path / "use_header.c"
+    src.write_text(
+        '#include "hcspmm.h"\n'
+        "#include <stdio.h>\n"
+        "int main(void) {\n"
+        "    hcspmm_options o;\n"
+        "    hcspmm_default_options(&o);\n"
+        "    hcspmm_plan* plan = NULL;\n"
+        "    hcspmm_status st = hcspmm_prepare(-1, 1, 0, NULL, NULL, NULL, &o, NULL, &plan);\n"
+        "    size_t ws = hcspmm_layer_backward_workspace_bytes(NULL, 4, 4);\n"
+        '    printf("%d %d %s %d\\n", (int)st, (int)ws, hcspmm_status_string(st), (int)hcspmm_version());\n'
+        "    return (st == HCSPMM_EINVAL && plan == NULL && ws == 0) ? 0 : 1;\n"
+        "}\n")
+    exe = tmp_path / "use_header"
+    lib_dir = os.path.dirname(hc.LIB_PATH)
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), str(src), "-o",
+                        str(exe), "-L", lib_dir, "-lhcspmm", "-Wl,-rpath," + lib_dir], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0, (r.stdout, r.stderr)
+    assert r.stdout.split()[0] == "1"
+
+
+def test_new_entry_points_reject_bad_arguments_on_the_host():
+    import paper_2412_08902_amd.binding as hc
+    lib = hc.load_library()
+    assert lib.hcspmm_layer_backward(None, None, 0, 4, None, 0, None, 0, 4, None, 0, None, 0, None, 0, None, 0, None) == hc.HCSPMM_EINVAL
+    assert lib.hcspmm_aggregate_update(None, None, 0, 4, 0, None, 0, 4, None, 0, 1, None, 0, None) == hc.HCSPMM_EINVAL
+    assert lib.hcspmm_layer_backward_workspace_bytes(None, 4, 4) == 0
+    assert lib.hcspmm_aggregate_update_workspace_bytes(None, 4, 4) == 0
