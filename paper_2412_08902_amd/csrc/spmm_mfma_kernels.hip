@@ -188,6 +188,27 @@ __device__ inline void block_stages(const float* __restrict__ blk, int ncols_blk
     }
 }
 
+// The same with the gathers three stages ahead of the MFMAs (four stage buffers in a ring), for
+// paths whose 64-column block has four stages.  On entry the block's stages 0..2 are in flight in
+// xa[0..2]; on exit, if there is a next block, its stages 0..2 are.  Stages past a block's last
+// column still have valid column ids (they repeat the last column), so requesting them is harmless
+// and the ring needs no per-stage bookkeeping.
+template <class P, int NG, int VW>
+__device__ inline void block_stages_deep(const float* __restrict__ blk, int ncols_blk, int32_t col_cur, bool has_next,
+                                         int32_t col_next, int lane, const char* __restrict__ X, int64_t ldxb, int d,
+                                         typename P::Buf (&xa)[4], v4f (&acc)[NG][VW])
+{
+    static_assert(64 / P::SCOLS == 4, "ring of four stage buffers");
+    if (3 * P::SCOLS < ncols_blk) P::load(3, col_cur, lane, X, ldxb, d, xa[3]);
+    P::compute(0, blk, lane, xa[0], acc);
+    if (has_next) P::load(0, col_next, lane, X, ldxb, d, xa[0]);
+    if (1 * P::SCOLS < ncols_blk) P::compute(1, blk, lane, xa[1], acc);
+    if (has_next) P::load(1, col_next, lane, X, ldxb, d, xa[1]);
+    if (2 * P::SCOLS < ncols_blk) P::compute(2, blk, lane, xa[2], acc);
+    if (has_next) P::load(2, col_next, lane, X, ldxb, d, xa[2]);
+    if (3 * P::SCOLS < ncols_blk) P::compute(3, blk, lane, xa[3], acc);
+}
+
 template <int VW, int NG>
 __device__ inline void store_tile(const v4f (&acc)[NG][VW], int lane, int32_t r0, int32_t n_rows, float* __restrict__ Y,
                                   int64_t ldy, int d, int relu)
@@ -379,7 +400,8 @@ __global__ __launch_bounds__(256) void k_mfma_wg(const WgSlice* __restrict__ sli
     for (int g = 0; g < NG; ++g)
 #pragma unroll
         for (int t = 0; t < VW; ++t) acc[g][t] = (v4f){0.f, 0.f, 0.f, 0.f};
-    typename P::Buf xa[2];
+    constexpr bool kDeep = XK != 0 && 64 / P::SCOLS == 4;   // 16-bit X: gathers three stages ahead instead of one
+    typename P::Buf xa[kDeep ? 4 : 2];
 
     // When every row's columns ascend, so do its condensed columns: 16 threads per row keep a
     // cursor that only moves forward, and a chunk costs only the entries that fall into it.
@@ -398,6 +420,10 @@ __global__ __launch_bounds__(256) void k_mfma_wg(const WgSlice* __restrict__ sli
     if (wave * 64 < min(KC, nc - sl.kc_begin)) {
         col_cur = wcols[wp + min(sl.kc_begin + wave * 64 + lane, nc - 1)];
         P::load(0, col_cur, lane, X, ldxb, d, xa[0]);
+        if constexpr (kDeep) {
+            P::load(1, col_cur, lane, X, ldxb, d, xa[1]);
+            P::load(2, col_cur, lane, X, ldxb, d, xa[2]);
+        }
     }
     for (int32_t kc0 = sl.kc_begin; kc0 < nc; kc0 += KC) {
         const int kend = min(KC, nc - kc0);
@@ -453,8 +479,12 @@ __global__ __launch_bounds__(256) void k_mfma_wg(const WgSlice* __restrict__ sli
             if (nkb >= kend) { nkc0 = kc0 + KC; nkb = wave * 64; }
             const bool has_next = nkc0 < nc && nkb < min(KC, nc - nkc0);
             col_next = has_next ? wcols[wp + min(nkc0 + nkb + lane, nc - 1)] : col_cur;
-            block_stages<P, NG, VW>(tile + kb * 16, min(64, kend - kb), col_cur, has_next, col_next, lane, X, ldxb, d,
-                                    xa, acc);
+            if constexpr (kDeep)
+                block_stages_deep<P, NG, VW>(tile + kb * 16, min(64, kend - kb), col_cur, has_next, col_next, lane, X, ldxb,
+                                             d, xa, acc);
+            else
+                block_stages<P, NG, VW>(tile + kb * 16, min(64, kend - kb), col_cur, has_next, col_next, lane, X, ldxb, d,
+                                        xa, acc);
             col_cur = col_next;
         }
         __syncthreads();
