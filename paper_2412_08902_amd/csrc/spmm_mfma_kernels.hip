@@ -58,37 +58,44 @@ template <int VW, int NG> struct Path<0, VW, NG> {
     static constexpr int U = SCOLS / 4;                        // K-steps (4 columns each) per stage
     struct Buf { float x[U][NG][VW]; };
     __device__ static inline int tidx(int k, int r) { return k * 16 + r; }
+    // one K-step (4 condensed columns) of a stage
+    __device__ static inline void load_step(int st, int u, int32_t mycol, int lane, const char* __restrict__ X,
+                                            int64_t ldxb, int d, Buf& b)
+    {
+        const int j = lane & 15, kk = lane >> 4;
+        const int q = st * U + u;                              // K-step inside the 64-column block
+        const int32_t c = __shfl(mycol, 4 * q + kk, 64);
+        const char* __restrict__ xr = X + (int64_t)c * ldxb;
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            const int col = g * 16 * VW + VW * j;              // columns past d read column 0 and are never stored
+            const char* p = xr + (col < d ? col : 0) * ES;
+            if constexpr (VW == 4) { const float4 v = *reinterpret_cast<const float4*>(p); b.x[u][g][0] = v.x; b.x[u][g][1] = v.y; b.x[u][g][2] = v.z; b.x[u][g][3] = v.w; }
+            else if constexpr (VW == 2) { const float2 v = *reinterpret_cast<const float2*>(p); b.x[u][g][0] = v.x; b.x[u][g][1] = v.y; }
+            else { b.x[u][g][0] = *reinterpret_cast<const float*>(p); }
+        }
+    }
+    __device__ static inline void compute_step(int st, int u, const float* __restrict__ blk, int lane, const Buf& b,
+                                               v4f (&acc)[NG][VW])
+    {
+        const int q = st * U + u;
+        const float av = blk[64 * q + lane];                   // tidx(4q + lane/16, lane%16)
+#pragma unroll
+        for (int g = 0; g < NG; ++g)
+#pragma unroll
+            for (int t = 0; t < VW; ++t)
+                acc[g][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, b.x[u][g][t], acc[g][t], 0, 0, 0);
+    }
     __device__ static inline void load(int st, int32_t mycol, int lane, const char* __restrict__ X, int64_t ldxb, int d,
                                        Buf& b)
     {
-        const int j = lane & 15, kk = lane >> 4;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int q = st * U + u;                          // K-step inside the 64-column block
-            const int32_t c = __shfl(mycol, 4 * q + kk, 64);
-            const char* __restrict__ xr = X + (int64_t)c * ldxb;
-#pragma unroll
-            for (int g = 0; g < NG; ++g) {
-                const int col = g * 16 * VW + VW * j;          // columns past d read column 0 and are never stored
-                const char* p = xr + (col < d ? col : 0) * ES;
-                if constexpr (VW == 4) { const float4 v = *reinterpret_cast<const float4*>(p); b.x[u][g][0] = v.x; b.x[u][g][1] = v.y; b.x[u][g][2] = v.z; b.x[u][g][3] = v.w; }
-                else if constexpr (VW == 2) { const float2 v = *reinterpret_cast<const float2*>(p); b.x[u][g][0] = v.x; b.x[u][g][1] = v.y; }
-                else { b.x[u][g][0] = *reinterpret_cast<const float*>(p); }
-            }
-        }
+        for (int u = 0; u < U; ++u) load_step(st, u, mycol, lane, X, ldxb, d, b);
     }
     __device__ static inline void compute(int st, const float* __restrict__ blk, int lane, const Buf& b, v4f (&acc)[NG][VW])
     {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int q = st * U + u;
-            const float av = blk[64 * q + lane];               // tidx(4q + lane/16, lane%16)
-#pragma unroll
-            for (int g = 0; g < NG; ++g)
-#pragma unroll
-                for (int t = 0; t < VW; ++t)
-                    acc[g][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, b.x[u][g][t], acc[g][t], 0, 0, 0);
-        }
+        for (int u = 0; u < U; ++u) compute_step(st, u, blk, lane, b, acc);
     }
 };
 
@@ -165,6 +172,19 @@ template <int XK, int VW, int NG> struct Path {
     }
 };
 
+// K-steps u, u+1, ... of a stage, each preceded by  s_waitcnt vmcnt(n)  with n = NG * (U-1-u) (capped at 15): the
+// wave's n most recent requests may still be outstanding, all older ones must have returned.  (vmcnt below 16 sits in
+// the low four bits of the operand; the expcnt and lgkmcnt fields are left at "no wait".)
+template <class P, int NG, int VW, int u_>
+__device__ inline void throttled_steps(int st, const float* __restrict__ blk, int lane, const typename P::Buf& b,
+                                       v4f (&acc)[NG][VW])
+{
+    constexpr int kAllow = NG * (P::U - 1 - u_) > 15 ? 15 : NG * (P::U - 1 - u_);
+    __builtin_amdgcn_s_waitcnt(0x0F70 | kAllow);
+    P::compute_step(st, u_, blk, lane, b, acc);
+    if constexpr (u_ + 1 < P::U) throttled_steps<P, NG, VW, u_ + 1>(st, blk, lane, b, acc);
+}
+
 // The stages of one 64-column block, software-pipelined: the X rows of stage s+1 -- or, after the
 // block's last stage, of the next block's first stage -- are requested before the MFMAs of stage s
 // are issued, so the gather latency hides behind the matrix work of the same wave.
@@ -177,14 +197,27 @@ __device__ inline void block_stages(const float* __restrict__ blk, int ncols_blk
 {
     constexpr int NST = 64 / P::SCOLS;
     static_assert(NST % 2 == 0, "stage buffers alternate, a block must end on buffer 1");
+    // Every request is unconditional (a stage past the block's last column, or a "next block" that does not exist,
+    // re-reads valid rows: the column registers repeat the last column): requests inside branches would make the
+    // compiler wait for ALL outstanding loads before a stage's MFMAs, which serialises gather and matrix work.
+    (void)has_next;
 #pragma unroll
     for (int st = 0; st < NST; ++st) {
-        if (st + 1 < NST) {
-            if ((st + 1) * P::SCOLS < ncols_blk) P::load(st + 1, col_cur, lane, X, ldxb, d, xa[(st + 1) & 1]);
-        } else if (has_next) {
-            P::load(0, col_next, lane, X, ldxb, d, xa[0]);
+        if constexpr (P::ES == 4) {
+            // fp32: the requests of the next stage are throttled -- before K-step u of this stage all but the last
+            // NG*(U-1-u) of them must have returned -- so a wave never has more than one stage of rows in flight
+            // and that window shrinks to nothing by the end of the stage (measured: more rows in flight per wave
+            // cost more in L2 hits on the shared columns than they hide in latency)
+            if (st + 1 < NST) P::load(st + 1, col_cur, lane, X, ldxb, d, xa[(st + 1) & 1]);
+            else P::load(0, col_next, lane, X, ldxb, d, xa[0]);
+            if (st * P::SCOLS < ncols_blk) {
+                throttled_steps<P, NG, VW, 0>(st, blk, lane, xa[st & 1], acc);
+            }
+        } else {
+            if (st + 1 < NST) P::load(st + 1, col_cur, lane, X, ldxb, d, xa[(st + 1) & 1]);
+            else P::load(0, col_next, lane, X, ldxb, d, xa[0]);
+            if (st * P::SCOLS < ncols_blk) P::compute(st, blk, lane, xa[st & 1], acc);
         }
-        if (st * P::SCOLS < ncols_blk) P::compute(st, blk, lane, xa[st & 1], acc);
     }
 }
 
@@ -199,13 +232,14 @@ __device__ inline void block_stages_deep(const float* __restrict__ blk, int ncol
                                          typename P::Buf (&xa)[4], v4f (&acc)[NG][VW])
 {
     static_assert(64 / P::SCOLS == 4, "ring of four stage buffers");
-    if (3 * P::SCOLS < ncols_blk) P::load(3, col_cur, lane, X, ldxb, d, xa[3]);
+    (void)has_next;                                             // requests are unconditional, see block_stages
+    P::load(3, col_cur, lane, X, ldxb, d, xa[3]);
     P::compute(0, blk, lane, xa[0], acc);
-    if (has_next) P::load(0, col_next, lane, X, ldxb, d, xa[0]);
+    P::load(0, col_next, lane, X, ldxb, d, xa[0]);
     if (1 * P::SCOLS < ncols_blk) P::compute(1, blk, lane, xa[1], acc);
-    if (has_next) P::load(1, col_next, lane, X, ldxb, d, xa[1]);
+    P::load(1, col_next, lane, X, ldxb, d, xa[1]);
     if (2 * P::SCOLS < ncols_blk) P::compute(2, blk, lane, xa[2], acc);
-    if (has_next) P::load(2, col_next, lane, X, ldxb, d, xa[2]);
+    P::load(2, col_next, lane, X, ldxb, d, xa[2]);
     if (3 * P::SCOLS < ncols_blk) P::compute(3, blk, lane, xa[3], acc);
 }
 
