@@ -297,6 +297,10 @@ size_t hcspmm_aggregate_update_workspace_bytes(const hcspmm_plan* plan, int32_t 
  *   d_W     device, d_in x d_out fp32 (ldw >= d_out)
  *   d_dX    device, n_rows x d_in fp32 (lddx >= d_in), overwritten;  NULL: dX is not computed
  *   d_dW    device, d_in x d_out fp32 (lddw >= d_out), overwritten;  NULL: dW is not computed
+ *   mask_dx_by_x  non-zero: d_dX receives dX where X > 0 and 0 elsewhere.  When the layer's input X is itself
+ *           the output of the previous layer's max(0, .), that is the gradient the previous layer's
+ *           backward call needs as its d_G, already masked (its d_Yfwd is then NULL): the mask is applied
+ *           when dX is stored, which saves that call's separate masking pass over G.
  *   d_workspace  device, at least hcspmm_layer_backward_workspace_bytes(plan, d_in, d_out) bytes,
  *                256-byte aligned; its first n_rows x d_out floats hold S on return when d_dW was given
  * Outputs must not alias inputs.  Asynchronous on `stream`.  Errors as hcspmm_spmm.
@@ -305,7 +309,7 @@ hcspmm_status hcspmm_layer_backward(const hcspmm_plan* plan, const void* d_G, in
                                     const void* d_Yfwd, int64_t ldyf,
                                     const void* d_X, int64_t ldx, int32_t d_in,
                                     const void* d_W, int64_t ldw,
-                                    void* d_dX, int64_t lddx, void* d_dW, int64_t lddw,
+                                    void* d_dX, int64_t lddx, void* d_dW, int64_t lddw, int32_t mask_dx_by_x,
                                     void* d_workspace, size_t workspace_bytes, void* stream);
 
 size_t hcspmm_layer_backward_workspace_bytes(const hcspmm_plan* plan, int32_t d_in, int32_t d_out);

@@ -194,7 +194,7 @@ def aggregate_update_rows(rows, rowptr, colind, vals, X, W, relu: bool = True, x
     return Y
 
 
-def layer_backward(rowptr, colind, vals, G, X, W, Y_fwd=None, use_abs: bool = False):
+def layer_backward(rowptr, colind, vals, G, X, W, Y_fwd=None, use_abs: bool = False, mask_dx_by_x: bool = False):
     """fp64 gradients of the layer X_next = act(A (X W)) given G = dL/dX_next (Eq. 3 and Eq. 4).
 
     In the backward pass of this layer the aggregation comes first and both products of the update
@@ -205,6 +205,8 @@ def layer_backward(rowptr, colind, vals, G, X, W, Y_fwd=None, use_abs: bool = Fa
         dX = S W^T                          (second product of Eq. 3)
         dW = X^T S                          (first product of Eq. 3: the transposed operand is the
                                              dense matrix whose rows match the aggregated rows)
+    mask_dx_by_x: dX is returned as 0 where X <= 0 -- the derivative of the max(0, .) that produced X when X is
+    the previous layer's output, i.e. the masked gradient that layer's backward pass starts from.
     Returns (dX, dW).  use_abs gives the magnitude bounds |A| |Gm| |W|^T and |X|^T |A| |Gm|.
     """
     G64 = np.asarray(G, dtype=np.float64)
@@ -215,4 +217,6 @@ def layer_backward(rowptr, colind, vals, G, X, W, Y_fwd=None, use_abs: bool = Fa
     Xt = np.ascontiguousarray(np.asarray(X, dtype=np.float64).T)
     dX = gemm(S, Wt, x_dtype=DT_F64, w_dtype=DT_F64, use_abs=use_abs)
     dW = gemm(Xt, S, x_dtype=DT_F64, w_dtype=DT_F64, use_abs=use_abs)
+    if mask_dx_by_x:
+        dX = np.where(np.asarray(X) > 0, dX, 0.0)
     return dX, dW

@@ -94,7 +94,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.hcspmm_aggregate_update.restype = ctypes.c_int
     lib.hcspmm_aggregate_update_workspace_bytes.argtypes = [vp, i32, i32]
     lib.hcspmm_aggregate_update_workspace_bytes.restype = ctypes.c_size_t
-    lib.hcspmm_layer_backward.argtypes = [vp, vp, i64, i32, vp, i64, vp, i64, i32, vp, i64, vp, i64, vp, i64, vp,
+    lib.hcspmm_layer_backward.argtypes = [vp, vp, i64, i32, vp, i64, vp, i64, i32, vp, i64, vp, i64, vp, i64, i32, vp,
                                           ctypes.c_size_t, vp]
     lib.hcspmm_layer_backward.restype = ctypes.c_int
     lib.hcspmm_layer_backward_workspace_bytes.argtypes = [vp, i32, i32]
@@ -282,8 +282,9 @@ def hcspmm_layer_backward_workspace_bytes(plan: Plan, d_in: int, d_out: int) -> 
     return int(load_library().hcspmm_layer_backward_workspace_bytes(plan.handle, d_in, d_out))
 
 
-def hcspmm_layer_backward(plan: Plan, G, X, W, dX, dW, workspace, *, Y_fwd=None, stream=None):
-    """S = A (G masked by Y_fwd > 0), dX = S W^T, dW = X^T S; dX or dW may be None (not computed)."""
+def hcspmm_layer_backward(plan: Plan, G, X, W, dX, dW, workspace, *, Y_fwd=None, mask_dx_by_x: bool = False, stream=None):
+    """S = A (G masked by Y_fwd > 0), dX = S W^T (stored as 0 where X <= 0 with mask_dx_by_x), dW = X^T S;
+    dX or dW may be None (not computed)."""
     assert G.stride(1) == 1 and X.stride(1) == 1 and W.stride(1) == 1
     assert dX is None or dX.stride(1) == 1
     assert dW is None or dW.stride(1) == 1
@@ -294,7 +295,7 @@ def hcspmm_layer_backward(plan: Plan, G, X, W, dX, dW, workspace, *, Y_fwd=None,
         _ptr(Y_fwd) if Y_fwd is not None else None, Y_fwd.stride(0) if Y_fwd is not None else 0,
         _ptr(X), X.stride(0), X.shape[1], _ptr(W), W.stride(0),
         _ptr(dX) if dX is not None else None, dX.stride(0) if dX is not None else 0,
-        _ptr(dW) if dW is not None else None, dW.stride(0) if dW is not None else 0,
+        _ptr(dW) if dW is not None else None, dW.stride(0) if dW is not None else 0, 1 if mask_dx_by_x else 0,
         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
     return dX, dW
 

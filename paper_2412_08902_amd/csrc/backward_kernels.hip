@@ -182,11 +182,11 @@ hipError_t launch_gemm_tn(int64_t n_rows, const float* X, int64_t ldx, int32_t d
     return hipGetLastError();
 }
 
-// Gm = G where the forward output is positive, else 0 (derivative of max(0, .)); Gm is n x d, pitch d.
-// VEC = 4: d and both pitches are multiples of 4 and the bases 16-byte aligned.
+// Gm = G where the forward output is positive, else 0 (derivative of max(0, .)); Gm is n x d, pitch ldo (it may be G
+// itself).  VEC = 4: d and all pitches are multiples of 4 and the bases 16-byte aligned.
 template <int VEC>
-__global__ __launch_bounds__(256) void k_relu_mask(int64_t n, int32_t d, const float* __restrict__ G, int64_t ldg,
-                                                   const float* __restrict__ Yf, int64_t ldy, float* __restrict__ Gm)
+__global__ __launch_bounds__(256) void k_relu_mask(int64_t n, int32_t d, const float* G, int64_t ldg,
+                                                   const float* __restrict__ Yf, int64_t ldy, float* Gm, int64_t ldo)
 {
     const int per_row = d / VEC;
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -196,23 +196,23 @@ __global__ __launch_bounds__(256) void k_relu_mask(int64_t n, int32_t d, const f
     if constexpr (VEC == 4) {
         const float4 g = *reinterpret_cast<const float4*>(G + r * ldg + c);
         const float4 y = *reinterpret_cast<const float4*>(Yf + r * ldy + c);
-        *reinterpret_cast<float4*>(Gm + r * d + c) =
+        *reinterpret_cast<float4*>(Gm + r * ldo + c) =
             make_float4(y.x > 0.f ? g.x : 0.f, y.y > 0.f ? g.y : 0.f, y.z > 0.f ? g.z : 0.f, y.w > 0.f ? g.w : 0.f);
     } else {
-        Gm[r * d + c] = Yf[r * ldy + c] > 0.f ? G[r * ldg + c] : 0.f;
+        Gm[r * ldo + c] = Yf[r * ldy + c] > 0.f ? G[r * ldg + c] : 0.f;
     }
 }
 
 hipError_t launch_relu_mask(int64_t n, int32_t d, const float* G, int64_t ldg, const float* Yf, int64_t ldy, float* Gm,
-                            hipStream_t s)
+                            int64_t ldo, hipStream_t s)
 {
     if (n <= 0 || d <= 0) return hipSuccess;
-    const bool vec = d % 4 == 0 && ldg % 4 == 0 && ldy % 4 == 0 && (uintptr_t)G % 16 == 0 && (uintptr_t)Yf % 16 == 0 &&
-                     (uintptr_t)Gm % 16 == 0;
+    const bool vec = d % 4 == 0 && ldg % 4 == 0 && ldy % 4 == 0 && ldo % 4 == 0 && (uintptr_t)G % 16 == 0 &&
+                     (uintptr_t)Yf % 16 == 0 && (uintptr_t)Gm % 16 == 0;
     const int64_t count = n * (vec ? d / 4 : d);
     const dim3 grid((unsigned)((count + 255) / 256));
-    if (vec) hipLaunchKernelGGL(k_relu_mask<4>, grid, dim3(256), 0, s, n, d, G, ldg, Yf, ldy, Gm);
-    else hipLaunchKernelGGL(k_relu_mask<1>, grid, dim3(256), 0, s, n, d, G, ldg, Yf, ldy, Gm);
+    if (vec) hipLaunchKernelGGL(k_relu_mask<4>, grid, dim3(256), 0, s, n, d, G, ldg, Yf, ldy, Gm, ldo);
+    else hipLaunchKernelGGL(k_relu_mask<1>, grid, dim3(256), 0, s, n, d, G, ldg, Yf, ldy, Gm, ldo);
     return hipGetLastError();
 }
 

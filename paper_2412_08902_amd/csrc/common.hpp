@@ -130,6 +130,8 @@ struct UpdateArgs {
     int64_t ldy;
     int32_t relu;
     int32_t keep_z;       // also store every aggregated row to the workspace (a.Y), not only the rows finished later
+    const float* mask;    // optional, n_rows x d_out (pitch ldm): results are stored as 0 where mask <= 0
+    int64_t ldm;
 };
 
 // With `upd` the kernels that can keep a 16-row result tile on chip multiply it by W and write
@@ -163,7 +165,7 @@ int32_t gemm_tn_spans(int64_t n_rows, int32_t d_in, int32_t d);
 hipError_t launch_gemm_tn(int64_t n_rows, const float* X, int64_t ldx, int32_t d_in, const float* S, int64_t lds_,
                           int32_t d, float* dW, int64_t lddw, float* partial, hipStream_t s);
 hipError_t launch_relu_mask(int64_t n, int32_t d, const float* G, int64_t ldg, const float* Yf, int64_t ldy, float* Gm,
-                            hipStream_t s);
+                            int64_t ldo, hipStream_t s);
 hipError_t launch_transpose(int32_t rows, int32_t cols, const float* W, int64_t ldw, float* Wt, hipStream_t s);
 // same product with the output stored as t_dtype (fp32, or bf16 / fp16 rounded from the fp32 accumulators)
 hipError_t launch_gemm_f32_out(int64_t m, int32_t k, int32_t n, const float* X, int64_t ldx, const float* W, int64_t ldw,

@@ -899,11 +899,12 @@ size_t hcspmm_layer_backward_workspace_bytes(const hcspmm_plan* plan, int32_t d_
 hcspmm_status hcspmm_layer_backward(const hcspmm_plan* plan, const void* d_G, int64_t ldg, int32_t d_out,
                                     const void* d_Yfwd, int64_t ldyf, const void* d_X, int64_t ldx, int32_t d_in,
                                     const void* d_W, int64_t ldw, void* d_dX, int64_t lddx, void* d_dW, int64_t lddw,
-                                    void* d_workspace, size_t workspace_bytes, void* stream)
+                                    int32_t mask_dx_by_x, void* d_workspace, size_t workspace_bytes, void* stream)
 {
     if (!plan) { set_error("plan is NULL"); return HCSPMM_EINVAL; }
     if (d_in < 1 || d_out < 1 || d_in > (1 << 20) || d_out > (1 << 20)) { set_error("d_in, d_out must be in [1, 2^20]"); return HCSPMM_EINVAL; }
     hcspmm_status st;
+    if (mask_dx_by_x && d_dX && (st = check_dense("X", d_X, ldx, d_in)) != HCSPMM_OK) return st;
     if ((st = check_dense("G", d_G, ldg, d_out)) != HCSPMM_OK) return st;
     if (d_Yfwd && (st = check_dense("Yfwd", d_Yfwd, ldyf, d_out)) != HCSPMM_OK) return st;
     if ((st = check_dense("W", d_W, ldw, d_out)) != HCSPMM_OK) return st;
@@ -924,7 +925,7 @@ hcspmm_status hcspmm_layer_backward(const hcspmm_plan* plan, const void* d_G, in
     const float* G = static_cast<const float*>(d_G);
     int64_t g_ld = ldg;
     if (d_Yfwd && plan->n_cols > 0) {
-        HC_HIP(launch_relu_mask(plan->n_cols, d_out, G, ldg, static_cast<const float*>(d_Yfwd), ldyf, Gm, s));
+        HC_HIP(launch_relu_mask(plan->n_cols, d_out, G, ldg, static_cast<const float*>(d_Yfwd), ldyf, Gm, d_out, s));
         G = Gm;
         g_ld = d_out;
     }
@@ -939,11 +940,16 @@ hcspmm_status hcspmm_layer_backward(const hcspmm_plan* plan, const void* d_G, in
             const bool worth = (4 * (int64_t)plan->n_rest < plan->n_rows && (!d_dW || d_out <= 32)) ||
                                getenv("HCSPMM_TUNE_FORCE_FUSE");
             if (update_fusable(a) && worth && !getenv("HCSPMM_TUNE_NO_FUSE")) {
-                const UpdateArgs u{Wt, d_in, d_in, static_cast<float*>(d_dX), lddx, 0, d_dW ? 1 : 0};
+                // the next layer's activation mask (its output is this layer's input X) goes into the update's epilogue
+                const UpdateArgs u{Wt, d_in, d_in, static_cast<float*>(d_dX), lddx, 0, d_dW ? 1 : 0,
+                                   mask_dx_by_x ? static_cast<const float*>(d_X) : nullptr, ldx};
                 if ((st = run_spmm(plan, a, s, nullptr, &u)) != HCSPMM_OK) return st;
             } else {
                 if ((st = run_spmm(plan, a, s)) != HCSPMM_OK) return st;
                 HC_HIP(launch_gemm_f32(plan->n_rows, d_out, d_in, S, d_out, Wt, d_in, static_cast<float*>(d_dX), lddx, 0, s));
+                if (mask_dx_by_x)
+                    HC_HIP(launch_relu_mask(plan->n_rows, d_in, static_cast<const float*>(d_dX), lddx,
+                                            static_cast<const float*>(d_X), ldx, static_cast<float*>(d_dX), lddx, s));
             }
         } else if ((st = run_spmm(plan, a, s)) != HCSPMM_OK) {
             return st;

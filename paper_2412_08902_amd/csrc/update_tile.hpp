@@ -77,6 +77,11 @@ __device__ inline void update_tile16_nt(const float* zt, int ldz, const int32_t*
             float y[NT];
 #pragma unroll
             for (int t = 0; t < NT; ++t) y[t] = u.relu ? fmaxf(acc[t][r], 0.f) : acc[t][r];
+            if (u.mask) {                                       // derivative of an activation applied to another matrix
+                const float* __restrict__ mp = u.mask + (int64_t)myrow[r] * u.ldm + col;
+#pragma unroll
+                for (int t = 0; t < NT; ++t) y[t] = mp[t] > 0.f ? y[t] : 0.f;
+            }
             float* __restrict__ p = u.Y + (int64_t)myrow[r] * u.ldy + col;
             if constexpr (NT == 4) *reinterpret_cast<float4*>(p) = make_float4(y[0], y[1], y[2], y[3]);
             else if constexpr (NT == 2) *reinterpret_cast<float2*>(p) = make_float2(y[0], y[1]);

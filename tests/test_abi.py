@@ -87,7 +87,7 @@ def test_header_is_plain_c(tmp_path):
 def test_new_entry_points_reject_bad_arguments_on_the_host():
     import paper_2412_08902_amd.binding as hc
     lib = hc.load_library()
-    assert lib.hcspmm_layer_backward(None, None, 0, 4, None, 0, None, 0, 4, None, 0, None, 0, None, 0, None, 0, None) == hc.HCSPMM_EINVAL
+    assert lib.hcspmm_layer_backward(None, None, 0, 4, None, 0, None, 0, 4, None, 0, None, 0, None, 0, 0, None, 0, None) == hc.HCSPMM_EINVAL
     assert lib.hcspmm_aggregate_update(None, None, 0, 4, 0, None, 0, 4, None, 0, 1, None, 0, None) == hc.HCSPMM_EINVAL
     assert lib.hcspmm_layer_backward_workspace_bytes(None, 4, 4) == 0
     assert lib.hcspmm_aggregate_update_workspace_bytes(None, 4, 4) == 0

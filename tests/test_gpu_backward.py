@@ -11,7 +11,7 @@ pytestmark = pytest.mark.gpu
 TOL_F32 = 1e-5
 
 
-def run_backward(g, G, X, W, mode=0, Y_fwd=None, want_dx=True, want_dw=True, pad=0, sel_coef=None):
+def run_backward(g, G, X, W, mode=0, Y_fwd=None, want_dx=True, want_dw=True, pad=0, sel_coef=None, mask_dx=False):
     import torch
     import paper_2412_08902_amd.binding as hc
     rp, ci, va = device_graph(g)
@@ -22,7 +22,7 @@ def run_backward(g, G, X, W, mode=0, Y_fwd=None, want_dx=True, want_dw=True, pad
     dW = torch.full((d_in, d_out + pad), -3.0, device="cuda") if want_dw else None
     hc.hcspmm_layer_backward(plan, torch.from_numpy(G).cuda(), torch.from_numpy(X).cuda(), torch.from_numpy(W).cuda(),
                              dX[:, :d_in] if want_dx else None, dW[:, :d_out] if want_dw else None, ws,
-                             Y_fwd=None if Y_fwd is None else torch.from_numpy(Y_fwd).cuda())
+                             Y_fwd=None if Y_fwd is None else torch.from_numpy(Y_fwd).cuda(), mask_dx_by_x=mask_dx)
     torch.cuda.synchronize()
     S = ws[:g.n_rows * d_out * 4].view(torch.float32).reshape(g.n_rows, d_out).cpu().numpy().astype(np.float64)
     plan.destroy()
@@ -34,8 +34,10 @@ def run_backward(g, G, X, W, mode=0, Y_fwd=None, want_dx=True, want_dw=True, pad
     return (None if out_dx is None else out_dx[:, :d_in]), (None if out_dw is None else out_dw[:, :d_out]), S
 
 
-def check(g, G, X, W, dX, dW, S, Y_fwd=None):
-    ref_dx, ref_dw = oracle.layer_backward(g.rowptr, g.colind, g.vals, G, X, W, Y_fwd=Y_fwd)
+def check(g, G, X, W, dX, dW, S, Y_fwd=None, mask_dx=False):
+    ref_dx, ref_dw = oracle.layer_backward(g.rowptr, g.colind, g.vals, G, X, W, Y_fwd=Y_fwd, mask_dx_by_x=mask_dx)
+    if mask_dx and dX is not None:
+        assert np.all(dX[X <= 0] == 0.0)
     b_dx, b_dw = oracle.layer_backward(g.rowptr, g.colind, g.vals, G, X, W, Y_fwd=Y_fwd, use_abs=True)
     Gm = G if Y_fwd is None else np.where(Y_fwd > 0, G, 0).astype(np.float32)
     ref_s = oracle.spmm(g.rowptr, g.colind, g.vals, Gm)
@@ -74,8 +76,9 @@ def test_backward_shapes(mode, din, dout, force, monkeypatch):
     g = gcn_normalise(chung_lu_graph(3003, 150000, 2.0, seed=71, max_degree=2800))
     X, W = dense_normal(g.n_rows, din, seed=72), glorot_uniform(din, dout, seed=73)
     G = dense_normal(g.n_cols, dout, seed=74)
-    dX, dW, S = run_backward(g, G, X, W, mode, pad=2, sel_coef=[1, 0, -300] if mode == 3 else None)
-    check(g, G, X, W, dX, dW, S)
+    mask_dx = din % 2 == 0                                   # half of the shapes also mask dX by the layer's input
+    dX, dW, S = run_backward(g, G, X, W, mode, pad=2, sel_coef=[1, 0, -300] if mode == 3 else None, mask_dx=mask_dx)
+    check(g, G, X, W, dX, dW, S, mask_dx=mask_dx)
 
 
 def test_backward_matches_central_differences_of_the_forward_layer():
@@ -272,8 +275,9 @@ def test_two_layer_gcn_forward_and_backward_compose():
                          hc.hcspmm_layer_backward_workspace_bytes(plan2, d1, d2)), dtype=torch.uint8, device="cuda")
     hc.hcspmm_gcn_layer(plan1, Xd, W1d, H1, ws, apply_relu=True)
     hc.hcspmm_gcn_layer(plan2, H1, W2d, out, ws, apply_relu=False)
-    hc.hcspmm_layer_backward(plan2, Cd, H1, W2d, dH1, dW2, ws)                    # layer 2: no activation
-    hc.hcspmm_layer_backward(plan1, dH1, Xd, W1d, dX, dW1, ws, Y_fwd=H1)          # layer 1: masked by its output
+    # layer 2 has no activation; its input H1 is layer 1's ReLU output, so dH1 is stored already masked by H1 > 0
+    hc.hcspmm_layer_backward(plan2, Cd, H1, W2d, dH1, dW2, ws, mask_dx_by_x=True)
+    hc.hcspmm_layer_backward(plan1, dH1, Xd, W1d, dX, dW1, ws)                    # layer 1: its G arrives masked
     torch.cuda.synchronize()
     plan1.destroy()
     plan2.destroy()
@@ -285,12 +289,12 @@ def test_two_layer_gcn_forward_and_backward_compose():
     assert_close(f64(out), oracle.gcn_layer(*a, H1h, W2, relu=False), oracle.gcn_layer(*a, H1h, W2, use_abs=True),
                  2 * TOL_F32, "out")
     # backward, layer 2 then layer 1 (the oracle's layer-1 input gradient is its own fp64 dH1)
-    r_dH1, r_dW2 = oracle.layer_backward(*a, C, H1h, W2)
+    r_dH1, r_dW2 = oracle.layer_backward(*a, C, H1h, W2, mask_dx_by_x=True)
     b_dH1, b_dW2 = oracle.layer_backward(*a, C, H1h, W2, use_abs=True)
     assert_close(f64(dH1), r_dH1, b_dH1, 2 * TOL_F32, "dH1")
     assert_close(f64(dW2), r_dW2, b_dW2, 2 * TOL_F32, "dW2")
-    r_dX, r_dW1 = oracle.layer_backward(*a, r_dH1, X, W1, Y_fwd=H1h)
-    b_dX, b_dW1 = oracle.layer_backward(*a, b_dH1, X, W1, Y_fwd=H1h, use_abs=True)
+    r_dX, r_dW1 = oracle.layer_backward(*a, r_dH1, X, W1)
+    b_dX, b_dW1 = oracle.layer_backward(*a, b_dH1, X, W1, use_abs=True)
     assert_close(f64(dX), r_dX, b_dX, 4 * TOL_F32, "dX")
     assert_close(f64(dW1), r_dW1, b_dW1, 4 * TOL_F32, "dW1")
     # the bilinear identity of the last layer ties the loss to its weight gradient: <dW2, W2> = <C, out>

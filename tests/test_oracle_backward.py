@@ -160,3 +160,51 @@ def test_magnitude_bound_dominates():
     np.testing.assert_allclose(bX, (A @ np.abs(G)) @ np.abs(W).T.astype(np.float64), rtol=1e-12)
     np.testing.assert_allclose(bW, np.abs(X).T.astype(np.float64) @ (A @ np.abs(G)), rtol=1e-12)
     assert np.all(np.abs(dX) <= bX + 1e-300) and np.all(np.abs(dW) <= bW + 1e-300)
+
+
+def test_masked_input_gradient_chains_two_layers():
+    """mask_dx_by_x hands the previous layer its gradient already masked: L = <C, A ReLU(A X W1) W2> differentiated by
+    central differences (dense numpy) against layer 2's call with the flag followed by layer 1's call without a mask."""
+    rng = np.random.default_rng(11)
+    n, d0, d1, d2 = 10, 3, 4, 2
+    B = (rng.random((n, n)) < 0.35) * rng.standard_normal((n, n))
+    A = (B + B.T).astype(np.float32).astype(np.float64)
+    rows, cols = np.nonzero(A)
+    rowptr = np.zeros(n + 1, dtype=np.int32)
+    np.cumsum(np.bincount(rows, minlength=n), out=rowptr[1:])
+    colind, vals = cols.astype(np.int32), A[rows, cols].astype(np.float32)
+    X = rng.standard_normal((n, d0))
+    W1 = rng.standard_normal((d0, d1))
+    W2 = rng.standard_normal((d1, d2))
+    C = rng.standard_normal((n, d2))
+
+    def loss(Xv, W1v):
+        return float(np.sum(C * (A @ (np.maximum(A @ (Xv @ W1v), 0.0) @ W2))))
+
+    pre = A @ (X @ W1)
+    assert np.min(np.abs(pre)) > 1e-4
+    H1 = np.maximum(pre, 0.0)
+    dH1m, dW2 = oracle.layer_backward(rowptr, colind, vals, C, H1, W2, mask_dx_by_x=True)
+    assert np.all(dH1m[H1 <= 0] == 0.0) and np.any(dH1m != 0.0)
+    np.testing.assert_allclose(dW2, H1.T @ (A @ C), rtol=1e-12, atol=1e-12)
+    dX, dW1 = oracle.layer_backward(rowptr, colind, vals, dH1m, X, W1)          # no mask pass: G arrives masked
+    h = 1e-6
+    num_dW1 = np.zeros_like(W1)
+    for a in range(d0):
+        for b in range(d1):
+            Wp, Wm = W1.copy(), W1.copy()
+            Wp[a, b] += h
+            Wm[a, b] -= h
+            num_dW1[a, b] = (loss(X, Wp) - loss(X, Wm)) / (2 * h)
+    num_dX = np.zeros_like(X)
+    for i in range(n):
+        for a in range(d0):
+            Xp, Xm = X.copy(), X.copy()
+            Xp[i, a] += h
+            Xm[i, a] -= h
+            num_dX[i, a] = (loss(Xp, W1) - loss(Xm, W1)) / (2 * h)
+    np.testing.assert_allclose(dW1, num_dW1, rtol=1e-6, atol=1e-7)
+    np.testing.assert_allclose(dX, num_dX, rtol=1e-6, atol=1e-7)
+    # and the flag is exactly "mask afterwards"
+    dH1, _ = oracle.layer_backward(rowptr, colind, vals, C, H1, W2)
+    assert np.array_equal(dH1m, np.where(H1 > 0, dH1, 0.0))
