@@ -296,17 +296,19 @@ def main():
         bw = lambda **kw: hc.hcspmm_layer_backward(plan, Gb, Xb, Wb, dXb, dWb, wsb, **kw)
         ms_b = time_steps(lambda: bw(), args.steps, args.warmup, torch)
         ms_b_mask = time_steps(lambda: bw(Y_fwd=Yf), args.steps, args.warmup, torch)
+        ms_b_emask = time_steps(lambda: bw(mask_dx_by_x=True), args.steps, args.warmup, torch)
         ms_dx = time_steps(lambda: hc.hcspmm_layer_backward(plan, Gb, Xb, Wb, dXb, None, wsb), args.steps, args.warmup, torch)
         ms_dw = time_steps(lambda: hc.hcspmm_layer_backward(plan, Gb, Xb, Wb, None, dWb, wsb), args.steps, args.warmup, torch)
         os.environ["HCSPMM_TUNE_NO_FUSE"] = "1"
         ms_b_split = time_steps(lambda: bw(), args.steps, args.warmup, torch)
         del os.environ["HCSPMM_TUNE_NO_FUSE"]
         out["layer_backward"] = dict(d_in=d_in, d_out=d, ms=round(ms_b, 5), ms_with_activation_mask=round(ms_b_mask, 5),
+                                     ms_with_dx_masked_in_epilogue=round(ms_b_emask, 5),
                                      ms_unfused=round(ms_b_split, 5), ms_dx_only=round(ms_dx, 5), ms_dw_only=round(ms_dw, 5),
                                      ms_spmm_alone=round(ms, 5),
                                      dw_stream_gbps=round((g.n_rows * (d_in + d) * 4) / max(ms_dw - ms, 1e-6) / 1e6, 1))
-        log("layer backward: %.4f ms (unfused %.4f; dX only %.4f, dW only %.4f, with mask %.4f; spmm alone %.4f)"
-            % (ms_b, ms_b_split, ms_dx, ms_dw, ms_b_mask, ms))
+        log("layer backward: %.4f ms (unfused %.4f; dX only %.4f, dW only %.4f, with mask pass %.4f, with dX masked in "
+            "the epilogue %.4f; spmm alone %.4f)" % (ms_b, ms_b_split, ms_dx, ms_dw, ms_b_mask, ms_b_emask, ms))
         del Wb, Xb, Yf, wsb, dXb, dWb
 
     if args.cold:
