@@ -144,6 +144,10 @@ hipError_t launch_csr(const SpmmArgs& a, int32_t n_segs, const Segment* segs, fl
                       int32_t mid_row, hipStream_t s, const UpdateArgs* upd = nullptr);
 hipError_t launch_update_rest(const SpmmArgs& a, int32_t n_rest, const int32_t* rest_rows, const UpdateArgs& upd,
                               hipStream_t s);
+// dense product through the 16-row update kernel (narrow W), see spmm_csr_kernels.hip
+bool gemm_rows16_usable(int64_t m, int32_t k, int32_t n, const float* X, int64_t ldx);
+hipError_t launch_gemm_rows16(int64_t m, int32_t k, int32_t n, const float* X, int64_t ldx, const float* W, int64_t ldw,
+                              float* T, int64_t ldt, int relu, hipStream_t s);
 hipError_t launch_rest_flag(int32_t n_rows, const int32_t* rowptr, const uint8_t* route, const int32_t* ncols,
                             int32_t mid_row, int32_t* flag, hipStream_t s);
 hipError_t launch_reduce_partials(const SpmmArgs& a, int32_t n_multi, const MultiRow* multi, const float* partial,

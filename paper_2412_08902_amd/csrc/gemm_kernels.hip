@@ -7,6 +7,8 @@
 // a 64 x 64 sub-tile as 2 x 2 MFMA tiles.  Both operands are staged k-major in LDS so that the
 // per-lane operand reads are unit-stride; the global loads of the next K slab are issued before
 // the MFMAs of the current one (register double buffering).
+#include <cstdlib>
+
 #include "common.hpp"
 
 namespace hcspmm {
@@ -139,6 +141,8 @@ hipError_t launch_gemm_f32_out(int64_t m, int32_t k, int32_t n, const float* X, 
                                void* T, int64_t ldt, int32_t t_dtype, int relu, hipStream_t s)
 {
     if (m <= 0 || n <= 0) return hipSuccess;
+    if (t_dtype == HCSPMM_F32 && gemm_rows16_usable(m, k, n, X, ldx) && !getenv("HCSPMM_TUNE_NO_ROWS16"))
+        return launch_gemm_rows16(m, k, n, X, ldx, W, ldw, static_cast<float*>(T), ldt, relu, s);
     dim3 grid((unsigned)((m + BM - 1) / BM), (unsigned)((n + BN - 1) / BN));
     const uintptr_t px = (uintptr_t)X;
     const int xv = (ldx % 4 == 0 && px % 16 == 0) ? 4 : ((ldx % 2 == 0 && px % 8 == 0) ? 2 : 1);

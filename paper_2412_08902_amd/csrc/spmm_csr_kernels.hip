@@ -446,13 +446,25 @@ __global__ __launch_bounds__(256) void k_update_rest(int32_t n_rest, const int32
     if (i0 >= n_rest) return;
     float* __restrict__ zt = tiles + wave * 16 * ldz;
     int32_t* __restrict__ rows16 = rows_s + wave * 16;
-    if (lane < 16) rows16[lane] = i0 + lane < n_rest ? rest_rows[i0 + lane] : -1;
+    if (lane < 16) rows16[lane] = i0 + lane < n_rest ? (rest_rows ? rest_rows[i0 + lane] : (int32_t)(i0 + lane)) : -1;
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    for (int r = 0; r < 16; ++r) {
-        const int32_t rr = rows16[r];
-        if (rr < 0) continue;                                   // tile rows past the list stay undefined, never stored
-        for (int c = lane * 4; c < a.d; c += 256)
-            *reinterpret_cast<float4*>(&zt[r * ldz + c]) = *reinterpret_cast<const float4*>(&a.Y[(int64_t)rr * a.ldy + c]);
+    // the whole 16 x d tile is requested at once, all lanes busy, and only then parked in LDS
+    constexpr int kPerLane = 16 * ZD / 4 / 64;                  // float4 per lane for the widest tile
+    const int per_row = a.d >> 2;
+    float4 v[kPerLane];
+#pragma unroll
+    for (int j = 0; j < kPerLane; ++j) {
+        const int idx = lane + 64 * j;
+        v[j] = make_float4(0.f, 0.f, 0.f, 0.f);                 // tile rows past the list are zero and never stored
+        if (idx < 16 * per_row) {
+            const int32_t rr = rows16[idx / per_row];
+            if (rr >= 0) v[j] = *reinterpret_cast<const float4*>(&a.Y[(int64_t)rr * a.ldy + (idx % per_row) * 4]);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < kPerLane; ++j) {
+        const int idx = lane + 64 * j;
+        if (idx < 16 * per_row) *reinterpret_cast<float4*>(&zt[(idx / per_row) * ldz + (idx % per_row) * 4]) = v[j];
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     update_tile16(zt, ldz, rows16, a.d, u, lane);
@@ -584,6 +596,23 @@ hipError_t launch_csr(const SpmmArgs& a, int32_t n_segs, const Segment* segs, fl
     HC_CSR_DISPATCH(HC_LAUNCH_CSR)
 #undef HC_LAUNCH_CSR
     return hipGetLastError();
+}
+
+// The same kernel as a dense product for narrow outputs: T = act(X W) for X m x k (k a multiple of 16 up to 128, rows
+// 16-byte aligned), every wave taking 16 consecutive rows.  A 128-column GEMM tile would spend most of its matrix work
+// on padding when W has 64 columns or fewer; here the product streams X once and W stays in L1/L2.
+bool gemm_rows16_usable(int64_t m, int32_t k, int32_t n, const float* X, int64_t ldx)
+{
+    return m < ((int64_t)1 << 31) && k % 16 == 0 && k >= 16 && k <= 128 && n <= 64 && ldx % 4 == 0 && (uintptr_t)X % 16 == 0;
+}
+
+hipError_t launch_gemm_rows16(int64_t m, int32_t k, int32_t n, const float* X, int64_t ldx, const float* W, int64_t ldw,
+                              float* T, int64_t ldt, int relu, hipStream_t s)
+{
+    SpmmArgs a{};
+    a.n_rows = (int32_t)m; a.d = k; a.Y = const_cast<float*>(X); a.ldy = ldx;      // the kernel only reads these rows
+    const UpdateArgs u{W, ldw, n, T, ldt, relu ? 1 : 0, 0, nullptr, 0};
+    return launch_update_rest(a, (int32_t)m, nullptr, u, s);
 }
 
 hipError_t launch_update_rest(const SpmmArgs& a, int32_t n_rest, const int32_t* rest_rows, const UpdateArgs& upd,

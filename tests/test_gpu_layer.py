@@ -11,7 +11,9 @@ TOL_F32 = 1e-5
 
 
 @pytest.mark.parametrize("m,k,n", [(1, 1, 1), (130, 17, 5), (257, 602, 128), (128, 16, 128), (300, 64, 200),
-                                   (1000, 33, 64), (64, 250, 130)])
+                                   (1000, 33, 64), (64, 250, 130),
+                                   # narrow outputs with K a multiple of 16: the 16-row streaming route
+                                   (257, 32, 32), (1000, 64, 16), (300, 256, 7), (5000, 128, 64), (15, 16, 1), (70001, 48, 33)])
 def test_gemm(m, k, n):
     import torch
     import paper_2412_08902_amd.binding as hc
