@@ -435,39 +435,50 @@ __global__ __launch_bounds__(256) void k_csr_fused(CsrWork wk, SpmmArgs a, Updat
 // the wave-per-window kernel handles, scalar-path rows above the short tier): they were written to
 // Z, are read back as a 16-row tile and multiplied by W.
 template <int ZD>
-__global__ __launch_bounds__(256) void k_update_rest(int32_t n_rest, const int32_t* __restrict__ rest_rows, SpmmArgs a,
-                                                     UpdateArgs u)
+__global__ __launch_bounds__(256) void k_update_rest(int32_t n_rest, const int32_t* __restrict__ rest_rows, int tiles_per_wave,
+                                                     SpmmArgs a, UpdateArgs u)
 {
     constexpr int ldz = ZD + 4;                                 // ZD >= d
     __shared__ float tiles[4 * 16 * ldz];
-    __shared__ int32_t rows_s[64];
+    __shared__ int32_t rows_s[2][64];                           // two row lists per wave, alternating between tiles
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int64_t i0 = ((int64_t)blockIdx.x * 4 + wave) * 16;
-    if (i0 >= n_rest) return;
+    const int64_t n_tiles = ((int64_t)n_rest + 15) / 16;
+    const int64_t t_begin = ((int64_t)blockIdx.x * 4 + wave) * tiles_per_wave;
+    const int64_t t_end = min(n_tiles, t_begin + tiles_per_wave);
+    if (t_begin >= t_end) return;
     float* __restrict__ zt = tiles + wave * 16 * ldz;
-    int32_t* __restrict__ rows16 = rows_s + wave * 16;
-    if (lane < 16) rows16[lane] = i0 + lane < n_rest ? (rest_rows ? rest_rows[i0 + lane] : (int32_t)(i0 + lane)) : -1;
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    // the whole 16 x d tile is requested at once, all lanes busy, and only then parked in LDS
     constexpr int kPerLane = 16 * ZD / 4 / 64;                  // float4 per lane for the widest tile
     const int per_row = a.d >> 2;
     float4 v[kPerLane];
+    // A wave walks tiles_per_wave consecutive 16-row tiles.  The whole 16 x d tile is requested at once, all lanes busy;
+    // the next tile's rows are requested as soon as the current tile is parked in LDS, so they arrive during its MFMAs.
+    auto request = [&](int64_t tile, int32_t* __restrict__ rows16) {
+        const int64_t i0 = tile * 16;
+        if (lane < 16) rows16[lane] = i0 + lane < n_rest ? (rest_rows ? rest_rows[i0 + lane] : (int32_t)(i0 + lane)) : -1;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 #pragma unroll
-    for (int j = 0; j < kPerLane; ++j) {
-        const int idx = lane + 64 * j;
-        v[j] = make_float4(0.f, 0.f, 0.f, 0.f);                 // tile rows past the list are zero and never stored
-        if (idx < 16 * per_row) {
-            const int32_t rr = rows16[idx / per_row];
-            if (rr >= 0) v[j] = *reinterpret_cast<const float4*>(&a.Y[(int64_t)rr * a.ldy + (idx % per_row) * 4]);
+        for (int j = 0; j < kPerLane; ++j) {
+            const int idx = lane + 64 * j;
+            v[j] = make_float4(0.f, 0.f, 0.f, 0.f);             // tile rows past the list are zero and never stored
+            if (idx < 16 * per_row) {
+                const int32_t rr = rows16[idx / per_row];
+                if (rr >= 0) v[j] = *reinterpret_cast<const float4*>(&a.Y[(int64_t)rr * a.ldy + (idx % per_row) * 4]);
+            }
         }
-    }
+    };
+    request(t_begin, rows_s[0] + wave * 16);
+    for (int64_t t = t_begin; t < t_end; ++t) {
+        int32_t* __restrict__ rows16 = rows_s[(t - t_begin) & 1] + wave * 16;
 #pragma unroll
-    for (int j = 0; j < kPerLane; ++j) {
-        const int idx = lane + 64 * j;
-        if (idx < 16 * per_row) *reinterpret_cast<float4*>(&zt[(idx / per_row) * ldz + (idx % per_row) * 4]) = v[j];
+        for (int j = 0; j < kPerLane; ++j) {
+            const int idx = lane + 64 * j;
+            if (idx < 16 * per_row) *reinterpret_cast<float4*>(&zt[(idx / per_row) * ldz + (idx % per_row) * 4]) = v[j];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        if (t + 1 < t_end) request(t + 1, rows_s[(t + 1 - t_begin) & 1] + wave * 16);
+        update_tile16(zt, ldz, rows16, a.d, u, lane);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the tile's LDS reads are done before it is overwritten
     }
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    update_tile16(zt, ldz, rows16, a.d, u, lane);
 }
 
 // ---- rows cut into several segments: add the partial rows in segment order ------------------
@@ -619,10 +630,15 @@ hipError_t launch_update_rest(const SpmmArgs& a, int32_t n_rest, const int32_t* 
                               hipStream_t s)
 {
     if (n_rest <= 0) return hipSuccess;
-    const dim3 grid((unsigned)((n_rest + 63) / 64));
-    if (a.d <= 64) hipLaunchKernelGGL(k_update_rest<64>, grid, dim3(256), 0, s, n_rest, rest_rows, a, upd);
-    else if (a.d <= 128) hipLaunchKernelGGL(k_update_rest<128>, grid, dim3(256), 0, s, n_rest, rest_rows, a, upd);
-    else if (a.d <= 256) hipLaunchKernelGGL(k_update_rest<256>, grid, dim3(256), 0, s, n_rest, rest_rows, a, upd);
+    // several consecutive tiles per wave once there are enough tiles to keep every CU supplied with waves
+    const int64_t n_tiles = ((int64_t)n_rest + 15) / 16;
+    int tpw = 1;
+    while (tpw < 8 && n_tiles / (2 * tpw) >= 16384) tpw *= 2;
+    if (const char* t = getenv("HCSPMM_TUNE_TILES_PER_WAVE")) { const int v = atoi(t); if (v >= 1 && v <= 64) tpw = v; }
+    const dim3 grid((unsigned)((n_tiles + 4 * (int64_t)tpw - 1) / (4 * (int64_t)tpw)));
+    if (a.d <= 64) hipLaunchKernelGGL(k_update_rest<64>, grid, dim3(256), 0, s, n_rest, rest_rows, tpw, a, upd);
+    else if (a.d <= 128) hipLaunchKernelGGL(k_update_rest<128>, grid, dim3(256), 0, s, n_rest, rest_rows, tpw, a, upd);
+    else if (a.d <= 256) hipLaunchKernelGGL(k_update_rest<256>, grid, dim3(256), 0, s, n_rest, rest_rows, tpw, a, upd);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

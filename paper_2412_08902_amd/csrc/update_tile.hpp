@@ -113,6 +113,7 @@ __device__ inline void update_tile16(const float* zt, int ldz, const int32_t* ro
     if (u.d_out % 4 == 0 && u.ldw % 4 == 0 && u.ldy % 4 == 0 && pw % 16 == 0 && py % 16 == 0) nt = 4;
     else if (u.d_out % 2 == 0 && u.ldw % 2 == 0 && u.ldy % 2 == 0 && pw % 8 == 0 && py % 8 == 0) nt = 2;
     while (nt > 1 && (u.d_out + 16 * nt - 1) / (16 * nt) < pass_step) nt >>= 1;
+    while (nt > 1 && 16 * (nt / 2) >= u.d_out) nt >>= 1;      // no accumulator tiles that hold only padding columns
     if (nt == 4) update_tile16_nt<4>(zt, ldz, rows16, d_in, u, lane, pass_first, pass_step);
     else if (nt == 2) update_tile16_nt<2>(zt, ldz, rows16, d_in, u, lane, pass_first, pass_step);
     else update_tile16_nt<1>(zt, ldz, rows16, d_in, u, lane, pass_first, pass_step);
