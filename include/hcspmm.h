@@ -257,7 +257,8 @@ size_t hcspmm_gcn_workspace_bytes(const hcspmm_plan* plan, int32_t d_in, int32_t
  * tiles stay in LDS and are multiplied by W on the fp32 matrix cores before anything is stored;
  * the remaining rows (long rows, very wide windows) pass through the workspace.  Otherwise, and when
  * those remaining rows are a quarter of the matrix or more, Z = A X is written to the workspace
- * and one fp32 MFMA GEMM applies W and the activation.
+ * and one fp32 MFMA kernel applies W and the activation (also for fp32 X with d_in of 48..128 and
+ * d_out <= 64 on matrices of 32,768 rows or more, where that route measured faster).
  *
  *   d_X   device, n_cols x d_in, element type x_dtype (ldx >= d_in)
  *   d_W   device, d_in x d_out fp32 (ldw >= d_out);  d_Y  device, n_rows x d_out fp32 (ldy >= d_out)

@@ -831,6 +831,14 @@ hcspmm_status hcspmm_gcn_layer_ex(const hcspmm_plan* plan, const void* d_X, int6
     return run_spmm(plan, a, s);
 }
 
+// Where the separate update runs through the streaming 16-row kernel (narrow W, aggregated width 64 or 128) it
+// measured 4-23 % ahead of the fused update on graphs large enough not to be launch-bound; everywhere else
+// (aggregated width up to 32 or of 256, wide W, small graphs) the fused kernels are level or ahead.
+static bool split_update_faster(int64_t n_rows, int32_t agg_width, int32_t out_width, const float* Z)
+{
+    return n_rows >= 32768 && agg_width > 32 && gemm_rows16_usable(n_rows, agg_width, out_width, Z, agg_width);
+}
+
 size_t hcspmm_aggregate_update_workspace_bytes(const hcspmm_plan* plan, int32_t d_in, int32_t d_out)
 {
     (void)d_out;
@@ -863,7 +871,9 @@ hcspmm_status hcspmm_aggregate_update(const hcspmm_plan* plan, const void* d_X, 
     // The fused update pays where most rows can keep their tile on chip; rows that go through the
     // workspace anyway (wide matrix-path windows, mid and long rows) are finished 16 at a time, which
     // a plain GEMM does better once they are a large share of the matrix.
-    const bool worth = 4 * (int64_t)plan->n_rest < plan->n_rows || getenv("HCSPMM_TUNE_FORCE_FUSE");
+    const bool worth = (4 * (int64_t)plan->n_rest < plan->n_rows &&
+                        !(x_dtype == HCSPMM_F32 && split_update_faster(plan->n_rows, d_in, d_out, Z))) ||
+                       getenv("HCSPMM_TUNE_FORCE_FUSE");
     if (update_fusable(a) && worth && !getenv("HCSPMM_TUNE_NO_FUSE")) {
         const UpdateArgs u{static_cast<const float*>(d_W), ldw, d_out, static_cast<float*>(d_Y), ldy, apply_relu ? 1 : 0};
         return run_spmm(plan, a, s, nullptr, &u);
@@ -937,7 +947,8 @@ hcspmm_status hcspmm_layer_backward(const hcspmm_plan* plan, const void* d_G, in
             HC_HIP(launch_transpose(d_in, d_out, static_cast<const float*>(d_W), ldw, Wt, s));
             // as in hcspmm_aggregate_update; when dW needs S in memory as well, the fused kernels store every
             // tile besides multiplying it, which measured faster than the separate GEMM only for narrow S
-            const bool worth = (4 * (int64_t)plan->n_rest < plan->n_rows && (!d_dW || d_out <= 32)) ||
+            const bool worth = (4 * (int64_t)plan->n_rest < plan->n_rows && (!d_dW || d_out <= 32) &&
+                                !split_update_faster(plan->n_rows, d_out, d_in, S)) ||
                                getenv("HCSPMM_TUNE_FORCE_FUSE");
             if (update_fusable(a) && worth && !getenv("HCSPMM_TUNE_NO_FUSE")) {
                 // the next layer's activation mask (its output is this layer's input X) goes into the update's epilogue

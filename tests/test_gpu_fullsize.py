@@ -134,8 +134,12 @@ def test_aggregate_update_fused_at_full_size(name, d_out):
     Xd, Wd = torch.from_numpy(X).cuda(), torch.from_numpy(Wm).cuda()
     ws = torch.empty(hc.hcspmm_aggregate_update_workspace_bytes(plan, X.shape[1], d_out), dtype=torch.uint8, device="cuda")
     Y = torch.full((g.n_rows, d_out), float("nan"), device="cuda")
-    hc.hcspmm_aggregate_update(plan, Xd, Wd, Y, ws)
-    torch.cuda.synchronize()
+    os.environ["HCSPMM_TUNE_FORCE_FUSE"] = "1"      # the fused kernels, also where the library would pick the other route
+    try:
+        hc.hcspmm_aggregate_update(plan, Xd, Wd, Y, ws)
+        torch.cuda.synchronize()
+    finally:
+        del os.environ["HCSPMM_TUNE_FORCE_FUSE"]
     rows = sample_rows(g, 300, seed=5)
     ref = oracle.aggregate_update_rows(rows, g.rowptr, g.colind, g.vals, X, Wm)
     bound = oracle.aggregate_update_rows(rows, g.rowptr, g.colind, g.vals, X, Wm, use_abs=True)
