@@ -434,7 +434,9 @@ __global__ __launch_bounds__(256) void k_csr_fused(CsrWork wk, SpmmArgs a, Updat
 // One wave per 16 entries of the plan's list of such rows (rows of matrix-path windows wider than
 // the wave-per-window kernel handles, scalar-path rows above the short tier): they were written to
 // Z, are read back as a 16-row tile and multiplied by W.
-template <int ZD>
+// NT: output columns per lane and pass (chosen on the host by update_tile_nt; a narrower NT needs fewer registers,
+// which is what bounds the waves in flight of this streaming kernel).
+template <int ZD, int NT>
 __global__ __launch_bounds__(256) void k_update_rest(int32_t n_rest, const int32_t* __restrict__ rest_rows, int tiles_per_wave,
                                                      SpmmArgs a, UpdateArgs u)
 {
@@ -476,7 +478,7 @@ __global__ __launch_bounds__(256) void k_update_rest(int32_t n_rest, const int32
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         if (t + 1 < t_end) request(t + 1, rows_s[(t + 1 - t_begin) & 1] + wave * 16);
-        update_tile16(zt, ldz, rows16, a.d, u, lane);
+        update_tile16_nt<NT>(zt, ldz, rows16, a.d, u, lane, 0, 1);
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the tile's LDS reads are done before it is overwritten
     }
 }
@@ -636,10 +638,18 @@ hipError_t launch_update_rest(const SpmmArgs& a, int32_t n_rest, const int32_t* 
     while (tpw < 8 && n_tiles / (2 * tpw) >= 16384) tpw *= 2;
     if (const char* t = getenv("HCSPMM_TUNE_TILES_PER_WAVE")) { const int v = atoi(t); if (v >= 1 && v <= 64) tpw = v; }
     const dim3 grid((unsigned)((n_tiles + 4 * (int64_t)tpw - 1) / (4 * (int64_t)tpw)));
-    if (a.d <= 64) hipLaunchKernelGGL(k_update_rest<64>, grid, dim3(256), 0, s, n_rest, rest_rows, tpw, a, upd);
-    else if (a.d <= 128) hipLaunchKernelGGL(k_update_rest<128>, grid, dim3(256), 0, s, n_rest, rest_rows, tpw, a, upd);
-    else if (a.d <= 256) hipLaunchKernelGGL(k_update_rest<256>, grid, dim3(256), 0, s, n_rest, rest_rows, tpw, a, upd);
+    const int nt = update_tile_nt(upd, 1);
+#define HC_REST(ZD)                                                                                                   \
+    {                                                                                                                 \
+        if (nt == 4) hipLaunchKernelGGL((k_update_rest<ZD, 4>), grid, dim3(256), 0, s, n_rest, rest_rows, tpw, a, upd);      \
+        else if (nt == 2) hipLaunchKernelGGL((k_update_rest<ZD, 2>), grid, dim3(256), 0, s, n_rest, rest_rows, tpw, a, upd); \
+        else hipLaunchKernelGGL((k_update_rest<ZD, 1>), grid, dim3(256), 0, s, n_rest, rest_rows, tpw, a, upd);              \
+    }
+    if (a.d <= 64) HC_REST(64)
+    else if (a.d <= 128) HC_REST(128)
+    else if (a.d <= 256) HC_REST(256)
     else return hipErrorInvalidValue;
+#undef HC_REST
     return hipGetLastError();
 }
 

@@ -105,8 +105,7 @@ __device__ inline void store_tile_rows(const float* zt, int ldz, const int32_t* 
 }
 
 // Picks the widest vector the operands allow, narrowed until the waves sharing the tile all get a pass.
-__device__ inline void update_tile16(const float* zt, int ldz, const int32_t* rows16, int d_in, const UpdateArgs& u,
-                                     int lane, int pass_first = 0, int pass_step = 1)
+__host__ __device__ inline int update_tile_nt(const UpdateArgs& u, int pass_step)
 {
     const uintptr_t pw = (uintptr_t)u.W, py = (uintptr_t)u.Y;
     int nt = 1;
@@ -114,6 +113,13 @@ __device__ inline void update_tile16(const float* zt, int ldz, const int32_t* ro
     else if (u.d_out % 2 == 0 && u.ldw % 2 == 0 && u.ldy % 2 == 0 && pw % 8 == 0 && py % 8 == 0) nt = 2;
     while (nt > 1 && (u.d_out + 16 * nt - 1) / (16 * nt) < pass_step) nt >>= 1;
     while (nt > 1 && 16 * (nt / 2) >= u.d_out) nt >>= 1;      // no accumulator tiles that hold only padding columns
+    return nt;
+}
+
+__device__ inline void update_tile16(const float* zt, int ldz, const int32_t* rows16, int d_in, const UpdateArgs& u,
+                                     int lane, int pass_first = 0, int pass_step = 1)
+{
+    const int nt = update_tile_nt(u, pass_step);
     if (nt == 4) update_tile16_nt<4>(zt, ldz, rows16, d_in, u, lane, pass_first, pass_step);
     else if (nt == 2) update_tile16_nt<2>(zt, ldz, rows16, d_in, u, lane, pass_first, pass_step);
     else update_tile16_nt<1>(zt, ldz, rows16, d_in, u, lane, pass_first, pass_step);
