@@ -347,6 +347,17 @@ hcspmm_status hcspmm_permute_csr(int32_t n, const int32_t* h_rowptr, const int32
                                  const int32_t* h_order, int32_t* h_out_rowptr, int32_t* h_out_colind,
                                  float* h_out_vals);
 
+/*
+ * Transpose of a CSR matrix on the host: the backward aggregation (Eq. 4) multiplies by the
+ * transpose of the forward matrix, which is the matrix itself only when it is symmetric; for a
+ * directed graph prepare a second plan from this function's output.  The result is n_cols x n_rows
+ * with ascending columns in every row.  h_out_rowptr has n_cols + 1 entries, h_out_colind and
+ * h_out_vals as many as the input.  Runs on the calling thread; touches no GPU.
+ */
+hcspmm_status hcspmm_transpose_csr(int32_t n_rows, int32_t n_cols, const int32_t* h_rowptr, const int32_t* h_colind,
+                                   const float* h_vals, int32_t* h_out_rowptr, int32_t* h_out_colind,
+                                   float* h_out_vals);
+
 /* Frees everything the plan owns (not the borrowed CSR).  NULL is allowed. */
 void hcspmm_plan_destroy(hcspmm_plan* plan);
 

@@ -22,7 +22,7 @@ EXPORTED_SYMBOLS = [
     "hcspmm_plan_export", "hcspmm_spmm", "hcspmm_spmm_timed", "hcspmm_gcn_layer", "hcspmm_gcn_layer_ex", "hcspmm_gcn_workspace_bytes",
     "hcspmm_aggregate_update", "hcspmm_aggregate_update_workspace_bytes",
     "hcspmm_layer_backward", "hcspmm_layer_backward_workspace_bytes",
-    "hcspmm_gemm_f32", "hcspmm_loa_order", "hcspmm_permute_csr", "hcspmm_plan_destroy", "hcspmm_status_string", "hcspmm_last_error", "hcspmm_version",
+    "hcspmm_gemm_f32", "hcspmm_loa_order", "hcspmm_permute_csr", "hcspmm_transpose_csr", "hcspmm_plan_destroy", "hcspmm_status_string", "hcspmm_last_error", "hcspmm_version",
 ]
 
 
@@ -103,6 +103,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.hcspmm_loa_order.restype = ctypes.c_int
     lib.hcspmm_permute_csr.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp]
     lib.hcspmm_permute_csr.restype = ctypes.c_int
+    lib.hcspmm_transpose_csr.argtypes = [i32, i32, vp, vp, vp, vp, vp, vp]
+    lib.hcspmm_transpose_csr.restype = ctypes.c_int
     lib.hcspmm_gemm_f32.argtypes = [i64, i32, i32, vp, i64, vp, i64, vp, i64, vp]
     lib.hcspmm_gemm_f32.restype = ctypes.c_int
     lib.hcspmm_plan_destroy.argtypes = [vp]
@@ -345,6 +347,20 @@ def hcspmm_permute_csr(n: int, rowptr, colind, vals, order):
     _check(load_library().hcspmm_permute_csr(n, _host_ptr(rowptr), _host_ptr(colind), _host_ptr(vals),
                                              _host_ptr(order), _host_ptr(out_rp), _host_ptr(out_ci),
                                              _host_ptr(out_va)))
+    return out_rp, out_ci, out_va
+
+
+def hcspmm_transpose_csr(n_rows: int, n_cols: int, rowptr, colind, vals):
+    """A^T on the host (n_cols x n_rows, ascending columns); returns (rowptr, colind, vals) numpy arrays."""
+    import numpy as np
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int32)
+    colind = np.ascontiguousarray(colind, dtype=np.int32)
+    vals = np.ascontiguousarray(vals, dtype=np.float32)
+    assert rowptr.shape[0] == n_rows + 1
+    out_rp = np.empty(n_cols + 1, dtype=np.int32)
+    out_ci, out_va = np.empty_like(colind), np.empty_like(vals)
+    _check(load_library().hcspmm_transpose_csr(n_rows, n_cols, _host_ptr(rowptr), _host_ptr(colind), _host_ptr(vals),
+                                               _host_ptr(out_rp), _host_ptr(out_ci), _host_ptr(out_va)))
     return out_rp, out_ci, out_va
 
 

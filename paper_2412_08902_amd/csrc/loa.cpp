@@ -195,4 +195,42 @@ hcspmm_status hcspmm_permute_csr(int32_t n, const int32_t* h_rowptr, const int32
     return HCSPMM_OK;
 }
 
+// Transpose of a CSR matrix by a counting sort over the column indices; rows of the result are
+// ascending in the column index and keep the input's row order among duplicates (stable).
+hcspmm_status hcspmm_transpose_csr(int32_t n_rows, int32_t n_cols, const int32_t* h_rowptr, const int32_t* h_colind,
+                                   const float* h_vals, int32_t* h_out_rowptr, int32_t* h_out_colind, float* h_out_vals)
+{
+    using hcspmm::set_error;
+    if (n_rows < 0 || n_cols < 0) { set_error("sizes must be non-negative"); return HCSPMM_EINVAL; }
+    if (!h_rowptr || !h_out_rowptr) { set_error("rowptr or out_rowptr is NULL"); return HCSPMM_EINVAL; }
+    if (h_rowptr[0] != 0) { set_error("invalid CSR: rowptr[0] != 0"); return HCSPMM_EBADCSR; }
+    const int32_t nnz = h_rowptr[n_rows];
+    if (nnz < 0) { set_error("invalid CSR: negative entry count"); return HCSPMM_EBADCSR; }
+    if (nnz > 0 && (!h_colind || !h_vals || !h_out_colind || !h_out_vals)) { set_error("an entry array is NULL"); return HCSPMM_EINVAL; }
+    for (int32_t c = 0; c <= n_cols; ++c) h_out_rowptr[c] = 0;
+    for (int32_t i = 0; i < n_rows; ++i) {
+        const int32_t s = h_rowptr[i], e = h_rowptr[i + 1];
+        if (s < 0 || s > e || e > nnz) { set_error("invalid CSR: rowptr not monotone"); return HCSPMM_EBADCSR; }
+        for (int32_t k = s; k < e; ++k) {
+            const int32_t c = h_colind[k];
+            if (c < 0 || c >= n_cols) { set_error("invalid CSR: column index out of range"); return HCSPMM_EBADCSR; }
+            ++h_out_rowptr[c + 1];
+        }
+    }
+    for (int32_t c = 0; c < n_cols; ++c) h_out_rowptr[c + 1] += h_out_rowptr[c];
+    try {
+        std::vector<int32_t> cursor(h_out_rowptr, h_out_rowptr + n_cols);
+        for (int32_t i = 0; i < n_rows; ++i)
+            for (int32_t k = h_rowptr[i]; k < h_rowptr[i + 1]; ++k) {
+                const int32_t p = cursor[h_colind[k]]++;
+                h_out_colind[p] = i;
+                h_out_vals[p] = h_vals[k];
+            }
+    } catch (const std::bad_alloc&) {
+        set_error("host allocation failed in the CSR transpose");
+        return HCSPMM_EALLOC;
+    }
+    return HCSPMM_OK;
+}
+
 }  // extern "C"

@@ -300,3 +300,29 @@ def test_two_layer_gcn_forward_and_backward_compose():
     # the bilinear identity of the last layer ties the loss to its weight gradient: <dW2, W2> = <C, out>
     L = float(np.sum(C.astype(np.float64) * f64(out)))
     assert abs(float(np.sum(f64(dW2) * W2)) - L) <= 1e-5 * float(np.sum(np.abs(C) * oracle.gcn_layer(*a, H1h, W2, use_abs=True)))
+
+
+def test_backward_of_a_directed_graph_through_the_transposed_plan():
+    """Forward with a non-symmetric matrix, backward with a plan of its transpose (hcspmm_transpose_csr): the GPU chain
+    against the oracle chain, and <dW, W> = <G, forward output> ties the two plans together."""
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    g = tiny_random_csr(3000, 3000, 0.004, seed=71)             # no symmetry at all
+    X, W = dense_normal(3000, 32, seed=72), glorot_uniform(32, 48, seed=73)
+    G = dense_normal(3000, 48, seed=74)
+    trp, tci, tva = hc.hcspmm_transpose_csr(g.n_rows, g.n_cols, g.rowptr, g.colind, g.vals)
+    from workloads import CSRGraph
+    gt = CSRGraph(g.n_cols, g.n_rows, trp, tci, tva)
+    dX, dW, S = run_backward(gt, G, X, W)
+    check(gt, G, X, W, dX, dW, S)
+    rp, ci, va = device_graph(g)
+    plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, d_hint=48)
+    ws = torch.empty(hc.hcspmm_gcn_workspace_bytes(plan, 32, 48), dtype=torch.uint8, device="cuda")
+    Y = torch.empty((3000, 48), device="cuda")
+    hc.hcspmm_gcn_layer(plan, torch.from_numpy(X).cuda(), torch.from_numpy(W).cuda(), Y, ws, apply_relu=False)
+    torch.cuda.synchronize()
+    plan.destroy()
+    L = float(np.sum(G.astype(np.float64) * Y.cpu().numpy().astype(np.float64)))
+    scale = float(np.sum(np.abs(G) * oracle.gcn_layer(g.rowptr, g.colind, g.vals, X, W, use_abs=True)))
+    assert abs(float(np.sum(dW * W)) - L) <= 1e-5 * scale
+    assert abs(float(np.sum(dX * X)) - L) <= 1e-5 * scale

@@ -89,3 +89,35 @@ def test_random_structures_match_oracle():
         np.testing.assert_array_equal(got, want)
 
     check()
+
+
+@pytest.mark.parametrize("shape", [(37, 53), (64, 64), (1, 9), (9, 1), (0, 5)])
+def test_transpose_csr_matches_scipy(shape):
+    """Host transpose (for the backward aggregation of a directed graph): structure and values against scipy,
+    ascending columns, duplicates kept in row order."""
+    import scipy.sparse as sp
+    import paper_2412_08902_amd.binding as hc
+    from workloads import tiny_random_csr
+    n, m = shape
+    g = tiny_random_csr(n, m, 0.2, seed=n + m, sorted_rows=False, duplicates=True)
+    rp, ci, va = hc.hcspmm_transpose_csr(n, m, g.rowptr, g.colind, g.vals)
+    assert rp.shape == (m + 1,) and rp[0] == 0 and rp[-1] == g.nnz
+    A = sp.csr_matrix((g.vals.astype(np.float64), g.colind, g.rowptr), shape=(n, m))
+    At = sp.csr_matrix((va.astype(np.float64), ci, rp), shape=(m, n))
+    assert abs(A.T - At).sum() == 0
+    for r in range(m):
+        assert np.all(np.diff(ci[rp[r]:rp[r + 1]]) >= 0)
+    # the entries keep their identity: every (row, col, value) of the input appears exactly once, transposed
+    rows = np.repeat(np.arange(n), np.diff(g.rowptr))
+    want = sorted(zip(g.colind.tolist(), rows.tolist(), g.vals.tolist()))
+    trows = np.repeat(np.arange(m), np.diff(rp))
+    got = sorted(zip(trows.tolist(), ci.tolist(), va.tolist()))
+    assert got == want
+
+
+def test_transpose_csr_rejects_bad_input():
+    import paper_2412_08902_amd.binding as hc
+    with pytest.raises(hc.HcspmmError):
+        hc.hcspmm_transpose_csr(2, 3, np.array([0, 1, 2], np.int32), np.array([0, 3], np.int32), np.ones(2, np.float32))
+    with pytest.raises(hc.HcspmmError):
+        hc.hcspmm_transpose_csr(2, 3, np.array([0, 2, 1], np.int32), np.array([0, 1], np.int32), np.ones(2, np.float32))

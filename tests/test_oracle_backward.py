@@ -208,3 +208,37 @@ def test_masked_input_gradient_chains_two_layers():
     # and the flag is exactly "mask afterwards"
     dH1, _ = oracle.layer_backward(rowptr, colind, vals, C, H1, W2)
     assert np.array_equal(dH1m, np.where(H1 > 0, dH1, 0.0))
+
+
+def test_directed_graph_backward_uses_the_transpose():
+    """For a non-symmetric forward matrix the backward aggregation multiplies by its transpose: central differences of
+    L = <C, ReLU(A_f X W)> against the oracle called with A_f^T (built here with scipy)."""
+    import scipy.sparse as sp
+    rng = np.random.default_rng(21)
+    n, d_in, d_out = 11, 3, 4
+    Af = ((rng.random((n, n)) < 0.3) * rng.standard_normal((n, n))).astype(np.float32).astype(np.float64)
+    assert np.abs(Af - Af.T).max() > 0.1
+    At = sp.csr_matrix(Af.T)
+    At.sort_indices()
+    X = rng.standard_normal((n, d_in))
+    W = rng.standard_normal((d_in, d_out))
+    C = rng.standard_normal((n, d_out))
+    pre = Af @ (X @ W)
+    assert np.min(np.abs(pre)) > 1e-4
+    Y = np.maximum(pre, 0.0)
+    dX, dW = oracle.layer_backward(At.indptr.astype(np.int32), At.indices.astype(np.int32), At.data.astype(np.float32),
+                                   C, X, W, Y_fwd=Y)
+    loss = lambda Xv, Wv: float(np.sum(C * np.maximum(Af @ (Xv @ Wv), 0.0)))
+    h = 1e-6
+    for a in range(d_in):
+        for b in range(d_out):
+            Wp, Wm = W.copy(), W.copy()
+            Wp[a, b] += h
+            Wm[a, b] -= h
+            assert abs((loss(X, Wp) - loss(X, Wm)) / (2 * h) - dW[a, b]) <= 1e-6 * max(1.0, abs(dW[a, b]))
+    for i in range(n):
+        for a in range(d_in):
+            Xp, Xm = X.copy(), X.copy()
+            Xp[i, a] += h
+            Xm[i, a] -= h
+            assert abs((loss(Xp, W) - loss(Xm, W)) / (2 * h) - dX[i, a]) <= 1e-6 * max(1.0, abs(dX[i, a]))
