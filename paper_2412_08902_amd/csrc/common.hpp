@@ -58,6 +58,12 @@ void set_error(const char* fmt, ...);
 // at least scan_scratch_elems(n) int64.  Enqueued on `stream`.
 size_t scan_scratch_elems(int64_t n);
 hipError_t exclusive_scan_i32_i64(const int32_t* in, int64_t n, int64_t* out, int64_t* scratch, hipStream_t stream);
+// up to kScanMaxArrays arrays of one length in one pass: out[a] (n + 1 entries; may be null when only the total is
+// wanted) and totals_dev[a] (device, may be null) for every array a; scratch holds scan_multi_scratch_elems(n) values
+constexpr int kScanMaxArrays = 8;
+struct ScanMulti { const int32_t* in[kScanMaxArrays]; int64_t* out[kScanMaxArrays]; int k; };
+size_t scan_multi_scratch_elems(int64_t n);
+hipError_t exclusive_scan_multi(const ScanMulti& m, int64_t n, int64_t* totals_dev, int64_t* scratch, hipStream_t stream);
 
 // ---- preprocessing launchers (prepare_kernels.hip) ---------------------------------------------
 hipError_t launch_validate(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
@@ -229,6 +235,9 @@ struct hcspmm_plan {
     int64_t n_slots;
     int32_t n_long_rows;
     int32_t condensed_complete;     // 0: wcols / erc are filled for matrix-path windows only (the rest on export)
+    int32_t erc_own, wcols_own;     // erc / wcols were allocated on their own (on export), not from the plan's chunks
+    void* chunks[64];               // device allocations that hold the plan-owned arrays (several arrays per chunk)
+    int32_t n_chunks;
     int32_t features_complete;    // ncols / wptr / total_ncols are filled (a scalar-only plan computes them on first request)
     int32_t n_rest;                 // rows finished through the workspace by the fused update
     int32_t* rest_rows;

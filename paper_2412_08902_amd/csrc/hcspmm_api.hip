@@ -89,11 +89,16 @@ struct DevAlloc {
         arena_used = 0;
         return hipSuccess;
     }
+    size_t chunk_min = 0;           // > 0: arrays are carved out of chunks of at least this size (few device allocations)
     static size_t padded(size_t sz) { return (sz + 255) & ~(size_t)255; }
     template <class T> hipError_t get(T** out, size_t count)
     {
         size_t sz = count * sizeof(T);
         if (sz == 0) sz = sizeof(T) < 16 ? 16 : sizeof(T);
+        if (chunk_min && !(arena && arena_used + padded(sz) <= arena_size)) {
+            const hipError_t e = reserve(padded(sz) > chunk_min ? padded(sz) : chunk_min);
+            if (e != hipSuccess) { *out = nullptr; return e; }
+        }
         if (arena && arena_used + padded(sz) <= arena_size) {
             *out = reinterpret_cast<T*>(arena + arena_used);
             arena_used += padded(sz);
@@ -139,9 +144,10 @@ struct DevAlloc {
 
 static void free_plan_arrays(hcspmm_plan* p)
 {
-    void* owned[] = {p->ncols, p->nnzw, p->route, p->wptr, p->wcols, p->erc, p->mfma_windows, p->csr_windows,
-                     p->mfma_small, p->mfma_small_desc, p->mfma_mid, p->mfma_big, p->mid_slices, p->big_slices, p->big_slice_rows, p->tile_multi,
-                     p->tile_partial, p->short_rows, p->mid_rows, p->segs, p->multi, p->partial, p->rest_rows};
+    // the plan's arrays live in a few chunks; only the lazily sized buffers and arrays completed on export are separate
+    for (int32_t i = 0; i < p->n_chunks; ++i) (void)hipFree(p->chunks[i]);
+    p->n_chunks = 0;
+    void* owned[] = {p->erc_own ? p->erc : nullptr, p->wcols_own ? p->wcols : nullptr, p->tile_partial, p->partial};
     for (void* q : owned)
         if (q) (void)hipFree(q);
 }
@@ -178,13 +184,19 @@ static hcspmm_status complete_condensed(hcspmm_plan* p, bool features_only)
         p->features_complete = 1;
     }
     if (!features_only && !p->condensed_complete) {
-        if (!p->erc && hipMalloc((void**)&p->erc, (size_t)(p->nnz > 0 ? p->nnz : 1) * sizeof(int32_t)) != hipSuccess) {
-            (void)hipGetLastError(); p->erc = nullptr;
-            set_error("device allocation failed while completing the condensed structure"); st = HCSPMM_EALLOC; goto fail;
+        if (!p->erc) {
+            if (hipMalloc((void**)&p->erc, (size_t)(p->nnz > 0 ? p->nnz : 1) * sizeof(int32_t)) != hipSuccess) {
+                (void)hipGetLastError(); p->erc = nullptr;
+                set_error("device allocation failed while completing the condensed structure"); st = HCSPMM_EALLOC; goto fail;
+            }
+            p->erc_own = 1;
         }
-        if (!p->wcols && hipMalloc((void**)&p->wcols, (size_t)(p->total_ncols > 0 ? p->total_ncols : 1) * sizeof(int32_t)) != hipSuccess) {
-            (void)hipGetLastError(); p->wcols = nullptr;
-            set_error("device allocation failed while completing the condensed structure"); st = HCSPMM_EALLOC; goto fail;
+        if (!p->wcols) {
+            if (hipMalloc((void**)&p->wcols, (size_t)(p->total_ncols > 0 ? p->total_ncols : 1) * sizeof(int32_t)) != hipSuccess) {
+                (void)hipGetLastError(); p->wcols = nullptr;
+                set_error("device allocation failed while completing the condensed structure"); st = HCSPMM_EALLOC; goto fail;
+            }
+            p->wcols_own = 1;
         }
         if (W > 0)
             HC_TRY(launch_ecol(W, p->n_rows, p->rowptr, p->colind, tmp_cols, p->ncols, p->wptr, p->wcols, p->erc, cnt, p->route, 0,
@@ -205,25 +217,28 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
 {
     hcspmm_status st = HCSPMM_OK;
     DevAlloc tmp;      // scratch, freed on exit
-    DevAlloc keep;     // plan-owned, freed on failure only
+    DevAlloc keep;     // plan-owned (chunks handed to the plan on success), freed on failure only
     const int32_t n_rows = p->n_rows, W = p->W;
     const int64_t nnz = p->nnz;
+    keep.chunk_min = (size_t)1 << 20;      // small graphs: all plan arrays in one or two device allocations
     int32_t *err = nullptr, *big_list = nullptr, *huge_list = nullptr, *big_count = nullptr, *tmp_cols = nullptr;
     int32_t *f_mfma = nullptr, *f_csr = nullptr, *f_small = nullptr, *f_midw = nullptr, *f_big = nullptr, *nnz_if = nullptr;
     int32_t *f_short = nullptr, *f_mid = nullptr, *n_seg = nullptr, *f_multi = nullptr, *n_slot = nullptr, *len_long = nullptr;
-    int64_t *scan_tmp = nullptr, *pos_a = nullptr, *pos_b = nullptr, *pos_c = nullptr, *pos_d = nullptr;
+    int64_t *scan_tmp = nullptr, *pos_a = nullptr, *pos_b = nullptr, *pos_c = nullptr, *pos_d = nullptr, *pos_e = nullptr, *pos_f = nullptr;
+    int32_t* f_rest = nullptr;
     int64_t *totals_dev = nullptr;
     int32_t h_err = 0, h_big = 0, h_cls[2] = {0, 0};
-    int64_t h_tot[8];
+    int64_t h_tot[16];
     const int64_t scan_n = (int64_t)(n_rows > W ? n_rows : W) + 1;
 
     {
         // every scratch array of this function has a size known from (n_rows, W, nnz): one allocation
         const size_t i32 = sizeof(int32_t), i64 = sizeof(int64_t);
         size_t total = DevAlloc::padded(4 * i32) + DevAlloc::padded((size_t)nnz * i32) + 2 * DevAlloc::padded((size_t)W * i32) +
-                       DevAlloc::padded((size_t)scan_scratch_elems(scan_n) * i64) + 4 * DevAlloc::padded((size_t)(scan_n + 1) * i64) +
-                       DevAlloc::padded(8 * i64) + 6 * DevAlloc::padded(((size_t)W + 1) * i32) +
-                       6 * DevAlloc::padded(((size_t)n_rows + 1) * i32) + 64 * 256;
+                       DevAlloc::padded((size_t)scan_multi_scratch_elems(scan_n) * i64) +
+                       6 * DevAlloc::padded((size_t)(scan_n + 1) * i64) +
+                       DevAlloc::padded(16 * i64) + 6 * DevAlloc::padded(((size_t)W + 1) * i32) +
+                       7 * DevAlloc::padded(((size_t)n_rows + 1) * i32) + 64 * 256;
         if (tmp.reserve(total) != hipSuccess) {
             (void)hipGetLastError();
             set_error("device allocation of %zu scratch bytes failed", total);
@@ -252,12 +267,14 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     HC_ALLOC(tmp, tmp_cols, nnz);
     HC_ALLOC(tmp, big_list, W);
     HC_ALLOC(tmp, huge_list, W);
-    HC_ALLOC(tmp, scan_tmp, scan_scratch_elems(scan_n));
+    HC_ALLOC(tmp, scan_tmp, scan_multi_scratch_elems(scan_n));
     HC_ALLOC(tmp, pos_a, scan_n + 1);
     HC_ALLOC(tmp, pos_b, scan_n + 1);
     HC_ALLOC(tmp, pos_c, scan_n + 1);
     HC_ALLOC(tmp, pos_d, scan_n + 1);
-    HC_ALLOC(tmp, totals_dev, 8);
+    HC_ALLOC(tmp, pos_e, scan_n + 1);
+    HC_ALLOC(tmp, pos_f, scan_n + 1);
+    HC_ALLOC(tmp, totals_dev, 16);
 
     // A scalar-only plan never reads the condensed structure (the paper has no preprocessing for its
     // scalar path either): its window features stay zero here and are computed when first asked for
@@ -282,13 +299,16 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
         }
     }
     if (p->features_complete) {
-        HC_TRY(exclusive_scan_i32_i64(p->ncols, W, p->wptr, scan_tmp, stream));
-        HC_TRY(hipMemcpyAsync(&p->total_ncols, p->wptr + W, sizeof(int64_t), hipMemcpyDeviceToHost, stream));
-        HC_TRY(hipStreamSynchronize(stream));
+        ScanMulti m{};
+        m.k = 1;
+        m.in[0] = p->ncols;
+        m.out[0] = p->wptr;
+        HC_TRY(exclusive_scan_multi(m, W, totals_dev + 8, scan_tmp, stream));     // the total is read back with the list sizes below
     } else {
         HC_TRY(hipMemsetAsync(p->wptr, 0, ((size_t)W + 1) * sizeof(int64_t), stream));
-        p->total_ncols = 0;
+        HC_TRY(hipMemsetAsync(totals_dev + 8, 0, sizeof(int64_t), stream));
     }
+    p->total_ncols = 0;
     p->rows_sorted = 1;
 
     // selection (Section IV-C) and the per-route window lists
@@ -318,20 +338,28 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
                                      f_mfma, f_csr, f_small, f_midw, f_big, nnz_if, stream));
         }
     }
-    HC_TRY(exclusive_scan_i32_i64(f_mfma, W, pos_a, scan_tmp, stream));
-    HC_TRY(hipMemcpyAsync(totals_dev + 0, pos_a + W, 8, hipMemcpyDeviceToDevice, stream));
-    HC_TRY(exclusive_scan_i32_i64(f_csr, W, pos_b, scan_tmp, stream));
-    HC_TRY(exclusive_scan_i32_i64(f_small, W, pos_c, scan_tmp, stream));
-    HC_TRY(hipMemcpyAsync(totals_dev + 1, pos_c + W, 8, hipMemcpyDeviceToDevice, stream));
-    HC_TRY(exclusive_scan_i32_i64(f_big, W, pos_d, scan_tmp, stream));
-    HC_TRY(hipMemcpyAsync(totals_dev + 2, pos_d + W, 8, hipMemcpyDeviceToDevice, stream));
-    HC_TRY(hipMemcpyAsync(h_tot, totals_dev, 3 * sizeof(int64_t), hipMemcpyDeviceToHost, stream));
-    HC_TRY(hipStreamSynchronize(stream));
+    {
+        // positions of every window in its lists, and the non-zeros on the matrix path: six scans in one pass,
+        // their totals in one read-back
+        ScanMulti m{};
+        m.k = 6;
+        m.in[0] = f_mfma;  m.out[0] = pos_a;
+        m.in[1] = f_csr;   m.out[1] = pos_b;
+        m.in[2] = f_small; m.out[2] = pos_c;
+        m.in[3] = f_big;   m.out[3] = pos_d;
+        m.in[4] = f_midw;  m.out[4] = pos_e;
+        m.in[5] = nnz_if;  m.out[5] = nullptr;
+        HC_TRY(exclusive_scan_multi(m, W, totals_dev, scan_tmp, stream));
+        HC_TRY(hipMemcpyAsync(h_tot, totals_dev, 9 * sizeof(int64_t), hipMemcpyDeviceToHost, stream));
+        HC_TRY(hipStreamSynchronize(stream));
+    }
+    p->total_ncols = h_tot[8];
     p->n_mfma = (int32_t)h_tot[0];
     p->n_csr = W - p->n_mfma;
-    p->n_mfma_small = (int32_t)h_tot[1];
-    p->n_mfma_big = (int32_t)h_tot[2];
-    p->n_mfma_mid = p->n_mfma - p->n_mfma_small - p->n_mfma_big;
+    p->n_mfma_small = (int32_t)h_tot[2];
+    p->n_mfma_big = (int32_t)h_tot[3];
+    p->n_mfma_mid = (int32_t)h_tot[4];
+    p->nnz_mfma = h_tot[5];
     // condensed structure (column lists, condensed column of every non-zero) of the matrix-path
     // windows; scalar-path windows never read theirs at SpMM time and get it on export only, and a
     // plan without matrix-path windows does not even allocate the arrays
@@ -371,24 +399,25 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     HC_TRY(launch_compact_ids(W, f_csr, pos_b, p->csr_windows, stream));
     HC_TRY(launch_compact_ids(W, f_small, pos_c, p->mfma_small, stream));
     HC_TRY(launch_compact_ids(W, f_big, pos_d, p->mfma_big, stream));
-    HC_TRY(exclusive_scan_i32_i64(f_midw, W, pos_c, scan_tmp, stream));
-    HC_TRY(launch_compact_ids(W, f_midw, pos_c, p->mfma_mid, stream));
-    HC_TRY(exclusive_scan_i32_i64(nnz_if, W, pos_a, scan_tmp, stream));
-    HC_TRY(hipMemcpyAsync(&p->nnz_mfma, pos_a + W, sizeof(int64_t), hipMemcpyDeviceToHost, stream));
-    HC_TRY(hipStreamSynchronize(stream));
+    HC_TRY(launch_compact_ids(W, f_midw, pos_e, p->mfma_mid, stream));
     if (W > 0) HC_TRY(launch_masked_copy(W, f_big, p->ncols, nnz_if, stream));     // nnz_if <- ncols of wide windows, else 0
     // workgroup slices: one per medium window, slice_cols condensed columns each for wide windows
     {
         int32_t* sc_n = f_mfma;      // the flag arrays are free again: reuse them as scratch (W + 1 ints each)
         int32_t* sc_multi = f_csr;
         int32_t* sc_slots = f_small;
+        ScanMulti m{};
+        m.k = 3;
+        m.in[0] = sc_n;     m.out[0] = pos_a;
+        m.in[1] = sc_multi; m.out[1] = pos_b;
+        m.in[2] = sc_slots; m.out[2] = pos_d;
         HC_ALLOC(keep, p->mid_slices, p->n_mfma_mid);
-        HC_TRY(launch_slice_count(p->n_mfma_mid, p->mfma_mid, p->ncols, 0x40000000, sc_n, sc_multi, sc_slots, stream));
-        HC_TRY(exclusive_scan_i32_i64(sc_n, p->n_mfma_mid, pos_a, scan_tmp, stream));
-        HC_TRY(exclusive_scan_i32_i64(sc_multi, p->n_mfma_mid, pos_b, scan_tmp, stream));
-        HC_TRY(exclusive_scan_i32_i64(sc_slots, p->n_mfma_mid, pos_d, scan_tmp, stream));
-        HC_TRY(launch_slice_fill(p->n_mfma_mid, p->mfma_mid, p->ncols, 0x40000000, pos_a, pos_b, pos_d, p->mid_slices,
-                                 nullptr, stream));
+        if (p->n_mfma_mid > 0) {
+            HC_TRY(launch_slice_count(p->n_mfma_mid, p->mfma_mid, p->ncols, 0x40000000, sc_n, sc_multi, sc_slots, stream));
+            HC_TRY(exclusive_scan_multi(m, p->n_mfma_mid, nullptr, scan_tmp, stream));
+            HC_TRY(launch_slice_fill(p->n_mfma_mid, p->mfma_mid, p->ncols, 0x40000000, pos_a, pos_b, pos_d, p->mid_slices,
+                                     nullptr, stream));
+        }
         // Wide windows are cut into slices only as far as parallelism needs it (a slice loses the
         // alignment of concurrently running windows on the same hot low-numbered columns): aim
         // at ~4 workgroups per CU over the summed width of the wide windows.
@@ -402,22 +431,21 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
             if (want > (1 << 27)) want = 1 << 27;
             p->slice_cols = (int32_t)((want + kKcBig - 1) / kKcBig * kKcBig);
         }
-        HC_TRY(launch_slice_count(p->n_mfma_big, p->mfma_big, p->ncols, p->slice_cols, sc_n, sc_multi, sc_slots, stream));
-        HC_TRY(exclusive_scan_i32_i64(sc_n, p->n_mfma_big, pos_a, scan_tmp, stream));
-        HC_TRY(hipMemcpyAsync(totals_dev + 0, pos_a + p->n_mfma_big, 8, hipMemcpyDeviceToDevice, stream));
-        HC_TRY(exclusive_scan_i32_i64(sc_multi, p->n_mfma_big, pos_b, scan_tmp, stream));
-        HC_TRY(hipMemcpyAsync(totals_dev + 1, pos_b + p->n_mfma_big, 8, hipMemcpyDeviceToDevice, stream));
-        HC_TRY(exclusive_scan_i32_i64(sc_slots, p->n_mfma_big, pos_d, scan_tmp, stream));
-        HC_TRY(hipMemcpyAsync(totals_dev + 2, pos_d + p->n_mfma_big, 8, hipMemcpyDeviceToDevice, stream));
-        HC_TRY(hipMemcpyAsync(h_tot, totals_dev, 3 * sizeof(int64_t), hipMemcpyDeviceToHost, stream));
-        HC_TRY(hipStreamSynchronize(stream));
+        h_tot[0] = h_tot[1] = h_tot[2] = 0;
+        if (p->n_mfma_big > 0) {
+            HC_TRY(launch_slice_count(p->n_mfma_big, p->mfma_big, p->ncols, p->slice_cols, sc_n, sc_multi, sc_slots, stream));
+            HC_TRY(exclusive_scan_multi(m, p->n_mfma_big, totals_dev, scan_tmp, stream));
+            HC_TRY(hipMemcpyAsync(h_tot, totals_dev, 3 * sizeof(int64_t), hipMemcpyDeviceToHost, stream));
+            HC_TRY(hipStreamSynchronize(stream));
+        }
         p->n_big_slices = (int32_t)h_tot[0];
         p->n_tile_multi = (int32_t)h_tot[1];
         p->n_tile_slots = h_tot[2];
         HC_ALLOC(keep, p->big_slices, p->n_big_slices);
         HC_ALLOC(keep, p->tile_multi, p->n_tile_multi);
-        HC_TRY(launch_slice_fill(p->n_mfma_big, p->mfma_big, p->ncols, p->slice_cols, pos_a, pos_b, pos_d, p->big_slices,
-                                 p->tile_multi, stream));
+        if (p->n_mfma_big > 0)
+            HC_TRY(launch_slice_fill(p->n_mfma_big, p->mfma_big, p->ncols, p->slice_cols, pos_a, pos_b, pos_d, p->big_slices,
+                                     p->tile_multi, stream));
         if (p->rows_sorted && p->n_big_slices > 0) {
             HC_ALLOC(keep, p->big_slice_rows, (size_t)p->n_big_slices * kH);
             HC_TRY(launch_slice_rows(p->n_big_slices, p->big_slices, n_rows, p->rowptr, p->erc, p->big_slice_rows,
@@ -435,39 +463,40 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     HC_ALLOC(tmp, f_multi, (size_t)n_rows + 1);
     HC_ALLOC(tmp, n_slot, (size_t)n_rows + 1);
     HC_ALLOC(tmp, len_long, (size_t)n_rows + 1);
+    HC_ALLOC(tmp, f_rest, (size_t)n_rows + 1);
     HC_TRY(launch_row_class(n_rows, p->rowptr, p->route, p->mid_row, p->long_row, f_short, f_mid, n_seg, f_multi, n_slot, len_long, stream));
-    HC_TRY(exclusive_scan_i32_i64(len_long, n_rows, pos_a, scan_tmp, stream));
-    HC_TRY(hipMemcpyAsync(totals_dev + 4, pos_a + n_rows, 8, hipMemcpyDeviceToDevice, stream));
-    HC_TRY(exclusive_scan_i32_i64(f_short, n_rows, pos_a, scan_tmp, stream));
-    HC_TRY(hipMemcpyAsync(totals_dev + 0, pos_a + n_rows, 8, hipMemcpyDeviceToDevice, stream));
-    HC_TRY(exclusive_scan_i32_i64(n_seg, n_rows, pos_b, scan_tmp, stream));
-    HC_TRY(hipMemcpyAsync(totals_dev + 1, pos_b + n_rows, 8, hipMemcpyDeviceToDevice, stream));
-    HC_TRY(exclusive_scan_i32_i64(f_multi, n_rows, pos_c, scan_tmp, stream));
-    HC_TRY(hipMemcpyAsync(totals_dev + 2, pos_c + n_rows, 8, hipMemcpyDeviceToDevice, stream));
-    HC_TRY(exclusive_scan_i32_i64(n_slot, n_rows, pos_d, scan_tmp, stream));
-    HC_TRY(hipMemcpyAsync(totals_dev + 3, pos_d + n_rows, 8, hipMemcpyDeviceToDevice, stream));
-    HC_TRY(hipMemcpyAsync(h_tot, totals_dev, 5 * sizeof(int64_t), hipMemcpyDeviceToHost, stream));
-    HC_TRY(hipStreamSynchronize(stream));
-    p->nnz_long = h_tot[4];
-    p->n_short = (int32_t)h_tot[0];
-    p->n_segs = (int32_t)h_tot[1];
-    p->n_multi = (int32_t)h_tot[2];
-    p->n_slots = h_tot[3];
+    // rows the fused update finishes through the workspace
+    HC_TRY(launch_rest_flag(n_rows, p->rowptr, p->route, p->ncols, p->fused_mid_row, f_rest, stream));
+    {
+        // all row-level positions and counts in one pass and one read-back
+        ScanMulti m{};
+        m.k = 7;
+        m.in[0] = len_long; m.out[0] = nullptr;
+        m.in[1] = f_short;  m.out[1] = pos_a;
+        m.in[2] = n_seg;    m.out[2] = pos_b;
+        m.in[3] = f_multi;  m.out[3] = pos_c;
+        m.in[4] = n_slot;   m.out[4] = pos_d;
+        m.in[5] = f_mid;    m.out[5] = pos_e;
+        m.in[6] = f_rest;   m.out[6] = pos_f;
+        HC_TRY(exclusive_scan_multi(m, n_rows, totals_dev, scan_tmp, stream));
+        HC_TRY(hipMemcpyAsync(h_tot, totals_dev, 7 * sizeof(int64_t), hipMemcpyDeviceToHost, stream));
+        HC_TRY(hipStreamSynchronize(stream));
+    }
+    p->nnz_long = h_tot[0];
+    p->n_short = (int32_t)h_tot[1];
+    p->n_segs = (int32_t)h_tot[2];
+    p->n_multi = (int32_t)h_tot[3];
+    p->n_slots = h_tot[4];
+    p->n_mid = (int32_t)h_tot[5];
+    p->n_rest = (int32_t)h_tot[6];
     p->n_long_rows = (int32_t)(p->n_segs - p->n_slots + p->n_multi);   // single-segment rows + multi-segment rows
     HC_ALLOC(keep, p->segs, p->n_segs);
     HC_ALLOC(keep, p->multi, p->n_multi);
     if (p->n_segs > 0)
         HC_TRY(launch_build_segments(n_rows, p->rowptr, n_seg, pos_b, pos_c, pos_d, p->segs, p->multi, stream));
     // rows that get a whole wave
-    HC_TRY(exclusive_scan_i32_i64(f_mid, n_rows, pos_b, scan_tmp, stream));
-    {
-        int64_t h_mid = 0;
-        HC_TRY(hipMemcpyAsync(&h_mid, pos_b + n_rows, 8, hipMemcpyDeviceToHost, stream));
-        HC_TRY(hipStreamSynchronize(stream));
-        p->n_mid = (int32_t)h_mid;
-    }
     HC_ALLOC(keep, p->mid_rows, p->n_mid);
-    HC_TRY(launch_compact_ids(n_rows, f_mid, pos_b, p->mid_rows, stream));
+    HC_TRY(launch_compact_ids(n_rows, f_mid, pos_e, p->mid_rows, stream));
     // Walking every row and skipping the ones another kernel owns is cheaper than an index list
     // while most rows are short scalar-path rows; otherwise keep the explicit list.
     if ((int64_t)p->n_short * 2 < n_rows) {
@@ -476,20 +505,17 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     } else {
         p->short_rows = nullptr;
     }
-    // rows the fused update finishes through the workspace
-    {
-        int32_t* f_rest = f_multi;                               // free again after the segment tables
-        HC_TRY(launch_rest_flag(n_rows, p->rowptr, p->route, p->ncols, p->fused_mid_row, f_rest, stream));
-        HC_TRY(exclusive_scan_i32_i64(f_rest, n_rows, pos_c, scan_tmp, stream));
-        int64_t h_rest = 0;
-        HC_TRY(hipMemcpyAsync(&h_rest, pos_c + n_rows, 8, hipMemcpyDeviceToHost, stream));
-        HC_TRY(hipStreamSynchronize(stream));
-        p->n_rest = (int32_t)h_rest;
-        HC_ALLOC(keep, p->rest_rows, p->n_rest);
-        HC_TRY(launch_compact_ids(n_rows, f_rest, pos_c, p->rest_rows, stream));
-    }
+    HC_ALLOC(keep, p->rest_rows, p->n_rest);
+    HC_TRY(launch_compact_ids(n_rows, f_rest, pos_f, p->rest_rows, stream));
     HC_TRY(hipStreamSynchronize(stream));
     p->device_bytes = keep.bytes;
+    if (keep.ptrs.size() > sizeof p->chunks / sizeof p->chunks[0]) {
+        set_error("internal: too many plan chunks");
+        st = HCSPMM_EALLOC;
+        goto fail;
+    }
+    p->n_chunks = (int32_t)keep.ptrs.size();
+    for (size_t i = 0; i < keep.ptrs.size(); ++i) p->chunks[i] = keep.ptrs[i];
     tmp.free_all();
     return HCSPMM_OK;
 

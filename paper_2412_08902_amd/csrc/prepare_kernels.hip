@@ -134,6 +134,121 @@ hipError_t exclusive_scan_i32_i64(const int32_t* in, int64_t n, int64_t* out, in
 }
 
 // ------------------------------------------------------------------------------------------------
+// several arrays of one length scanned by one three-kernel sequence (the preprocessing is bound by
+// the number of its small launches and read-backs, not by their work)
+// ------------------------------------------------------------------------------------------------
+size_t scan_multi_scratch_elems(int64_t n) { return (size_t)kScanMaxArrays * scan_scratch_elems(n); }
+
+__global__ __launch_bounds__(kScanThreads) void k_scan_tile_sums_m(ScanMulti m, int64_t n, int64_t stride,
+                                                                   int64_t* __restrict__ tile_sums)
+{
+    __shared__ long long part[kScanThreads / 64];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile;
+    for (int a = 0; a < m.k; ++a) {
+        const int32_t* __restrict__ in = m.in[a];
+        long long acc = 0;
+        for (int i = 0; i < kScanItems; ++i) {
+            const int64_t idx = base + (int64_t)i * kScanThreads + threadIdx.x;
+            if (idx < n) acc += in[idx];
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
+        __syncthreads();                                        // part[] of the previous array has been read
+        if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            long long t = 0;
+            for (int i = 0; i < kScanThreads / 64; ++i) t += part[i];
+            tile_sums[a * stride + blockIdx.x] = t;
+        }
+    }
+}
+
+// workgroup a walks the tile sums of array a in order; totals[a] receives the array's sum
+__global__ __launch_bounds__(256) void k_scan_tile_offsets_m(int64_t* __restrict__ tile_sums_all, int64_t n_tiles,
+                                                             int64_t stride, int64_t* __restrict__ totals)
+{
+    __shared__ long long wsum[4];
+    __shared__ long long carry_s;
+    int64_t* __restrict__ tile_sums = tile_sums_all + blockIdx.x * stride;
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    for (int64_t base = 0; base < n_tiles; base += 256) {
+        const int64_t idx = base + threadIdx.x;
+        const long long v = idx < n_tiles ? tile_sums[idx] : 0;
+        long long inc = v;
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const long long t = __shfl_up(inc, off, 64);
+            if (lane >= off) inc += t;
+        }
+        if (lane == 63) wsum[wave] = inc;
+        __syncthreads();
+        long long wave_off = 0;
+        for (int i = 0; i < wave; ++i) wave_off += wsum[i];
+        const long long carry = carry_s;
+        if (idx < n_tiles) tile_sums[idx] = carry + wave_off + inc - v;
+        __syncthreads();
+        if (threadIdx.x == 255) carry_s = carry + wave_off + inc;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        tile_sums[n_tiles] = carry_s;
+        if (totals) totals[blockIdx.x] = carry_s;
+    }
+}
+
+__global__ __launch_bounds__(kScanThreads) void k_scan_apply_m(ScanMulti m, int64_t n, int64_t stride,
+                                                               const int64_t* __restrict__ tile_offsets_all,
+                                                               int64_t n_tiles)
+{
+    __shared__ int smem[kScanThreads / 64 + 1];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+    for (int a = 0; a < m.k; ++a) {
+        int64_t* __restrict__ out = m.out[a];
+        if (!out) continue;                                     // only the total of this array was wanted
+        const int32_t* __restrict__ in = m.in[a];
+        const int64_t* __restrict__ tile_offsets = tile_offsets_all + a * stride;
+        int v[kScanItems];
+        int local = 0;
+#pragma unroll
+        for (int i = 0; i < kScanItems; ++i) {
+            const int64_t idx = base + i;
+            v[i] = idx < n ? in[idx] : 0;
+            local += v[i];
+        }
+        int total;
+        const long long off = (long long)block_exclusive_scan<kScanThreads>(local, &total, smem);
+        long long run = tile_offsets[blockIdx.x] + off;
+#pragma unroll
+        for (int i = 0; i < kScanItems; ++i) {
+            const int64_t idx = base + i;
+            if (idx < n) out[idx] = run;
+            run += v[i];
+        }
+        if (blockIdx.x == 0 && threadIdx.x == 0) out[n] = tile_offsets[n_tiles];
+    }
+}
+
+hipError_t exclusive_scan_multi(const ScanMulti& m, int64_t n, int64_t* totals_dev, int64_t* scratch, hipStream_t stream)
+{
+    if (m.k < 1 || m.k > kScanMaxArrays) return hipErrorInvalidValue;
+    if (n <= 0) {
+        for (int a = 0; a < m.k; ++a)
+            if (m.out[a]) { hipError_t e = hipMemsetAsync(m.out[a], 0, sizeof(int64_t), stream); if (e != hipSuccess) return e; }
+        if (totals_dev) return hipMemsetAsync(totals_dev, 0, (size_t)m.k * sizeof(int64_t), stream);
+        return hipSuccess;
+    }
+    const int64_t n_tiles = (n + kScanTile - 1) / kScanTile;
+    const int64_t stride = (int64_t)scan_scratch_elems(n);
+    hipLaunchKernelGGL(k_scan_tile_sums_m, dim3((unsigned)n_tiles), dim3(kScanThreads), 0, stream, m, n, stride, scratch);
+    hipLaunchKernelGGL(k_scan_tile_offsets_m, dim3((unsigned)m.k), dim3(256), 0, stream, scratch, n_tiles, stride, totals_dev);
+    hipLaunchKernelGGL(k_scan_apply_m, dim3((unsigned)n_tiles), dim3(kScanThreads), 0, stream, m, n, stride, scratch, n_tiles);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
 // CSR validation
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_validate_rowptr(int32_t n_rows, int64_t nnz, const int32_t* __restrict__ rowptr,
