@@ -95,9 +95,18 @@ struct DevAlloc {
     {
         size_t sz = count * sizeof(T);
         if (sz == 0) sz = sizeof(T) < 16 ? 16 : sizeof(T);
-        if (chunk_min && !(arena && arena_used + padded(sz) <= arena_size)) {
-            const hipError_t e = reserve(padded(sz) > chunk_min ? padded(sz) : chunk_min);
+        if (chunk_min && 2 * padded(sz) < chunk_min && !(arena && arena_used + padded(sz) <= arena_size)) {
+            const hipError_t e = reserve(chunk_min);            // small arrays share chunks; large ones get their own allocation below
             if (e != hipSuccess) { *out = nullptr; return e; }
+        }
+        if (chunk_min && 2 * padded(sz) >= chunk_min) {
+            void* q = nullptr;
+            const hipError_t e = hipMalloc(&q, sz);
+            if (e != hipSuccess) { *out = nullptr; return e; }
+            ptrs.push_back(q);
+            bytes += (int64_t)sz;
+            *out = static_cast<T*>(q);
+            return hipSuccess;
         }
         if (arena && arena_used + padded(sz) <= arena_size) {
             *out = reinterpret_cast<T*>(arena + arena_used);
