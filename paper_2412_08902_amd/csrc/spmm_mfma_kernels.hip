@@ -54,7 +54,7 @@ template <int XK, int VW, int NG> struct Path;
 
 template <int VW, int NG> struct Path<0, VW, NG> {
     static constexpr int ES = 4;
-    static constexpr int SCOLS = (NG * VW >= 8) ? 16 : 32;
+    static constexpr int SCOLS = 16;
     static constexpr int U = SCOLS / 4;                        // K-steps (4 columns each) per stage
     struct Buf { float x[U][NG][VW]; };
     __device__ static inline int tidx(int k, int r) { return k * 16 + r; }
