@@ -373,6 +373,18 @@ def main():
                                           (stride, rows.shape[0], int(lens.sum()), cpu_s))
         out["parity_on_sample"] = ok
         log("cpu oracle: %.2f GFLOP/s on %d threads; GPU rows match oracle: %s" % (cpu_gflops, oracle.num_threads(), ok))
+        # the same oracle on one thread, on every 8th window of that sample
+        n_thr = oracle.num_threads()
+        sub = rows.reshape(-1, 16)[::8].reshape(-1) if rows.shape[0] % 16 == 0 and rows.shape[0] >= 128 else rows
+        try:
+            oracle.set_num_threads(1)
+            t1 = time.perf_counter()
+            oracle.spmm_rows(sub, g.rowptr, g.colind, g.vals, x_or, code)
+            one_s = time.perf_counter() - t1
+        finally:
+            oracle.set_num_threads(n_thr)
+        sub_nnz = float(np.diff(g.rowptr.astype(np.int64))[sub].sum())
+        out["cpu_baseline"]["one_thread_value"] = round(2.0 * sub_nnz * d / max(one_s, 1e-9) / 1e9, 3)
 
     print(json.dumps(out), flush=True)
 
