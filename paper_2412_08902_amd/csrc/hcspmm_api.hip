@@ -327,29 +327,14 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     HC_ALLOC(tmp, f_midw, (size_t)W + 1);
     HC_ALLOC(tmp, f_big, (size_t)W + 1);
     HC_ALLOC(tmp, nnz_if, (size_t)W + 1);
-    if (W > 0) {
-        HC_TRY(launch_select(W, p->ncols, p->nnzw, p->coef[0], p->coef[1], p->coef[2], p->opt.route_mode, p->route,
-                             f_mfma, f_csr, f_small, f_midw, f_big, nnz_if, stream));
-        if (p->opt.route_mode == HCSPMM_ROUTE_HYBRID) {
-            // launch guard: a path whose share cannot repay a kernel launch of its own joins the other path
-            int64_t on_matrix = 0;
-            HC_TRY(exclusive_scan_i32_i64(nnz_if, W, pos_a, scan_tmp, stream));
-            HC_TRY(hipMemcpyAsync(&on_matrix, pos_a + W, sizeof(int64_t), hipMemcpyDeviceToHost, stream));
-            HC_TRY(hipStreamSynchronize(stream));
-            const int64_t on_scalar = p->nnz - on_matrix;
-            int32_t forced = -1;
-            if (on_matrix > 0 && on_scalar > 0) {
-                if (on_matrix < kGuardNnz && kGuardShare * on_matrix < p->nnz) forced = HCSPMM_ROUTE_ALL_CSR;
-                else if (on_scalar < kGuardNnz && kGuardShare * on_scalar < p->nnz) forced = HCSPMM_ROUTE_ALL_MFMA;
-            }
-            if (forced >= 0)
-                HC_TRY(launch_select(W, p->ncols, p->nnzw, p->coef[0], p->coef[1], p->coef[2], forced, p->route,
-                                     f_mfma, f_csr, f_small, f_midw, f_big, nnz_if, stream));
-        }
-    }
-    {
-        // positions of every window in its lists, and the non-zeros on the matrix path: six scans in one pass,
-        // their totals in one read-back
+    // Selection, then the positions of every window in its lists and the non-zeros on the matrix path: six scans in
+    // one pass, their totals in one read-back.  Launch guard (hybrid mode): a path whose share cannot repay a kernel
+    // launch of its own joins the other path -- decided from the same totals, so only a plan that is actually merged
+    // pays a second selection pass.
+    for (int32_t mode = p->opt.route_mode, pass = 0;; ++pass) {
+        if (W > 0)
+            HC_TRY(launch_select(W, p->ncols, p->nnzw, p->coef[0], p->coef[1], p->coef[2], mode, p->route, f_mfma, f_csr,
+                                 f_small, f_midw, f_big, nnz_if, stream));
         ScanMulti m{};
         m.k = 6;
         m.in[0] = f_mfma;  m.out[0] = pos_a;
@@ -361,6 +346,16 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
         HC_TRY(exclusive_scan_multi(m, W, totals_dev, scan_tmp, stream));
         HC_TRY(hipMemcpyAsync(h_tot, totals_dev, 9 * sizeof(int64_t), hipMemcpyDeviceToHost, stream));
         HC_TRY(hipStreamSynchronize(stream));
+        if (pass == 0 && p->opt.route_mode == HCSPMM_ROUTE_HYBRID) {
+            const int64_t on_matrix = h_tot[5], on_scalar = p->nnz - on_matrix;
+            int32_t forced = -1;
+            if (on_matrix > 0 && on_scalar > 0) {
+                if (on_matrix < kGuardNnz && kGuardShare * on_matrix < p->nnz) forced = HCSPMM_ROUTE_ALL_CSR;
+                else if (on_scalar < kGuardNnz && kGuardShare * on_scalar < p->nnz) forced = HCSPMM_ROUTE_ALL_MFMA;
+            }
+            if (forced >= 0) { mode = forced; continue; }
+        }
+        break;
     }
     p->total_ncols = h_tot[8];
     p->n_mfma = (int32_t)h_tot[0];
