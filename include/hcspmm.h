@@ -14,6 +14,10 @@
  *     own disjoint output rows so nothing is merged      (Alg. 1-4, Eq. 1);
  *   - the GNN layer couples the aggregation with the dense update X W
  *                                                        (Section V-A, Eq. 1-2).
+ *   - the layer's backward pass aggregates the incoming gradient first and
+ *     then applies both products of the update          (Section V-A, Eq. 3-4);
+ *   - an offline vertex reordering raises the windows' computing intensity
+ *                                                        (Section V-B, Alg. 5/6).
  *
  * Conventions for every entry point
  *   - "device" pointers are HIP device pointers owned by the caller; "host"
