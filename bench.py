@@ -372,6 +372,8 @@ def main():
                                    sample="every %d-th 16-row window (%d rows, %d non-zeros), %.1f s" %
                                           (stride, rows.shape[0], int(lens.sum()), cpu_s))
         out["parity_on_sample"] = ok
+        # largest error relative to the componentwise magnitude bound |A| |X| (the gate is 1e-5, or 2e-2 for 16-bit X)
+        out["parity_max_err_over_bound"] = float(np.max(err / (bound + 1e-300)))
         log("cpu oracle: %.2f GFLOP/s on %d threads; GPU rows match oracle: %s" % (cpu_gflops, oracle.num_threads(), ok))
         # the same oracle on one thread, on every 8th window of that sample
         n_thr = oracle.num_threads()
