@@ -202,6 +202,33 @@ hcspmm_status hcspmm_spmm(const hcspmm_plan* plan, const void* d_X, int64_t ldx,
                           void* d_Y, int64_t ldy, int32_t y_dtype, void* stream);
 
 /*
+ * hcspmm_spmm for callers that must not allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same result bits as
+ * hcspmm_spmm; the difference is where the call's scratch lives (the partial rows of long rows cut
+ * into segments and the partial tiles of wide matrix-path windows cut into slices): not in buffers the
+ * plan allocates on first use, but in one fixed array of HCSPMM_STATIC_SCRATCH_BYTES that is part of the
+ * library's device image (every GPU the library runs on holds its own copy until the process ends).
+ * The call allocates and frees nothing, on the device or through any library.
+ *
+ *   HCSPMM_EUNSUPPORTED  when the plan needs more scratch at this d than the array holds
+ *                        (256-byte-padded 4*d*(segments of multi-segment rows) plus 64*d*(slices of
+ *                        multi-slice windows) bytes); nothing is launched then, use hcspmm_spmm
+ *   HCSPMM_EINVAL        also when the current device is not the plan's
+ *
+ * Every call on a GPU shares that GPU's array, across plans and streams: calls of this entry point that
+ * overlap in time on one GPU race on it and must be ordered by the caller (one stream, or events).
+ * Nothing in the array has to start at zero (every partial row and tile is written before it is
+ * read), so the previous call's contents need no clearing.
+ */
+#define HCSPMM_STATIC_SCRATCH_BYTES ((size_t)16 << 20)
+
+hcspmm_status hcspmm_spmm_noalloc(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d, int32_t x_dtype,
+                                  void* d_Y, int64_t ldy, int32_t y_dtype, void* stream);
+
+/* HCSPMM_STATIC_SCRATCH_BYTES as the loaded library was built with it. */
+size_t hcspmm_spmm_noalloc_scratch_limit(void);
+
+/*
  * Same as hcspmm_spmm, but brackets every kernel stage with HIP events on `stream`, waits for
  * completion and reports the elapsed milliseconds per stage (for benchmarks and profiling; the
  * stages run in this order).  A stage that launches nothing reports 0.

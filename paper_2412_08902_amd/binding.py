@@ -19,7 +19,7 @@ HCSPMM_ROUTE_HYBRID, HCSPMM_ROUTE_ALL_CSR, HCSPMM_ROUTE_ALL_MFMA, HCSPMM_ROUTE_P
 
 EXPORTED_SYMBOLS = [
     "hcspmm_default_options", "hcspmm_default_selector", "hcspmm_prepare", "hcspmm_plan_info",
-    "hcspmm_plan_export", "hcspmm_spmm", "hcspmm_spmm_timed", "hcspmm_gcn_layer", "hcspmm_gcn_layer_ex", "hcspmm_gcn_workspace_bytes",
+    "hcspmm_plan_export", "hcspmm_spmm", "hcspmm_spmm_noalloc", "hcspmm_spmm_noalloc_scratch_limit", "hcspmm_spmm_timed", "hcspmm_gcn_layer", "hcspmm_gcn_layer_ex", "hcspmm_gcn_workspace_bytes",
     "hcspmm_aggregate_update", "hcspmm_aggregate_update_workspace_bytes",
     "hcspmm_layer_backward", "hcspmm_layer_backward_workspace_bytes",
     "hcspmm_gemm_f32", "hcspmm_loa_order", "hcspmm_permute_csr", "hcspmm_transpose_csr", "hcspmm_plan_destroy", "hcspmm_status_string", "hcspmm_last_error", "hcspmm_version",
@@ -82,6 +82,10 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.hcspmm_plan_export.restype = ctypes.c_int
     lib.hcspmm_spmm.argtypes = [vp, vp, i64, i32, i32, vp, i64, i32, vp]
     lib.hcspmm_spmm.restype = ctypes.c_int
+    lib.hcspmm_spmm_noalloc.argtypes = [vp, vp, i64, i32, i32, vp, i64, i32, vp]
+    lib.hcspmm_spmm_noalloc.restype = ctypes.c_int
+    lib.hcspmm_spmm_noalloc_scratch_limit.argtypes = []
+    lib.hcspmm_spmm_noalloc_scratch_limit.restype = ctypes.c_size_t
     lib.hcspmm_spmm_timed.argtypes = [vp, vp, i64, i32, i32, vp, i64, i32, vp, ctypes.POINTER(HcspmmStageTimes)]
     lib.hcspmm_spmm_timed.restype = ctypes.c_int
     lib.hcspmm_gcn_layer.argtypes = [vp, vp, i64, i32, vp, i64, i32, vp, i64, i32, vp, ctypes.c_size_t, vp]
@@ -240,6 +244,20 @@ def hcspmm_spmm(plan: Plan, X, Y, *, d: Optional[int] = None, stream=None):
     _check(load_library().hcspmm_spmm(plan.handle, _ptr(X), X.stride(0), d, _dtype_code(X), _ptr(Y), Y.stride(0),
                                       _dtype_code(Y), _stream_ptr(stream)))
     return Y
+
+
+def hcspmm_spmm_noalloc(plan: Plan, X, Y, *, d: Optional[int] = None, stream=None):
+    """hcspmm_spmm with the call's scratch in the library's fixed device array (allocates nothing)."""
+    assert X.dim() == 2 and Y.dim() == 2 and X.stride(1) == 1 and Y.stride(1) == 1
+    if d is None:
+        d = X.shape[1]
+    _check(load_library().hcspmm_spmm_noalloc(plan.handle, _ptr(X), X.stride(0), d, _dtype_code(X), _ptr(Y),
+                                              Y.stride(0), _dtype_code(Y), _stream_ptr(stream)))
+    return Y
+
+
+def hcspmm_spmm_noalloc_scratch_limit() -> int:
+    return int(load_library().hcspmm_spmm_noalloc_scratch_limit())
 
 
 def hcspmm_spmm_timed(plan: Plan, X, Y, *, d: Optional[int] = None, stream=None) -> dict:

@@ -6,6 +6,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -530,13 +531,32 @@ fail:
     return st;
 }
 
+// Scratch of one SpMM call: partial rows of long rows cut into several segments, then partial tiles of
+// wide windows cut into several slices (each part padded to 256 bytes).
+static size_t spmm_scratch_bytes(const hcspmm_plan* p, int32_t d, size_t* tile_off)
+{
+    const size_t part = ((size_t)p->n_slots * (size_t)d * sizeof(float) + 255) & ~(size_t)255;
+    const size_t tiles = ((size_t)p->n_tile_slots * kH * (size_t)d * sizeof(float) + 255) & ~(size_t)255;
+    if (tile_off) *tile_off = part;
+    return part + tiles;
+}
+
 static hcspmm_status run_spmm(const hcspmm_plan* plan, const SpmmArgs& a, hipStream_t stream,
                               hipEvent_t* ev = nullptr /* 5 events when timing stages */,
-                              const UpdateArgs* upd = nullptr /* fuse the update stage where a tile stays on chip */)
+                              const UpdateArgs* upd = nullptr /* fuse the update stage where a tile stays on chip */,
+                              char* scratch_mem = nullptr /* device, spmm_scratch_bytes(): used instead of the plan's own lazily sized buffers */)
 {
     hcspmm_plan* p = const_cast<hcspmm_plan*>(plan);
+    float* partial = p->partial;
+    float* tile_partial = p->tile_partial;
+    if (scratch_mem) {
+        size_t tile_off = 0;
+        (void)spmm_scratch_bytes(p, a.d, &tile_off);
+        partial = reinterpret_cast<float*>(scratch_mem);
+        tile_partial = reinterpret_cast<float*>(scratch_mem + tile_off);
+    }
     // long rows cut into several segments need one partial row per segment
-    if (p->n_slots > 0 && p->partial_elems < p->n_slots * (int64_t)a.d) {
+    if (!scratch_mem && p->n_slots > 0 && p->partial_elems < p->n_slots * (int64_t)a.d) {
         if (p->partial) { HC_HIP(hipStreamSynchronize(stream)); (void)hipFree(p->partial); p->partial = nullptr; }
         const int64_t want = p->n_slots * (int64_t)a.d;
         if (hipMalloc((void**)&p->partial, (size_t)want * sizeof(float)) != hipSuccess) {
@@ -547,8 +567,9 @@ static hcspmm_status run_spmm(const hcspmm_plan* plan, const SpmmArgs& a, hipStr
             return HCSPMM_EALLOC;
         }
         p->partial_elems = want;
+        partial = p->partial;
     }
-    if (p->n_tile_slots > 0 && p->tile_partial_elems < p->n_tile_slots * kH * (int64_t)a.d) {
+    if (!scratch_mem && p->n_tile_slots > 0 && p->tile_partial_elems < p->n_tile_slots * kH * (int64_t)a.d) {
         if (p->tile_partial) { HC_HIP(hipStreamSynchronize(stream)); (void)hipFree(p->tile_partial); p->tile_partial = nullptr; }
         const int64_t want = p->n_tile_slots * kH * (int64_t)a.d;
         if (hipMalloc((void**)&p->tile_partial, (size_t)want * sizeof(float)) != hipSuccess) {
@@ -559,6 +580,7 @@ static hcspmm_status run_spmm(const hcspmm_plan* plan, const SpmmArgs& a, hipStr
             return HCSPMM_EALLOC;
         }
         p->tile_partial_elems = want;
+        tile_partial = p->tile_partial;
     }
     const bool has_wg = p->n_big_slices > 0 || p->n_mfma_mid > 0;
     const bool has_small = p->n_mfma_small > 0;
@@ -575,22 +597,22 @@ static hcspmm_status run_spmm(const hcspmm_plan* plan, const SpmmArgs& a, hipStr
     }
     if (ev) HC_HIP(hipEventRecord(ev[0], stream));
     HC_HIP(launch_mfma_wg(a, p->n_big_slices, p->big_slices, p->ncols, p->wptr, p->wcols, p->erc, p->rows_sorted,
-                          p->big_slice_rows, p->tile_partial, true, s_wg));
-    HC_HIP(launch_reduce_tiles(a, p->n_tile_multi, p->tile_multi, p->tile_partial, s_wg));
+                          p->big_slice_rows, tile_partial, true, s_wg));
+    HC_HIP(launch_reduce_tiles(a, p->n_tile_multi, p->tile_multi, tile_partial, s_wg));
     HC_HIP(launch_mfma_wg(a, p->n_mfma_mid, p->mid_slices, p->ncols, p->wptr, p->wcols, p->erc, p->rows_sorted,
-                          nullptr, p->tile_partial, false, s_wg));
+                          nullptr, tile_partial, false, s_wg));
     if (ev) HC_HIP(hipEventRecord(ev[1], stream));
     HC_HIP(launch_mfma_small(a, p->n_mfma_small, p->mfma_small_desc, p->wcols, p->erc, s_small, upd));
     if (ev) HC_HIP(hipEventRecord(ev[2], stream));
     if (upd)        // the fused launch walks every row: its tile tier also takes the shorter mid rows
-        HC_HIP(launch_csr(a, p->n_segs, p->segs, p->partial, p->n_mid, p->mid_rows, p->n_csr > 0 ? p->n_rows : 0, nullptr,
+        HC_HIP(launch_csr(a, p->n_segs, p->segs, partial, p->n_mid, p->mid_rows, p->n_csr > 0 ? p->n_rows : 0, nullptr,
                           p->route, p->fused_mid_row, stream, upd));
     else
-        HC_HIP(launch_csr(a, p->n_segs, p->segs, p->partial, p->n_mid, p->mid_rows,
+        HC_HIP(launch_csr(a, p->n_segs, p->segs, partial, p->n_mid, p->mid_rows,
                           p->short_rows ? p->n_short : (p->n_short > 0 ? p->n_rows : 0), p->short_rows, p->route,
                           p->mid_row, stream));
     if (ev) HC_HIP(hipEventRecord(ev[3], stream));
-    HC_HIP(launch_reduce_partials(a, p->n_multi, p->multi, p->partial, stream));
+    HC_HIP(launch_reduce_partials(a, p->n_multi, p->multi, partial, stream));
     if (ev) HC_HIP(hipEventRecord(ev[4], stream));
     if (s_wg != stream) {
         HC_HIP(hipEventRecord(p->ev_join[0], s_wg));
@@ -608,6 +630,34 @@ static hcspmm_status run_spmm(const hcspmm_plan* plan, const SpmmArgs& a, hipStr
 }  // namespace hcspmm
 
 using namespace hcspmm;
+
+// ---- scratch of the entry point that allocates nothing ------------------------------------------
+// One array per GPU, part of the library's device image: it exists from the moment the library is loaded
+// on a device until the process ends.  `scratch` itself is only the host-side handle of the symbol; the
+// array's device address is looked up once per device and kept in g_scratch_ptr.
+constexpr size_t kStaticScratchBytes = HCSPMM_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static char* g_scratch_ptr[kMaxDevices] = {};
+
+// device address of the current GPU's copy of the array; the current device must be the plan's
+static hcspmm_status static_scratch_ptr(const hcspmm_plan* plan, char** out)
+{
+    int dev = -1;
+    HC_HIP(hipGetDevice(&dev));
+    if (dev != plan->device) { set_error("the current device (%d) is not the plan's (%d)", dev, plan->device); return HCSPMM_EINVAL; }
+    if (dev < 0 || dev >= kMaxDevices) { set_error("device index %d is beyond the %d devices supported", dev, kMaxDevices); return HCSPMM_EUNSUPPORTED; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        HC_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) { set_error("hipGetSymbolAddress returned no address for the static scratch array"); return HCSPMM_EHIP; }
+        g_scratch_ptr[dev] = static_cast<char*>(ptr);
+    }
+    *out = g_scratch_ptr[dev];
+    return HCSPMM_OK;
+}
 
 extern "C" {
 
@@ -680,6 +730,12 @@ hcspmm_status hcspmm_prepare(int32_t n_rows, int32_t n_cols, int64_t nnz, const 
         lookup_selector(o.mfma_dtype, o.d_hint, nnz, p->coef);
     }
     if (hipGetDevice(&p->device) != hipSuccess) { (void)hipGetLastError(); delete p; set_error("hipGetDevice failed"); return HCSPMM_EHIP; }
+    {
+        // set-up of hcspmm_spmm_noalloc: this device's address of the static scratch array, looked up once per device
+        char* unused = nullptr;
+        const hcspmm_status st0 = static_scratch_ptr(p, &unused);
+        if (st0 != HCSPMM_OK) { delete p; return st0; }
+    }
     hcspmm_status st = build_plan(p, static_cast<hipStream_t>(stream));
     if (st != HCSPMM_OK) { delete p; return st; }
     // side streams (default priority) and events for running the paths side by side; optional
@@ -751,7 +807,8 @@ static hcspmm_status check_dense(const char* name, const void* ptr, int64_t ld, 
 }
 
 static hcspmm_status spmm_impl(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d, int32_t x_dtype,
-                               void* d_Y, int64_t ldy, int32_t y_dtype, void* stream, hipEvent_t* ev);
+                               void* d_Y, int64_t ldy, int32_t y_dtype, void* stream, hipEvent_t* ev,
+                               bool static_scratch = false);
 
 hcspmm_status hcspmm_spmm(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d, int32_t x_dtype, void* d_Y,
                           int64_t ldy, int32_t y_dtype, void* stream)
@@ -783,7 +840,7 @@ hcspmm_status hcspmm_spmm_timed(const hcspmm_plan* plan, const void* d_X, int64_
 }
 
 static hcspmm_status spmm_impl(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d, int32_t x_dtype,
-                               void* d_Y, int64_t ldy, int32_t y_dtype, void* stream, hipEvent_t* ev)
+                               void* d_Y, int64_t ldy, int32_t y_dtype, void* stream, hipEvent_t* ev, bool static_scratch)
 {
     if (!plan) { set_error("plan is NULL"); return HCSPMM_EINVAL; }
     if (d < 1 || d > (1 << 20)) { set_error("d must be in [1, 2^20]"); return HCSPMM_EINVAL; }
@@ -800,8 +857,26 @@ static hcspmm_status spmm_impl(const hcspmm_plan* plan, const void* d_X, int64_t
         set_error("16-bit X on the matrix path needs d, ldx and ldy to be multiples of 4 and 8-byte aligned X, 16-byte aligned Y");
         return HCSPMM_EUNSUPPORTED;
     }
-    return run_spmm(plan, a, static_cast<hipStream_t>(stream), ev);
+    char* scratch_mem = nullptr;
+    if (static_scratch) {
+        const size_t need = spmm_scratch_bytes(plan, d, nullptr);
+        if (need > kStaticScratchBytes) {
+            set_error("this plan needs %zu bytes of scratch at d = %d, the static scratch array holds %zu; use hcspmm_spmm",
+                      need, d, kStaticScratchBytes);
+            return HCSPMM_EUNSUPPORTED;
+        }
+        if ((st = static_scratch_ptr(plan, &scratch_mem)) != HCSPMM_OK) return st;
+    }
+    return run_spmm(plan, a, static_cast<hipStream_t>(stream), ev, nullptr, scratch_mem);
 }
+
+hcspmm_status hcspmm_spmm_noalloc(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d, int32_t x_dtype,
+                                  void* d_Y, int64_t ldy, int32_t y_dtype, void* stream)
+{
+    return spmm_impl(plan, d_X, ldx, d, x_dtype, d_Y, ldy, y_dtype, stream, nullptr, true);
+}
+
+size_t hcspmm_spmm_noalloc_scratch_limit(void) { return kStaticScratchBytes; }
 
 size_t hcspmm_gcn_workspace_bytes(const hcspmm_plan* plan, int32_t d_in, int32_t d_out)
 {
