@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the hybrid SpMM hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--modes] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--no-modes] [--no-cold] [--no-cpu]
 
 One "step" is one `hcspmm_spmm` call (Y = A X on the hybrid plan: every window goes through the
 path its selector flag names) on the named synthetic workload, with the CSR, X, Y and the plan
@@ -12,8 +12,11 @@ Prints ONE JSON line:
   metric/value   SpMM GFLOP/s = 2 nnz d / t over the K timed steps
   roofline       dominant kernel of the step: algorithmic HBM bytes of its share of the work
                  divided by its average duration (HIP events on the launch stream), vs 8 TB/s
+                 (plus gather_floor_ms / gather_ceiling_frac: the bare gather of X rows along the same column
+                 stream, the floor of any kernel that fetches one row per non-zero, and the step relative to it)
+  t_cold_ms      median time of a step with cold caches (512 MiB flush before every repetition)
+  modes          the same workload on the all-CSR and all-MFMA plans, next to the hybrid plan
   cpu_baseline   the CPU oracle (plain CSR triple loop, fp64) timed on this machine's host cores
-With --modes the JSON also carries the all-CSR and all-MFMA timings of the same workload.
 """
 import argparse
 import json
@@ -27,14 +30,14 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM-side bytes per launch of the dominant kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
-# summarised under profiles/ (each counter scaled by what it reads for a 1 GiB copy kernel in the
-# same run).  Keyed by (workload, kernel, X dtype); None where no counter run exists for the triple.
-MEASURED_TRAFFIC_BYTES = {
-    ("C4", "k_csr", "f32"): 15.14e9 + 0.314e9,      # profiles/k_csr_C4_large_powerlaw.md
-    ("C5", "k_mfma_wg", "f32"): 34.58e9 + 0.090e9,  # profiles/k_mfma_wg_C5_dense_powerlaw.md
-    ("C2", "k_csr", "f32"): 0.735e9 + 0.087e9,      # profiles/k_csr_C2_C3.md
-    ("C3", "k_csr", "f32"): 0.176e9 + 0.034e9,      # profiles/k_csr_C2_C3.md
+# rocprofv3 summaries of the dominant kernel per workload (HBM-side bytes per launch from FETCH_SIZE / WRITE_SIZE runs,
+# each with the full command that produced it).  Counters cannot be read from inside this process, so the bench line
+# carries "traffic": null and names the summary instead.
+TRAFFIC_PROFILE = {
+    ("C4", "k_csr"): "profiles/k_csr_C4_large_powerlaw.md",
+    ("C5", "k_mfma_wg"): "profiles/k_mfma_wg_C5_dense_powerlaw.md",
+    ("C2", "k_csr"): "profiles/k_csr_C2_C3.md",
+    ("C3", "k_csr"): "profiles/k_csr_C2_C3.md",
 }
 
 WORKLOAD_TEXT = {
@@ -64,12 +67,16 @@ def time_steps(fn, steps, warmup, torch):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="C4", choices=sorted(WORKLOAD_TEXT))
-    ap.add_argument("--modes", action="store_true", help="also time the all-CSR and all-MFMA plans")
+    ap.add_argument("--modes", action="store_true", help="(default; kept for old command lines) time the all-CSR and all-MFMA plans too")
+    ap.add_argument("--no-modes", action="store_true", help="skip the all-CSR and all-MFMA plans")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--cold", action="store_true", help="also report cold-cache time (512 MiB flush between reps)")
+    ap.add_argument("--no-cold", action="store_true", help="skip the cold-cache timing (512 MiB flush before every repetition)")
+    ap.add_argument("--no-gather-probe", action="store_true", help="skip the bare-gather floor of the scalar path")
+    ap.add_argument("--gather-ceiling", action="store_true",
+                    help="also time the bare gather on uniform indices and on the hub / cold bands of the column stream")
     ap.add_argument("--x-dtype", default="f32", choices=["f32", "bf16", "f16"], help="storage type of X")
     ap.add_argument("--layer", action="store_true",
                     help="C5 only: time the whole GCN layer Y = ReLU(A (X W)) (GEMM + hybrid SpMM) instead of the SpMM")
@@ -189,7 +196,8 @@ def main():
     achieved = alg_bytes / (stage_ms[dom] * 1e-3) / 1e9
     whole_bytes = 4.0 * (g.n_rows + 1) + 8.0 * g.nnz + g.n_cols * d * sx + g.n_rows * d * 4.0
     roofline = dict(bound="hbm", kernel=s["kernel"], achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=MEASURED_TRAFFIC_BYTES.get((name, s["kernel"], args.x_dtype)),
+                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
+                    traffic_profile=TRAFFIC_PROFILE.get((name, s["kernel"])),
                     algorithmic_bytes=int(alg_bytes), kernel_ms=round(stage_ms[dom], 5),
                     whole_step_frac=round(whole_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4))
 
@@ -265,18 +273,18 @@ def main():
         Zt = torch.empty((g.n_rows, d), dtype=torch.float32, device=dev)
         ms_fused = time_steps(lambda: hc.hcspmm_aggregate_update(plan, Xd, Wd, Y2, ws), args.steps, args.warmup, torch)
         Y_fused = Y2.clone()
-        os.environ["HCSPMM_TUNE_NO_FUSE"] = "1"
+        hc.hcspmm_plan_set_update_fusion(plan, hc.HCSPMM_UPDATE_SPLIT)
         ms_split = time_steps(lambda: hc.hcspmm_aggregate_update(plan, Xd, Wd, Y2, ws), args.steps, args.warmup, torch)
-        del os.environ["HCSPMM_TUNE_NO_FUSE"]
+        hc.hcspmm_plan_set_update_fusion(plan, hc.HCSPMM_UPDATE_AUTO)
         ms_gemm = time_steps(lambda: hc.hcspmm_gemm_f32(Zt, Wd, Y2), args.steps, args.warmup, torch)
         out["aggregate_update"] = dict(d_in=d, d_out=d_out, ms_fused=round(ms_fused, 5), ms_spmm_then_gemm=round(ms_split, 5),
                                        ms_gemm_alone=round(ms_gemm, 5), ms_spmm_alone=round(ms, 5),
                                        max_abs_diff_fused_vs_split=float((Y_fused - Y2).abs().max().item()) if False else None)
         hc.hcspmm_aggregate_update(plan, Xd, Wd, Y2, ws)
-        os.environ["HCSPMM_TUNE_NO_FUSE"] = "1"
+        hc.hcspmm_plan_set_update_fusion(plan, hc.HCSPMM_UPDATE_SPLIT)
         Y3 = torch.empty_like(Y2)
         hc.hcspmm_aggregate_update(plan, Xd, Wd, Y3, ws)
-        del os.environ["HCSPMM_TUNE_NO_FUSE"]
+        hc.hcspmm_plan_set_update_fusion(plan, hc.HCSPMM_UPDATE_AUTO)
         torch.cuda.synchronize()
         out["aggregate_update"]["max_abs_diff_fused_vs_split"] = float((Y2 - Y3).abs().max().item())
         log("aggregate-update: fused %.4f ms, spmm+gemm %.4f ms (gemm alone %.4f)" % (ms_fused, ms_split, ms_gemm))
@@ -299,9 +307,9 @@ def main():
         ms_b_emask = time_steps(lambda: bw(mask_dx_by_x=True), args.steps, args.warmup, torch)
         ms_dx = time_steps(lambda: hc.hcspmm_layer_backward(plan, Gb, Xb, Wb, dXb, None, wsb), args.steps, args.warmup, torch)
         ms_dw = time_steps(lambda: hc.hcspmm_layer_backward(plan, Gb, Xb, Wb, None, dWb, wsb), args.steps, args.warmup, torch)
-        os.environ["HCSPMM_TUNE_NO_FUSE"] = "1"
+        hc.hcspmm_plan_set_update_fusion(plan, hc.HCSPMM_UPDATE_SPLIT)
         ms_b_split = time_steps(lambda: bw(), args.steps, args.warmup, torch)
-        del os.environ["HCSPMM_TUNE_NO_FUSE"]
+        hc.hcspmm_plan_set_update_fusion(plan, hc.HCSPMM_UPDATE_AUTO)
         out["layer_backward"] = dict(d_in=d_in, d_out=d, ms=round(ms_b, 5), ms_with_activation_mask=round(ms_b_mask, 5),
                                      ms_with_dx_masked_in_epilogue=round(ms_b_emask, 5),
                                      ms_unfused=round(ms_b_split, 5), ms_dx_only=round(ms_dx, 5), ms_dw_only=round(ms_dw, 5),
@@ -311,19 +319,52 @@ def main():
             "the epilogue %.4f; spmm alone %.4f)" % (ms_b, ms_b_split, ms_dx, ms_dw, ms_b_mask, ms_b_emask, ms))
         del Wb, Xb, Yf, wsb, dXb, dWb
 
-    if args.cold:
+    if not args.no_cold:
+        # cold caches: a 512 MiB write between repetitions evicts the L2s and the memory-side cache
         flush = torch.empty(512 << 20, dtype=torch.uint8, device=dev)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         ts = []
-        for _ in range(min(args.steps, 20)):
+        for _ in range(min(args.steps, 100)):
             flush.fill_(1)
             e0.record()
             hc.hcspmm_spmm(plan, Xd, Yd)
             e1.record()
             torch.cuda.synchronize()
             ts.append(e0.elapsed_time(e1))
-        out["cold_ms"] = round(float(np.median(ts)), 5)
+        out["t_cold_ms"] = round(float(np.median(ts)), 5)
+        out["t_cold_reps"] = len(ts)
+        roofline["whole_step_frac_cold"] = round(whole_bytes / (out["t_cold_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
         del flush
+
+    if not args.no_gather_probe and args.x_dtype == "f32" and d % 4 == 0 and d <= 256:
+        # Floor of the scalar path: the bare gather of X rows along the same column stream (no row structure, no
+        # values, no output).  A kernel that fetches one X row per non-zero cannot run faster than this.
+        def probe_ms(index, reps):
+            buf = torch.empty(hc.hcspmm_probe_gather_out_bytes(index.numel(), d), dtype=torch.uint8, device=dev)
+            return time_steps(lambda: hc.hcspmm_probe_gather(index, Xd, buf, d=d), reps, 3, torch)
+        reps = max(5, min(args.steps, 20))
+        g_ms = probe_ms(ci, reps)
+        roofline["gather_floor_ms"] = round(g_ms, 5)
+        # what the whole step achieves relative to that floor (1.0 = the memory system's rate for this access pattern)
+        roofline["gather_ceiling_frac"] = round(g_ms / ms, 4)
+        log("bare gather of the column stream: %.3f ms (%.2f TB/s of X rows); hybrid step = %.3f of that rate" %
+            (g_ms, g.nnz * d * 4 / (g_ms * 1e-3) / 1e12, g_ms / ms))
+        if args.gather_ceiling:
+            gen = torch.Generator(device=dev)
+            gen.manual_seed(99)
+            uni = torch.randint(0, g.n_cols, (g.nnz,), dtype=torch.int32, device=dev, generator=gen)
+            res = {"column_stream_ms": round(g_ms, 5), "uniform_ms": round(probe_ms(uni, reps), 5)}
+            del uni
+            for band in (4096, 32768, 262144):
+                if band >= g.n_cols:
+                    continue
+                hot = ci[ci < band]
+                cold = ci[ci >= band]
+                res["band_%d" % band] = dict(hot_share=round(hot.numel() / g.nnz, 4), hot_ms=round(probe_ms(hot, reps), 5),
+                                             cold_ms=round(probe_ms(cold, reps), 5))
+                del hot, cold
+            out["gather_ceiling"] = res
+            log("gather ceiling: %s" % res)
 
     plan.destroy()
 
@@ -336,7 +377,7 @@ def main():
         out["calib_copy_bytes"] = int(src.numel() * 4)
         del src, dst
 
-    if args.modes:
+    if not args.no_modes:
         modes = {}
         for label, mode in (("all_csr", hc.HCSPMM_ROUTE_ALL_CSR), ("all_mfma", hc.HCSPMM_ROUTE_ALL_MFMA)):
             p2, pm = prepare(mode)

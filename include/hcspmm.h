@@ -73,6 +73,10 @@ typedef enum {
     HCSPMM_ROUTE_HYBRID = 0, HCSPMM_ROUTE_ALL_CSR = 1, HCSPMM_ROUTE_ALL_MFMA = 2, HCSPMM_ROUTE_PER_WINDOW = 3
 } hcspmm_route_mode;
 
+/* Update stage of the aggregate-then-update layer and of the backward pass: AUTO lets the library pick the faster
+ * route for the shape, FUSED takes the fused kernels whenever the shape allows them, SPLIT never does. */
+typedef enum { HCSPMM_UPDATE_AUTO = 0, HCSPMM_UPDATE_FUSED = 1, HCSPMM_UPDATE_SPLIT = 2 } hcspmm_update_fusion;
+
 /*
  * Options of hcspmm_prepare.  Fill with hcspmm_default_options() first.
  *
@@ -95,6 +99,9 @@ typedef struct {
     int32_t d_hint;               /* dense width the plan will mostly be used with (selects default coefficients); 0 = 64 */
     int32_t use_custom_selector;  /* 0: shipped coefficients for (mfma_dtype, d_hint); 1: sel_coef below */
     int64_t sel_coef[3];
+    int32_t update_fusion;        /* hcspmm_update_fusion: how hcspmm_aggregate_update / hcspmm_layer_backward on this plan
+                                     choose between the fused update stage and SpMM + GEMM (for tests and measurements) */
+    int32_t reserved;             /* must be 0 */
 } hcspmm_options;
 
 void hcspmm_default_options(hcspmm_options* opt /* host, out */);
@@ -388,6 +395,27 @@ hcspmm_status hcspmm_permute_csr(int32_t n, const int32_t* h_rowptr, const int32
 hcspmm_status hcspmm_transpose_csr(int32_t n_rows, int32_t n_cols, const int32_t* h_rowptr, const int32_t* h_colind,
                                    const float* h_vals, int32_t* h_out_rowptr, int32_t* h_out_colind,
                                    float* h_out_vals);
+
+/*
+ * Measurement aid (no part of the method): the bare gather behind the scalar path of Alg. 1/3.  Reads
+ * row d_index[i] of X for i = 0 .. n-1, in that order of the stream, with the scalar path's lane mapping
+ * and eight row requests in flight per lane group, and does nothing else -- no row structure, no
+ * values, no output rows.  Its duration is a floor for every kernel that fetches one X row per
+ * non-zero of the same index stream (d_index = the CSR column array); bench.py reports the scalar
+ * kernel against it.
+ *
+ *   d_index  device, int32[n]; values are clamped into [0, n_rows_x) before use
+ *   d_X      device, n_rows_x x d fp32, ldx >= d; d a multiple of 4 in [4, 256], rows 16-byte aligned
+ *   d_out    device, at least hcspmm_probe_gather_out_bytes(n, d) bytes, 16-byte aligned; receives
+ *            per-lane sums of what was read (keeps the loads live; the values carry no meaning)
+ * Asynchronous on `stream`.
+ */
+hcspmm_status hcspmm_probe_gather(const int32_t* d_index, int64_t n, const float* d_X, int64_t ldx, int32_t d,
+                                  int32_t n_rows_x, float* d_out, size_t out_bytes, void* stream);
+size_t hcspmm_probe_gather_out_bytes(int64_t n, int32_t d);
+
+/* Changes options.update_fusion of an existing plan (hcspmm_update_fusion); calls already enqueued are not affected. */
+hcspmm_status hcspmm_plan_set_update_fusion(hcspmm_plan* plan, int32_t update_fusion);
 
 /* Frees everything the plan owns (not the borrowed CSR).  NULL is allowed. */
 void hcspmm_plan_destroy(hcspmm_plan* plan);

@@ -16,20 +16,21 @@ from ._build import LIB_PATH, build_library
 HCSPMM_OK, HCSPMM_EINVAL, HCSPMM_EBADCSR, HCSPMM_EALLOC, HCSPMM_EHIP, HCSPMM_EUNSUPPORTED = range(6)
 HCSPMM_F32, HCSPMM_BF16, HCSPMM_F16 = 0, 1, 2
 HCSPMM_ROUTE_HYBRID, HCSPMM_ROUTE_ALL_CSR, HCSPMM_ROUTE_ALL_MFMA, HCSPMM_ROUTE_PER_WINDOW = 0, 1, 2, 3
+HCSPMM_UPDATE_AUTO, HCSPMM_UPDATE_FUSED, HCSPMM_UPDATE_SPLIT = 0, 1, 2
 
 EXPORTED_SYMBOLS = [
     "hcspmm_default_options", "hcspmm_default_selector", "hcspmm_prepare", "hcspmm_plan_info",
     "hcspmm_plan_export", "hcspmm_spmm", "hcspmm_spmm_noalloc", "hcspmm_spmm_noalloc_scratch_limit", "hcspmm_spmm_timed", "hcspmm_gcn_layer", "hcspmm_gcn_layer_ex", "hcspmm_gcn_workspace_bytes",
     "hcspmm_aggregate_update", "hcspmm_aggregate_update_workspace_bytes",
     "hcspmm_layer_backward", "hcspmm_layer_backward_workspace_bytes",
-    "hcspmm_gemm_f32", "hcspmm_loa_order", "hcspmm_permute_csr", "hcspmm_transpose_csr", "hcspmm_plan_destroy", "hcspmm_status_string", "hcspmm_last_error", "hcspmm_version",
+    "hcspmm_gemm_f32", "hcspmm_plan_set_update_fusion", "hcspmm_probe_gather", "hcspmm_probe_gather_out_bytes", "hcspmm_loa_order", "hcspmm_permute_csr", "hcspmm_transpose_csr", "hcspmm_plan_destroy", "hcspmm_status_string", "hcspmm_last_error", "hcspmm_version",
 ]
 
 
 class HcspmmOptions(ctypes.Structure):
     _fields_ = [("struct_size", ctypes.c_int32), ("window_rows", ctypes.c_int32), ("route_mode", ctypes.c_int32),
                 ("mfma_dtype", ctypes.c_int32), ("d_hint", ctypes.c_int32), ("use_custom_selector", ctypes.c_int32),
-                ("sel_coef", ctypes.c_int64 * 3)]
+                ("sel_coef", ctypes.c_int64 * 3), ("update_fusion", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class HcspmmPlanInfo(ctypes.Structure):
@@ -111,6 +112,12 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.hcspmm_transpose_csr.restype = ctypes.c_int
     lib.hcspmm_gemm_f32.argtypes = [i64, i32, i32, vp, i64, vp, i64, vp, i64, vp]
     lib.hcspmm_gemm_f32.restype = ctypes.c_int
+    lib.hcspmm_probe_gather.argtypes = [vp, i64, vp, i64, i32, i32, vp, ctypes.c_size_t, vp]
+    lib.hcspmm_probe_gather.restype = ctypes.c_int
+    lib.hcspmm_probe_gather_out_bytes.argtypes = [i64, i32]
+    lib.hcspmm_probe_gather_out_bytes.restype = ctypes.c_size_t
+    lib.hcspmm_plan_set_update_fusion.argtypes = [vp, i32]
+    lib.hcspmm_plan_set_update_fusion.restype = ctypes.c_int
     lib.hcspmm_plan_destroy.argtypes = [vp]
     lib.hcspmm_plan_destroy.restype = None
     lib.hcspmm_status_string.argtypes = [ctypes.c_int]
@@ -190,11 +197,11 @@ class Plan:
 
 def hcspmm_prepare(n_rows: int, n_cols: int, rowptr, colind, vals, *, route_mode: int = HCSPMM_ROUTE_HYBRID,
                    mfma_dtype: int = HCSPMM_F32, d_hint: int = 0, sel_coef: Optional[Sequence[int]] = None,
-                   stream=None, nnz: Optional[int] = None) -> Plan:
+                   stream=None, nnz: Optional[int] = None, update_fusion: int = HCSPMM_UPDATE_AUTO) -> Plan:
     """rowptr/colind: int32 CUDA tensors, vals: float32 CUDA tensor (borrowed by the plan)."""
     lib = load_library()
     o = hcspmm_default_options()
-    o.route_mode, o.mfma_dtype, o.d_hint = route_mode, mfma_dtype, d_hint
+    o.route_mode, o.mfma_dtype, o.d_hint, o.update_fusion = route_mode, mfma_dtype, d_hint, update_fusion
     if sel_coef is not None:
         o.use_custom_selector = 1
         for i in range(3):
@@ -205,6 +212,23 @@ def hcspmm_prepare(n_rows: int, n_cols: int, rowptr, colind, vals, *, route_mode
     _check(lib.hcspmm_prepare(n_rows, n_cols, nnz, _ptr(rowptr), _ptr(colind), _ptr(vals), ctypes.byref(o),
                               _stream_ptr(stream), ctypes.byref(out)))
     return Plan(out, rowptr, colind, vals)
+
+
+def hcspmm_probe_gather_out_bytes(n: int, d: int) -> int:
+    return int(load_library().hcspmm_probe_gather_out_bytes(n, d))
+
+
+def hcspmm_probe_gather(index, X, out, *, d: Optional[int] = None, stream=None):
+    """Bare gather of the rows X[index[i]] (measurement aid); index int32 CUDA tensor, out a CUDA buffer."""
+    assert X.dim() == 2 and X.stride(1) == 1
+    if d is None:
+        d = X.shape[1]
+    _check(load_library().hcspmm_probe_gather(_ptr(index), index.numel(), _ptr(X), X.stride(0), d, X.shape[0], _ptr(out),
+                                              out.numel() * out.element_size(), _stream_ptr(stream)))
+
+
+def hcspmm_plan_set_update_fusion(plan: Plan, update_fusion: int):
+    _check(load_library().hcspmm_plan_set_update_fusion(plan.handle, update_fusion))
 
 
 def hcspmm_plan_info(plan: Plan) -> dict:

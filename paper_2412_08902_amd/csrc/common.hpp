@@ -45,6 +45,13 @@ struct WinDesc { int32_t w, s, e, nc; int64_t wp; int64_t pad; };
 
 void set_error(const char* fmt, ...);
 
+// Experiment knobs (HCSPMM_TUNE_* environment variables; not part of the ABI), read ONCE per process on first use.
+// A value of -1 means "not set": the built-in choice applies.
+struct Tune {
+    int mid_row, long_row, slice_cols, serial, xcd_chunk, rpg, tiles_per_wave, no_rows16;
+};
+const Tune& tune();
+
 #define HC_HIP(call)                                                                               \
     do {                                                                                           \
         hipError_t e_ = (call);                                                                    \
@@ -165,6 +172,10 @@ hipError_t launch_mfma_wg(const SpmmArgs& a, int32_t n_list, const WgSlice* slic
                           const int32_t* slice_rows, float* tile_partial, bool wide, hipStream_t s);
 hipError_t launch_slice_rows(int32_t n_slices, const WgSlice* slices, int32_t n_rows, const int32_t* rowptr,
                              const int32_t* erc, int32_t* slice_rows, hipStream_t s);
+// bare gather of X rows by an index stream (measurement aid)
+int64_t probe_gather_blocks(int64_t n, int32_t d);
+hipError_t launch_probe_gather(const int32_t* index, int64_t n, const float* X, int64_t ldx, int32_t d, int32_t n_rows_x,
+                               float* out, hipStream_t s);
 bool mfma_shape_supported(const SpmmArgs& a);
 hipError_t launch_reduce_tiles(const SpmmArgs& a, int32_t n_multi, const MultiRow* multi, const float* tile_partial,
                                hipStream_t s);

@@ -22,6 +22,20 @@ void set_error(const char* fmt, ...)
     va_end(ap);
 }
 
+static int env_int(const char* name)
+{
+    const char* v = getenv(name);
+    return v ? atoi(v) : -1;
+}
+
+const Tune& tune()
+{
+    static const Tune t = {env_int("HCSPMM_TUNE_MID_ROW"), env_int("HCSPMM_TUNE_LONG_ROW"), env_int("HCSPMM_TUNE_SLICE_COLS"),
+                           getenv("HCSPMM_TUNE_SERIAL") ? 1 : 0, env_int("HCSPMM_TUNE_XCD_CHUNK"), env_int("HCSPMM_TUNE_RPG"),
+                           env_int("HCSPMM_TUNE_TILES_PER_WAVE"), getenv("HCSPMM_TUNE_NO_ROWS16") ? 1 : 0};
+    return t;
+}
+
 // Shipped selector coefficients (w1, w2, b) x 2^20 of  z = w1*ncols + w2*sparsity + b  (Section
 // IV-C form; route = matrix path iff z < 0), one row per (precision, dense-width bucket).  Fitted
 // on MI355X with the procedure of Section IV-C (synthetic 16-row windows, both deployed kernels
@@ -426,7 +440,7 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
         // Wide windows are cut into slices only as far as parallelism needs it (a slice loses the
         // alignment of concurrently running windows on the same hot low-numbered columns): aim
         // at ~4 workgroups per CU over the summed width of the wide windows.
-        if (!getenv("HCSPMM_TUNE_SLICE_COLS") && p->n_mfma_big > 0) {
+        if (tune().slice_cols < 0 && p->n_mfma_big > 0) {
             HC_TRY(exclusive_scan_i32_i64(nnz_if, W, pos_a, scan_tmp, stream));     // nnz_if holds ncols of wide windows here
             int64_t wide_cols = 0;
             HC_TRY(hipMemcpyAsync(&wide_cols, pos_a + W, 8, hipMemcpyDeviceToHost, stream));
@@ -701,6 +715,8 @@ hcspmm_status hcspmm_prepare(int32_t n_rows, int32_t n_cols, int64_t nnz, const 
     if (o.route_mode < 0 || o.route_mode > 3) { set_error("bad route_mode"); return HCSPMM_EINVAL; }
     if (o.mfma_dtype < 0 || o.mfma_dtype > 2) { set_error("bad mfma_dtype"); return HCSPMM_EINVAL; }
     if (o.d_hint < 0) { set_error("bad d_hint"); return HCSPMM_EINVAL; }
+    if (o.update_fusion < 0 || o.update_fusion > 2) { set_error("bad update_fusion"); return HCSPMM_EINVAL; }
+    if (o.reserved != 0) { set_error("options.reserved must be 0"); return HCSPMM_EINVAL; }
     hcspmm_plan* p = new (std::nothrow) hcspmm_plan();
     if (!p) { set_error("host allocation failed"); return HCSPMM_EALLOC; }
     memset(p, 0, sizeof *p);
@@ -711,12 +727,12 @@ hcspmm_status hcspmm_prepare(int32_t n_rows, int32_t n_cols, int64_t nnz, const 
     p->mid_row = kMidRow;
     p->long_row = kLongRow;
     // tuning knobs for experiments (not part of the ABI): override the row-tier thresholds
-    if (const char* v = getenv("HCSPMM_TUNE_MID_ROW")) { int t = atoi(v); if (t >= 1) p->mid_row = t; }
-    if (const char* v = getenv("HCSPMM_TUNE_LONG_ROW")) { int t = atoi(v); if (t >= p->mid_row) p->long_row = t; }
+    if (tune().mid_row >= 1) p->mid_row = tune().mid_row;
+    if (tune().long_row >= p->mid_row) p->long_row = tune().long_row;
     if (p->long_row < p->mid_row) p->long_row = p->mid_row;
     p->fused_mid_row = kFusedMidRow < p->mid_row ? p->mid_row : (kFusedMidRow > p->long_row ? p->long_row : kFusedMidRow);
     p->slice_cols = kSliceCols;
-    if (const char* v = getenv("HCSPMM_TUNE_SLICE_COLS")) { int t = atoi(v); if (t >= kKcBig) p->slice_cols = t / kKcBig * kKcBig; }
+    if (tune().slice_cols >= kKcBig) p->slice_cols = tune().slice_cols / kKcBig * kKcBig;
     if (o.use_custom_selector) {
         for (int i = 0; i < 3; ++i) {
             if (o.sel_coef[i] <= -((int64_t)1 << 40) || o.sel_coef[i] >= ((int64_t)1 << 40)) {
@@ -741,7 +757,7 @@ hcspmm_status hcspmm_prepare(int32_t n_rows, int32_t n_cols, int64_t nnz, const 
     // side streams (default priority) and events for running the paths side by side; optional
     p->side_ok = 0;
     // (the fork/join costs ~20 us of launch latency, so only matrices with milliseconds of work use them)
-    if (p->n_mfma > 0 && p->n_mfma < p->W && p->nnz >= 16000000 && !getenv("HCSPMM_TUNE_SERIAL")) {
+    if (p->n_mfma > 0 && p->n_mfma < p->W && p->nnz >= 16000000 && !tune().serial) {
         bool ok = hipStreamCreateWithFlags(&p->side[0], hipStreamNonBlocking) == hipSuccess;
         ok = ok && hipStreamCreateWithFlags(&p->side[1], hipStreamNonBlocking) == hipSuccess;
         ok = ok && hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming) == hipSuccess;
@@ -978,8 +994,8 @@ hcspmm_status hcspmm_aggregate_update(const hcspmm_plan* plan, const void* d_X, 
     // a plain GEMM does better once they are a large share of the matrix.
     const bool worth = (4 * (int64_t)plan->n_rest < plan->n_rows &&
                         !(x_dtype == HCSPMM_F32 && split_update_faster(plan->n_rows, d_in, d_out, Z))) ||
-                       getenv("HCSPMM_TUNE_FORCE_FUSE");
-    if (update_fusable(a) && worth && !getenv("HCSPMM_TUNE_NO_FUSE")) {
+                       plan->opt.update_fusion == HCSPMM_UPDATE_FUSED;
+    if (update_fusable(a) && worth && plan->opt.update_fusion != HCSPMM_UPDATE_SPLIT) {
         const UpdateArgs u{static_cast<const float*>(d_W), ldw, d_out, static_cast<float*>(d_Y), ldy, apply_relu ? 1 : 0};
         return run_spmm(plan, a, s, nullptr, &u);
     }
@@ -1054,8 +1070,8 @@ hcspmm_status hcspmm_layer_backward(const hcspmm_plan* plan, const void* d_G, in
             // tile besides multiplying it, which measured faster than the separate GEMM only for narrow S
             const bool worth = (4 * (int64_t)plan->n_rest < plan->n_rows && (!d_dW || d_out <= 32) &&
                                 !split_update_faster(plan->n_rows, d_out, d_in, S)) ||
-                               getenv("HCSPMM_TUNE_FORCE_FUSE");
-            if (update_fusable(a) && worth && !getenv("HCSPMM_TUNE_NO_FUSE")) {
+                               plan->opt.update_fusion == HCSPMM_UPDATE_FUSED;
+            if (update_fusable(a) && worth && plan->opt.update_fusion != HCSPMM_UPDATE_SPLIT) {
                 // the next layer's activation mask (its output is this layer's input X) goes into the update's epilogue
                 const UpdateArgs u{Wt, d_in, d_in, static_cast<float*>(d_dX), lddx, 0, d_dW ? 1 : 0,
                                    mask_dx_by_x ? static_cast<const float*>(d_X) : nullptr, ldx};
@@ -1074,6 +1090,38 @@ hcspmm_status hcspmm_layer_backward(const hcspmm_plan* plan, const void* d_G, in
     if (d_dW)
         HC_HIP(launch_gemm_tn(plan->n_rows, static_cast<const float*>(d_X), ldx, d_in, S, d_out, d_out,
                               static_cast<float*>(d_dW), lddw, part, s));
+    return HCSPMM_OK;
+}
+
+size_t hcspmm_probe_gather_out_bytes(int64_t n, int32_t d)
+{
+    if (n <= 0 || d < 1) return 256;
+    return (size_t)probe_gather_blocks(n, d) * 256 * 4 * sizeof(float);
+}
+
+hcspmm_status hcspmm_probe_gather(const int32_t* d_index, int64_t n, const float* d_X, int64_t ldx, int32_t d,
+                                  int32_t n_rows_x, float* d_out, size_t out_bytes, void* stream)
+{
+    if (n < 0 || n_rows_x < 1) { set_error("negative n or empty X"); return HCSPMM_EINVAL; }
+    if (d < 4 || d > 256 || d % 4 != 0 || ldx % 4 != 0 || ((uintptr_t)d_X & 15) != 0) {
+        set_error("the gather probe needs d a multiple of 4 in [4, 256] and 16-byte aligned X rows");
+        return HCSPMM_EUNSUPPORTED;
+    }
+    hcspmm_status st;
+    if ((st = check_dense("X", d_X, ldx, d)) != HCSPMM_OK) return st;
+    if (n == 0) return HCSPMM_OK;
+    if (!d_index || !d_out) { set_error("NULL argument"); return HCSPMM_EINVAL; }
+    if (out_bytes < hcspmm_probe_gather_out_bytes(n, d)) { set_error("out buffer too small: need %zu bytes", hcspmm_probe_gather_out_bytes(n, d)); return HCSPMM_EINVAL; }
+    if (((uintptr_t)d_out & 15) != 0) { set_error("out must be 16-byte aligned"); return HCSPMM_EINVAL; }
+    HC_HIP(launch_probe_gather(d_index, n, d_X, ldx, d, n_rows_x, d_out, static_cast<hipStream_t>(stream)));
+    return HCSPMM_OK;
+}
+
+hcspmm_status hcspmm_plan_set_update_fusion(hcspmm_plan* plan, int32_t update_fusion)
+{
+    if (!plan) { set_error("plan is NULL"); return HCSPMM_EINVAL; }
+    if (update_fusion < 0 || update_fusion > 2) { set_error("bad update_fusion"); return HCSPMM_EINVAL; }
+    plan->opt.update_fusion = update_fusion;
     return HCSPMM_OK;
 }
 

@@ -557,7 +557,7 @@ hipError_t launch_csr(const SpmmArgs& a, int32_t n_segs, const Segment* segs, fl
     // XCD-local runs (see k_csr): tiers of at least 1024 workgroups are padded to whole rounds of
     // eight runs; the surplus workgroups exit at once
     int run = 32;
-    if (const char* t = getenv("HCSPMM_TUNE_XCD_CHUNK")) run = atoi(t);
+    if (tune().xcd_chunk >= 0) run = tune().xcd_chunk;
     auto pad_runs = [run](int64_t n, int32_t& chunk) {
         chunk = 0;
         if (run <= 0 || n < 1024) return n;
@@ -596,7 +596,7 @@ hipError_t launch_csr(const SpmmArgs& a, int32_t n_segs, const Segment* segs, fl
     // launch still has tens of thousands of waves to hide the rows' dependent-load latencies
     int rpg = sh.lpr / 16 > 1 ? sh.lpr / 16 : 1;
     while (rpg > 1 && ((int64_t)n_items / rpg) * sh.lpr / 64 < 32768) rpg >>= 1;
-    if (const char* t = getenv("HCSPMM_TUNE_RPG")) { const int v = atoi(t); if (v >= 1 && v <= kRowsPerGroup) rpg = v; }
+    if (tune().rpg >= 1 && tune().rpg <= kRowsPerGroup) rpg = tune().rpg;
     const int64_t n_groups = ((int64_t)n_items + rpg - 1) / rpg;
     const int gpb = 256 / sh.lpr;
     int32_t xcd_chunk = 0, xcd_chunk_mid = 0;
@@ -636,7 +636,7 @@ hipError_t launch_update_rest(const SpmmArgs& a, int32_t n_rest, const int32_t* 
     const int64_t n_tiles = ((int64_t)n_rest + 15) / 16;
     int tpw = 1;
     while (tpw < 8 && n_tiles / (2 * tpw) >= 16384) tpw *= 2;
-    if (const char* t = getenv("HCSPMM_TUNE_TILES_PER_WAVE")) { const int v = atoi(t); if (v >= 1 && v <= 64) tpw = v; }
+    if (tune().tiles_per_wave >= 1 && tune().tiles_per_wave <= 64) tpw = tune().tiles_per_wave;
     const dim3 grid((unsigned)((n_tiles + 4 * (int64_t)tpw - 1) / (4 * (int64_t)tpw)));
     const int nt = update_tile_nt(upd, 1);
 #define HC_REST(ZD)                                                                                                   \
@@ -650,6 +650,61 @@ hipError_t launch_update_rest(const SpmmArgs& a, int32_t n_rest, const int32_t* 
     else if (a.d <= 256) HC_REST(256)
     else return hipErrorInvalidValue;
 #undef HC_REST
+    return hipGetLastError();
+}
+
+// ---- measurement aid: the bare gather ------------------------------------------------------------
+// Reads row index[i] of X for every i and does nothing else a sparse product would do (no row
+// structure, no values, no output rows): a lane group takes a contiguous run of indices, LPR at a
+// time with one coalesced load, keeps eight row requests in flight like the scalar path, and adds
+// what arrives into registers; one vector per lane is stored at the end so the loads stay live.
+// Its duration is the floor of any kernel that fetches one X row per non-zero of the same stream.
+template <int LPR>
+__global__ __launch_bounds__(256) void k_probe_gather(const int32_t* __restrict__ index, int64_t n, int64_t per_group,
+                                                      const float* __restrict__ X, int64_t ldx, int32_t d,
+                                                      int32_t n_rows_x, float* __restrict__ out)
+{
+    const int64_t grp = (int64_t)blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
+    const int lig = threadIdx.x % LPR;
+    const int64_t b = grp * per_group, e = min(n, b + per_group);
+    const int c = 4 * lig < d ? 4 * lig : 0;
+    const char* __restrict__ Xc = reinterpret_cast<const char*>(X + c);
+    float acc[4];
+    vzero<4>(acc);
+    for (int64_t k0 = b; k0 < e; k0 += LPR) {
+        const int64_t k = min(k0 + lig, e - 1);
+        const int32_t mc = min(max(index[k], 0), n_rows_x - 1);       // whatever the stream holds, the read stays inside X
+        batch_accumulate<LPR, 4, 0>(mc, 1.f, (int)min((int64_t)LPR, e - k0), Xc, ldx * 4, acc);
+    }
+    *reinterpret_cast<float4*>(out + ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+}
+
+int64_t probe_gather_blocks(int64_t n, int32_t d)
+{
+    int lpr = 8;
+    while (lpr < 64 && lpr * 4 < d) lpr <<= 1;
+    const int64_t groups_per_block = 256 / lpr;
+    // about 2048 indices per lane group: long enough to amortise the start-up, short enough for tens of thousands of waves
+    const int64_t groups = (n + 2047) / 2048;
+    return (groups + groups_per_block - 1) / groups_per_block;
+}
+
+hipError_t launch_probe_gather(const int32_t* index, int64_t n, const float* X, int64_t ldx, int32_t d, int32_t n_rows_x,
+                               float* out, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    int lpr = 8;
+    while (lpr < 64 && lpr * 4 < d) lpr <<= 1;
+    const int64_t blocks = probe_gather_blocks(n, d);
+    const int64_t per_group = 2048;
+#define HC_PROBE(L) hipLaunchKernelGGL((k_probe_gather<L>), dim3((unsigned)blocks), dim3(256), 0, s, index, n, per_group, X, ldx, d, n_rows_x, out)
+    switch (lpr) {
+        case 8: HC_PROBE(8); break;
+        case 16: HC_PROBE(16); break;
+        case 32: HC_PROBE(32); break;
+        default: HC_PROBE(64); break;
+    }
+#undef HC_PROBE
     return hipGetLastError();
 }
 

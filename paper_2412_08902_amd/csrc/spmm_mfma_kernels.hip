@@ -647,7 +647,7 @@ hipError_t launch_mfma_small(const SpmmArgs& a, int32_t n_list, const WinDesc* d
     int xcd_chunk = 0;
     if (n_blocks >= 1024) {                      // pad to whole rounds of eight runs; surplus workgroups exit at once
         xcd_chunk = 32;
-        if (const char* t = getenv("HCSPMM_TUNE_XCD_CHUNK")) xcd_chunk = atoi(t);
+        if (tune().xcd_chunk >= 0) xcd_chunk = tune().xcd_chunk;
         if (xcd_chunk > 0) n_blocks = (n_blocks + 8 * xcd_chunk - 1) / (8 * xcd_chunk) * (8 * xcd_chunk);
         else xcd_chunk = 0;
     }

@@ -11,12 +11,14 @@ pytestmark = pytest.mark.gpu
 TOL_F32 = 1e-5
 
 
-def run_backward(g, G, X, W, mode=0, Y_fwd=None, want_dx=True, want_dw=True, pad=0, sel_coef=None, mask_dx=False):
+def run_backward(g, G, X, W, mode=0, Y_fwd=None, want_dx=True, want_dw=True, pad=0, sel_coef=None, mask_dx=False,
+                 update_fusion=0):
     import torch
     import paper_2412_08902_amd.binding as hc
     rp, ci, va = device_graph(g)
     d_in, d_out = W.shape
-    plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, route_mode=mode, d_hint=d_out, sel_coef=sel_coef)
+    plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, route_mode=mode, d_hint=d_out, sel_coef=sel_coef,
+                             update_fusion=update_fusion)
     ws = torch.empty(hc.hcspmm_layer_backward_workspace_bytes(plan, d_in, d_out), dtype=torch.uint8, device="cuda")
     dX = torch.full((g.n_rows, d_in + pad), -3.0, device="cuda") if want_dx else None
     dW = torch.full((d_in, d_out + pad), -3.0, device="cuda") if want_dw else None
@@ -44,11 +46,11 @@ def check(g, G, X, W, dX, dW, S, Y_fwd=None, mask_dx=False):
     b_s = oracle.spmm(g.rowptr, g.colind, g.vals, Gm, use_abs=True)
     if dW is not None or dX is None:
         assert_close(S, ref_s, b_s, TOL_F32, "S")
-    # two chained fp32 stages: the aggregation's rounding is amplified by at most |W| resp. |X|
+    # two chained fp32 stages, still inside the single-stage gate (measured errors are a few unit roundoffs)
     if dX is not None:
-        assert_close(dX, ref_dx, b_dx, 2 * TOL_F32, "dX")
+        assert_close(dX, ref_dx, b_dx, TOL_F32, "dX")
     if dW is not None:
-        assert_close(dW, ref_dw, b_dw, 2 * TOL_F32, "dW")
+        assert_close(dW, ref_dw, b_dw, TOL_F32, "dW")
 
 
 @pytest.mark.parametrize("mode", [0, 1, 2])
@@ -68,16 +70,15 @@ def test_backward_small(mode, relu):
 @pytest.mark.parametrize("mode", [0, 1, 2, 3])
 @pytest.mark.parametrize("din,dout", [(16, 16), (1, 32), (17, 48), (64, 64), (200, 128), (128, 256), (72, 112),
                                       (602, 128), (40, 300)])
-def test_backward_shapes(mode, din, dout, force, monkeypatch):
+def test_backward_shapes(mode, din, dout, force):
     """Widths in and out of the fused update's range (d_out a multiple of 16 up to 256), on a power-law graph whose
     hub rows and wide windows take the memory route, with a ragged last window and every routing."""
-    if force:
-        monkeypatch.setenv("HCSPMM_TUNE_FORCE_FUSE", "1")
     g = gcn_normalise(chung_lu_graph(3003, 150000, 2.0, seed=71, max_degree=2800))
     X, W = dense_normal(g.n_rows, din, seed=72), glorot_uniform(din, dout, seed=73)
     G = dense_normal(g.n_cols, dout, seed=74)
     mask_dx = din % 2 == 0                                   # half of the shapes also mask dX by the layer's input
-    dX, dW, S = run_backward(g, G, X, W, mode, pad=2, sel_coef=[1, 0, -300] if mode == 3 else None, mask_dx=mask_dx)
+    dX, dW, S = run_backward(g, G, X, W, mode, pad=2, sel_coef=[1, 0, -300] if mode == 3 else None, mask_dx=mask_dx,
+                             update_fusion=1 if force else 0)
     check(g, G, X, W, dX, dW, S, mask_dx=mask_dx)
 
 
@@ -285,18 +286,18 @@ def test_two_layer_gcn_forward_and_backward_compose():
     H1h = H1.cpu().numpy()
     a = (g.rowptr, g.colind, g.vals)
     # forward
-    assert_close(f64(H1), oracle.gcn_layer(*a, X, W1), oracle.gcn_layer(*a, X, W1, use_abs=True), 2 * TOL_F32, "H1")
+    assert_close(f64(H1), oracle.gcn_layer(*a, X, W1), oracle.gcn_layer(*a, X, W1, use_abs=True), TOL_F32, "H1")
     assert_close(f64(out), oracle.gcn_layer(*a, H1h, W2, relu=False), oracle.gcn_layer(*a, H1h, W2, use_abs=True),
-                 2 * TOL_F32, "out")
+                 TOL_F32, "out")
     # backward, layer 2 then layer 1 (the oracle's layer-1 input gradient is its own fp64 dH1)
     r_dH1, r_dW2 = oracle.layer_backward(*a, C, H1h, W2, mask_dx_by_x=True)
     b_dH1, b_dW2 = oracle.layer_backward(*a, C, H1h, W2, use_abs=True)
-    assert_close(f64(dH1), r_dH1, b_dH1, 2 * TOL_F32, "dH1")
-    assert_close(f64(dW2), r_dW2, b_dW2, 2 * TOL_F32, "dW2")
+    assert_close(f64(dH1), r_dH1, b_dH1, TOL_F32, "dH1")
+    assert_close(f64(dW2), r_dW2, b_dW2, TOL_F32, "dW2")
     r_dX, r_dW1 = oracle.layer_backward(*a, r_dH1, X, W1)
     b_dX, b_dW1 = oracle.layer_backward(*a, b_dH1, X, W1, use_abs=True)
-    assert_close(f64(dX), r_dX, b_dX, 4 * TOL_F32, "dX")
-    assert_close(f64(dW1), r_dW1, b_dW1, 4 * TOL_F32, "dW1")
+    assert_close(f64(dX), r_dX, b_dX, TOL_F32, "dX")
+    assert_close(f64(dW1), r_dW1, b_dW1, TOL_F32, "dW1")
     # the bilinear identity of the last layer ties the loss to its weight gradient: <dW2, W2> = <C, out>
     L = float(np.sum(C.astype(np.float64) * f64(out)))
     assert abs(float(np.sum(f64(dW2) * W2)) - L) <= 1e-5 * float(np.sum(np.abs(C) * oracle.gcn_layer(*a, H1h, W2, use_abs=True)))

@@ -50,8 +50,8 @@ def test_layer_small(mode, relu):
     got = run_layer(g, X, W, mode, relu)
     ref = oracle.gcn_layer(g.rowptr, g.colind, g.vals, X, W, relu=relu)
     bound = oracle.gcn_layer(g.rowptr, g.colind, g.vals, X, W, use_abs=True)
-    # two chained fp32 stages: the dense product's rounding is amplified by at most |A|
-    assert_close(got, ref, bound, 2 * TOL_F32)
+    # two chained fp32 stages, still inside the single-stage gate (measured errors are a few unit roundoffs)
+    assert_close(got, ref, bound, TOL_F32)
     if relu:
         assert got.min() >= 0.0 and (got == 0).any()
 
@@ -61,7 +61,7 @@ def test_layer_scaled_config5():
     got = run_layer(g, X, W, 0)
     ref = oracle.gcn_layer(g.rowptr, g.colind, g.vals, X, W)
     bound = oracle.gcn_layer(g.rowptr, g.colind, g.vals, X, W, use_abs=True)
-    assert_close(got, ref, bound, 2 * TOL_F32)
+    assert_close(got, ref, bound, TOL_F32)
 
 
 def run_aggregate_update(g, X, W, mode, relu=True, x_bits=None, ldy_pad=0):
@@ -94,7 +94,7 @@ def test_aggregate_update_small(mode, relu):
     got = run_aggregate_update(g, X, W, mode, relu, ldy_pad=3)
     ref = oracle.aggregate_update(g.rowptr, g.colind, g.vals, X, W, relu=relu)
     bound = oracle.aggregate_update(g.rowptr, g.colind, g.vals, X, W, use_abs=True)
-    assert_close(got, ref, bound, 2 * TOL_F32)
+    assert_close(got, ref, bound, TOL_F32)
     if relu:
         assert got.min() >= 0.0 and (got == 0).any()
 
@@ -107,7 +107,7 @@ def test_aggregate_update_widths(din, dout):
     got = run_aggregate_update(g, X, W, 0)
     ref = oracle.aggregate_update(g.rowptr, g.colind, g.vals, X, W)
     bound = oracle.aggregate_update(g.rowptr, g.colind, g.vals, X, W, use_abs=True)
-    assert_close(got, ref, bound, 2 * TOL_F32)
+    assert_close(got, ref, bound, TOL_F32)
 
 
 def test_aggregate_update_bf16_x():
@@ -169,12 +169,10 @@ def test_spmm_on_reformatted_layout():
 @pytest.mark.parametrize("force", [False, True])
 @pytest.mark.parametrize("mode", [0, 1, 2, 3])
 @pytest.mark.parametrize("din,dout", [(16, 16), (32, 1), (48, 17), (64, 64), (128, 200), (256, 128), (112, 72)])
-def test_aggregate_update_fused_shapes(mode, din, dout, force, monkeypatch):
+def test_aggregate_update_fused_shapes(mode, din, dout, force):
     """Widths the fused update covers (d_in a multiple of 16 up to 256), on a power-law graph whose hub rows
     and wide windows take the memory route, with a ragged last window and every routing.  `force` keeps the
     fused kernels on even where the library would judge the workspace rows too many to bother."""
-    if force:
-        monkeypatch.setenv("HCSPMM_TUNE_FORCE_FUSE", "1")
     g = gcn_normalise(chung_lu_graph(3003, 150000, 2.0, seed=71, max_degree=2800))
     assert np.diff(g.rowptr).max() > 1024                    # a long row: several tiers are in play
     X, W = dense_normal(g.n_cols, din, seed=72), glorot_uniform(din, dout, seed=73)
@@ -182,7 +180,8 @@ def test_aggregate_update_fused_shapes(mode, din, dout, force, monkeypatch):
     import torch
     rp, ci, va = device_graph(g)
     plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, route_mode=mode, d_hint=din,
-                             sel_coef=[1, 0, -300] if mode == 3 else None)
+                             sel_coef=[1, 0, -300] if mode == 3 else None,
+                             update_fusion=hc.HCSPMM_UPDATE_FUSED if force else hc.HCSPMM_UPDATE_AUTO)
     ws = torch.empty(hc.hcspmm_aggregate_update_workspace_bytes(plan, din, dout), dtype=torch.uint8, device="cuda")
     Y = torch.full((g.n_rows, dout + 2), -3.0, device="cuda")
     hc.hcspmm_aggregate_update(plan, torch.from_numpy(X).cuda(), torch.from_numpy(W).cuda(), Y[:, :dout], ws,
@@ -196,7 +195,7 @@ def test_aggregate_update_fused_shapes(mode, din, dout, force, monkeypatch):
     assert np.all(got[:, dout:] == -3.0)
     ref = oracle.aggregate_update(g.rowptr, g.colind, g.vals, X, W, relu=(dout % 2 == 0))
     bound = oracle.aggregate_update(g.rowptr, g.colind, g.vals, X, W, use_abs=True)
-    assert_close(got[:, :dout], ref, bound, 2 * TOL_F32)
+    assert_close(got[:, :dout], ref, bound, TOL_F32)
 
 
 def test_aggregate_update_fused_community_graph_with_empty_rows():
@@ -216,17 +215,16 @@ def test_aggregate_update_fused_community_graph_with_empty_rows():
         got = run_aggregate_update(g, X, W, mode, relu=False)
         ref = oracle.aggregate_update(g.rowptr, g.colind, g.vals, X, W, relu=False)
         bound = oracle.aggregate_update(g.rowptr, g.colind, g.vals, X, W, use_abs=True)
-        assert_close(got, ref, bound, 2 * TOL_F32)
+        assert_close(got, ref, bound, TOL_F32)
         assert np.all(got[32:48] == 0.0) and np.all(got[5] == 0.0)
 
 
 @pytest.mark.parametrize("kind", ["bf16", "f16"])
 @pytest.mark.parametrize("mode", [0, 1, 2, 3])
 @pytest.mark.parametrize("din,dout", [(32, 48), (64, 64), (128, 32), (256, 130), (80, 16)])
-def test_aggregate_update_fused_16bit_x(kind, mode, din, dout, monkeypatch):
+def test_aggregate_update_fused_16bit_x(kind, mode, din, dout):
     """16-bit X through the fused update (fp32 tile in LDS, fp32 update): scalar path exact widening, matrix
     path 16-bit products; hub rows and wide windows go through the workspace."""
-    monkeypatch.setenv("HCSPMM_TUNE_FORCE_FUSE", "1")
     from workloads import to_bf16_bits, to_f16_bits
     g = gcn_normalise(chung_lu_graph(3003, 150000, 2.0, seed=171, max_degree=2800))
     X, W = dense_normal(g.n_cols, din, seed=172), glorot_uniform(din, dout, seed=173)
@@ -236,7 +234,8 @@ def test_aggregate_update_fused_16bit_x(kind, mode, din, dout, monkeypatch):
     import torch
     rp, ci, va = device_graph(g)
     plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, route_mode=mode, d_hint=din,
-                             mfma_dtype=1 if kind == "bf16" else 2, sel_coef=[1, 0, -300] if mode == 3 else None)
+                             mfma_dtype=1 if kind == "bf16" else 2, sel_coef=[1, 0, -300] if mode == 3 else None,
+                             update_fusion=hc.HCSPMM_UPDATE_FUSED)
     ws = torch.empty(hc.hcspmm_aggregate_update_workspace_bytes(plan, din, dout), dtype=torch.uint8, device="cuda")
     Y = torch.full((g.n_rows, dout), -3.0, device="cuda")
     Xd = torch.from_numpy(Xb.view(np.int16)).cuda().view(torch.bfloat16 if kind == "bf16" else torch.float16)
@@ -245,7 +244,7 @@ def test_aggregate_update_fused_16bit_x(kind, mode, din, dout, monkeypatch):
     plan.destroy()
     ref = oracle.aggregate_update(g.rowptr, g.colind, g.vals, Xb, W, relu=False, x_dtype=code)
     bound = oracle.aggregate_update(g.rowptr, g.colind, g.vals, Xb, W, x_dtype=code, use_abs=True)
-    assert_close(Y.cpu().numpy().astype(np.float64), ref, bound, 2e-2 if mode != 1 else 2 * TOL_F32)
+    assert_close(Y.cpu().numpy().astype(np.float64), ref, bound, 2e-2 if mode != 1 else TOL_F32)
 
 
 @pytest.mark.parametrize("kind,code", [("bf16", 1), ("f16", 2)])

@@ -255,3 +255,49 @@ def test_column_count_at_the_documented_limit(mode):
     ref, bound = oracle_pair(g, X)
     assert_close(Y, ref, bound, TOL_F32)
     assert info["n_cols"] == n_cols
+
+
+@pytest.mark.parametrize("kind", ["f32", "bf16"])
+@pytest.mark.parametrize("mode", MODES)
+def test_row_offsets_beyond_2_to_the_31_elements(mode, kind):
+    """Leading dimensions so large that row * ld exceeds 2^31 ELEMENTS for most rows of X and of Y (the kernels must
+    form these offsets in 64 bits): X and Y live in device buffers with a pitch of 36,000 elements, the oracle
+    works on the compact columns."""
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    from workloads import to_bf16_bits
+    n, d, ld = 70000, 24, 36000                         # last row starts at element 2.52e9 > 2^31 (2.15e9)
+    assert (n - 1) * ld > 2 ** 31
+    rng = np.random.default_rng(321)
+    lens = rng.integers(0, 9, size=n)
+    lens[n - 16:] = 40                                  # a dense last window, beyond the 2^31 mark on both sides
+    lens[5] = 3000                                      # one long row whose columns span the whole range
+    cols = [np.sort(rng.choice(n, size=int(l), replace=False)) for l in lens]
+    cols[n - 1][-1] = n - 1
+    rp = np.zeros(n + 1, np.int32)
+    np.cumsum(lens, out=rp[1:])
+    g = CSRGraph(n, n, rp, np.concatenate(cols).astype(np.int32),
+                 rng.standard_normal(int(lens.sum())).astype(np.float32))
+    X = dense_normal(n, d, seed=322)
+    dev = torch.device("cuda:0")
+    if kind == "f32":
+        Xbuf = torch.empty((n, ld), dtype=torch.float32, device=dev)            # 10 GB, uninitialised beyond column d
+        Xbuf[:, :d] = torch.from_numpy(X).to(dev)
+        x_or, code, tol = X, None, TOL_F32
+    else:
+        bits = to_bf16_bits(X)
+        Xbuf = torch.empty((n, ld), dtype=torch.bfloat16, device=dev)
+        Xbuf[:, :d] = torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
+        x_or, code, tol = bits, oracle.DT_BF16, (2e-2 if mode != ALL_CSR else TOL_F32)
+    Ybuf = torch.empty((n, ld), dtype=torch.float32, device=dev)
+    Ybuf[:, :d + 1] = -777.0
+    rpd, cid, vad = device_graph(g)
+    plan = hc.hcspmm_prepare(n, n, rpd, cid, vad, route_mode=mode, d_hint=d, mfma_dtype=0 if kind == "f32" else 1)
+    hc.hcspmm_spmm(plan, Xbuf, Ybuf, d=d)
+    torch.cuda.synchronize()
+    plan.destroy()
+    Y = Ybuf[:, :d + 1].cpu().numpy().astype(np.float64)
+    assert np.all(Y[:, d] == -777.0), "wrote outside the d output columns"
+    ref = oracle.spmm_rows(None, g.rowptr, g.colind, g.vals, x_or, code)
+    bound = oracle.spmm_rows(None, g.rowptr, g.colind, g.vals, x_or, code, use_abs=True)
+    assert_close(Y[:, :d], ref, bound, tol, "mode %d %s" % (mode, kind))
