@@ -82,6 +82,8 @@ def main():
                     help="C5 only: time the whole GCN layer Y = ReLU(A (X W)) (GEMM + hybrid SpMM) instead of the SpMM")
     ap.add_argument("--t-dtype", default="f32", choices=["f32", "bf16", "f16"],
                     help="with --layer: storage type of the intermediate X W (f32 is the headline layer)")
+    ap.add_argument("--matrix-kernels", default="auto", choices=["auto", "per_window", "runs"],
+                    help="kernels of the matrix path: per window (what auto picks), or runs of four windows sharing X rows in LDS")
     ap.add_argument("--sel-coef", default=None, help="three comma-separated integers overriding the shipped selector")
     ap.add_argument("--agg-update", type=int, default=None, metavar="D_OUT",
                     help="also time the aggregate-then-update layer Y = ReLU((A X) W) with a d x D_OUT W, with the "
@@ -154,7 +156,8 @@ def main():
         torch.cuda.synchronize()
         t = time.perf_counter()
         plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, route_mode=mode, d_hint=d, sel_coef=sel_coef,
-                                 mfma_dtype=mfma_dtype)
+                                 mfma_dtype=mfma_dtype,
+                                 matrix_kernels={"auto": 0, "per_window": 1, "runs": 2}[args.matrix_kernels])
         torch.cuda.synchronize()
         return plan, (time.perf_counter() - t) * 1e3
 
@@ -206,7 +209,8 @@ def main():
                dtype=args.x_dtype, data="synthetic",
                config=dict(workload=WORKLOAD_TEXT[name], name=name, n=g.n_rows, nnz=g.nnz, d=d, route_mode="hybrid",
                            n_windows=info["n_windows"], mfma_windows=info["n_mfma_windows"],
-                           nnz_on_matrix_path=nnz_mfma, sel_coef=info["sel_coef"]),
+                           nnz_on_matrix_path=nnz_mfma, sel_coef=info["sel_coef"], matrix_kernels=args.matrix_kernels,
+                           total_ncols=info["total_ncols"], n_runs=info["n_runs"], run_union_cols=info["run_union_cols"]),
                roofline=roofline, prepare_ms=round(prepare_ms, 3),
                stage_ms={k: round(v, 5) for k, v in stage_ms.items()})
 

@@ -77,6 +77,14 @@ typedef enum {
  * route for the shape, FUSED takes the fused kernels whenever the shape allows them, SPLIT never does. */
 typedef enum { HCSPMM_UPDATE_AUTO = 0, HCSPMM_UPDATE_FUSED = 1, HCSPMM_UPDATE_SPLIT = 2 } hcspmm_update_fusion;
 
+/* Kernels of the matrix path.  PER_WINDOW (what AUTO selects): one wave, or for wide windows one workgroup, per
+ * window; windows that share columns meet in L2 through the launch order.  RUNS: runs of four neighbouring
+ * matrix-path windows, one workgroup each, share their gathered X rows through LDS (Section IV-B: loading X is
+ * the larger part of the matrix path) -- used when the plan and the call allow it (rows with ascending columns,
+ * n_cols <= 2^22, X rows readable in 16-byte pieces, no fused update), else PER_WINDOW.  RUNS is kept as an option
+ * because it measured slower on every benchmark graph: the rows it saves are the ones L2 already served. */
+typedef enum { HCSPMM_MATRIX_AUTO = 0, HCSPMM_MATRIX_PER_WINDOW = 1, HCSPMM_MATRIX_RUNS = 2 } hcspmm_matrix_kernels;
+
 /*
  * Options of hcspmm_prepare.  Fill with hcspmm_default_options() first.
  *
@@ -101,7 +109,7 @@ typedef struct {
     int64_t sel_coef[3];
     int32_t update_fusion;        /* hcspmm_update_fusion: how hcspmm_aggregate_update / hcspmm_layer_backward on this plan
                                      choose between the fused update stage and SpMM + GEMM (for tests and measurements) */
-    int32_t reserved;             /* must be 0 */
+    int32_t matrix_kernels;       /* hcspmm_matrix_kernels: which kernels serve the matrix path (for tests and measurements) */
 } hcspmm_options;
 
 void hcspmm_default_options(hcspmm_options* opt /* host, out */);
@@ -158,6 +166,10 @@ typedef struct {
     int64_t nnz_long;         /* non-zeros inside mid and long rows */
     int32_t n_mfma_small;     /* route-1 windows handled one wave per window */
     int32_t n_mfma_big;       /* route-1 windows handled one workgroup per window */
+    /* runs of neighbouring route-1 windows with merged column lists (0 when the plan has no run tables) */
+    int32_t n_runs;
+    int32_t n_run_slices;     /* workgroups of the run kernel */
+    int64_t run_union_cols;   /* sum over runs of the merged list's length (total_ncols of the same windows counts shared columns per window) */
 } hcspmm_plan_info_t;
 
 /* Synchronises with the device the first time it is called on an HCSPMM_ROUTE_ALL_CSR plan (it then
@@ -181,6 +193,18 @@ hcspmm_status hcspmm_plan_info(const hcspmm_plan* plan, hcspmm_plan_info_t* info
 hcspmm_status hcspmm_plan_export(const hcspmm_plan* plan, int32_t* ncols, int32_t* nnzw, uint8_t* route,
                                  int64_t* wptr, int32_t* wcols, int32_t* ecol,
                                  int32_t* mfma_windows, int32_t* csr_windows);
+
+/*
+ * Launch table of the run kernel (plans prepared with matrix_kernels = HCSPMM_MATRIX_RUNS; sizes from
+ * hcspmm_plan_info: n_runs, run_union_cols, total_ncols).  Run r covers entries [4r, min(4r + 4, n_mfma_windows))
+ * of mfma_windows.  Each pointer may be NULL:
+ *   run_nu  int32[n_runs]          length of the run's merged column list
+ *   ucols   int32[run_union_cols]  the merged lists, run after run, each ascending
+ *   wslot   int32[total_ncols]     indexed like wcols: position of that window column in its run's merged
+ *                                  list (-1 for columns of scalar-path windows)
+ * HCSPMM_EINVAL when the plan has no run table.  Synchronises with the device.
+ */
+hcspmm_status hcspmm_plan_export_runs(const hcspmm_plan* plan, int32_t* run_nu, int32_t* ucols, int32_t* wslot);
 
 /*
  * Y = A X on the hybrid paths (Eq. 1; Alg. 1/3 for route-0 windows, Alg. 2/4

@@ -27,4 +27,5 @@ from .plan import (  # noqa: F401
     derive_plan,
     derive_plan_vectorised,
     derive_window,
+    derive_runs,
 )

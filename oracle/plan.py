@@ -25,6 +25,10 @@ Steps, in the paper's order (Section IV-A "Combination Strategy", Section IV-C
    take the other path -- checked for the matrix side first, then for the scalar side.
    Mode ROUTE_PER_WINDOW skips this step.
 5. the ascending lists of window ids per route.
+6. runs (a launch table of this implementation's optional run kernel, not of the paper): the
+   matrix path's window list is cut into runs of RUN_WINDOWS consecutive entries; a run's union
+   is the ascending list of the distinct columns of its windows, and every window column gets
+   its position in that union.
 
 All arithmetic is Python / numpy integer arithmetic.
 """
@@ -37,6 +41,7 @@ import numpy as np
 
 ROUTE_HYBRID, ROUTE_ALL_CSR, ROUTE_ALL_MFMA, ROUTE_PER_WINDOW = 0, 1, 2, 3
 GUARD_NNZ, GUARD_SHARE = 1 << 18, 8
+RUN_WINDOWS = 4
 
 
 def window_features(cols_in_window: np.ndarray):
@@ -160,3 +165,21 @@ def derive_plan_vectorised(rowptr: np.ndarray, colind: np.ndarray, coef: Sequenc
     return dict(H=H, W=W, ncols=ncols.astype(np.int32), nnzw=nnzw.astype(np.int32), route=route, wptr=wptr,
                 wcols=wcols.astype(np.int32), ecol=ecol.astype(np.int32),
                 mfma_windows=ids[route == 1], csr_windows=ids[route == 0])
+
+
+def derive_runs(mfma_windows: Sequence[int], wptr: np.ndarray, wcols: np.ndarray, run_windows: int = RUN_WINDOWS):
+    """Step 6: per run of ``run_windows`` consecutive entries of the matrix path's window list, the ascending
+    union of the windows' column lists and, per window, the position of each of its columns in that union.
+
+    Returns a list of dicts {first, windows, union, slots} with ``slots[i][k]`` = position of column k of
+    window ``windows[i]`` in ``union``; plain Python set/sort per run."""
+    out = []
+    lst = [int(w) for w in mfma_windows]
+    for first in range(0, len(lst), run_windows):
+        wins = lst[first:first + run_windows]
+        lists = [[int(c) for c in wcols[int(wptr[w]):int(wptr[w + 1])]] for w in wins]
+        union = sorted(set(c for l in lists for c in l))
+        pos = {c: i for i, c in enumerate(union)}
+        out.append(dict(first=first, windows=wins, union=np.array(union, dtype=np.int64),
+                        slots=[np.array([pos[c] for c in l], dtype=np.int64) for l in lists]))
+    return out

@@ -17,10 +17,11 @@ HCSPMM_OK, HCSPMM_EINVAL, HCSPMM_EBADCSR, HCSPMM_EALLOC, HCSPMM_EHIP, HCSPMM_EUN
 HCSPMM_F32, HCSPMM_BF16, HCSPMM_F16 = 0, 1, 2
 HCSPMM_ROUTE_HYBRID, HCSPMM_ROUTE_ALL_CSR, HCSPMM_ROUTE_ALL_MFMA, HCSPMM_ROUTE_PER_WINDOW = 0, 1, 2, 3
 HCSPMM_UPDATE_AUTO, HCSPMM_UPDATE_FUSED, HCSPMM_UPDATE_SPLIT = 0, 1, 2
+HCSPMM_MATRIX_AUTO, HCSPMM_MATRIX_PER_WINDOW, HCSPMM_MATRIX_RUNS = 0, 1, 2
 
 EXPORTED_SYMBOLS = [
     "hcspmm_default_options", "hcspmm_default_selector", "hcspmm_prepare", "hcspmm_plan_info",
-    "hcspmm_plan_export", "hcspmm_spmm", "hcspmm_spmm_noalloc", "hcspmm_spmm_noalloc_scratch_limit", "hcspmm_spmm_timed", "hcspmm_gcn_layer", "hcspmm_gcn_layer_ex", "hcspmm_gcn_workspace_bytes",
+    "hcspmm_plan_export", "hcspmm_plan_export_runs", "hcspmm_spmm", "hcspmm_spmm_noalloc", "hcspmm_spmm_noalloc_scratch_limit", "hcspmm_spmm_timed", "hcspmm_gcn_layer", "hcspmm_gcn_layer_ex", "hcspmm_gcn_workspace_bytes",
     "hcspmm_aggregate_update", "hcspmm_aggregate_update_workspace_bytes",
     "hcspmm_layer_backward", "hcspmm_layer_backward_workspace_bytes",
     "hcspmm_gemm_f32", "hcspmm_plan_set_update_fusion", "hcspmm_probe_gather", "hcspmm_probe_gather_out_bytes", "hcspmm_loa_order", "hcspmm_permute_csr", "hcspmm_transpose_csr", "hcspmm_plan_destroy", "hcspmm_status_string", "hcspmm_last_error", "hcspmm_version",
@@ -30,7 +31,7 @@ EXPORTED_SYMBOLS = [
 class HcspmmOptions(ctypes.Structure):
     _fields_ = [("struct_size", ctypes.c_int32), ("window_rows", ctypes.c_int32), ("route_mode", ctypes.c_int32),
                 ("mfma_dtype", ctypes.c_int32), ("d_hint", ctypes.c_int32), ("use_custom_selector", ctypes.c_int32),
-                ("sel_coef", ctypes.c_int64 * 3), ("update_fusion", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("sel_coef", ctypes.c_int64 * 3), ("update_fusion", ctypes.c_int32), ("matrix_kernels", ctypes.c_int32)]
 
 
 class HcspmmPlanInfo(ctypes.Structure):
@@ -40,7 +41,8 @@ class HcspmmPlanInfo(ctypes.Structure):
                 ("route_mode", ctypes.c_int32), ("mfma_dtype", ctypes.c_int32), ("d_hint", ctypes.c_int32),
                 ("sel_coef", ctypes.c_int64 * 3), ("device_bytes", ctypes.c_int64),
                 ("n_short_rows", ctypes.c_int32), ("n_mid_rows", ctypes.c_int32), ("n_long_rows", ctypes.c_int32), ("n_segments", ctypes.c_int32),
-                ("nnz_long", ctypes.c_int64), ("n_mfma_small", ctypes.c_int32), ("n_mfma_big", ctypes.c_int32)]
+                ("nnz_long", ctypes.c_int64), ("n_mfma_small", ctypes.c_int32), ("n_mfma_big", ctypes.c_int32),
+                ("n_runs", ctypes.c_int32), ("n_run_slices", ctypes.c_int32), ("run_union_cols", ctypes.c_int64)]
 
 
 class HcspmmStageTimes(ctypes.Structure):
@@ -81,6 +83,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.hcspmm_plan_info.restype = ctypes.c_int
     lib.hcspmm_plan_export.argtypes = [vp] + [vp] * 8
     lib.hcspmm_plan_export.restype = ctypes.c_int
+    lib.hcspmm_plan_export_runs.argtypes = [vp, vp, vp, vp]
+    lib.hcspmm_plan_export_runs.restype = ctypes.c_int
     lib.hcspmm_spmm.argtypes = [vp, vp, i64, i32, i32, vp, i64, i32, vp]
     lib.hcspmm_spmm.restype = ctypes.c_int
     lib.hcspmm_spmm_noalloc.argtypes = [vp, vp, i64, i32, i32, vp, i64, i32, vp]
@@ -197,11 +201,13 @@ class Plan:
 
 def hcspmm_prepare(n_rows: int, n_cols: int, rowptr, colind, vals, *, route_mode: int = HCSPMM_ROUTE_HYBRID,
                    mfma_dtype: int = HCSPMM_F32, d_hint: int = 0, sel_coef: Optional[Sequence[int]] = None,
-                   stream=None, nnz: Optional[int] = None, update_fusion: int = HCSPMM_UPDATE_AUTO) -> Plan:
+                   stream=None, nnz: Optional[int] = None, update_fusion: int = HCSPMM_UPDATE_AUTO,
+                   matrix_kernels: int = HCSPMM_MATRIX_AUTO) -> Plan:
     """rowptr/colind: int32 CUDA tensors, vals: float32 CUDA tensor (borrowed by the plan)."""
     lib = load_library()
     o = hcspmm_default_options()
     o.route_mode, o.mfma_dtype, o.d_hint, o.update_fusion = route_mode, mfma_dtype, d_hint, update_fusion
+    o.matrix_kernels = matrix_kernels
     if sel_coef is not None:
         o.use_custom_selector = 1
         for i in range(3):
@@ -257,6 +263,20 @@ def hcspmm_plan_export(plan: Plan, with_ecol: bool = True) -> dict:
     _check(load_library().hcspmm_plan_export(plan.handle, p("ncols"), p("nnzw"), p("route"),
                                              out["wptr"].ctypes.data_as(ctypes.c_void_p), p("wcols"),
                                              p("ecol") if with_ecol else None, p("mfma_windows"), p("csr_windows")))
+    return out
+
+
+def hcspmm_plan_export_runs(plan: Plan) -> dict:
+    """Launch table of the run kernel as numpy arrays (host): run_nu, ucols (concatenated), wslot (indexed like wcols)."""
+    info = hcspmm_plan_info(plan)
+    out = dict(run_nu=np.zeros(info["n_runs"], np.int32), ucols=np.zeros(info["run_union_cols"], np.int32),
+               wslot=np.zeros(info["total_ncols"], np.int32))
+
+    def p(name):
+        a = out[name]
+        return a.ctypes.data_as(ctypes.c_void_p) if a.size else None
+
+    _check(load_library().hcspmm_plan_export_runs(plan.handle, p("run_nu"), p("ucols"), p("wslot")))
     return out
 
 

@@ -42,13 +42,21 @@ struct MultiRow { int32_t row, first_slot, n_slots, pad; };
 // one workgroup's share of a matrix-path window: condensed columns [kc_begin, kc_end); slot < 0: writes Y
 struct WgSlice { int32_t w, kc_begin, kc_end, slot; };
 struct WinDesc { int32_t w, s, e, nc; int64_t wp; int64_t pad; };
+// a run of up to kRunWindows consecutive entries of the matrix path's window list whose column lists were merged
+struct RunDesc { int64_t up; int32_t first, nw, nu, n_slices, slot0, pad; };   // union at ucols[up .. up + nu)
+// one workgroup's share of a run: union positions [u_begin, u_end) of the list at ucols[up ..], q-th of the run's
+// n_slices slices; nw windows; partial tiles (n_slices > 1) at slot0 + wave * n_slices + q
+struct RunSlice { int64_t up; int32_t run, u_begin, u_end, q, nw, n_slices, slot0, pad[3]; };
+// the window a wave of a slice's workgroup owns (waves beyond the run's last window repeat its first)
+struct RunWin { int64_t wp; int32_t w, nc, k_last, pad; };
+constexpr int kRunWindows = 4;
 
 void set_error(const char* fmt, ...);
 
 // Experiment knobs (HCSPMM_TUNE_* environment variables; not part of the ABI), read ONCE per process on first use.
 // A value of -1 means "not set": the built-in choice applies.
 struct Tune {
-    int mid_row, long_row, slice_cols, serial, xcd_chunk, rpg, tiles_per_wave, no_rows16;
+    int mid_row, long_row, slice_cols, serial, xcd_chunk, rpg, tiles_per_wave, no_rows16, runs, run_slice;
 };
 const Tune& tune();
 
@@ -177,6 +185,18 @@ int64_t probe_gather_blocks(int64_t n, int32_t d);
 hipError_t launch_probe_gather(const int32_t* index, int64_t n, const float* X, int64_t ldx, int32_t d, int32_t n_rows_x,
                                float* out, hipStream_t s);
 bool mfma_shape_supported(const SpmmArgs& a);
+bool mfma_run_shape_supported(const SpmmArgs& a);
+hipError_t launch_mfma_run(const SpmmArgs& a, int32_t n_slices, const RunSlice* slices, const RunWin* wins,
+                           const int32_t* ucols, const int32_t* wslot, const int32_t* erc, float* tile_partial, hipStream_t s);
+hipError_t launch_run_wins(int32_t n_slices, const RunSlice* slices, const RunDesc* runs, const int32_t* win_list,
+                           const int32_t* ncols, const int64_t* wptr, int32_t n_rows, const int32_t* rowptr, RunWin* wins,
+                           hipStream_t s);
+// union column list of every run and the position of each window column in it (prepare)
+hipError_t launch_run_union(int32_t n_runs, const int32_t* win_list, int32_t n_list, const int32_t* ncols,
+                            const int64_t* wptr, const int32_t* wcols, int32_t* ucols, int32_t* wslot, RunDesc* runs,
+                            hipStream_t s);
+constexpr int kRunMinSlice = 2048;     // union columns per workgroup slice of a run, at least
+constexpr int kRunTargetSlices = 4096; // ... and about this many slices over all runs of a large matrix
 hipError_t launch_reduce_tiles(const SpmmArgs& a, int32_t n_multi, const MultiRow* multi, const float* tile_partial,
                                hipStream_t s);
 hipError_t launch_gemm_f32(int64_t m, int32_t k, int32_t n, const float* X, int64_t ldx, const float* W, int64_t ldw,
@@ -231,6 +251,17 @@ struct hcspmm_plan {
     int64_t n_tile_slots;
     float* tile_partial;             // lazily sized: n_tile_slots x 16 x d
     int64_t tile_partial_elems;
+    // runs of matrix-path windows with merged column lists (the kernel that shares gathered rows through LDS)
+    int32_t* ucols;                  // per run: ascending union of its windows' column lists, at RunDesc::up
+    int32_t* wslot;                  // per window column (indexed like wcols): its position in the run's union
+    hcspmm::RunDesc* runs;
+    hcspmm::RunSlice* run_slices;
+    hcspmm::RunWin* run_wins;        // kRunWindows records per slice
+    hcspmm::MultiRow* run_multi;     // windows of runs cut into several slices (row = window id)
+    int32_t n_runs, n_run_slices, n_run_multi;
+    int64_t n_run_tile_slots;
+    int64_t run_union_cols;          // sum of the runs' union sizes
+    int32_t runs_ok;                 // the run tables exist (sorted rows, column count within the bitmap-rank range)
     int32_t rows_sorted;         // 1 when every row's column indices are non-decreasing
     int32_t slice_cols;          // condensed columns per workgroup slice of a wide window (default kSliceCols)
     int32_t mid_row, long_row;   // tier thresholds this plan was built with (defaults kMidRow, kLongRow)

@@ -32,7 +32,8 @@ const Tune& tune()
 {
     static const Tune t = {env_int("HCSPMM_TUNE_MID_ROW"), env_int("HCSPMM_TUNE_LONG_ROW"), env_int("HCSPMM_TUNE_SLICE_COLS"),
                            getenv("HCSPMM_TUNE_SERIAL") ? 1 : 0, env_int("HCSPMM_TUNE_XCD_CHUNK"), env_int("HCSPMM_TUNE_RPG"),
-                           env_int("HCSPMM_TUNE_TILES_PER_WAVE"), getenv("HCSPMM_TUNE_NO_ROWS16") ? 1 : 0};
+                           env_int("HCSPMM_TUNE_TILES_PER_WAVE"), getenv("HCSPMM_TUNE_NO_ROWS16") ? 1 : 0,
+                           getenv("HCSPMM_TUNE_RUNS") ? 1 : 0, env_int("HCSPMM_TUNE_RUN_SLICE")};
     return t;
 }
 
@@ -419,6 +420,65 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     HC_TRY(launch_compact_ids(W, f_small, pos_c, p->mfma_small, stream));
     HC_TRY(launch_compact_ids(W, f_big, pos_d, p->mfma_big, stream));
     HC_TRY(launch_compact_ids(W, f_midw, pos_e, p->mfma_mid, stream));
+    // Runs of matrix-path windows (kRunWindows consecutive list entries each): merged column lists and slots on the
+    // device, the slice layout on the host from the union sizes (a few bytes per run cross the bus).
+    p->runs_ok = 0;
+    if (p->n_mfma > 0 && p->rows_sorted && p->n_cols <= kRankMaxCols && (p->opt.matrix_kernels == HCSPMM_MATRIX_RUNS || tune().runs)) {
+        const int32_t n_runs = (p->n_mfma + kRunWindows - 1) / kRunWindows;
+        HC_ALLOC(keep, p->ucols, p->total_ncols);
+        HC_ALLOC(keep, p->wslot, p->total_ncols);
+        HC_ALLOC(keep, p->runs, n_runs);
+        HC_TRY(hipMemsetAsync(p->wslot, 0xff, (size_t)p->total_ncols * sizeof(int32_t), stream));   // -1 where no run owns the column
+        HC_TRY(launch_run_union(n_runs, p->mfma_windows, p->n_mfma, p->ncols, p->wptr, p->wcols, p->ucols, p->wslot, p->runs,
+                                stream));
+        std::vector<RunDesc> h_runs((size_t)n_runs);
+        std::vector<int32_t> h_list((size_t)p->n_mfma);
+        HC_TRY(hipMemcpyAsync(h_runs.data(), p->runs, (size_t)n_runs * sizeof(RunDesc), hipMemcpyDeviceToHost, stream));
+        HC_TRY(hipMemcpyAsync(h_list.data(), p->mfma_windows, (size_t)p->n_mfma * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+        HC_TRY(hipStreamSynchronize(stream));
+        int64_t u_total = 0;
+        for (const RunDesc& r : h_runs) u_total += r.nu;
+        int64_t slice_u = (u_total / kRunTargetSlices + 63) / 64 * 64;
+        if (slice_u < kRunMinSlice) slice_u = kRunMinSlice;
+        if (tune().run_slice >= 64) slice_u = tune().run_slice / 64 * 64;
+        std::vector<RunSlice> h_slices;
+        std::vector<MultiRow> h_multi;
+        int64_t slots = 0;
+        for (int32_t r = 0; r < n_runs; ++r) {
+            RunDesc& rd = h_runs[(size_t)r];
+            const int32_t ns = (int32_t)((rd.nu + slice_u - 1) / slice_u);
+            rd.n_slices = ns < 1 ? 1 : ns;
+            rd.slot0 = 0;
+            if (rd.n_slices > 1) {
+                if (slots + (int64_t)rd.nw * rd.n_slices >= ((int64_t)1 << 27)) { set_error("too many partial tiles"); st = HCSPMM_EUNSUPPORTED; goto fail; }
+                rd.slot0 = (int32_t)slots;
+                for (int32_t i = 0; i < rd.nw; ++i)
+                    h_multi.push_back(MultiRow{h_list[(size_t)rd.first + i], rd.slot0 + i * rd.n_slices, rd.n_slices, 0});
+                slots += (int64_t)rd.nw * rd.n_slices;
+            }
+            for (int32_t q = 0; q < rd.n_slices; ++q) {
+                const int64_t b = (int64_t)q * slice_u;
+                h_slices.push_back(RunSlice{rd.up, r, (int32_t)b, (int32_t)(b + slice_u < rd.nu ? b + slice_u : rd.nu), q, rd.nw,
+                                            rd.n_slices, rd.slot0, {0, 0, 0}});
+            }
+        }
+        p->n_runs = n_runs;
+        p->n_run_slices = (int32_t)h_slices.size();
+        p->n_run_multi = (int32_t)h_multi.size();
+        p->n_run_tile_slots = slots;
+        p->run_union_cols = u_total;
+        HC_ALLOC(keep, p->run_slices, h_slices.size());
+        HC_ALLOC(keep, p->run_multi, h_multi.size());
+        HC_TRY(hipMemcpyAsync(p->runs, h_runs.data(), (size_t)n_runs * sizeof(RunDesc), hipMemcpyHostToDevice, stream));
+        HC_TRY(hipMemcpyAsync(p->run_slices, h_slices.data(), h_slices.size() * sizeof(RunSlice), hipMemcpyHostToDevice, stream));
+        if (!h_multi.empty())
+            HC_TRY(hipMemcpyAsync(p->run_multi, h_multi.data(), h_multi.size() * sizeof(MultiRow), hipMemcpyHostToDevice, stream));
+        HC_ALLOC(keep, p->run_wins, h_slices.size() * kRunWindows);
+        HC_TRY(launch_run_wins(p->n_run_slices, p->run_slices, p->runs, p->mfma_windows, p->ncols, p->wptr, n_rows, p->rowptr,
+                               p->run_wins, stream));
+        HC_TRY(hipStreamSynchronize(stream));                    // the host vectors go out of scope
+        p->runs_ok = 1;
+    }
     if (W > 0) HC_TRY(launch_masked_copy(W, f_big, p->ncols, nnz_if, stream));     // nnz_if <- ncols of wide windows, else 0
     // workgroup slices: one per medium window, slice_cols condensed columns each for wide windows
     {
@@ -545,12 +605,15 @@ fail:
     return st;
 }
 
+// partial tiles a call may need: the slices of wide windows, or of wide runs when the run kernel serves the matrix path
+static int64_t tile_slots(const hcspmm_plan* p) { return p->n_tile_slots > p->n_run_tile_slots ? p->n_tile_slots : p->n_run_tile_slots; }
+
 // Scratch of one SpMM call: partial rows of long rows cut into several segments, then partial tiles of
 // wide windows cut into several slices (each part padded to 256 bytes).
 static size_t spmm_scratch_bytes(const hcspmm_plan* p, int32_t d, size_t* tile_off)
 {
     const size_t part = ((size_t)p->n_slots * (size_t)d * sizeof(float) + 255) & ~(size_t)255;
-    const size_t tiles = ((size_t)p->n_tile_slots * kH * (size_t)d * sizeof(float) + 255) & ~(size_t)255;
+    const size_t tiles = ((size_t)tile_slots(p) * kH * (size_t)d * sizeof(float) + 255) & ~(size_t)255;
     if (tile_off) *tile_off = part;
     return part + tiles;
 }
@@ -583,9 +646,9 @@ static hcspmm_status run_spmm(const hcspmm_plan* plan, const SpmmArgs& a, hipStr
         p->partial_elems = want;
         partial = p->partial;
     }
-    if (!scratch_mem && p->n_tile_slots > 0 && p->tile_partial_elems < p->n_tile_slots * kH * (int64_t)a.d) {
+    if (!scratch_mem && tile_slots(p) > 0 && p->tile_partial_elems < tile_slots(p) * kH * (int64_t)a.d) {
         if (p->tile_partial) { HC_HIP(hipStreamSynchronize(stream)); (void)hipFree(p->tile_partial); p->tile_partial = nullptr; }
-        const int64_t want = p->n_tile_slots * kH * (int64_t)a.d;
+        const int64_t want = tile_slots(p) * kH * (int64_t)a.d;
         if (hipMalloc((void**)&p->tile_partial, (size_t)want * sizeof(float)) != hipSuccess) {
             (void)hipGetLastError();
             p->tile_partial = nullptr;
@@ -596,8 +659,9 @@ static hcspmm_status run_spmm(const hcspmm_plan* plan, const SpmmArgs& a, hipStr
         p->tile_partial_elems = want;
         tile_partial = p->tile_partial;
     }
-    const bool has_wg = p->n_big_slices > 0 || p->n_mfma_mid > 0;
-    const bool has_small = p->n_mfma_small > 0;
+    const bool use_runs = p->runs_ok && !upd && mfma_run_shape_supported(a);
+    const bool has_wg = use_runs ? p->n_run_slices > 0 : (p->n_big_slices > 0 || p->n_mfma_mid > 0);
+    const bool has_small = !use_runs && p->n_mfma_small > 0;
     const bool has_csr = p->n_segs > 0 || p->n_mid > 0 || p->n_short > 0;
     // The paths own disjoint rows of Y.  When more than one has work (and the stages are not being
     // timed one by one) they run side by side: the matrix-path kernels on the plan's two side
@@ -610,14 +674,21 @@ static hcspmm_status run_spmm(const hcspmm_plan* plan, const SpmmArgs& a, hipStr
         if (has_small && (has_csr || has_wg)) { s_small = p->side[1]; HC_HIP(hipStreamWaitEvent(s_small, p->ev_fork, 0)); }
     }
     if (ev) HC_HIP(hipEventRecord(ev[0], stream));
-    HC_HIP(launch_mfma_wg(a, p->n_big_slices, p->big_slices, p->ncols, p->wptr, p->wcols, p->erc, p->rows_sorted,
-                          p->big_slice_rows, tile_partial, true, s_wg));
-    HC_HIP(launch_reduce_tiles(a, p->n_tile_multi, p->tile_multi, tile_partial, s_wg));
-    HC_HIP(launch_mfma_wg(a, p->n_mfma_mid, p->mid_slices, p->ncols, p->wptr, p->wcols, p->erc, p->rows_sorted,
-                          nullptr, tile_partial, false, s_wg));
-    if (ev) HC_HIP(hipEventRecord(ev[1], stream));
-    HC_HIP(launch_mfma_small(a, p->n_mfma_small, p->mfma_small_desc, p->wcols, p->erc, s_small, upd));
-    if (ev) HC_HIP(hipEventRecord(ev[2], stream));
+    if (use_runs) {
+        // every matrix-path window through the run kernel: neighbouring windows share their gathered rows in LDS
+        HC_HIP(launch_mfma_run(a, p->n_run_slices, p->run_slices, p->run_wins, p->ucols, p->wslot, p->erc, tile_partial, s_wg));
+        HC_HIP(launch_reduce_tiles(a, p->n_run_multi, p->run_multi, tile_partial, s_wg));
+        if (ev) { HC_HIP(hipEventRecord(ev[1], stream)); HC_HIP(hipEventRecord(ev[2], stream)); }
+    } else {
+        HC_HIP(launch_mfma_wg(a, p->n_big_slices, p->big_slices, p->ncols, p->wptr, p->wcols, p->erc, p->rows_sorted,
+                              p->big_slice_rows, tile_partial, true, s_wg));
+        HC_HIP(launch_reduce_tiles(a, p->n_tile_multi, p->tile_multi, tile_partial, s_wg));
+        HC_HIP(launch_mfma_wg(a, p->n_mfma_mid, p->mid_slices, p->ncols, p->wptr, p->wcols, p->erc, p->rows_sorted,
+                              nullptr, tile_partial, false, s_wg));
+        if (ev) HC_HIP(hipEventRecord(ev[1], stream));
+        HC_HIP(launch_mfma_small(a, p->n_mfma_small, p->mfma_small_desc, p->wcols, p->erc, s_small, upd));
+        if (ev) HC_HIP(hipEventRecord(ev[2], stream));
+    }
     if (upd)        // the fused launch walks every row: its tile tier also takes the shorter mid rows
         HC_HIP(launch_csr(a, p->n_segs, p->segs, partial, p->n_mid, p->mid_rows, p->n_csr > 0 ? p->n_rows : 0, nullptr,
                           p->route, p->fused_mid_row, stream, upd));
@@ -716,7 +787,7 @@ hcspmm_status hcspmm_prepare(int32_t n_rows, int32_t n_cols, int64_t nnz, const 
     if (o.mfma_dtype < 0 || o.mfma_dtype > 2) { set_error("bad mfma_dtype"); return HCSPMM_EINVAL; }
     if (o.d_hint < 0) { set_error("bad d_hint"); return HCSPMM_EINVAL; }
     if (o.update_fusion < 0 || o.update_fusion > 2) { set_error("bad update_fusion"); return HCSPMM_EINVAL; }
-    if (o.reserved != 0) { set_error("options.reserved must be 0"); return HCSPMM_EINVAL; }
+    if (o.matrix_kernels < 0 || o.matrix_kernels > 2) { set_error("bad matrix_kernels"); return HCSPMM_EINVAL; }
     hcspmm_plan* p = new (std::nothrow) hcspmm_plan();
     if (!p) { set_error("host allocation failed"); return HCSPMM_EALLOC; }
     memset(p, 0, sizeof *p);
@@ -788,6 +859,9 @@ hcspmm_status hcspmm_plan_info(const hcspmm_plan* p, hcspmm_plan_info_t* info)
     info->n_mid_rows = p->n_mid;
     info->nnz_long = p->nnz_long; info->n_mfma_small = p->n_mfma_small;
     info->n_mfma_big = p->n_mfma_mid + p->n_mfma_big;
+    info->n_runs = p->runs_ok ? p->n_runs : 0;
+    info->n_run_slices = p->runs_ok ? p->n_run_slices : 0;
+    info->run_union_cols = p->runs_ok ? p->run_union_cols : 0;
     return HCSPMM_OK;
 }
 
@@ -812,6 +886,23 @@ hcspmm_status hcspmm_plan_export(const hcspmm_plan* p, int32_t* ncols, int32_t* 
     }
     if (mfma_windows && p->n_mfma) HC_HIP(hipMemcpy(mfma_windows, p->mfma_windows, (size_t)p->n_mfma * 4, hipMemcpyDeviceToHost));
     if (csr_windows && p->n_csr) HC_HIP(hipMemcpy(csr_windows, p->csr_windows, (size_t)p->n_csr * 4, hipMemcpyDeviceToHost));
+    return HCSPMM_OK;
+}
+
+hcspmm_status hcspmm_plan_export_runs(const hcspmm_plan* p, int32_t* run_nu, int32_t* ucols, int32_t* wslot)
+{
+    if (!p) { set_error("plan is NULL"); return HCSPMM_EINVAL; }
+    if (!p->runs_ok) { set_error("the plan has no run table (prepare with matrix_kernels = HCSPMM_MATRIX_RUNS)"); return HCSPMM_EINVAL; }
+    HC_HIP(hipDeviceSynchronize());
+    std::vector<RunDesc> h_runs((size_t)p->n_runs);
+    HC_HIP(hipMemcpy(h_runs.data(), p->runs, h_runs.size() * sizeof(RunDesc), hipMemcpyDeviceToHost));
+    int64_t at = 0;
+    for (const RunDesc& r : h_runs) {
+        if (run_nu) run_nu[&r - h_runs.data()] = r.nu;
+        if (ucols && r.nu > 0) HC_HIP(hipMemcpy(ucols + at, p->ucols + r.up, (size_t)r.nu * sizeof(int32_t), hipMemcpyDeviceToHost));
+        at += r.nu;
+    }
+    if (wslot && p->total_ncols > 0) HC_HIP(hipMemcpy(wslot, p->wslot, (size_t)p->total_ncols * sizeof(int32_t), hipMemcpyDeviceToHost));
     return HCSPMM_OK;
 }
 

@@ -699,6 +699,122 @@ hipError_t launch_condense_rank(int32_t n_list, const int32_t* list, int32_t n_r
 }
 
 // ------------------------------------------------------------------------------------------------
+// runs of matrix-path windows: the union of the windows' column lists and every window column's
+// position in it, by the same bitmap ranks (the lists are ascending, the union comes out ascending)
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void k_run_union(const int32_t* __restrict__ win_list, int32_t n_list,
+                                                    const int32_t* __restrict__ ncols, const int64_t* __restrict__ wptr,
+                                                    const int32_t* __restrict__ wcols, int32_t* __restrict__ ucols,
+                                                    int32_t* __restrict__ wslot, RunDesc* __restrict__ runs)
+{
+    __shared__ uint32_t bm[kRankWords];
+    __shared__ int32_t pre[kRankWords];
+    __shared__ int smem[1024 / 64 + 1];
+    constexpr int kBits = kRankWords * 32;
+    constexpr int kWordsPerThread = kRankWords / 1024;
+    const int32_t first = blockIdx.x * kRunWindows;
+    const int nw = min(kRunWindows, n_list - first);
+    int64_t wp[kRunWindows];
+    int32_t nc[kRunWindows];
+    int32_t lo = 0x7fffffff, hi = -1;
+    for (int i = 0; i < nw; ++i) {
+        const int32_t w = win_list[first + i];
+        wp[i] = wptr[w];
+        nc[i] = ncols[w];
+        if (nc[i] > 0) {
+            lo = min(lo, wcols[wp[i]]);
+            hi = max(hi, wcols[wp[i] + nc[i] - 1]);
+        }
+    }
+    const int64_t up = wp[0];                                  // the union is stored where the run's first window's list starts
+    int32_t running = 0;
+    const int w0 = threadIdx.x * kWordsPerThread;
+    for (int64_t base = lo & ~31; base <= hi; base += kBits) {
+        for (int i = threadIdx.x; i < kRankWords; i += 1024) bm[i] = 0u;
+        __syncthreads();
+        for (int i = 0; i < nw; ++i)
+            for (int32_t k = threadIdx.x; k < nc[i]; k += 1024) {
+                const int64_t c = (int64_t)wcols[wp[i] + k] - base;
+                if (c >= 0 && c < kBits) atomicOr(&bm[c >> 5], 1u << (c & 31));
+            }
+        __syncthreads();
+        int cnt = 0;
+#pragma unroll 4
+        for (int i = 0; i < kWordsPerThread; ++i) cnt += __popc(bm[w0 + i]);
+        int total;
+        const int off = block_exclusive_scan<1024>(cnt, &total, smem);
+        {
+            int run = off;
+            int32_t* out = ucols + up + running + off;
+            for (int i = 0; i < kWordsPerThread; ++i) {
+                uint32_t bits = bm[w0 + i];
+                pre[w0 + i] = run;
+                run += __popc(bits);
+                while (bits) {
+                    const int b = __ffs(bits) - 1;
+                    bits &= bits - 1;
+                    *out++ = (int32_t)(base + (int64_t)(w0 + i) * 32 + b);
+                }
+            }
+        }
+        __syncthreads();
+        for (int i = 0; i < nw; ++i)
+            for (int32_t k = threadIdx.x; k < nc[i]; k += 1024) {
+                const int64_t c = (int64_t)wcols[wp[i] + k] - base;
+                if (c < 0 || c >= kBits) continue;
+                const int word = (int)(c >> 5);
+                wslot[wp[i] + k] = running + pre[word] + __popc(bm[word] & ((1u << (c & 31)) - 1u));
+            }
+        running += total;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        RunDesc rd;
+        rd.up = up; rd.first = first; rd.nw = nw; rd.nu = running;
+        rd.n_slices = 1; rd.slot0 = 0; rd.pad = 0;              // slices are laid out by the host from the union sizes
+        runs[blockIdx.x] = rd;
+    }
+}
+
+// per slice and wave: the window the wave owns, with what the kernel needs to start on it
+__global__ __launch_bounds__(256) void k_run_wins(int32_t n_slices, const RunSlice* __restrict__ slices,
+                                                  const RunDesc* __restrict__ runs, const int32_t* __restrict__ win_list,
+                                                  const int32_t* __restrict__ ncols, const int64_t* __restrict__ wptr,
+                                                  int32_t n_rows, const int32_t* __restrict__ rowptr, RunWin* __restrict__ wins)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (int64_t)n_slices * kRunWindows) return;
+    const RunDesc rd = runs[slices[t / kRunWindows].run];
+    const int i = (int)(t % kRunWindows);
+    const int32_t w = win_list[rd.first + (i < rd.nw ? i : 0)];
+    RunWin rw;
+    rw.w = w; rw.nc = ncols[w]; rw.wp = wptr[w]; rw.pad = 0;
+    rw.k_last = rowptr[min((int64_t)w * kH + kH, (int64_t)n_rows)] - 1;
+    wins[t] = rw;
+}
+
+hipError_t launch_run_wins(int32_t n_slices, const RunSlice* slices, const RunDesc* runs, const int32_t* win_list,
+                           const int32_t* ncols, const int64_t* wptr, int32_t n_rows, const int32_t* rowptr, RunWin* wins,
+                           hipStream_t s)
+{
+    if (n_slices <= 0) return hipSuccess;
+    const int64_t n = (int64_t)n_slices * kRunWindows;
+    hipLaunchKernelGGL(k_run_wins, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n_slices, slices, runs, win_list, ncols,
+                       wptr, n_rows, rowptr, wins);
+    return hipGetLastError();
+}
+
+hipError_t launch_run_union(int32_t n_runs, const int32_t* win_list, int32_t n_list, const int32_t* ncols,
+                            const int64_t* wptr, const int32_t* wcols, int32_t* ucols, int32_t* wslot, RunDesc* runs,
+                            hipStream_t s)
+{
+    if (n_runs <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_run_union, dim3(n_runs), dim3(1024), 0, s, win_list, n_list, ncols, wptr, wcols, ucols, wslot,
+                       runs);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
 // selection (Section IV-C): z' = c0*H*ncols^2 + c1*(H*ncols - nnzw) + c2*H*ncols ; matrix path iff z' < 0
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_select(int32_t W, const int32_t* __restrict__ ncols,

@@ -38,6 +38,7 @@ namespace hcspmm {
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef short v4s __attribute__((ext_vector_type(4)));
 typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 
 // ------------------------------------------------------------------------------------------------
 // Path policies.  A policy fixes, for one element kind XK (0 fp32, 1 bf16, 2 fp16), lane vector
@@ -551,6 +552,267 @@ __global__ __launch_bounds__(256) void k_mfma_wg(const WgSlice* __restrict__ sli
     }
 }
 
+// ---- workgroup per run of windows: gathered X rows shared through LDS -------------------------
+// Neighbouring windows share columns (a community's members, a power-law graph's hubs), and on the
+// matrix path loading X is the larger part of the work (Section IV-B, Table I).  Here a workgroup owns a
+// RUN of up to four consecutive matrix-path windows, one per wave.  Preprocessing merges the windows'
+// column lists into the run's ascending UNION list and gives every condensed column of a window its
+// position ("slot") in that union.  The workgroup walks the union in chunks of UC columns: all 256
+// threads fetch the chunk's X rows ONCE into LDS (requests for chunk c+1 are in flight during the
+// matrix work of chunk c; two LDS buffers alternate, one barrier per chunk), and every wave multiplies
+// ITS OWN window's condensed columns that fall into the chunk -- a contiguous range of its list, since
+// both lists ascend -- taking the B operands from the staged rows by slot.  The dense A tile is still
+// the 16-row window's own (the MFMA work does not grow with the run), only the row fetches shrink to
+// the union's.  The A slice of a chunk is rebuilt in the wave's private LDS tile from the rows'
+// non-zeros with per-row cursors (rows are sorted, so a row's entries inside a column range are
+// contiguous; four lanes per row).  Wide runs are cut into slices of the union; a slice's waves find
+// their starting cursors by binary search and write partial tiles that k_reduce_tiles adds in slice order.
+// staging of one chunk of union rows: piece i of this thread is bytes [soff[i], soff[i] + 16) of staged row srow[i];
+// rows past the chunk's end repeat its last row, so every staged LDS row holds finite data
+template <int NPT>
+__device__ __forceinline__ void run_request(v4u (&stg)[NPT], const int (&srow)[NPT], const int (&soff)[NPT], int32_t uc_reg,
+                                            int n_rows_chunk, const char* __restrict__ X, int64_t ldxb)
+{
+#pragma unroll
+    for (int i = 0; i < NPT; ++i) {
+        const int32_t c = __shfl(uc_reg, min(srow[i], n_rows_chunk - 1), 64);
+        stg[i] = *reinterpret_cast<const v4u*>(X + (int64_t)c * ldxb + soff[i]);
+    }
+}
+
+template <int NPT, int UC, int PITCH>
+__device__ __forceinline__ void run_park(const v4u (&stg)[NPT], const int (&srow)[NPT], const int (&soff)[NPT],
+                                         char* __restrict__ buf)
+{
+#pragma unroll
+    for (int i = 0; i < NPT; ++i)
+        if (srow[i] < UC) *reinterpret_cast<v4u*>(buf + srow[i] * PITCH + soff[i]) = stg[i];
+}
+
+struct RunCursor {
+    int32_t k;          // wave: next condensed column of the window
+    int32_t cur;        // lane: next non-zero of row lane/4
+    int32_t row_e;      // lane: end of that row
+};
+
+// one K-step (four condensed columns) of a chunk on the fp32 path: B operands from the staged rows by slot
+template <int VW, int NG> struct RunStepB { float x[NG][VW]; };
+
+template <int VW, int NG, int PITCH>
+__device__ __forceinline__ void run_load_step(int q, int32_t sloc, int lane, const char* __restrict__ xb, int d,
+                                              RunStepB<VW, NG>& b)
+{
+    const int j = lane & 15, kk = lane >> 4;
+    const int32_t c = __shfl(sloc, 4 * q + kk, 64);
+    const char* __restrict__ xr = xb + c * PITCH;
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        const int col = g * 16 * VW + VW * j;                  // columns past d read column 0 and are never stored
+        const char* p = xr + (col < d ? col : 0) * 4;
+        if constexpr (VW == 4) { const float4 v = *reinterpret_cast<const float4*>(p); b.x[g][0] = v.x; b.x[g][1] = v.y; b.x[g][2] = v.z; b.x[g][3] = v.w; }
+        else if constexpr (VW == 2) { const float2 v = *reinterpret_cast<const float2*>(p); b.x[g][0] = v.x; b.x[g][1] = v.y; }
+        else { b.x[g][0] = *reinterpret_cast<const float*>(p); }
+    }
+}
+
+template <int VW, int NG>
+__device__ __forceinline__ void run_compute_step(int q, const float* __restrict__ tile, int lane, const RunStepB<VW, NG>& b,
+                                                 v4f (&acc)[NG][VW])
+{
+    const float av = tile[64 * q + lane];                      // A(row lane%16, column 4q + lane/16)
+#pragma unroll
+    for (int g = 0; g < NG; ++g)
+#pragma unroll
+        for (int t = 0; t < VW; ++t) acc[g][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, b.x[g][t], acc[g][t], 0, 0, 0);
+}
+
+template <int XK, int VW, int NG, int UC>
+__global__ __launch_bounds__(256) void k_mfma_run(const RunSlice* __restrict__ slices, const RunWin* __restrict__ wins,
+                                                   const int32_t* __restrict__ ucols, const int32_t* __restrict__ wslot,
+                                                   const int32_t* __restrict__ erc, float* __restrict__ tile_partial,
+                                                   int col0, SpmmArgs a)
+{
+    using P = Path<XK, VW, NG>;
+    constexpr int ES = P::ES;
+    constexpr int SPANB = NG * 16 * VW * ES;                   // bytes of one X row's share of this launch
+    constexpr int PITCH = SPANB + 16;                          // LDS row pitch: neighbouring rows start 4 banks apart
+    constexpr int NPT = UC * SPANB / 16 / 256 > 0 ? UC * SPANB / 16 / 256 : 1;   // 16-byte pieces per thread and chunk
+    constexpr int NST = UC / P::SCOLS;                         // pipeline stages per chunk (16-bit path)
+    static_assert(UC % P::SCOLS == 0 && UC <= 64, "a chunk is a whole number of stages and fits one lane per column");
+    __shared__ __align__(16) char xs[2][UC * PITCH];
+    __shared__ __align__(16) float tiles[4][UC * 16];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    // everything a workgroup needs to start comes from two records read side by side: the slice, and this wave's window
+    const RunSlice sl = slices[blockIdx.x];
+    const RunWin wn = wins[(int64_t)blockIdx.x * kRunWindows + wave];
+    const int32_t u_begin = sl.u_begin, u_end = sl.u_end;
+    const int64_t up = sl.up;
+    const char* __restrict__ X = static_cast<const char*>(a.X) + (int64_t)col0 * ES;
+    const int64_t ldxb = a.ldx * ES;
+    const int d = min(a.d - col0, NG * 16 * VW);
+    const int ppr = (d * ES + 15) >> 4;                        // 16-byte pieces per staged row
+
+    // Waves beyond the run's last window only help staging: their record repeats the run's first window and every
+    // column is masked out, so that all waves execute the same straight-line sequence of loads (a load inside a
+    // branch makes the compiler wait for ALL outstanding loads at the next join, the staged rows included).
+    const bool has_win = wave < sl.nw;
+    const int32_t nc = wn.nc, r0 = wn.w * kH, k_last = wn.k_last;
+    const int64_t wp = wn.wp;
+
+    // staging map of this thread: piece p = tid + 256 i of a chunk is bytes [soff, soff + 16) of staged row `srow`
+    int srow[NPT], soff[NPT];
+#pragma unroll
+    for (int i = 0; i < NPT; ++i) {
+        const int pidx = threadIdx.x + 256 * i;
+        srow[i] = pidx / ppr;
+        soff[i] = (pidx - srow[i] * ppr) * 16;
+    }
+    auto union_ids = [&](int32_t cb) { return ucols[up + min(cb + lane, u_end - 1)]; };
+    // two chunks of rows are in flight: while chunk c is multiplied, chunk c+1 waits in registers for its LDS buffer
+    // and chunk c+2 is on its way
+    v4u stg_a[NPT], stg_b[NPT];
+    const int32_t uc0 = union_ids(u_begin), uc1 = union_ids(u_begin + UC);
+    int32_t uc_next = union_ids(u_begin + 2 * UC);
+    run_request<NPT>(stg_a, srow, soff, uc0, min(UC, u_end - u_begin), X, ldxb);
+
+    RunCursor cs{0, 0, 0};
+    {
+        const int32_t row = min(r0 + (lane >> 2), a.n_rows);
+        cs.cur = a.rowptr[row];
+        cs.row_e = a.rowptr[min(row + 1, a.n_rows)];
+        if (u_begin > 0) {
+            // first condensed column at or beyond the slice, then every row's first non-zero at or beyond it
+            int32_t lo = 0, hi = nc;
+            while (lo < hi) { const int32_t mid = (lo + hi) >> 1; if (wslot[wp + mid] < u_begin) lo = mid + 1; else hi = mid; }
+            cs.k = lo;
+            int32_t a0 = cs.cur, a1 = cs.row_e;
+            while (a0 < a1) { const int32_t mid = a0 + ((a1 - a0) >> 1); if ((erc[mid] >> 4) < lo) a0 = mid + 1; else a1 = mid; }
+            cs.cur = a0;
+        }
+    }
+    float* __restrict__ tile = tiles[wave];
+    v4f acc[NG][VW];
+#pragma unroll
+    for (int g = 0; g < NG; ++g)
+#pragma unroll
+        for (int t = 0; t < VW; ++t) acc[g][t] = (v4f){0.f, 0.f, 0.f, 0.f};
+
+    // the next kRound*4 non-zeros of every row, four lanes per row; slots past the row's end are marked, their loads
+    // are clamped to a valid index and issued all the same
+    constexpr int kRound = 2;
+    int32_t pr[kRound];
+    float vr[kRound];
+    auto fetch_round = [&]() {
+#pragma unroll
+        for (int j = 0; j < kRound; ++j) {
+            const int32_t k = cs.cur + 4 * j + (lane & 3);
+            const int32_t kc = min(k, k_last);
+            const int32_t pe = erc[kc];
+            const float ve = a.vals[kc];
+            pr[j] = k < cs.row_e ? pe : 0x7fffffff;
+            vr[j] = ve;
+        }
+    };
+    int32_t s_cur = wslot[wp + min(cs.k + lane, nc - 1)];
+    fetch_round();
+    run_request<NPT>(stg_b, srow, soff, uc1, max(1, min(UC, u_end - u_begin - UC)), X, ldxb);
+
+    const int n_chunks = (u_end - u_begin + UC - 1) / UC;
+    // one chunk: request the rows of chunk c+2 into `stg_req`, multiply chunk c out of xs[c & 1], then move chunk c+1
+    // from `stg_park` into the other buffer
+    auto chunk = [&](int c, v4u (&stg_req)[NPT], const v4u (&stg_park)[NPT]) {
+        const int32_t cb = u_begin + c * UC, ce = min(cb + UC, u_end);
+        // the window's columns inside this chunk: [k, k + n)
+        const int n = has_win ? __popcll(__ballot(cs.k + lane < nc && s_cur < ce)) : 0;
+        const int32_t sloc = min(max(s_cur - cb, 0), UC - 1);
+        const int32_t limit = cs.k + n;
+        if (n > 0) {
+            const int nz = ((n + P::SCOLS - 1) / P::SCOLS) * P::SCOLS * 16;      // floats of the tile the K-steps will read
+            for (int i = lane * 4; i < nz; i += 256)
+                *reinterpret_cast<float4*>(&tile[i]) = make_float4(0.f, 0.f, 0.f, 0.f);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            const int shift = lane & ~3;
+            bool more;
+            {
+                int taken = 0;
+#pragma unroll
+                for (int j = 0; j < kRound; ++j) {
+                    const bool take = (pr[j] >> 4) < limit;             // marked slots compare as beyond every limit
+                    const float vv = take ? vr[j] : 0.f;                // the value is consumed outside the masked store
+                    if (take) atomicAdd(&tile[P::tidx((pr[j] >> 4) - cs.k, lane >> 2)], vv);
+                    taken += __popcll((__ballot(take) >> shift) & 0xfull);
+                }
+                cs.cur += taken;
+                more = taken == 4 * kRound;                             // the row may have further entries inside the range
+            }
+            while (__any(more)) {                                       // rare: a row with more than kRound*4 entries in one chunk
+                int taken = 0;
+#pragma unroll
+                for (int j = 0; j < kRound; ++j) {
+                    const int32_t k = cs.cur + 4 * j + (lane & 3);
+                    const int32_t kc = min(k, k_last);
+                    const int32_t pe = erc[kc];
+                    const float ve = a.vals[kc];
+                    const bool take = more && k < cs.row_e && (pe >> 4) < limit;
+                    const float vv = take ? ve : 0.f;
+                    if (take) atomicAdd(&tile[P::tidx((pe >> 4) - cs.k, lane >> 2)], vv);
+                    taken += __popcll((__ballot(take) >> shift) & 0xfull);
+                }
+                cs.cur += taken;
+                more = more && taken == 4 * kRound;
+            }
+        }
+        cs.k = limit;
+        // Requested before this chunk's matrix work, in this order (outstanding loads are counted in order of issue, so
+        // whatever is needed first has to be requested first): the next chunk's slots and first round of non-zeros, the
+        // union ids of chunk c+3, then the rows of chunk c+2, which stay in flight until the end of chunk c+1.
+        const int32_t s_next = wslot[wp + min(cs.k + lane, nc - 1)];
+        fetch_round();
+        const int32_t uc_req = uc_next;
+        uc_next = union_ids(cb + 3 * UC);
+        run_request<NPT>(stg_req, srow, soff, uc_req, max(1, min(UC, u_end - cb - 2 * UC)), X, ldxb);
+        if (n > 0) {
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            const char* __restrict__ xb = xs[c & 1];
+            if constexpr (XK == 0) {
+                // K-steps of four columns, only as many as the window has columns in this chunk
+                const int nk = (n + 3) >> 2;
+                RunStepB<VW, NG> b0, b1;
+                run_load_step<VW, NG, PITCH>(0, sloc, lane, xb, d, b0);
+                for (int q = 0; q < nk; q += 2) {
+                    run_load_step<VW, NG, PITCH>(min(q + 1, nk - 1), sloc, lane, xb, d, b1);
+                    run_compute_step<VW, NG>(q, tile, lane, b0, acc);
+                    run_load_step<VW, NG, PITCH>(min(q + 2, nk - 1), sloc, lane, xb, d, b0);
+                    if (q + 1 < nk) run_compute_step<VW, NG>(q + 1, tile, lane, b1, acc);
+                }
+            } else {
+                typename P::Buf xa[2];
+                P::load(0, sloc, lane, xb, PITCH, d, xa[0]);
+#pragma unroll
+                for (int st = 0; st < NST; ++st) {
+                    if (st + 1 < NST) P::load(st + 1, sloc, lane, xb, PITCH, d, xa[(st + 1) & 1]);
+                    if (st * P::SCOLS < n) P::compute(st, tile, lane, xa[st & 1], acc);
+                }
+            }
+        }
+        s_cur = s_next;
+        run_park<NPT, UC, PITCH>(stg_park, srow, soff, xs[(c + 1) & 1]);
+        __syncthreads();
+    };
+    run_park<NPT, UC, PITCH>(stg_a, srow, soff, xs[0]);
+    __syncthreads();
+    // chunks are taken in pairs (the register sets alternate); an odd count ends with one empty chunk rather than a
+    // branch around the second half, whose loads would otherwise cost a full wait at the join
+    for (int c = 0; c < n_chunks; c += 2) {
+        chunk(c, stg_a, stg_b);
+        chunk(c + 1, stg_b, stg_a);
+    }
+    if (has_win) {
+        if (sl.n_slices == 1) store_tile<VW, NG>(acc, lane, r0, a.n_rows, a.Y + col0, a.ldy, d, a.relu);
+        else store_tile<VW, NG>(acc, lane, (sl.slot0 + wave * sl.n_slices + sl.q) * kH, 0x7fffffff, tile_partial + col0, a.d, d, 0);
+    }
+}
+
 // windows cut into several column slices: add the slices' 16 x d partial tiles in slice order
 __global__ __launch_bounds__(256) void k_reduce_tiles(const MultiRow* __restrict__ multi,
                                                       const float* __restrict__ tile_partial, SpmmArgs a)
@@ -688,6 +950,38 @@ hipError_t launch_mfma_wg(const SpmmArgs& a, int32_t n_list, const WgSlice* slic
                            erc, rows_sorted, slice_rows, tile_partial, col0, a)
         HC_MFMA_DISPATCH(HC_LAUNCH_MB)
 #undef HC_LAUNCH_MB
+    }
+    return hipGetLastError();
+}
+
+// The run kernel stages whole 16-byte pieces of X rows: fp32 rows in float4 steps, 16-bit rows in steps of 8 elements.
+bool mfma_run_shape_supported(const SpmmArgs& a)
+{
+    MfmaShape sh;
+    if (!pick_mfma_shape(a, sh)) return false;
+    const uintptr_t px = (uintptr_t)a.X;
+    if (a.x_dtype == HCSPMM_F32) return a.d % 4 == 0 && a.ldx % 4 == 0 && px % 16 == 0;
+    return a.d % 8 == 0 && a.ldx % 8 == 0 && px % 16 == 0;
+}
+
+hipError_t launch_mfma_run(const SpmmArgs& a, int32_t n_slices, const RunSlice* slices, const RunWin* wins,
+                           const int32_t* ucols, const int32_t* wslot, const int32_t* erc, float* tile_partial, hipStream_t s)
+{
+    if (n_slices <= 0) return hipSuccess;
+    MfmaShape sh;
+    if (!pick_mfma_shape(a, sh) || !mfma_run_shape_supported(a)) return hipErrorInvalidValue;
+    const int span = sh.ng * 16 * sh.vw;
+    for (int col0 = 0; col0 < a.d; col0 += span) {
+        // chunk of the union staged per step: about 16 KiB of X rows
+#define HC_LAUNCH_RUN(K, V, G)                                                                     \
+    {                                                                                              \
+        constexpr int kSpanB = G * 16 * V * (K == 0 ? 4 : 2);                                      \
+        constexpr int kUC = kSpanB >= 1024 ? 16 : (kSpanB >= 512 ? 32 : 64);                       \
+        hipLaunchKernelGGL((k_mfma_run<K, V, G, (kUC < Path<K, V, G>::SCOLS ? Path<K, V, G>::SCOLS : kUC)>),   \
+                           dim3(n_slices), dim3(256), 0, s, slices, wins, ucols, wslot, erc, tile_partial, col0, a);   \
+    }
+        HC_MFMA_DISPATCH(HC_LAUNCH_RUN)
+#undef HC_LAUNCH_RUN
     }
     return hipGetLastError();
 }

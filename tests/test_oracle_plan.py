@@ -172,3 +172,28 @@ def test_guard_applies_to_hybrid_mode_only():
     np.testing.assert_array_equal(hybrid["route"], oracle.launch_guard(expect, per_window["ncols"], per_window["nnzw"]))
     vec = oracle.derive_plan_vectorised(g.rowptr, g.colind, coef, mode=oracle.plan.ROUTE_HYBRID, n_cols=g.n_cols)
     np.testing.assert_array_equal(vec["route"], hybrid["route"])
+
+
+def test_runs_merge_the_column_lists_of_neighbouring_matrix_path_windows():
+    # hand-worked: three matrix-path windows 0, 2, 5 whose column lists overlap; run length 2 -> runs (0, 2) and (5)
+    wcols = np.array([1, 4, 9,   7,   4, 5, 9, 30,   0,   2, 30], np.int32)      # windows 0 | 1 | 2 | 3,4 (3 empty) | 5
+    wptr = np.array([0, 3, 4, 8, 8, 9, 11], np.int64)
+    runs = oracle.derive_runs([0, 2, 5], wptr, wcols, run_windows=2)
+    assert len(runs) == 2
+    assert runs[0]["windows"] == [0, 2] and runs[0]["union"].tolist() == [1, 4, 5, 9, 30]
+    assert runs[0]["slots"][0].tolist() == [0, 1, 3] and runs[0]["slots"][1].tolist() == [1, 2, 3, 4]
+    assert runs[1]["windows"] == [5] and runs[1]["union"].tolist() == [2, 30] and runs[1]["slots"][0].tolist() == [0, 1]
+    # property on a random plan: the union is strictly ascending, a slot leads back to the column, and the union has
+    # no column that none of the run's windows holds
+    g = tiny_random_csr(200, 150, 0.1, seed=8)
+    plan = oracle.derive_plan(g.rowptr, g.colind, [0, 0, -1])
+    lst = np.nonzero(plan["ncols"] > 0)[0]
+    for r in oracle.derive_runs(lst, plan["wptr"], plan["wcols"]):
+        u = r["union"]
+        assert np.all(np.diff(u) > 0)
+        seen = np.zeros(u.shape[0], bool)
+        for w, sl in zip(r["windows"], r["slots"]):
+            cols = plan["wcols"][plan["wptr"][w]:plan["wptr"][w + 1]]
+            assert np.array_equal(u[sl], cols)
+            seen[sl] = True
+        assert seen.all()
