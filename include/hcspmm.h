@@ -216,7 +216,9 @@ hcspmm_status hcspmm_plan_export_runs(const hcspmm_plan* plan, int32_t* run_nu, 
  *            HCSPMM_BF16 / HCSPMM_F16: the matrix path multiplies 16-bit
  *            operands (A values rounded to the same type) with fp32
  *            accumulation, the scalar path widens X to fp32.
- *   y_dtype  must be HCSPMM_F32.
+ *   y_dtype  HCSPMM_F32, or HCSPMM_BF16 / HCSPMM_F16: the fp32 result of either path is rounded ONCE, to
+ *            nearest even, when it is stored (the next layer can then gather 16-bit rows without a
+ *            conversion pass in between).  ldy counts elements of that type.
  * X and Y must not overlap.  1 <= d <= 2^20.  Asynchronous on `stream`.
  *
  * A plan holds scratch buffers of its own (partial rows of long rows, partial tiles of wide
@@ -298,14 +300,15 @@ hcspmm_status hcspmm_gcn_layer(const hcspmm_plan* plan, const void* d_X, int64_t
  * HCSPMM_BF16 / HCSPMM_F16 round the fp32 MFMA accumulators of the update once (nearest even) and
  * let the aggregation gather half the bytes, with the arithmetic hcspmm_spmm documents for a
  * 16-bit X (the plan should then have been prepared with mfma_dtype = t_dtype, which selects the
- * selector coefficients fitted for 16-bit gathers).  X, W and Y stay fp32; the workspace
+ * selector coefficients fitted for 16-bit gathers).  y_dtype is the element type of Y as in
+ * hcspmm_spmm (one rounding of the fp32 result when it is stored).  X and W stay fp32; the workspace
  * requirement is that of hcspmm_gcn_workspace_bytes.  HCSPMM_EUNSUPPORTED when the plan has
  * matrix-path windows and d_out / ldy do not fit the 16-bit matrix-path kernels (d_out % 4,
  * 16-byte aligned Y rows).
  */
 hcspmm_status hcspmm_gcn_layer_ex(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d_in,
                                   const void* d_W, int64_t ldw, int32_t d_out,
-                                  void* d_Y, int64_t ldy, int32_t apply_relu, int32_t t_dtype,
+                                  void* d_Y, int64_t ldy, int32_t y_dtype, int32_t apply_relu, int32_t t_dtype,
                                   void* d_workspace, size_t workspace_bytes, void* stream);
 
 size_t hcspmm_gcn_workspace_bytes(const hcspmm_plan* plan, int32_t d_in, int32_t d_out);
@@ -323,14 +326,17 @@ size_t hcspmm_gcn_workspace_bytes(const hcspmm_plan* plan, int32_t d_in, int32_t
  * d_out <= 64 on matrices of 32,768 rows or more, where that route measured faster).
  *
  *   d_X   device, n_cols x d_in, element type x_dtype (ldx >= d_in)
- *   d_W   device, d_in x d_out fp32 (ldw >= d_out);  d_Y  device, n_rows x d_out fp32 (ldy >= d_out)
+ *   d_W   device, d_in x d_out fp32 (ldw >= d_out)
+ *   d_Y   device, n_rows x d_out of element type y_dtype (ldy >= d_out, in elements): fp32, or bf16 / fp16 with one
+ *         rounding of the fp32 result when it is stored -- a chain of such layers with 16-bit X and Y needs no
+ *         conversion pass between layers
  *   d_workspace  device, at least hcspmm_aggregate_update_workspace_bytes(plan, d_in, d_out) bytes,
  *                256-byte aligned; holds Z (n_rows x d_in fp32) on return when the update was not fused
  * Asynchronous on `stream`.  Errors as hcspmm_spmm.
  */
 hcspmm_status hcspmm_aggregate_update(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d_in,
                                       int32_t x_dtype, const void* d_W, int64_t ldw, int32_t d_out,
-                                      void* d_Y, int64_t ldy, int32_t apply_relu,
+                                      void* d_Y, int64_t ldy, int32_t y_dtype, int32_t apply_relu,
                                       void* d_workspace, size_t workspace_bytes, void* stream);
 
 size_t hcspmm_aggregate_update_workspace_bytes(const hcspmm_plan* plan, int32_t d_in, int32_t d_out);

@@ -14,6 +14,7 @@ from .numeric import (  # noqa: F401
     aggregate_update,
     aggregate_update_rows,
     layer_backward,
+    round_to_16bit,
     num_threads,
     set_num_threads,
     DT_F32, DT_BF16, DT_F16, DT_F64,

@@ -95,11 +95,11 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.hcspmm_spmm_timed.restype = ctypes.c_int
     lib.hcspmm_gcn_layer.argtypes = [vp, vp, i64, i32, vp, i64, i32, vp, i64, i32, vp, ctypes.c_size_t, vp]
     lib.hcspmm_gcn_layer.restype = ctypes.c_int
-    lib.hcspmm_gcn_layer_ex.argtypes = [vp, vp, i64, i32, vp, i64, i32, vp, i64, i32, i32, vp, ctypes.c_size_t, vp]
+    lib.hcspmm_gcn_layer_ex.argtypes = [vp, vp, i64, i32, vp, i64, i32, vp, i64, i32, i32, i32, vp, ctypes.c_size_t, vp]
     lib.hcspmm_gcn_layer_ex.restype = ctypes.c_int
     lib.hcspmm_gcn_workspace_bytes.argtypes = [vp, i32, i32]
     lib.hcspmm_gcn_workspace_bytes.restype = ctypes.c_size_t
-    lib.hcspmm_aggregate_update.argtypes = [vp, vp, i64, i32, i32, vp, i64, i32, vp, i64, i32, vp, ctypes.c_size_t, vp]
+    lib.hcspmm_aggregate_update.argtypes = [vp, vp, i64, i32, i32, vp, i64, i32, vp, i64, i32, i32, vp, ctypes.c_size_t, vp]
     lib.hcspmm_aggregate_update.restype = ctypes.c_int
     lib.hcspmm_aggregate_update_workspace_bytes.argtypes = [vp, i32, i32]
     lib.hcspmm_aggregate_update_workspace_bytes.restype = ctypes.c_size_t
@@ -320,8 +320,8 @@ def hcspmm_gcn_workspace_bytes(plan: Plan, d_in: int, d_out: int) -> int:
 
 
 def hcspmm_gcn_layer(plan: Plan, X, W, Y, workspace, *, apply_relu: bool = True, stream=None):
-    """Y = act(A (X W)); workspace: a uint8/float CUDA tensor of at least hcspmm_gcn_workspace_bytes bytes."""
-    assert X.stride(1) == 1 and W.stride(1) == 1 and Y.stride(1) == 1
+    """Y = act(A (X W)), all fp32; workspace: a uint8/float CUDA tensor of at least hcspmm_gcn_workspace_bytes bytes."""
+    assert X.stride(1) == 1 and W.stride(1) == 1 and Y.stride(1) == 1 and _dtype_code(Y) == HCSPMM_F32
     _check(load_library().hcspmm_gcn_layer(plan.handle, _ptr(X), X.stride(0), X.shape[1], _ptr(W), W.stride(0),
                                            W.shape[1], _ptr(Y), Y.stride(0), 1 if apply_relu else 0, _ptr(workspace),
                                            workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
@@ -336,7 +336,7 @@ def hcspmm_aggregate_update(plan: Plan, X, W, Y, workspace, *, apply_relu: bool 
     """Y = act((A X) W); workspace: a CUDA tensor of at least hcspmm_aggregate_update_workspace_bytes bytes."""
     assert X.stride(1) == 1 and W.stride(1) == 1 and Y.stride(1) == 1
     _check(load_library().hcspmm_aggregate_update(plan.handle, _ptr(X), X.stride(0), X.shape[1], _dtype_code(X),
-                                                  _ptr(W), W.stride(0), W.shape[1], _ptr(Y), Y.stride(0),
+                                                  _ptr(W), W.stride(0), W.shape[1], _ptr(Y), Y.stride(0), _dtype_code(Y),
                                                   1 if apply_relu else 0, _ptr(workspace),
                                                   workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
     return Y
@@ -368,7 +368,7 @@ def hcspmm_gcn_layer_ex(plan: Plan, X, W, Y, workspace, *, t_dtype: int = HCSPMM
     """Y = act(A (X W)) with the intermediate X W stored as t_dtype (HCSPMM_F32 / BF16 / F16)."""
     assert X.stride(1) == 1 and W.stride(1) == 1 and Y.stride(1) == 1
     _check(load_library().hcspmm_gcn_layer_ex(plan.handle, _ptr(X), X.stride(0), X.shape[1], _ptr(W), W.stride(0),
-                                              W.shape[1], _ptr(Y), Y.stride(0), 1 if apply_relu else 0, t_dtype,
+                                              W.shape[1], _ptr(Y), Y.stride(0), _dtype_code(Y), 1 if apply_relu else 0, t_dtype,
                                               _ptr(workspace), workspace.numel() * workspace.element_size(),
                                               _stream_ptr(stream)))
     return Y

@@ -137,9 +137,10 @@ struct SpmmArgs {
     int64_t ldx;
     int32_t d;
     int32_t x_dtype;
-    float* Y;
+    float* Y;             // element type y_dtype (fp32 unless the caller asked for a 16-bit output); ldy in elements
     int64_t ldy;
     int32_t relu;
+    int32_t y_dtype;
 };
 
 // Update stage of the aggregate-then-update layer: Y = act(Z W) for aggregated rows Z (Section V-A).
@@ -153,7 +154,57 @@ struct UpdateArgs {
     int32_t keep_z;       // also store every aggregated row to the workspace (a.Y), not only the rows finished later
     const float* mask;    // optional, n_rows x d_out (pitch ldm): results are stored as 0 where mask <= 0
     int64_t ldm;
+    int32_t y_dtype;      // element type of Y
 };
+
+#if defined(__HIPCC__)
+// fp32 -> 16-bit storage, one rounding to nearest even (the only rounding a 16-bit output adds to the fp32 result)
+__device__ inline uint32_t out16_bits(float f, int y_dtype)
+{
+    if (y_dtype == HCSPMM_BF16) {
+        uint32_t u = __float_as_uint(f);
+        if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;   // NaN stays NaN
+        u += 0x7fffu + ((u >> 16) & 1u);
+        return u >> 16;
+    }
+    return (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)f);
+}
+
+// Stores VEC consecutive results at element offset `off` of an output matrix of element type y_dtype, after the
+// optional max(0, .).  The address is aligned for VEC fp32 elements when y_dtype is fp32 and for min(VEC, 4) 16-bit
+// elements otherwise (no 16-bit store is wider than 8 bytes).
+template <int VEC> __device__ inline void out_store(float* __restrict__ Y, int y_dtype, int64_t off, const float (&x)[VEC], int relu)
+{
+    float y[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) y[i] = relu ? fmaxf(x[i], 0.f) : x[i];
+    if (y_dtype == HCSPMM_F32) {
+        float* __restrict__ p = Y + off;
+        if constexpr (VEC == 8) {
+            *reinterpret_cast<float4*>(p) = make_float4(y[0], y[1], y[2], y[3]);
+            *reinterpret_cast<float4*>(p + 4) = make_float4(y[4], y[5], y[6], y[7]);
+        } else if constexpr (VEC == 4) {
+            *reinterpret_cast<float4*>(p) = make_float4(y[0], y[1], y[2], y[3]);
+        } else if constexpr (VEC == 2) {
+            *reinterpret_cast<float2*>(p) = make_float2(y[0], y[1]);
+        } else {
+            *p = y[0];
+        }
+    } else {
+        unsigned short* __restrict__ p = reinterpret_cast<unsigned short*>(Y) + off;
+        if constexpr (VEC >= 4) {
+#pragma unroll
+            for (int i = 0; i < VEC; i += 4)
+                *reinterpret_cast<uint2*>(p + i) = make_uint2(out16_bits(y[i], y_dtype) | (out16_bits(y[i + 1], y_dtype) << 16),
+                                                              out16_bits(y[i + 2], y_dtype) | (out16_bits(y[i + 3], y_dtype) << 16));
+        } else if constexpr (VEC == 2) {
+            *reinterpret_cast<uint32_t*>(p) = out16_bits(y[0], y_dtype) | (out16_bits(y[1], y_dtype) << 16);
+        } else {
+            *p = (unsigned short)out16_bits(y[0], y_dtype);
+        }
+    }
+}
+#endif
 
 // With `upd` the kernels that can keep a 16-row result tile on chip multiply it by W and write
 // upd->Y (short rows of the scalar path, wave-per-window tiles of the matrix path); every other
@@ -168,7 +219,7 @@ hipError_t launch_update_rest(const SpmmArgs& a, int32_t n_rest, const int32_t* 
 // dense product through the 16-row update kernel (narrow W), see spmm_csr_kernels.hip
 bool gemm_rows16_usable(int64_t m, int32_t k, int32_t n, const float* X, int64_t ldx);
 hipError_t launch_gemm_rows16(int64_t m, int32_t k, int32_t n, const float* X, int64_t ldx, const float* W, int64_t ldw,
-                              float* T, int64_t ldt, int relu, hipStream_t s);
+                              float* T, int64_t ldt, int relu, hipStream_t s, int32_t t_dtype = HCSPMM_F32);
 hipError_t launch_rest_flag(int32_t n_rows, const int32_t* rowptr, const uint8_t* route, const int32_t* ncols,
                             int32_t mid_row, int32_t* flag, hipStream_t s);
 hipError_t launch_reduce_partials(const SpmmArgs& a, int32_t n_multi, const MultiRow* multi, const float* partial,

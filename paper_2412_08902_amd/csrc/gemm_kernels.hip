@@ -141,8 +141,8 @@ hipError_t launch_gemm_f32_out(int64_t m, int32_t k, int32_t n, const float* X, 
                                void* T, int64_t ldt, int32_t t_dtype, int relu, hipStream_t s)
 {
     if (m <= 0 || n <= 0) return hipSuccess;
-    if (t_dtype == HCSPMM_F32 && gemm_rows16_usable(m, k, n, X, ldx) && !tune().no_rows16)
-        return launch_gemm_rows16(m, k, n, X, ldx, W, ldw, static_cast<float*>(T), ldt, relu, s);
+    if (gemm_rows16_usable(m, k, n, X, ldx) && !tune().no_rows16)
+        return launch_gemm_rows16(m, k, n, X, ldx, W, ldw, static_cast<float*>(T), ldt, relu, s, t_dtype);
     dim3 grid((unsigned)((m + BM - 1) / BM), (unsigned)((n + BN - 1) / BN));
     const uintptr_t px = (uintptr_t)X;
     const int xv = (ldx % 4 == 0 && px % 16 == 0) ? 4 : ((ldx % 2 == 0 && px % 8 == 0) ? 2 : 1);

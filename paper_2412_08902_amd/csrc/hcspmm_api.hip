@@ -952,14 +952,14 @@ static hcspmm_status spmm_impl(const hcspmm_plan* plan, const void* d_X, int64_t
     if (!plan) { set_error("plan is NULL"); return HCSPMM_EINVAL; }
     if (d < 1 || d > (1 << 20)) { set_error("d must be in [1, 2^20]"); return HCSPMM_EINVAL; }
     if (x_dtype < 0 || x_dtype > 2 || y_dtype < 0 || y_dtype > 2) { set_error("bad dtype"); return HCSPMM_EINVAL; }
-    if (y_dtype != HCSPMM_F32) { set_error("only fp32 output is implemented"); return HCSPMM_EUNSUPPORTED; }
     if (plan->n_rows == 0) return HCSPMM_OK;
     hcspmm_status st;
     if ((st = check_dense("X", d_X, ldx, d)) != HCSPMM_OK) return st;
     if ((st = check_dense("Y", d_Y, ldy, d)) != HCSPMM_OK) return st;
-    SpmmArgs a;
+    SpmmArgs a{};
     a.n_rows = plan->n_rows; a.rowptr = plan->rowptr; a.colind = plan->colind; a.vals = plan->vals;
     a.X = d_X; a.ldx = ldx; a.d = d; a.x_dtype = x_dtype; a.Y = static_cast<float*>(d_Y); a.ldy = ldy; a.relu = 0;
+    a.y_dtype = y_dtype;
     if (plan->n_mfma > 0 && !mfma_shape_supported(a)) {
         set_error("16-bit X on the matrix path needs d, ldx and ldy to be multiples of 4 and 8-byte aligned X, 16-byte aligned Y");
         return HCSPMM_EUNSUPPORTED;
@@ -1010,15 +1010,16 @@ hcspmm_status hcspmm_gcn_layer(const hcspmm_plan* plan, const void* d_X, int64_t
                                int64_t ldw, int32_t d_out, void* d_Y, int64_t ldy, int32_t apply_relu,
                                void* d_workspace, size_t workspace_bytes, void* stream)
 {
-    return hcspmm_gcn_layer_ex(plan, d_X, ldx, d_in, d_W, ldw, d_out, d_Y, ldy, apply_relu, HCSPMM_F32, d_workspace,
+    return hcspmm_gcn_layer_ex(plan, d_X, ldx, d_in, d_W, ldw, d_out, d_Y, ldy, HCSPMM_F32, apply_relu, HCSPMM_F32, d_workspace,
                                workspace_bytes, stream);
 }
 
 hcspmm_status hcspmm_gcn_layer_ex(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d_in, const void* d_W,
-                                  int64_t ldw, int32_t d_out, void* d_Y, int64_t ldy, int32_t apply_relu, int32_t t_dtype,
-                                  void* d_workspace, size_t workspace_bytes, void* stream)
+                                  int64_t ldw, int32_t d_out, void* d_Y, int64_t ldy, int32_t y_dtype, int32_t apply_relu,
+                                  int32_t t_dtype, void* d_workspace, size_t workspace_bytes, void* stream)
 {
     if (!plan) { set_error("plan is NULL"); return HCSPMM_EINVAL; }
+    if (y_dtype != HCSPMM_F32 && y_dtype != HCSPMM_BF16 && y_dtype != HCSPMM_F16) { set_error("y_dtype %d is not a dtype code", y_dtype); return HCSPMM_EINVAL; }
     if (d_in < 1 || d_out < 1 || d_in > (1 << 20) || d_out > (1 << 20)) { set_error("d_in, d_out must be in [1, 2^20]"); return HCSPMM_EINVAL; }
     if (t_dtype != HCSPMM_F32 && t_dtype != HCSPMM_BF16 && t_dtype != HCSPMM_F16) { set_error("t_dtype %d is not a dtype code", t_dtype); return HCSPMM_EINVAL; }
     hcspmm_status st;
@@ -1029,10 +1030,11 @@ hcspmm_status hcspmm_gcn_layer_ex(const hcspmm_plan* plan, const void* d_X, int6
     if (!d_workspace || workspace_bytes < need) { set_error("workspace too small: need %zu bytes", need); return HCSPMM_EINVAL; }
     if (((uintptr_t)d_workspace & 255) != 0) { set_error("workspace must be 256-byte aligned"); return HCSPMM_EINVAL; }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    SpmmArgs a;
+    SpmmArgs a{};
     a.n_rows = plan->n_rows; a.rowptr = plan->rowptr; a.colind = plan->colind; a.vals = plan->vals;
     a.X = d_workspace; a.ldx = d_out; a.d = d_out; a.x_dtype = t_dtype; a.Y = static_cast<float*>(d_Y); a.ldy = ldy;
     a.relu = apply_relu ? 1 : 0;
+    a.y_dtype = y_dtype;
     if (t_dtype != HCSPMM_F32 && plan->n_mfma > 0 && !mfma_shape_supported(a)) {
         set_error("the matrix path with 16-bit T needs d_out a multiple of 4 and 16-byte aligned Y rows");
         return HCSPMM_EUNSUPPORTED;
@@ -1061,10 +1063,11 @@ size_t hcspmm_aggregate_update_workspace_bytes(const hcspmm_plan* plan, int32_t 
 
 hcspmm_status hcspmm_aggregate_update(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d_in,
                                       int32_t x_dtype, const void* d_W, int64_t ldw, int32_t d_out, void* d_Y,
-                                      int64_t ldy, int32_t apply_relu, void* d_workspace, size_t workspace_bytes,
-                                      void* stream)
+                                      int64_t ldy, int32_t y_dtype, int32_t apply_relu, void* d_workspace,
+                                      size_t workspace_bytes, void* stream)
 {
     if (!plan) { set_error("plan is NULL"); return HCSPMM_EINVAL; }
+    if (y_dtype != HCSPMM_F32 && y_dtype != HCSPMM_BF16 && y_dtype != HCSPMM_F16) { set_error("y_dtype %d is not a dtype code", y_dtype); return HCSPMM_EINVAL; }
     if (d_in < 1 || d_out < 1 || d_in > (1 << 20) || d_out > (1 << 20)) { set_error("d_in, d_out must be in [1, 2^20]"); return HCSPMM_EINVAL; }
     if (x_dtype != HCSPMM_F32 && x_dtype != HCSPMM_BF16 && x_dtype != HCSPMM_F16) { set_error("x_dtype %d is not a dtype code", x_dtype); return HCSPMM_EINVAL; }
     hcspmm_status st;
@@ -1077,7 +1080,7 @@ hcspmm_status hcspmm_aggregate_update(const hcspmm_plan* plan, const void* d_X, 
     if (plan->n_rows == 0) return HCSPMM_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
     float* Z = static_cast<float*>(d_workspace);
-    SpmmArgs a;
+    SpmmArgs a{};
     a.n_rows = plan->n_rows; a.rowptr = plan->rowptr; a.colind = plan->colind; a.vals = plan->vals;
     a.X = d_X; a.ldx = ldx; a.d = d_in; a.x_dtype = x_dtype; a.Y = Z; a.ldy = d_in; a.relu = 0;
     // The fused update pays where most rows can keep their tile on chip; rows that go through the
@@ -1087,12 +1090,13 @@ hcspmm_status hcspmm_aggregate_update(const hcspmm_plan* plan, const void* d_X, 
                         !(x_dtype == HCSPMM_F32 && split_update_faster(plan->n_rows, d_in, d_out, Z))) ||
                        plan->opt.update_fusion == HCSPMM_UPDATE_FUSED;
     if (update_fusable(a) && worth && plan->opt.update_fusion != HCSPMM_UPDATE_SPLIT) {
-        const UpdateArgs u{static_cast<const float*>(d_W), ldw, d_out, static_cast<float*>(d_Y), ldy, apply_relu ? 1 : 0};
+        const UpdateArgs u{static_cast<const float*>(d_W), ldw, d_out, static_cast<float*>(d_Y), ldy, apply_relu ? 1 : 0, 0,
+                           nullptr, 0, y_dtype};
         return run_spmm(plan, a, s, nullptr, &u);
     }
     if ((st = run_spmm(plan, a, s)) != HCSPMM_OK) return st;
-    HC_HIP(launch_gemm_f32(plan->n_rows, d_in, d_out, Z, d_in, static_cast<const float*>(d_W), ldw,
-                           static_cast<float*>(d_Y), ldy, apply_relu ? 1 : 0, s));
+    HC_HIP(launch_gemm_f32_out(plan->n_rows, d_in, d_out, Z, d_in, static_cast<const float*>(d_W), ldw, d_Y, ldy, y_dtype,
+                               apply_relu ? 1 : 0, s));
     return HCSPMM_OK;
 }
 
@@ -1152,7 +1156,7 @@ hcspmm_status hcspmm_layer_backward(const hcspmm_plan* plan, const void* d_G, in
         g_ld = d_out;
     }
     if (plan->n_rows > 0) {
-        SpmmArgs a;
+        SpmmArgs a{};
         a.n_rows = plan->n_rows; a.rowptr = plan->rowptr; a.colind = plan->colind; a.vals = plan->vals;
         a.X = G; a.ldx = g_ld; a.d = d_out; a.x_dtype = HCSPMM_F32; a.Y = S; a.ldy = d_out; a.relu = 0;
         if (d_dX) {
@@ -1244,6 +1248,6 @@ const char* hcspmm_status_string(hcspmm_status s)
 
 const char* hcspmm_last_error(void) { return g_err; }
 
-int32_t hcspmm_version(void) { return 100; }
+int32_t hcspmm_version(void) { return 10100; }
 
 }  // extern "C"

@@ -175,7 +175,7 @@ __device__ inline void csr_short_body(int64_t block, int32_t n_items, const int3
         float mv = 0.f;
         for (;;) {
             if (k >= e) {
-                if (row >= 0 && col_ok) vstore<VEC>(a.Y + (int64_t)row * a.ldy + c, acc, a.relu);
+                if (row >= 0 && col_ok) out_store<VEC>(a.Y, a.y_dtype, (int64_t)row * a.ldy + c, acc, a.relu);
                 row = -1;
                 while (j < nr && row < 0) {
                     row = __shfl(my_row, j, LPR);
@@ -306,7 +306,7 @@ __device__ inline void csr_mid_body(int64_t block, int32_t n_mid, const int32_t*
         for (int off = LPR; off < 64; off <<= 1)
 #pragma unroll
             for (int i = 0; i < VEC; ++i) acc[i] += __shfl_xor(acc[i], off, 64);
-        if (g == 0 && col_ok) vstore<VEC>(a.Y + (int64_t)row * a.ldy + c, acc, a.relu);
+        if (g == 0 && col_ok) out_store<VEC>(a.Y, a.y_dtype, (int64_t)row * a.ldy + c, acc, a.relu);
     }
 }
 
@@ -343,7 +343,7 @@ __device__ inline void csr_long_body(int64_t block, const Segment* __restrict__ 
         if (g == 0 && col_ok) {
 #pragma unroll
             for (int i = 0; i < VEC; ++i) acc[i] = red[lig * VEC + i];
-            if (sg.slot < 0) vstore<VEC>(a.Y + (int64_t)sg.row * a.ldy + c, acc, a.relu);
+            if (sg.slot < 0) out_store<VEC>(a.Y, a.y_dtype, (int64_t)sg.row * a.ldy + c, acc, a.relu);
             else vstore<VEC>(partial + (int64_t)sg.slot * a.d + c, acc, 0);
         }
         __syncthreads();
@@ -491,7 +491,8 @@ __global__ __launch_bounds__(256) void k_reduce_partials(int32_t n_multi, const 
     for (int c = threadIdx.x; c < a.d; c += 256) {
         float acc = 0.f;
         for (int q = 0; q < m.n_slots; ++q) acc += partial[(int64_t)(m.first_slot + q) * a.d + c];
-        a.Y[(int64_t)m.row * a.ldy + c] = a.relu ? fmaxf(acc, 0.f) : acc;
+        const float one[1] = {acc};
+        out_store<1>(a.Y, a.y_dtype, (int64_t)m.row * a.ldy + c, one, a.relu);
     }
 }
 
@@ -620,11 +621,11 @@ bool gemm_rows16_usable(int64_t m, int32_t k, int32_t n, const float* X, int64_t
 }
 
 hipError_t launch_gemm_rows16(int64_t m, int32_t k, int32_t n, const float* X, int64_t ldx, const float* W, int64_t ldw,
-                              float* T, int64_t ldt, int relu, hipStream_t s)
+                              float* T, int64_t ldt, int relu, hipStream_t s, int32_t t_dtype)
 {
     SpmmArgs a{};
     a.n_rows = (int32_t)m; a.d = k; a.Y = const_cast<float*>(X); a.ldy = ldx;      // the kernel only reads these rows
-    const UpdateArgs u{W, ldw, n, T, ldt, relu ? 1 : 0, 0, nullptr, 0};
+    const UpdateArgs u{W, ldw, n, T, ldt, relu ? 1 : 0, 0, nullptr, 0, t_dtype};
     return launch_update_rest(a, (int32_t)m, nullptr, u, s);
 }
 

@@ -246,7 +246,7 @@ __device__ inline void block_stages_deep(const float* __restrict__ blk, int ncol
 
 template <int VW, int NG>
 __device__ inline void store_tile(const v4f (&acc)[NG][VW], int lane, int32_t r0, int32_t n_rows, float* __restrict__ Y,
-                                  int64_t ldy, int d, int relu)
+                                  int64_t ldy, int col0, int d, int relu, int y_dtype = HCSPMM_F32)
 {
     const int j = lane & 15, kk = lane >> 4;
 #pragma unroll
@@ -259,18 +259,8 @@ __device__ inline void store_tile(const v4f (&acc)[NG][VW], int lane, int32_t r0
             if (row >= n_rows) continue;
             float y[VW];
 #pragma unroll
-            for (int t = 0; t < VW; ++t) y[t] = relu ? fmaxf(acc[g][t][r], 0.f) : acc[g][t][r];
-            float* __restrict__ p = Y + (int64_t)row * ldy + col;
-            if constexpr (VW == 8) {
-                *reinterpret_cast<float4*>(p) = make_float4(y[0], y[1], y[2], y[3]);
-                *reinterpret_cast<float4*>(p + 4) = make_float4(y[4], y[5], y[6], y[7]);
-            } else if constexpr (VW == 4) {
-                *reinterpret_cast<float4*>(p) = make_float4(y[0], y[1], y[2], y[3]);
-            } else if constexpr (VW == 2) {
-                *reinterpret_cast<float2*>(p) = make_float2(y[0], y[1]);
-            } else {
-                *p = y[0];
-            }
+            for (int t = 0; t < VW; ++t) y[t] = acc[g][t][r];
+            out_store<VW>(Y, y_dtype, (int64_t)row * ldy + col0 + col, y, relu);
         }
     }
 }
@@ -395,7 +385,7 @@ __global__ __launch_bounds__(256) void k_mfma_small(int32_t n_list, const WinDes
         if (u.keep_z) store_tile_rows(tile, kLdz, rows16, 16, a.d, a.Y, a.ldy, lane, 64);
         update_tile16(tile, kLdz, rows16, a.d, u, lane);
     } else {
-        store_tile<VW, NG>(acc, lane, r0, a.n_rows, a.Y + col0, a.ldy, d, a.relu);
+        store_tile<VW, NG>(acc, lane, r0, a.n_rows, a.Y, a.ldy, col0, d, a.relu, a.y_dtype);
     }
 }
 
@@ -547,8 +537,8 @@ __global__ __launch_bounds__(256) void k_mfma_wg(const WgSlice* __restrict__ sli
         __syncthreads();
     }
     if (wave == 0) {
-        if (sl.slot < 0) store_tile<VW, NG>(acc, lane, r0, a.n_rows, a.Y + col0, a.ldy, d, a.relu);
-        else store_tile<VW, NG>(acc, lane, sl.slot * kH, 0x7fffffff, tile_partial + col0, a.d, d, 0);
+        if (sl.slot < 0) store_tile<VW, NG>(acc, lane, r0, a.n_rows, a.Y, a.ldy, col0, d, a.relu, a.y_dtype);
+        else store_tile<VW, NG>(acc, lane, sl.slot * kH, 0x7fffffff, tile_partial, a.d, col0, d, 0);
     }
 }
 
@@ -808,8 +798,8 @@ __global__ __launch_bounds__(256) void k_mfma_run(const RunSlice* __restrict__ s
         chunk(c + 1, stg_b, stg_a);
     }
     if (has_win) {
-        if (sl.n_slices == 1) store_tile<VW, NG>(acc, lane, r0, a.n_rows, a.Y + col0, a.ldy, d, a.relu);
-        else store_tile<VW, NG>(acc, lane, (sl.slot0 + wave * sl.n_slices + sl.q) * kH, 0x7fffffff, tile_partial + col0, a.d, d, 0);
+        if (sl.n_slices == 1) store_tile<VW, NG>(acc, lane, r0, a.n_rows, a.Y, a.ldy, col0, d, a.relu, a.y_dtype);
+        else store_tile<VW, NG>(acc, lane, (sl.slot0 + wave * sl.n_slices + sl.q) * kH, 0x7fffffff, tile_partial, a.d, col0, d, 0);
     }
 }
 
@@ -824,7 +814,8 @@ __global__ __launch_bounds__(256) void k_reduce_tiles(const MultiRow* __restrict
         if (row >= a.n_rows) continue;
         float acc = 0.f;
         for (int q = 0; q < m.n_slots; ++q) acc += tile_partial[((int64_t)(m.first_slot + q) * kH + r) * a.d + c];
-        a.Y[row * a.ldy + c] = a.relu ? fmaxf(acc, 0.f) : acc;
+        const float one[1] = {acc};
+        out_store<1>(a.Y, a.y_dtype, row * a.ldy + c, one, a.relu);
     }
 }
 

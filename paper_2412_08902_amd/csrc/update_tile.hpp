@@ -82,10 +82,7 @@ __device__ inline void update_tile16_nt(const float* zt, int ldz, const int32_t*
 #pragma unroll
                 for (int t = 0; t < NT; ++t) y[t] = mp[t] > 0.f ? y[t] : 0.f;
             }
-            float* __restrict__ p = u.Y + (int64_t)myrow[r] * u.ldy + col;
-            if constexpr (NT == 4) *reinterpret_cast<float4*>(p) = make_float4(y[0], y[1], y[2], y[3]);
-            else if constexpr (NT == 2) *reinterpret_cast<float2*>(p) = make_float2(y[0], y[1]);
-            else *p = y[0];
+            out_store<NT>(u.Y, u.y_dtype, (int64_t)myrow[r] * u.ldy + col, y, 0);
         }
     }
 }

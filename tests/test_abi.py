@@ -88,6 +88,10 @@ def test_new_entry_points_reject_bad_arguments_on_the_host():
     import paper_2412_08902_amd.binding as hc
     lib = hc.load_library()
     assert lib.hcspmm_layer_backward(None, None, 0, 4, None, 0, None, 0, 4, None, 0, None, 0, None, 0, 0, None, 0, None) == hc.HCSPMM_EINVAL
-    assert lib.hcspmm_aggregate_update(None, None, 0, 4, 0, None, 0, 4, None, 0, 1, None, 0, None) == hc.HCSPMM_EINVAL
+    assert lib.hcspmm_aggregate_update(None, None, 0, 4, 0, None, 0, 4, None, 0, 0, 1, None, 0, None) == hc.HCSPMM_EINVAL
+    assert lib.hcspmm_gcn_layer_ex(None, None, 0, 4, None, 0, 4, None, 0, 0, 1, 0, None, 0, None) == hc.HCSPMM_EINVAL
+    assert lib.hcspmm_spmm_noalloc(None, None, 0, 4, 0, None, 0, 0, None) == hc.HCSPMM_EINVAL
+    assert lib.hcspmm_plan_export_runs(None, None, None, None) == hc.HCSPMM_EINVAL
+    assert lib.hcspmm_probe_gather(None, -1, None, 0, 4, 1, None, 0, None) == hc.HCSPMM_EINVAL
     assert lib.hcspmm_layer_backward_workspace_bytes(None, 4, 4) == 0
     assert lib.hcspmm_aggregate_update_workspace_bytes(None, 4, 4) == 0
