@@ -158,16 +158,16 @@ struct UpdateArgs {
 };
 
 #if defined(__HIPCC__)
-// fp32 -> 16-bit storage, one rounding to nearest even (the only rounding a 16-bit output adds to the fp32 result)
-__device__ inline uint32_t out16_bits(float f, int y_dtype)
+// fp32 -> 16-bit storage, one rounding to nearest even (the only rounding a 16-bit output adds to the fp32 result);
+// two values per call, packed low | high << 16.  The conversions are the hardware's (gfx950 converts to bf16 natively).
+typedef float out_f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 out_bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 out_f16x2 __attribute__((ext_vector_type(2)));
+__device__ inline uint32_t out16_pack(float lo, float hi, int y_dtype)
 {
-    if (y_dtype == HCSPMM_BF16) {
-        uint32_t u = __float_as_uint(f);
-        if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;   // NaN stays NaN
-        u += 0x7fffu + ((u >> 16) & 1u);
-        return u >> 16;
-    }
-    return (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)f);
+    const out_f32x2 v = {lo, hi};
+    if (y_dtype == HCSPMM_BF16) return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, out_bf16x2));
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, out_f16x2));
 }
 
 // Stores VEC consecutive results at element offset `off` of an output matrix of element type y_dtype, after the
@@ -195,12 +195,11 @@ template <int VEC> __device__ inline void out_store(float* __restrict__ Y, int y
         if constexpr (VEC >= 4) {
 #pragma unroll
             for (int i = 0; i < VEC; i += 4)
-                *reinterpret_cast<uint2*>(p + i) = make_uint2(out16_bits(y[i], y_dtype) | (out16_bits(y[i + 1], y_dtype) << 16),
-                                                              out16_bits(y[i + 2], y_dtype) | (out16_bits(y[i + 3], y_dtype) << 16));
+                *reinterpret_cast<uint2*>(p + i) = make_uint2(out16_pack(y[i], y[i + 1], y_dtype), out16_pack(y[i + 2], y[i + 3], y_dtype));
         } else if constexpr (VEC == 2) {
-            *reinterpret_cast<uint32_t*>(p) = out16_bits(y[0], y_dtype) | (out16_bits(y[1], y_dtype) << 16);
+            *reinterpret_cast<uint32_t*>(p) = out16_pack(y[0], y[1], y_dtype);
         } else {
-            *p = (unsigned short)out16_bits(y[0], y_dtype);
+            *p = (unsigned short)out16_pack(y[0], 0.f, y_dtype);
         }
     }
 }
