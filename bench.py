@@ -91,6 +91,8 @@ def main():
                          "update stage fused into the SpMM kernels and as SpMM + GEMM")
     ap.add_argument("--backward", type=int, default=0, metavar="D_IN",
                     help="also time the layer's backward pass (S = A G, dX = S W^T, dW = X^T S) for a D_IN x d W")
+    ap.add_argument("--update", action="store_true",
+                    help="also time hcspmm_plan_update for 1, 10^3 and 10^5 changed rows against a preparation from scratch")
     ap.add_argument("--graph", type=int, default=0, metavar="N",
                     help="also capture N back-to-back SpMM calls in a HIP graph and time its replays "
                          "(separates launch latency from kernel time on the small configs)")
@@ -325,6 +327,32 @@ def main():
         log("layer backward: %.4f ms (unfused %.4f; dX only %.4f, dW only %.4f, with mask pass %.4f, with dX masked in "
             "the epilogue %.4f; spmm alone %.4f)" % (ms_b, ms_b_split, ms_dx, ms_dw, ms_b_mask, ms_b_emask, ms))
         del Wb, Xb, Yf, wsb, dXb, dWb
+
+    if args.update:
+        # structural change without moving the arrays: the last column index of each chosen row is raised by one (rows
+        # stay sorted and duplicate-free); successive calls alternate between the two versions of the column array
+        rng = np.random.default_rng(4711)
+        lens = np.diff(g.rowptr)
+        res = {"prepare_from_scratch_ms": round(prepare_ms, 3)}
+        for n_changed in (1, 1000, 100000):
+            rows = np.unique(rng.choice(g.n_rows, min(n_changed, g.n_rows), replace=False)).astype(np.int32)
+            last = g.rowptr[rows + 1].astype(np.int64) - 1
+            ok = (lens[rows] > 0) & (g.colind[np.maximum(last, 0)] < g.n_cols - 1)
+            rows, last = rows[ok], last[ok]
+            ci2 = ci.clone()
+            ci2[torch.from_numpy(last).to(dev)] += 1
+            ts = []
+            for rep in range(6):
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
+                hc.hcspmm_plan_update(plan, rp, ci2 if rep % 2 == 0 else ci, va, rows)
+                torch.cuda.synchronize()
+                ts.append((time.perf_counter() - t1) * 1e3)
+            res["update_ms_%d_rows" % n_changed] = round(float(np.median(ts[1:])), 3)
+            res["windows_touched_%d_rows" % n_changed] = int(np.unique(rows // 16).shape[0])
+            del ci2
+        out["plan_update"] = res
+        log("plan update: %s" % res)
 
     if not args.no_cold:
         # cold caches: a 512 MiB write between repetitions evicts the L2s and the memory-side cache

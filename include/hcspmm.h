@@ -143,6 +143,31 @@ hcspmm_status hcspmm_prepare(int32_t n_rows, int32_t n_cols, int64_t nnz,
                              const int32_t* d_rowptr, const int32_t* d_colind, const float* d_vals,
                              const hcspmm_options* opt, void* stream, hcspmm_plan** out_plan);
 
+/*
+ * Preprocessing again after the matrix's STRUCTURE changed (edges inserted or deleted; the paper's
+ * Appendix F counts preprocessing as the price of a changing graph).  The caller hands over the new
+ * CSR arrays (same n_rows and n_cols; nnz and all three arrays may differ, the plan borrows the new
+ * ones from now on) and the list of rows whose set of entries changed.  Windows without a changed
+ * row keep their distinct-column counts, so the passes over the column indices -- validation and
+ * counting, the part of hcspmm_prepare proportional to the non-zeros -- run over the touched windows
+ * only; routes (selector and launch guard), the window lists and the launch tables are then rebuilt
+ * for the whole matrix, which costs time proportional to the rows, not to the non-zeros, and the
+ * condensed structure of the matrix-path windows is rebuilt.  The result is the plan
+ * hcspmm_prepare would build for the new arrays, bit for bit.
+ *
+ *   nnz, d_rowptr, d_colind, d_vals   the new matrix, as for hcspmm_prepare
+ *   h_changed_rows   host, int32[n_changed]: every row whose column indices (their values or their
+ *                    number) differ from the old matrix, in any order, repeats allowed.  A row that
+ *                    changed but is not listed leaves the plan inconsistent with the matrix.
+ * Falls back to a preparation from scratch when an eighth of the windows or more are touched, or when the
+ * plan's window features were never computed (HCSPMM_ROUTE_ALL_CSR plans, whose preparation has no
+ * pass over the column indices to save).  Synchronises with `stream`; no call may be using the plan.
+ * On an error the plan is unchanged and still valid for the old arrays.
+ */
+hcspmm_status hcspmm_plan_update(hcspmm_plan* plan, int64_t nnz, const int32_t* d_rowptr, const int32_t* d_colind,
+                                 const float* d_vals, const int32_t* h_changed_rows /* host */, int32_t n_changed,
+                                 void* stream);
+
 /* Sizes of a plan's arrays (host struct, filled by hcspmm_plan_info). */
 typedef struct {
     int32_t window_rows;      /* H */

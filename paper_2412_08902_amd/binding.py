@@ -21,7 +21,7 @@ HCSPMM_MATRIX_AUTO, HCSPMM_MATRIX_PER_WINDOW, HCSPMM_MATRIX_RUNS = 0, 1, 2
 
 EXPORTED_SYMBOLS = [
     "hcspmm_default_options", "hcspmm_default_selector", "hcspmm_prepare", "hcspmm_plan_info",
-    "hcspmm_plan_export", "hcspmm_plan_export_runs", "hcspmm_spmm", "hcspmm_spmm_noalloc", "hcspmm_spmm_noalloc_scratch_limit", "hcspmm_spmm_timed", "hcspmm_gcn_layer", "hcspmm_gcn_layer_ex", "hcspmm_gcn_workspace_bytes",
+    "hcspmm_plan_export", "hcspmm_plan_export_runs", "hcspmm_plan_update", "hcspmm_spmm", "hcspmm_spmm_noalloc", "hcspmm_spmm_noalloc_scratch_limit", "hcspmm_spmm_timed", "hcspmm_gcn_layer", "hcspmm_gcn_layer_ex", "hcspmm_gcn_workspace_bytes",
     "hcspmm_aggregate_update", "hcspmm_aggregate_update_workspace_bytes",
     "hcspmm_layer_backward", "hcspmm_layer_backward_workspace_bytes",
     "hcspmm_gemm_f32", "hcspmm_plan_set_update_fusion", "hcspmm_probe_gather", "hcspmm_probe_gather_out_bytes", "hcspmm_loa_order", "hcspmm_permute_csr", "hcspmm_transpose_csr", "hcspmm_plan_destroy", "hcspmm_status_string", "hcspmm_last_error", "hcspmm_version",
@@ -83,6 +83,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.hcspmm_plan_info.restype = ctypes.c_int
     lib.hcspmm_plan_export.argtypes = [vp] + [vp] * 8
     lib.hcspmm_plan_export.restype = ctypes.c_int
+    lib.hcspmm_plan_update.argtypes = [vp, i64, vp, vp, vp, vp, i32, vp]
+    lib.hcspmm_plan_update.restype = ctypes.c_int
     lib.hcspmm_plan_export_runs.argtypes = [vp, vp, vp, vp]
     lib.hcspmm_plan_export_runs.restype = ctypes.c_int
     lib.hcspmm_spmm.argtypes = [vp, vp, i64, i32, i32, vp, i64, i32, vp]
@@ -231,6 +233,16 @@ def hcspmm_probe_gather(index, X, out, *, d: Optional[int] = None, stream=None):
         d = X.shape[1]
     _check(load_library().hcspmm_probe_gather(_ptr(index), index.numel(), _ptr(X), X.stride(0), d, X.shape[0], _ptr(out),
                                               out.numel() * out.element_size(), _stream_ptr(stream)))
+
+
+def hcspmm_plan_update(plan: Plan, rowptr, colind, vals, changed_rows, *, stream=None, nnz: Optional[int] = None):
+    """Re-prepare ``plan`` for new CSR tensors (same shape) given the rows whose entries changed (host int32 array)."""
+    rows = np.ascontiguousarray(changed_rows, dtype=np.int32)
+    if nnz is None:
+        nnz = int(colind.numel())
+    _check(load_library().hcspmm_plan_update(plan.handle, nnz, _ptr(rowptr), _ptr(colind), _ptr(vals), _host_ptr(rows),
+                                             rows.shape[0], _stream_ptr(stream)))
+    plan._keep = (rowptr, colind, vals)
 
 
 def hcspmm_plan_set_update_fusion(plan: Plan, update_fusion: int):

@@ -96,6 +96,13 @@ hipError_t launch_window_classes(int32_t W, int32_t n_rows, const int32_t* rowpt
                                  int32_t* huge_list, int32_t* counts, hipStream_t s);
 hipError_t launch_count_small(int32_t W, int32_t n_rows, const int32_t* rowptr, const int32_t* colind, int32_t* ncols,
                               hipStream_t s);
+// incremental preparation: the touched windows by size class (+ range check of their columns), counts over a list
+hipError_t launch_touched_classes(int32_t n_touched, const int32_t* touched, int32_t n_rows, int32_t n_cols,
+                                  const int32_t* rowptr, const int32_t* colind, int32_t* t_small, int32_t* t_mid,
+                                  int32_t* t_huge, int32_t* counts, int32_t* err, hipStream_t s);
+hipError_t launch_count_small_list(int32_t n_list, const int32_t* list, int32_t n_rows, const int32_t* rowptr,
+                                   const int32_t* colind, int32_t* ncols, hipStream_t s);
+hipError_t launch_validate_rowptr(int32_t n_rows, int64_t nnz, const int32_t* rowptr, int32_t* err_flag, hipStream_t s);
 hipError_t launch_count_mid(int32_t n_mid, const int32_t* mid_list, int32_t n_rows, const int32_t* rowptr,
                             const int32_t* colind, int32_t* ncols, hipStream_t s);
 hipError_t launch_ecol(int32_t W, int32_t n_rows, const int32_t* rowptr, const int32_t* colind,

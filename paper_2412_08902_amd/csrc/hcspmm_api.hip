@@ -6,6 +6,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <mutex>
 #include <new>
 #include <vector>
@@ -238,7 +239,11 @@ fail:
     return st;
 }
 
-static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
+// What an incremental preparation carries over from the previous plan: the distinct-column counts of the windows
+// that hold no changed row (device array of the old plan) and the list of windows that do (device, distinct ids).
+struct PlanCarry { const int32_t* old_ncols; const int32_t* touched; int32_t n_touched; };
+
+static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream, const PlanCarry* carry = nullptr)
 {
     hcspmm_status st = HCSPMM_OK;
     DevAlloc tmp;      // scratch, freed on exit
@@ -251,8 +256,9 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     int32_t *f_short = nullptr, *f_mid = nullptr, *n_seg = nullptr, *f_multi = nullptr, *n_slot = nullptr, *len_long = nullptr;
     int64_t *scan_tmp = nullptr, *pos_a = nullptr, *pos_b = nullptr, *pos_c = nullptr, *pos_d = nullptr, *pos_e = nullptr, *pos_f = nullptr;
     int32_t* f_rest = nullptr;
+    int32_t *t_small = nullptr, *t_mid = nullptr, *t_huge = nullptr, *t_counts = nullptr;
     int64_t *totals_dev = nullptr;
-    int32_t h_err = 0, h_big = 0, h_cls[2] = {0, 0};
+    int32_t h_err = 0, h_big = 0, h_cls[2] = {0, 0}, h_tc[3] = {0, 0, 0};
     int64_t h_tot[16];
     const int64_t scan_n = (int64_t)(n_rows > W ? n_rows : W) + 1;
 
@@ -263,7 +269,8 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
                        DevAlloc::padded((size_t)scan_multi_scratch_elems(scan_n) * i64) +
                        6 * DevAlloc::padded((size_t)(scan_n + 1) * i64) +
                        DevAlloc::padded(16 * i64) + 6 * DevAlloc::padded(((size_t)W + 1) * i32) +
-                       7 * DevAlloc::padded(((size_t)n_rows + 1) * i32) + 64 * 256;
+                       7 * DevAlloc::padded(((size_t)n_rows + 1) * i32) + 64 * 256 +
+                       (carry ? 3 * DevAlloc::padded((size_t)carry->n_touched * i32) + 256 : 0);
         if (tmp.reserve(total) != hipSuccess) {
             (void)hipGetLastError();
             set_error("device allocation of %zu scratch bytes failed", total);
@@ -274,7 +281,24 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
     HC_ALLOC(tmp, err, 4);
     big_count = err + 1;                           // two counters: windows for the large hash set, for the bitmap
     HC_TRY(hipMemsetAsync(err, 0, 4 * sizeof(int32_t), stream));
-    HC_TRY(launch_validate(n_rows, p->n_cols, nnz, p->rowptr, p->colind, err, stream));
+    if (carry) {
+        // the row offsets are checked in full (they all move when a row grows), the columns only where rows changed
+        HC_ALLOC(tmp, t_small, carry->n_touched);
+        HC_ALLOC(tmp, t_mid, carry->n_touched);
+        HC_ALLOC(tmp, t_huge, carry->n_touched);
+        HC_ALLOC(tmp, t_counts, 4);
+        HC_TRY(hipMemsetAsync(t_counts, 0, 4 * sizeof(int32_t), stream));
+        HC_TRY(launch_validate_rowptr(n_rows, nnz, p->rowptr, err, stream));
+        HC_TRY(hipMemcpyAsync(&h_err, err, sizeof h_err, hipMemcpyDeviceToHost, stream));
+        HC_TRY(hipStreamSynchronize(stream));
+        if (!h_err) {           // the windows' spans are only meaningful with sound row offsets
+            HC_TRY(launch_touched_classes(carry->n_touched, carry->touched, n_rows, p->n_cols, p->rowptr, p->colind, t_small,
+                                          t_mid, t_huge, t_counts, err, stream));
+            HC_TRY(hipMemcpyAsync(h_tc, t_counts, 3 * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+        }
+    } else {
+        HC_TRY(launch_validate(n_rows, p->n_cols, nnz, p->rowptr, p->colind, err, stream));
+    }
     HC_TRY(hipMemcpyAsync(&h_err, err, sizeof h_err, hipMemcpyDeviceToHost, stream));
     HC_TRY(hipStreamSynchronize(stream));
     if (h_err) {
@@ -311,7 +335,17 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream)
         // for the windows it sends to the matrix path: count with LDS hash sets first (bitmap passes for
         // the few windows beyond the hash set's capacity, which leave their lists behind as well).
         HC_TRY(launch_window_classes(W, n_rows, p->rowptr, p->nnzw, big_list, huge_list, big_count, stream));
-        if (p->features_complete) {
+        if (p->features_complete && carry) {
+            // counts of the untouched windows are the previous plan's; the touched ones are counted again
+            HC_TRY(hipMemcpyAsync(p->ncols, carry->old_ncols, (size_t)W * sizeof(int32_t), hipMemcpyDeviceToDevice, stream));
+            HC_TRY(hipMemcpyAsync(h_cls, big_count, sizeof h_cls, hipMemcpyDeviceToHost, stream));
+            HC_TRY(hipStreamSynchronize(stream));
+            h_big = h_cls[0];
+            HC_TRY(launch_count_small_list(h_tc[0], t_small, n_rows, p->rowptr, p->colind, p->ncols, stream));
+            HC_TRY(launch_count_mid(h_tc[1], t_mid, n_rows, p->rowptr, p->colind, p->ncols, stream));
+            HC_TRY(launch_unique_big(h_tc[2], t_huge, n_rows, p->n_cols, p->rowptr, p->colind, tmp_cols, p->ncols, nullptr,
+                                     stream));
+        } else if (p->features_complete) {
             HC_TRY(launch_count_small(W, n_rows, p->rowptr, p->colind, p->ncols, stream));
             HC_TRY(hipMemcpyAsync(h_cls, big_count, sizeof h_cls, hipMemcpyDeviceToHost, stream));
             HC_TRY(hipStreamSynchronize(stream));
@@ -744,6 +778,58 @@ static hcspmm_status static_scratch_ptr(const hcspmm_plan* plan, char** out)
     return HCSPMM_OK;
 }
 
+// everything of a plan that does not depend on the matrix's entries
+static hcspmm_status init_plan_header(hcspmm_plan* p, int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_t* d_rowptr,
+                                      const int32_t* d_colind, const float* d_vals, const hcspmm_options& o)
+{
+    memset(p, 0, sizeof *p);
+    p->H = kH; p->n_rows = n_rows; p->n_cols = n_cols; p->nnz = nnz;
+    p->W = (int32_t)(((int64_t)n_rows + kH - 1) / kH);
+    p->rowptr = d_rowptr; p->colind = d_colind; p->vals = d_vals;
+    p->opt = o;
+    p->mid_row = kMidRow;
+    p->long_row = kLongRow;
+    // tuning knobs for experiments (not part of the ABI): override the row-tier thresholds
+    if (tune().mid_row >= 1) p->mid_row = tune().mid_row;
+    if (tune().long_row >= p->mid_row) p->long_row = tune().long_row;
+    if (p->long_row < p->mid_row) p->long_row = p->mid_row;
+    p->fused_mid_row = kFusedMidRow < p->mid_row ? p->mid_row : (kFusedMidRow > p->long_row ? p->long_row : kFusedMidRow);
+    p->slice_cols = kSliceCols;
+    if (tune().slice_cols >= kKcBig) p->slice_cols = tune().slice_cols / kKcBig * kKcBig;
+    if (o.use_custom_selector) {
+        for (int i = 0; i < 3; ++i) {
+            if (o.sel_coef[i] <= -((int64_t)1 << 40) || o.sel_coef[i] >= ((int64_t)1 << 40)) {
+                set_error("selector coefficients must be below 2^40 in magnitude");
+                return HCSPMM_EINVAL;
+            }
+            p->coef[i] = o.sel_coef[i];
+        }
+    } else {
+        lookup_selector(o.mfma_dtype, o.d_hint, nnz, p->coef);
+    }
+    if (hipGetDevice(&p->device) != hipSuccess) { (void)hipGetLastError(); set_error("hipGetDevice failed"); return HCSPMM_EHIP; }
+    // set-up of hcspmm_spmm_noalloc: this device's address of the static scratch array, looked up once per device
+    char* unused = nullptr;
+    return static_scratch_ptr(p, &unused);
+}
+
+// side streams (default priority) and events for running the paths side by side; optional
+// (the fork/join costs ~20 us of launch latency, so only matrices with milliseconds of work use them)
+static void setup_side_streams(hcspmm_plan* p)
+{
+    if (p->side_ok || p->side[0]) return;
+    p->side_ok = 0;
+    if (p->n_mfma > 0 && p->n_mfma < p->W && p->nnz >= 16000000 && !tune().serial) {
+        bool ok = hipStreamCreateWithFlags(&p->side[0], hipStreamNonBlocking) == hipSuccess;
+        ok = ok && hipStreamCreateWithFlags(&p->side[1], hipStreamNonBlocking) == hipSuccess;
+        ok = ok && hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming) == hipSuccess;
+        ok = ok && hipEventCreateWithFlags(&p->ev_join[0], hipEventDisableTiming) == hipSuccess;
+        ok = ok && hipEventCreateWithFlags(&p->ev_join[1], hipEventDisableTiming) == hipSuccess;
+        if (!ok) (void)hipGetLastError();
+        p->side_ok = ok ? 1 : 0;
+    }
+}
+
 extern "C" {
 
 void hcspmm_default_options(hcspmm_options* opt)
@@ -790,54 +876,74 @@ hcspmm_status hcspmm_prepare(int32_t n_rows, int32_t n_cols, int64_t nnz, const 
     if (o.matrix_kernels < 0 || o.matrix_kernels > 2) { set_error("bad matrix_kernels"); return HCSPMM_EINVAL; }
     hcspmm_plan* p = new (std::nothrow) hcspmm_plan();
     if (!p) { set_error("host allocation failed"); return HCSPMM_EALLOC; }
-    memset(p, 0, sizeof *p);
-    p->H = kH; p->n_rows = n_rows; p->n_cols = n_cols; p->nnz = nnz;
-    p->W = (int32_t)(((int64_t)n_rows + kH - 1) / kH);
-    p->rowptr = d_rowptr; p->colind = d_colind; p->vals = d_vals;
-    p->opt = o;
-    p->mid_row = kMidRow;
-    p->long_row = kLongRow;
-    // tuning knobs for experiments (not part of the ABI): override the row-tier thresholds
-    if (tune().mid_row >= 1) p->mid_row = tune().mid_row;
-    if (tune().long_row >= p->mid_row) p->long_row = tune().long_row;
-    if (p->long_row < p->mid_row) p->long_row = p->mid_row;
-    p->fused_mid_row = kFusedMidRow < p->mid_row ? p->mid_row : (kFusedMidRow > p->long_row ? p->long_row : kFusedMidRow);
-    p->slice_cols = kSliceCols;
-    if (tune().slice_cols >= kKcBig) p->slice_cols = tune().slice_cols / kKcBig * kKcBig;
-    if (o.use_custom_selector) {
-        for (int i = 0; i < 3; ++i) {
-            if (o.sel_coef[i] <= -((int64_t)1 << 40) || o.sel_coef[i] >= ((int64_t)1 << 40)) {
-                delete p;
-                set_error("selector coefficients must be below 2^40 in magnitude");
-                return HCSPMM_EINVAL;
-            }
-            p->coef[i] = o.sel_coef[i];
-        }
-    } else {
-        lookup_selector(o.mfma_dtype, o.d_hint, nnz, p->coef);
-    }
-    if (hipGetDevice(&p->device) != hipSuccess) { (void)hipGetLastError(); delete p; set_error("hipGetDevice failed"); return HCSPMM_EHIP; }
-    {
-        // set-up of hcspmm_spmm_noalloc: this device's address of the static scratch array, looked up once per device
-        char* unused = nullptr;
-        const hcspmm_status st0 = static_scratch_ptr(p, &unused);
-        if (st0 != HCSPMM_OK) { delete p; return st0; }
-    }
-    hcspmm_status st = build_plan(p, static_cast<hipStream_t>(stream));
+    hcspmm_status st = init_plan_header(p, n_rows, n_cols, nnz, d_rowptr, d_colind, d_vals, o);
     if (st != HCSPMM_OK) { delete p; return st; }
-    // side streams (default priority) and events for running the paths side by side; optional
-    p->side_ok = 0;
-    // (the fork/join costs ~20 us of launch latency, so only matrices with milliseconds of work use them)
-    if (p->n_mfma > 0 && p->n_mfma < p->W && p->nnz >= 16000000 && !tune().serial) {
-        bool ok = hipStreamCreateWithFlags(&p->side[0], hipStreamNonBlocking) == hipSuccess;
-        ok = ok && hipStreamCreateWithFlags(&p->side[1], hipStreamNonBlocking) == hipSuccess;
-        ok = ok && hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming) == hipSuccess;
-        ok = ok && hipEventCreateWithFlags(&p->ev_join[0], hipEventDisableTiming) == hipSuccess;
-        ok = ok && hipEventCreateWithFlags(&p->ev_join[1], hipEventDisableTiming) == hipSuccess;
-        if (!ok) (void)hipGetLastError();
-        p->side_ok = ok ? 1 : 0;
-    }
+    st = build_plan(p, static_cast<hipStream_t>(stream));
+    if (st != HCSPMM_OK) { delete p; return st; }
+    setup_side_streams(p);
     *out_plan = p;
+    return HCSPMM_OK;
+}
+
+hcspmm_status hcspmm_plan_update(hcspmm_plan* plan, int64_t nnz, const int32_t* d_rowptr, const int32_t* d_colind,
+                                 const float* d_vals, const int32_t* h_changed_rows, int32_t n_changed, void* stream)
+{
+    if (!plan) { set_error("plan is NULL"); return HCSPMM_EINVAL; }
+    if (nnz < 0 || n_changed < 0 || (n_changed > 0 && !h_changed_rows)) { set_error("negative size or NULL row list"); return HCSPMM_EINVAL; }
+    if (nnz >= ((int64_t)1 << 31)) { set_error("nnz must be below 2^31"); return HCSPMM_EUNSUPPORTED; }
+    if (!d_rowptr || (nnz > 0 && (!d_colind || !d_vals))) { set_error("NULL CSR array"); return HCSPMM_EINVAL; }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // the windows that hold a changed row, ascending and distinct
+    std::vector<int32_t> touched;
+    {
+        std::vector<uint8_t> mark((size_t)plan->W, 0);
+        for (int32_t i = 0; i < n_changed; ++i) {
+            const int32_t r = h_changed_rows[i];
+            if (r < 0 || r >= plan->n_rows) { set_error("changed row %d is outside the matrix", r); return HCSPMM_EINVAL; }
+            mark[(size_t)(r / kH)] = 1;
+        }
+        for (int32_t w = 0; w < plan->W; ++w)
+            if (mark[(size_t)w]) touched.push_back(w);
+    }
+    HC_HIP(hipStreamSynchronize(s));                             // calls that still use the old arrays are done
+    hcspmm_plan fresh;
+    hcspmm_status st = init_plan_header(&fresh, plan->n_rows, plan->n_cols, nnz, d_rowptr, d_colind, d_vals, plan->opt);
+    if (st != HCSPMM_OK) return st;
+    int32_t* d_touched = nullptr;
+    PlanCarry carry{plan->ncols, nullptr, (int32_t)touched.size()};
+    // The counts of untouched windows are carried over whenever the old plan has them and fewer than an eighth of
+    // the windows changed (beyond that the list-driven passes cost as much as the plain ones); otherwise this is a
+    // preparation from scratch.
+    const bool incremental = plan->features_complete && plan->nnz > 0 && !touched.empty() && 8 * (int64_t)touched.size() < plan->W &&
+                             !(plan->opt.route_mode == HCSPMM_ROUTE_ALL_CSR);
+    if (incremental) {
+        if (hipMalloc((void**)&d_touched, touched.size() * sizeof(int32_t)) != hipSuccess) {
+            (void)hipGetLastError(); set_error("device allocation failed"); return HCSPMM_EALLOC;
+        }
+        if (hipMemcpyAsync(d_touched, touched.data(), touched.size() * sizeof(int32_t), hipMemcpyHostToDevice, s) != hipSuccess) {
+            (void)hipGetLastError(); (void)hipFree(d_touched); set_error("copy of the window list failed"); return HCSPMM_EHIP;
+        }
+        carry.touched = d_touched;
+    }
+    const bool nothing_changed = touched.empty() && nnz == plan->nnz && plan->features_complete;
+    if (nothing_changed) {
+        // same structure: only the borrowed pointers move
+        plan->rowptr = d_rowptr; plan->colind = d_colind; plan->vals = d_vals;
+        return HCSPMM_OK;
+    }
+    st = build_plan(&fresh, s, incremental ? &carry : nullptr);
+    if (d_touched) (void)hipFree(d_touched);
+    if (st != HCSPMM_OK) return st;                              // the old plan is untouched and still valid for the old arrays
+    // the new tables replace the old ones; streams, events and the lazily sized scratch buffers stay
+    fresh.partial = plan->partial; fresh.partial_elems = plan->partial_elems;
+    fresh.tile_partial = plan->tile_partial; fresh.tile_partial_elems = plan->tile_partial_elems;
+    plan->partial = nullptr; plan->tile_partial = nullptr;
+    free_plan_arrays(plan);
+    fresh.side_ok = plan->side_ok;
+    fresh.side[0] = plan->side[0]; fresh.side[1] = plan->side[1];
+    fresh.ev_fork = plan->ev_fork; fresh.ev_join[0] = plan->ev_join[0]; fresh.ev_join[1] = plan->ev_join[1];
+    *plan = fresh;
+    setup_side_streams(plan);
     return HCSPMM_OK;
 }
 

@@ -519,6 +519,65 @@ __global__ __launch_bounds__(1024) void k_count_mid(const int32_t* __restrict__ 
     count_distinct_body<1024, 2 * kCountMidCap>(mid_list[blockIdx.x], n_rows, rowptr, colind, ncols, table, smem);
 }
 
+// ---- incremental preparation: only the windows that hold a changed row are looked at again ------
+// classes of the touched windows by size (which counting kernel serves them), and the range check of their columns
+__global__ __launch_bounds__(256) void k_touched_classes(int32_t n_touched, const int32_t* __restrict__ touched,
+                                                         int32_t n_rows, int32_t n_cols, const int32_t* __restrict__ rowptr,
+                                                         const int32_t* __restrict__ colind, int32_t* __restrict__ t_small,
+                                                         int32_t* __restrict__ t_mid, int32_t* __restrict__ t_huge,
+                                                         int32_t* __restrict__ counts /* 3 */, int32_t* __restrict__ err)
+{
+    const int32_t w = touched[blockIdx.x];
+    int32_t s, e;
+    window_span(w, n_rows, rowptr, s, e);
+    const int32_t n = e - s;
+    if (threadIdx.x == 0) {
+        if (n > kCountMidCap) t_huge[atomicAdd(counts + 2, 1)] = w;
+        else if (n > kUniqueSmallCap) t_mid[atomicAdd(counts + 1, 1)] = w;
+        else t_small[atomicAdd(counts, 1)] = w;
+    }
+    bool bad = false;
+    for (int32_t k = s + threadIdx.x; k < e; k += 256) {
+        const int32_t c = colind[k];
+        bad |= (c < 0 || c >= n_cols);
+    }
+    if (bad) atomicOr(err, 8);
+}
+
+__global__ __launch_bounds__(256) void k_count_small_list(const int32_t* __restrict__ list, int32_t n_rows,
+                                                          const int32_t* __restrict__ rowptr,
+                                                          const int32_t* __restrict__ colind, int32_t* __restrict__ ncols)
+{
+    __shared__ int32_t table[2 * kUniqueSmallCap];
+    __shared__ int smem[256 / 64 + 1];
+    count_distinct_body<256, 2 * kUniqueSmallCap>(list[blockIdx.x], n_rows, rowptr, colind, ncols, table, smem);
+}
+
+hipError_t launch_touched_classes(int32_t n_touched, const int32_t* touched, int32_t n_rows, int32_t n_cols,
+                                  const int32_t* rowptr, const int32_t* colind, int32_t* t_small, int32_t* t_mid,
+                                  int32_t* t_huge, int32_t* counts, int32_t* err, hipStream_t s)
+{
+    if (n_touched <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_touched_classes, dim3(n_touched), dim3(256), 0, s, n_touched, touched, n_rows, n_cols, rowptr, colind,
+                       t_small, t_mid, t_huge, counts, err);
+    return hipGetLastError();
+}
+
+hipError_t launch_count_small_list(int32_t n_list, const int32_t* list, int32_t n_rows, const int32_t* rowptr,
+                                   const int32_t* colind, int32_t* ncols, hipStream_t s)
+{
+    if (n_list <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_count_small_list, dim3(n_list), dim3(256), 0, s, list, n_rows, rowptr, colind, ncols);
+    return hipGetLastError();
+}
+
+hipError_t launch_validate_rowptr(int32_t n_rows, int64_t nnz, const int32_t* rowptr, int32_t* err_flag, hipStream_t s)
+{
+    const unsigned g = (unsigned)(((int64_t)n_rows + 1 + 255) / 256);
+    hipLaunchKernelGGL(k_validate_rowptr, dim3(g), dim3(256), 0, s, n_rows, nnz, rowptr, err_flag);
+    return hipGetLastError();
+}
+
 hipError_t launch_count_small(int32_t W, int32_t n_rows, const int32_t* rowptr, const int32_t* colind, int32_t* ncols,
                               hipStream_t s)
 {
