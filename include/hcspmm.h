@@ -306,9 +306,14 @@ hcspmm_status hcspmm_spmm_timed(const hcspmm_plan* plan, const void* d_X, int64_
 /*
  * GCN layer  Y = act(A (X W))  (Eq. 1 and Eq. 2; Section V-A couples the two
  * phases).  The update X W is formed first by an fp32 MFMA GEMM into the
- * workspace, which is consumed at once by the hybrid SpMM while it is still
- * cache-resident; the activation (ReLU when apply_relu != 0) is applied in the
- * SpMM epilogue, after the complete row sum.
+ * workspace and the hybrid SpMM gathers its rows from there at once; the
+ * activation (ReLU when apply_relu != 0) is applied in the SpMM epilogue, after
+ * the complete row sum, so the call is two kernel families and no separate
+ * activation or layout pass.  In this association every window needs arbitrary
+ * rows of X W, so the intermediate cannot stay inside one kernel (Section V-A
+ * says the same of update-before-aggregate), and at the benchmark's layer size
+ * the call costs what the two stages cost separately (hcspmm_gcn_layer_ex can
+ * store the intermediate in 16 bits, which halves the gather bytes).
  *
  *   d_X   device, n_cols x d_in fp32 (ldx >= d_in);  d_W  device, d_in x d_out fp32 (ldw >= d_out)
  *   d_Y   device, n_rows x d_out fp32 (ldy >= d_out)
