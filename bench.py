@@ -125,12 +125,15 @@ def main():
             g = random_relabel(g, seed=777)
         if args.loa is not None:
             t1 = time.perf_counter()
-            order = hc.hcspmm_loa_order(g.n_rows, g.n_cols, g.rowptr, g.colind, args.loa)
+            order, before, after = hc.hcspmm_loa_order_checked(g.n_rows, g.n_cols, g.rowptr, g.colind, args.loa)
             layout["loa_order_ms"] = round((time.perf_counter() - t1) * 1e3, 1)
-            t1 = time.perf_counter()
-            rp2, ci2, va2 = hc.hcspmm_permute_csr(g.n_rows, g.rowptr, g.colind, g.vals, order)
-            layout["permute_ms"] = round((time.perf_counter() - t1) * 1e3, 1)
-            g = CSRGraph(g.n_rows, g.n_cols, rp2, ci2, va2)
+            layout["total_ncols_before"], layout["total_ncols_after"] = before, after
+            layout["applied"] = bool(after < before)
+            if after < before:                       # the regrouping can scatter a layout that already had locality
+                t1 = time.perf_counter()
+                rp2, ci2, va2 = hc.hcspmm_permute_csr(g.n_rows, g.rowptr, g.colind, g.vals, order)
+                layout["permute_ms"] = round((time.perf_counter() - t1) * 1e3, 1)
+                g = CSRGraph(g.n_rows, g.n_cols, rp2, ci2, va2)
         log("layout: %s" % layout)
     X_in = X
     if name == "C5":                      # SpMM stage of the layer: T = X W has the layer's output width

@@ -436,6 +436,18 @@ hcspmm_status hcspmm_loa_order(int32_t n_rows, int32_t n_cols, const int32_t* h_
                                int32_t vw, int32_t window_rows, int32_t* h_order /* host, out */);
 
 /*
+ * hcspmm_loa_order plus its effect: h_total_ncols[0] receives the sum over all row windows of the number of
+ * distinct columns for the layout as stored, h_total_ncols[1] the same sum for the returned order (the number of
+ * non-zeros divided by these sums is the computing intensity of Eq. 5 over the whole matrix, before and after).
+ * The greedy regrouping starts from the vertices sorted by their smallest neighbour, which can scatter a layout
+ * that already had locality: apply the order only when h_total_ncols[1] < h_total_ncols[0].  The two sums are
+ * computed by several host threads.
+ */
+hcspmm_status hcspmm_loa_order_checked(int32_t n_rows, int32_t n_cols, const int32_t* h_rowptr, const int32_t* h_colind,
+                                       int32_t vw, int32_t window_rows, int32_t* h_order /* host, out */,
+                                       int64_t* h_total_ncols /* host, out, 2 entries */);
+
+/*
  * Applies a vertex order to a square CSR matrix on the host ("reorder G", Alg. 5): row and column
  * h_order[i] of the input become row and column i of the output, columns ascending within a row.
  * With P the permutation matrix of the order, the output is P A P^T, so Y' = A' X' holds for

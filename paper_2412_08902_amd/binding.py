@@ -24,7 +24,7 @@ EXPORTED_SYMBOLS = [
     "hcspmm_plan_export", "hcspmm_plan_export_runs", "hcspmm_plan_update", "hcspmm_spmm", "hcspmm_spmm_noalloc", "hcspmm_spmm_noalloc_scratch_limit", "hcspmm_spmm_timed", "hcspmm_gcn_layer", "hcspmm_gcn_layer_ex", "hcspmm_gcn_workspace_bytes",
     "hcspmm_aggregate_update", "hcspmm_aggregate_update_workspace_bytes",
     "hcspmm_layer_backward", "hcspmm_layer_backward_workspace_bytes",
-    "hcspmm_gemm_f32", "hcspmm_plan_set_update_fusion", "hcspmm_probe_gather", "hcspmm_probe_gather_out_bytes", "hcspmm_loa_order", "hcspmm_permute_csr", "hcspmm_transpose_csr", "hcspmm_plan_destroy", "hcspmm_status_string", "hcspmm_last_error", "hcspmm_version",
+    "hcspmm_gemm_f32", "hcspmm_plan_set_update_fusion", "hcspmm_probe_gather", "hcspmm_probe_gather_out_bytes", "hcspmm_loa_order", "hcspmm_loa_order_checked", "hcspmm_permute_csr", "hcspmm_transpose_csr", "hcspmm_plan_destroy", "hcspmm_status_string", "hcspmm_last_error", "hcspmm_version",
 ]
 
 
@@ -112,6 +112,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.hcspmm_layer_backward_workspace_bytes.restype = ctypes.c_size_t
     lib.hcspmm_loa_order.argtypes = [i32, i32, vp, vp, i32, i32, vp]
     lib.hcspmm_loa_order.restype = ctypes.c_int
+    lib.hcspmm_loa_order_checked.argtypes = [i32, i32, vp, vp, i32, i32, vp, vp]
+    lib.hcspmm_loa_order_checked.restype = ctypes.c_int
     lib.hcspmm_permute_csr.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp]
     lib.hcspmm_permute_csr.restype = ctypes.c_int
     lib.hcspmm_transpose_csr.argtypes = [i32, i32, vp, vp, vp, vp, vp, vp]
@@ -407,6 +409,19 @@ def hcspmm_loa_order(n_rows: int, n_cols: int, rowptr, colind, vw: int, window_r
     _check(load_library().hcspmm_loa_order(n_rows, n_cols, _host_ptr(rowptr), _host_ptr(colind), vw, window_rows,
                                            _host_ptr(order)))
     return order
+
+
+def hcspmm_loa_order_checked(n_rows: int, n_cols: int, rowptr, colind, vw: int, window_rows: int = 16):
+    """hcspmm_loa_order plus (total_ncols before, total_ncols after): apply the order only when the second is smaller."""
+    import numpy as np
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int32)
+    colind = np.ascontiguousarray(colind, dtype=np.int32)
+    assert rowptr.shape[0] == n_rows + 1
+    order = np.empty(n_rows, dtype=np.int32)
+    totals = np.zeros(2, dtype=np.int64)
+    _check(load_library().hcspmm_loa_order_checked(n_rows, n_cols, _host_ptr(rowptr), _host_ptr(colind), vw, window_rows,
+                                                   _host_ptr(order), ctypes.c_void_p(totals.ctypes.data)))
+    return order, int(totals[0]), int(totals[1])
 
 
 def hcspmm_permute_csr(n: int, rowptr, colind, vals, order):

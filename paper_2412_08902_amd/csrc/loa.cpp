@@ -13,6 +13,7 @@
 #include <limits>
 #include <new>
 #include <numeric>
+#include <thread>
 #include <vector>
 
 #include "common.hpp"
@@ -150,6 +151,62 @@ hcspmm_status hcspmm_loa_order(int32_t n_rows, int32_t n_cols, const int32_t* h_
         }
     } catch (const std::bad_alloc&) {
         set_error("host allocation failed in layout reformatting");
+        return HCSPMM_EALLOC;
+    }
+    return HCSPMM_OK;
+}
+
+// Sum over the row windows of the number of distinct columns, for the rows grouped as `order` lists them (NULL: as
+// stored).  The windows are independent: worker threads take contiguous ranges of windows, each with its own stamp
+// array over the columns.
+static int64_t total_window_columns(int32_t n_rows, int32_t n_cols, const int32_t* rowptr, const int32_t* colind,
+                                    const int32_t* order, int32_t window_rows)
+{
+    const int64_t n_win = ((int64_t)n_rows + window_rows - 1) / window_rows;
+    unsigned n_thr = std::thread::hardware_concurrency();
+    if (n_thr < 1) n_thr = 1;
+    if (n_thr > 16) n_thr = 16;
+    if ((int64_t)n_thr > n_win) n_thr = (unsigned)(n_win > 0 ? n_win : 1);
+    std::vector<int64_t> part(n_thr, 0);
+    auto work = [&](unsigned t) {
+        std::vector<int32_t> stamp((size_t)n_cols, -1);
+        const int64_t w0 = n_win * t / n_thr, w1 = n_win * (t + 1) / n_thr;
+        int64_t sum = 0;
+        for (int64_t w = w0; w < w1; ++w) {
+            const int64_t r1 = std::min<int64_t>((w + 1) * window_rows, n_rows);
+            for (int64_t i = w * window_rows; i < r1; ++i) {
+                const int32_t v = order ? order[i] : (int32_t)i;
+                for (int32_t k = rowptr[v]; k < rowptr[v + 1]; ++k) {
+                    const int32_t c = colind[k];
+                    if (stamp[c] != (int32_t)w) { stamp[c] = (int32_t)w; ++sum; }
+                }
+            }
+        }
+        part[t] = sum;
+    };
+    std::vector<std::thread> pool;
+    for (unsigned t = 1; t < n_thr; ++t) pool.emplace_back(work, t);
+    work(0);
+    for (std::thread& th : pool) th.join();
+    int64_t total = 0;
+    for (int64_t v : part) total += v;
+    return total;
+}
+
+hcspmm_status hcspmm_loa_order_checked(int32_t n_rows, int32_t n_cols, const int32_t* h_rowptr, const int32_t* h_colind,
+                                       int32_t vw, int32_t window_rows, int32_t* h_order, int64_t* h_total_ncols)
+{
+    const hcspmm_status st = hcspmm_loa_order(n_rows, n_cols, h_rowptr, h_colind, vw, window_rows, h_order);
+    if (st != HCSPMM_OK) return st;
+    if (!h_total_ncols) { hcspmm::set_error("h_total_ncols is NULL"); return HCSPMM_EINVAL; }
+    h_total_ncols[0] = h_total_ncols[1] = 0;
+    if (n_rows == 0) return HCSPMM_OK;
+    try {
+        // hcspmm_loa_order has validated the arrays
+        h_total_ncols[0] = total_window_columns(n_rows, n_cols, h_rowptr, h_colind, nullptr, window_rows);
+        h_total_ncols[1] = total_window_columns(n_rows, n_cols, h_rowptr, h_colind, h_order, window_rows);
+    } catch (const std::exception&) {
+        hcspmm::set_error("host allocation or thread start failed while evaluating the layout");
         return HCSPMM_EALLOC;
     }
     return HCSPMM_OK;

@@ -121,3 +121,22 @@ def test_transpose_csr_rejects_bad_input():
         hc.hcspmm_transpose_csr(2, 3, np.array([0, 1, 2], np.int32), np.array([0, 3], np.int32), np.ones(2, np.float32))
     with pytest.raises(hc.HcspmmError):
         hc.hcspmm_transpose_csr(2, 3, np.array([0, 2, 1], np.int32), np.array([0, 1], np.int32), np.ones(2, np.float32))
+
+
+def test_checked_order_reports_the_windows_distinct_columns_before_and_after():
+    """total_ncols of the stored layout and of the returned order, against the plan oracle's own count; on a block
+    graph whose blocks are contiguous the regrouping makes the layout worse, and the numbers say so."""
+    import oracle
+    import paper_2412_08902_amd.binding as hc
+    g = sbm_graph(40, 64, 0.25, 4.0, seed=3)
+    order, before, after = hc.hcspmm_loa_order_checked(g.n_rows, g.n_cols, g.rowptr, g.colind, 256)
+    assert np.array_equal(order, hc.hcspmm_loa_order(g.n_rows, g.n_cols, g.rowptr, g.colind, 256))
+    plan = oracle.derive_plan_vectorised(g.rowptr, g.colind, [0, 0, 1], n_cols=g.n_cols)
+    assert before == int(plan["ncols"].sum())
+    rp2, ci2, _ = hc.hcspmm_permute_csr(g.n_rows, g.rowptr, g.colind, g.vals, order)
+    plan2 = oracle.derive_plan_vectorised(rp2, ci2, [0, 0, 1], n_cols=g.n_cols)
+    assert after == int(plan2["ncols"].sum())
+    assert after > before                               # contiguous blocks: leave this layout alone
+    gs = random_relabel(g, seed=9)                      # no locality: here the regrouping helps
+    _, before_s, after_s = hc.hcspmm_loa_order_checked(gs.n_rows, gs.n_cols, gs.rowptr, gs.colind, 256)
+    assert after_s < before_s
