@@ -665,14 +665,17 @@ __global__ __launch_bounds__(256) void k_probe_gather(const int32_t* __restrict_
                                                       const float* __restrict__ X, int64_t ldx, int32_t d,
                                                       int32_t n_rows_x, float* __restrict__ out)
 {
-    const int64_t grp = (int64_t)blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
+    // workgroups in XCD-local runs of 32, like the scalar path's short rows (the grid is padded to whole rounds)
+    const int64_t x = blockIdx.x & 7, q = blockIdx.x >> 3;
+    const int64_t blk = ((q / 32) * 8 + x) * 32 + q % 32;
+    const int64_t grp = blk * (256 / LPR) + threadIdx.x / LPR;
     const int lig = threadIdx.x % LPR;
-    const int64_t b = grp * per_group, e = min(n, b + per_group);
+    const int64_t b = min(n, grp * per_group), e = min(n, b + per_group);
     const int c = 4 * lig < d ? 4 * lig : 0;
     const char* __restrict__ Xc = reinterpret_cast<const char*>(X + c);
     float acc[4];
     vzero<4>(acc);
-    for (int64_t k0 = b; k0 < e; k0 += LPR) {
+    for (int64_t k0 = b; k0 < e; k0 += LPR) {                   // (a group past the end of the stream has b == e)
         const int64_t k = min(k0 + lig, e - 1);
         const int32_t mc = min(max(index[k], 0), n_rows_x - 1);       // whatever the stream holds, the read stays inside X
         batch_accumulate<LPR, 4, 0>(mc, 1.f, (int)min((int64_t)LPR, e - k0), Xc, ldx * 4, acc);
@@ -685,9 +688,10 @@ int64_t probe_gather_blocks(int64_t n, int32_t d)
     int lpr = 8;
     while (lpr < 64 && lpr * 4 < d) lpr <<= 1;
     const int64_t groups_per_block = 256 / lpr;
-    // about 2048 indices per lane group: long enough to amortise the start-up, short enough for tens of thousands of waves
-    const int64_t groups = (n + 2047) / 2048;
-    return (groups + groups_per_block - 1) / groups_per_block;
+    // 512 indices per lane group: long enough to amortise the start-up, short enough for tens of thousands of waves
+    const int64_t groups = (n + 511) / 512;
+    const int64_t blocks = (groups + groups_per_block - 1) / groups_per_block;
+    return (blocks + 255) / 256 * 256;                         // whole rounds of eight XCD-local runs of 32 workgroups
 }
 
 hipError_t launch_probe_gather(const int32_t* index, int64_t n, const float* X, int64_t ldx, int32_t d, int32_t n_rows_x,
@@ -697,7 +701,7 @@ hipError_t launch_probe_gather(const int32_t* index, int64_t n, const float* X, 
     int lpr = 8;
     while (lpr < 64 && lpr * 4 < d) lpr <<= 1;
     const int64_t blocks = probe_gather_blocks(n, d);
-    const int64_t per_group = 2048;
+    const int64_t per_group = 512;
 #define HC_PROBE(L) hipLaunchKernelGGL((k_probe_gather<L>), dim3((unsigned)blocks), dim3(256), 0, s, index, n, per_group, X, ldx, d, n_rows_x, out)
     switch (lpr) {
         case 8: HC_PROBE(8); break;
