@@ -683,25 +683,36 @@ __global__ __launch_bounds__(256) void k_probe_gather(const int32_t* __restrict_
     *reinterpret_cast<float4*>(out + ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4) = make_float4(acc[0], acc[1], acc[2], acc[3]);
 }
 
-int64_t probe_gather_blocks(int64_t n, int32_t d)
+// Launch shape of the probe: lanes per row from d like the scalar path; indices per lane group 512 (long enough
+// to amortise the start-up) unless the stream is too short to give every CU some tens of workgroups that way --
+// then fewer, down to 64.
+static void probe_gather_shape(int64_t n, int32_t d, int& lpr, int64_t& per_group, int64_t& blocks)
 {
-    int lpr = 8;
+    lpr = 8;
     while (lpr < 64 && lpr * 4 < d) lpr <<= 1;
     const int64_t groups_per_block = 256 / lpr;
-    // 512 indices per lane group: long enough to amortise the start-up, short enough for tens of thousands of waves
-    const int64_t groups = (n + 511) / 512;
-    const int64_t blocks = (groups + groups_per_block - 1) / groups_per_block;
-    return (blocks + 255) / 256 * 256;                         // whole rounds of eight XCD-local runs of 32 workgroups
+    per_group = (n / (8192 * groups_per_block) + 63) / 64 * 64;
+    per_group = per_group < 64 ? 64 : (per_group > 512 ? 512 : per_group);
+    const int64_t groups = (n + per_group - 1) / per_group;
+    blocks = (groups + groups_per_block - 1) / groups_per_block;
+    blocks = (blocks + 255) / 256 * 256;                       // whole rounds of eight XCD-local runs of 32 workgroups
+}
+
+int64_t probe_gather_blocks(int64_t n, int32_t d)
+{
+    int lpr;
+    int64_t per_group, blocks;
+    probe_gather_shape(n, d, lpr, per_group, blocks);
+    return blocks;
 }
 
 hipError_t launch_probe_gather(const int32_t* index, int64_t n, const float* X, int64_t ldx, int32_t d, int32_t n_rows_x,
                                float* out, hipStream_t s)
 {
     if (n <= 0) return hipSuccess;
-    int lpr = 8;
-    while (lpr < 64 && lpr * 4 < d) lpr <<= 1;
-    const int64_t blocks = probe_gather_blocks(n, d);
-    const int64_t per_group = 512;
+    int lpr;
+    int64_t per_group, blocks;
+    probe_gather_shape(n, d, lpr, per_group, blocks);
 #define HC_PROBE(L) hipLaunchKernelGGL((k_probe_gather<L>), dim3((unsigned)blocks), dim3(256), 0, s, index, n, per_group, X, ldx, d, n_rows_x, out)
     switch (lpr) {
         case 8: HC_PROBE(8); break;

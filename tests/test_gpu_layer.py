@@ -10,15 +10,19 @@ pytestmark = pytest.mark.gpu
 TOL_F32 = 1e-5
 
 
+@pytest.mark.parametrize("pad", [3, 2])        # odd and even leading dimension of T: single and paired stores
 @pytest.mark.parametrize("m,k,n", [(1, 1, 1), (130, 17, 5), (257, 602, 128), (128, 16, 128), (300, 64, 200),
-                                   (1000, 33, 64), (64, 250, 130),
+                                   (1000, 33, 64), (64, 250, 130), (96, 0, 8),
+                                   # 256 tall row tiles and a ragged tail of 32-row tiles; K with a partial last slab
+                                   (32768 + 77, 40, 128), (2 * 32768 + 32 * 5, 24, 130), (32768, 32, 12),
                                    # narrow outputs with K a multiple of 16: the 16-row streaming route
                                    (257, 32, 32), (1000, 64, 16), (300, 256, 7), (5000, 128, 64), (15, 16, 1), (70001, 48, 33)])
-def test_gemm(m, k, n):
+def test_gemm(m, k, n, pad):
     import torch
     import paper_2412_08902_amd.binding as hc
-    X, W = dense_normal(m, k, seed=m + k), dense_normal(k, n, seed=k + n)
-    T = torch.full((m, n + 3), -5.0, device="cuda")
+    X, W = dense_normal(m, max(k, 1), seed=m + k)[:, :k], dense_normal(max(k, 1), n, seed=k + n)[:k]
+    X, W = np.ascontiguousarray(X), np.ascontiguousarray(W)
+    T = torch.full((m, n + pad), -5.0, device="cuda")
     hc.hcspmm_gemm_f32(torch.from_numpy(X).cuda(), torch.from_numpy(W).cuda(), T[:, :n])
     torch.cuda.synchronize()
     got = T.cpu().numpy().astype(np.float64)
@@ -26,6 +30,30 @@ def test_gemm(m, k, n):
     ref = oracle.gemm(X, W)
     bound = oracle.gemm(X, W, use_abs=True)
     assert_close(got[:, :n], ref, bound, TOL_F32)
+
+
+@pytest.mark.parametrize("m,k,n", [(700, 75, 132), (129, 602, 128), (33, 32, 4), (5, 38, 2)])
+@pytest.mark.parametrize("xoff,ldx_extra", [(0, 1), (0, 0), (2, 1), (1, 0), (4, 1), (0, 3), (2, 3), (6, 7)])
+def test_gemm_operand_alignment(m, k, n, xoff, ldx_extra):
+    """X views whose base and leading dimension allow aligned 16-byte loads, 16-byte pieces around 8-byte aligned rows
+    (base on or off a 16-byte boundary; the first and the last piece stick out of the matrix), or only 4-byte loads;
+    W with an odd leading dimension.  X sits at the very start and end of its allocation's used range."""
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    X, W = dense_normal(m, k, seed=5), dense_normal(k, n, seed=6)
+    ldx = k + ldx_extra
+    flat = torch.full((xoff + (m - 1) * ldx + k,), float("nan"), device="cuda")       # nothing valid outside the view
+    Xv = torch.as_strided(flat, (m, k), (ldx, 1), xoff)
+    Xv.copy_(torch.from_numpy(X).cuda())
+    if ldx_extra:
+        pad = torch.as_strided(flat, (m - 1, ldx_extra), (ldx, 1), xoff + k)
+        pad.fill_(float("nan"))
+    Wbig = torch.zeros((k, n + (1 if ldx_extra % 2 else 0)), device="cuda")
+    Wbig[:, :n] = torch.from_numpy(W).cuda()
+    T = torch.full((m, n), -5.0, device="cuda")
+    hc.hcspmm_gemm_f32(Xv, Wbig[:, :n], T)
+    torch.cuda.synchronize()
+    assert_close(T.cpu().numpy().astype(np.float64), oracle.gemm(X, W), oracle.gemm(X, W, use_abs=True), TOL_F32)
 
 
 def run_layer(g, X, W, mode, relu=True):
