@@ -46,6 +46,8 @@ WORKLOAD_TEXT = {
     "C3": "C3 community SBM: N=131,072 (2,048 blocks of 64), p_in 0.25, inter degree 4, values 1, X Nx64 fp32 N(0,1)",
     "C4": "C4 large power-law: N=2,449,029, 123.7M edges + self-loops, GCN-normalised, X Nx32 fp32 U[-1,1]",
     "C5": "C5 dense-ish power-law, SpMM stage of the GCN layer: N=232,965, 114.6M edges + self-loops, T Nx128 fp32",
+    "C6": "C6 mixed (not in the baseline's list): 131,072 nodes in blocks of 64 at 75 % fill + 169,343 power-law nodes "
+          "(C2's recipe), disjoint, GCN-normalised, X Nx128 fp32 N(0,1)",
 }
 
 

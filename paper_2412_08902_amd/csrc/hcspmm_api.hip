@@ -34,7 +34,7 @@ const Tune& tune()
     static const Tune t = {env_int("HCSPMM_TUNE_MID_ROW"), env_int("HCSPMM_TUNE_LONG_ROW"), env_int("HCSPMM_TUNE_SLICE_COLS"),
                            getenv("HCSPMM_TUNE_SERIAL") ? 1 : 0, env_int("HCSPMM_TUNE_XCD_CHUNK"), env_int("HCSPMM_TUNE_RPG"),
                            env_int("HCSPMM_TUNE_TILES_PER_WAVE"), getenv("HCSPMM_TUNE_NO_ROWS16") ? 1 : 0,
-                           getenv("HCSPMM_TUNE_RUNS") ? 1 : 0, env_int("HCSPMM_TUNE_RUN_SLICE")};
+                           getenv("HCSPMM_TUNE_RUNS") ? 1 : 0, env_int("HCSPMM_TUNE_RUN_SLICE"), env_int("HCSPMM_TUNE_SIDE_NNZ")};
     return t;
 }
 
@@ -815,11 +815,12 @@ static hcspmm_status init_plan_header(hcspmm_plan* p, int32_t n_rows, int32_t n_
 
 // side streams (default priority) and events for running the paths side by side; optional
 // (the fork/join costs ~20 us of launch latency, so only matrices with milliseconds of work use them)
+constexpr int64_t kSideStreamNnz = 16000000;
 static void setup_side_streams(hcspmm_plan* p)
 {
     if (p->side_ok || p->side[0]) return;
     p->side_ok = 0;
-    if (p->n_mfma > 0 && p->n_mfma < p->W && p->nnz >= 16000000 && !tune().serial) {
+    if (p->n_mfma > 0 && p->n_mfma < p->W && p->nnz >= (tune().side_nnz >= 0 ? tune().side_nnz : kSideStreamNnz) && !tune().serial) {
         bool ok = hipStreamCreateWithFlags(&p->side[0], hipStreamNonBlocking) == hipSuccess;
         ok = ok && hipStreamCreateWithFlags(&p->side[1], hipStreamNonBlocking) == hipSuccess;
         ok = ok && hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming) == hipSuccess;

@@ -144,6 +144,18 @@ def test_c5_spmm_at_full_size(mode):
         assert 0.1 < share < 0.9, share
 
 
+def test_mixed_graph_routes_both_ways():
+    """The mixed graph (dense communities followed by a power-law part, d = 128): the shipped selector sends the
+    community windows to the matrix path and the power-law windows to the scalar path; sampled rows of both parts
+    against the oracle."""
+    g, X = cached_config("C6")
+    rows = sample_rows(g, 4096, seed=13)
+    info = spmm_sampled(g, X, rows, "C6 hybrid", route_mode=0)
+    n_comm = CONFIGS["C6"]["n_blocks"] * CONFIGS["C6"]["block"] // 16
+    assert info["n_mfma_windows"] == n_comm, (info["n_mfma_windows"], n_comm)
+    assert info["n_windows"] > n_comm
+
+
 def test_c5_hybrid_call_replays_from_a_hip_graph():
     """A call that forks onto the plan's side streams (large matrix, work on both paths) captured in a HIP graph:
     every replay, with eager work between the replays, reproduces the eager result bit for bit."""

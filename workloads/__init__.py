@@ -8,6 +8,7 @@ from .graphs import (  # noqa: F401
     CSRGraph,
     chung_lu_graph,
     sbm_graph,
+    disjoint_union,
     gcn_normalise,
     random_relabel,
     CONFIGS,

@@ -22,6 +22,8 @@ Stochastic block model (config 3)
     unordered pair present with probability ``p_in``; ``N * inter_deg / 2``
     distinct inter-block undirected pairs with endpoints uniform in different
     blocks; ids are then permuted at random inside each block.  No self-loops.
+Mixed (config 6, not one of the benchmark's five)
+    the block model (75 % fill) and the power law of config 2 as a disjoint union, block-model nodes first.
 Values
     1.0f, or the GCN normalisation ``1/sqrt(d_i d_j)`` with ``d_i`` the row
     length (self-loop included), computed in fp64 and rounded once to fp32.
@@ -184,6 +186,15 @@ def sbm_graph(n_blocks: int, block: int, p_in: float, inter_deg: float, seed: in
     return _pairs_to_csr(n, (keys // n).astype(np.int32), (keys % n).astype(np.int32), self_loops=False)
 
 
+def disjoint_union(a: CSRGraph, b: CSRGraph) -> CSRGraph:
+    """Block-diagonal union: the nodes of ``b`` follow those of ``a``; no edge joins the two parts."""
+    rowptr = np.concatenate([a.rowptr.astype(np.int64), a.rowptr[-1].astype(np.int64) + b.rowptr[1:].astype(np.int64)])
+    assert rowptr[-1] < 2 ** 31
+    colind = np.concatenate([a.colind, (b.colind.astype(np.int64) + a.n_cols).astype(np.int32)])
+    vals = np.concatenate([a.vals, b.vals])
+    return CSRGraph(a.n_rows + b.n_rows, a.n_cols + b.n_cols, rowptr.astype(np.int32), colind, vals)
+
+
 def gcn_normalise(g: CSRGraph) -> CSRGraph:
     """values <- 1/sqrt(d_i d_j), d_i = row length of i (self-loop already in the graph)."""
     deg = np.diff(g.rowptr.astype(np.int64)).astype(np.float64)
@@ -261,6 +272,11 @@ CONFIGS = {
                d=32, x="uniform", index=3),
     "C5": dict(kind="chung_lu", n=232_965, edges=114_600_000, gamma=1.9, max_degree=None, values="gcn",
                d=128, d_in=602, x="normal", index=4),
+    # Not one of the benchmark's five: a graph whose row windows are of both kinds -- dense communities (blocks of 64
+    # at 75 % fill) followed by a sparse power-law part (the recipe of C2) -- for the claim that per-window routing
+    # beats both single-path plans.
+    "C6": dict(kind="mixed", n_blocks=2048, block=64, p_in=0.75, inter_deg=4.0,
+               n=169343, edges=2_300_000, gamma=2.0, max_degree=13000, values="gcn", d=128, x="normal", index=5),
 }
 
 
@@ -280,6 +296,12 @@ def make_config(name: str, scale: float = 1.0, with_dense: bool = True):
         if md is not None and scale != 1.0:
             md = max(8, min(int(md * scale), n // 2))
         g = chung_lu_graph(n, e, c["gamma"], seed, max_degree=md)
+    elif c["kind"] == "mixed":
+        nb = max(2, int(round(c["n_blocks"] * scale)))
+        n = max(64, int(round(c["n"] * scale)))
+        md = c["max_degree"] if scale == 1.0 else max(8, min(int(c["max_degree"] * scale), n // 2))
+        g = disjoint_union(sbm_graph(nb, c["block"], c["p_in"], c["inter_deg"], seed),
+                           chung_lu_graph(n, int(round(c["edges"] * scale)) // 2 * 2, c["gamma"], seed + 1, max_degree=md))
     else:
         nb = max(2, int(round(c["n_blocks"] * scale)))
         g = sbm_graph(nb, c["block"], c["p_in"], c["inter_deg"], seed)
