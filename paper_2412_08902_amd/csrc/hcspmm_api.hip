@@ -66,16 +66,15 @@ static const SelectorRow kSelectorTable[] = {
     // few hundred columns stay on the scalar path (N0 = 2048), above there is no width limit.
     {HCSPMM_F32, 1 << 30, 16000000, {0, 1120000, -1048576}},     // S0 = 0.936
     {HCSPMM_F32, 1 << 30, 0, {512, 1263344, -1048576}},          // N0 = 2048, S0 = 0.83
-    // 16-bit X.  Half the gather bytes make the scalar path more than twice as fast on the large
-    // dense power-law graph (X fits the caches better), while the matrix path gains less: there the
-    // scalar path wins on every window (2.87 vs 3.48 ms all-matrix), so large matrices keep only
-    // nearly full tiles on the matrix path.  Community graphs at d = 128 still favour the matrix
-    // path (49/64/91 vs 60/78/116 us), which the small-matrix row keeps.
+    // 16-bit X: the rows of fp32.  On the large dense power-law graph half the gather bytes make the
+    // scalar path 2.2x faster than with fp32 X and the matrix path (whose 16-bit stages run three
+    // ahead) 2.0x: all-matrix 2.63 ms, all-scalar 2.85 ms, this routing 2.64 ms.  Community graphs
+    // at d = 128 favour the matrix path as in fp32 (49/64/91 vs 60/78/116 us), at d = 64 neither.
     {HCSPMM_BF16, 64, 0, {171, 4194304, -1048576}},
-    {HCSPMM_BF16, 1 << 30, 16000000, {0, 4194304, -1048576}},    // S0 = 0.25
+    {HCSPMM_BF16, 1 << 30, 16000000, {0, 1120000, -1048576}},    // S0 = 0.936
     {HCSPMM_BF16, 1 << 30, 0, {512, 1120000, -1048576}},
     {HCSPMM_F16, 64, 0, {171, 4194304, -1048576}},
-    {HCSPMM_F16, 1 << 30, 16000000, {0, 4194304, -1048576}},
+    {HCSPMM_F16, 1 << 30, 16000000, {0, 1120000, -1048576}},
     {HCSPMM_F16, 1 << 30, 0, {512, 1120000, -1048576}},
 };
 
