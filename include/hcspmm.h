@@ -253,8 +253,11 @@ hcspmm_status hcspmm_plan_export_runs(const hcspmm_plan* plan, int32_t* run_nu, 
  * largest d in use has been made, later calls allocate nothing and can be captured in a HIP graph.
  * The same holds for hcspmm_gcn_layer(_ex), hcspmm_aggregate_update and hcspmm_layer_backward: after
  * one eager call of each with the shapes in use they only enqueue kernels on `stream`.
- * On the matrix path X must be finite: the dense-tile product multiplies every gathered row with
- * explicit zeros, so a NaN or Inf in a gathered row reaches all 16 rows of its window.
+ * X must be finite.  On the matrix path the dense-tile product multiplies every gathered row with
+ * explicit zeros, so a NaN or Inf in a gathered row reaches all 16 rows of its window.  The scalar path
+ * pads a row's last batch of non-zeros with (the row's last column, value 0): an Inf in that X row
+ * then gives NaN where exact arithmetic gives +-Inf (rows that do not reference a non-finite X row
+ * are unaffected on this path).
  */
 hcspmm_status hcspmm_spmm(const hcspmm_plan* plan, const void* d_X, int64_t ldx, int32_t d, int32_t x_dtype,
                           void* d_Y, int64_t ldy, int32_t y_dtype, void* stream);
