@@ -674,7 +674,6 @@ __global__ __launch_bounds__(1024) void k_condense_rank(const int32_t* __restric
     __shared__ int32_t rp[kH + 1];
     __shared__ int32_t span_lo, span_hi;
     constexpr int kBits = kRankWords * 32;
-    constexpr int kWordsPerThread = kRankWords / 1024;
     const int32_t w = list[blockIdx.x];
     if (route[w] == 0) return;
     int32_t s, e;
@@ -700,24 +699,27 @@ __global__ __launch_bounds__(1024) void k_condense_rank(const int32_t* __restric
     __syncthreads();
     const int32_t cmax = span_hi;
     int32_t running = 0;
-    const int w0 = threadIdx.x * kWordsPerThread;
     for (int64_t base = span_lo & ~31; base <= cmax; base += kBits) {
-        for (int i = threadIdx.x; i < kRankWords; i += 1024) bm[i] = 0u;
+        // words of this pass that can hold a column of the window, dealt to the threads in equal consecutive runs
+        const int n_words = (int)min((int64_t)kRankWords, (cmax - base) / 32 + 1);
+        const int wpt = (n_words + 1023) / 1024;
+        const int w0 = threadIdx.x * wpt;
+        for (int i = threadIdx.x; i < n_words; i += 1024) bm[i] = 0u;
         __syncthreads();
         for (int32_t k = s + threadIdx.x; k < e; k += 1024) {
             const int64_t c = (int64_t)colind[k] - base;
             if (c >= 0 && c < kBits) atomicOr(&bm[c >> 5], 1u << (c & 31));
         }
         __syncthreads();
+        const int my_words = max(0, min(wpt, n_words - w0));
         int cnt = 0;
-#pragma unroll 4
-        for (int i = 0; i < kWordsPerThread; ++i) cnt += __popc(bm[w0 + i]);
+        for (int i = 0; i < my_words; ++i) cnt += __popc(bm[w0 + i]);
         int total;
         const int off = block_exclusive_scan<1024>(cnt, &total, smem);
         {
             int run = off;
             int32_t* out = wcols + wp + running + off;
-            for (int i = 0; i < kWordsPerThread; ++i) {
+            for (int i = 0; i < my_words; ++i) {
                 uint32_t bits = bm[w0 + i];
                 pre[w0 + i] = run;
                 run += __popc(bits);
