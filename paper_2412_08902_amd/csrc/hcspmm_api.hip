@@ -7,6 +7,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <deque>
 #include <mutex>
 #include <new>
 #include <vector>
@@ -238,6 +239,65 @@ fail:
     return st;
 }
 
+// Small device-to-host read-backs of a preparation go through a page of pinned host memory: a copy into
+// pageable memory costs the runtime tens of microseconds each, and a preparation makes five to eight of them.
+// The pages are allocated on first use, handed out one per running preparation and kept until the process ends.
+class PinnedPage {
+public:
+    static constexpr size_t kBytes = 4096;
+    PinnedPage()
+    {
+        std::lock_guard<std::mutex> g(mu());
+        for (Slot& sl : pool())
+            if (!sl.busy) { sl.busy = true; slot_ = &sl; return; }
+        void* q = nullptr;
+        if (hipHostMalloc(&q, kBytes, hipHostMallocPortable) != hipSuccess) { (void)hipGetLastError(); return; }
+        pool().push_back(Slot{q, true});
+        slot_ = &pool().back();
+    }
+    ~PinnedPage()
+    {
+        if (!slot_) return;
+        std::lock_guard<std::mutex> g(mu());
+        slot_->busy = false;
+    }
+    PinnedPage(const PinnedPage&) = delete;
+    PinnedPage& operator=(const PinnedPage&) = delete;
+    char* ptr() const { return slot_ ? static_cast<char*>(slot_->p) : nullptr; }
+private:
+    struct Slot { void* p; bool busy; };
+    static std::mutex& mu() { static std::mutex m; return m; }
+    static std::deque<Slot>& pool() { static std::deque<Slot> v; return v; }   // (deque: growth keeps the slots in place)
+    Slot* slot_ = nullptr;
+};
+
+// Read-backs queued on a stream into the pinned page, copied to their host destinations after the stream's next
+// synchronisation.  Without a page (or for a block that does not fit) the copy goes straight to its destination.
+struct Readback {
+    char* page = nullptr;
+    size_t used = 0;
+    struct Pending { void* dst; size_t off, n; };
+    Pending pend[16];
+    int n_pend = 0;
+    hipError_t add(void* dst, const void* src, size_t n, hipStream_t stream)
+    {
+        const size_t off = (used + 15) & ~(size_t)15;
+        if (!page || n_pend == 16 || off + n > PinnedPage::kBytes) return hipMemcpyAsync(dst, src, n, hipMemcpyDeviceToHost, stream);
+        pend[n_pend++] = Pending{dst, off, n};
+        used = off + n;
+        return hipMemcpyAsync(page + off, src, n, hipMemcpyDeviceToHost, stream);
+    }
+    hipError_t sync(hipStream_t stream)
+    {
+        const hipError_t e = hipStreamSynchronize(stream);
+        if (e == hipSuccess)
+            for (int i = 0; i < n_pend; ++i) memcpy(pend[i].dst, page + pend[i].off, pend[i].n);
+        n_pend = 0;
+        used = 0;
+        return e;
+    }
+};
+
 // What an incremental preparation carries over from the previous plan: the distinct-column counts of the windows
 // that hold no changed row (device array of the old plan) and the list of windows that do (device, distinct ids).
 struct PlanCarry { const int32_t* old_ncols; const int32_t* touched; int32_t n_touched; };
@@ -247,6 +307,9 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream, const PlanCa
     hcspmm_status st = HCSPMM_OK;
     DevAlloc tmp;      // scratch, freed on exit
     DevAlloc keep;     // plan-owned (chunks handed to the plan on success), freed on failure only
+    PinnedPage pinned;
+    Readback rb;
+    rb.page = pinned.ptr();
     const int32_t n_rows = p->n_rows, W = p->W;
     const int64_t nnz = p->nnz;
     keep.chunk_min = (size_t)1 << 20;      // small graphs: all plan arrays in one or two device allocations
@@ -288,18 +351,18 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream, const PlanCa
         HC_ALLOC(tmp, t_counts, 4);
         HC_TRY(hipMemsetAsync(t_counts, 0, 4 * sizeof(int32_t), stream));
         HC_TRY(launch_validate_rowptr(n_rows, nnz, p->rowptr, err, stream));
-        HC_TRY(hipMemcpyAsync(&h_err, err, sizeof h_err, hipMemcpyDeviceToHost, stream));
-        HC_TRY(hipStreamSynchronize(stream));
+        HC_TRY(rb.add(&h_err, err, sizeof h_err, stream));
+        HC_TRY(rb.sync(stream));
         if (!h_err) {           // the windows' spans are only meaningful with sound row offsets
             HC_TRY(launch_touched_classes(carry->n_touched, carry->touched, n_rows, p->n_cols, p->rowptr, p->colind, t_small,
                                           t_mid, t_huge, t_counts, err, stream));
-            HC_TRY(hipMemcpyAsync(h_tc, t_counts, 3 * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+            HC_TRY(rb.add(h_tc, t_counts, 3 * sizeof(int32_t), stream));
         }
     } else {
         HC_TRY(launch_validate(n_rows, p->n_cols, nnz, p->rowptr, p->colind, err, stream));
     }
-    HC_TRY(hipMemcpyAsync(&h_err, err, sizeof h_err, hipMemcpyDeviceToHost, stream));
-    HC_TRY(hipStreamSynchronize(stream));
+    HC_TRY(rb.add(&h_err, err, sizeof h_err, stream));
+    HC_TRY(rb.sync(stream));
     if (h_err) {
         set_error("invalid CSR: %s%s%s%s", (h_err & 1) ? "rowptr[0] != 0; " : "",
                   (h_err & 2) ? "rowptr[n_rows] != nnz; " : "", (h_err & 4) ? "rowptr not non-decreasing; " : "",
@@ -337,8 +400,8 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream, const PlanCa
         if (p->features_complete && carry) {
             // counts of the untouched windows are the previous plan's; the touched ones are counted again
             HC_TRY(hipMemcpyAsync(p->ncols, carry->old_ncols, (size_t)W * sizeof(int32_t), hipMemcpyDeviceToDevice, stream));
-            HC_TRY(hipMemcpyAsync(h_cls, big_count, sizeof h_cls, hipMemcpyDeviceToHost, stream));
-            HC_TRY(hipStreamSynchronize(stream));
+            HC_TRY(rb.add(h_cls, big_count, sizeof h_cls, stream));
+            HC_TRY(rb.sync(stream));
             h_big = h_cls[0];
             HC_TRY(launch_count_small_list(h_tc[0], t_small, n_rows, p->rowptr, p->colind, p->ncols, stream));
             HC_TRY(launch_count_mid(h_tc[1], t_mid, n_rows, p->rowptr, p->colind, p->ncols, stream));
@@ -346,8 +409,8 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream, const PlanCa
                                      stream));
         } else if (p->features_complete) {
             HC_TRY(launch_count_small(W, n_rows, p->rowptr, p->colind, p->ncols, stream));
-            HC_TRY(hipMemcpyAsync(h_cls, big_count, sizeof h_cls, hipMemcpyDeviceToHost, stream));
-            HC_TRY(hipStreamSynchronize(stream));
+            HC_TRY(rb.add(h_cls, big_count, sizeof h_cls, stream));
+            HC_TRY(rb.sync(stream));
             h_big = h_cls[0];
             HC_TRY(launch_count_mid(h_big, big_list, n_rows, p->rowptr, p->colind, p->ncols, stream));
             HC_TRY(launch_unique_big(h_cls[1], huge_list, n_rows, p->n_cols, p->rowptr, p->colind, tmp_cols, p->ncols,
@@ -393,8 +456,8 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream, const PlanCa
         m.in[4] = f_midw;  m.out[4] = pos_e;
         m.in[5] = nnz_if;  m.out[5] = nullptr;
         HC_TRY(exclusive_scan_multi(m, W, totals_dev, scan_tmp, stream));
-        HC_TRY(hipMemcpyAsync(h_tot, totals_dev, 9 * sizeof(int64_t), hipMemcpyDeviceToHost, stream));
-        HC_TRY(hipStreamSynchronize(stream));
+        HC_TRY(rb.add(h_tot, totals_dev, 9 * sizeof(int64_t), stream));
+        HC_TRY(rb.sync(stream));
         if (pass == 0 && p->opt.route_mode == HCSPMM_ROUTE_HYBRID) {
             const int64_t on_matrix = h_tot[5], on_scalar = p->nnz - on_matrix;
             int32_t forced = -1;
@@ -437,8 +500,8 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream, const PlanCa
         }
         HC_TRY(launch_ecol(W, n_rows, p->rowptr, p->colind, tmp_cols, p->ncols, p->wptr, p->wcols, p->erc, err, p->route, 1,
                            by_rank ? kUniqueSmallCap : 0x7fffffff, stream));
-        HC_TRY(hipMemcpyAsync(&h_err, err, sizeof h_err, hipMemcpyDeviceToHost, stream));
-        HC_TRY(hipStreamSynchronize(stream));
+        HC_TRY(rb.add(&h_err, err, sizeof h_err, stream));
+        HC_TRY(rb.sync(stream));
         p->rows_sorted = h_err ? 0 : 1;
     } else if (nnz == 0) {
         p->condensed_complete = 1;
@@ -466,9 +529,9 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream, const PlanCa
                                 stream));
         std::vector<RunDesc> h_runs((size_t)n_runs);
         std::vector<int32_t> h_list((size_t)p->n_mfma);
-        HC_TRY(hipMemcpyAsync(h_runs.data(), p->runs, (size_t)n_runs * sizeof(RunDesc), hipMemcpyDeviceToHost, stream));
-        HC_TRY(hipMemcpyAsync(h_list.data(), p->mfma_windows, (size_t)p->n_mfma * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
-        HC_TRY(hipStreamSynchronize(stream));
+        HC_TRY(rb.add(h_runs.data(), p->runs, (size_t)n_runs * sizeof(RunDesc), stream));
+        HC_TRY(rb.add(h_list.data(), p->mfma_windows, (size_t)p->n_mfma * sizeof(int32_t), stream));
+        HC_TRY(rb.sync(stream));
         int64_t u_total = 0;
         for (const RunDesc& r : h_runs) u_total += r.nu;
         int64_t slice_u = (u_total / kRunTargetSlices + 63) / 64 * 64;
@@ -509,7 +572,7 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream, const PlanCa
         HC_ALLOC(keep, p->run_wins, h_slices.size() * kRunWindows);
         HC_TRY(launch_run_wins(p->n_run_slices, p->run_slices, p->runs, p->mfma_windows, p->ncols, p->wptr, n_rows, p->rowptr,
                                p->run_wins, stream));
-        HC_TRY(hipStreamSynchronize(stream));                    // the host vectors go out of scope
+        HC_TRY(rb.sync(stream));                    // the host vectors go out of scope
         p->runs_ok = 1;
     }
     if (W > 0) HC_TRY(launch_masked_copy(W, f_big, p->ncols, nnz_if, stream));     // nnz_if <- ncols of wide windows, else 0
@@ -536,8 +599,8 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream, const PlanCa
         if (tune().slice_cols < 0 && p->n_mfma_big > 0) {
             HC_TRY(exclusive_scan_i32_i64(nnz_if, W, pos_a, scan_tmp, stream));     // nnz_if holds ncols of wide windows here
             int64_t wide_cols = 0;
-            HC_TRY(hipMemcpyAsync(&wide_cols, pos_a + W, 8, hipMemcpyDeviceToHost, stream));
-            HC_TRY(hipStreamSynchronize(stream));
+            HC_TRY(rb.add(&wide_cols, pos_a + W, 8, stream));
+            HC_TRY(rb.sync(stream));
             int64_t want = wide_cols / 1024;
             if (want < kKcBig) want = kKcBig;
             if (want > (1 << 27)) want = 1 << 27;
@@ -547,8 +610,8 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream, const PlanCa
         if (p->n_mfma_big > 0) {
             HC_TRY(launch_slice_count(p->n_mfma_big, p->mfma_big, p->ncols, p->slice_cols, sc_n, sc_multi, sc_slots, stream));
             HC_TRY(exclusive_scan_multi(m, p->n_mfma_big, totals_dev, scan_tmp, stream));
-            HC_TRY(hipMemcpyAsync(h_tot, totals_dev, 3 * sizeof(int64_t), hipMemcpyDeviceToHost, stream));
-            HC_TRY(hipStreamSynchronize(stream));
+            HC_TRY(rb.add(h_tot, totals_dev, 3 * sizeof(int64_t), stream));
+            HC_TRY(rb.sync(stream));
         }
         p->n_big_slices = (int32_t)h_tot[0];
         p->n_tile_multi = (int32_t)h_tot[1];
@@ -591,8 +654,8 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream, const PlanCa
         m.in[5] = f_mid;    m.out[5] = pos_e;
         m.in[6] = f_rest;   m.out[6] = pos_f;
         HC_TRY(exclusive_scan_multi(m, n_rows, totals_dev, scan_tmp, stream));
-        HC_TRY(hipMemcpyAsync(h_tot, totals_dev, 7 * sizeof(int64_t), hipMemcpyDeviceToHost, stream));
-        HC_TRY(hipStreamSynchronize(stream));
+        HC_TRY(rb.add(h_tot, totals_dev, 7 * sizeof(int64_t), stream));
+        HC_TRY(rb.sync(stream));
     }
     p->nnz_long = h_tot[0];
     p->n_short = (int32_t)h_tot[1];
@@ -619,7 +682,7 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream, const PlanCa
     }
     HC_ALLOC(keep, p->rest_rows, p->n_rest);
     HC_TRY(launch_compact_ids(n_rows, f_rest, pos_f, p->rest_rows, stream));
-    HC_TRY(hipStreamSynchronize(stream));
+    HC_TRY(rb.sync(stream));
     p->device_bytes = keep.bytes;
     if (keep.ptrs.size() > sizeof p->chunks / sizeof p->chunks[0]) {
         set_error("internal: too many plan chunks");
