@@ -55,3 +55,18 @@ def test_random_relabel_keeps_the_graph():
     _check_csr(h)
     assert h.nnz == g.nnz
     assert sorted(np.diff(h.rowptr).tolist()) == sorted(np.diff(g.rowptr).tolist())
+
+
+def test_mixed_config_is_a_disjoint_union():
+    g, X, _ = make_config("C6", scale=0.02)
+    _check_csr(g)
+    c = CONFIGS["C6"]
+    n_comm = max(2, int(round(c["n_blocks"] * 0.02))) * c["block"]
+    rows = np.repeat(np.arange(g.n_rows), np.diff(g.rowptr))
+    assert g.n_rows > n_comm and X.shape == (g.n_rows, c["d"])
+    assert np.all((rows < n_comm) == (g.colind < n_comm))                 # no entry joins the two parts
+    deg = np.diff(g.rowptr)
+    assert deg[:n_comm].mean() > 3 * deg[n_comm:].mean()                  # dense communities, sparse power-law part
+    assert not np.any((rows == g.colind) & (rows < n_comm))               # block model: no self-loops
+    assert np.count_nonzero((rows == g.colind) & (rows >= n_comm)) == g.n_rows - n_comm
+    np.testing.assert_allclose(g.vals, 1.0 / np.sqrt(deg[rows].astype(np.float64) * deg[g.colind]), rtol=1e-6)
