@@ -151,8 +151,9 @@ hcspmm_status hcspmm_prepare(int32_t n_rows, int32_t n_cols, int64_t nnz,
  * row keep their distinct-column counts, so the passes over the column indices -- validation and
  * counting, the part of hcspmm_prepare proportional to the non-zeros -- run over the touched windows
  * only; routes (selector and launch guard), the window lists and the launch tables are then rebuilt
- * for the whole matrix, which costs time proportional to the rows, not to the non-zeros, and the
- * condensed structure of the matrix-path windows is rebuilt.  The result is the plan
+ * for the whole matrix, which costs time proportional to the rows, not to the non-zeros.  The
+ * condensed structure (column lists, condensed columns) of untouched windows that were and remain on
+ * the matrix path is copied to its new offsets, that of the others is built.  The result is the plan
  * hcspmm_prepare would build for the new arrays, bit for bit.
  *
  *   nnz, d_rowptr, d_colind, d_vals   the new matrix, as for hcspmm_prepare
@@ -163,6 +164,10 @@ hcspmm_status hcspmm_prepare(int32_t n_rows, int32_t n_cols, int64_t nnz,
  * plan's window features were never computed (HCSPMM_ROUTE_ALL_CSR plans, whose preparation has no
  * pass over the column indices to save).  Synchronises with `stream`; no call may be using the plan.
  * On an error the plan is unchanged and still valid for the old arrays.
+ * A plan that has been updated keeps the device blocks of its last updates (scratch and the arrays of
+ * the plan it replaced, about as much again as the plan's own arrays) for the next update instead of
+ * returning them to the runtime; hcspmm_plan_destroy releases them.  hcspmm_plan_info's device_bytes
+ * does not count them.
  */
 hcspmm_status hcspmm_plan_update(hcspmm_plan* plan, int64_t nnz, const int32_t* d_rowptr, const int32_t* d_colind,
                                  const float* d_vals, const int32_t* h_changed_rows /* host */, int32_t n_changed,

@@ -103,6 +103,12 @@ hipError_t launch_touched_classes(int32_t n_touched, const int32_t* touched, int
 hipError_t launch_count_small_list(int32_t n_list, const int32_t* list, int32_t n_rows, const int32_t* rowptr,
                                    const int32_t* colind, int32_t* ncols, hipStream_t s);
 hipError_t launch_validate_rowptr(int32_t n_rows, int64_t nnz, const int32_t* rowptr, int32_t* err_flag, hipStream_t s);
+// incremental preparation: which matrix-path windows keep the previous plan's condensed structure, and its copy
+hipError_t launch_carry_mask(int32_t W, const uint8_t* old_route, const uint8_t* route, int32_t n_touched,
+                             const int32_t* touched, uint8_t* carried, uint8_t* todo, hipStream_t s);
+hipError_t launch_carry_copy(int32_t W, int32_t n_rows, const uint8_t* carried, const int64_t* old_wptr, const int64_t* wptr,
+                             const int32_t* old_wcols, int32_t* wcols, const int64_t* old_start, const int32_t* rowptr,
+                             const int32_t* old_erc, int32_t* erc, hipStream_t s);
 hipError_t launch_count_mid(int32_t n_mid, const int32_t* mid_list, int32_t n_rows, const int32_t* rowptr,
                             const int32_t* colind, int32_t* ncols, hipStream_t s);
 hipError_t launch_ecol(int32_t W, int32_t n_rows, const int32_t* rowptr, const int32_t* colind,
@@ -271,6 +277,7 @@ hipError_t launch_gemm_f32_out(int64_t m, int32_t k, int32_t n, const float* X, 
 
 }  // namespace hcspmm
 
+struct BlockCache;
 struct hcspmm_plan {
     int32_t H, n_rows, n_cols, W;
     int64_t nnz;
@@ -336,7 +343,9 @@ struct hcspmm_plan {
     int32_t condensed_complete;     // 0: wcols / erc are filled for matrix-path windows only (the rest on export)
     int32_t erc_own, wcols_own;     // erc / wcols were allocated on their own (on export), not from the plan's chunks
     void* chunks[64];               // device allocations that hold the plan-owned arrays (several arrays per chunk)
+    size_t chunk_bytes[64];
     int32_t n_chunks;
+    struct BlockCache* cache;       // device blocks kept between hcspmm_plan_update calls (null until the first one)
     int32_t features_complete;    // ncols / wptr / total_ncols are filled (a scalar-only plan computes them on first request)
     int32_t n_rest;                 // rows finished through the workspace by the fused update
     int32_t* rest_rows;

@@ -12,6 +12,43 @@
 #include <new>
 #include <vector>
 
+// Device blocks a plan keeps between hcspmm_plan_update calls: the scratch of the last update and the arrays of
+// the plan it replaced go here instead of back to the runtime, and the next update takes its blocks from here
+// (an allocation and its release cost the runtime 20-40 us each, a dozen of them per update).  A block that two
+// updates in a row did not use is released.  Freed with the plan.
+struct BlockCache {
+    struct Block { void* p; size_t n; int age; };
+    std::vector<Block> blocks;
+    // smallest cached block that holds n bytes without wasting more than half of itself (or 1 MiB)
+    void* take(size_t n, size_t* got)
+    {
+        int best = -1;
+        for (int i = 0; i < (int)blocks.size(); ++i) {
+            const size_t b = blocks[(size_t)i].n;
+            if (b < n || b > n + (n / 2 > ((size_t)1 << 20) ? n / 2 : ((size_t)1 << 20))) continue;
+            if (best < 0 || b < blocks[(size_t)best].n) best = i;
+        }
+        if (best < 0) return nullptr;
+        void* q = blocks[(size_t)best].p;
+        *got = blocks[(size_t)best].n;
+        blocks.erase(blocks.begin() + best);
+        return q;
+    }
+    void give(void* q, size_t n) { if (q) blocks.push_back(Block{q, n, 0}); }
+    void end_of_update()
+    {
+        for (size_t i = 0; i < blocks.size();) {
+            if (++blocks[i].age > 2) { (void)hipFree(blocks[i].p); blocks.erase(blocks.begin() + (long)i); }
+            else ++i;
+        }
+    }
+    void clear()
+    {
+        for (Block& b : blocks) (void)hipFree(b.p);
+        blocks.clear();
+    }
+};
+
 namespace hcspmm {
 
 static thread_local char g_err[512] = "";
@@ -92,15 +129,31 @@ static bool lookup_selector(int32_t dtype, int32_t d_hint, int64_t nnz, int64_t*
 
 struct DevAlloc {
     std::vector<void*> ptrs;
+    std::vector<size_t> sizes;      // true size of every block in ptrs
     int64_t bytes = 0;
+    ::BlockCache* cache = nullptr;  // optional: blocks come from / go back to a plan's cache
     char* arena = nullptr;          // optional: one allocation that get() carves up (scratch of known total size)
     size_t arena_size = 0, arena_used = 0;
+    hipError_t raw(void** out, size_t n)
+    {
+        if (n == 0) n = 256;
+        size_t got = n;
+        void* q = cache ? cache->take(n, &got) : nullptr;
+        if (!q) {
+            const hipError_t e = hipMalloc(&q, n);
+            if (e != hipSuccess) { *out = nullptr; return e; }
+            got = n;
+        }
+        ptrs.push_back(q);
+        sizes.push_back(got);
+        *out = q;
+        return hipSuccess;
+    }
     hipError_t reserve(size_t total)
     {
         void* p = nullptr;
-        hipError_t e = hipMalloc(&p, total ? total : 256);
+        const hipError_t e = raw(&p, total);
         if (e != hipSuccess) return e;
-        ptrs.push_back(p);
         arena = static_cast<char*>(p);
         arena_size = total;
         arena_used = 0;
@@ -116,33 +169,27 @@ struct DevAlloc {
             const hipError_t e = reserve(chunk_min);            // small arrays share chunks; large ones get their own allocation below
             if (e != hipSuccess) { *out = nullptr; return e; }
         }
-        if (chunk_min && 2 * padded(sz) >= chunk_min) {
-            void* q = nullptr;
-            const hipError_t e = hipMalloc(&q, sz);
-            if (e != hipSuccess) { *out = nullptr; return e; }
-            ptrs.push_back(q);
-            bytes += (int64_t)sz;
-            *out = static_cast<T*>(q);
-            return hipSuccess;
-        }
-        if (arena && arena_used + padded(sz) <= arena_size) {
+        if (!(chunk_min && 2 * padded(sz) >= chunk_min) && arena && arena_used + padded(sz) <= arena_size) {
             *out = reinterpret_cast<T*>(arena + arena_used);
             arena_used += padded(sz);
             bytes += (int64_t)sz;
             return hipSuccess;
         }
-        void* p = nullptr;
-        hipError_t e = hipMalloc(&p, sz);
+        void* q = nullptr;
+        const hipError_t e = raw(&q, sz);
         if (e != hipSuccess) { *out = nullptr; return e; }
-        ptrs.push_back(p);
         bytes += (int64_t)sz;
-        *out = static_cast<T*>(p);
+        *out = static_cast<T*>(q);
         return hipSuccess;
     }
     void free_all()
     {
-        for (void* p : ptrs) (void)hipFree(p);
+        for (size_t i = 0; i < ptrs.size(); ++i) {
+            if (cache) cache->give(ptrs[i], sizes[i]);
+            else (void)hipFree(ptrs[i]);
+        }
         ptrs.clear();
+        sizes.clear();
         arena = nullptr;
         arena_size = arena_used = 0;
     }
@@ -171,7 +218,10 @@ struct DevAlloc {
 static void free_plan_arrays(hcspmm_plan* p)
 {
     // the plan's arrays live in a few chunks; only the lazily sized buffers and arrays completed on export are separate
-    for (int32_t i = 0; i < p->n_chunks; ++i) (void)hipFree(p->chunks[i]);
+    for (int32_t i = 0; i < p->n_chunks; ++i) {
+        if (p->cache) p->cache->give(p->chunks[i], p->chunk_bytes[i]);
+        else (void)hipFree(p->chunks[i]);
+    }
     p->n_chunks = 0;
     void* owned[] = {p->erc_own ? p->erc : nullptr, p->wcols_own ? p->wcols : nullptr, p->tile_partial, p->partial};
     for (void* q : owned)
@@ -300,7 +350,12 @@ struct Readback {
 
 // What an incremental preparation carries over from the previous plan: the distinct-column counts of the windows
 // that hold no changed row (device array of the old plan) and the list of windows that do (device, distinct ids).
-struct PlanCarry { const int32_t* old_ncols; const int32_t* touched; int32_t n_touched; };
+struct PlanCarry {
+    const int32_t* old_ncols; const int32_t* touched; int32_t n_touched;
+    // the previous plan's condensed structure (matrix-path windows), when it has one whose rows were all sorted
+    const uint8_t* old_route = nullptr; const int64_t* old_wptr = nullptr; const int32_t* old_nnzw = nullptr;
+    const int32_t* old_wcols = nullptr; const int32_t* old_erc = nullptr;
+};
 
 static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream, const PlanCarry* carry = nullptr)
 {
@@ -310,6 +365,7 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream, const PlanCa
     PinnedPage pinned;
     Readback rb;
     rb.page = pinned.ptr();
+    tmp.cache = keep.cache = p->cache;
     const int32_t n_rows = p->n_rows, W = p->W;
     const int64_t nnz = p->nnz;
     keep.chunk_min = (size_t)1 << 20;      // small graphs: all plan arrays in one or two device allocations
@@ -488,17 +544,33 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream, const PlanCa
         // Larger ones: list and positions together from bitmap ranks, unless the matrix is so wide that the
         // bitmap passes would cost more than searching (then the bitmap list + search route serves them too).
         const bool by_rank = p->n_cols <= kRankMaxCols;
-        HC_TRY(launch_unique_small(W, n_rows, p->rowptr, p->colind, tmp_cols, p->ncols, p->route, stream));
+        // After a structural change the untouched windows that were and are on the matrix path keep the previous
+        // plan's lists and condensed columns (copied to their new offsets); only the others are condensed, through
+        // a route array masked down to them.
+        const uint8_t* todo_route = p->route;
+        if (carry && carry->old_erc && carry->old_wcols) {
+            uint8_t *carried = nullptr, *todo = nullptr;
+            int64_t* old_start = nullptr;
+            HC_ALLOC(tmp, carried, (size_t)W);
+            HC_ALLOC(tmp, todo, (size_t)W);
+            HC_ALLOC(tmp, old_start, (size_t)W + 1);
+            HC_TRY(launch_carry_mask(W, carry->old_route, p->route, carry->n_touched, carry->touched, carried, todo, stream));
+            HC_TRY(exclusive_scan_i32_i64(carry->old_nnzw, W, old_start, scan_tmp, stream));
+            HC_TRY(launch_carry_copy(W, n_rows, carried, carry->old_wptr, p->wptr, carry->old_wcols, p->wcols, old_start,
+                                     p->rowptr, carry->old_erc, p->erc, stream));
+            todo_route = todo;
+        }
+        HC_TRY(launch_unique_small(W, n_rows, p->rowptr, p->colind, tmp_cols, p->ncols, todo_route, stream));
         if (by_rank) {
-            HC_TRY(launch_condense_rank(h_big, big_list, n_rows, p->rowptr, p->colind, p->route, p->wptr, p->wcols, p->erc,
+            HC_TRY(launch_condense_rank(h_big, big_list, n_rows, p->rowptr, p->colind, todo_route, p->wptr, p->wcols, p->erc,
                                         err, stream));
-            HC_TRY(launch_condense_rank(h_cls[1], huge_list, n_rows, p->rowptr, p->colind, p->route, p->wptr, p->wcols,
+            HC_TRY(launch_condense_rank(h_cls[1], huge_list, n_rows, p->rowptr, p->colind, todo_route, p->wptr, p->wcols,
                                         p->erc, err, stream));
         } else {
-            HC_TRY(launch_unique_big(h_big, big_list, n_rows, p->n_cols, p->rowptr, p->colind, tmp_cols, p->ncols, p->route,
+            HC_TRY(launch_unique_big(h_big, big_list, n_rows, p->n_cols, p->rowptr, p->colind, tmp_cols, p->ncols, todo_route,
                                      stream));
         }
-        HC_TRY(launch_ecol(W, n_rows, p->rowptr, p->colind, tmp_cols, p->ncols, p->wptr, p->wcols, p->erc, err, p->route, 1,
+        HC_TRY(launch_ecol(W, n_rows, p->rowptr, p->colind, tmp_cols, p->ncols, p->wptr, p->wcols, p->erc, err, todo_route, 1,
                            by_rank ? kUniqueSmallCap : 0x7fffffff, stream));
         HC_TRY(rb.add(&h_err, err, sizeof h_err, stream));
         HC_TRY(rb.sync(stream));
@@ -690,7 +762,7 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream, const PlanCa
         goto fail;
     }
     p->n_chunks = (int32_t)keep.ptrs.size();
-    for (size_t i = 0; i < keep.ptrs.size(); ++i) p->chunks[i] = keep.ptrs[i];
+    for (size_t i = 0; i < keep.ptrs.size(); ++i) { p->chunks[i] = keep.ptrs[i]; p->chunk_bytes[i] = keep.sizes[i]; }
     tmp.free_all();
     return HCSPMM_OK;
 
@@ -972,7 +1044,11 @@ hcspmm_status hcspmm_plan_update(hcspmm_plan* plan, int64_t nnz, const int32_t* 
     hcspmm_plan fresh;
     hcspmm_status st = init_plan_header(&fresh, plan->n_rows, plan->n_cols, nnz, d_rowptr, d_colind, d_vals, plan->opt);
     if (st != HCSPMM_OK) return st;
+    // a plan that is updated keeps the device blocks of its updates (see BlockCache)
+    if (!plan->cache) plan->cache = new (std::nothrow) BlockCache;
+    fresh.cache = plan->cache;
     int32_t* d_touched = nullptr;
+    size_t touched_bytes = 0;
     PlanCarry carry{plan->ncols, nullptr, (int32_t)touched.size()};
     // The counts of untouched windows are carried over whenever the old plan has them and fewer than an eighth of
     // the windows changed (beyond that the list-driven passes cost as much as the plain ones); otherwise this is a
@@ -980,13 +1056,20 @@ hcspmm_status hcspmm_plan_update(hcspmm_plan* plan, int64_t nnz, const int32_t* 
     const bool incremental = plan->features_complete && plan->nnz > 0 && !touched.empty() && 8 * (int64_t)touched.size() < plan->W &&
                              !(plan->opt.route_mode == HCSPMM_ROUTE_ALL_CSR);
     if (incremental) {
-        if (hipMalloc((void**)&d_touched, touched.size() * sizeof(int32_t)) != hipSuccess) {
+        touched_bytes = touched.size() * sizeof(int32_t);
+        if (plan->cache) d_touched = static_cast<int32_t*>(plan->cache->take(touched_bytes, &touched_bytes));
+        if (!d_touched && hipMalloc((void**)&d_touched, touched_bytes) != hipSuccess) {
             (void)hipGetLastError(); set_error("device allocation failed"); return HCSPMM_EALLOC;
         }
         if (hipMemcpyAsync(d_touched, touched.data(), touched.size() * sizeof(int32_t), hipMemcpyHostToDevice, s) != hipSuccess) {
             (void)hipGetLastError(); (void)hipFree(d_touched); set_error("copy of the window list failed"); return HCSPMM_EHIP;
         }
         carry.touched = d_touched;
+        // (a plan with an unsorted row somewhere does not say where: its structure is not carried)
+        if (plan->n_mfma > 0 && plan->erc && plan->wcols && plan->rows_sorted) {
+            carry.old_route = plan->route; carry.old_wptr = plan->wptr; carry.old_nnzw = plan->nnzw;
+            carry.old_wcols = plan->wcols; carry.old_erc = plan->erc;
+        }
     }
     const bool nothing_changed = touched.empty() && nnz == plan->nnz && plan->features_complete;
     if (nothing_changed) {
@@ -995,7 +1078,10 @@ hcspmm_status hcspmm_plan_update(hcspmm_plan* plan, int64_t nnz, const int32_t* 
         return HCSPMM_OK;
     }
     st = build_plan(&fresh, s, incremental ? &carry : nullptr);
-    if (d_touched) (void)hipFree(d_touched);
+    if (d_touched) {
+        if (plan->cache) plan->cache->give(d_touched, touched_bytes);
+        else (void)hipFree(d_touched);
+    }
     if (st != HCSPMM_OK) return st;                              // the old plan is untouched and still valid for the old arrays
     // the new tables replace the old ones; streams, events and the lazily sized scratch buffers stay
     fresh.partial = plan->partial; fresh.partial_elems = plan->partial_elems;
@@ -1007,6 +1093,7 @@ hcspmm_status hcspmm_plan_update(hcspmm_plan* plan, int64_t nnz, const int32_t* 
     fresh.ev_fork = plan->ev_fork; fresh.ev_join[0] = plan->ev_join[0]; fresh.ev_join[1] = plan->ev_join[1];
     *plan = fresh;
     setup_side_streams(plan);
+    if (plan->cache) plan->cache->end_of_update();
     return HCSPMM_OK;
 }
 
@@ -1399,6 +1486,7 @@ void hcspmm_plan_destroy(hcspmm_plan* plan)
     if (plan->ev_join[0]) (void)hipEventDestroy(plan->ev_join[0]);
     if (plan->ev_join[1]) (void)hipEventDestroy(plan->ev_join[1]);
     free_plan_arrays(plan);
+    if (plan->cache) { plan->cache->clear(); delete plan->cache; }
     delete plan;
 }
 

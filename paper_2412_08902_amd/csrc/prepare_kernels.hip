@@ -553,6 +553,70 @@ __global__ __launch_bounds__(256) void k_count_small_list(const int32_t* __restr
     count_distinct_body<256, 2 * kUniqueSmallCap>(list[blockIdx.x], n_rows, rowptr, colind, ncols, table, smem);
 }
 
+// Which matrix-path windows keep the previous plan's condensed structure: on that path before and now, and not
+// touched.  todo[w] is the route restricted to the windows that still have to be condensed.
+__global__ __launch_bounds__(256) void k_carry_mask(int32_t W, const uint8_t* __restrict__ old_route,
+                                                    const uint8_t* __restrict__ route, uint8_t* __restrict__ carried,
+                                                    uint8_t* __restrict__ todo)
+{
+    const int32_t w = blockIdx.x * 256 + threadIdx.x;
+    if (w >= W) return;
+    const uint8_t c = (old_route[w] != 0 && route[w] != 0) ? 1 : 0;
+    carried[w] = c;
+    todo[w] = (route[w] != 0 && !c) ? 1 : 0;
+}
+
+__global__ __launch_bounds__(256) void k_carry_untouch(int32_t n_touched, const int32_t* __restrict__ touched,
+                                                       const uint8_t* __restrict__ route, uint8_t* __restrict__ carried,
+                                                       uint8_t* __restrict__ todo)
+{
+    const int32_t i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n_touched) return;
+    const int32_t w = touched[i];
+    carried[w] = 0;
+    todo[w] = route[w] != 0 ? 1 : 0;
+}
+
+// Copies a carried window's column list and the condensed columns of its non-zeros from the previous plan's arrays
+// to their new places (both move when windows in front of it changed size).
+__global__ __launch_bounds__(256) void k_carry_copy(int32_t n_rows, const uint8_t* __restrict__ carried,
+                                                    const int64_t* __restrict__ old_wptr, const int64_t* __restrict__ wptr,
+                                                    const int32_t* __restrict__ old_wcols, int32_t* __restrict__ wcols,
+                                                    const int64_t* __restrict__ old_start, const int32_t* __restrict__ rowptr,
+                                                    const int32_t* __restrict__ old_erc, int32_t* __restrict__ erc)
+{
+    const int32_t w = blockIdx.x;
+    if (!carried[w]) return;
+    const int64_t so = old_wptr[w], sn = wptr[w];
+    const int32_t nc = (int32_t)(wptr[w + 1] - sn);
+    for (int32_t i = threadIdx.x; i < nc; i += 256) wcols[sn + i] = old_wcols[so + i];
+    int32_t s, e;
+    window_span(w, n_rows, rowptr, s, e);
+    const int64_t eo = old_start[w];
+    for (int32_t k = threadIdx.x; k < e - s; k += 256) erc[s + k] = old_erc[eo + k];
+}
+
+hipError_t launch_carry_mask(int32_t W, const uint8_t* old_route, const uint8_t* route, int32_t n_touched,
+                             const int32_t* touched, uint8_t* carried, uint8_t* todo, hipStream_t s)
+{
+    if (W <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_carry_mask, dim3((W + 255) / 256), dim3(256), 0, s, W, old_route, route, carried, todo);
+    if (n_touched > 0)
+        hipLaunchKernelGGL(k_carry_untouch, dim3((n_touched + 255) / 256), dim3(256), 0, s, n_touched, touched, route,
+                           carried, todo);
+    return hipGetLastError();
+}
+
+hipError_t launch_carry_copy(int32_t W, int32_t n_rows, const uint8_t* carried, const int64_t* old_wptr, const int64_t* wptr,
+                             const int32_t* old_wcols, int32_t* wcols, const int64_t* old_start, const int32_t* rowptr,
+                             const int32_t* old_erc, int32_t* erc, hipStream_t s)
+{
+    if (W <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_carry_copy, dim3(W), dim3(256), 0, s, n_rows, carried, old_wptr, wptr, old_wcols, wcols, old_start,
+                       rowptr, old_erc, erc);
+    return hipGetLastError();
+}
+
 hipError_t launch_touched_classes(int32_t n_touched, const int32_t* touched, int32_t n_rows, int32_t n_cols,
                                   const int32_t* rowptr, const int32_t* colind, int32_t* t_small, int32_t* t_mid,
                                   int32_t* t_huge, int32_t* counts, int32_t* err, hipStream_t s)
