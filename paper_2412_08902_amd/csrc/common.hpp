@@ -56,7 +56,7 @@ void set_error(const char* fmt, ...);
 // Experiment knobs (HCSPMM_TUNE_* environment variables; not part of the ABI), read ONCE per process on first use.
 // A value of -1 means "not set": the built-in choice applies.
 struct Tune {
-    int mid_row, long_row, slice_cols, serial, xcd_chunk, rpg, tiles_per_wave, no_rows16, runs, run_slice, side_nnz;
+    int mid_row, long_row, slice_cols, serial, xcd_chunk, rpg, tiles_per_wave, no_rows16, runs, run_slice, side_nnz, bands;
 };
 const Tune& tune();
 

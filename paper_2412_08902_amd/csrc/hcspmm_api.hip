@@ -72,7 +72,7 @@ const Tune& tune()
     static const Tune t = {env_int("HCSPMM_TUNE_MID_ROW"), env_int("HCSPMM_TUNE_LONG_ROW"), env_int("HCSPMM_TUNE_SLICE_COLS"),
                            getenv("HCSPMM_TUNE_SERIAL") ? 1 : 0, env_int("HCSPMM_TUNE_XCD_CHUNK"), env_int("HCSPMM_TUNE_RPG"),
                            env_int("HCSPMM_TUNE_TILES_PER_WAVE"), getenv("HCSPMM_TUNE_NO_ROWS16") ? 1 : 0,
-                           getenv("HCSPMM_TUNE_RUNS") ? 1 : 0, env_int("HCSPMM_TUNE_RUN_SLICE"), env_int("HCSPMM_TUNE_SIDE_NNZ")};
+                           getenv("HCSPMM_TUNE_RUNS") ? 1 : 0, env_int("HCSPMM_TUNE_RUN_SLICE"), env_int("HCSPMM_TUNE_SIDE_NNZ"), env_int("HCSPMM_TUNE_BANDS")};
     return t;
 }
 
@@ -688,11 +688,53 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream, const PlanCa
         p->n_big_slices = (int32_t)h_tot[0];
         p->n_tile_multi = (int32_t)h_tot[1];
         p->n_tile_slots = h_tot[2];
+        if (tune().bands > 0 && p->n_mfma_big > 0) {
+            // EXPERIMENT: slices by global column band, band-major (built on the host)
+            const int32_t Bc = tune().bands;
+            std::vector<int32_t> h_list((size_t)p->n_mfma_big), h_nc((size_t)W), h_wc((size_t)p->total_ncols);
+            std::vector<int64_t> h_wp((size_t)W + 1);
+            HC_TRY(hipMemcpyAsync(h_list.data(), p->mfma_big, h_list.size() * 4, hipMemcpyDeviceToHost, stream));
+            HC_TRY(hipMemcpyAsync(h_nc.data(), p->ncols, h_nc.size() * 4, hipMemcpyDeviceToHost, stream));
+            HC_TRY(hipMemcpyAsync(h_wp.data(), p->wptr, h_wp.size() * 8, hipMemcpyDeviceToHost, stream));
+            HC_TRY(hipMemcpyAsync(h_wc.data(), p->wcols, h_wc.size() * 4, hipMemcpyDeviceToHost, stream));
+            HC_TRY(hipStreamSynchronize(stream));
+            const int32_t n_bands = (p->n_cols + Bc - 1) / Bc;
+            std::vector<std::vector<WgSlice>> per_band((size_t)n_bands);
+            std::vector<MultiRow> h_multi;
+            int64_t slots = 0;
+            for (int32_t w : h_list) {
+                const int32_t* c0 = h_wc.data() + h_wp[(size_t)w];
+                const int32_t nc = h_nc[(size_t)w];
+                int32_t n_here = 0;
+                const int64_t first = slots;
+                int32_t kb = 0;
+                while (kb < nc) {
+                    const int32_t b = c0[kb] / Bc;
+                    const int32_t ke = (int32_t)(std::lower_bound(c0 + kb, c0 + nc, (b + 1) * Bc) - c0);
+                    per_band[(size_t)b].push_back(WgSlice{w, kb, ke, (int32_t)(first + n_here)});
+                    ++n_here;
+                    kb = ke;
+                }
+                slots += n_here;
+                h_multi.push_back(MultiRow{w, (int32_t)first, n_here, 0});
+            }
+            std::vector<WgSlice> h_sl;
+            for (auto& v : per_band) h_sl.insert(h_sl.end(), v.begin(), v.end());
+            p->n_big_slices = (int32_t)h_sl.size();
+            p->n_tile_multi = (int32_t)h_multi.size();
+            p->n_tile_slots = slots;
+            HC_ALLOC(keep, p->big_slices, p->n_big_slices);
+            HC_ALLOC(keep, p->tile_multi, p->n_tile_multi);
+            HC_TRY(hipMemcpy(p->big_slices, h_sl.data(), h_sl.size() * sizeof(WgSlice), hipMemcpyHostToDevice));
+            HC_TRY(hipMemcpy(p->tile_multi, h_multi.data(), h_multi.size() * sizeof(MultiRow), hipMemcpyHostToDevice));
+            fprintf(stderr, "[hcspmm] bands of %d columns: %d bands, %d slices, %lld tile slots\n", Bc, n_bands, p->n_big_slices, (long long)slots);
+        } else {
         HC_ALLOC(keep, p->big_slices, p->n_big_slices);
         HC_ALLOC(keep, p->tile_multi, p->n_tile_multi);
         if (p->n_mfma_big > 0)
             HC_TRY(launch_slice_fill(p->n_mfma_big, p->mfma_big, p->ncols, p->slice_cols, pos_a, pos_b, pos_d, p->big_slices,
                                      p->tile_multi, stream));
+        }
         if (p->rows_sorted && p->n_big_slices > 0) {
             HC_ALLOC(keep, p->big_slice_rows, (size_t)p->n_big_slices * kH);
             HC_TRY(launch_slice_rows(p->n_big_slices, p->big_slices, n_rows, p->rowptr, p->erc, p->big_slice_rows,
@@ -849,7 +891,7 @@ static hcspmm_status run_spmm(const hcspmm_plan* plan, const SpmmArgs& a, hipStr
         if (ev) { HC_HIP(hipEventRecord(ev[1], stream)); HC_HIP(hipEventRecord(ev[2], stream)); }
     } else {
         HC_HIP(launch_mfma_wg(a, p->n_big_slices, p->big_slices, p->ncols, p->wptr, p->wcols, p->erc, p->rows_sorted,
-                              p->big_slice_rows, tile_partial, true, s_wg));
+                              p->big_slice_rows, tile_partial, tune().bands <= 0 || getenv("HCSPMM_TUNE_BANDS_WIDE"), s_wg));
         HC_HIP(launch_reduce_tiles(a, p->n_tile_multi, p->tile_multi, tile_partial, s_wg));
         HC_HIP(launch_mfma_wg(a, p->n_mfma_mid, p->mid_slices, p->ncols, p->wptr, p->wcols, p->erc, p->rows_sorted,
                               nullptr, tile_partial, false, s_wg));

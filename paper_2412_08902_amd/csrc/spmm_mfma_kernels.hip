@@ -475,7 +475,7 @@ __global__ __launch_bounds__(256) void k_mfma_wg(const WgSlice* __restrict__ sli
             *reinterpret_cast<float4*>(&tile[i]) = make_float4(0.f, 0.f, 0.f, 0.f);
         __syncthreads();
         if (rows_sorted) {
-            const int32_t limit = kc0 + KC;
+            const int32_t limit = min(kc0 + KC, nc);          // (entries from nc on belong to the window's next slice)
             const int shift = 16 * ((threadIdx.x & 63) >> 4);
             for (;;) {
                 int n = 0;
@@ -495,7 +495,7 @@ __global__ __launch_bounds__(256) void k_mfma_wg(const WgSlice* __restrict__ sli
             for (int32_t k = s + threadIdx.x; k < e; k += 256) {
                 const int32_t p = erc[k];
                 const int32_t ec = (p >> 4) - kc0;
-                if (ec >= 0 && ec < KC) atomicAdd(&tile[P::tidx(ec, p & 15)], a.vals[k]);
+                if (ec >= 0 && ec < kend) atomicAdd(&tile[P::tidx(ec, p & 15)], a.vals[k]);
             }
         }
         __syncthreads();
