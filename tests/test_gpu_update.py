@@ -155,3 +155,38 @@ def test_bad_arguments_leave_the_plan_usable():
     ref = oracle.spmm(g.rowptr, g.colind, g.vals, X)
     assert_close(Y.cpu().numpy().astype(np.float64), ref, oracle.spmm(g.rowptr, g.colind, g.vals, X, use_abs=True), 1e-5)
     plan.destroy()
+
+
+def test_many_updates_reuse_their_blocks_and_release_them_with_the_plan():
+    """A plan that is updated keeps the device blocks of its last update; a chain of updates must neither grow the
+    process's device memory step by step nor leave anything behind once the plan is destroyed."""
+    import torch
+    g = gcn_normalise(chung_lu_graph(20000, 600000, 2.1, seed=71, max_degree=4000))
+    rng = np.random.default_rng(72)
+    torch.cuda.synchronize()
+    free0 = torch.cuda.mem_get_info()[0]
+    plan = prepare(g, 2)                      # every window on the matrix path: the largest plan arrays
+    cur = g
+    graphs = []
+    for step in range(4):                     # the edited matrices first (host work), their device copies stay alive below
+        ins = [(int(r), int(rng.integers(0, g.n_cols))) for r in rng.integers(0, g.n_rows, 30)]
+        cur, changed = edit(cur, ins)
+        graphs.append((cur, changed))
+    used = []
+    for rep in range(3):
+        for cur, changed in graphs:
+            # (going back to an earlier matrix of the list changes the rows of every edit in between: list them all)
+            rows = np.unique(np.concatenate([c for _, c in graphs]))
+            update_and_check(plan, cur, rows, 2) if rep == 0 else None
+            import paper_2412_08902_amd.binding as hc
+            rp, ci, va = device_graph(cur)
+            hc.hcspmm_plan_update(plan, rp, ci, va, rows)
+            torch.cuda.synchronize()
+            used.append(free0 - torch.cuda.mem_get_info()[0])
+    # after the first rounds the footprint no longer grows (blocks are reused, unused ones released)
+    assert max(used[-4:]) <= max(used[:8]) + (8 << 20), used
+    plan.destroy()
+    del rp, ci, va
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    assert free0 - torch.cuda.mem_get_info()[0] < (64 << 20)
