@@ -190,3 +190,29 @@ def test_many_updates_reuse_their_blocks_and_release_them_with_the_plan():
     torch.cuda.synchronize()
     torch.cuda.empty_cache()
     assert free0 - torch.cuda.mem_get_info()[0] < (64 << 20)
+
+
+def test_update_of_a_plan_with_run_tables_and_after_an_export():
+    """The optional run tables (matrix_kernels = RUNS) are rebuilt by an update; an update after an export (which had
+    completed the condensed structure of scalar-path windows) still equals the re-derivation."""
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    g = gcn_normalise(chung_lu_graph(5000, 150000, 2.1, seed=81, max_degree=2000))
+    rng = np.random.default_rng(82)
+    rp, ci, va = device_graph(g)
+    plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, route_mode=2, d_hint=32, matrix_kernels=hc.HCSPMM_MATRIX_RUNS)
+    ins = [(int(r), int(rng.integers(0, g.n_cols))) for r in rng.integers(0, g.n_rows, 25)]
+    g2, changed = edit(g, ins)
+    update_and_check(plan, g2, changed, 2)                      # exports: the plan now holds every window's lists
+    runs = hc.hcspmm_plan_export_runs(plan)
+    got = hc.hcspmm_plan_export(plan)
+    want = oracle.derive_runs(got["mfma_windows"], got["wptr"], got["wcols"])
+    assert runs["run_nu"].tolist() == [r["union"].shape[0] for r in want]
+    assert np.array_equal(runs["ucols"], np.concatenate([r["union"] for r in want]))
+    for r in want:
+        for w, slots in zip(r["windows"], r["slots"]):
+            assert np.array_equal(runs["wslot"][got["wptr"][w]:got["wptr"][w + 1]], slots)
+    dels = [(int(r), int(g2.colind[g2.rowptr[r]])) for r in rng.integers(0, g.n_rows, 25) if g2.rowptr[r + 1] > g2.rowptr[r]]
+    g3, changed = edit(g2, deletes=dels)
+    update_and_check(plan, g3, changed, 2)
+    plan.destroy()
