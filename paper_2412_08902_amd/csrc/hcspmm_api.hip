@@ -698,7 +698,9 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream, const PlanCa
             HC_TRY(hipMemcpyAsync(h_wp.data(), p->wptr, h_wp.size() * 8, hipMemcpyDeviceToHost, stream));
             HC_TRY(hipMemcpyAsync(h_wc.data(), p->wcols, h_wc.size() * 4, hipMemcpyDeviceToHost, stream));
             HC_TRY(hipStreamSynchronize(stream));
-            const int32_t n_bands = (p->n_cols + Bc - 1) / Bc;
+            // HCSPMM_TUNE_BANDS_HOT=k: only the first k bands are cut; all columns behind them form one last band
+            const int32_t hot = getenv("HCSPMM_TUNE_BANDS_HOT") ? atoi(getenv("HCSPMM_TUNE_BANDS_HOT")) : 0x7fffffff;
+            const int32_t n_bands = std::min((p->n_cols + Bc - 1) / Bc, hot < 0x7fffffff ? hot + 1 : 0x7fffffff);
             std::vector<std::vector<WgSlice>> per_band((size_t)n_bands);
             std::vector<MultiRow> h_multi;
             int64_t slots = 0;
@@ -709,8 +711,8 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream, const PlanCa
                 const int64_t first = slots;
                 int32_t kb = 0;
                 while (kb < nc) {
-                    const int32_t b = c0[kb] / Bc;
-                    const int32_t ke = (int32_t)(std::lower_bound(c0 + kb, c0 + nc, (b + 1) * Bc) - c0);
+                    const int32_t b = std::min(c0[kb] / Bc, n_bands - 1);
+                    const int32_t ke = b == n_bands - 1 ? nc : (int32_t)(std::lower_bound(c0 + kb, c0 + nc, (b + 1) * Bc) - c0);
                     per_band[(size_t)b].push_back(WgSlice{w, kb, ke, (int32_t)(first + n_here)});
                     ++n_here;
                     kb = ke;
