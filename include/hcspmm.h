@@ -32,6 +32,11 @@
  *     recent failure on the calling thread.
  *   - All index arithmetic on row*ld and nnz*d is done in 64 bits; CSR indices
  *     are int32, so nnz < 2^31.
+ *   - Device memory the library holds beyond its plans: one 16 MiB static array
+ *     per GPU (scratch of hcspmm_spmm_noalloc) and, per GPU, up to 64 MiB of
+ *     blocks of at most 16 MiB each that preparations and destroyed plans leave
+ *     behind for the next preparation (an allocation costs more than the
+ *     kernels of a small matrix's preparation); both live until the process ends.
  */
 #ifndef HCSPMM_H
 #define HCSPMM_H

@@ -12,16 +12,21 @@
 #include <new>
 #include <vector>
 
-// Device blocks a plan keeps between hcspmm_plan_update calls: the scratch of the last update and the arrays of
-// the plan it replaced go here instead of back to the runtime, and the next update takes its blocks from here
-// (an allocation and its release cost the runtime 20-40 us each, a dozen of them per update).  A block that two
-// updates in a row did not use is released.  Freed with the plan.
+// Device blocks kept for reuse instead of going back to the runtime (an allocation and its release cost the
+// runtime 20-40 us each, a dozen of them per preparation).  Two uses:
+//  * a plan that is updated (hcspmm_plan_update) keeps the scratch of its last update and the arrays of the plan it
+//    replaced for the next update; a block that two updates in a row did not use is released; freed with the plan;
+//  * one bounded cache per GPU for the whole process serves the preparations of small matrices (blocks of at most
+//    16 MiB, 64 MiB in all; what does not fit is released at once).  It lives until the process ends.
 struct BlockCache {
     struct Block { void* p; size_t n; int age; };
     std::vector<Block> blocks;
+    std::mutex mu;
+    size_t max_block = 0, cap = 0, held = 0;      // bounds of the per-GPU cache (0: none)
     // smallest cached block that holds n bytes without wasting more than half of itself (or 1 MiB)
     void* take(size_t n, size_t* got)
     {
+        std::lock_guard<std::mutex> g(mu);
         int best = -1;
         for (int i = 0; i < (int)blocks.size(); ++i) {
             const size_t b = blocks[(size_t)i].n;
@@ -31,23 +36,51 @@ struct BlockCache {
         if (best < 0) return nullptr;
         void* q = blocks[(size_t)best].p;
         *got = blocks[(size_t)best].n;
+        held -= *got;
         blocks.erase(blocks.begin() + best);
         return q;
     }
-    void give(void* q, size_t n) { if (q) blocks.push_back(Block{q, n, 0}); }
+    void give(void* q, size_t n)
+    {
+        if (!q) return;
+        {
+            std::lock_guard<std::mutex> g(mu);
+            if (!(max_block && n > max_block) && !(cap && held + n > cap)) {
+                blocks.push_back(Block{q, n, 0});
+                held += n;
+                return;
+            }
+        }
+        (void)hipFree(q);
+    }
     void end_of_update()
     {
+        std::lock_guard<std::mutex> g(mu);
         for (size_t i = 0; i < blocks.size();) {
-            if (++blocks[i].age > 2) { (void)hipFree(blocks[i].p); blocks.erase(blocks.begin() + (long)i); }
+            if (++blocks[i].age > 2) { held -= blocks[i].n; (void)hipFree(blocks[i].p); blocks.erase(blocks.begin() + (long)i); }
             else ++i;
         }
     }
     void clear()
     {
+        std::lock_guard<std::mutex> g(mu);
         for (Block& b : blocks) (void)hipFree(b.p);
         blocks.clear();
+        held = 0;
     }
 };
+
+// the process-wide cache of the given GPU (null for a device number beyond the table)
+static BlockCache* small_block_cache(int device)
+{
+    constexpr int kMaxDevices = 64;
+    static BlockCache caches[kMaxDevices];
+    static std::once_flag once;
+    std::call_once(once, [] {
+        for (BlockCache& c : caches) { c.max_block = (size_t)16 << 20; c.cap = (size_t)64 << 20; }
+    });
+    return device >= 0 && device < kMaxDevices ? &caches[device] : nullptr;
+}
 
 namespace hcspmm {
 
@@ -218,8 +251,9 @@ struct DevAlloc {
 static void free_plan_arrays(hcspmm_plan* p)
 {
     // the plan's arrays live in a few chunks; only the lazily sized buffers and arrays completed on export are separate
+    BlockCache* to = p->cache ? p->cache : small_block_cache(p->device);
     for (int32_t i = 0; i < p->n_chunks; ++i) {
-        if (p->cache) p->cache->give(p->chunks[i], p->chunk_bytes[i]);
+        if (to) to->give(p->chunks[i], p->chunk_bytes[i]);
         else (void)hipFree(p->chunks[i]);
     }
     p->n_chunks = 0;
@@ -365,7 +399,7 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream, const PlanCa
     PinnedPage pinned;
     Readback rb;
     rb.page = pinned.ptr();
-    tmp.cache = keep.cache = p->cache;
+    tmp.cache = keep.cache = p->cache ? p->cache : small_block_cache(p->device);
     const int32_t n_rows = p->n_rows, W = p->W;
     const int64_t nnz = p->nnz;
     keep.chunk_min = (size_t)1 << 20;      // small graphs: all plan arrays in one or two device allocations
