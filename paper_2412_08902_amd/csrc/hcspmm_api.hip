@@ -723,7 +723,9 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream, const PlanCa
         p->n_tile_multi = (int32_t)h_tot[1];
         p->n_tile_slots = h_tot[2];
         if (tune().bands > 0 && p->n_mfma_big > 0) {
-            // EXPERIMENT: slices by global column band, band-major (built on the host)
+            // Measurement aid (HCSPMM_TUNE_BANDS): wide windows are cut at the same global column boundaries and the
+            // slices ordered band by band, so that all windows walk one band's X rows at about the same time.  Built on
+            // the host from a copy of the column lists: slow, and only for the experiment that profiles/ reports.
             const int32_t Bc = tune().bands;
             std::vector<int32_t> h_list((size_t)p->n_mfma_big), h_nc((size_t)W), h_wc((size_t)p->total_ncols);
             std::vector<int64_t> h_wp((size_t)W + 1);
@@ -763,7 +765,6 @@ static hcspmm_status build_plan(hcspmm_plan* p, hipStream_t stream, const PlanCa
             HC_ALLOC(keep, p->tile_multi, p->n_tile_multi);
             HC_TRY(hipMemcpy(p->big_slices, h_sl.data(), h_sl.size() * sizeof(WgSlice), hipMemcpyHostToDevice));
             HC_TRY(hipMemcpy(p->tile_multi, h_multi.data(), h_multi.size() * sizeof(MultiRow), hipMemcpyHostToDevice));
-            fprintf(stderr, "[hcspmm] bands of %d columns: %d bands, %d slices, %lld tile slots\n", Bc, n_bands, p->n_big_slices, (long long)slots);
         } else {
         HC_ALLOC(keep, p->big_slices, p->n_big_slices);
         HC_ALLOC(keep, p->tile_multi, p->n_tile_multi);
