@@ -56,6 +56,34 @@ def test_gemm_operand_alignment(m, k, n, xoff, ldx_extra):
     assert_close(T.cpu().numpy().astype(np.float64), oracle.gemm(X, W), oracle.gemm(X, W, use_abs=True), TOL_F32)
 
 
+def test_gemm_random_shapes_and_alignments():
+    """Random sizes, bases and leading dimensions of all three matrices (every load and store form of the kernel and
+    the narrow-W route) against the oracle's fp64 loops.  HCSPMM_TEST_EXAMPLES=N runs N cases with a fresh seed."""
+    import os
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    n_cases = int(os.environ.get("HCSPMM_TEST_EXAMPLES", "60"))
+    rng = np.random.default_rng(None if "HCSPMM_TEST_EXAMPLES" in os.environ else 20250102)
+    for case in range(n_cases):
+        m = int(rng.choice([1, 7, 31, 33, 100, 129, 1000, 4097]))
+        k, n = int(rng.integers(0, 300)), int(rng.integers(1, 200))
+        xoff, xpad, wpad, tpad = (int(v) for v in rng.integers(0, 9, 4))
+        X, W = dense_normal(m, max(k, 1), seed=case)[:, :k], dense_normal(max(k, 1), n, seed=case + 1)[:k]
+        X, W = np.ascontiguousarray(X), np.ascontiguousarray(W)
+        ldx = max(k + xpad, 1)
+        flat = torch.full((xoff + (m - 1) * ldx + k + 1,), float("nan"), device="cuda")
+        Xv = torch.as_strided(flat, (m, k), (ldx, 1), xoff)
+        Xv.copy_(torch.from_numpy(X).cuda())
+        Wb = torch.zeros((k, n + wpad), device="cuda")
+        Wb[:, :n] = torch.from_numpy(W).cuda()
+        T = torch.full((m, n + tpad), -5.0, device="cuda")
+        hc.hcspmm_gemm_f32(Xv, Wb[:, :n], T[:, :n])
+        torch.cuda.synchronize()
+        got = T.cpu().numpy().astype(np.float64)
+        assert np.all(got[:, n:] == -5.0), (case, m, k, n)
+        assert_close(got[:, :n], oracle.gemm(X, W), oracle.gemm(X, W, use_abs=True), TOL_F32, str((case, m, k, n, xoff, xpad, wpad, tpad)))
+
+
 def run_layer(g, X, W, mode, relu=True):
     import torch
     import paper_2412_08902_amd.binding as hc

@@ -217,3 +217,53 @@ def test_update_of_a_plan_with_run_tables_and_after_an_export():
     g3, changed = edit(g2, deletes=dels)
     update_and_check(plan, g3, changed, 2)
     plan.destroy()
+
+
+def test_random_update_chains_equal_a_preparation_from_scratch():
+    """Random graphs, routings, selector coefficients and chains of edits (with an export thrown in, which completes
+    the condensed structure the next update carries over): after every update the plan's arrays and its product are
+    bit-identical to those of a plan prepared from scratch for the same matrix.  (The comparison with the CPU
+    re-derivation is in the tests above; this one hunts for state that an update could leave behind.)
+    HCSPMM_TEST_EXAMPLES=N runs N cases with a fresh seed."""
+    import os
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    n_cases = int(os.environ.get("HCSPMM_TEST_EXAMPLES", "12"))
+    rng = np.random.default_rng(None if "HCSPMM_TEST_EXAMPLES" in os.environ else 20250101)
+    for case in range(n_cases):
+        n = int(rng.integers(400, 4000))
+        e = int(rng.integers(n, 20 * n)) // 2 * 2
+        avg = max(1, e // n)
+        g = gcn_normalise(chung_lu_graph(n, e, 2.1 + 0.4 * rng.random(), seed=int(rng.integers(1 << 30)),
+                                         max_degree=int(rng.integers(8 * avg, max(8 * avg + 1, n // 2)))))
+        mode = int(rng.integers(0, 4))
+        coef = None
+        if mode in (0, 3) and rng.random() < 0.7:
+            coef = [int(rng.integers(0, 50)), int(rng.integers(0, 2000)), -int(rng.integers(100, 3000))]
+        d = int(rng.choice([16, 32, 64, 128]))
+        plan = prepare(g, mode, coef, d)
+        cur = g
+        for step in range(int(rng.integers(1, 4))):
+            ins = [(int(r), int(rng.integers(0, g.n_cols))) for r in rng.integers(0, g.n_rows, int(rng.integers(0, 50)))]
+            dels = []
+            for r in rng.integers(0, g.n_rows, int(rng.integers(0, 50))):
+                if cur.rowptr[r + 1] > cur.rowptr[r]:
+                    dels.append((int(r), int(cur.colind[rng.integers(cur.rowptr[r], cur.rowptr[r + 1])])))
+            cur, changed = edit(cur, ins, dels)
+            if rng.random() < 0.3:
+                hc.hcspmm_plan_export(plan)
+            rp, ci, va = device_graph(cur)
+            hc.hcspmm_plan_update(plan, rp, ci, va, changed)
+            fresh = prepare(cur, mode, coef, d)
+            a, b = hc.hcspmm_plan_export(plan), hc.hcspmm_plan_export(fresh)
+            for k in KEYS:
+                assert np.array_equal(a[k], b[k]), (case, step, k, n, e, mode, coef)
+            X = torch.from_numpy(dense_normal(cur.n_cols, d, seed=case)).cuda()
+            Y1 = torch.empty((cur.n_rows, d), device="cuda")
+            Y2 = torch.empty_like(Y1)
+            hc.hcspmm_spmm(plan, X, Y1)
+            hc.hcspmm_spmm(fresh, X, Y2)
+            torch.cuda.synchronize()
+            assert torch.equal(Y1, Y2), (case, step, n, e, mode, coef)
+            fresh.destroy()
+        plan.destroy()
