@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 
 import oracle
-from workloads import tiny_random_csr, make_config, CSRGraph, sbm_graph
+from workloads import tiny_random_csr, make_config, CSRGraph, sbm_graph, chung_lu_graph, gcn_normalise, dense_normal
 from gpu_util import device_graph
 
 pytestmark = pytest.mark.gpu
@@ -306,3 +306,54 @@ def test_large_matrix_path_windows_lists_and_positions(m, srt):
     plan.destroy()
     ref, bound = oracle_pair(g, X)
     assert_close(Y.cpu().numpy().astype(np.float64), ref, bound, 1e-5)
+
+
+def test_concurrent_preparations_share_the_library_state():
+    """Four host threads prepare, use and destroy plans at the same time, each on its own stream (the binding releases
+    the GIL during a call): the pinned read-back pages and the per-GPU cache of device blocks are shared by all of
+    them.  Every thread's plans and products must equal those computed alone."""
+    import threading
+    import torch
+    import paper_2412_08902_amd.binding as hc
+    graphs = [gcn_normalise(chung_lu_graph(1500 + 300 * i, 30000 + 9000 * i, 2.2, seed=90 + i, max_degree=600)) for i in range(4)]
+    Xs = [dense_normal(g.n_cols, 32, seed=95 + i) for i, g in enumerate(graphs)]
+    ref = []
+    for g, X in zip(graphs, Xs):
+        rp, ci, va = device_graph(g)
+        plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, route_mode=3, sel_coef=[1, 0, -150], d_hint=32)
+        Y = torch.empty((g.n_rows, 32), device="cuda")
+        hc.hcspmm_spmm(plan, torch.from_numpy(X).cuda(), Y)
+        torch.cuda.synchronize()
+        ref.append((hc.hcspmm_plan_export(plan), Y.clone()))
+        plan.destroy()
+    errors = []
+
+    def worker(i):
+        try:
+            g, X = graphs[i], Xs[i]
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                rp, ci, va = device_graph(g)
+                Xd = torch.from_numpy(X).cuda()
+                Y = torch.empty((g.n_rows, 32), device="cuda")
+            stream.synchronize()
+            for it in range(25):
+                plan = hc.hcspmm_prepare(g.n_rows, g.n_cols, rp, ci, va, route_mode=3, sel_coef=[1, 0, -150], d_hint=32,
+                                         stream=stream)
+                hc.hcspmm_spmm(plan, Xd, Y, stream=stream)
+                stream.synchronize()
+                if it % 8 == 0:
+                    got = hc.hcspmm_plan_export(plan)
+                    for k in ("ncols", "route", "wptr", "wcols", "ecol"):
+                        assert np.array_equal(got[k], ref[i][0][k]), (i, it, k)
+                assert torch.equal(Y, ref[i][1]), (i, it)
+                plan.destroy()
+        except Exception as ex:      # noqa: BLE001 - reported below, in the main thread
+            errors.append((i, repr(ex)))
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(4)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
